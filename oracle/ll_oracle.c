@@ -1,0 +1,342 @@
+/*
+ * CPU oracle for the Linear-Layouts hot path (arXiv 2505.23819).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, written from the paper's definitions.
+ * It shares no code with the HIP library: nothing here is included, linked or
+ * imported by the product path, and nothing here includes product headers.
+ *
+ * Conventions (paper Sec. 4.1, the worked Layout A example and its footnote):
+ *   - A layout with d_in input bits is stored as its matrix COLUMNS:
+ *     bases[k] is the image of input bit k, written as a flattened output
+ *     index.  Input bits are ordered register bits first, then lane (thread)
+ *     bits, then wave (warp) bits; least-significant bit first.
+ *   - The flattened output index puts the LAST logical dimension in the lowest
+ *     bits (the fastest moving one), e.g. for a rows x cols tile
+ *     flat = col | row << log2(cols).
+ *   - L(h) is the XOR of the columns selected by the set bits of h
+ *     (matrix-vector product over F2, Sec. 2.4).
+ *
+ * Functions and the passage each follows:
+ *   oracle_apply            Sec. 4.1  w = A v over F2
+ *   oracle_compose          Def. Composition (label-wise matrix product), with
+ *                           the product written out as c_ij = XOR_k a_ik b_kj
+ *   oracle_inverse_table    Def. Right Inverse, restricted to bijective
+ *                           layouts: the inverse is found by tabulating L(h)
+ *                           for every h (no elimination)
+ *   oracle_convert          Sec. 5.4: the conversion is B^-1 o A; element by
+ *                           element on images (see below)
+ *   oracle_convert_table    same result; the composed map is tabulated once
+ *                           and tiles are processed by all host threads
+ *   oracle_gather           Sec. 5.5: out[.., i, ..] = in[.., idx[.., i, ..], ..]
+ *                           along `axis`, all three tensors under layout L
+ *   oracle_wavefronts       Sec. 5.4 "Optimal Swizzling" + the wavefront lemma
+ *                           of the appendix: exhaustive enumeration of the
+ *                           shared-memory (LDS) wavefronts an access needs
+ *
+ * Images.  A tensor tile held "under layout L" is stored as an array indexed
+ * by the hardware index h = reg | lane << nreg | wave << (nreg+nlane): element
+ * h of tile t sits at buf[t * 2^d + h] and is the logical element L(h).
+ *
+ * Pins: tests/test_oracle_pins.py (values the paper prints for Layout A,
+ * closed forms, textbook transpose / take_along_axis, brute force).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG 1
+#define ORACLE_ERR_NOT_BIJECTIVE 2
+#define ORACLE_ERR_AXIS 3
+#define ORACLE_ERR_ALLOC 4
+
+/* w = L v : XOR of the columns picked by the set bits of v (Sec. 4.1). */
+uint64_t oracle_apply(const uint64_t *bases, int d_in, uint64_t h)
+{
+    uint64_t x = 0;
+    for (int k = 0; k < d_in; ++k)
+        if ((h >> k) & 1u)
+            x ^= bases[k];
+    return x;
+}
+
+/*
+ * Composition outer o inner (Def. Composition): the matrix product over F2,
+ * entry by entry: c_ij = XOR_k a_ik * b_kj  (Sec. 2.4).
+ * inner: d_in columns, each a d_mid-bit vector; outer: d_mid columns.
+ */
+int oracle_compose(const uint64_t *outer, int d_mid, int d_out,
+                   const uint64_t *inner, int d_in, uint64_t *result)
+{
+    if (!outer || !inner || !result || d_mid < 0 || d_mid > 63 || d_out > 63)
+        return ORACLE_ERR_ARG;
+    for (int j = 0; j < d_in; ++j) {
+        uint64_t col = 0;
+        for (int i = 0; i < d_out; ++i) {
+            unsigned c = 0;
+            for (int k = 0; k < d_mid; ++k) {
+                unsigned a_ik = (unsigned)((outer[k] >> i) & 1u); /* row i, col k of outer */
+                unsigned b_kj = (unsigned)((inner[j] >> k) & 1u); /* row k, col j of inner */
+                c ^= (a_ik & b_kj);
+            }
+            col |= (uint64_t)c << i;
+        }
+        result[j] = col;
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Inverse of a bijective layout on d bits by tabulation: table[L(h)] = h.
+ * Fails unless every output index is hit exactly once (this is the
+ * bijectivity check of the oracle).
+ */
+int oracle_inverse_table(const uint64_t *bases, int d, uint32_t *table)
+{
+    if (!bases || !table || d < 0 || d > 30)
+        return ORACLE_ERR_ARG;
+    const uint64_t n = 1ull << d;
+    for (uint64_t x = 0; x < n; ++x)
+        table[x] = 0xFFFFFFFFu;
+    for (uint64_t h = 0; h < n; ++h) {
+        uint64_t x = oracle_apply(bases, d, h);
+        if (x >= n || table[x] != 0xFFFFFFFFu)
+            return ORACLE_ERR_NOT_BIJECTIVE;
+        table[x] = (uint32_t)h;
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Layout conversion A -> B on images (Sec. 5.4: the conversion is B^-1 o A).
+ * For every tile t and every source hardware index hA:
+ *     x  = A(hA)                      (logical element held at hA)
+ *     hB = the unique index with B(hB) = x
+ *     dst[t*2^d + hB] = src[t*2^d + hA]      (bytes copied verbatim)
+ */
+int oracle_convert(const uint64_t *basesA, const uint64_t *basesB, int d,
+                   int elem_bytes, const void *src, void *dst, int64_t ntiles)
+{
+    if (!basesA || !basesB || d < 0 || d > 30 || elem_bytes <= 0 || ntiles < 0)
+        return ORACLE_ERR_ARG;
+    if (ntiles > 0 && (!src || !dst))
+        return ORACLE_ERR_ARG;
+    const uint64_t n = 1ull << d;
+    uint32_t *invB = (uint32_t *)malloc(n * sizeof(uint32_t));
+    uint32_t *invA = (uint32_t *)malloc(n * sizeof(uint32_t));
+    if (!invB || !invA) { free(invB); free(invA); return ORACLE_ERR_ALLOC; }
+    int rc = oracle_inverse_table(basesB, d, invB);
+    if (rc == ORACLE_OK)
+        rc = oracle_inverse_table(basesA, d, invA); /* A must be bijective too */
+    if (rc != ORACLE_OK) { free(invB); free(invA); return rc; }
+    const unsigned char *s = (const unsigned char *)src;
+    unsigned char *o = (unsigned char *)dst;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        for (uint64_t hA = 0; hA < n; ++hA) {
+            uint64_t x = oracle_apply(basesA, d, hA);
+            uint64_t hB = invB[x];
+            memcpy(o + ((uint64_t)t * n + hB) * (uint64_t)elem_bytes,
+                   s + ((uint64_t)t * n + hA) * (uint64_t)elem_bytes,
+                   (size_t)elem_bytes);
+        }
+    }
+    free(invB);
+    free(invA);
+    return ORACLE_OK;
+}
+
+/*
+ * Same result as oracle_convert.  The composed map hA -> hB is tabulated once
+ * (it does not depend on the tile) and the tile loop runs on all host threads.
+ * Returns the number of threads used through *threads_used (may be NULL).
+ */
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+int oracle_convert_table(const uint64_t *basesA, const uint64_t *basesB, int d,
+                         int elem_bytes, const void *src, void *dst,
+                         int64_t ntiles, int *threads_used)
+{
+    if (!basesA || !basesB || d < 0 || d > 30 || elem_bytes <= 0 || ntiles < 0)
+        return ORACLE_ERR_ARG;
+    if (ntiles > 0 && (!src || !dst))
+        return ORACLE_ERR_ARG;
+    const uint64_t n = 1ull << d;
+    uint32_t *invB = (uint32_t *)malloc(n * sizeof(uint32_t));
+    uint32_t *pmap = (uint32_t *)malloc(n * sizeof(uint32_t));
+    if (!invB || !pmap) { free(invB); free(pmap); return ORACLE_ERR_ALLOC; }
+    int rc = oracle_inverse_table(basesB, d, invB);
+    if (rc == ORACLE_OK) {
+        /* A bijective <=> the composed map is a permutation of [0, 2^d) */
+        unsigned char *seen = (unsigned char *)calloc(n, 1);
+        if (!seen) { free(invB); free(pmap); return ORACLE_ERR_ALLOC; }
+        for (uint64_t hA = 0; hA < n && rc == ORACLE_OK; ++hA) {
+            uint64_t x = oracle_apply(basesA, d, hA);
+            if (x >= n) { rc = ORACLE_ERR_NOT_BIJECTIVE; break; }
+            pmap[hA] = invB[x];
+            if (seen[pmap[hA]]) rc = ORACLE_ERR_NOT_BIJECTIVE;
+            seen[pmap[hA]] = 1;
+        }
+        free(seen);
+    }
+    if (rc != ORACLE_OK) { free(invB); free(pmap); return rc; }
+    const unsigned char *s = (const unsigned char *)src;
+    unsigned char *o = (unsigned char *)dst;
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = omp_get_max_threads();
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const unsigned char *st = s + (uint64_t)t * n * (uint64_t)elem_bytes;
+        unsigned char *ot = o + (uint64_t)t * n * (uint64_t)elem_bytes;
+        for (uint64_t hA = 0; hA < n; ++hA)
+            memcpy(ot + (uint64_t)pmap[hA] * (uint64_t)elem_bytes,
+                   st + hA * (uint64_t)elem_bytes, (size_t)elem_bytes);
+    }
+    if (threads_used) *threads_used = nthreads;
+    free(invB);
+    free(pmap);
+    return ORACLE_OK;
+}
+
+/*
+ * Gather along `axis` (Sec. 5.5), all three tensors under the same bijective
+ * layout L on d bits.  out_dim_bits[k] is log2 of logical dimension k, slowest
+ * dimension first (the last one is the fastest, in the low bits of the
+ * flattened index).  For every tile and every hardware index h:
+ *     x = L(h); split x into coordinates; s = idx_img[h] & (len(axis) - 1);
+ *     x' = x with the axis coordinate replaced by s;
+ *     out_img[h] = in_img[L^-1(x')].
+ * Out-of-range indices are reduced modulo the axis length (a power of two).
+ */
+int oracle_gather(const uint64_t *basesL, int d, const int32_t *out_dim_bits,
+                  int n_out_dims, int axis, int elem_bytes, const void *in,
+                  const int32_t *idx, void *out, int64_t ntiles)
+{
+    if (!basesL || !out_dim_bits || d < 0 || d > 30 || elem_bytes <= 0 ||
+        ntiles < 0 || n_out_dims <= 0)
+        return ORACLE_ERR_ARG;
+    if (axis < 0 || axis >= n_out_dims)
+        return ORACLE_ERR_AXIS;
+    if (ntiles > 0 && (!in || !idx || !out))
+        return ORACLE_ERR_ARG;
+    int total = 0, axis_shift = 0;
+    for (int k = n_out_dims - 1; k >= 0; --k) { /* last dim sits lowest */
+        if (k == axis) axis_shift = total;
+        total += out_dim_bits[k];
+    }
+    if (total != d)
+        return ORACLE_ERR_ARG;
+    const int axis_bits = out_dim_bits[axis];
+    const uint64_t axis_len_mask = (1ull << axis_bits) - 1;
+    const uint64_t n = 1ull << d;
+    uint32_t *invL = (uint32_t *)malloc(n * sizeof(uint32_t));
+    if (!invL) return ORACLE_ERR_ALLOC;
+    int rc = oracle_inverse_table(basesL, d, invL);
+    if (rc != ORACLE_OK) { free(invL); return rc; }
+    const unsigned char *pi = (const unsigned char *)in;
+    unsigned char *po = (unsigned char *)out;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const uint64_t base = (uint64_t)t * n;
+        for (uint64_t h = 0; h < n; ++h) {
+            uint64_t x = oracle_apply(basesL, d, h);
+            uint64_t s = (uint64_t)(uint32_t)idx[base + h] & axis_len_mask;
+            uint64_t xs = (x & ~(axis_len_mask << axis_shift)) | (s << axis_shift);
+            uint64_t hs = invL[xs];
+            memcpy(po + (base + h) * (uint64_t)elem_bytes,
+                   pi + (base + hs) * (uint64_t)elem_bytes, (size_t)elem_bytes);
+        }
+    }
+    free(invL);
+    return ORACLE_OK;
+}
+
+/*
+ * Exhaustive wavefront (bank-conflict) count of one shared-memory access
+ * pattern (Sec. 5.4 "Optimal Swizzling"; appendix lemma on wavefronts).
+ *
+ *   mem_bases   memory layout M on d bits: offset (in elements) -> logical
+ *   dist_bases  distributed layout L on d bits: hardware index -> logical,
+ *               input bits ordered reg (nreg), lane (nlane), then the rest
+ *   elem_bytes  w
+ *   vec_bits    v: one instruction moves the 2^v elements of registers
+ *               r0 .. r0 + 2^v - 1 (r0 a multiple of 2^v) of a lane
+ *   nbanks      number of 4-byte banks
+ *   phase_of_lane[l]  lanes with the same value are served together
+ *
+ * For every wave (all settings of the bits above the lane bits), every vector
+ * slot r0 and every phase: gather the 4-byte words the lanes of the phase
+ * touch at offsets M^-1(L(h)); the phase needs max over banks of the number
+ * of DISTINCT words that fall in that bank (same word twice is a broadcast).
+ *
+ * Results: *max_wavefronts = largest count over all phases;
+ *          *total_wavefronts = sum over all phases;
+ *          *total_phases = number of (wave, slot, phase) triples that touch
+ *          at least one word (the conflict-free total).
+ */
+int oracle_wavefronts(const uint64_t *mem_bases, const uint64_t *dist_bases,
+                      int d, int nreg, int nlane, int elem_bytes, int vec_bits,
+                      int nbanks, const int32_t *phase_of_lane,
+                      int64_t *max_wavefronts, int64_t *total_wavefronts,
+                      int64_t *total_phases)
+{
+    if (!mem_bases || !dist_bases || !phase_of_lane || d < 0 || d > 26 ||
+        nreg < 0 || nlane < 0 || nreg + nlane > d || vec_bits < 0 ||
+        vec_bits > nreg || nbanks <= 0 || elem_bytes <= 0)
+        return ORACLE_ERR_ARG;
+    const uint64_t n = 1ull << d;
+    const int nlanes = 1 << nlane;
+    uint32_t *invM = (uint32_t *)malloc(n * sizeof(uint32_t));
+    if (!invM) return ORACLE_ERR_ALLOC;
+    int rc = oracle_inverse_table(mem_bases, d, invM);
+    if (rc != ORACLE_OK) { free(invM); return rc; }
+    int nphases = 0;
+    for (int l = 0; l < nlanes; ++l)
+        if (phase_of_lane[l] + 1 > nphases) nphases = phase_of_lane[l] + 1;
+    const int vec = 1 << vec_bits;
+    const int max_words = nlanes * vec * ((elem_bytes + 3) / 4 + 1);
+    uint64_t *words = (uint64_t *)malloc((size_t)max_words * sizeof(uint64_t));
+    int *bank_count = (int *)malloc((size_t)nbanks * sizeof(int));
+    if (!words || !bank_count) { free(invM); free(words); free(bank_count); return ORACLE_ERR_ALLOC; }
+    int64_t maxw = 0, totw = 0, totp = 0;
+    const uint64_t nwaves = n >> (nreg + nlane);
+    for (uint64_t wv = 0; wv < nwaves; ++wv) {
+        for (int r0 = 0; r0 < (1 << nreg); r0 += vec) {
+            for (int ph = 0; ph < nphases; ++ph) {
+                int nw = 0;
+                for (int l = 0; l < nlanes; ++l) {
+                    if (phase_of_lane[l] != ph) continue;
+                    for (int e = 0; e < vec; ++e) {
+                        uint64_t h = (uint64_t)(r0 + e) | ((uint64_t)l << nreg) |
+                                     (wv << (nreg + nlane));
+                        uint64_t off = invM[oracle_apply(dist_bases, d, h)];
+                        uint64_t b0 = off * (uint64_t)elem_bytes;
+                        uint64_t b1 = b0 + (uint64_t)elem_bytes - 1;
+                        for (uint64_t wd = b0 / 4; wd <= b1 / 4; ++wd) {
+                            int dup = 0;
+                            for (int q = 0; q < nw; ++q)
+                                if (words[q] == wd) { dup = 1; break; }
+                            if (!dup) words[nw++] = wd;
+                        }
+                    }
+                }
+                if (nw == 0) continue;
+                memset(bank_count, 0, (size_t)nbanks * sizeof(int));
+                int worst = 0;
+                for (int q = 0; q < nw; ++q) {
+                    int b = (int)(words[q] % (uint64_t)nbanks);
+                    if (++bank_count[b] > worst) worst = bank_count[b];
+                }
+                if (worst > maxw) maxw = worst;
+                totw += worst;
+                totp += 1;
+            }
+        }
+    }
+    if (max_wavefronts) *max_wavefronts = maxw;
+    if (total_wavefronts) *total_wavefronts = totw;
+    if (total_phases) *total_phases = totp;
+    free(invM); free(words); free(bank_count);
+    return ORACLE_OK;
+}
