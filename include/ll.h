@@ -1,0 +1,186 @@
+/*
+ * ll.h - C ABI of the MI355X-native Linear-Layouts library (arXiv 2505.23819).
+ *
+ * A linear layout is a linear map over F2 between labeled bit spaces
+ * (paper Sec. 4.2, Def. "Linear Layouts").  Its matrix is stored by COLUMNS:
+ * bases[k] is the image of input bit k.  Input bits are the concatenation of
+ * the input dimensions in canonical order register, lane, wave[, tile] (or a
+ * single `offset` dimension for memory layouts), least-significant bit first
+ * (Sec. 4.1, Layout A and its footnote).  An image is a FLATTENED output
+ * index: the LAST output dimension occupies the lowest bits (it is the fastest
+ * moving one, Sec. 4.1: w_0:3 = j, w_4:7 = i).
+ *
+ * Images.  A tensor tile held "under layout L" is an array indexed by the
+ * hardware index h = reg | lane << nreg | wave << (nreg + nlane): element h of
+ * tile t is stored at buf[t * 2^d + h] and is the logical element L(h).
+ * A row-major logical tile is the special case L = identity on flattened bits.
+ *
+ * Ownership and threading.  ll_layout and ll_plan objects are allocated by the
+ * library, immutable after creation, usable from any thread, and released with
+ * the matching destroy call.  Device buffers belong to the caller, must be
+ * 16-byte aligned, must not overlap each other, and hold ntiles * 2^d elements.
+ * `hip_stream` is the caller's hipStream_t (NULL = the default stream).  The
+ * device entry points only enqueue work on that stream: they never
+ * synchronize, never allocate device memory and never touch the host copy of
+ * the data.  There is NO host fallback: without a usable HIP device the device
+ * entry points return LL_ERR_DEVICE.
+ *
+ * Errors.  Every call returns an ll_status; argument errors are detected on
+ * the host before anything is launched.  ll_last_error() returns a
+ * thread-local, human-readable description of the last failure on this thread.
+ */
+#ifndef LL_H_
+#define LL_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LL_OK = 0,
+    LL_ERR_INVALID_ARG = 1,      /* null pointer, size out of range, bad label order, misaligned buffer */
+    LL_ERR_DIM_MISMATCH = 2,     /* input/output spaces of the operands do not match */
+    LL_ERR_NOT_SURJECTIVE = 3,   /* a right inverse was requested of a non-surjective layout */
+    LL_ERR_NOT_INJECTIVE = 4,    /* the hot path needs bijective layouts (no broadcasting yet) */
+    LL_ERR_TILE_MIXED = 5,       /* the conversion would move data between tiles */
+    LL_ERR_AXIS_NOT_IN_WAVE = 6, /* gather axis is not contained in one wave (Sec. 5.5) */
+    LL_ERR_UNSUPPORTED = 7,      /* valid request outside what is implemented */
+    LL_ERR_DEVICE = 8            /* a HIP call failed; see ll_last_error() */
+} ll_status;
+
+typedef enum { LL_IN_REG = 0, LL_IN_LANE = 1, LL_IN_WAVE = 2, LL_IN_TILE = 3, LL_IN_OFFSET = 4 } ll_in_label;
+
+typedef struct { int32_t label; int32_t nbits; } ll_in_dim;   /* canonical order: labels strictly ascending */
+typedef struct { int32_t nbits; } ll_out_dim;                 /* logical dims, slowest first */
+
+typedef struct ll_layout ll_layout;   /* opaque */
+typedef struct ll_plan ll_plan;       /* opaque */
+
+#define LL_MAX_IN_DIMS 5
+#define LL_MAX_OUT_DIMS 8
+#define LL_MAX_BITS 30                /* input and output bits of a layout */
+#define LL_WAVE_LANE_BITS 6           /* wave64 */
+
+/* ---- host-side F2 algebra (paper Sec. 4.2) ----------------------------------------------- */
+
+/* Build a layout from its basis vectors (matrix columns, Sec. 4.1 / 4.2).  `bases` holds
+ * sum(in_dims[].nbits) values, each < 2^sum(out_dims[].nbits).  The new layout is returned
+ * through *out.  Any linear map is accepted here (surjectivity / injectivity are checked by the
+ * calls that need them). */
+ll_status ll_layout_create(const ll_in_dim *in_dims, int n_in, const ll_out_dim *out_dims, int n_out,
+                           const uint64_t *bases, ll_layout **out);
+ll_status ll_layout_destroy(ll_layout *layout);
+
+/* Read a layout back.  Any output pointer may be NULL.  in_dims / out_dims / bases must have room
+ * for LL_MAX_IN_DIMS / LL_MAX_OUT_DIMS / LL_MAX_BITS entries. */
+ll_status ll_layout_get(const ll_layout *layout, int *n_in, ll_in_dim *in_dims, int *n_out,
+                        ll_out_dim *out_dims, uint64_t *bases);
+
+/* y = L x over F2: XOR of the columns selected by the set bits of in_index (Sec. 4.1). Host only. */
+ll_status ll_layout_apply(const ll_layout *layout, uint64_t in_index, uint64_t *out_index);
+
+/* Composition outer o inner (Def. "Composition"): the matrix product over F2.  The output space
+ * of `inner` must have as many bits as the input space of `outer`.  The result maps the input
+ * dims of `inner` to the output dims of `outer`. */
+ll_status ll_compose(const ll_layout *outer, const ll_layout *inner, ll_layout **out);
+
+/* Product L1 x L2 (Def. "Product"): the block-diagonal layout acting on the concatenated inputs.
+ * Input dims are merged label-wise (bits of `a` below bits of `b` inside one label); the output
+ * dims of `b` are placed above (slower than) those of `a` in the flattened index. */
+ll_status ll_product(const ll_layout *a, const ll_layout *b, ll_layout **out);
+
+/* Right inverse (Def. "Right Inverse") by Gaussian elimination over F2.  L must be surjective,
+ * else LL_ERR_NOT_SURJECTIVE.  If L is not injective the free variables are set to zero, with
+ * input columns taken as pivots in order (register bits first).  The result maps one `offset`
+ * input dim of d_out bits to one output dim of d_in bits (the flattened hardware index). */
+ll_status ll_invert(const ll_layout *layout, ll_layout **out);
+
+/* ---- conversion (paper Sec. 5.4) ------------------------------------------------------- */
+
+typedef enum {
+    LL_KIND_NOOP = 0,        /* B^-1 o A is the identity */
+    LL_KIND_REG_ONLY = 1,    /* only register bits move ("intra-thread data exchange") */
+    LL_KIND_INTRA_WAVE = 2,  /* the wave part of B^-1 o A is the identity ("intra-warp") */
+    LL_KIND_LDS = 3          /* data crosses waves: staged through shared memory (LDS) */
+} ll_plan_kind;
+
+typedef enum {
+    LL_STRATEGY_COPY = 0,      /* plain 16-byte vector copy */
+    LL_STRATEGY_REG_PERMUTE = 1, /* each lane loads whole vectors, permutes them in registers, stores */
+    LL_STRATEGY_WAVE_SHUFFLE = 2, /* wave64 exchange by cross-lane shuffles */
+    LL_STRATEGY_LDS_ELEM = 3,  /* LDS staging, element-wide (or common-vector-wide) accesses, XOR swizzle */
+    LL_STRATEGY_LDS_VEC = 4    /* LDS staging with in-register transposes and 128-bit LDS accesses */
+} ll_strategy;
+
+#define LL_PLAN_MAX_BLOCK_BITS 20
+
+typedef struct {
+    int32_t kind;               /* ll_plan_kind: the paper's classification of B^-1 o A */
+    int32_t strategy;           /* ll_strategy: the kernel that ll_convert launches */
+    int32_t d;                  /* index bits of one tile */
+    int32_t elem_bytes;
+    uint64_t conv[LL_MAX_BITS]; /* columns of B^-1 o A on the d hardware-index bits */
+    int32_t global_vec_bytes;   /* width of every global load and store */
+    int32_t lds_write_bytes;    /* width of one LDS write (0 if LDS unused) */
+    int32_t lds_read_bytes;     /* width of one LDS read  (0 if LDS unused) */
+    int32_t lds_bytes;          /* LDS bytes per workgroup */
+    int32_t threads;            /* threads per workgroup */
+    int32_t vectors_per_thread;
+    int32_t block_bits;         /* log2 elements staged per workgroup iteration */
+    int32_t group_bits;         /* log2 tiles that share one block (small tiles) */
+    int32_t segment_bits;       /* log2 elements of the contiguous runs a block reads and writes */
+    int32_t shuffle_rounds;     /* cross-lane exchange stages (WAVE_SHUFFLE) */
+    /* LDS layout of one block, as linear layouts on block_bits bits over a common "block-local"
+     * logical space (paper Sec. 5.4 "Optimal Swizzling"): lds_mem maps an LDS element offset to
+     * a block-local index; lds_write / lds_read map (register, lane, wave) of the writing /
+     * reading instruction to the same space, with lds_*_reg_bits register bits first, then
+     * LL_WAVE_LANE_BITS lane bits, then wave bits. */
+    uint64_t lds_mem[LL_PLAN_MAX_BLOCK_BITS];
+    uint64_t lds_write[LL_PLAN_MAX_BLOCK_BITS];
+    uint64_t lds_read[LL_PLAN_MAX_BLOCK_BITS];
+    int32_t lds_write_reg_bits, lds_read_reg_bits;
+    int32_t lds_vec_bits;       /* log2 elements per LDS access */
+    int32_t lds_banks;          /* hardware model used by the synthesizer */
+    int32_t lds_phase_lanes_write, lds_phase_lanes_read; /* lanes served together */
+    int32_t predicted_wavefronts_write, predicted_wavefronts_read; /* per access phase; 1 = conflict free */
+} ll_plan_desc;
+
+/* Plan the conversion of images under `src` into images under `dst` (both map the same
+ * register/lane/wave input dims onto output spaces of equal size).  Computes B^-1 o A
+ * (Sec. 5.4), classifies it (intra-thread / intra-warp / shared memory), and picks the kernel,
+ * its vector widths and, for LDS paths, the XOR swizzle.  elem_bytes is 1, 2, 4 or 8.
+ * Both layouts must be bijective (LL_ERR_NOT_INJECTIVE / LL_ERR_NOT_SURJECTIVE otherwise); a
+ * `tile` input dim, if present, must map identically in both (LL_ERR_TILE_MIXED otherwise). */
+ll_status ll_plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan **out);
+ll_status ll_plan_info(const ll_plan *plan, ll_plan_desc *out);
+ll_status ll_plan_destroy(ll_plan *plan);
+
+/* Apply a plan: dst_dev[t * 2^d + (B^-1 o A)(h)] = src_dev[t * 2^d + h] for every tile t < ntiles
+ * and every h (Sec. 5.4).  Pointers are DEVICE pointers.  Asynchronous on hip_stream.
+ * ntiles == 0 is a no-op. */
+ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, int64_t ntiles, void *hip_stream);
+
+/* ---- gather (paper Sec. 5.5) ----------------------------------------------------------- */
+
+/* out[.., i, ..] = in[.., idx[.., i, ..], ..] along output dim `axis`, where in, idx (int32) and
+ * out are images under the same bijective layout L.  The axis must lie inside one wave: moving
+ * along it must change lane bits only (LL_ERR_AXIS_NOT_IN_WAVE if it changes wave bits,
+ * LL_ERR_UNSUPPORTED if it changes register bits).  Indices are reduced modulo the axis
+ * length.  Pointers are DEVICE pointers.  Asynchronous on hip_stream. */
+ll_status ll_gather(const ll_layout *layout, int axis, int elem_bytes, const void *in_dev,
+                    const int32_t *idx_dev, void *out_dev, int64_t ntiles, void *hip_stream);
+
+/* ---- misc -------------------------------------------------------------------------------- */
+
+/* Plain 16-byte-vector device copy of `bytes` bytes (a multiple of 16): the achievable-bandwidth
+ * yardstick the benchmark prints next to each conversion.  Asynchronous on hip_stream. */
+ll_status ll_copy(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream);
+
+const char *ll_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LL_H_ */

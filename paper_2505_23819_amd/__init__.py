@@ -1,0 +1,257 @@
+"""MI355X-native Linear-Layouts library: Python binding of the C ABI in include/ll.h.
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels of
+``libll355.so``.  PyTorch is used by callers for device memory and streams; this
+module only needs ``tensor.data_ptr()`` and a stream handle.  There is no CPU
+fallback: if the library cannot be loaded the import fails, and device calls
+without a GPU return an error status (raised as ``LLError``).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+from . import build as _build
+
+# ---- status codes and enums of ll.h ------------------------------------------------------------
+LL_OK, LL_ERR_INVALID_ARG, LL_ERR_DIM_MISMATCH, LL_ERR_NOT_SURJECTIVE, LL_ERR_NOT_INJECTIVE, \
+    LL_ERR_TILE_MIXED, LL_ERR_AXIS_NOT_IN_WAVE, LL_ERR_UNSUPPORTED, LL_ERR_DEVICE = range(9)
+LL_IN_REG, LL_IN_LANE, LL_IN_WAVE, LL_IN_TILE, LL_IN_OFFSET = range(5)
+LL_KIND_NOOP, LL_KIND_REG_ONLY, LL_KIND_INTRA_WAVE, LL_KIND_LDS = range(4)
+LL_STRATEGY_COPY, LL_STRATEGY_REG_PERMUTE, LL_STRATEGY_WAVE_SHUFFLE, LL_STRATEGY_LDS_ELEM, \
+    LL_STRATEGY_LDS_VEC = range(5)
+LL_MAX_IN_DIMS, LL_MAX_OUT_DIMS, LL_MAX_BITS, LL_PLAN_MAX_BLOCK_BITS = 5, 8, 30, 20
+
+KIND_NAMES = ["noop", "reg_only", "intra_wave", "lds"]
+STRATEGY_NAMES = ["copy", "reg_permute", "wave_shuffle", "lds_elem", "lds_vec"]
+
+EXPORTED_SYMBOLS = [
+    "ll_layout_create", "ll_layout_destroy", "ll_layout_get", "ll_layout_apply", "ll_compose",
+    "ll_product", "ll_invert", "ll_plan_convert", "ll_plan_info", "ll_plan_destroy", "ll_convert",
+    "ll_gather", "ll_copy", "ll_last_error",
+]
+
+
+class ll_in_dim(ctypes.Structure):
+    _fields_ = [("label", ctypes.c_int32), ("nbits", ctypes.c_int32)]
+
+
+class ll_out_dim(ctypes.Structure):
+    _fields_ = [("nbits", ctypes.c_int32)]
+
+
+class ll_plan_desc(ctypes.Structure):
+    _fields_ = [
+        ("kind", ctypes.c_int32), ("strategy", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("elem_bytes", ctypes.c_int32),
+        ("conv", ctypes.c_uint64 * LL_MAX_BITS),
+        ("global_vec_bytes", ctypes.c_int32), ("lds_write_bytes", ctypes.c_int32),
+        ("lds_read_bytes", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
+        ("threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
+        ("block_bits", ctypes.c_int32), ("group_bits", ctypes.c_int32),
+        ("segment_bits", ctypes.c_int32), ("shuffle_rounds", ctypes.c_int32),
+        ("lds_mem", ctypes.c_uint64 * LL_PLAN_MAX_BLOCK_BITS),
+        ("lds_write", ctypes.c_uint64 * LL_PLAN_MAX_BLOCK_BITS),
+        ("lds_read", ctypes.c_uint64 * LL_PLAN_MAX_BLOCK_BITS),
+        ("lds_write_reg_bits", ctypes.c_int32), ("lds_read_reg_bits", ctypes.c_int32),
+        ("lds_vec_bits", ctypes.c_int32), ("lds_banks", ctypes.c_int32),
+        ("lds_phase_lanes_write", ctypes.c_int32), ("lds_phase_lanes_read", ctypes.c_int32),
+        ("predicted_wavefronts_write", ctypes.c_int32), ("predicted_wavefronts_read", ctypes.c_int32),
+    ]
+
+
+class LLError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ll status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+def _load() -> ctypes.CDLL:
+    path = _build.LIB
+    if not os.path.exists(path):
+        _build.build(force=True)      # nothing built yet: build once, loudly on failure
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
+    P = ctypes.POINTER
+    lib.ll_layout_create.argtypes = [P(ll_in_dim), i32, P(ll_out_dim), i32, P(u64), P(vp)]
+    lib.ll_layout_destroy.argtypes = [vp]
+    lib.ll_layout_get.argtypes = [vp, P(i32), P(ll_in_dim), P(i32), P(ll_out_dim), P(u64)]
+    lib.ll_layout_apply.argtypes = [vp, u64, P(u64)]
+    lib.ll_compose.argtypes = [vp, vp, P(vp)]
+    lib.ll_product.argtypes = [vp, vp, P(vp)]
+    lib.ll_invert.argtypes = [vp, P(vp)]
+    lib.ll_plan_convert.argtypes = [vp, vp, i32, P(vp)]
+    lib.ll_plan_info.argtypes = [vp, P(ll_plan_desc)]
+    lib.ll_plan_destroy.argtypes = [vp]
+    lib.ll_convert.argtypes = [vp, vp, vp, i64, vp]
+    lib.ll_gather.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp]
+    lib.ll_copy.argtypes = [vp, vp, i64, vp]
+    lib.ll_last_error.restype = ctypes.c_char_p
+    lib.ll_last_error.argtypes = []
+    for name in EXPORTED_SYMBOLS:
+        if name != "ll_last_error":
+            getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+LIBRARY_PATH = _build.LIB
+
+
+def _check(status: int):
+    if status != LL_OK:
+        raise LLError(status, (_lib.ll_last_error() or b"").decode())
+
+
+def ll_last_error() -> str:
+    return (_lib.ll_last_error() or b"").decode()
+
+
+# ---- handles ------------------------------------------------------------------------------------
+
+class Layout:
+    """Owning wrapper of an ``ll_layout*``."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.ll_layout_destroy(h)
+
+    def get(self) -> Tuple[List[Tuple[int, int]], List[int], List[int]]:
+        n_in, n_out = ctypes.c_int(0), ctypes.c_int(0)
+        ind = (ll_in_dim * LL_MAX_IN_DIMS)()
+        outd = (ll_out_dim * LL_MAX_OUT_DIMS)()
+        bases = (ctypes.c_uint64 * LL_MAX_BITS)()
+        _check(_lib.ll_layout_get(self._h, ctypes.byref(n_in), ind, ctypes.byref(n_out), outd, bases))
+        in_dims = [(ind[i].label, ind[i].nbits) for i in range(n_in.value)]
+        out_dims = [outd[i].nbits for i in range(n_out.value)]
+        d_in = sum(b for _, b in in_dims)
+        return in_dims, out_dims, [int(bases[k]) for k in range(d_in)]
+
+    @property
+    def bases(self) -> List[int]:
+        return self.get()[2]
+
+    @property
+    def in_dims(self):
+        return self.get()[0]
+
+    @property
+    def out_dims(self):
+        return self.get()[1]
+
+    def apply(self, index: int) -> int:
+        return ll_layout_apply(self, index)
+
+
+class Plan:
+    """Owning wrapper of an ``ll_plan*``."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.ll_plan_destroy(h)
+
+    def info(self) -> dict:
+        return ll_plan_info(self)
+
+
+# ---- the calls of ll.h, same names --------------------------------------------------------------
+
+def ll_layout_create(in_dims: Sequence[Tuple[int, int]], out_dims: Sequence[int], bases: Sequence[int]) -> Layout:
+    """in_dims: [(label, nbits)] in canonical order; out_dims: [nbits] slowest first; bases: columns."""
+    ind = (ll_in_dim * max(1, len(in_dims)))(*[ll_in_dim(int(l), int(n)) for l, n in in_dims])
+    outd = (ll_out_dim * max(1, len(out_dims)))(*[ll_out_dim(int(n)) for n in out_dims])
+    arr = (ctypes.c_uint64 * max(1, len(bases)))(*[int(b) for b in bases])
+    h = ctypes.c_void_p()
+    _check(_lib.ll_layout_create(ind, len(in_dims), outd, len(out_dims), arr, ctypes.byref(h)))
+    return Layout(h.value)
+
+
+def ll_layout_apply(layout: Layout, index: int) -> int:
+    out = ctypes.c_uint64(0)
+    _check(_lib.ll_layout_apply(layout._h, int(index), ctypes.byref(out)))
+    return int(out.value)
+
+
+def _binary(fn, a: Layout, b: Layout) -> Layout:
+    h = ctypes.c_void_p()
+    _check(fn(a._h, b._h, ctypes.byref(h)))
+    return Layout(h.value)
+
+
+def ll_compose(outer: Layout, inner: Layout) -> Layout:
+    return _binary(_lib.ll_compose, outer, inner)
+
+
+def ll_product(a: Layout, b: Layout) -> Layout:
+    return _binary(_lib.ll_product, a, b)
+
+
+def ll_invert(layout: Layout) -> Layout:
+    h = ctypes.c_void_p()
+    _check(_lib.ll_invert(layout._h, ctypes.byref(h)))
+    return Layout(h.value)
+
+
+def ll_plan_convert(src: Layout, dst: Layout, elem_bytes: int) -> Plan:
+    h = ctypes.c_void_p()
+    _check(_lib.ll_plan_convert(src._h, dst._h, int(elem_bytes), ctypes.byref(h)))
+    return Plan(h.value)
+
+
+def ll_plan_info(plan: Plan) -> dict:
+    d = ll_plan_desc()
+    _check(_lib.ll_plan_info(plan._h, ctypes.byref(d)))
+    out = {}
+    for name, _ in ll_plan_desc._fields_:
+        v = getattr(d, name)
+        out[name] = [int(x) for x in v] if hasattr(v, "__len__") else int(v)
+    out["conv"] = out["conv"][:d.d]
+    for key in ("lds_mem", "lds_write", "lds_read"):
+        out[key] = out[key][:d.block_bits]
+    out["kind_name"] = KIND_NAMES[d.kind]
+    out["strategy_name"] = STRATEGY_NAMES[d.strategy]
+    return out
+
+
+def _ptr(x) -> int:
+    """Device pointer of a torch tensor (or a raw integer address)."""
+    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def ll_convert(plan: Plan, src, dst, ntiles: int, stream=None) -> None:
+    """Enqueue the conversion on `stream` (default: torch's current stream)."""
+    _check(_lib.ll_convert(plan._h, _ptr(src), _ptr(dst), int(ntiles), _stream(stream)))
+
+
+def ll_gather(layout: Layout, axis: int, elem_bytes: int, inp, idx, out, ntiles: int, stream=None) -> None:
+    _check(_lib.ll_gather(layout._h, int(axis), int(elem_bytes), _ptr(inp), _ptr(idx), _ptr(out),
+                          int(ntiles), _stream(stream)))
+
+
+def ll_copy(src, dst, nbytes: int, stream=None) -> None:
+    _check(_lib.ll_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)))
+
+
+# ---- small conveniences --------------------------------------------------------------------------
+
+def distributed_layout(nreg: int, nlane: int, nwave: int, out_dims: Sequence[int], bases: Sequence[int]) -> Layout:
+    """Layout with register / lane / wave inputs (labels with zero bits are dropped)."""
+    dims = [(l, n) for l, n in ((LL_IN_REG, nreg), (LL_IN_LANE, nlane), (LL_IN_WAVE, nwave)) if n > 0]
+    return ll_layout_create(dims, out_dims, bases)

@@ -1,0 +1,68 @@
+// Kernel argument blocks (plain data, passed by value) and host-side launchers.
+//
+// All index tables hold XOR-combinable offsets: the offset of an element is the XOR of the table
+// entries selected by the bits of (block, thread, iteration) indices, because every map involved
+// is linear over F2 (paper Sec. 4.2).
+#pragma once
+#include <cstdint>
+
+#include "../../include/ll.h"
+
+namespace ll {
+
+constexpr int kMaxThreadBits = 10;   // up to 1024 threads per workgroup
+constexpr int kMaxIter = 32;         // 16-byte vectors per thread
+constexpr int kMaxSub = 16;          // LDS accesses per 16-byte vector (1-byte elements: 16)
+constexpr int kMaxCosetBits = 24;
+
+// LDS-staged conversion with element-wide (or common-vector-wide) LDS accesses
+// (paper Sec. 5.4 "Optimal Swizzling"; vector width = the common contiguous elements).
+//
+// Work decomposition: tiles are bundled in groups of 2^group_bits; the 2^(d+group_bits) elements
+// of a group are split into 2^coset_bits blocks of 2^block_bits elements, one block per
+// workgroup.  Element offsets below are in ELEMENTS relative to the start of the group; LDS
+// offsets are in BYTES.
+struct LdsElemArgs {
+    const void *src;
+    void *dst;
+    long long ntiles;
+    long long nblocks;
+    int d;              // index bits of one tile
+    int group_bits;     // log2 tiles per group
+    int coset_bits;     // log2 blocks per group
+    int thread_bits;    // log2 threads per workgroup
+    uint32_t coset_src[kMaxCosetBits], coset_dst[kMaxCosetBits];    // per block-index bit
+    uint32_t coset_lds_rd[kMaxCosetBits];                           // per block-index bit: XOR on LDS read addresses
+    uint32_t lane_src[kMaxThreadBits], lane_dst[kMaxThreadBits];    // per thread-index bit
+    uint32_t iter_src[kMaxIter], iter_dst[kMaxIter];                // per iteration
+    uint32_t lds_wr_lane[kMaxThreadBits], lds_rd_lane[kMaxThreadBits];
+    uint32_t lds_wr_iter[kMaxIter], lds_rd_iter[kMaxIter];
+    uint32_t lds_wr_sub[kMaxSub], lds_rd_sub[kMaxSub];              // per sub-access of a vector
+};
+
+// Wave-local gather (paper Sec. 5.5): one kernel wave per layout wave; lane = layout lane.
+struct GatherArgs {
+    const void *in;
+    const int32_t *idx;
+    void *out;
+    long long nchunks;        // number of (tile, wave) chunks = ntiles * 2^nwave
+    int nreg;                 // register bits of the layout
+    uint32_t axis_mask;       // (axis length - 1)
+    int fast;                 // 1: source lane = (lane & keep_mask) | ((idx & axis_mask) << shift)
+    uint32_t keep_mask;
+    int shift;
+    // general form: source lane = lane ^ XOR_b [bit b of (idx ^ own)] * lane_delta[b], where own
+    // is the element's own axis coordinate = own_lane(lane) ^ own_reg[r] ^ own_wave(chunk)
+    uint32_t lane_delta[6];
+    uint32_t own_lane[6];     // per lane bit: axis coordinate contribution
+    uint32_t own_reg[64];     // per register: axis coordinate contribution
+    uint32_t own_wave[16];    // per wave-index bit
+    int nwave;
+};
+
+ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,
+                          int lds_bytes, void *stream);
+ll_status launch_gather(const GatherArgs &a, int elem_bytes, void *stream);
+ll_status launch_copy(const void *src, void *dst, long long bytes, void *stream);
+
+}  // namespace ll

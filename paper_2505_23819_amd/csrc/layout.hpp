@@ -1,0 +1,43 @@
+// Internal definitions behind the opaque handles of ll.h.
+#pragma once
+#include <cstdarg>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/ll.h"
+#include "f2.hpp"
+
+struct ll_layout {
+    int n_in = 0;
+    ll_in_dim in_dims[LL_MAX_IN_DIMS] = {};
+    int n_out = 0;
+    ll_out_dim out_dims[LL_MAX_OUT_DIMS] = {};
+    int d_in = 0;
+    int d_out = 0;
+    f2::mat bases;   // d_in columns, each a d_out-bit flattened output index
+
+    int bits_of(int label) const
+    {
+        for (int i = 0; i < n_in; ++i)
+            if (in_dims[i].label == label) return in_dims[i].nbits;
+        return 0;
+    }
+    int first_bit_of(int label) const   // position of the first input bit of `label` (or d_in)
+    {
+        int pos = 0;
+        for (int i = 0; i < n_in; ++i) {
+            if (in_dims[i].label >= label) return pos;
+            pos += in_dims[i].nbits;
+        }
+        return pos;
+    }
+};
+
+namespace ll {
+
+// thread-local error text behind ll_last_error()
+ll_status fail(ll_status code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+const char *last_error();
+
+}  // namespace ll

@@ -1,0 +1,432 @@
+// Conversion planner (paper Sec. 5.4): B^-1 o A, classification, block decomposition for
+// coalesced 16-byte global access, and the swizzled LDS layout.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cstring>
+
+using f2::mat;
+using f2::vec;
+
+namespace ll {
+
+static int ilog2(unsigned x) { return 31 - __builtin_clz(x); }
+
+int lds_width_class(int access_bytes) { return access_bytes <= 4 ? 0 : (access_bytes == 8 ? 1 : 2); }
+
+static vec lane_image(const mat &lanes, uint32_t lane_vec)
+{
+    vec r = 0;
+    for (size_t b = 0; b < lanes.size(); ++b)
+        if ((lane_vec >> b) & 1) r ^= lanes[b];
+    return r;
+}
+
+static mat concat(const mat &a, const mat &b)
+{
+    mat r = a;
+    r.insert(r.end(), b.begin(), b.end());
+    return r;
+}
+
+// Wavefronts per phase of an access whose lanes of one phase span `phase_space`:
+// lanes collide when their offsets agree on the bank bits but differ above them.
+static int predict_wavefronts(const mat &m, int n, int low_bits, int row_bits, const mat &phase_space)
+{
+    mat low(m.begin(), m.begin() + low_bits);
+    mat low_seg = low;
+    low_seg.insert(low_seg.end(), m.begin() + row_bits, m.end());
+    int k = (int)f2::intersect(low_seg, phase_space, n).size();
+    int k0 = (int)f2::intersect(low, phase_space, n).size();
+    return 1 << (k - k0);
+}
+
+// Paper Sec. 5.4 "Optimal Swizzling" (and the appendix of the same name), stated for subspaces so
+// that layouts whose columns are not unit vectors are covered (the appendix's abstract lemma):
+//   U, W   the spans of (vector elements + images of the lanes served in one phase) for the
+//          write and the read access;
+//   I = U n W,  U = I + E,  W = I + F,  G = {e_i ^ f_i},  C = a complement of U + W;
+//   the segment (row-index) columns come from G u C, which meets U u W only in 0;
+//   the bank columns complete the basis.
+// The hardware constants (banks, lanes per phase) come from the LdsModel instead of the
+// 32-bank / 32-lane figures of the paper.
+mat synthesize_swizzle(int n, int v, int w, const mat &wr_lanes, const mat &rd_lanes, const LdsModel &hw,
+                       int *wf_write, int *wf_read)
+{
+    const int access = (1 << v) * w;
+    const int cls = lds_width_class(access);
+    int row_bits = ilog2((unsigned)(hw.banks[cls] * 4 / w));   // offset bits that pick (bank, byte)
+    if (row_bits > n) row_bits = n;
+    const int low_bits = std::max(v, ilog2((unsigned)std::max(1, 4 / w)));   // bits inside one access / word
+
+    mat vecs;
+    for (int b = 0; b < v; ++b) vecs.push_back(vec(1) << b);
+    mat wl, rl;     // images of the lanes served in one phase
+    for (int k = 0; k < hw.phase_dim[cls]; ++k) {
+        wl.push_back(lane_image(wr_lanes, hw.phase_basis[cls][k]));
+        rl.push_back(lane_image(rd_lanes, hw.phase_basis[cls][k]));
+    }
+    // "low" columns: the offsets inside one access or one 4-byte word, whichever is larger.  They
+    // start with the vector; for sub-word accesses they are completed with directions shared by
+    // the write and read lanes if there are any (lanes that differ only there share a word on
+    // both sides), else with write-lane directions.
+    mat low = vecs;
+    if ((int)low.size() < low_bits) {
+        const mat shared = f2::intersect(f2::extend({}, concat(vecs, wl)), f2::extend({}, concat(vecs, rl)), n);
+        for (vec x : f2::extend(vecs, concat(concat(shared, wl), f2::identity(n))))
+            if ((int)low.size() < low_bits) low.push_back(x);
+    }
+    const mat U = f2::extend({}, concat(low, wl)), W = f2::extend({}, concat(low, rl));
+    const mat I = f2::intersect(U, W, n);
+    const mat E = f2::extend(I, U), F = f2::extend(I, W);
+    mat G;
+    for (size_t i = 0; i < std::min(E.size(), F.size()); ++i) G.push_back(E[i] ^ F[i]);
+    const mat C = f2::complement(concat(U, W), n);
+
+    const int need = n - row_bits;
+    mat seg;
+    for (vec g : concat(G, C))
+        if ((int)seg.size() < need) seg.push_back(g);
+    if ((int)seg.size() < need) {
+        // conflicts are unavoidable: fill up with vectors of the write space, then anything
+        for (vec x : f2::extend(concat(low, seg), concat(concat(U, W), f2::identity(n))))
+            if ((int)seg.size() < need) seg.push_back(x);
+    }
+    // bank columns: complete low + seg to a basis, preferring the write lanes so that a write
+    // instruction of consecutive lanes stays contiguous
+    mat fixed = concat(low, seg);
+    mat bank = f2::extend(fixed, concat(concat(U, W), f2::identity(n)));
+    // Keep vectors aligned: an index whose low v bits are zero must get an offset whose low v bits
+    // are zero, i.e. every non-vector column must have zero low v bits.  Clearing them adds vector
+    // columns to the others, which changes neither the spans used above nor invertibility.
+    const vec vmask = (vec(1) << v) - 1;
+    for (vec &x : bank) x &= ~vmask;
+    for (vec &x : seg) x &= ~vmask;
+    for (size_t i = (size_t)v; i < low.size(); ++i) low[i] &= ~vmask;
+    mat m = concat(concat(low, bank), seg);
+
+    if (wf_write) *wf_write = predict_wavefronts(m, n, std::min(low_bits, row_bits), row_bits, U);
+    if (wf_read) *wf_read = predict_wavefronts(m, n, std::min(low_bits, row_bits), row_bits, W);
+    return m;
+}
+
+// ---------------------------------------------------------------------------------------------
+
+static bool same_inputs(const ll_layout *a, const ll_layout *b)
+{
+    if (a->n_in != b->n_in) return false;
+    for (int i = 0; i < a->n_in; ++i)
+        if (a->in_dims[i].label != b->in_dims[i].label || a->in_dims[i].nbits != b->in_dims[i].nbits) return false;
+    return true;
+}
+
+static int classify(const mat &p, int d, int reg_bits, int wave_first)
+{
+    bool ident = true;
+    for (int k = 0; k < d; ++k) ident &= (p[k] == (vec(1) << k));
+    if (ident) return LL_KIND_NOOP;
+    const vec reg_mask = (vec(1) << reg_bits) - 1;
+    const vec wave_mask = ((vec(1) << d) - 1) & ~((vec(1) << wave_first) - 1);
+    bool reg_only = true, intra_wave = true;
+    for (int k = 0; k < d; ++k) {
+        if (k < reg_bits) {
+            if (p[k] & ~reg_mask) reg_only = false;
+        } else if (p[k] != (vec(1) << k)) {
+            reg_only = false;
+        }
+        if (k >= wave_first) {
+            if (p[k] != (vec(1) << k)) intra_wave = false;
+        } else if (p[k] & wave_mask) {
+            intra_wave = false;
+        }
+    }
+    if (reg_only) return LL_KIND_REG_ONLY;
+    if (intra_wave) return LL_KIND_INTRA_WAVE;
+    return LL_KIND_LDS;
+}
+
+// Host-side walk through blocks of a finished plan, exactly as the kernel indexes them: every
+// global offset (16-byte aligned) and LDS address must be in range, the LDS writes must tile the
+// block without overlap, and every element read back must be stored where the conversion sends
+// it.  Block 0, the block of every single block-index bit and the block of all bits are walked;
+// the offsets of the others are XOR combinations of these.  Guards the GPU against a planner
+// mistake.
+static ll_status check_lds_elem_block(const LdsElemArgs &a, const mat &pext, int n, int vs, int v, int w, int nvec,
+                                       uint32_t cs, uint32_t cd, uint32_t cr);
+
+static ll_status check_lds_elem_tables(const LdsElemArgs &a, const mat &pext, int n, int vs, int v, int w, int nvec)
+{
+    ll_status st = check_lds_elem_block(a, pext, n, vs, v, w, nvec, 0, 0, 0);
+    uint32_t cs = 0, cd = 0, cr = 0;
+    for (int c = 0; c < a.coset_bits && st == LL_OK; ++c) {
+        st = check_lds_elem_block(a, pext, n, vs, v, w, nvec, a.coset_src[c], a.coset_dst[c], a.coset_lds_rd[c]);
+        cs ^= a.coset_src[c];
+        cd ^= a.coset_dst[c];
+        cr ^= a.coset_lds_rd[c];
+    }
+    if (st == LL_OK && a.coset_bits > 1) st = check_lds_elem_block(a, pext, n, vs, v, w, nvec, cs, cd, cr);
+    return st;
+}
+
+static ll_status check_lds_elem_block(const LdsElemArgs &a, const mat &pext, int n, int vs, int v, int w, int nvec,
+                                       uint32_t cs, uint32_t cd, uint32_t cr)
+{
+    const int threads = 1 << a.thread_bits;
+    const int nsub = 1 << (vs - v);
+    const int run = 1 << v;                       // elements per LDS access
+    const uint32_t block_bytes = (uint32_t)((1u << n) * (unsigned)w);
+    const uint64_t group_elems = 1ull << (a.d + a.group_bits);
+    std::vector<int64_t> held(block_bytes / w, -1);   // LDS element slot -> source element offset
+    auto lane_part = [&](const uint32_t *tab, int tid) {
+        uint32_t x = 0;
+        for (int b = 0; b < a.thread_bits; ++b)
+            if ((tid >> b) & 1) x ^= tab[b];
+        return x;
+    };
+    for (int tid = 0; tid < threads; ++tid) {
+        for (int i = 0; i < nvec; ++i) {
+            const uint32_t off = cs ^ lane_part(a.lane_src, tid) ^ a.iter_src[i];
+            if (off >= group_elems || (off & ((1u << vs) - 1))) return fail(LL_ERR_INVALID_ARG, "internal: bad source offset in plan");
+            for (int s = 0; s < nsub; ++s) {
+                const uint32_t addr = lane_part(a.lds_wr_lane, tid) ^ a.lds_wr_iter[i] ^ a.lds_wr_sub[s];
+                if (addr >= block_bytes || addr % (uint32_t)(run * w)) return fail(LL_ERR_INVALID_ARG, "internal: bad LDS write address in plan");
+                for (int e = 0; e < run; ++e) {
+                    int64_t &slot = held[addr / w + e];
+                    if (slot >= 0) return fail(LL_ERR_INVALID_ARG, "internal: LDS writes overlap in plan");
+                    slot = (int64_t)off + s * run + e;
+                }
+            }
+        }
+    }
+    for (int tid = 0; tid < threads; ++tid) {
+        for (int i = 0; i < nvec; ++i) {
+            const uint32_t off = cd ^ lane_part(a.lane_dst, tid) ^ a.iter_dst[i];
+            if (off >= group_elems || (off & ((1u << vs) - 1))) return fail(LL_ERR_INVALID_ARG, "internal: bad destination offset in plan");
+            for (int s = 0; s < nsub; ++s) {
+                const uint32_t addr = cr ^ lane_part(a.lds_rd_lane, tid) ^ a.lds_rd_iter[i] ^ a.lds_rd_sub[s];
+                if (addr >= block_bytes || addr % (uint32_t)(run * w)) return fail(LL_ERR_INVALID_ARG, "internal: bad LDS read address in plan");
+                for (int e = 0; e < run; ++e) {
+                    const int64_t from = held[addr / w + e];
+                    if (from < 0 || f2::apply(pext, (vec)from) != (vec)off + s * run + e)
+                        return fail(LL_ERR_INVALID_ARG, "internal: plan does not realise the conversion");
+                }
+            }
+        }
+    }
+    return LL_OK;
+}
+
+// Fill the LDS-staged plan.  P acts on d bits; elements are w bytes.
+static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
+{
+    const LdsModel hw;
+    ll_plan_desc &desc = plan->desc;
+    LdsElemArgs &a = plan->lds_elem;
+    const int vs = ilog2(16u / (unsigned)w);          // elements per 16-byte vector (log2)
+    const int tb = 8;                                 // 256 threads
+    const int n_max = ilog2(32768u / (unsigned)w);    // at most 32 KiB staged per workgroup
+    const int n_pref = ilog2(16384u / (unsigned)w);   // small tiles are bundled up to 16 KiB
+
+    // bundle small tiles so that a block holds at least one vector per thread
+    const int g = std::max(0, n_pref - d);
+    const int D = d + g;
+    if (D + ilog2((unsigned)w) > 31) return fail(LL_ERR_UNSUPPORTED, "tile of 2^%d elements of %d bytes is too large", d, w);
+    mat pext = p;
+    for (int k = d; k < D; ++k) pext.push_back(vec(1) << k);
+    mat pinv;
+    if (!f2::invert(pext, D, &pinv)) return fail(LL_ERR_INVALID_ARG, "internal: conversion matrix is singular");
+
+    // Block subspace U_k = span(e_0..e_{k-1}) + P^-1 span(e_0..e_{k-1}): both the source and the
+    // destination side of a block are made of whole runs of 2^k contiguous elements.
+    auto block_space = [&](int k) {
+        mat gens;
+        for (int j = 0; j < k; ++j) gens.push_back(vec(1) << j);
+        for (int j = 0; j < k; ++j) gens.push_back(pinv[j]);
+        return f2::extend({}, gens);
+    };
+    int k = vs;
+    while (k < D && (int)block_space(k + 1).size() <= n_max) ++k;
+    mat U = block_space(k);
+    // at least one vector per thread
+    for (int j = k; j < D && (int)U.size() < vs + tb; ++j) U = f2::extend({}, concat(U, {vec(1) << j}));
+    const int n = (int)U.size();
+    if (n < vs + tb) return fail(LL_ERR_UNSUPPORTED, "internal: block smaller than one vector per thread");
+    const int nvec_bits = n - vs - tb;
+    if ((1 << nvec_bits) > kMaxIter) return fail(LL_ERR_UNSUPPORTED, "internal: too many vectors per thread");
+
+    const vec low_mask = (vec(1) << k) - 1;
+    // source-local basis: the k contiguous bits, then the remaining directions of U with their
+    // low k bits cleared (they select the run)
+    mat us;
+    for (int j = 0; j < k; ++j) us.push_back(vec(1) << j);
+    {
+        mat cand;
+        for (vec x : U) cand.push_back(x & ~low_mask);
+        for (vec x : f2::extend(us, cand)) us.push_back(x);
+    }
+    // destination-local basis of P(U)
+    mat ud;
+    for (int j = 0; j < k; ++j) ud.push_back(vec(1) << j);
+    {
+        mat cand;
+        for (vec x : us) cand.push_back(f2::apply(pext, x) & ~low_mask);
+        for (vec x : f2::extend(ud, cand)) ud.push_back(x);
+    }
+    if ((int)us.size() != n || (int)ud.size() != n) return fail(LL_ERR_INVALID_ARG, "internal: block basis mismatch");
+    // Q = Ud^-1 P Us : block-local source index -> block-local destination index
+    f2::Basis udb;
+    for (int j = 0; j < n; ++j) udb.add(ud[j], vec(1) << j);
+    mat q(n), qinv;
+    for (int j = 0; j < n; ++j) {
+        vec tag = 0;
+        if (udb.reduce(f2::apply(pext, us[j]), &tag) != 0) return fail(LL_ERR_INVALID_ARG, "internal: block not closed");
+        q[j] = tag;
+    }
+    if (!f2::invert(q, n, &qinv)) return fail(LL_ERR_INVALID_ARG, "internal: block map singular");
+
+    // cosets of U: blocks of one tile group
+    const mat comp = f2::complement(U, D);
+    const int nco = (int)comp.size();
+    if (nco > kMaxCosetBits) return fail(LL_ERR_UNSUPPORTED, "internal: too many blocks per tile");
+
+    // common contiguous run: Q e_b = e_b for b < v
+    // (the low v bits of the destination index must be the low v bits of the source index: column
+    // b is e_b and no other column touches row b)
+    int v = 0;
+    while (v < vs && q[v] == (vec(1) << v)) ++v;
+    for (int j = 0; j < n; ++j)
+        while (v > 0 && j >= v && (q[j] & ((vec(1) << v) - 1))) --v;
+    // a block may land shifted by low bits of P h_c (see the block offsets below); the run must
+    // survive that shift as a unit
+    for (vec h : comp)
+        while (v > 0 && (f2::apply(pext, h) & ((vec(1) << v) - 1))) --v;
+
+    // LDS layout
+    mat wr_lanes, rd_lanes;
+    for (int b = 0; b < 6; ++b) {
+        wr_lanes.push_back(vec(1) << (vs + b));
+        rd_lanes.push_back(qinv[vs + b]);
+    }
+    int wfw = 1, wfr = 1;
+    const mat m = synthesize_swizzle(n, v, w, wr_lanes, rd_lanes, hw, &wfw, &wfr);
+    mat sw;
+    if (!f2::invert(m, n, &sw)) return fail(LL_ERR_INVALID_ARG, "internal: swizzle not invertible");
+    const mat swq = f2::compose(sw, qinv);    // destination-local index -> LDS element offset
+
+    // ---- kernel tables
+    std::memset(&a, 0, sizeof(a));
+    a.d = d;
+    a.group_bits = g;
+    a.coset_bits = nco;
+    a.thread_bits = tb;
+    // Block c starts at the source offset h_c (unit vectors above the runs) and lands on the coset
+    // P h_c + P U.  The destination base keeps only the bits of P h_c above the runs, so that
+    // stores stay aligned; the low bits of P h_c become a per-block XOR on the LDS read address
+    // (the reader of destination element x fetches the element that belongs at x ^ low(P h_c)).
+    for (int c = 0; c < nco; ++c) {
+        const vec ph = f2::apply(pext, comp[c]);
+        a.coset_src[c] = (uint32_t)comp[c];
+        a.coset_dst[c] = (uint32_t)(ph & ~low_mask);
+        a.coset_lds_rd[c] = (uint32_t)(f2::apply(swq, ph & low_mask) * (vec)w);
+    }
+    auto xor_bits = [](const mat &cols, int first, unsigned idx) {
+        vec r = 0;
+        for (int b = 0; (idx >> b) != 0; ++b)
+            if ((idx >> b) & 1) r ^= cols[first + b];
+        return r;
+    };
+    for (int b = 0; b < tb; ++b) {
+        a.lane_src[b] = (uint32_t)us[vs + b];
+        a.lane_dst[b] = (uint32_t)ud[vs + b];
+        a.lds_wr_lane[b] = (uint32_t)(sw[vs + b] * (vec)w);
+        a.lds_rd_lane[b] = (uint32_t)(swq[vs + b] * (vec)w);
+    }
+    for (int i = 0; i < (1 << nvec_bits); ++i) {
+        a.iter_src[i] = (uint32_t)xor_bits(us, vs + tb, (unsigned)i);
+        a.iter_dst[i] = (uint32_t)xor_bits(ud, vs + tb, (unsigned)i);
+        a.lds_wr_iter[i] = (uint32_t)(xor_bits(sw, vs + tb, (unsigned)i) * (vec)w);
+        a.lds_rd_iter[i] = (uint32_t)(xor_bits(swq, vs + tb, (unsigned)i) * (vec)w);
+    }
+    for (int s = 0; s < (1 << (vs - v)); ++s) {
+        a.lds_wr_sub[s] = (uint32_t)(xor_bits(sw, v, (unsigned)s) * (vec)w);
+        a.lds_rd_sub[s] = (uint32_t)(xor_bits(swq, v, (unsigned)s) * (vec)w);
+    }
+    plan->nvec = 1 << nvec_bits;
+
+    // ---- description
+    desc.strategy = LL_STRATEGY_LDS_ELEM;
+    desc.global_vec_bytes = 16;
+    desc.lds_write_bytes = desc.lds_read_bytes = (1 << v) * w;
+    desc.lds_bytes = (1 << n) * w;
+    desc.threads = 1 << tb;
+    desc.vectors_per_thread = 1 << nvec_bits;
+    desc.block_bits = n;
+    desc.group_bits = g;
+    desc.segment_bits = k;
+    desc.shuffle_rounds = 0;
+    desc.lds_vec_bits = v;
+    const int cls = lds_width_class((1 << v) * w);
+    desc.lds_banks = hw.banks[cls];
+    desc.lds_phase_lanes_write = desc.lds_phase_lanes_read = 1 << hw.phase_dim[cls];
+    desc.predicted_wavefronts_write = wfw;
+    desc.predicted_wavefronts_read = wfr;
+    desc.lds_write_reg_bits = desc.lds_read_reg_bits = vs + nvec_bits;
+    // access layouts in the order: element-in-vector bits, iteration bits, 6 lane bits, wave bits
+    int pos = 0;
+    auto put = [&](int local_bit) {
+        desc.lds_write[pos] = vec(1) << local_bit;
+        desc.lds_read[pos] = qinv[local_bit];
+        ++pos;
+    };
+    for (int b = 0; b < vs; ++b) put(b);
+    for (int b = 0; b < nvec_bits; ++b) put(vs + tb + b);
+    for (int b = 0; b < tb; ++b) put(vs + b);
+    for (int j = 0; j < n; ++j) desc.lds_mem[j] = m[j];
+    return check_lds_elem_tables(a, pext, n, vs, v, w, 1 << nvec_bits);
+}
+
+ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan)
+{
+    if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8)
+        return fail(LL_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8 (got %d)", elem_bytes);
+    if (!same_inputs(src, dst)) return fail(LL_ERR_DIM_MISMATCH, "source and destination layouts have different input dims");
+    if (src->d_out != dst->d_out)
+        return fail(LL_ERR_DIM_MISMATCH, "source and destination map to output spaces of %d and %d bits", src->d_out, dst->d_out);
+    for (int i = 0; i < src->n_in; ++i)
+        if (src->in_dims[i].label == LL_IN_OFFSET)
+            return fail(LL_ERR_INVALID_ARG, "conversion needs distributed layouts (register / lane / wave / tile inputs)");
+    const int d = src->d_in;
+    if (f2::rank(src->bases) < src->d_out || f2::rank(dst->bases) < dst->d_out)
+        return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
+    if (d > src->d_out) return fail(LL_ERR_NOT_INJECTIVE, "layouts with broadcasting (more input than output bits) are not supported");
+    if (d < 1) return fail(LL_ERR_INVALID_ARG, "empty layout");
+
+    // B^-1 o A (Sec. 5.4)
+    mat binv;
+    if (!f2::invert(dst->bases, d, &binv)) return fail(LL_ERR_NOT_INJECTIVE, "destination layout is not bijective");
+    const mat p = f2::compose(binv, src->bases);
+
+    // a tile label must pass through untouched
+    const int tile_first = src->first_bit_of(LL_IN_TILE);
+    for (int k = 0; k < d; ++k) {
+        const vec tile_mask = ((vec(1) << d) - 1) & ~((vec(1) << tile_first) - 1);
+        if (k >= tile_first ? p[k] != (vec(1) << k) : (p[k] & tile_mask) != 0)
+            return fail(LL_ERR_TILE_MIXED, "the conversion would move data between tiles");
+    }
+
+    ll_plan_desc &desc = plan->desc;
+    std::memset(&desc, 0, sizeof(desc));
+    desc.d = d;
+    desc.elem_bytes = elem_bytes;
+    for (int k = 0; k < d; ++k) desc.conv[k] = p[k];
+    desc.kind = classify(p, d, src->bits_of(LL_IN_REG), src->first_bit_of(LL_IN_WAVE));
+    if (desc.kind == LL_KIND_NOOP) {
+        desc.strategy = LL_STRATEGY_COPY;
+        desc.global_vec_bytes = 16;
+        desc.threads = 256;
+        return LL_OK;
+    }
+    return plan_lds_elem(p, d, elem_bytes, plan);
+}
+
+}  // namespace ll

@@ -1,0 +1,48 @@
+// Conversion planner: B^-1 o A, its classification, work decomposition and kernel tables
+// (paper Sec. 5.4).
+#pragma once
+#include "kernels.hpp"
+#include "layout.hpp"
+
+namespace ll {
+
+// LDS hardware model used by the swizzle synthesizer.  An LDS instruction of a wave is served in
+// phases; the lanes of one phase must fall in distinct banks (or read the same 4-byte word).
+// A phase is a coset of a subspace of the 6-bit lane index.  The defaults describe gfx950 as
+// measured with a two-active-lane micro-benchmark of ds_read_b32 / _b64 / _b128:
+//   <= 4 bytes: lanes 0-31 and 32-63 are served separately, 32 banks
+//      8 bytes: the same two halves, 64 banks
+//     16 bytes: four groups of 16 lanes, {l5 = const, l2^l3^l4 = const}, 64 banks
+struct LdsModel {
+    int banks[3] = {32, 64, 64};               // index: 0 = up to 4 bytes, 1 = 8 bytes, 2 = 16 bytes
+    int phase_dim[3] = {5, 5, 4};
+    uint32_t phase_basis[3][6] = {{1, 2, 4, 8, 16}, {1, 2, 4, 8, 16}, {1, 2, 12, 20}};
+};
+
+// Swizzled LDS layout for one staged block (paper Sec. 5.4 "Optimal Swizzling" and appendix).
+//   n         block bits; all vectors live in the block-local space F2^n
+//   v         log2 of the elements moved by one LDS access (the common contiguous run)
+//   w         element bytes
+//   wr_lanes  images of the 6 lane bits of a writing instruction
+//   rd_lanes  images of the 6 lane bits of a reading instruction
+// Returns the memory layout M (n columns: LDS element offset -> block-local index) with
+// M e_b = e_b for b < v.  *wf_write / *wf_read receive the predicted wavefronts per phase.
+f2::mat synthesize_swizzle(int n, int v, int w, const f2::mat &wr_lanes, const f2::mat &rd_lanes,
+                           const LdsModel &hw, int *wf_write, int *wf_read);
+
+int lds_width_class(int access_bytes);   // 0, 1, 2 for <=4, 8, 16 bytes
+
+}  // namespace ll
+
+struct ll_plan {
+    ll_plan_desc desc = {};
+    int nvec = 0;                 // 16-byte vectors per thread
+    ll::LdsElemArgs lds_elem = {};
+};
+
+namespace ll {
+ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan);
+ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long ntiles, void *stream);
+ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *in, const int32_t *idx,
+                     void *out, long long ntiles, void *stream);
+}  // namespace ll

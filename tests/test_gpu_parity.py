@@ -1,0 +1,154 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ll = pytest.importorskip("paper_2505_23819_amd")
+
+DTYPES = {1: torch.uint8, 2: torch.int16, 4: torch.int32, 8: torch.int64}
+NP_DTYPES = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}
+
+
+def layouts_of(cfg):
+    a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+    b = None
+    if cfg.dst_bases is not None:
+        b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
+    return a, b
+
+
+def run_convert(plan, src_bits: np.ndarray, d: int) -> np.ndarray:
+    """src_bits: host array of unsigned ints (raw bits).  Returns the converted image."""
+    w = src_bits.itemsize
+    ntiles = src_bits.size >> d
+    src = torch.from_numpy(src_bits.view({1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}[w])).cuda()
+    dst = torch.full_like(src, 0x5A if w == 1 else 0x5A5A)      # poison: every slot must be written
+    ll.ll_convert(plan, src, dst, ntiles)
+    torch.cuda.synchronize()
+    return dst.cpu().numpy().view(NP_DTYPES[w])
+
+
+def random_invertible(rng, d):
+    while True:
+        cols = [int(rng.integers(0, 1 << d)) for _ in range(d)]
+        seen = {0}
+        for c in cols:
+            seen |= {x ^ c for x in seen}
+        if len(seen) == 1 << d:
+            return cols
+
+
+@pytest.mark.parametrize("cid,ntiles", [(1, 1), (2, 3), (3, 5), (4, 2), (2, 1), (3, 1), (4, 1)])
+def test_convert_configs_small(cid, ntiles):
+    cfg = wl.config(cid)
+    a, b = layouts_of(cfg)
+    plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+    src = wl.to_numpy_bits(cfg.gen_data(0, ntiles))
+    got = run_convert(plan, src, cfg.d)
+    want = oracle.convert(cfg.src_bases, cfg.dst_bases, src)
+    assert np.array_equal(got, want), f"config {cid}: {np.count_nonzero(got != want)} mismatches"
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+@pytest.mark.parametrize("d,nreg,nlane", [(8, 2, 5), (10, 2, 6), (12, 4, 6), (13, 3, 6), (15, 5, 6)])
+def test_convert_random_xor_layouts(w, d, nreg, nlane):
+    rng = np.random.default_rng(1000 * w + d)
+    nwave = d - nreg - nlane
+    for trial in range(3):
+        ca, cb = random_invertible(rng, d), random_invertible(rng, d)
+        a = ll.distributed_layout(nreg, nlane, nwave, [d], ca)
+        b = ll.distributed_layout(nreg, nlane, nwave, [d], cb)
+        plan = ll.ll_plan_convert(a, b, w)
+        ntiles = int(rng.integers(1, 40))            # ragged: not a multiple of the tile group
+        src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+        got = run_convert(plan, src, d)
+        want = oracle.convert(ca, cb, src)
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_convert_random_permutation_layouts(w):
+    rng = np.random.default_rng(77 + w)
+    for d, nreg, nlane in [(9, 3, 6), (12, 4, 6), (14, 6, 6), (16, 6, 6)]:
+        nwave = d - nreg - nlane
+        ca = [1 << int(p) for p in rng.permutation(d)]
+        cb = [1 << int(p) for p in rng.permutation(d)]
+        a = ll.distributed_layout(nreg, nlane, nwave, [d], ca)
+        b = ll.distributed_layout(nreg, nlane, nwave, [d], cb)
+        plan = ll.ll_plan_convert(a, b, w)
+        ntiles = int(rng.integers(1, 9))
+        src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+        assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src))
+
+
+def test_convert_identity_is_copy_and_zero_tiles():
+    cfg = wl.config(1)
+    a, _ = layouts_of(cfg)
+    plan = ll.ll_plan_convert(a, a, 4)
+    assert plan.info()["kind_name"] == "noop"
+    src = wl.to_numpy_bits(cfg.gen_data(0, 3))
+    assert np.array_equal(run_convert(plan, src, cfg.d), src)
+    ll.ll_convert(plan, 0, 0, 0)                       # ntiles == 0: nothing is touched
+
+
+def run_gather(layout, axis, inp_bits: np.ndarray, idx: np.ndarray, d: int) -> np.ndarray:
+    w = inp_bits.itemsize
+    ntiles = inp_bits.size >> d
+    tin = torch.from_numpy(inp_bits.view({1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}[w])).cuda()
+    tidx = torch.from_numpy(idx).cuda()
+    tout = torch.full_like(tin, 0x5A if w == 1 else 0x5A5A)
+    ll.ll_gather(layout, axis, w, tin, tidx, tout, ntiles)
+    torch.cuda.synchronize()
+    return tout.cpu().numpy().view(NP_DTYPES[w])
+
+
+@pytest.mark.parametrize("ntiles", [1, 3])
+def test_gather_config5_small(ntiles):
+    cfg = wl.config(5)
+    layout, _ = layouts_of(cfg)
+    inp = wl.to_numpy_bits(cfg.gen_data(0, ntiles))
+    idx = cfg.gen_idx(0, ntiles).numpy()
+    got = run_gather(layout, cfg.axis, inp, idx, cfg.d)
+    want = oracle.gather(cfg.src_bases, cfg.out_dim_bits, cfg.axis, inp, idx)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+@pytest.mark.parametrize("nreg,nwave,axis_bits", [(2, 0, 6), (3, 1, 4), (4, 2, 6), (5, 1, 3), (1, 3, 5)])
+def test_gather_random_lane_axis(w, nreg, nwave, axis_bits):
+    """Axis bits live on an arbitrary subset of the lane bits, mixed by XOR with other lane bits;
+    the other logical bits are spread over registers, the remaining lanes and waves."""
+    if (1 << nreg) * w < 4:
+        pytest.skip("fewer than 4 bytes per lane")
+    rng = np.random.default_rng(31 * w + nreg + 7 * nwave + axis_bits)
+    d = nreg + 6 + nwave
+    other_bits = d - axis_bits
+    dims = [axis_bits, other_bits]                    # axis is dim 0 (upper logical bits)
+    # lane part: a random invertible 6x6 map of lane bits onto [axis bits | 6 - axis_bits others]
+    lane_mix = random_invertible(rng, 6)
+    others = list(rng.permutation(other_bits))        # logical "other" bit taken by each non-axis hw bit
+    bases = [0] * d
+    lane_targets = [1 << (other_bits + k) for k in range(axis_bits)] + \
+                   [1 << int(others[k]) for k in range(6 - axis_bits)]
+    for b in range(6):
+        v = 0
+        for k in range(6):
+            if (lane_mix[b] >> k) & 1:
+                v ^= lane_targets[k]
+        bases[nreg + b] = v
+    rest = [1 << int(o) for o in others[6 - axis_bits:]]
+    for k, hw_bit in enumerate(list(range(nreg)) + list(range(nreg + 6, d))):
+        bases[hw_bit] = rest[k]
+    layout = ll.distributed_layout(nreg, 6, nwave, dims, bases)
+    ntiles = 3
+    inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+    idx = rng.integers(0, 1 << axis_bits, size=ntiles << d, dtype=np.int32)
+    idx[::17] += 1 << axis_bits                        # out-of-range entries wrap
+    got = run_gather(layout, 0, inp, idx, d)
+    want = oracle.gather(bases, dims, 0, inp, idx)
+    assert np.array_equal(got, want)
