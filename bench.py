@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the layout-conversion / gather hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--only-main]
+
+A step is one pass of the headline workload (benchmark configs[1]: 8192 tiles of
+128x128 bf16 transposed through LDS) with inputs already resident in HBM.  The
+JSON line printed at the end carries the whole-job GB/s (read + write algorithmic
+bytes), a roofline object for the dominant kernel, the CPU oracle timed on a
+bounded sample, and per-config figures for all five configurations next to a
+plain 16-byte copy at the same footprint.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--only-main", action="store_true", help="skip the per-config table")
+    ap.add_argument("--workload", type=int, default=2, help="config id timed as the main line (default 2)")
+    ap.add_argument("--table-steps", type=int, default=30, help="launches per config in the per-config table")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; tiles are independent, so more GPUs would each "
+              "take a tile range with no communication, but no multi-GPU path is built or measured. "
+              "Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2505_23819_amd as ll
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    dev = "cuda"
+
+    def make_case(cfg, nsets):
+        """Device buffers (nsets rotating copies) and a launcher for one configuration."""
+        a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+        sets = []
+        for s in range(nsets):
+            x = cfg.gen_data(0, cfg.ntiles, dev) if s == 0 else sets[0][0].clone()
+            if cfg.kind == "gather":
+                idx = cfg.gen_idx(0, cfg.ntiles, dev) if s == 0 else sets[0][1].clone()
+                sets.append((x, idx, torch.empty_like(x)))
+            else:
+                sets.append((x, None, torch.empty_like(x)))
+        if cfg.kind == "gather":
+            info = {"strategy_name": "gather", "kind_name": "gather"}
+
+            def launch(k):
+                x, idx, out = sets[k % nsets]
+                ll.ll_gather(a, cfg.axis, cfg.elem_bytes, x, idx, out, cfg.ntiles)
+        else:
+            b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
+            plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+            info = plan.info()
+
+            def launch(k, plan=plan):
+                x, _, out = sets[k % nsets]
+                ll.ll_convert(plan, x, out, cfg.ntiles)
+        return launch, info, sets
+
+    def time_launches(launch, steps, warmup):
+        """Returns (wall ms per step over exactly `steps` steps, mean per-launch ms from events)."""
+        for k in range(warmup):
+            launch(k)
+        torch.cuda.synchronize()
+        # one HIP event between consecutive launches, on the stream the kernels run on (torch's
+        # current stream is the stream handed to the library): launch k lasts from event k to k+1
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        evs[0].record()
+        for k in range(steps):
+            launch(k)
+            evs[k + 1].record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        per = [evs[k].elapsed_time(evs[k + 1]) for k in range(steps)]
+        return wall_ms, statistics.mean(per), statistics.median(per), min(per)
+
+    def copy_ceiling(nbytes_each, steps=20):
+        """Plain 16-byte vector copy moving the same read + write footprint."""
+        n = max(16, (nbytes_each // 16) * 16)
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+        dsts = [torch.empty_like(src) for _ in range(2)]
+        _, mean_ms, med_ms, _ = time_launches(lambda k: ll.ll_copy(src, dsts[k % 2], n), steps, 3)
+        return 2.0 * n / med_ms / 1e6
+
+    main_cfg = wl.config(args.workload)
+    launch, info, sets = make_case(main_cfg, nsets=2)
+    wall_ms, mean_ms, med_ms, min_ms = time_launches(launch, args.steps, args.warmup)
+    alg_bytes = main_cfg.algorithmic_bytes()
+    value = alg_bytes / wall_ms / 1e6                      # GB/s over the timed region (wall clock)
+    achieved = alg_bytes / mean_ms / 1e6                   # GB/s of the kernel itself (HIP events)
+    ceiling = copy_ceiling(alg_bytes // 2)
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_config%d.txt" % main_cfg.cid)
+    if os.path.exists(tpath):                              # measured separately with rocprofv3 --pmc
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split()[1])
+
+    result = {
+        "metric": "layout-conversion GB/s (read+write) vs HBM peak",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {1: "u8", 2: "u16", 4: "u32", 8: "u64"}[main_cfg.elem_bytes] + " (raw bits moved; elements are "
+                 + str(main_cfg.dtype).replace("torch.", "") + ")",
+        "data": "synthetic",
+        "config": {"workload": "config %d: %s, %d tiles of 2^%d elements x %d B" %
+                               (main_cfg.cid, main_cfg.name, main_cfg.ntiles, main_cfg.d, main_cfg.elem_bytes),
+                   "kernel": info["strategy_name"], "class": info["kind_name"],
+                   "buffer_sets_rotated": 2},
+        "fraction_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "copy_kernel_ceiling_GBps": round(ceiling, 1),
+        "fraction_of_copy_ceiling": round(achieved / ceiling, 4),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "kernel": info["strategy_name"], "launch_ms_mean": round(mean_ms, 5),
+                     "launch_ms_median": round(med_ms, 5), "launch_ms_min": round(min_ms, 5),
+                     "algorithmic_bytes_per_launch": alg_bytes},
+    }
+    del sets, launch
+    torch.cuda.empty_cache()
+
+    if not args.only_main:
+        table = []
+        for cfg in wl.configs():
+            nsets = 2 if cfg.algorithmic_bytes() < (1 << 30) else 1
+            l, inf, s = make_case(cfg, nsets)
+            steps = args.table_steps if cfg.cid != 1 else max(args.table_steps, 200 if args.table_steps >= 30 else 0)
+            w_ms, m_ms, md_ms, mn_ms = time_launches(l, steps, 3)
+            ab = cfg.algorithmic_bytes()
+            entry = {"config": cfg.cid, "name": cfg.name, "kernel": inf["strategy_name"], "class": inf["kind_name"],
+                     "algorithmic_bytes": ab, "us_median": round(md_ms * 1e3, 2), "us_min": round(mn_ms * 1e3, 2),
+                     "GBps": round(ab / md_ms / 1e6, 1), "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)}
+            if "lds_write_bytes" in inf:
+                entry.update({"lds_access_bytes": inf["lds_write_bytes"], "lds_bytes": inf["lds_bytes"],
+                              "predicted_wavefronts": [inf["predicted_wavefronts_write"], inf["predicted_wavefronts_read"]]})
+            del s, l
+            torch.cuda.empty_cache()
+            if cfg.cid != 1:
+                entry["copy_GBps_same_footprint"] = round(copy_ceiling(ab // 2), 1)
+            table.append(entry)
+        result["per_config"] = table
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(main_cfg)
+
+    print(json.dumps(result))
+    return 0
+
+
+def cpu_baseline(cfg):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+    import workloads as wl
+    if cfg.kind == "gather":
+        nt = 256
+        x, idx = wl.to_numpy_bits(cfg.gen_data(0, nt)), cfg.gen_idx(0, nt).numpy()
+        t0 = time.perf_counter()
+        oracle.gather(cfg.src_bases, cfg.out_dim_bits, cfg.axis, x, idx)
+        dt = time.perf_counter() - t0
+        return {"value": round(cfg.algorithmic_bytes(nt) / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                "sample": "oracle_gather on the first %d of %d tiles, single thread" % (nt, cfg.ntiles)}
+    nt_table = min(cfg.ntiles, max(1, (512 << 20) // (cfg.tile_elems * cfg.elem_bytes)))   # at most 512 MiB of input
+    nt_plain = min(cfg.ntiles, max(1, (48 << 20) // (cfg.tile_elems * cfg.elem_bytes)))    # about 48 MiB of input
+    src = wl.to_numpy_bits(cfg.gen_data(0, nt_table))
+    oracle.convert(cfg.src_bases, cfg.dst_bases, src[: cfg.tile_elems])                    # builds / loads the C library
+    best, threads = None, 1
+    for _ in range(3):
+        t0 = time.perf_counter()
+        _, threads = oracle.convert(cfg.src_bases, cfg.dst_bases, src, table=True)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    t0 = time.perf_counter()
+    oracle.convert(cfg.src_bases, cfg.dst_bases, src[: nt_plain * cfg.tile_elems])
+    dt_plain = time.perf_counter() - t0
+    return {"value": round(cfg.algorithmic_bytes(nt_table) / best / 1e9, 3), "unit": "GB/s", "cores": threads,
+            "kind": "oracle",
+            "sample": "oracle_convert_table (tabulated map, OpenMP over tiles) on the first %d of %d tiles, best of 3"
+                      % (nt_table, cfg.ntiles),
+            "plain_single_thread_GBps": round(cfg.algorithmic_bytes(nt_plain) / dt_plain / 1e9, 4),
+            "plain_sample": "oracle_convert (bit-by-bit definition) on the first %d tiles, 1 thread" % nt_plain}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

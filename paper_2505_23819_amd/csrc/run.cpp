@@ -56,10 +56,11 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
     std::memset(&a, 0, sizeof(a));
     // Moving one step along axis bit b moves the hardware index by L^-1(e_b): it must stay inside
     // the wave (Sec. 5.5: the warp part of the layout restricted to the axis vanishes).
+    for (int b = 0; b < na; ++b)
+        if (linv[axis_shift + b] & ~(reg_mask | lane_mask))
+            return fail(LL_ERR_AXIS_NOT_IN_WAVE, "axis bit %d crosses waves: the gather axis must lie inside one wave", b);
     for (int b = 0; b < na; ++b) {
         const vec delta = linv[axis_shift + b];
-        if (delta & ~(reg_mask | lane_mask))
-            return fail(LL_ERR_AXIS_NOT_IN_WAVE, "axis bit %d crosses waves: the gather axis must lie inside one wave", b);
         if (delta & reg_mask)
             return fail(LL_ERR_UNSUPPORTED, "axis bit %d lives in registers; only lane-resident axes are implemented", b);
         a.lane_delta[b] = (uint32_t)((delta & lane_mask) >> nreg);

@@ -1,0 +1,205 @@
+"""The conversion planner and swizzle synthesizer, checked on the CPU by invariants and against
+the oracle's exhaustive wavefront enumerator (many swizzles are equally valid, so plans are not
+compared bit for bit).  No GPU needed: planning is host-only."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+ll = pytest.importorskip("paper_2505_23819_amd")
+
+
+def span(vectors):
+    s = {0}
+    for v in vectors:
+        s |= {x ^ v for x in s}
+    return s
+
+
+def random_invertible(rng, d):
+    while True:
+        cols = [int(rng.integers(0, 1 << d)) for _ in range(d)]
+        if len(span(cols)) == 1 << d:
+            return cols
+
+
+def gfx950_phases(access_bytes):
+    """Lanes served together by one LDS instruction, as measured on gfx950: halves of the wave
+    for accesses up to 8 bytes; for 16 bytes the groups {l5, l2^l3^l4}."""
+    if access_bytes <= 8:
+        return [l >> 5 for l in range(64)]
+    return [(l >> 5) * 2 + (((l >> 2) ^ (l >> 3) ^ (l >> 4)) & 1) for l in range(64)]
+
+
+def plan_of(cfg):
+    a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+    b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
+    return ll.ll_plan_convert(a, b, cfg.elem_bytes)
+
+
+def test_conversion_matrix_equals_tabulated_composition():
+    # B^-1 o A (Sec. 5.4) against the oracle's table-based inverse
+    for cid in (1, 2, 3, 4):
+        cfg = wl.config(cid)
+        conv = plan_of(cfg).info()["conv"]
+        inv_b = oracle.inverse_table(cfg.dst_bases)
+        for k in range(cfg.d):
+            assert conv[k] == int(inv_b[cfg.src_bases[k]])
+
+
+def test_classification_of_the_configs():
+    kinds = {cid: plan_of(wl.config(cid)).info()["kind_name"] for cid in (1, 2, 3, 4)}
+    assert kinds == {1: "lds", 2: "lds", 3: "intra_wave", 4: "lds"}
+
+
+def test_classification_rules():
+    # Sec. 5.4: identity -> nothing to do; only register columns differ -> intra-thread;
+    # wave part identity -> intra-warp; otherwise shared memory.
+    d, nreg, nlane, nwave = 12, 4, 6, 2
+    ident = [1 << k for k in range(d)]
+    mk = lambda cols: ll.distributed_layout(nreg, nlane, nwave, [d], cols)
+    kind = lambda a, b: ll.ll_plan_convert(mk(a), mk(b), 4).info()["kind_name"]
+    assert kind(ident, ident) == "noop"
+    regs_swapped = [2, 1] + ident[2:]
+    assert kind(ident, regs_swapped) == "reg_only"
+    reg_xor = [1, 3] + ident[2:]                       # register bit 1 -> r0 ^ r1: still registers only
+    assert kind(ident, reg_xor) == "reg_only"
+    lane_reg = ident[:]
+    lane_reg[0], lane_reg[5] = lane_reg[5], lane_reg[0]
+    assert kind(ident, lane_reg) == "intra_wave"
+    wave_lane = ident[:]
+    wave_lane[10], lane5 = wave_lane[5], wave_lane[10]
+    wave_lane[5] = lane5
+    assert kind(ident, wave_lane) == "lds"
+    reg_into_wave = ident[:]
+    reg_into_wave[0] = 1 | (1 << 11)                   # a register bit leaks into a wave bit
+    assert kind(ident, reg_into_wave) == "lds"
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_swizzle_of_configs_is_conflict_free_by_enumeration(cid):
+    info = plan_of(wl.config(cid)).info()
+    assert info["strategy_name"] in ("lds_elem", "lds_vec")
+    n = info["block_bits"]
+    assert len(span(info["lds_mem"])) == 1 << n        # M is invertible
+    for side in ("lds_write", "lds_read"):
+        mx, tot, nph = oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6,
+                                         info["elem_bytes"], info["lds_vec_bits"], info["lds_banks"],
+                                         gfx950_phases(info["lds_write_bytes"]))
+        assert mx == 1 and tot == nph
+    assert info["predicted_wavefronts_write"] == 1 and info["predicted_wavefronts_read"] == 1
+
+
+def test_unswizzled_staging_of_config1_conflicts():
+    # control: the same accesses against a linear (unswizzled) LDS layout do collide
+    info = plan_of(wl.config(1)).info()
+    n = info["block_bits"]
+    linear = [1 << k for k in range(n)]
+    worst = max(oracle.wavefronts(linear, info[side], info["lds_write_reg_bits"], 6, 4, 0, 32,
+                                  gfx950_phases(4))[0] for side in ("lds_write", "lds_read"))
+    assert worst > 1
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_random_layouts_plan_and_swizzle(w):
+    rng = np.random.default_rng(100 + w)
+    for d, nreg in [(8, 2), (10, 2), (12, 4), (13, 3), (15, 5), (16, 6)]:
+        for trial in range(4):
+            if trial % 2:
+                ca = [1 << int(p) for p in rng.permutation(d)]
+                cb = [1 << int(p) for p in rng.permutation(d)]
+            else:
+                ca, cb = random_invertible(rng, d), random_invertible(rng, d)
+            nlane = min(6, d - nreg)
+            a = ll.distributed_layout(nreg, nlane, d - nreg - nlane, [d], ca)
+            b = ll.distributed_layout(nreg, nlane, d - nreg - nlane, [d], cb)
+            info = ll.ll_plan_convert(a, b, w).info()      # runs the library's own table walk too
+            if info["strategy_name"] not in ("lds_elem", "lds_vec"):
+                continue
+            assert info["lds_bytes"] == (1 << info["block_bits"]) * w <= 64 * 1024
+            assert info["threads"] * info["vectors_per_thread"] * 16 == info["lds_bytes"]
+            assert (1 << info["segment_bits"]) * w >= 16
+            for side in ("lds_write", "lds_read"):
+                mx, tot, nph = oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6, w,
+                                                 info["lds_vec_bits"], info["lds_banks"],
+                                                 gfx950_phases(info["lds_write_bytes"]))
+                assert mx == 1, (w, d, trial, side)
+
+
+def test_common_vector_is_kept_wide():
+    # both layouts keep register bits 0,1 on logical bits 0,1 (4-byte elements): 16-byte LDS accesses
+    d = 12
+    rng = np.random.default_rng(3)
+    rest_a = [1 << int(p) for p in (rng.permutation(d - 2) + 2)]
+    rest_b = [1 << int(p) for p in (rng.permutation(d - 2) + 2)]
+    a = ll.distributed_layout(4, 6, 2, [d], [1, 2] + rest_a)
+    b = ll.distributed_layout(4, 6, 2, [d], [1, 2] + rest_b)
+    info = ll.ll_plan_convert(a, b, 4).info()
+    if info["strategy_name"] == "lds_elem":
+        assert info["lds_vec_bits"] == 2 and info["lds_write_bytes"] == 16
+        for side in ("lds_write", "lds_read"):
+            assert oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6, 4, 2, 64,
+                                     gfx950_phases(16))[0] == 1
+
+
+def test_plan_errors():
+    d = 8
+    ident = [1 << k for k in range(d)]
+    a = ll.distributed_layout(2, 5, 1, [d], ident)
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_plan_convert(a, ll.distributed_layout(3, 5, 0, [d], ident), 4)
+    assert e.value.status == ll.LL_ERR_DIM_MISMATCH
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_plan_convert(a, a, 3)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG
+    singular = ident[:]
+    singular[3] = singular[2]
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_plan_convert(a, ll.distributed_layout(2, 5, 1, [d], singular), 4)
+    assert e.value.status == ll.LL_ERR_NOT_SURJECTIVE
+    wide = ll.distributed_layout(3, 5, 1, [d], [1, 2, 0, 4, 8, 16, 32, 64, 128])     # broadcast register bit
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_plan_convert(wide, wide, 4)
+    assert e.value.status == ll.LL_ERR_NOT_INJECTIVE
+    # tile label must pass through
+    t_in = [(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 5), (ll.LL_IN_TILE, 1)]
+    ta = ll.ll_layout_create(t_in, [d], ident)
+    mixed = ident[:]
+    mixed[0], mixed[7] = mixed[7], mixed[0]
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_plan_convert(ta, ll.ll_layout_create(t_in, [d], mixed), 4)
+    assert e.value.status == ll.LL_ERR_TILE_MIXED
+
+
+def test_device_entry_points_reject_bad_arguments_before_launch():
+    cfg = wl.config(1)
+    plan = plan_of(cfg)
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_convert(plan, 0, 0, 1, stream=0)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG                 # null pointers
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_convert(plan, 4096 + 4, 1 << 20, 1, stream=0)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG                 # misaligned
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_convert(plan, 4096, 4096 + 1024, 1, stream=0)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG                 # overlap
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_convert(plan, 4096, 1 << 20, -1, stream=0)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG
+    ll.ll_convert(plan, 0, 0, 0, stream=0)                         # ntiles == 0: no-op
+
+    g = wl.config(5)
+    lay = ll.distributed_layout(g.nreg, g.nlane, g.nwave, g.out_dim_bits, g.src_bases)
+    ll.ll_gather(lay, 0, 2, 0, 0, 0, 0, stream=0)                  # valid layout, nothing to move
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_gather(lay, 1, 2, 0, 0, 0, 0, stream=0)              # columns live in registers and waves
+    assert e.value.status == ll.LL_ERR_AXIS_NOT_IN_WAVE
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_gather(lay, 2, 2, 0, 0, 0, 0, stream=0)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG
+    # axis on register bits only: inside the wave, but not implemented
+    regaxis = ll.distributed_layout(2, 6, 0, [2, 6], [1 << 6, 1 << 7] + [1 << k for k in range(6)])
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_gather(regaxis, 0, 4, 0, 0, 0, 0, stream=0)
+    assert e.value.status == ll.LL_ERR_UNSUPPORTED
