@@ -2,6 +2,8 @@
 // LDS staging or cross-lane shuffles in between, no MFMA.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "../../include/ll.h"
 #include "kernels.hpp"
 #include "layout.hpp"
@@ -20,6 +22,23 @@ static __device__ __forceinline__ void store16(void *p, u32x4 v)
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
 }
 
+// Raw buffer access (16 bytes per lane) with streaming cache policy.  The descriptor covers
+// [base, base + bytes): loads beyond it return zero and stores beyond it are dropped by the
+// hardware, which is how ragged tails are handled without branches.
+constexpr int kStream = 16 | 2;   // cache-policy bits "sc1 nt": stream through, do not keep in cache
+static __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+static __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kStream);
+}
+static __device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, u32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, kStream);
+}
+
 static ll_status check_launch(const char *what)
 {
     hipError_t e = hipGetLastError();
@@ -31,22 +50,19 @@ static ll_status check_launch(const char *what)
 // plain copy (bandwidth yardstick, and the NOOP conversion)
 // ---------------------------------------------------------------------------------------------
 
-constexpr int kCopyVec = 4;   // vectors per thread
+// One 16-byte vector per thread with the streaming cache policy: the fastest plain copy found on
+// MI355X (many short-lived waves; about 32 KiB in flight per CU).
+constexpr int kCopyVec = 1;
 
-__global__ __launch_bounds__(256) void k_copy(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, long long nvec)
+__global__ __launch_bounds__(256) void k_copy(const void *__restrict__ src, void *__restrict__ dst, long long nvec)
 {
-    const long long base = (long long)blockIdx.x * (kCopyVec * 256) + threadIdx.x;
-    u32x4 r[kCopyVec];
-#pragma unroll
-    for (int i = 0; i < kCopyVec; ++i) {
-        const long long k = base + i * 256;
-        if (k < nvec) r[i] = load16(src + k);
-    }
-#pragma unroll
-    for (int i = 0; i < kCopyVec; ++i) {
-        const long long k = base + i * 256;
-        if (k < nvec) store16(dst + k, r[i]);
-    }
+    // descriptors cover this workgroup's 4 KiB (or the tail): out-of-range lanes do nothing
+    const long long first = (long long)blockIdx.x * 256;
+    const long long left = nvec - first;
+    const uint32_t bytes = (uint32_t)(left >= 256 ? 256 : left) * 16u;
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(static_cast<const unsigned char *>(src) + first * 16, bytes);
+    const __amdgpu_buffer_rsrc_t rd = make_rsrc(static_cast<unsigned char *>(dst) + first * 16, bytes);
+    buf_store16(rd, threadIdx.x * 16, buf_load16(rs, threadIdx.x * 16));
 }
 
 ll_status launch_copy(const void *src, void *dst, long long bytes, void *stream)
@@ -55,8 +71,7 @@ ll_status launch_copy(const void *src, void *dst, long long bytes, void *stream)
     const long long per = kCopyVec * 256;
     const long long grid = (nvec + per - 1) / per;
     if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "copy of %lld bytes is too large for one launch", bytes);
-    hipLaunchKernelGGL(k_copy, dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst), nvec);
+    hipLaunchKernelGGL(k_copy, dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(stream), src, dst, nvec);
     return check_launch("copy kernel launch");
 }
 
@@ -138,16 +153,19 @@ __global__ __launch_bounds__(256) void k_lds_elem(const LdsElemArgs a)
     const int gshift = a.d + a.group_bits;
     const unsigned char *sbase = static_cast<const unsigned char *>(a.src) + (((size_t)group << gshift) * W);
     unsigned char *dbase = static_cast<unsigned char *>(a.dst) + (((size_t)group << gshift) * W);
-    // tiles of this group that exist (the last group may be partly empty)
+    // tiles of this group that exist (the last group may be partly empty): they are a prefix of the
+    // group, and the buffer descriptors end there
     const long long left = a.ntiles - (group << a.group_bits);
     const uint32_t tiles_here = left > (1ll << a.group_bits) ? (1u << a.group_bits) : (uint32_t)left;
+    const uint32_t valid_bytes = (tiles_here << a.d) * W;
+    const __amdgpu_buffer_rsrc_t srsrc = make_rsrc(sbase, valid_bytes);
+    const __amdgpu_buffer_rsrc_t drsrc = make_rsrc(dbase, valid_bytes);
 
     uint32_t r[NV][4];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const uint32_t off = cs ^ ls ^ a.iter_src[i];
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if ((off >> a.d) < tiles_here) v = load16(sbase + (size_t)off * W);
+        const u32x4 v = buf_load16(srsrc, off * W);
         r[i][0] = v.x; r[i][1] = v.y; r[i][2] = v.z; r[i][3] = v.w;
     }
 #pragma unroll
@@ -166,24 +184,21 @@ __global__ __launch_bounds__(256) void k_lds_elem(const LdsElemArgs a)
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const uint32_t off = cd ^ ld ^ a.iter_dst[i];
-        if ((off >> a.d) < tiles_here) {
-            u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
-            store16(dbase + (size_t)off * W, v);
-        }
+        const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
+        buf_store16(drsrc, off * W, v);
     }
 }
 
 template <int W, int NV, int V>
 static ll_status launch_lds_elem_t(const LdsElemArgs &a, int lds_bytes, hipStream_t stream)
 {
-    static bool attr_set = false;
-    if (!attr_set && lds_bytes > 48 * 1024) {
+    static const int pad = getenv("LL_LDS_PAD") ? atoi(getenv("LL_LDS_PAD")) : 0;   // experiment knob: caps occupancy
+    if (lds_bytes + pad > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lds_elem<W, NV, V>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-        attr_set = true;
     }
-    hipLaunchKernelGGL((k_lds_elem<W, NV, V>), dim3((unsigned)a.nblocks), dim3(256), (size_t)lds_bytes, stream, a);
+    hipLaunchKernelGGL((k_lds_elem<W, NV, V>), dim3((unsigned)a.nblocks), dim3(256), (size_t)(lds_bytes + pad), stream, a);
     return check_launch("LDS conversion kernel launch");
 }
 
@@ -323,6 +338,155 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a)
     }
 }
 
+// Same gather with every global access fully coalesced.  A lane no longer stands for a layout lane:
+// lane k of a load or store instruction takes the k-th 16-byte (or 8-byte) piece of the chunk.  The
+// source values of the wave's chunk are staged in a wave-private LDS region, one row per layout
+// lane, and each output element is fetched with one LDS read at the row its index names.  This is
+// the same crossbar the lane shuffle uses (ds_bpermute reads a 64-dword row through it); the
+// condition that lets it run without workgroup synchronisation is the one of Sec. 5.5: the axis
+// stays inside the wave.  Rows are XOR-swizzled so that reads of one register from 32 different
+// rows fall in 32 different banks (random indices then collide only as often as random lanes do).
+//   unit      the 4- or 8-byte word an element lives in
+//   row s     holds RU units; unit q of row s is stored at unit address s*RU + (q ^ f(s))
+template <int W, int NREG>
+__global__ __launch_bounds__(256) void k_gather_staged(const GatherArgs a)
+{
+    constexpr int NE = 1 << NREG;                 // elements per layout lane
+    constexpr int PL = NE * W;                    // bytes per layout lane (row), >= 16
+    constexpr int M = PL / 16;                    // 16-byte vectors per row
+    constexpr int U = (W == 8) ? 8 : 4;           // unit bytes
+    constexpr int RU = PL / U;                    // units per row
+    constexpr int UV = 16 / U;                    // units per 16-byte vector
+    constexpr int EPS = (W == 8) ? 2 : 4;         // elements per lane per step (one idx load)
+    constexpr int NSTEP = NE / EPS;               // steps per lane: 64 * NE elements / (64 * EPS)
+    constexpr int LOG_M = (M == 1) ? 0 : (M == 2) ? 1 : (M == 4) ? 2 : (M == 8) ? 3 : 4;
+    constexpr int FS_SHIFT = (RU >= 32) ? 0 : (RU == 16) ? 1 : (RU == 8) ? 2 : (RU == 4) ? 3 : (RU == 2) ? 4 : 5;
+    constexpr int FS_MASK = (RU >= 32) ? 31 : RU - 1;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long chunk0 = (long long)blockIdx.x * 4;
+    const long long chunk = chunk0 + wave;
+    const long long left = a.nchunks - chunk0;
+    const uint32_t chunks_here = left >= 4 ? 4u : (left > 0 ? (uint32_t)left : 0u);
+    // descriptors cover the (up to four) chunks of this workgroup: out-of-range lanes read zero and
+    // write nothing
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(static_cast<const unsigned char *>(a.in) + (size_t)chunk0 * 64 * PL, chunks_here * 64 * PL);
+    const __amdgpu_buffer_rsrc_t rix = make_rsrc(reinterpret_cast<const unsigned char *>(a.idx) + (size_t)chunk0 * 64 * NE * 4, chunks_here * 64 * NE * 4);
+    const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (size_t)chunk0 * 64 * PL, chunks_here * 64 * PL);
+    unsigned char *my = lds + wave * (64 * PL);
+
+    // issue all loads first
+    u32x4 vin[M];
+#pragma unroll
+    for (int j = 0; j < M; ++j) vin[j] = buf_load16(rin, wave * (64 * PL) + (j * 64 + lane) * 16);
+    uint32_t idx[NSTEP][EPS];
+#pragma unroll
+    for (int j = 0; j < NSTEP; ++j) {
+        const uint32_t off = wave * (64 * NE * 4) + (j * 64 + lane) * (EPS * 4);
+        if constexpr (EPS == 4) {
+            const u32x4 v = buf_load16(rix, off);
+            idx[j][0] = v.x; idx[j][1] = v.y; idx[j][2] = v.z; idx[j][3] = v.w;
+        } else {
+            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rix, off, 0, kStream);
+            idx[j][0] = v.x; idx[j][1] = v.y;
+        }
+    }
+    // stage the source rows
+#pragma unroll
+    for (int j = 0; j < M; ++j) {
+        const uint32_t vecno = j * 64 + lane;
+        const uint32_t s = vecno >> LOG_M, hv = vecno & (M - 1);
+        const uint32_t fs = (s >> FS_SHIFT) & FS_MASK;
+        const uint32_t w4[4] = {vin[j].x, vin[j].y, vin[j].z, vin[j].w};
+#pragma unroll
+        for (int c = 0; c < UV; ++c) {
+            const uint32_t q = hv * UV + c;
+            const uint32_t addr = (s * RU + (q ^ fs)) * U;
+            if constexpr (U == 8) {
+                u32x2 v = {w4[2 * c], w4[2 * c + 1]};
+                *reinterpret_cast<u32x2 *>(my + addr) = v;
+            } else {
+                *reinterpret_cast<uint32_t *>(my + addr) = w4[c];
+            }
+        }
+    }
+    __syncthreads();
+
+    uint32_t own_w = 0;
+    if (!a.fast) {
+        const uint32_t wv = (uint32_t)(chunk & ((1ll << a.nwave) - 1));
+        for (int b = 0; b < a.nwave; ++b) own_w ^= a.own_wave[b] & (0u - ((wv >> b) & 1u));
+    }
+#pragma unroll
+    for (int j = 0; j < NSTEP; ++j) {
+        const uint32_t e0 = (j * 64 + lane) * EPS;       // first element of this step, inside the chunk
+        const uint32_t l = e0 >> NREG;                   // its layout lane (all EPS elements share it)
+        uint32_t own_l = own_w;
+        if (!a.fast) {
+#pragma unroll
+            for (int b = 0; b < 6; ++b) own_l ^= a.own_lane[b] & (0u - ((l >> b) & 1u));
+        }
+        uint32_t got[EPS * ((W == 8) ? 2 : 1)];
+#pragma unroll
+        for (int t = 0; t < EPS; ++t) {
+            const uint32_t r = (e0 + t) & (NE - 1);
+            const uint32_t sidx = idx[j][t] & a.axis_mask;
+            uint32_t src;
+            if (a.fast) {
+                src = (l & a.keep_mask) | (sidx << a.shift);
+            } else {
+                uint32_t own = own_l;
+#pragma unroll
+                for (int b = 0; b < NREG; ++b) own ^= a.own_regbit[b] & (0u - ((r >> b) & 1u));
+                const uint32_t x = (sidx ^ own) & a.axis_mask;
+                src = l;
+#pragma unroll
+                for (int b = 0; b < 6; ++b) src ^= a.lane_delta[b] & (0u - ((x >> b) & 1u));
+            }
+            const uint32_t fs = (src >> FS_SHIFT) & FS_MASK;
+            const uint32_t q = (r * W) / U;
+            const uint32_t addr = (src * RU + (q ^ fs)) * U + (r * W) % U;
+            if constexpr (W == 8) {
+                const u32x2 v = *reinterpret_cast<const u32x2 *>(my + addr);
+                got[2 * t] = v.x; got[2 * t + 1] = v.y;
+            } else if constexpr (W == 4) {
+                got[t] = *reinterpret_cast<const uint32_t *>(my + addr);
+            } else if constexpr (W == 2) {
+                got[t] = *reinterpret_cast<const uint16_t *>(my + addr);
+            } else {
+                got[t] = *reinterpret_cast<const uint8_t *>(my + addr);
+            }
+        }
+        const uint32_t ooff = wave * (64 * PL) + e0 * W;
+        if constexpr (W == 8 || W == 4) {
+            const u32x4 v = {got[0], got[1], got[2], got[3]};
+            buf_store16(rout, ooff, v);
+        } else if constexpr (W == 2) {
+            const u32x2 v = {got[0] | (got[1] << 16), got[2] | (got[3] << 16)};
+            __builtin_amdgcn_raw_buffer_store_b64(v, rout, ooff, 0, kStream);
+        } else {
+            const uint32_t v = got[0] | (got[1] << 8) | (got[2] << 16) | (got[3] << 24);
+            __builtin_amdgcn_raw_buffer_store_b32(v, rout, ooff, 0, kStream);
+        }
+    }
+}
+
+template <int W, int NREG>
+static ll_status launch_gather_staged_t(const GatherArgs &a, hipStream_t stream)
+{
+    constexpr int PL = (1 << NREG) * W;
+    if constexpr (PL < 16 || PL > 256 || (1 << NREG) < 4) {
+        return fail(LL_ERR_UNSUPPORTED, "staged gather needs 16 to 256 bytes and at least 4 elements per lane");
+    } else {
+        const long long grid = (a.nchunks + 3) / 4;
+        if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", grid);
+        constexpr int lds_bytes = 4 * 64 * PL;
+        hipLaunchKernelGGL((k_gather_staged<W, NREG>), dim3((unsigned)grid), dim3(256), lds_bytes, stream, a);
+        return check_launch("gather kernel launch");
+    }
+}
+
 template <int W, int NREG>
 static ll_status launch_gather_t(const GatherArgs &a, hipStream_t stream)
 {
@@ -339,6 +503,16 @@ static ll_status launch_gather_t(const GatherArgs &a, hipStream_t stream)
 template <int W>
 static ll_status launch_gather_w(const GatherArgs &a, hipStream_t stream)
 {
+    if (a.staged) {
+        switch (a.nreg) {
+        case 2: return launch_gather_staged_t<W, 2>(a, stream);
+        case 3: return launch_gather_staged_t<W, 3>(a, stream);
+        case 4: return launch_gather_staged_t<W, 4>(a, stream);
+        case 5: return launch_gather_staged_t<W, 5>(a, stream);
+        case 6: return launch_gather_staged_t<W, 6>(a, stream);
+        default: return fail(LL_ERR_UNSUPPORTED, "staged gather needs 2 to 6 register bits (got %d)", a.nreg);
+        }
+    }
     switch (a.nreg) {
     case 0: return launch_gather_t<W, 0>(a, stream);
     case 1: return launch_gather_t<W, 1>(a, stream);

@@ -57,7 +57,9 @@ struct GatherArgs {
     uint32_t own_lane[6];     // per lane bit: axis coordinate contribution
     uint32_t own_reg[64];     // per register: axis coordinate contribution
     uint32_t own_wave[16];    // per wave-index bit
+    uint32_t own_regbit[6];   // per register bit (own_reg is linear: own_reg[r] = XOR of these)
     int nwave;
+    int staged;               // 1: coalesced global access with the source staged in wave-private LDS
 };
 
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,

@@ -3,6 +3,7 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 using f2::mat;
@@ -224,8 +225,13 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     LdsElemArgs &a = plan->lds_elem;
     const int vs = ilog2(16u / (unsigned)w);          // elements per 16-byte vector (log2)
     const int tb = 8;                                 // 256 threads
-    const int n_max = ilog2(32768u / (unsigned)w);    // at most 32 KiB staged per workgroup
-    const int n_pref = ilog2(16384u / (unsigned)w);   // small tiles are bundled up to 16 KiB
+    // experiment knobs (bytes, powers of two): largest staged block, and the size small tiles are bundled to
+    // Small blocks measured best on MI355X (more, shorter-lived workgroups keep about 32-64 KiB in
+    // flight per CU, which is where a plain copy also peaks).
+    const unsigned max_block = getenv("LL_BLOCK_BYTES") ? (unsigned)atoi(getenv("LL_BLOCK_BYTES")) : 8192u;
+    const unsigned pref_block = getenv("LL_PREF_BYTES") ? (unsigned)atoi(getenv("LL_PREF_BYTES")) : 8192u;
+    const int n_max = ilog2(max_block / (unsigned)w);    // largest block staged per workgroup
+    const int n_pref = ilog2(pref_block / (unsigned)w);  // small tiles are bundled up to this size
 
     // bundle small tiles so that a block holds at least one vector per thread
     const int g = std::max(0, n_pref - d);

@@ -1,5 +1,6 @@
 // Host side of the device entry points: pick the kernel a plan names, fill the per-call fields of
 // its argument block, validate the gather layout (paper Sec. 5.5) and launch.
+#include <cstdlib>
 #include <cstring>
 
 #include "plan.hpp"
@@ -70,6 +71,7 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
     for (int b = 0; b < 6; ++b) a.own_lane[b] = axis_coord(vec(1) << (nreg + b));
     for (int r = 0; r < (1 << nreg); ++r) a.own_reg[r] = axis_coord((vec)r);
     for (int b = 0; b < nhigh; ++b) a.own_wave[b] = axis_coord(vec(1) << (nreg + 6 + b));
+    for (int b = 0; b < nreg; ++b) a.own_regbit[b] = axis_coord(vec(1) << b);
     a.nwave = nhigh;
     a.nreg = nreg;
     a.axis_mask = (1u << na) - 1;
@@ -106,6 +108,11 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
     a.idx = idx;
     a.out = out;
     a.nchunks = ntiles << nhigh;
+    // Rows of 16 bytes are already one coalesced vector per lane: shuffle directly.  Wider rows would
+    // make every lane's accesses strided, so they are staged through wave-private LDS instead.
+    const int row_bytes = (1 << nreg) * elem_bytes;
+    a.staged = (row_bytes > 16 && row_bytes <= 256 && nreg >= 2) ? 1 : 0;
+    if (const char *force = getenv("LL_GATHER_STAGED")) a.staged = atoi(force) && row_bytes >= 16 && row_bytes <= 256 && nreg >= 2;
     return launch_gather(a, elem_bytes, stream);
 }
 
