@@ -132,6 +132,7 @@ typedef struct {
     int32_t group_bits;         /* log2 tiles that share one block (small tiles) */
     int32_t segment_bits;       /* log2 elements of the contiguous runs a block reads and writes */
     int32_t shuffle_rounds;     /* cross-lane exchange stages (WAVE_SHUFFLE) */
+    int32_t register_transpose; /* 0: none; 1 / 2: in-register transpose before / after the exchange */
     /* LDS layout of one block, as linear layouts on block_bits bits over a common "block-local"
      * logical space (paper Sec. 5.4 "Optimal Swizzling"): lds_mem maps an LDS element offset to
      * a block-local index; lds_write / lds_read map (register, lane, wave) of the writing /

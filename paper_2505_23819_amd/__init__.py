@@ -51,6 +51,7 @@ class ll_plan_desc(ctypes.Structure):
         ("threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
         ("block_bits", ctypes.c_int32), ("group_bits", ctypes.c_int32),
         ("segment_bits", ctypes.c_int32), ("shuffle_rounds", ctypes.c_int32),
+        ("register_transpose", ctypes.c_int32),
         ("lds_mem", ctypes.c_uint64 * LL_PLAN_MAX_BLOCK_BITS),
         ("lds_write", ctypes.c_uint64 * LL_PLAN_MAX_BLOCK_BITS),
         ("lds_read", ctypes.c_uint64 * LL_PLAN_MAX_BLOCK_BITS),

@@ -39,6 +39,13 @@ static __device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, uin
     __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, kStream);
 }
 
+static unsigned env_inflight_bytes()
+{
+    const char *v = getenv("LL_INFLIGHT_BYTES");     // experiment knob
+    const long x = v ? atol(v) : 0;
+    return x >= 4096 ? (unsigned)x : 32768u;
+}
+
 static ll_status check_launch(const char *what)
 {
     hipError_t e = hipGetLastError();
@@ -239,6 +246,223 @@ ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int ld
     case 4: return launch_lds_elem_n<4>(a, nvec, lds_vec_bits, lds_bytes, s);
     case 8: return launch_lds_elem_n<8>(a, nvec, lds_vec_bits, lds_bytes, s);
     default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// vector-preserving conversion: register transposes + (nothing | wave shuffle | 128-bit LDS)
+// ---------------------------------------------------------------------------------------------
+
+// Transpose, inside one thread, between the position of an element in its 16-byte vector and the
+// low VS bits of the iteration index: element p of vector (c + 2^VS * h) becomes element c of
+// vector (p + 2^VS * h).  4- and 8-byte elements: pure register renaming.  2-byte elements: one
+// v_perm_b32 per output dword.
+template <int W, int NV>
+static __device__ __forceinline__ void transpose_regs(uint32_t (&r)[NV][4])
+{
+    constexpr int VS = (W == 2) ? 3 : (W == 4) ? 2 : 1;
+    constexpr int E = 1 << VS;
+    uint32_t t[NV][4];
+#pragma unroll
+    for (int h = 0; h < NV / E; ++h) {
+#pragma unroll
+        for (int p = 0; p < E; ++p) {          // new vector index (old position)
+            if constexpr (W == 4) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) t[p + E * h][c] = r[c + E * h][p];
+            } else if constexpr (W == 8) {
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    t[p + E * h][2 * c] = r[c + E * h][2 * p];
+                    t[p + E * h][2 * c + 1] = r[c + E * h][2 * p + 1];
+                }
+            } else {
+                // new dword q holds new positions 2q, 2q+1 = old vectors 2q, 2q+1, old position p
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t a = r[2 * q + E * h][p >> 1], b = r[2 * q + 1 + E * h][p >> 1];
+                    t[p + E * h][q] = (p & 1) ? __builtin_amdgcn_perm(b, a, 0x07060302u)
+                                              : __builtin_amdgcn_perm(b, a, 0x05040100u);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r[i][c] = t[i][c];
+}
+
+// One butterfly stage: lanes l and l ^ mask exchange the vectors whose iteration bit B differs
+// from their own side, i.e. the lane index bit selected by `mask` and iteration bit B trade
+// places.  The lane with the mask bit clear keeps its (B = 0) vectors and sends its (B = 1)
+// vectors; the partner does the opposite.  32-bit payload per ds_bpermute_b32.
+template <int NV, int B>
+static __device__ __forceinline__ void shuffle_stage(uint32_t (&r)[NV][4], uint32_t lane, uint32_t mask)
+{
+    const bool upper = (lane & mask) != 0;
+    const int partner = (int)((lane ^ mask) << 2);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        if ((i >> B) & 1) continue;
+        constexpr int bit = 1 << B;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t send = upper ? r[i][c] : r[i | bit][c];
+            const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute(partner, (int)send);
+            if (upper) r[i][c] = got; else r[i | bit][c] = got;
+        }
+    }
+}
+
+template <int NV, int NVB>
+static __device__ __forceinline__ void shuffle_stages(uint32_t (&r)[NV][4], uint32_t lane, const VecArgs &a)
+{
+    if constexpr (NVB > 0) { if (a.stage_mask[0]) shuffle_stage<NV, 0>(r, lane, a.stage_mask[0]); }
+    if constexpr (NVB > 1) { if (a.stage_mask[1]) shuffle_stage<NV, 1>(r, lane, a.stage_mask[1]); }
+    if constexpr (NVB > 2) { if (a.stage_mask[2]) shuffle_stage<NV, 2>(r, lane, a.stage_mask[2]); }
+    if constexpr (NVB > 3) { if (a.stage_mask[3]) shuffle_stage<NV, 3>(r, lane, a.stage_mask[3]); }
+    if constexpr (NVB > 4) { if (a.stage_mask[4]) shuffle_stage<NV, 4>(r, lane, a.stage_mask[4]); }
+}
+
+template <int W, int NVB, int TPOSE, int XCHG>
+__global__ __launch_bounds__(256) void k_vec(const VecArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int NV = 1 << NVB;
+    const uint32_t tid = threadIdx.x;
+
+    uint32_t ls = 0, ld = 0, lw = 0, lr = 0;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const uint32_t m = 0u - ((tid >> b) & 1u);
+        ls ^= a.lane_src[b] & m;
+        ld ^= a.lane_dst[b] & m;
+        if constexpr (XCHG == kXchgLds) {
+            lw ^= a.lds_wr_lane[b] & m;
+            lr ^= a.lds_rd_lane[b] & m;
+        }
+    }
+    const long long blk = blockIdx.x;
+    const long long group = blk >> a.coset_bits;
+    const uint32_t c = (uint32_t)(blk & ((1ll << a.coset_bits) - 1));
+    uint32_t cs = 0, cd = 0, cr = 0;
+    for (int b = 0; b < a.coset_bits; ++b) {
+        const uint32_t m = 0u - ((c >> b) & 1u);
+        cs ^= a.coset_src[b] & m;
+        cd ^= a.coset_dst[b] & m;
+        cr ^= a.coset_lds_rd[b] & m;
+    }
+    const int gshift = a.d + a.group_bits;
+    const unsigned char *sbase = static_cast<const unsigned char *>(a.src) + (((size_t)group << gshift) * W);
+    unsigned char *dbase = static_cast<unsigned char *>(a.dst) + (((size_t)group << gshift) * W);
+    const long long left = a.ntiles - (group << a.group_bits);
+    const uint32_t tiles_here = left > (1ll << a.group_bits) ? (1u << a.group_bits) : (uint32_t)left;
+    const uint32_t valid_bytes = (tiles_here << a.d) * W;
+    const __amdgpu_buffer_rsrc_t srsrc = make_rsrc(sbase, valid_bytes);
+    const __amdgpu_buffer_rsrc_t drsrc = make_rsrc(dbase, valid_bytes);
+
+    uint32_t r[NV][4];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const uint32_t off = cs ^ ls ^ a.iter_src[i];
+        const u32x4 v = buf_load16(srsrc, off * W);
+        r[i][0] = v.x; r[i][1] = v.y; r[i][2] = v.z; r[i][3] = v.w;
+    }
+    if constexpr (TPOSE == kTposeBefore) transpose_regs<W, NV>(r);
+    if constexpr (XCHG == kXchgShuffle) shuffle_stages<NV, NVB>(r, tid & 63, a);
+    if constexpr (XCHG == kXchgLds) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
+            *reinterpret_cast<u32x4 *>(lds + (lw ^ a.lds_wr_iter[i])) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + (cr ^ lr ^ a.lds_rd_iter[i]));
+            r[i][0] = v.x; r[i][1] = v.y; r[i][2] = v.z; r[i][3] = v.w;
+        }
+    }
+    if constexpr (TPOSE == kTposeAfter) transpose_regs<W, NV>(r);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const uint32_t off = cd ^ ld ^ a.iter_dst[i];
+        const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
+        buf_store16(drsrc, off * W, v);
+    }
+}
+
+template <int W, int NVB, int TPOSE, int XCHG>
+static ll_status launch_vec_t(const VecArgs &a, int threads, int lds_bytes, hipStream_t stream)
+{
+    constexpr int VS = (W == 2) ? 3 : (W == 4) ? 2 : 1;
+    if constexpr (TPOSE != kTposeNone && NVB < VS) {
+        return fail(LL_ERR_UNSUPPORTED, "internal: transposing kernel needs 2^%d vectors per thread", VS);
+    } else {
+        // Occupancy cap: a plain copy on this chip peaks with roughly 32-64 KiB in flight per CU and
+        // loses bandwidth beyond that, so workgroups are kept to (in-flight budget / block bytes) per
+        // CU by asking for a matching share of the 160 KiB LDS.
+        static const unsigned budget = env_inflight_bytes();
+        const unsigned block_bytes = (unsigned)threads * (16u << NVB);
+        const unsigned per_cu = budget / block_bytes > 1 ? budget / block_bytes : 1;
+        unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
+        if (alloc > 64u * 1024u) alloc = 64u * 1024u;
+        if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
+        hipLaunchKernelGGL((k_vec<W, NVB, TPOSE, XCHG>), dim3((unsigned)a.nblocks), dim3((unsigned)threads),
+                           (size_t)alloc, stream, a);
+        return check_launch("vector conversion kernel launch");
+    }
+}
+
+template <int W, int NVB, int TPOSE>
+static ll_status launch_vec_x(const VecArgs &a, int xchg, int threads, int lds_bytes, hipStream_t stream)
+{
+    switch (xchg) {
+    case kXchgNone: return launch_vec_t<W, NVB, TPOSE, kXchgNone>(a, threads, lds_bytes, stream);
+    case kXchgShuffle: return launch_vec_t<W, NVB, TPOSE, kXchgShuffle>(a, threads, lds_bytes, stream);
+    case kXchgLds: return launch_vec_t<W, NVB, TPOSE, kXchgLds>(a, threads, lds_bytes, stream);
+    default: return fail(LL_ERR_INVALID_ARG, "internal: exchange kind %d", xchg);
+    }
+}
+
+template <int W, int NVB>
+static ll_status launch_vec_p(const VecArgs &a, int tpose, int xchg, int threads, int lds_bytes, hipStream_t stream)
+{
+    switch (tpose) {
+    case kTposeNone: return launch_vec_x<W, NVB, kTposeNone>(a, xchg, threads, lds_bytes, stream);
+    case kTposeBefore: return launch_vec_x<W, NVB, kTposeBefore>(a, xchg, threads, lds_bytes, stream);
+    case kTposeAfter: return launch_vec_x<W, NVB, kTposeAfter>(a, xchg, threads, lds_bytes, stream);
+    default: return fail(LL_ERR_INVALID_ARG, "internal: transpose kind %d", tpose);
+    }
+}
+
+template <int W>
+static ll_status launch_vec_n(const VecArgs &a, int nvb, int tpose, int xchg, int threads, int lds_bytes, hipStream_t stream)
+{
+    switch (nvb) {
+    case 0: return launch_vec_p<W, 0>(a, tpose, xchg, threads, lds_bytes, stream);
+    case 1: return launch_vec_p<W, 1>(a, tpose, xchg, threads, lds_bytes, stream);
+    case 2: return launch_vec_p<W, 2>(a, tpose, xchg, threads, lds_bytes, stream);
+    case 3: return launch_vec_p<W, 3>(a, tpose, xchg, threads, lds_bytes, stream);
+    case 4: return launch_vec_p<W, 4>(a, tpose, xchg, threads, lds_bytes, stream);
+    default: return fail(LL_ERR_UNSUPPORTED, "no vector kernel for 2^%d vectors per thread", nvb);
+    }
+}
+
+ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose, int xchg, int threads, int lds_bytes,
+                     void *stream)
+{
+    if (threads != 64 && threads != 128 && threads != 256) return fail(LL_ERR_UNSUPPORTED, "vector kernel runs 64, 128 or 256 threads");
+    if (xchg == kXchgShuffle && threads != 64) return fail(LL_ERR_UNSUPPORTED, "shuffle kernel runs one wave per workgroup");
+    if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
+    if (lds_bytes < 0 || lds_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "LDS block of %d bytes", lds_bytes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (elem_bytes) {
+    case 2: return launch_vec_n<2>(a, nvec_bits, tpose, xchg, threads, lds_bytes, s);
+    case 4: return launch_vec_n<4>(a, nvec_bits, tpose, xchg, threads, lds_bytes, s);
+    case 8: return launch_vec_n<8>(a, nvec_bits, tpose, xchg, threads, lds_bytes, s);
+    default: return fail(LL_ERR_UNSUPPORTED, "vector kernel handles 2-, 4- and 8-byte elements");
     }
 }
 
@@ -482,7 +706,14 @@ static ll_status launch_gather_staged_t(const GatherArgs &a, hipStream_t stream)
         const long long grid = (a.nchunks + 3) / 4;
         if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", grid);
         constexpr int lds_bytes = 4 * 64 * PL;
-        hipLaunchKernelGGL((k_gather_staged<W, NREG>), dim3((unsigned)grid), dim3(256), lds_bytes, stream, a);
+        // Occupancy cap (see launch_vec_t): a workgroup has 4 chunks of `in` and `idx` in flight.
+        static const unsigned budget = getenv("LL_GATHER_INFLIGHT_BYTES") ? (unsigned)atol(getenv("LL_GATHER_INFLIGHT_BYTES")) : 49152u;
+        constexpr unsigned wg_bytes = 4u * 64u * (PL + 4u * (1u << NREG));
+        const unsigned per_cu = budget / wg_bytes > 1 ? budget / wg_bytes : 1;
+        unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
+        if (alloc > 64u * 1024u) alloc = 64u * 1024u;
+        if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
+        hipLaunchKernelGGL((k_gather_staged<W, NREG>), dim3((unsigned)grid), dim3(256), alloc, stream, a);
         return check_launch("gather kernel launch");
     }
 }

@@ -40,6 +40,29 @@ struct LdsElemArgs {
     uint32_t lds_wr_sub[kMaxSub], lds_rd_sub[kMaxSub];              // per sub-access of a vector
 };
 
+// Vector-preserving conversion: every thread keeps whole 16-byte vectors, optionally transposes
+// 2^vs x 2^vs element blocks between "position in the vector" and the low iteration bits in
+// registers (paper Sec. 5.4 "Intra-thread Data Exchange", Sec. 5.3 "Generalized Vectorization"),
+// and exchanges vectors either not at all, by lane <-> register butterfly stages inside the wave
+// (Sec. 5.4 "Intra-warp Data Exchange"), or through XOR-swizzled LDS with 128-bit accesses
+// (Sec. 5.4 "Optimal Swizzling" with the full vector as the common run).
+struct VecArgs {
+    const void *src;
+    void *dst;
+    long long ntiles;
+    long long nblocks;
+    int d, group_bits, coset_bits, thread_bits;
+    uint32_t coset_src[kMaxCosetBits], coset_dst[kMaxCosetBits], coset_lds_rd[kMaxCosetBits];
+    uint32_t lane_src[kMaxThreadBits], lane_dst[kMaxThreadBits];
+    uint32_t iter_src[kMaxIter], iter_dst[kMaxIter];
+    uint32_t stage_mask[5];       // per iteration bit: lane XOR mask of the butterfly stage (0 = none)
+    uint32_t lds_wr_lane[kMaxThreadBits], lds_rd_lane[kMaxThreadBits];
+    uint32_t lds_wr_iter[kMaxIter], lds_rd_iter[kMaxIter];
+};
+
+enum { kTposeNone = 0, kTposeBefore = 1, kTposeAfter = 2 };
+enum { kXchgNone = 0, kXchgShuffle = 1, kXchgLds = 2 };
+
 // Wave-local gather (paper Sec. 5.5): one kernel wave per layout wave; lane = layout lane.
 struct GatherArgs {
     const void *in;
@@ -64,6 +87,8 @@ struct GatherArgs {
 
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,
                           int lds_bytes, void *stream);
+ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose, int xchg, int threads, int lds_bytes,
+                     void *stream);
 ll_status launch_gather(const GatherArgs &a, int elem_bytes, void *stream);
 ll_status launch_copy(const void *src, void *dst, long long bytes, void *stream);
 

@@ -13,6 +13,13 @@ namespace ll {
 
 static int ilog2(unsigned x) { return 31 - __builtin_clz(x); }
 
+unsigned env_bytes(const char *name, unsigned fallback)
+{
+    const char *v = getenv(name);
+    const long x = v ? atol(v) : 0;
+    return (x >= 16 && x <= (1 << 20) && (x & (x - 1)) == 0) ? (unsigned)x : fallback;
+}
+
 int lds_width_class(int access_bytes) { return access_bytes <= 4 ? 0 : (access_bytes == 8 ? 1 : 2); }
 
 static vec lane_image(const mat &lanes, uint32_t lane_vec)
@@ -146,6 +153,73 @@ static int classify(const mat &p, int d, int reg_bits, int wave_first)
     return LL_KIND_LDS;
 }
 
+// Work decomposition shared by the staged kernels.  Tiles smaller than `pref_bytes` are bundled
+// (the conversion is extended by the identity on the bundling bits).  A block is a coset of
+// U_k = span(e_0..e_{k-1}) + P^-1 span(e_0..e_{k-1}) for the largest k with |U_k| * w <= max_bytes:
+// on BOTH sides a block consists of whole runs of 2^k contiguous elements.  `min_bits` is the
+// smallest block the kernel can take (one unit of work per thread).
+ll_status build_blocks(const mat &p, int d, int w, int min_bits, unsigned max_bytes, unsigned pref_bytes, BlockGeom *out)
+{
+    BlockGeom &b = *out;
+    const int vs = ilog2(16u / (unsigned)w);
+    const int n_max = std::max(min_bits, ilog2(max_bytes / (unsigned)w));
+    const int n_pref = std::max(min_bits, ilog2(pref_bytes / (unsigned)w));
+    const int g = std::max(0, n_pref - d);
+    const int D = d + g;
+    if (D + ilog2((unsigned)w) > 31) return fail(LL_ERR_UNSUPPORTED, "tile of 2^%d elements of %d bytes is too large", d, w);
+    mat pext = p;
+    for (int k = d; k < D; ++k) pext.push_back(vec(1) << k);
+    mat pinv;
+    if (!f2::invert(pext, D, &pinv)) return fail(LL_ERR_INVALID_ARG, "internal: conversion matrix is singular");
+    auto block_space = [&](int k) {
+        mat gens;
+        for (int j = 0; j < k; ++j) gens.push_back(vec(1) << j);
+        for (int j = 0; j < k; ++j) gens.push_back(pinv[j]);
+        return f2::extend({}, gens);
+    };
+    int k = vs;
+    while (k < D && (int)block_space(k + 1).size() <= n_max) ++k;
+    mat U = block_space(k);
+    for (int j = k; j < D && (int)U.size() < min_bits; ++j) U = f2::extend({}, concat(U, {vec(1) << j}));
+    const int n = (int)U.size();
+    if (n < min_bits) return fail(LL_ERR_UNSUPPORTED, "internal: block smaller than the kernel's unit of work");
+    const vec low_mask = (vec(1) << k) - 1;
+    // source-local basis: the k contiguous bits, then the remaining directions of U with their
+    // low k bits cleared (they select the run)
+    mat us;
+    for (int j = 0; j < k; ++j) us.push_back(vec(1) << j);
+    {
+        mat cand;
+        for (vec x : U) cand.push_back(x & ~low_mask);
+        for (vec x : f2::extend(us, cand)) us.push_back(x);
+    }
+    // destination-local basis of P(U)
+    mat ud;
+    for (int j = 0; j < k; ++j) ud.push_back(vec(1) << j);
+    {
+        mat cand;
+        for (vec x : us) cand.push_back(f2::apply(pext, x) & ~low_mask);
+        for (vec x : f2::extend(ud, cand)) ud.push_back(x);
+    }
+    if ((int)us.size() != n || (int)ud.size() != n) return fail(LL_ERR_INVALID_ARG, "internal: block basis mismatch");
+    // Q = Ud^-1 P Us : block-local source index -> block-local destination index
+    f2::Basis udb;
+    for (int j = 0; j < n; ++j) udb.add(ud[j], vec(1) << j);
+    mat q(n), qinv;
+    for (int j = 0; j < n; ++j) {
+        vec tag = 0;
+        if (udb.reduce(f2::apply(pext, us[j]), &tag) != 0) return fail(LL_ERR_INVALID_ARG, "internal: block not closed");
+        q[j] = tag;
+    }
+    if (!f2::invert(q, n, &qinv)) return fail(LL_ERR_INVALID_ARG, "internal: block map singular");
+    // cosets of U: the blocks of one tile group, enumerated by unit vectors outside U
+    const mat comp = f2::complement(U, D);
+    if ((int)comp.size() > kMaxCosetBits) return fail(LL_ERR_UNSUPPORTED, "internal: too many blocks per tile");
+    b.d = d; b.g = g; b.D = D; b.k = k; b.n = n; b.vs = vs; b.w = w;
+    b.pext = pext; b.us = us; b.ud = ud; b.q = q; b.qinv = qinv; b.comp = comp;
+    return LL_OK;
+}
+
 // Host-side walk through blocks of a finished plan, exactly as the kernel indexes them: every
 // global offset (16-byte aligned) and LDS address must be in range, the LDS writes must tile the
 // block without overlap, and every element read back must be stored where the conversion sends
@@ -228,72 +302,17 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     // experiment knobs (bytes, powers of two): largest staged block, and the size small tiles are bundled to
     // Small blocks measured best on MI355X (more, shorter-lived workgroups keep about 32-64 KiB in
     // flight per CU, which is where a plain copy also peaks).
-    const unsigned max_block = getenv("LL_BLOCK_BYTES") ? (unsigned)atoi(getenv("LL_BLOCK_BYTES")) : 8192u;
-    const unsigned pref_block = getenv("LL_PREF_BYTES") ? (unsigned)atoi(getenv("LL_PREF_BYTES")) : 8192u;
-    const int n_max = ilog2(max_block / (unsigned)w);    // largest block staged per workgroup
-    const int n_pref = ilog2(pref_block / (unsigned)w);  // small tiles are bundled up to this size
+    const unsigned max_block = env_bytes("LL_BLOCK_BYTES", 8192u);
+    const unsigned pref_block = env_bytes("LL_PREF_BYTES", 8192u);
 
-    // bundle small tiles so that a block holds at least one vector per thread
-    const int g = std::max(0, n_pref - d);
-    const int D = d + g;
-    if (D + ilog2((unsigned)w) > 31) return fail(LL_ERR_UNSUPPORTED, "tile of 2^%d elements of %d bytes is too large", d, w);
-    mat pext = p;
-    for (int k = d; k < D; ++k) pext.push_back(vec(1) << k);
-    mat pinv;
-    if (!f2::invert(pext, D, &pinv)) return fail(LL_ERR_INVALID_ARG, "internal: conversion matrix is singular");
-
-    // Block subspace U_k = span(e_0..e_{k-1}) + P^-1 span(e_0..e_{k-1}): both the source and the
-    // destination side of a block are made of whole runs of 2^k contiguous elements.
-    auto block_space = [&](int k) {
-        mat gens;
-        for (int j = 0; j < k; ++j) gens.push_back(vec(1) << j);
-        for (int j = 0; j < k; ++j) gens.push_back(pinv[j]);
-        return f2::extend({}, gens);
-    };
-    int k = vs;
-    while (k < D && (int)block_space(k + 1).size() <= n_max) ++k;
-    mat U = block_space(k);
-    // at least one vector per thread
-    for (int j = k; j < D && (int)U.size() < vs + tb; ++j) U = f2::extend({}, concat(U, {vec(1) << j}));
-    const int n = (int)U.size();
-    if (n < vs + tb) return fail(LL_ERR_UNSUPPORTED, "internal: block smaller than one vector per thread");
+    BlockGeom geom;
+    if (ll_status st = build_blocks(p, d, w, vs + tb, max_block, pref_block, &geom); st != LL_OK) return st;
+    const int g = geom.g, k = geom.k, n = geom.n;
+    const mat &pext = geom.pext, &us = geom.us, &ud = geom.ud, &q = geom.q, &qinv = geom.qinv, &comp = geom.comp;
+    const int nco = (int)comp.size();
+    const vec low_mask = (vec(1) << k) - 1;
     const int nvec_bits = n - vs - tb;
     if ((1 << nvec_bits) > kMaxIter) return fail(LL_ERR_UNSUPPORTED, "internal: too many vectors per thread");
-
-    const vec low_mask = (vec(1) << k) - 1;
-    // source-local basis: the k contiguous bits, then the remaining directions of U with their
-    // low k bits cleared (they select the run)
-    mat us;
-    for (int j = 0; j < k; ++j) us.push_back(vec(1) << j);
-    {
-        mat cand;
-        for (vec x : U) cand.push_back(x & ~low_mask);
-        for (vec x : f2::extend(us, cand)) us.push_back(x);
-    }
-    // destination-local basis of P(U)
-    mat ud;
-    for (int j = 0; j < k; ++j) ud.push_back(vec(1) << j);
-    {
-        mat cand;
-        for (vec x : us) cand.push_back(f2::apply(pext, x) & ~low_mask);
-        for (vec x : f2::extend(ud, cand)) ud.push_back(x);
-    }
-    if ((int)us.size() != n || (int)ud.size() != n) return fail(LL_ERR_INVALID_ARG, "internal: block basis mismatch");
-    // Q = Ud^-1 P Us : block-local source index -> block-local destination index
-    f2::Basis udb;
-    for (int j = 0; j < n; ++j) udb.add(ud[j], vec(1) << j);
-    mat q(n), qinv;
-    for (int j = 0; j < n; ++j) {
-        vec tag = 0;
-        if (udb.reduce(f2::apply(pext, us[j]), &tag) != 0) return fail(LL_ERR_INVALID_ARG, "internal: block not closed");
-        q[j] = tag;
-    }
-    if (!f2::invert(q, n, &qinv)) return fail(LL_ERR_INVALID_ARG, "internal: block map singular");
-
-    // cosets of U: blocks of one tile group
-    const mat comp = f2::complement(U, D);
-    const int nco = (int)comp.size();
-    if (nco > kMaxCosetBits) return fail(LL_ERR_UNSUPPORTED, "internal: too many blocks per tile");
 
     // common contiguous run: Q e_b = e_b for b < v
     // (the low v bits of the destination index must be the low v bits of the source index: column
@@ -431,6 +450,20 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
         desc.global_vec_bytes = 16;
         desc.threads = 256;
         return LL_OK;
+    }
+    // Strategy, most specific first.  Conversions that stay inside a wave try the shuffle /
+    // register-only kernel; everything else (and whatever that kernel's structure does not cover)
+    // is staged through LDS, with 128-bit accesses when the in-register transpose applies and with
+    // element-wide accesses otherwise (always possible).
+    const char *force = getenv("LL_FORCE_STRATEGY");
+    bool applied = false;
+    if ((desc.kind == LL_KIND_REG_ONLY || desc.kind == LL_KIND_INTRA_WAVE) && !(force && atoi(force) >= LL_STRATEGY_LDS_ELEM)) {
+        if (ll_status st = plan_wave_shuffle(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
+        if (applied) return LL_OK;
+    }
+    if (!(force && atoi(force) == LL_STRATEGY_LDS_ELEM)) {
+        if (ll_status st = plan_lds_vec(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
+        if (applied) return LL_OK;
     }
     return plan_lds_elem(p, d, elem_bytes, plan);
 }

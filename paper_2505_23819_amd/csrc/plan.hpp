@@ -32,15 +32,35 @@ f2::mat synthesize_swizzle(int n, int v, int w, const f2::mat &wr_lanes, const f
 
 int lds_width_class(int access_bytes);   // 0, 1, 2 for <=4, 8, 16 bytes
 
+// Geometry of the blocks a conversion is cut into (see build_blocks).
+struct BlockGeom {
+    int d = 0, g = 0, D = 0;      // tile bits, bundling bits, D = d + g
+    int k = 0, n = 0;             // run bits, block bits
+    int vs = 0, w = 0;            // log2 elements per 16-byte vector, element bytes
+    f2::mat pext;                 // conversion extended by the identity on the bundling bits (D columns)
+    f2::mat us, ud;               // block-local bases (n columns each, low k = unit vectors) on the source / destination side
+    f2::mat q, qinv;              // Q = Ud^-1 P Us and its inverse (n x n)
+    f2::mat comp;                 // unit vectors enumerating the blocks of a tile group
+};
+ll_status build_blocks(const f2::mat &p, int d, int w, int min_bits, unsigned max_bytes, unsigned pref_bytes, BlockGeom *out);
+unsigned env_bytes(const char *name, unsigned fallback);
+
 }  // namespace ll
 
 struct ll_plan {
     ll_plan_desc desc = {};
     int nvec = 0;                 // 16-byte vectors per thread
     ll::LdsElemArgs lds_elem = {};
+    ll::VecArgs vec = {};
+    int vec_nvec_bits = 0, vec_tpose = 0, vec_xchg = 0;
 };
 
 namespace ll {
+// Vector-preserving strategies (plan_vec.cpp).  Each returns LL_OK and sets *applied when the
+// conversion has the structure the strategy needs; otherwise *applied is false and the plan is
+// untouched.
+ll_status plan_wave_shuffle(const f2::mat &p, int d, int w, ll_plan *plan, bool *applied);
+ll_status plan_lds_vec(const f2::mat &p, int d, int w, ll_plan *plan, bool *applied);
 ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan);
 ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long ntiles, void *stream);
 ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *in, const int32_t *idx,

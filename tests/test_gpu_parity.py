@@ -152,3 +152,88 @@ def test_gather_random_lane_axis(w, nreg, nwave, axis_bits):
     got = run_gather(layout, 0, inp, idx, d)
     want = oracle.gather(bases, dims, 0, inp, idx)
     assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_convert_configs_reverse_direction(cid):
+    cfg = wl.config(cid)
+    a, b = layouts_of(cfg)
+    plan = ll.ll_plan_convert(b, a, cfg.elem_bytes)
+    src = wl.to_numpy_bits(cfg.gen_data(0, 3))
+    assert np.array_equal(run_convert(plan, src, cfg.d), oracle.convert(cfg.dst_bases, cfg.src_bases, src))
+
+
+@pytest.mark.parametrize("force", ["3", "4"])
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_convert_configs_forced_lds_strategies(cid, force, monkeypatch):
+    """Every config through the element-wide LDS kernel (3) and, where it applies, the 128-bit one (4)."""
+    monkeypatch.setenv("LL_FORCE_STRATEGY", force)
+    cfg = wl.config(cid)
+    a, b = layouts_of(cfg)
+    plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+    name = plan.info()["strategy_name"]
+    assert name in ("lds_elem", "lds_vec") and (force != "3" or name == "lds_elem")
+    src = wl.to_numpy_bits(cfg.gen_data(1, 3))
+    assert np.array_equal(run_convert(plan, src, cfg.d), oracle.convert(cfg.src_bases, cfg.dst_bases, src))
+
+
+@pytest.mark.parametrize("w", [2, 4, 8])
+@pytest.mark.parametrize("nreg", [2, 3, 4, 5, 6])
+def test_convert_intra_wave_bit_permutations(w, nreg):
+    """Register and lane bits permuted among themselves (wave bits fixed): the shuffle / register
+    kernels where their structure applies, LDS otherwise; all must match the oracle."""
+    rng = np.random.default_rng(500 + 10 * w + nreg)
+    nwave = 2
+    d = nreg + 6 + nwave
+    seen = set()
+    for trial in range(12):
+        low = nreg + 6
+        if trial % 3 == 2:      # registers only
+            pa = list(rng.permutation(nreg)) + list(range(nreg, d))
+            pb = list(rng.permutation(nreg)) + list(range(nreg, d))
+        else:
+            pa = list(rng.permutation(low)) + list(range(low, d))
+            pb = list(rng.permutation(low)) + list(range(low, d))
+        ca, cb = [1 << int(x) for x in pa], [1 << int(x) for x in pb]
+        a = ll.distributed_layout(nreg, 6, nwave, [d], ca)
+        b = ll.distributed_layout(nreg, 6, nwave, [d], cb)
+        plan = ll.ll_plan_convert(a, b, w)
+        info = plan.info()
+        assert info["kind_name"] in ("noop", "reg_only", "intra_wave")
+        seen.add(info["strategy_name"])
+        ntiles = int(rng.integers(1, 6))
+        src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+        assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src)), (trial, info["strategy_name"])
+    print("strategies used:", sorted(seen))
+
+
+def test_convert_structured_shuffle_cases():
+    """Hand-built conversions that need lane <-> register stages with the transpose before, after,
+    and not at all (4-byte elements, 6 register + 6 lane bits)."""
+    d, nreg = 12, 6
+    ident = list(range(d))
+
+    def swap(perm, x, y):
+        p = perm[:]
+        p[x], p[y] = p[y], p[x]
+        return p
+
+    cases = {
+        "no transpose, one stage": swap(ident, 3, 8),                 # register bit 3 <-> lane bit 2
+        "vector bits to lanes": swap(swap(ident, 0, 6), 1, 7),        # position bits <-> lane bits 0, 1
+        "vector bits to registers": swap(swap(ident, 0, 4), 1, 5),    # position bits <-> register bits 4, 5
+        "three stages": swap(swap(swap(ident, 2, 9), 3, 10), 4, 11),
+    }
+    rng = np.random.default_rng(9)
+    used = {}
+    for name, perm in cases.items():
+        ca = [1 << k for k in range(d)]
+        cb = [1 << perm[k] for k in range(d)]
+        for x, y, cx, cy in ((ca, cb, ca, cb), (cb, ca, cb, ca)):
+            a = ll.distributed_layout(nreg, 6, 0, [d], x)
+            b = ll.distributed_layout(nreg, 6, 0, [d], y)
+            plan = ll.ll_plan_convert(a, b, 4)
+            used[name] = plan.info()["strategy_name"]
+            src = rng.integers(0, 1 << 32, size=5 << d, dtype=np.uint32)
+            assert np.array_equal(run_convert(plan, src, d), oracle.convert(cx, cy, src)), name
+    print(used)
