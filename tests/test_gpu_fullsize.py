@@ -1,0 +1,89 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times: sampled
+tiles against the oracle (tiles are independent, so the oracle can take them one by one) plus a
+property that holds at any size (a conversion permutes each tile: per-tile sums are preserved)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ll = pytest.importorskip("paper_2505_23819_amd")
+
+
+def sample_tiles(ntiles, count, seed):
+    rng = np.random.default_rng(seed)
+    picks = {0, ntiles - 1, ntiles // 2}
+    while len(picks) < min(count, ntiles):
+        picks.add(int(rng.integers(0, ntiles)))
+    return sorted(picks)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_convert_full_size_sampled(cid):
+    cfg = wl.config(cid)
+    a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+    b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
+    plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+    src = cfg.gen_data(0, cfg.ntiles, "cuda")
+    dst = torch.empty_like(src)
+    wl.bits_view(dst).fill_(0x5A5A)
+    ll.ll_convert(plan, src, dst, cfg.ntiles)
+    torch.cuda.synchronize()
+    te = cfg.tile_elems
+    # property: every tile is permuted within itself
+    s_sum = wl.bits_view(src).view(cfg.ntiles, te).to(torch.int64).sum(dim=1)
+    d_sum = wl.bits_view(dst).view(cfg.ntiles, te).to(torch.int64).sum(dim=1)
+    assert torch.equal(s_sum, d_sum)
+    # sampled tiles, bit for bit
+    for t in sample_tiles(cfg.ntiles, 12 if cid != 4 else 6, cid):
+        s_tile = wl.to_numpy_bits(src[t * te:(t + 1) * te])
+        d_tile = wl.to_numpy_bits(dst[t * te:(t + 1) * te])
+        # the input on the device is what the seeded generator produces on the host too
+        if cfg.data_recipe != "normal":
+            assert np.array_equal(s_tile, wl.to_numpy_bits(cfg.gen_data(t, 1)))
+        want = oracle.convert(cfg.src_bases, cfg.dst_bases, s_tile)
+        assert np.array_equal(d_tile, want), f"config {cid} tile {t}"
+
+
+def test_gather_full_size_sampled():
+    cfg = wl.config(5)
+    layout = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+    inp = cfg.gen_data(0, cfg.ntiles, "cuda")
+    idx = cfg.gen_idx(0, cfg.ntiles, "cuda")
+    out = torch.empty_like(inp)
+    wl.bits_view(out).fill_(0x5A5A)
+    ll.ll_gather(layout, cfg.axis, cfg.elem_bytes, inp, idx, out, cfg.ntiles)
+    torch.cuda.synchronize()
+    te = cfg.tile_elems
+    for t in sample_tiles(cfg.ntiles, 12, 5):
+        i_tile = wl.to_numpy_bits(inp[t * te:(t + 1) * te])
+        x_tile = idx[t * te:(t + 1) * te].cpu().numpy()
+        assert np.array_equal(i_tile, wl.to_numpy_bits(cfg.gen_data(t, 1)))
+        assert np.array_equal(x_tile, cfg.gen_idx(t, 1).numpy())
+        want = oracle.gather(cfg.src_bases, cfg.out_dim_bits, cfg.axis, i_tile, x_tile)
+        assert np.array_equal(wl.to_numpy_bits(out[t * te:(t + 1) * te]), want), f"tile {t}"
+    # property: with idx[i, j] = i the gather is the identity, at full size
+    rows = torch.arange(te, device="cuda", dtype=torch.int32)
+    # hardware index h = reg | lane << 4 | wave << 10: the row of element h is its lane
+    ident = ((rows >> 4) & 63).repeat(cfg.ntiles)
+    ll.ll_gather(layout, cfg.axis, cfg.elem_bytes, inp, ident, out, cfg.ntiles)
+    torch.cuda.synchronize()
+    assert torch.equal(wl.bits_view(out), wl.bits_view(inp))
+
+
+def test_gather_both_kernels_agree(monkeypatch):
+    """The shuffle kernel (one ds_bpermute_b32 per element) and the staged kernel on config 5."""
+    cfg = wl.config(5)
+    layout = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+    nt = 37
+    inp, idx = cfg.gen_data(0, nt, "cuda"), cfg.gen_idx(0, nt, "cuda")
+    want = oracle.gather(cfg.src_bases, cfg.out_dim_bits, cfg.axis, wl.to_numpy_bits(inp), idx.cpu().numpy())
+    for staged in ("0", "1"):
+        monkeypatch.setenv("LL_GATHER_STAGED", staged)
+        out = torch.zeros_like(inp)
+        ll.ll_gather(layout, cfg.axis, cfg.elem_bytes, inp, idx, out, nt)
+        torch.cuda.synchronize()
+        assert np.array_equal(wl.to_numpy_bits(out), want), f"staged={staged}"

@@ -77,10 +77,26 @@ def test_classification_rules():
     assert kind(ident, reg_into_wave) == "lds"
 
 
+def test_strategies_of_the_configs():
+    got = {cid: plan_of(wl.config(cid)).info() for cid in (1, 2, 3, 4)}
+    assert got[1]["strategy_name"] == "lds_vec" and got[2]["strategy_name"] == "lds_vec"
+    assert got[3]["strategy_name"] in ("reg_permute", "wave_shuffle")
+    assert got[4]["strategy_name"] == "lds_elem"          # XOR layouts: no common run, element-wide LDS
+    for cid in (1, 2):
+        assert got[cid]["lds_write_bytes"] == 16 and got[cid]["lds_read_bytes"] == 16
+        assert got[cid]["register_transpose"] == 1
+    for cid in (1, 2, 3, 4):
+        assert got[cid]["global_vec_bytes"] == 16
+
+
+@pytest.mark.parametrize("force", ["3", "4"])
 @pytest.mark.parametrize("cid", [1, 2, 3, 4])
-def test_swizzle_of_configs_is_conflict_free_by_enumeration(cid):
+def test_swizzle_of_configs_is_conflict_free_by_enumeration(cid, force, monkeypatch):
+    monkeypatch.setenv("LL_FORCE_STRATEGY", force)        # 3: element-wide LDS, 4: 128-bit LDS where it applies
     info = plan_of(wl.config(cid)).info()
     assert info["strategy_name"] in ("lds_elem", "lds_vec")
+    if force == "3":
+        assert info["strategy_name"] == "lds_elem"
     n = info["block_bits"]
     assert len(span(info["lds_mem"])) == 1 << n        # M is invertible
     for side in ("lds_write", "lds_read"):
@@ -91,13 +107,16 @@ def test_swizzle_of_configs_is_conflict_free_by_enumeration(cid):
     assert info["predicted_wavefronts_write"] == 1 and info["predicted_wavefronts_read"] == 1
 
 
-def test_unswizzled_staging_of_config1_conflicts():
+@pytest.mark.parametrize("force", ["3", "4"])
+def test_unswizzled_staging_of_config1_conflicts(force, monkeypatch):
     # control: the same accesses against a linear (unswizzled) LDS layout do collide
+    monkeypatch.setenv("LL_FORCE_STRATEGY", force)
     info = plan_of(wl.config(1)).info()
     n = info["block_bits"]
     linear = [1 << k for k in range(n)]
-    worst = max(oracle.wavefronts(linear, info[side], info["lds_write_reg_bits"], 6, 4, 0, 32,
-                                  gfx950_phases(4))[0] for side in ("lds_write", "lds_read"))
+    worst = max(oracle.wavefronts(linear, info[side], info["lds_write_reg_bits"], 6, 4, info["lds_vec_bits"],
+                                  info["lds_banks"], gfx950_phases(info["lds_write_bytes"]))[0]
+                for side in ("lds_write", "lds_read"))
     assert worst > 1
 
 
@@ -136,7 +155,8 @@ def test_common_vector_is_kept_wide():
     a = ll.distributed_layout(4, 6, 2, [d], [1, 2] + rest_a)
     b = ll.distributed_layout(4, 6, 2, [d], [1, 2] + rest_b)
     info = ll.ll_plan_convert(a, b, 4).info()
-    if info["strategy_name"] == "lds_elem":
+    assert info["strategy_name"] in ("lds_elem", "lds_vec")
+    if True:
         assert info["lds_vec_bits"] == 2 and info["lds_write_bytes"] == 16
         for side in ("lds_write", "lds_read"):
             assert oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6, 4, 2, 64,
