@@ -143,7 +143,8 @@ typedef struct {
     uint64_t lds_read[LL_PLAN_MAX_BLOCK_BITS];
     int32_t lds_write_reg_bits, lds_read_reg_bits;
     int32_t lds_vec_bits;       /* log2 elements per LDS access */
-    int32_t lds_banks;          /* hardware model used by the synthesizer */
+    int32_t lds_banks;          /* hardware model used by the synthesizer: 4-byte banks a read phase spans */
+    int32_t lds_banks_write;    /* ... and a write phase */
     int32_t lds_phase_lanes_write, lds_phase_lanes_read; /* lanes served together */
     int32_t predicted_wavefronts_write, predicted_wavefronts_read; /* per access phase; 1 = conflict free */
 } ll_plan_desc;

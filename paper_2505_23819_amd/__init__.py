@@ -56,7 +56,7 @@ class ll_plan_desc(ctypes.Structure):
         ("lds_write", ctypes.c_uint64 * LL_PLAN_MAX_BLOCK_BITS),
         ("lds_read", ctypes.c_uint64 * LL_PLAN_MAX_BLOCK_BITS),
         ("lds_write_reg_bits", ctypes.c_int32), ("lds_read_reg_bits", ctypes.c_int32),
-        ("lds_vec_bits", ctypes.c_int32), ("lds_banks", ctypes.c_int32),
+        ("lds_vec_bits", ctypes.c_int32), ("lds_banks", ctypes.c_int32), ("lds_banks_write", ctypes.c_int32),
         ("lds_phase_lanes_write", ctypes.c_int32), ("lds_phase_lanes_read", ctypes.c_int32),
         ("predicted_wavefronts_write", ctypes.c_int32), ("predicted_wavefronts_read", ctypes.c_int32),
     ]

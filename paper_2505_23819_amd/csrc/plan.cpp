@@ -57,23 +57,26 @@ static int predict_wavefronts(const mat &m, int n, int low_bits, int row_bits, c
 //   the segment (row-index) columns come from G u C, which meets U u W only in 0;
 //   the bank columns complete the basis.
 // The hardware constants (banks, lanes per phase) come from the LdsModel instead of the
-// 32-bank / 32-lane figures of the paper.
+// 32-bank / 32-lane figures of the paper.  On gfx950 a wide write phase covers a 128-byte row and
+// a wide read phase a 256-byte row, so the offset bits between the two row sizes are row-index
+// bits for one side and bank bits for the other: they are filled with vectors that keep the
+// narrower-row side conflict free (always possible: a subspace meeting U only in 0 extends to a
+// complement of U).
 mat synthesize_swizzle(int n, int v, int w, const mat &wr_lanes, const mat &rd_lanes, const LdsModel &hw,
                        int *wf_write, int *wf_read)
 {
     const int access = (1 << v) * w;
     const int cls = lds_width_class(access);
-    int row_bits = ilog2((unsigned)(hw.banks[cls] * 4 / w));   // offset bits that pick (bank, byte)
-    if (row_bits > n) row_bits = n;
-    const int low_bits = std::max(v, ilog2((unsigned)std::max(1, 4 / w)));   // bits inside one access / word
+    const int row_w = std::min(n, ilog2((unsigned)(hw.wr_banks[cls] * 4 / w)));   // offset bits that pick (bank, byte)
+    const int row_r = std::min(n, ilog2((unsigned)(hw.rd_banks[cls] * 4 / w)));
+    const int row_lo = std::min(row_w, row_r), row_hi = std::max(row_w, row_r);
+    const int low_bits = std::min(row_lo, std::max(v, ilog2((unsigned)std::max(1, 4 / w))));   // bits inside one access / word
 
     mat vecs;
     for (int b = 0; b < v; ++b) vecs.push_back(vec(1) << b);
     mat wl, rl;     // images of the lanes served in one phase
-    for (int k = 0; k < hw.phase_dim[cls]; ++k) {
-        wl.push_back(lane_image(wr_lanes, hw.phase_basis[cls][k]));
-        rl.push_back(lane_image(rd_lanes, hw.phase_basis[cls][k]));
-    }
+    for (int k = 0; k < hw.wr_phase_dim[cls]; ++k) wl.push_back(lane_image(wr_lanes, hw.wr_phase_basis[cls][k]));
+    for (int k = 0; k < hw.rd_phase_dim[cls]; ++k) rl.push_back(lane_image(rd_lanes, hw.rd_phase_basis[cls][k]));
     // "low" columns: the offsets inside one access or one 4-byte word, whichever is larger.  They
     // start with the vector; for sub-word accesses they are completed with directions shared by
     // the write and read lanes if there are any (lanes that differ only there share a word on
@@ -91,7 +94,8 @@ mat synthesize_swizzle(int n, int v, int w, const mat &wr_lanes, const mat &rd_l
     for (size_t i = 0; i < std::min(E.size(), F.size()); ++i) G.push_back(E[i] ^ F[i]);
     const mat C = f2::complement(concat(U, W), n);
 
-    const int need = n - row_bits;
+    // columns above the larger row: row index for both sides
+    const int need = n - row_hi;
     mat seg;
     for (vec g : concat(G, C))
         if ((int)seg.size() < need) seg.push_back(g);
@@ -100,21 +104,37 @@ mat synthesize_swizzle(int n, int v, int w, const mat &wr_lanes, const mat &rd_l
         for (vec x : f2::extend(concat(low, seg), concat(concat(U, W), f2::identity(n))))
             if ((int)seg.size() < need) seg.push_back(x);
     }
-    // bank columns: complete low + seg to a basis, preferring the write lanes so that a write
-    // instruction of consecutive lanes stays contiguous
-    mat fixed = concat(low, seg);
+    // columns between the two row sizes: row index for the side with the smaller row (call its
+    // phase space T), bank bits for the other side
+    const mat &T = (row_w <= row_r) ? U : W;
+    const mat &other = (row_w <= row_r) ? W : U;
+    mat mid;
+    {
+        f2::Basis taken;                 // low + seg + mid + T: a candidate must stay outside
+        for (vec x : concat(concat(low, seg), T)) taken.add(x);
+        for (vec x : concat(other, f2::identity(n))) {
+            if ((int)mid.size() >= row_hi - row_lo) break;
+            if (taken.add(x)) mid.push_back(x);
+        }
+        for (vec x : f2::extend(concat(concat(low, seg), mid), f2::identity(n)))      // unavoidable conflicts
+            if ((int)mid.size() < row_hi - row_lo) mid.push_back(x);
+    }
+    // bank columns: complete to a basis, preferring the write lanes so that a write instruction of
+    // consecutive lanes stays contiguous
+    mat fixed = concat(concat(low, seg), mid);
     mat bank = f2::extend(fixed, concat(concat(U, W), f2::identity(n)));
     // Keep vectors aligned: an index whose low v bits are zero must get an offset whose low v bits
     // are zero, i.e. every non-vector column must have zero low v bits.  Clearing them adds vector
     // columns to the others, which changes neither the spans used above nor invertibility.
     const vec vmask = (vec(1) << v) - 1;
     for (vec &x : bank) x &= ~vmask;
+    for (vec &x : mid) x &= ~vmask;
     for (vec &x : seg) x &= ~vmask;
     for (size_t i = (size_t)v; i < low.size(); ++i) low[i] &= ~vmask;
-    mat m = concat(concat(low, bank), seg);
+    mat m = concat(concat(concat(low, bank), mid), seg);
 
-    if (wf_write) *wf_write = predict_wavefronts(m, n, std::min(low_bits, row_bits), row_bits, U);
-    if (wf_read) *wf_read = predict_wavefronts(m, n, std::min(low_bits, row_bits), row_bits, W);
+    if (wf_write) *wf_write = predict_wavefronts(m, n, low_bits, row_w, U);
+    if (wf_read) *wf_read = predict_wavefronts(m, n, low_bits, row_r, W);
     return m;
 }
 
@@ -391,8 +411,10 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     desc.shuffle_rounds = 0;
     desc.lds_vec_bits = v;
     const int cls = lds_width_class((1 << v) * w);
-    desc.lds_banks = hw.banks[cls];
-    desc.lds_phase_lanes_write = desc.lds_phase_lanes_read = 1 << hw.phase_dim[cls];
+    desc.lds_banks = hw.rd_banks[cls];
+    desc.lds_banks_write = hw.wr_banks[cls];
+    desc.lds_phase_lanes_write = 1 << hw.wr_phase_dim[cls];
+    desc.lds_phase_lanes_read = 1 << hw.rd_phase_dim[cls];
     desc.predicted_wavefronts_write = wfw;
     desc.predicted_wavefronts_read = wfr;
     desc.lds_write_reg_bits = desc.lds_read_reg_bits = vs + nvec_bits;

@@ -451,8 +451,10 @@ ll_status plan_lds_vec(const mat &p, int d, int w, ll_plan *plan, bool *applied)
     desc.shuffle_rounds = 0;
     desc.register_transpose = kTposeBefore;
     desc.lds_vec_bits = vs;
-    desc.lds_banks = hw.banks[2];
-    desc.lds_phase_lanes_write = desc.lds_phase_lanes_read = 1 << hw.phase_dim[2];
+    desc.lds_banks = hw.rd_banks[2];
+    desc.lds_banks_write = hw.wr_banks[2];
+    desc.lds_phase_lanes_write = 1 << hw.wr_phase_dim[2];
+    desc.lds_phase_lanes_read = 1 << hw.rd_phase_dim[2];
     desc.predicted_wavefronts_write = wfw;
     desc.predicted_wavefronts_read = wfr;
     desc.lds_write_reg_bits = desc.lds_read_reg_bits = vs + nvb;

@@ -24,12 +24,20 @@ def random_invertible(rng, d):
             return cols
 
 
-def gfx950_phases(access_bytes):
-    """Lanes served together by one LDS instruction, as measured on gfx950: halves of the wave
-    for accesses up to 8 bytes; for 16 bytes the groups {l5, l2^l3^l4}."""
+def gfx950_phases(access_bytes, side="lds_read"):
+    """Lanes served together by one LDS instruction, as measured on gfx950.  Reads: halves of the
+    wave for accesses up to 8 bytes, the groups {l5, l2^l3^l4} for 16 bytes.  Writes: halves up to
+    4 bytes, 16 consecutive lanes for 8 bytes, 8 consecutive lanes for 16 bytes."""
+    if side == "lds_write":
+        shift = 5 if access_bytes <= 4 else (4 if access_bytes == 8 else 3)
+        return [l >> shift for l in range(64)]
     if access_bytes <= 8:
         return [l >> 5 for l in range(64)]
     return [(l >> 5) * 2 + (((l >> 2) ^ (l >> 3) ^ (l >> 4)) & 1) for l in range(64)]
+
+
+def banks_of(info, side):
+    return info["lds_banks_write"] if side == "lds_write" else info["lds_banks"]
 
 
 def plan_of(cfg):
@@ -101,8 +109,8 @@ def test_swizzle_of_configs_is_conflict_free_by_enumeration(cid, force, monkeypa
     assert len(span(info["lds_mem"])) == 1 << n        # M is invertible
     for side in ("lds_write", "lds_read"):
         mx, tot, nph = oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6,
-                                         info["elem_bytes"], info["lds_vec_bits"], info["lds_banks"],
-                                         gfx950_phases(info["lds_write_bytes"]))
+                                         info["elem_bytes"], info["lds_vec_bits"], banks_of(info, side),
+                                         gfx950_phases(info["lds_write_bytes"], side))
         assert mx == 1 and tot == nph
     assert info["predicted_wavefronts_write"] == 1 and info["predicted_wavefronts_read"] == 1
 
@@ -115,7 +123,7 @@ def test_unswizzled_staging_of_config1_conflicts(force, monkeypatch):
     n = info["block_bits"]
     linear = [1 << k for k in range(n)]
     worst = max(oracle.wavefronts(linear, info[side], info["lds_write_reg_bits"], 6, 4, info["lds_vec_bits"],
-                                  info["lds_banks"], gfx950_phases(info["lds_write_bytes"]))[0]
+                                  banks_of(info, side), gfx950_phases(info["lds_write_bytes"], side))[0]
                 for side in ("lds_write", "lds_read"))
     assert worst > 1
 
@@ -141,8 +149,8 @@ def test_random_layouts_plan_and_swizzle(w):
             assert (1 << info["segment_bits"]) * w >= 16
             for side in ("lds_write", "lds_read"):
                 mx, tot, nph = oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6, w,
-                                                 info["lds_vec_bits"], info["lds_banks"],
-                                                 gfx950_phases(info["lds_write_bytes"]))
+                                                 info["lds_vec_bits"], banks_of(info, side),
+                                                 gfx950_phases(info["lds_write_bytes"], side))
                 assert mx == 1, (w, d, trial, side)
 
 
@@ -159,8 +167,8 @@ def test_common_vector_is_kept_wide():
     if True:
         assert info["lds_vec_bits"] == 2 and info["lds_write_bytes"] == 16
         for side in ("lds_write", "lds_read"):
-            assert oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6, 4, 2, 64,
-                                     gfx950_phases(16))[0] == 1
+            assert oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6, 4, 2,
+                                     banks_of(info, side), gfx950_phases(16, side))[0] == 1
 
 
 def test_plan_errors():
