@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the layout-conversion / gather hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--only-main]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--only-main] [--strategy N]
 
 A step is one pass of the headline workload (benchmark configs[1]: 8192 tiles of
 128x128 bf16 transposed through LDS) with inputs already resident in HBM.  The
@@ -35,12 +35,18 @@ def main() -> int:
     ap.add_argument("--only-main", action="store_true", help="skip the per-config table")
     ap.add_argument("--workload", type=int, default=2, help="config id timed as the main line (default 2)")
     ap.add_argument("--table-steps", type=int, default=30, help="launches per config in the per-config table")
+    ap.add_argument("--strategy", type=int, default=None,
+                    help="force a conversion strategy for every plan (3: element-wide LDS, 4: 128-bit LDS "
+                         "where it applies); default: the planner's choice")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; tiles are independent, so more GPUs would each "
               "take a tile range with no communication, but no multi-GPU path is built or measured. "
               "Run with --gpus 1.", file=sys.stderr)
         return 2
+
+    if args.strategy is not None:
+        os.environ["LL_FORCE_STRATEGY"] = str(args.strategy)     # read by the planner at plan time
 
     import torch
     import paper_2505_23819_amd as ll
@@ -162,13 +168,24 @@ def main() -> int:
             entry = {"config": cfg.cid, "name": cfg.name, "kernel": inf["strategy_name"], "class": inf["kind_name"],
                      "algorithmic_bytes": ab, "us_median": round(md_ms * 1e3, 2), "us_min": round(mn_ms * 1e3, 2),
                      "GBps": round(ab / md_ms / 1e6, 1), "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)}
-            if "lds_write_bytes" in inf:
+            if inf.get("lds_write_bytes"):
                 entry.update({"lds_access_bytes": inf["lds_write_bytes"], "lds_bytes": inf["lds_bytes"],
                               "predicted_wavefronts": [inf["predicted_wavefronts_write"], inf["predicted_wavefronts_read"]]})
             del s, l
             torch.cuda.empty_cache()
             if cfg.cid != 1:
                 entry["copy_GBps_same_footprint"] = round(copy_ceiling(ab // 2), 1)
+            if cfg.kind == "convert" and args.strategy is None and inf["strategy_name"] in ("reg_permute", "wave_shuffle"):
+                # the same conversion staged through LDS (128-bit accesses), for comparison
+                os.environ["LL_FORCE_STRATEGY"] = "4"
+                l2, inf2, s2 = make_case(cfg, nsets)
+                del os.environ["LL_FORCE_STRATEGY"]
+                _, _, md2, _ = time_launches(l2, steps, 3)
+                entry["through_lds"] = {"kernel": inf2["strategy_name"], "lds_access_bytes": inf2["lds_write_bytes"],
+                                        "GBps": round(ab / md2 / 1e6, 1),
+                                        "predicted_wavefronts": [inf2["predicted_wavefronts_write"], inf2["predicted_wavefronts_read"]]}
+                del s2, l2
+                torch.cuda.empty_cache()
             table.append(entry)
         result["per_config"] = table
 

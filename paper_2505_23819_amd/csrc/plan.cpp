@@ -473,13 +473,15 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
         desc.threads = 256;
         return LL_OK;
     }
-    // Strategy, most specific first.  Conversions that stay inside a wave try the shuffle /
-    // register-only kernel; everything else (and whatever that kernel's structure does not cover)
-    // is staged through LDS, with 128-bit accesses when the in-register transpose applies and with
-    // element-wide accesses otherwise (always possible).
+    // Strategy, cheapest exchange first.  The kernel's lanes are not the layout's lanes (only the
+    // conversion and the image order are observable), so even a conversion that moves data between
+    // the layout's waves may need no exchange between the KERNEL's lanes once small blocks with the
+    // right run selectors as lanes are used: the register / shuffle planner is tried for every
+    // class.  What its structure does not cover is staged through LDS, with 128-bit accesses when
+    // the in-register transpose applies and element-wide accesses otherwise (always possible).
     const char *force = getenv("LL_FORCE_STRATEGY");
     bool applied = false;
-    if ((desc.kind == LL_KIND_REG_ONLY || desc.kind == LL_KIND_INTRA_WAVE) && !(force && atoi(force) >= LL_STRATEGY_LDS_ELEM)) {
+    if (!(force && atoi(force) >= LL_STRATEGY_LDS_ELEM)) {
         if (ll_status st = plan_wave_shuffle(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
         if (applied) return LL_OK;
     }

@@ -85,16 +85,22 @@ def test_classification_rules():
     assert kind(ident, reg_into_wave) == "lds"
 
 
-def test_strategies_of_the_configs():
+def test_strategies_of_the_configs(monkeypatch):
     got = {cid: plan_of(wl.config(cid)).info() for cid in (1, 2, 3, 4)}
-    assert got[1]["strategy_name"] == "lds_vec" and got[2]["strategy_name"] == "lds_vec"
+    # bit-permutation conversions need no LDS once the kernel picks its own lanes: registers only,
+    # or a few lane <-> register stages
+    assert got[1]["strategy_name"] in ("reg_permute", "wave_shuffle")
+    assert got[2]["strategy_name"] == "reg_permute" and got[2]["register_transpose"] == 1
     assert got[3]["strategy_name"] in ("reg_permute", "wave_shuffle")
     assert got[4]["strategy_name"] == "lds_elem"          # XOR layouts: no common run, element-wide LDS
-    for cid in (1, 2):
-        assert got[cid]["lds_write_bytes"] == 16 and got[cid]["lds_read_bytes"] == 16
-        assert got[cid]["register_transpose"] == 1
     for cid in (1, 2, 3, 4):
         assert got[cid]["global_vec_bytes"] == 16
+    # with the register / shuffle planner switched off, configs 1-3 stage through LDS with 128-bit accesses
+    monkeypatch.setenv("LL_FORCE_STRATEGY", "4")
+    for cid in (1, 2, 3):
+        info = plan_of(wl.config(cid)).info()
+        assert info["strategy_name"] == "lds_vec"
+        assert info["lds_write_bytes"] == 16 and info["lds_read_bytes"] == 16 and info["register_transpose"] == 1
 
 
 @pytest.mark.parametrize("force", ["3", "4"])
@@ -154,7 +160,7 @@ def test_random_layouts_plan_and_swizzle(w):
                 assert mx == 1, (w, d, trial, side)
 
 
-def test_common_vector_is_kept_wide():
+def test_common_vector_is_kept_wide(monkeypatch):
     # both layouts keep register bits 0,1 on logical bits 0,1 (4-byte elements): 16-byte LDS accesses
     d = 12
     rng = np.random.default_rng(3)
@@ -162,8 +168,10 @@ def test_common_vector_is_kept_wide():
     rest_b = [1 << int(p) for p in (rng.permutation(d - 2) + 2)]
     a = ll.distributed_layout(4, 6, 2, [d], [1, 2] + rest_a)
     b = ll.distributed_layout(4, 6, 2, [d], [1, 2] + rest_b)
+    assert ll.ll_plan_convert(a, b, 4).info()["strategy_name"] in ("reg_permute", "wave_shuffle", "lds_elem")
+    monkeypatch.setenv("LL_FORCE_STRATEGY", "3")
     info = ll.ll_plan_convert(a, b, 4).info()
-    assert info["strategy_name"] in ("lds_elem", "lds_vec")
+    assert info["strategy_name"] == "lds_elem"
     if True:
         assert info["lds_vec_bits"] == 2 and info["lds_write_bytes"] == 16
         for side in ("lds_write", "lds_read"):
