@@ -147,6 +147,16 @@ typedef struct {
     int32_t lds_banks_write;    /* ... and a write phase */
     int32_t lds_phase_lanes_write, lds_phase_lanes_read; /* lanes served together */
     int32_t predicted_wavefronts_write, predicted_wavefronts_read; /* per access phase; 1 = conflict free */
+    /* The shuffle schedule of Sec. 5.4 "Intra-warp Data Exchange", computed on the layouts' own
+     * lanes when both are distributed layouts (Def. "Distributed Layout") and the wave part of
+     * B^-1 o A is the identity; vectors are flattened logical indices.  V: common register vectors
+     * that fit one 32-bit shuffle; I = A_lane n B_lane; G = {e_i ^ f_i} with E = A_lane \ I and
+     * F = B_lane \ I in ascending order; R completes V u I u G (and the wave images) to a basis:
+     * the exchange takes 2^sched_nr rounds, one shuffle per lane and round.  Reported for
+     * reference and tests; the kernels use lane <-> register butterfly stages instead (see
+     * shuffle_rounds). */
+    int32_t sched_valid, sched_nv, sched_ni, sched_ng, sched_nr;
+    uint64_t sched_v[2], sched_i[8], sched_g[8], sched_r[LL_MAX_BITS];
 } ll_plan_desc;
 
 /* Plan the conversion of images under `src` into images under `dst` (both map the same

@@ -59,6 +59,10 @@ class ll_plan_desc(ctypes.Structure):
         ("lds_vec_bits", ctypes.c_int32), ("lds_banks", ctypes.c_int32), ("lds_banks_write", ctypes.c_int32),
         ("lds_phase_lanes_write", ctypes.c_int32), ("lds_phase_lanes_read", ctypes.c_int32),
         ("predicted_wavefronts_write", ctypes.c_int32), ("predicted_wavefronts_read", ctypes.c_int32),
+        ("sched_valid", ctypes.c_int32), ("sched_nv", ctypes.c_int32), ("sched_ni", ctypes.c_int32),
+        ("sched_ng", ctypes.c_int32), ("sched_nr", ctypes.c_int32),
+        ("sched_v", ctypes.c_uint64 * 2), ("sched_i", ctypes.c_uint64 * 8), ("sched_g", ctypes.c_uint64 * 8),
+        ("sched_r", ctypes.c_uint64 * LL_MAX_BITS),
     ]
 
 
@@ -219,6 +223,8 @@ def ll_plan_info(plan: Plan) -> dict:
     out["conv"] = out["conv"][:d.d]
     for key in ("lds_mem", "lds_write", "lds_read"):
         out[key] = out[key][:d.block_bits]
+    for key, cnt in (("sched_v", d.sched_nv), ("sched_i", d.sched_ni), ("sched_g", d.sched_ng), ("sched_r", d.sched_nr)):
+        out[key] = out[key][:cnt]
     out["kind_name"] = KIND_NAMES[d.kind]
     out["strategy_name"] = STRATEGY_NAMES[d.strategy]
     return out

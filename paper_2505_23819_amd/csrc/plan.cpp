@@ -432,6 +432,55 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     return check_lds_elem_tables(a, pext, n, vs, v, w, 1 << nvec_bits);
 }
 
+// The shuffle schedule exactly as Sec. 5.4 "Intra-warp Data Exchange" states it, on the layouts'
+// own registers and lanes.  Only for distributed layouts (every column a unit vector) whose
+// conversion keeps the wave part fixed.
+static void paper_shuffle_schedule(const ll_layout *a, const ll_layout *b, int w, ll_plan_desc *desc)
+{
+    desc->sched_valid = 0;
+    const int d = a->d_in;
+    for (int k = 0; k < d; ++k)
+        if (f2::popcount(a->bases[k]) != 1 || f2::popcount(b->bases[k]) != 1) return;
+    if (desc->kind != LL_KIND_REG_ONLY && desc->kind != LL_KIND_INTRA_WAVE) return;
+    const int nreg = a->bits_of(LL_IN_REG), lane0 = a->first_bit_of(LL_IN_LANE), wave0 = a->first_bit_of(LL_IN_WAVE);
+    auto members = [](const ll_layout *l, int from, int to) {
+        mat r(l->bases.begin() + from, l->bases.begin() + to);
+        std::sort(r.begin(), r.end());
+        return r;
+    };
+    auto both = [](const mat &x, const mat &y) {
+        mat r;
+        for (vec v : x)
+            if (std::find(y.begin(), y.end(), v) != y.end()) r.push_back(v);
+        return r;
+    };
+    auto minus = [](const mat &x, const mat &y) {
+        mat r;
+        for (vec v : x)
+            if (std::find(y.begin(), y.end(), v) == y.end()) r.push_back(v);
+        return r;
+    };
+    const mat areg = members(a, 0, nreg), breg = members(b, 0, nreg);
+    const mat alane = members(a, lane0, wave0), blane = members(b, lane0, wave0);
+    mat V = both(areg, breg);
+    const size_t vmax = w >= 4 ? 0 : (size_t)ilog2(4u / (unsigned)w);      // 32-bit shuffle payload
+    if (V.size() > vmax) V.resize(vmax);
+    const mat I = both(alane, blane), E = minus(alane, I), F = minus(blane, I);
+    if (E.size() != F.size()) return;                                       // cannot happen without broadcasting
+    mat G;
+    for (size_t i = 0; i < E.size(); ++i) G.push_back(E[i] ^ F[i]);
+    mat fixed = concat(concat(V, I), G);
+    fixed.insert(fixed.end(), a->bases.begin() + wave0, a->bases.end());    // waves (and tiles) stay where they are
+    const mat R = f2::complement(fixed, a->d_out);
+    if (V.size() > 2 || I.size() > 8 || G.size() > 8 || R.size() > LL_MAX_BITS) return;
+    desc->sched_nv = (int)V.size(); desc->sched_ni = (int)I.size(); desc->sched_ng = (int)G.size(); desc->sched_nr = (int)R.size();
+    std::copy(V.begin(), V.end(), desc->sched_v);
+    std::copy(I.begin(), I.end(), desc->sched_i);
+    std::copy(G.begin(), G.end(), desc->sched_g);
+    std::copy(R.begin(), R.end(), desc->sched_r);
+    desc->sched_valid = 1;
+}
+
 ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan)
 {
     if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8)
@@ -467,6 +516,7 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     desc.elem_bytes = elem_bytes;
     for (int k = 0; k < d; ++k) desc.conv[k] = p[k];
     desc.kind = classify(p, d, src->bits_of(LL_IN_REG), src->first_bit_of(LL_IN_WAVE));
+    paper_shuffle_schedule(src, dst, elem_bytes, &desc);
     if (desc.kind == LL_KIND_NOOP) {
         desc.strategy = LL_STRATEGY_COPY;
         desc.global_vec_bytes = 16;

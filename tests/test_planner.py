@@ -239,3 +239,46 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     with pytest.raises(ll.LLError) as e:
         ll.ll_gather(regaxis, 0, 4, 0, 0, 0, 0, stream=0)
     assert e.value.status == ll.LL_ERR_UNSUPPORTED
+
+
+def test_paper_shuffle_schedule_invariants():
+    """Sec. 5.4 "Intra-warp Data Exchange": with V, I, E, F, G and the completion R as the paper
+    defines them, every affine space R(i) + span(V u I u G) holds exactly one vectorized element per
+    thread in layout A and in layout B, and the exchange takes 2^|R| rounds.  Checked by brute
+    force over all hardware indices with the oracle's apply."""
+    rng = np.random.default_rng(42)
+    for w, nreg, nlane, nwave in [(4, 2, 5, 1), (4, 4, 6, 0), (2, 3, 6, 1), (1, 4, 6, 0), (4, 5, 5, 1), (2, 5, 4, 0)]:
+        d = nreg + nlane + nwave
+        low = nreg + nlane
+        for trial in range(2):
+            waves = [1 << int(x) for x in rng.choice(d, size=nwave, replace=False)]
+            rest = [1 << k for k in range(d) if (1 << k) not in waves]
+            ca = [rest[int(i)] for i in rng.permutation(low)] + waves
+            cb = [rest[int(i)] for i in rng.permutation(low)] + waves
+            a = ll.distributed_layout(nreg, nlane, nwave, [d], ca)
+            b = ll.distributed_layout(nreg, nlane, nwave, [d], cb)
+            info = ll.ll_plan_convert(a, b, w).info()
+            if info["kind_name"] == "noop":
+                continue
+            assert info["kind_name"] in ("reg_only", "intra_wave") and info["sched_valid"] == 1
+            V, I, G, R = info["sched_v"], info["sched_i"], info["sched_g"], info["sched_r"]
+            assert len(V) <= {1: 2, 2: 1, 4: 0, 8: 0}[w]                     # 32-bit payload
+            assert set(V) <= set(ca[:nreg]) & set(cb[:nreg])
+            assert set(I) == set(ca[nreg:low]) & set(cb[nreg:low])
+            assert len(G) == nlane - len(I) and len(R) + len(V) == nreg
+            sub = span(V + I + G)
+            assert len(sub) == 1 << (len(V) + len(I) + len(G))                # a basis
+            for cols in (ca, cb):
+                for wv in range(1 << nwave):
+                    wave_img = oracle.apply(cols, wv << low)
+                    for r in span(R):
+                        coset = {r ^ wave_img ^ x for x in sub}
+                        per_lane = {}
+                        for h in range(1 << low):
+                            x = oracle.apply(cols, h | (wv << low))
+                            if x in coset:
+                                per_lane.setdefault(h >> nreg, []).append(x)
+                        assert len(per_lane) == 1 << nlane                    # every thread takes part
+                        for xs in per_lane.values():
+                            assert len(xs) == 1 << len(V)                     # exactly one vectorized element
+                            assert {x ^ xs[0] for x in xs} == span(V)
