@@ -57,6 +57,11 @@ def _load():
         lib.oracle_compose.argtypes = [u64p, ctypes.c_int, ctypes.c_int, u64p, ctypes.c_int, u64p]
         lib.oracle_inverse_table.restype = ctypes.c_int
         lib.oracle_inverse_table.argtypes = [u64p, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32)]
+        lib.oracle_right_inverse_table.restype = ctypes.c_int
+        lib.oracle_right_inverse_table.argtypes = [u64p, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32)]
+        lib.oracle_convert_general.restype = ctypes.c_int
+        lib.oracle_convert_general.argtypes = [u64p, ctypes.c_int, u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
         lib.oracle_convert.restype = ctypes.c_int
         lib.oracle_convert.argtypes = [u64p, u64p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                        ctypes.c_void_p, ctypes.c_int64]
@@ -104,6 +109,29 @@ def inverse_table(bases: Sequence[int]) -> np.ndarray:
     if rc != OK:
         raise OracleError(rc, "inverse_table")
     return table
+
+
+def right_inverse_table(bases: Sequence[int], d_out: int) -> np.ndarray:
+    """table[x] = the h with L(h) = x whose free variables are zero (surjective L, broadcasting allowed)."""
+    table = np.empty(1 << d_out, dtype=np.uint32)
+    rc = _load().oracle_right_inverse_table(_u64(bases), len(bases), d_out,
+                                            table.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)))
+    if rc != OK:
+        raise OracleError(rc, "right_inverse_table")
+    return table
+
+
+def convert_general(bases_a: Sequence[int], bases_b: Sequence[int], d_out: int, src: np.ndarray) -> np.ndarray:
+    """Conversion with broadcasting: dst[hB] = src[A^+(B hB)]; src holds ntiles * 2^len(A) elements."""
+    da, db = len(bases_a), len(bases_b)
+    _check_img(src, da, "src")
+    ntiles = src.size >> da
+    dst = np.empty(ntiles << db, dtype=src.dtype)
+    rc = _load().oracle_convert_general(_u64(bases_a), da, _u64(bases_b), db, d_out, src.itemsize,
+                                        src.ctypes.data, dst.ctypes.data, ntiles)
+    if rc != OK:
+        raise OracleError(rc, "convert_general")
+    return dst
 
 
 def _check_img(a: np.ndarray, d: int, what: str):

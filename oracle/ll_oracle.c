@@ -23,6 +23,13 @@
  *   oracle_inverse_table    Def. Right Inverse, restricted to bijective
  *                           layouts: the inverse is found by tabulating L(h)
  *                           for every h (no elimination)
+ *   oracle_right_inverse_table  Def. Right Inverse / Sec. 5.4 rule 2 for surjective
+ *                           layouts that are not injective (broadcasting): the
+ *                           solution with all free variables zero, built by
+ *                           growing the span column by column (no elimination)
+ *   oracle_convert_general  Sec. 5.4 with broadcasting: every destination unit
+ *                           reads the value of its logical element from the
+ *                           canonical source unit
  *   oracle_convert          Sec. 5.4: the conversion is B^-1 o A; element by
  *                           element on images (see below)
  *   oracle_convert_table    same result; the composed map is tabulated once
@@ -104,6 +111,83 @@ int oracle_inverse_table(const uint64_t *bases, int d, uint32_t *table)
             return ORACLE_ERR_NOT_BIJECTIVE;
         table[x] = (uint32_t)h;
     }
+    return ORACLE_OK;
+}
+
+/*
+ * Right inverse of a surjective layout with d_in >= d_out input bits
+ * (Def. Right Inverse; Sec. 5.4 rule 2: "set the slack variables to zero").
+ * Columns are visited in input order (register bits first).  A column that is
+ * not yet in the span of the earlier ones is a pivot: it doubles the span, and
+ * every new element x ^ col gets the representative table[x] | 1 << k.  A
+ * column already in the span is a free variable and is never used.  Hence
+ * table[x] is the unique h with L(h) = x whose free variables are all zero.
+ */
+int oracle_right_inverse_table(const uint64_t *bases, int d_in, int d_out, uint32_t *table)
+{
+    if (!bases || !table || d_in < 0 || d_in > 30 || d_out < 0 || d_out > 30)
+        return ORACLE_ERR_ARG;
+    const uint64_t n = 1ull << d_out;
+    for (uint64_t x = 0; x < n; ++x)
+        table[x] = 0xFFFFFFFFu;
+    table[0] = 0;
+    uint64_t *members = (uint64_t *)malloc(n * sizeof(uint64_t));   /* elements of the span so far */
+    if (!members) return ORACLE_ERR_ALLOC;
+    uint64_t count = 1;
+    members[0] = 0;
+    for (int k = 0; k < d_in; ++k) {
+        const uint64_t col = bases[k];
+        if (col >= n) { free(members); return ORACLE_ERR_ARG; }
+        if (table[col] != 0xFFFFFFFFu)
+            continue;                           /* dependent column: a free variable, left at zero */
+        for (uint64_t i = 0; i < count; ++i) {
+            const uint64_t x = members[i] ^ col;
+            table[x] = table[members[i]] | (1u << k);
+            members[count + i] = x;
+        }
+        count *= 2;
+    }
+    free(members);
+    return count == n ? ORACLE_OK : ORACLE_ERR_NOT_BIJECTIVE;      /* not surjective */
+}
+
+/*
+ * Conversion with broadcasting (Sec. 5.4: B^-1 o A with rule 2; Sec. 5.1
+ * "Broadcasting").  A has dA input bits, B has dB, both map onto the same d_out
+ * logical bits and both are surjective.  For every tile t and every destination
+ * hardware index hB:
+ *     x  = B(hB)                 (the logical element unit hB must hold)
+ *     hA = A^+(x)                (canonical source unit: free variables zero)
+ *     dst[t*2^dB + hB] = src[t*2^dA + hA]
+ */
+int oracle_convert_general(const uint64_t *basesA, int dA, const uint64_t *basesB, int dB, int d_out,
+                           int elem_bytes, const void *src, void *dst, int64_t ntiles)
+{
+    if (!basesA || !basesB || dA < 0 || dA > 30 || dB < 0 || dB > 30 || d_out < 0 || d_out > 30 ||
+        elem_bytes <= 0 || ntiles < 0)
+        return ORACLE_ERR_ARG;
+    if (ntiles > 0 && (!src || !dst))
+        return ORACLE_ERR_ARG;
+    uint32_t *invA = (uint32_t *)malloc((1ull << d_out) * sizeof(uint32_t));
+    uint32_t *invB = (uint32_t *)malloc((1ull << d_out) * sizeof(uint32_t));
+    if (!invA || !invB) { free(invA); free(invB); return ORACLE_ERR_ALLOC; }
+    int rc = oracle_right_inverse_table(basesA, dA, d_out, invA);
+    if (rc == ORACLE_OK)
+        rc = oracle_right_inverse_table(basesB, dB, d_out, invB);   /* only to check that B is surjective */
+    if (rc != ORACLE_OK) { free(invA); free(invB); return rc; }
+    const unsigned char *s = (const unsigned char *)src;
+    unsigned char *o = (unsigned char *)dst;
+    const uint64_t nA = 1ull << dA, nB = 1ull << dB;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        for (uint64_t hB = 0; hB < nB; ++hB) {
+            const uint64_t x = oracle_apply(basesB, dB, hB);
+            const uint64_t hA = invA[x];
+            memcpy(o + ((uint64_t)t * nB + hB) * (uint64_t)elem_bytes,
+                   s + ((uint64_t)t * nA + hA) * (uint64_t)elem_bytes, (size_t)elem_bytes);
+        }
+    }
+    free(invA);
+    free(invB);
     return ORACLE_OK;
 }
 

@@ -450,3 +450,93 @@ def test_wavefronts_match_lemma_closed_form(vec_bits, elem_bytes):
         c = len(span(s_vec + s_idx) & span(l_thr))
         if c == 1:
             assert tot == nph                               # conflict free: one wavefront per transaction
+
+
+# ----------------------------------------------------------------------------
+# broadcasting: right inverse with free variables zero, conversion between non-injective layouts
+# ----------------------------------------------------------------------------
+
+def random_surjective(rng, d_in, d_out):
+    while True:
+        cols = [int(rng.integers(0, 1 << d_out)) for _ in range(d_in)]
+        cols[int(rng.integers(0, d_in))] = 0 if d_in > d_out else cols[0]      # make a zero column likely
+        if len(span(cols)) == 1 << d_out:
+            return cols
+
+
+def test_right_inverse_small_hand_cases():
+    # duplicated column: the leftmost copy is the pivot, the second stays zero
+    assert list(oracle.right_inverse_table([1, 1, 2], 2)) == [0, 1, 4, 5]
+    # zero column in the middle (Sec. 5.1: a zero register column = broadcast): never used
+    assert list(oracle.right_inverse_table([1, 0, 2], 2)) == [0, 1, 4, 5]
+    # third column = sum of the first two: free variable
+    assert list(oracle.right_inverse_table([1, 2, 3, 4], 3)) == [0, 1, 2, 3, 8, 9, 10, 11]
+    with pytest.raises(oracle.OracleError):
+        oracle.right_inverse_table([1, 1, 1], 2)          # not surjective
+
+
+def test_right_inverse_is_a_right_inverse_with_zero_free_variables():
+    rng = np.random.default_rng(23)
+    for d_in, d_out in [(4, 3), (6, 4), (9, 8), (12, 8), (5, 5)]:
+        for _ in range(4):
+            cols = random_surjective(rng, d_in, d_out)
+            table = oracle.right_inverse_table(cols, d_out)
+            # pivots = columns not in the span of the earlier ones (python sets, independent of the oracle)
+            pivots, have = [], {0}
+            for k, c in enumerate(cols):
+                if c not in have:
+                    pivots.append(k)
+                    have |= {x ^ c for x in have}
+            pivot_mask = sum(1 << k for k in pivots)
+            for x in range(1 << d_out):
+                h = int(table[x])
+                assert np_apply(cols, d_out, h) == x           # M X = I
+                assert h & ~pivot_mask == 0                    # free variables are zero
+    # bijective case: coincides with the plain inverse
+    cols = random_invertible(np.random.default_rng(24), 7)
+    assert np.array_equal(oracle.right_inverse_table(cols, 7), oracle.inverse_table(cols))
+
+
+def test_convert_general_delivers_the_logical_element():
+    # "every destination unit receives the element at logical B(hB)": build a consistent source
+    # image from a logical tensor X (src[hA] = X[A hA]); then dst[hB] must be X[B hB], whatever
+    # representative the right inverse picks.
+    rng = np.random.default_rng(25)
+    for da, db, d_out in [(5, 4, 4), (4, 6, 4), (7, 7, 5), (10, 9, 8), (8, 8, 8)]:
+        for _ in range(3):
+            a, b = random_surjective(rng, da, d_out), random_surjective(rng, db, d_out)
+            x_log = rng.integers(0, 1 << 32, size=2 << d_out, dtype=np.uint32).reshape(2, -1)
+            src = np.stack([x_log[t][np_images(a, da) if da == d_out else
+                                     np.array([np_apply(a, d_out, h) for h in range(1 << da)])] for t in range(2)]).reshape(-1)
+            dst = oracle.convert_general(a, b, d_out, src)
+            img_b = np.array([np_apply(b, d_out, h) for h in range(1 << db)])
+            want = np.stack([x_log[t][img_b] for t in range(2)]).reshape(-1)
+            assert np.array_equal(dst, want)
+
+
+def test_convert_general_reads_the_canonical_source_unit():
+    # inconsistent source (replicas differ): the value must come from the unit with free variables zero
+    a = [1, 1, 2]          # bits 0 and 1 of the source index are replicas of logical bit 0
+    b = [1, 2]
+    src = np.arange(8, dtype=np.uint32) + 100
+    dst = oracle.convert_general(a, b, 2, src)
+    assert list(dst) == [100 + 0, 100 + 1, 100 + 4, 100 + 5]
+    # bijective layouts: same as the plain conversion
+    rng = np.random.default_rng(26)
+    a, b = random_invertible(rng, 6), random_invertible(rng, 6)
+    src = rng.integers(0, 1 << 16, size=3 << 6, dtype=np.uint16)
+    assert np.array_equal(oracle.convert_general(a, b, 6, src), oracle.convert(a, b, src))
+
+
+def test_convert_general_paper_broadcast_example(golden_dir):
+    # Sec. 5.1: a zero column added to A_reg makes registers 4-7 hold the same elements as 0-3.
+    a = load_layout_a(golden_dir)
+    widened = a[:2] + [0] + a[2:]
+    rng = np.random.default_rng(27)
+    src = rng.integers(0, 1 << 32, size=256, dtype=np.uint32)             # image under Layout A
+    wide = oracle.convert_general(a, widened, 8, src)                    # 512 elements
+    for h in range(512):
+        reg, rest = h & 7, h >> 3
+        assert wide[h] == src[(reg & 3) | (rest << 2)]                    # registers 4-7 alias 0-3
+    back = oracle.convert_general(widened, a, 8, wide)
+    assert np.array_equal(back, src)
