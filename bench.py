@@ -189,6 +189,28 @@ def main() -> int:
             table.append(entry)
         result["per_config"] = table
 
+        # conversions between layouts that replicate data (zero columns): one copy of every logical
+        # element read, every destination slot written
+        btable = []
+        for case in wl.broadcast_cases():
+            a = ll.distributed_layout(*case.src_in, case.out_dim_bits, case.src_bases)
+            b = ll.distributed_layout(*case.dst_in, case.out_dim_bits, case.dst_bases)
+            plan = ll.ll_plan_convert(a, b, case.elem_bytes)
+            inf = plan.info()
+            x = case.gen_data(0, case.ntiles, dev)
+            outs = [torch.empty(case.ntiles << case.d_dst, dtype=x.dtype, device=dev) for _ in range(2)]
+            _, _, md_ms, mn_ms = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % 2], case.ntiles),
+                                               args.table_steps, 3)
+            ab = case.algorithmic_bytes()
+            btable.append({"name": case.name, "kernel": inf["strategy_name"], "src_tile_bits": case.d_src,
+                           "dst_tile_bits": case.d_dst, "logical_bits": case.d_out, "algorithmic_bytes": ab,
+                           "us_median": round(md_ms * 1e3, 2), "GBps": round(ab / md_ms / 1e6, 1),
+                           "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                           "predicted_wavefronts": [inf["predicted_wavefronts_write"], inf["predicted_wavefronts_read"]]})
+            del x, outs
+            torch.cuda.empty_cache()
+        result["broadcast_conversions"] = btable
+
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(main_cfg)
 

@@ -103,7 +103,8 @@ typedef enum {
     LL_KIND_NOOP = 0,        /* B^-1 o A is the identity */
     LL_KIND_REG_ONLY = 1,    /* only register bits move ("intra-thread data exchange") */
     LL_KIND_INTRA_WAVE = 2,  /* the wave part of B^-1 o A is the identity ("intra-warp") */
-    LL_KIND_LDS = 3          /* data crosses waves: staged through shared memory (LDS) */
+    LL_KIND_LDS = 3,         /* data crosses waves: staged through shared memory (LDS) */
+    LL_KIND_BROADCAST = 4    /* a layout is not injective (Sec. 5.1 "Broadcasting", Sec. 5.4 rule 2) */
 } ll_plan_kind;
 
 typedef enum {
@@ -111,7 +112,8 @@ typedef enum {
     LL_STRATEGY_REG_PERMUTE = 1, /* each lane loads whole vectors, permutes them in registers, stores */
     LL_STRATEGY_WAVE_SHUFFLE = 2, /* wave64 exchange by cross-lane shuffles */
     LL_STRATEGY_LDS_ELEM = 3,  /* LDS staging, element-wide (or common-vector-wide) accesses, XOR swizzle */
-    LL_STRATEGY_LDS_VEC = 4    /* LDS staging with in-register transposes and 128-bit LDS accesses */
+    LL_STRATEGY_LDS_VEC = 4,   /* LDS staging with in-register transposes and 128-bit LDS accesses */
+    LL_STRATEGY_LDS_PULL = 5   /* broadcasting layouts: destination units pull from LDS-staged source runs */
 } ll_strategy;
 
 #define LL_PLAN_MAX_BLOCK_BITS 20
@@ -119,9 +121,11 @@ typedef enum {
 typedef struct {
     int32_t kind;               /* ll_plan_kind: the paper's classification of B^-1 o A */
     int32_t strategy;           /* ll_strategy: the kernel that ll_convert launches */
-    int32_t d;                  /* index bits of one tile */
+    int32_t d;                  /* index bits of one (source) tile */
+    int32_t d_dst;              /* index bits of one destination tile (= d unless a layout broadcasts) */
     int32_t elem_bytes;
-    uint64_t conv[LL_MAX_BITS]; /* columns of B^-1 o A on the d hardware-index bits */
+    uint64_t conv[LL_MAX_BITS]; /* columns of B^-1 o A on the d hardware-index bits (bijective layouts) */
+    uint64_t pull[LL_MAX_BITS]; /* broadcasting layouts: columns of A^+ o B, destination index -> source index */
     int32_t global_vec_bytes;   /* width of every global load and store */
     int32_t lds_write_bytes;    /* width of one LDS write (0 if LDS unused) */
     int32_t lds_read_bytes;     /* width of one LDS read  (0 if LDS unused) */
@@ -159,18 +163,24 @@ typedef struct {
     uint64_t sched_v[2], sched_i[8], sched_g[8], sched_r[LL_MAX_BITS];
 } ll_plan_desc;
 
-/* Plan the conversion of images under `src` into images under `dst` (both map the same
- * register/lane/wave input dims onto output spaces of equal size).  Computes B^-1 o A
- * (Sec. 5.4), classifies it (intra-thread / intra-warp / shared memory), and picks the kernel,
- * its vector widths and, for LDS paths, the XOR swizzle.  elem_bytes is 1, 2, 4 or 8.
- * Both layouts must be bijective (LL_ERR_NOT_INJECTIVE / LL_ERR_NOT_SURJECTIVE otherwise); a
- * `tile` input dim, if present, must map identically in both (LL_ERR_TILE_MIXED otherwise). */
+/* Plan the conversion of images under `src` into images under `dst` (both map register / lane /
+ * wave [/ tile] inputs onto output spaces of equal size).  Computes B^-1 o A (Sec. 5.4),
+ * classifies it (intra-thread / intra-warp / shared memory), and picks the kernel, its vector
+ * widths and, for LDS paths, the XOR swizzle.  elem_bytes is 1, 2, 4 or 8.
+ * Both layouts must be surjective (LL_ERR_NOT_SURJECTIVE otherwise).  If both are bijective they
+ * must have the same input dims (LL_ERR_DIM_MISMATCH), and a `tile` input dim, if present, must
+ * map identically in both (LL_ERR_TILE_MIXED).  If a layout is not injective (broadcasting:
+ * zero or dependent columns, Sec. 5.1) the two may have different input dims; the plan then
+ * pulls every destination unit's logical element from the source unit given by the right
+ * inverse with free variables zero (Sec. 5.4 rule 2), source tiles hold 2^d and destination
+ * tiles 2^d_dst elements. */
 ll_status ll_plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan **out);
 ll_status ll_plan_info(const ll_plan *plan, ll_plan_desc *out);
 ll_status ll_plan_destroy(ll_plan *plan);
 
 /* Apply a plan: dst_dev[t * 2^d + (B^-1 o A)(h)] = src_dev[t * 2^d + h] for every tile t < ntiles
- * and every h (Sec. 5.4).  Pointers are DEVICE pointers.  Asynchronous on hip_stream.
+ * and every h (Sec. 5.4); for broadcasting plans dst_dev[t * 2^d_dst + hB] =
+ * src_dev[t * 2^d + (A^+ o B)(hB)].  Pointers are DEVICE pointers.  Asynchronous on hip_stream.
  * ntiles == 0 is a no-op. */
 ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, int64_t ntiles, void *hip_stream);
 

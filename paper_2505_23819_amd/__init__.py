@@ -18,13 +18,13 @@ from . import build as _build
 LL_OK, LL_ERR_INVALID_ARG, LL_ERR_DIM_MISMATCH, LL_ERR_NOT_SURJECTIVE, LL_ERR_NOT_INJECTIVE, \
     LL_ERR_TILE_MIXED, LL_ERR_AXIS_NOT_IN_WAVE, LL_ERR_UNSUPPORTED, LL_ERR_DEVICE = range(9)
 LL_IN_REG, LL_IN_LANE, LL_IN_WAVE, LL_IN_TILE, LL_IN_OFFSET = range(5)
-LL_KIND_NOOP, LL_KIND_REG_ONLY, LL_KIND_INTRA_WAVE, LL_KIND_LDS = range(4)
+LL_KIND_NOOP, LL_KIND_REG_ONLY, LL_KIND_INTRA_WAVE, LL_KIND_LDS, LL_KIND_BROADCAST = range(5)
 LL_STRATEGY_COPY, LL_STRATEGY_REG_PERMUTE, LL_STRATEGY_WAVE_SHUFFLE, LL_STRATEGY_LDS_ELEM, \
-    LL_STRATEGY_LDS_VEC = range(5)
+    LL_STRATEGY_LDS_VEC, LL_STRATEGY_LDS_PULL = range(6)
 LL_MAX_IN_DIMS, LL_MAX_OUT_DIMS, LL_MAX_BITS, LL_PLAN_MAX_BLOCK_BITS = 5, 8, 30, 20
 
-KIND_NAMES = ["noop", "reg_only", "intra_wave", "lds"]
-STRATEGY_NAMES = ["copy", "reg_permute", "wave_shuffle", "lds_elem", "lds_vec"]
+KIND_NAMES = ["noop", "reg_only", "intra_wave", "lds", "broadcast"]
+STRATEGY_NAMES = ["copy", "reg_permute", "wave_shuffle", "lds_elem", "lds_vec", "lds_pull"]
 
 EXPORTED_SYMBOLS = [
     "ll_layout_create", "ll_layout_destroy", "ll_layout_get", "ll_layout_apply", "ll_compose",
@@ -43,9 +43,9 @@ class ll_out_dim(ctypes.Structure):
 
 class ll_plan_desc(ctypes.Structure):
     _fields_ = [
-        ("kind", ctypes.c_int32), ("strategy", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("kind", ctypes.c_int32), ("strategy", ctypes.c_int32), ("d", ctypes.c_int32), ("d_dst", ctypes.c_int32),
         ("elem_bytes", ctypes.c_int32),
-        ("conv", ctypes.c_uint64 * LL_MAX_BITS),
+        ("conv", ctypes.c_uint64 * LL_MAX_BITS), ("pull", ctypes.c_uint64 * LL_MAX_BITS),
         ("global_vec_bytes", ctypes.c_int32), ("lds_write_bytes", ctypes.c_int32),
         ("lds_read_bytes", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
         ("threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
@@ -221,6 +221,7 @@ def ll_plan_info(plan: Plan) -> dict:
         v = getattr(d, name)
         out[name] = [int(x) for x in v] if hasattr(v, "__len__") else int(v)
     out["conv"] = out["conv"][:d.d]
+    out["pull"] = out["pull"][:d.d_dst]
     for key in ("lds_mem", "lds_write", "lds_read"):
         out[key] = out[key][:d.block_bits]
     for key, cnt in (("sched_v", d.sched_nv), ("sched_i", d.sched_ni), ("sched_g", d.sched_ng), ("sched_r", d.sched_nr)):

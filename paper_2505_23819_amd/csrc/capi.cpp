@@ -210,11 +210,12 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
     if (ntiles == 0) return LL_OK;
     if (!src_dev || !dst_dev) return fail(LL_ERR_INVALID_ARG, "null device pointer");
     if (misaligned(src_dev) || misaligned(dst_dev)) return fail(LL_ERR_INVALID_ARG, "device buffers must be 16-byte aligned");
-    const unsigned long long bytes = (unsigned long long)ntiles * plan->desc.elem_bytes << plan->desc.d;
-    if ((bytes >> plan->desc.d) / plan->desc.elem_bytes != (unsigned long long)ntiles || bytes > (1ull << 46))
-        return fail(LL_ERR_INVALID_ARG, "ntiles is too large");
+    const int dmax = plan->desc.d > plan->desc.d_dst ? plan->desc.d : plan->desc.d_dst;
+    if (ntiles > (1ll << 40) >> dmax) return fail(LL_ERR_INVALID_ARG, "ntiles is too large");
+    const unsigned long long sbytes = (unsigned long long)ntiles * plan->desc.elem_bytes << plan->desc.d;
+    const unsigned long long dbytes = (unsigned long long)ntiles * plan->desc.elem_bytes << plan->desc.d_dst;
     const char *s = static_cast<const char *>(src_dev), *t = static_cast<const char *>(dst_dev);
-    if (s < t + bytes && t < s + bytes) return fail(LL_ERR_INVALID_ARG, "source and destination buffers overlap");
+    if (s < t + dbytes && t < s + sbytes) return fail(LL_ERR_INVALID_ARG, "source and destination buffers overlap");
     return ll::run_convert(plan, src_dev, dst_dev, ntiles, hip_stream);
 }
 

@@ -467,6 +467,106 @@ ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose,
 }
 
 // ---------------------------------------------------------------------------------------------
+// conversion with broadcasting: destination units pull from the canonical source unit
+// ---------------------------------------------------------------------------------------------
+
+// W: element bytes, NVS: source vectors staged per thread.  256 threads.  Element-wide LDS accesses.
+template <int W, int NVS>
+__global__ __launch_bounds__(256) void k_pull(const PullArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
+    constexpr int NSUB = 1 << VS;
+    const uint32_t tid = threadIdx.x;
+    uint32_t ls = 0, ld = 0, lw = 0, lr = 0;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const uint32_t m = 0u - ((tid >> b) & 1u);
+        ls ^= a.lane_src[b] & m;
+        ld ^= a.lane_dst[b] & m;
+        lw ^= a.lds_wr_lane[b] & m;
+        lr ^= a.lds_rd_lane[b] & m;
+    }
+    const long long blk = blockIdx.x;
+    const long long group = blk >> a.coset_bits;
+    const uint32_t c = (uint32_t)(blk & ((1ll << a.coset_bits) - 1));
+    uint32_t cs = 0, cd = 0, cr = 0;
+    for (int b = 0; b < a.coset_bits; ++b) {
+        const uint32_t m = 0u - ((c >> b) & 1u);
+        cs ^= a.coset_src[b] & m;
+        cd ^= a.coset_dst[b] & m;
+        cr ^= a.coset_lds_rd[b] & m;
+    }
+    const unsigned char *sbase = static_cast<const unsigned char *>(a.src) + (((size_t)group << (a.d_src + a.group_bits)) * W);
+    unsigned char *dbase = static_cast<unsigned char *>(a.dst) + (((size_t)group << (a.d_dst + a.group_bits)) * W);
+    const long long left = a.ntiles - (group << a.group_bits);
+    const uint32_t tiles_here = left > (1ll << a.group_bits) ? (1u << a.group_bits) : (uint32_t)left;
+    const __amdgpu_buffer_rsrc_t srsrc = make_rsrc(sbase, (tiles_here << a.d_src) * W);
+    const __amdgpu_buffer_rsrc_t drsrc = make_rsrc(dbase, (tiles_here << a.d_dst) * W);
+    const uint32_t nsrc = 1u << a.src_vec_bits;
+
+    uint32_t r[NVS][4];
+#pragma unroll
+    for (int i = 0; i < NVS; ++i) {
+        const uint32_t off = cs ^ ls ^ a.iter_src[i];
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (tid + 256u * i < nsrc) v = buf_load16(srsrc, off * W);
+        r[i][0] = v.x; r[i][1] = v.y; r[i][2] = v.z; r[i][3] = v.w;
+    }
+#pragma unroll
+    for (int i = 0; i < NVS; ++i) {
+        if (tid + 256u * i < nsrc) {
+            const uint32_t base = lw ^ a.lds_wr_iter[i];
+#pragma unroll
+            for (int s = 0; s < NSUB; ++s) lds_put<W>(lds, base ^ a.lds_wr_sub[s], r[i], s);
+        }
+    }
+    __syncthreads();
+    for (int it = 0; it < a.dst_iters; ++it) {
+        uint32_t ib = 0, ob = 0;                     // wave-uniform parts of this iteration
+        for (int b = 0; (it >> b) != 0; ++b) {
+            const uint32_t m = 0u - (((uint32_t)it >> b) & 1u);
+            ib ^= a.lds_rd_iter_bit[b] & m;
+            ob ^= a.iter_dst_bit[b] & m;
+        }
+        const uint32_t base = cr ^ lr ^ ib;
+        uint32_t o[4];
+#pragma unroll
+        for (int s = 0; s < NSUB; ++s) lds_get<W>(lds, base ^ a.lds_rd_sub[s], o, s);
+        const u32x4 v = {o[0], o[1], o[2], o[3]};
+        buf_store16(drsrc, (cd ^ ld ^ ob) * W, v);
+    }
+}
+
+template <int W>
+static ll_status launch_pull_w(const PullArgs &a, int src_iters, int lds_bytes, hipStream_t stream)
+{
+    const dim3 grid((unsigned)a.nblocks), block(256);
+    switch (src_iters) {
+    case 1: hipLaunchKernelGGL((k_pull<W, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 2: hipLaunchKernelGGL((k_pull<W, 2>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 4: hipLaunchKernelGGL((k_pull<W, 4>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 8: hipLaunchKernelGGL((k_pull<W, 8>), grid, block, (size_t)lds_bytes, stream, a); break;
+    default: return fail(LL_ERR_UNSUPPORTED, "no broadcast kernel for %d source vectors per thread", src_iters);
+    }
+    return check_launch("broadcast conversion kernel launch");
+}
+
+ll_status launch_pull(const PullArgs &a, int elem_bytes, int src_iters, int lds_bytes, void *stream)
+{
+    if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
+    if (lds_bytes <= 0 || lds_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "LDS block of %d bytes", lds_bytes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (elem_bytes) {
+    case 1: return launch_pull_w<1>(a, src_iters, lds_bytes, s);
+    case 2: return launch_pull_w<2>(a, src_iters, lds_bytes, s);
+    case 4: return launch_pull_w<4>(a, src_iters, lds_bytes, s);
+    case 8: return launch_pull_w<8>(a, src_iters, lds_bytes, s);
+    default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // wave-local gather (paper Sec. 5.5): one kernel wave per layout wave, lane = layout lane
 // ---------------------------------------------------------------------------------------------
 

@@ -60,6 +60,29 @@ struct VecArgs {
     uint32_t lds_wr_iter[kMaxIter], lds_rd_iter[kMaxIter];
 };
 
+// Conversion between layouts with broadcasting (paper Sec. 5.1 "Broadcasting", Sec. 5.4 rule 2):
+// every destination unit pulls the value of its logical element from the canonical source unit.
+// A workgroup stages the source runs that hold the elements of one destination block in LDS and
+// then assembles the block's destination vectors from them; several destination elements may read
+// the same LDS word.  Offsets in elements relative to the group start; LDS offsets in bytes.
+struct PullArgs {
+    const void *src;
+    void *dst;
+    long long ntiles;
+    long long nblocks;
+    int d_src, d_dst;           // index bits of one source / destination tile
+    int group_bits, coset_bits;
+    int src_vec_bits;           // log2 of the 16-byte vectors staged per block
+    int dst_iters;              // destination vectors per thread
+    uint32_t coset_src[kMaxCosetBits], coset_dst[kMaxCosetBits], coset_lds_rd[kMaxCosetBits];
+    uint32_t lane_src[8], lane_dst[8];
+    uint32_t iter_src[kMaxIter];
+    uint32_t iter_dst_bit[8];                       // per bit of the destination iteration index
+    uint32_t lds_wr_lane[8], lds_rd_lane[8];
+    uint32_t lds_wr_iter[kMaxIter], lds_rd_iter_bit[8];
+    uint32_t lds_wr_sub[kMaxSub], lds_rd_sub[kMaxSub];
+};
+
 enum { kTposeNone = 0, kTposeBefore = 1, kTposeAfter = 2 };
 enum { kXchgNone = 0, kXchgShuffle = 1, kXchgLds = 2 };
 
@@ -89,6 +112,7 @@ ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int ld
                           int lds_bytes, void *stream);
 ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose, int xchg, int threads, int lds_bytes,
                      void *stream);
+ll_status launch_pull(const PullArgs &a, int elem_bytes, int src_iters, int lds_bytes, void *stream);
 ll_status launch_gather(const GatherArgs &a, int elem_bytes, void *stream);
 ll_status launch_copy(const void *src, void *dst, long long bytes, void *stream);
 

@@ -485,17 +485,25 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
 {
     if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8)
         return fail(LL_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8 (got %d)", elem_bytes);
-    if (!same_inputs(src, dst)) return fail(LL_ERR_DIM_MISMATCH, "source and destination layouts have different input dims");
     if (src->d_out != dst->d_out)
         return fail(LL_ERR_DIM_MISMATCH, "source and destination map to output spaces of %d and %d bits", src->d_out, dst->d_out);
     for (int i = 0; i < src->n_in; ++i)
         if (src->in_dims[i].label == LL_IN_OFFSET)
             return fail(LL_ERR_INVALID_ARG, "conversion needs distributed layouts (register / lane / wave / tile inputs)");
+    for (int i = 0; i < dst->n_in; ++i)
+        if (dst->in_dims[i].label == LL_IN_OFFSET)
+            return fail(LL_ERR_INVALID_ARG, "conversion needs distributed layouts (register / lane / wave / tile inputs)");
     const int d = src->d_in;
     if (f2::rank(src->bases) < src->d_out || f2::rank(dst->bases) < dst->d_out)
         return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
-    if (d > src->d_out) return fail(LL_ERR_NOT_INJECTIVE, "layouts with broadcasting (more input than output bits) are not supported");
-    if (d < 1) return fail(LL_ERR_INVALID_ARG, "empty layout");
+    if (d < 1 || dst->d_in < 1) return fail(LL_ERR_INVALID_ARG, "empty layout");
+    if (d > src->d_out || dst->d_in > dst->d_out) {
+        // broadcasting (Sec. 5.1, Sec. 5.4 rule 2): destination units pull from canonical source units
+        std::memset(&plan->desc, 0, sizeof(plan->desc));
+        plan->desc.elem_bytes = elem_bytes;
+        return plan_pull(src, dst, elem_bytes, plan);
+    }
+    if (!same_inputs(src, dst)) return fail(LL_ERR_DIM_MISMATCH, "source and destination layouts have different input dims");
 
     // B^-1 o A (Sec. 5.4)
     mat binv;
@@ -512,7 +520,7 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
 
     ll_plan_desc &desc = plan->desc;
     std::memset(&desc, 0, sizeof(desc));
-    desc.d = d;
+    desc.d = desc.d_dst = d;
     desc.elem_bytes = elem_bytes;
     for (int k = 0; k < d; ++k) desc.conv[k] = p[k];
     desc.kind = classify(p, d, src->bits_of(LL_IN_REG), src->first_bit_of(LL_IN_WAVE));

@@ -58,6 +58,8 @@ struct ll_plan {
     ll::LdsElemArgs lds_elem = {};
     ll::VecArgs vec = {};
     int vec_nvec_bits = 0, vec_tpose = 0, vec_xchg = 0;
+    ll::PullArgs pull = {};
+    int pull_src_iters = 0;
 };
 
 namespace ll {
@@ -66,6 +68,8 @@ namespace ll {
 // untouched.
 ll_status plan_wave_shuffle(const f2::mat &p, int d, int w, ll_plan *plan, bool *applied);
 ll_status plan_lds_vec(const f2::mat &p, int d, int w, ll_plan *plan, bool *applied);
+// Broadcasting layouts (plan_pull.cpp): A, B surjective, possibly not injective.
+ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan);
 ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan);
 ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long ntiles, void *stream);
 ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *in, const int32_t *idx,

@@ -37,6 +37,15 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         return launch_vec(a, desc.elem_bytes, plan->vec_nvec_bits, plan->vec_tpose, plan->vec_xchg, desc.threads,
                           desc.lds_bytes, stream);
     }
+    case LL_STRATEGY_LDS_PULL: {
+        PullArgs a = plan->pull;
+        a.src = src;
+        a.dst = dst;
+        a.ntiles = ntiles;
+        const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
+        a.nblocks = groups << a.coset_bits;
+        return launch_pull(a, desc.elem_bytes, plan->pull_src_iters, desc.lds_bytes, stream);
+    }
     default:
         return fail(LL_ERR_UNSUPPORTED, "plan strategy %d has no kernel", desc.strategy);
     }

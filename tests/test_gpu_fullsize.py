@@ -87,3 +87,29 @@ def test_gather_both_kernels_agree(monkeypatch):
         ll.ll_gather(layout, cfg.axis, cfg.elem_bytes, inp, idx, out, nt)
         torch.cuda.synchronize()
         assert np.array_equal(wl.to_numpy_bits(out), want), f"staged={staged}"
+
+
+@pytest.mark.parametrize("case", wl.broadcast_cases(), ids=lambda c: c.name.split(" (")[0].replace(" ", "_"))
+def test_broadcast_convert_full_size_sampled(case):
+    """Conversions between replicating layouts at the sizes bench.py times.  Sampled tiles against
+    the oracle; at full size, every destination slot along a zero column of the destination layout
+    holds the same bits as its partner (replicas of one logical element are equal)."""
+    a = ll.distributed_layout(*case.src_in, case.out_dim_bits, case.src_bases)
+    b = ll.distributed_layout(*case.dst_in, case.out_dim_bits, case.dst_bases)
+    plan = ll.ll_plan_convert(a, b, case.elem_bytes)
+    nt, ds, dd = case.ntiles, case.d_src, case.d_dst
+    src = case.gen_data(0, nt, "cuda")
+    dst = torch.empty(nt << dd, dtype=src.dtype, device="cuda")
+    wl.bits_view(dst).fill_(0x5A5A)
+    ll.ll_convert(plan, src, dst, nt)
+    torch.cuda.synchronize()
+    dbits = wl.bits_view(dst)
+    for k, col in enumerate(case.dst_bases):
+        if col == 0:                                   # replica bit k of the destination index
+            v = dbits.view(-1, 2, 1 << k)
+            assert torch.equal(v[:, 0, :], v[:, 1, :]), f"replicas along destination bit {k} differ"
+    for t in sample_tiles(nt, 8, case.data_seed):
+        s_tile = wl.to_numpy_bits(src[t << ds:(t + 1) << ds])
+        assert np.array_equal(s_tile, wl.to_numpy_bits(case.gen_data(t, 1)))
+        want = oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, s_tile)
+        assert np.array_equal(wl.to_numpy_bits(dst[t << dd:(t + 1) << dd]), want), f"{case.name} tile {t}"

@@ -237,3 +237,76 @@ def test_convert_structured_shuffle_cases():
             src = rng.integers(0, 1 << 32, size=5 << d, dtype=np.uint32)
             assert np.array_equal(run_convert(plan, src, d), oracle.convert(cx, cy, src)), name
     print(used)
+
+
+# ---------------------------------------------------------------------------------------------
+# layouts with broadcasting (Sec. 5.1 "Broadcasting", Sec. 5.4 rule 2)
+# ---------------------------------------------------------------------------------------------
+
+def run_convert_general(plan, src_bits: np.ndarray, d_src: int, d_dst: int) -> np.ndarray:
+    w = src_bits.itemsize
+    ntiles = src_bits.size >> d_src
+    tdt = {1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}[w]
+    src = torch.from_numpy(src_bits.view(tdt)).cuda()
+    dst = torch.full((ntiles << d_dst,), 0x5A if w == 1 else 0x5A5A, dtype=src.dtype, device="cuda")
+    ll.ll_convert(plan, src, dst, ntiles)
+    torch.cuda.synchronize()
+    return dst.cpu().numpy().view(NP_DTYPES[w])
+
+
+def surjective_bases(rng, d_in, d_out):
+    while True:
+        cols = [int(rng.integers(0, 1 << d_out)) for _ in range(d_in)]
+        if d_in > d_out:
+            cols[int(rng.integers(0, d_in))] = 0
+        seen = {0}
+        for c in cols:
+            seen |= {x ^ c for x in seen}
+        if len(seen) == 1 << d_out:
+            return cols
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_convert_paper_zero_column_example(w):
+    """Layout A of Sec. 4.1 and its copy with a zero column after the register bits: expand,
+    collapse and replica-to-replica.  Replicas in the source hold different values, so reading any
+    slot but the one whose replica bit is zero fails."""
+    base = wl.PAPER_LAYOUT_A
+    wide = base[:2] + [0] + base[2:]
+    a = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 5), (ll.LL_IN_WAVE, 1)], [4, 4], base)
+    b = ll.ll_layout_create([(ll.LL_IN_REG, 3), (ll.LL_IN_LANE, 5), (ll.LL_IN_WAVE, 1)], [4, 4], wide)
+    rng = np.random.default_rng(w)
+    for x, y, cx, cy in ((a, b, base, wide), (b, a, wide, base), (b, b, wide, wide)):
+        plan = ll.ll_plan_convert(x, y, w)
+        for ntiles in (1, 7, 150):
+            src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << len(cx), dtype=NP_DTYPES[w])
+            got = run_convert_general(plan, src, len(cx), len(cy))
+            assert np.array_equal(got, oracle.convert_general(cx, cy, 8, src)), (len(cx), len(cy), ntiles)
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+@pytest.mark.parametrize("da,db,dl", [(9, 8, 8), (8, 10, 8), (12, 12, 10), (14, 13, 12), (16, 14, 12),
+                                      (7, 9, 6), (10, 12, 10), (13, 13, 13)])
+def test_convert_random_broadcast_layouts(w, da, db, dl):
+    rng = np.random.default_rng(7000 + 100 * w + da + 3 * db)
+    for trial in range(3):
+        ca, cb = surjective_bases(rng, da, dl), surjective_bases(rng, db, dl)
+        a = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, da - 2)], [dl], ca)
+        b = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, db - 2)], [dl], cb)
+        plan = ll.ll_plan_convert(a, b, w)
+        ntiles = int(rng.integers(1, 40))
+        src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << da, dtype=NP_DTYPES[w])
+        got = run_convert_general(plan, src, da, db)
+        assert np.array_equal(got, oracle.convert_general(ca, cb, dl, src)), (trial, plan.info()["strategy_name"])
+
+
+@pytest.mark.parametrize("case", wl.broadcast_cases(), ids=lambda c: c.name.split(" (")[0].replace(" ", "_"))
+def test_convert_broadcast_workloads_small(case):
+    a = ll.distributed_layout(*case.src_in, case.out_dim_bits, case.src_bases)
+    b = ll.distributed_layout(*case.dst_in, case.out_dim_bits, case.dst_bases)
+    plan = ll.ll_plan_convert(a, b, case.elem_bytes)
+    assert plan.info()["kind_name"] == "broadcast"
+    for ntiles in (1, 5):
+        src = wl.to_numpy_bits(case.gen_data(0, ntiles))
+        got = run_convert_general(plan, src, case.d_src, case.d_dst)
+        assert np.array_equal(got, oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, src))

@@ -194,10 +194,11 @@ def test_plan_errors():
     with pytest.raises(ll.LLError) as e:
         ll.ll_plan_convert(a, ll.distributed_layout(2, 5, 1, [d], singular), 4)
     assert e.value.status == ll.LL_ERR_NOT_SURJECTIVE
-    wide = ll.distributed_layout(3, 5, 1, [d], [1, 2, 0, 4, 8, 16, 32, 64, 128])     # broadcast register bit
+    # a layout with a zero column broadcasts; it still has to cover the logical tensor
+    hole = ll.distributed_layout(3, 5, 1, [d], [1, 2, 0, 4, 8, 16, 32, 64, 64])
     with pytest.raises(ll.LLError) as e:
-        ll.ll_plan_convert(wide, wide, 4)
-    assert e.value.status == ll.LL_ERR_NOT_INJECTIVE
+        ll.ll_plan_convert(a, hole, 4)
+    assert e.value.status == ll.LL_ERR_NOT_SURJECTIVE
     # tile label must pass through
     t_in = [(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 5), (ll.LL_IN_TILE, 1)]
     ta = ll.ll_layout_create(t_in, [d], ident)
@@ -206,6 +207,59 @@ def test_plan_errors():
     with pytest.raises(ll.LLError) as e:
         ll.ll_plan_convert(ta, ll.ll_layout_create(t_in, [d], mixed), 4)
     assert e.value.status == ll.LL_ERR_TILE_MIXED
+
+
+def surjective_bases(rng, d_in, d_out):
+    """Random columns spanning F2^d_out; when d_in > d_out one column is zero (a plain replica bit)."""
+    while True:
+        cols = [int(rng.integers(0, 1 << d_out)) for _ in range(d_in)]
+        if d_in > d_out:
+            cols[int(rng.integers(0, d_in))] = 0
+        seen = {0}
+        for c in cols:
+            seen |= {x ^ c for x in seen}
+        if len(seen) == 1 << d_out:
+            return cols
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_broadcast_plans_pull_from_the_right_inverse(w):
+    """Sec. 5.1 broadcasting / Sec. 5.4 rule 2: the plan's pull map sends every destination index to
+    the source index the oracle's right inverse (free variables zero) names for its logical element."""
+    rng = np.random.default_rng(500 + w)
+    for da, db, dl in [(9, 8, 8), (8, 10, 8), (12, 12, 10), (14, 13, 12), (16, 14, 12), (7, 9, 6), (10, 12, 10)]:
+        ca, cb = surjective_bases(rng, da, dl), surjective_bases(rng, db, dl)
+        a = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, da - 2)], [dl], ca)
+        b = ll.ll_layout_create([(ll.LL_IN_REG, 3), (ll.LL_IN_LANE, db - 3)], [dl], cb)
+        info = ll.ll_plan_convert(a, b, w).info()
+        assert info["kind_name"] == "broadcast" and info["strategy_name"] == "lds_pull"
+        assert info["d"] == da and info["d_dst"] == db
+        rinv = oracle.right_inverse_table(ca, dl)
+        hb = np.arange(1 << db, dtype=np.uint64)
+        pulled = np.zeros(1 << db, dtype=np.uint64)
+        logical = np.zeros(1 << db, dtype=np.uint64)
+        for k in range(db):
+            bit = ((hb >> np.uint64(k)) & np.uint64(1)).astype(bool)
+            pulled[bit] ^= np.uint64(info["pull"][k])
+            logical[bit] ^= np.uint64(cb[k])
+        assert np.array_equal(pulled, rinv[logical].astype(np.uint64))
+        assert info["predicted_wavefronts_write"] == 1 and info["lds_bytes"] <= 64 * 1024
+
+
+def test_broadcast_plan_of_the_paper_zero_column_example():
+    """Layout A of Sec. 4.1 with a zero column spliced in after its two register bits
+    (Sec. 5.1 "Broadcasting"): 512 hardware slots hold 256 logical elements."""
+    base = wl.PAPER_LAYOUT_A
+    wide = base[:2] + [0] + base[2:]
+    a = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 5), (ll.LL_IN_WAVE, 1)], [4, 4], base)
+    b = ll.ll_layout_create([(ll.LL_IN_REG, 3), (ll.LL_IN_LANE, 5), (ll.LL_IN_WAVE, 1)], [4, 4], wide)
+    for x, y, dx, dy in ((a, b, 8, 9), (b, a, 9, 8), (b, b, 9, 9)):
+        info = ll.ll_plan_convert(x, y, 4).info()
+        assert (info["kind_name"], info["d"], info["d_dst"]) == ("broadcast", dx, dy)
+    # expanding A into its widened copy: the replica bit (destination bit 2) pulls from nowhere new
+    info = ll.ll_plan_convert(a, b, 2).info()
+    assert info["pull"][2] == 0
+    assert info["pull"][:2] == [1, 2] and info["pull"][3:9] == [4, 8, 16, 32, 64, 128]
 
 
 def test_device_entry_points_reject_bad_arguments_before_launch():

@@ -262,3 +262,77 @@ def config(cid: int) -> Config:
 # reg0, reg1, thr0..thr4, warp0 -> j0, i0, j1, j2, j3, i1, i2, i3 with
 # flat = j | i << 4.
 PAPER_LAYOUT_A = [1 << 0, 1 << 4, 1 << 1, 1 << 2, 1 << 3, 1 << 5, 1 << 6, 1 << 7]
+
+
+# ---------------------------------------------------------------------------
+# Layouts with broadcasting (paper Sec. 5.1 "Broadcasting"): zero columns mean that several
+# hardware slots hold the same logical element, as the result of a reduction along lanes does.
+# ---------------------------------------------------------------------------
+
+@dataclass
+class BroadcastCase:
+    """Conversion between layouts of one logical tensor that replicate it differently."""
+    name: str
+    out_dim_bits: List[int]
+    src_in: List[int]               # [register bits, lane bits, wave bits]
+    dst_in: List[int]
+    src_bases: List[int]
+    dst_bases: List[int]
+    dtype: torch.dtype
+    ntiles: int
+    data_seed: int
+
+    @property
+    def d_out(self) -> int:
+        return sum(self.out_dim_bits)
+
+    @property
+    def d_src(self) -> int:
+        return sum(self.src_in)
+
+    @property
+    def d_dst(self) -> int:
+        return sum(self.dst_in)
+
+    @property
+    def elem_bytes(self) -> int:
+        return torch.empty((), dtype=self.dtype).element_size()
+
+    def algorithmic_bytes(self, ntiles: Optional[int] = None) -> int:
+        """One copy of every logical element read, every destination slot written."""
+        n = self.ntiles if ntiles is None else ntiles
+        return n * ((1 << self.d_out) + (1 << self.d_dst)) * self.elem_bytes
+
+    def gen_data(self, tile_start: int, ntiles: int, device="cpu") -> torch.Tensor:
+        """Source image.  Replicas of one logical element are NOT made equal: which replica a
+        conversion reads is part of its definition, and unequal replicas expose a wrong choice."""
+        start, count = tile_start << self.d_src, ntiles << self.d_src
+        if self.dtype == torch.int32:
+            return gen_int32(self.data_seed, start, count, device)
+        return gen_uniform_pm1(self.data_seed, start, count, self.dtype, device)
+
+
+def _bits(spec: Sequence[Optional[int]]) -> List[int]:
+    return [0 if s is None else 1 << s for s in spec]
+
+
+def broadcast_cases() -> List[BroadcastCase]:
+    Z = None
+    # a 1024-vector left by a row reduction: 16 lanes of every wave hold the same values
+    sliced = _bits([0, 1, 6, 7] + [Z, Z, Z, Z, 2, 3] + [4, 5, 8, 9])
+    blocked = _bits([0, 1] + [2, 3, 4, 5, 6, 7] + [8, 9])
+    # a 64 x 64 tile whose rows are replicated over 4 lanes and 2 waves, against a plain blocked one
+    rep2d = _bits([0, 1, 10, 11] + [2, 3, Z, Z, 4, 5] + [6, 7, Z, 8, 9])
+    blk2d = _bits([0, 1, 2, 3] + [4, 5, 6, 7, 8, 9] + [10, 11])
+    return [
+        BroadcastCase("reduction result -> blocked vector (collapse 16x)", [10], [4, 6, 4], [2, 6, 2],
+                      sliced, blocked, torch.float32, 1 << 16, 61),
+        BroadcastCase("blocked vector -> replicated over 16 lanes (expand 16x)", [10], [2, 6, 2], [4, 6, 4],
+                      blocked, sliced, torch.float32, 1 << 16, 62),
+        BroadcastCase("64x64 replicated 8x -> blocked bf16", [6, 6], [4, 6, 5], [4, 6, 2],
+                      rep2d, blk2d, torch.bfloat16, 1 << 14, 63),
+        BroadcastCase("64x64 blocked -> replicated 8x bf16", [6, 6], [4, 6, 2], [4, 6, 5],
+                      blk2d, rep2d, torch.bfloat16, 1 << 14, 64),
+        BroadcastCase("replicated 16x -> differently replicated 8x int32", [10], [4, 6, 4], [3, 6, 4],
+                      sliced, _bits([0, 1, 2] + [3, Z, 4, Z, 5, 6] + [7, 8, Z, 9]), torch.int32, 1 << 15, 65),
+    ]
