@@ -43,7 +43,7 @@ typedef enum {
     LL_ERR_INVALID_ARG = 1,      /* null pointer, size out of range, bad label order, misaligned buffer */
     LL_ERR_DIM_MISMATCH = 2,     /* input/output spaces of the operands do not match */
     LL_ERR_NOT_SURJECTIVE = 3,   /* a right inverse was requested of a non-surjective layout */
-    LL_ERR_NOT_INJECTIVE = 4,    /* the hot path needs bijective layouts (no broadcasting yet) */
+    LL_ERR_NOT_INJECTIVE = 4,    /* the operation needs an injective layout (gather; inversion) */
     LL_ERR_TILE_MIXED = 5,       /* the conversion would move data between tiles */
     LL_ERR_AXIS_NOT_IN_WAVE = 6, /* gather axis is not contained in one wave (Sec. 5.5) */
     LL_ERR_UNSUPPORTED = 7,      /* valid request outside what is implemented */

@@ -470,13 +470,15 @@ ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose,
 // conversion with broadcasting: destination units pull from the canonical source unit
 // ---------------------------------------------------------------------------------------------
 
-// W: element bytes, NVS: source vectors staged per thread.  256 threads.  Element-wide LDS accesses.
-template <int W, int NVS>
+// W: element bytes, NVS: source vectors staged per thread, V: log2 elements per LDS access.
+// 256 threads.
+template <int W, int NVS, int V>
 __global__ __launch_bounds__(256) void k_pull(const PullArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
-    constexpr int NSUB = 1 << VS;
+    constexpr int NSUB = 1 << (VS - V);
+    constexpr int AB = W << V;
     const uint32_t tid = threadIdx.x;
     uint32_t ls = 0, ld = 0, lw = 0, lr = 0;
 #pragma unroll
@@ -518,7 +520,7 @@ __global__ __launch_bounds__(256) void k_pull(const PullArgs a)
         if (tid + 256u * i < nsrc) {
             const uint32_t base = lw ^ a.lds_wr_iter[i];
 #pragma unroll
-            for (int s = 0; s < NSUB; ++s) lds_put<W>(lds, base ^ a.lds_wr_sub[s], r[i], s);
+            for (int s = 0; s < NSUB; ++s) lds_put<AB>(lds, base ^ a.lds_wr_sub[s], r[i], s);
         }
     }
     __syncthreads();
@@ -532,36 +534,60 @@ __global__ __launch_bounds__(256) void k_pull(const PullArgs a)
         const uint32_t base = cr ^ lr ^ ib;
         uint32_t o[4];
 #pragma unroll
-        for (int s = 0; s < NSUB; ++s) lds_get<W>(lds, base ^ a.lds_rd_sub[s], o, s);
+        for (int s = 0; s < NSUB; ++s) lds_get<AB>(lds, base ^ a.lds_rd_sub[s], o, s);
         const u32x4 v = {o[0], o[1], o[2], o[3]};
         buf_store16(drsrc, (cd ^ ld ^ ob) * W, v);
     }
 }
 
-template <int W>
-static ll_status launch_pull_w(const PullArgs &a, int src_iters, int lds_bytes, hipStream_t stream)
+template <int W, int V>
+static ll_status launch_pull_wv(const PullArgs &a, int src_iters, int lds_bytes, hipStream_t stream)
 {
     const dim3 grid((unsigned)a.nblocks), block(256);
+    // Occupancy cap through the LDS allocation (see launch_vec_t): bytes a workgroup stores.
+    static const unsigned budget = getenv("LL_PULL_INFLIGHT_BYTES") ? (unsigned)atol(getenv("LL_PULL_INFLIGHT_BYTES")) : 0u;
+    if (budget) {
+        const unsigned wg_bytes = 256u * 16u * (unsigned)a.dst_iters;
+        const unsigned per_cu = budget / wg_bytes > 1 ? budget / wg_bytes : 1;
+        unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
+        if (alloc > 64u * 1024u) alloc = 64u * 1024u;
+        if (alloc > (unsigned)lds_bytes) lds_bytes = (int)alloc;
+    }
     switch (src_iters) {
-    case 1: hipLaunchKernelGGL((k_pull<W, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 2: hipLaunchKernelGGL((k_pull<W, 2>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 4: hipLaunchKernelGGL((k_pull<W, 4>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 8: hipLaunchKernelGGL((k_pull<W, 8>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 1: hipLaunchKernelGGL((k_pull<W, 1, V>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 2: hipLaunchKernelGGL((k_pull<W, 2, V>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 4: hipLaunchKernelGGL((k_pull<W, 4, V>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 8: hipLaunchKernelGGL((k_pull<W, 8, V>), grid, block, (size_t)lds_bytes, stream, a); break;
     default: return fail(LL_ERR_UNSUPPORTED, "no broadcast kernel for %d source vectors per thread", src_iters);
     }
     return check_launch("broadcast conversion kernel launch");
 }
 
-ll_status launch_pull(const PullArgs &a, int elem_bytes, int src_iters, int lds_bytes, void *stream)
+template <int W>
+static ll_status launch_pull_w(const PullArgs &a, int src_iters, int vec_bits, int lds_bytes, hipStream_t stream)
+{
+    constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
+    switch (vec_bits) {
+    case 0: return launch_pull_wv<W, 0>(a, src_iters, lds_bytes, stream);
+    case 1: return launch_pull_wv<W, 1>(a, src_iters, lds_bytes, stream);
+    case 2: if constexpr (VS >= 2) return launch_pull_wv<W, 2>(a, src_iters, lds_bytes, stream); break;
+    case 3: if constexpr (VS >= 3) return launch_pull_wv<W, 3>(a, src_iters, lds_bytes, stream); break;
+    case 4: if constexpr (VS >= 4) return launch_pull_wv<W, 4>(a, src_iters, lds_bytes, stream); break;
+    default: break;
+    }
+    return fail(LL_ERR_INVALID_ARG, "LDS accesses of 2^%d elements of %d bytes exceed 16 bytes", vec_bits, W);
+}
+
+ll_status launch_pull(const PullArgs &a, int elem_bytes, int src_iters, int vec_bits, int lds_bytes, void *stream)
 {
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     if (lds_bytes <= 0 || lds_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "LDS block of %d bytes", lds_bytes);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {
-    case 1: return launch_pull_w<1>(a, src_iters, lds_bytes, s);
-    case 2: return launch_pull_w<2>(a, src_iters, lds_bytes, s);
-    case 4: return launch_pull_w<4>(a, src_iters, lds_bytes, s);
-    case 8: return launch_pull_w<8>(a, src_iters, lds_bytes, s);
+    case 1: return launch_pull_w<1>(a, src_iters, vec_bits, lds_bytes, s);
+    case 2: return launch_pull_w<2>(a, src_iters, vec_bits, lds_bytes, s);
+    case 4: return launch_pull_w<4>(a, src_iters, vec_bits, lds_bytes, s);
+    case 8: return launch_pull_w<8>(a, src_iters, vec_bits, lds_bytes, s);
     default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
     }
 }

@@ -32,10 +32,10 @@ static vec xor_sel(const mat &cols, int first, unsigned idx)
 }
 
 // Host-side walk of one block, as the kernel indexes it.
-static ll_status check_pull_block(const PullArgs &a, const mat &rext, int vs, int w, int src_iters, int lds_bytes,
+static ll_status check_pull_block(const PullArgs &a, const mat &rext, int vs, int v, int w, int src_iters, int lds_bytes,
                                   uint32_t cs, uint32_t cd, uint32_t cr)
 {
-    const int E = 1 << vs;
+    const int E = 1 << vs, A = 1 << v;                // elements per global vector / per LDS access
     const uint64_t src_group = 1ull << (a.d_src + a.group_bits), dst_group = 1ull << (a.d_dst + a.group_bits);
     std::vector<int64_t> held((size_t)lds_bytes / w, -1);
     auto lane_part = [&](const uint32_t *tab, int tid) {
@@ -50,8 +50,10 @@ static ll_status check_pull_block(const PullArgs &a, const mat &rext, int vs, in
             const uint32_t off = cs ^ lane_part(a.lane_src, tid) ^ a.iter_src[i];
             if (off >= src_group || (off & (uint32_t)(E - 1))) return fail(LL_ERR_INVALID_ARG, "internal: bad source offset in broadcast plan");
             for (int s = 0; s < E; ++s) {
-                const uint32_t addr = lane_part(a.lds_wr_lane, tid) ^ a.lds_wr_iter[i] ^ a.lds_wr_sub[s];
-                if (addr >= (uint32_t)lds_bytes || addr % (uint32_t)w) return fail(LL_ERR_INVALID_ARG, "internal: bad LDS write address in broadcast plan");
+                const uint32_t base = lane_part(a.lds_wr_lane, tid) ^ a.lds_wr_iter[i] ^ a.lds_wr_sub[s / A];
+                if (base % (uint32_t)(w * A)) return fail(LL_ERR_INVALID_ARG, "internal: misaligned LDS write in broadcast plan");
+                const uint32_t addr = base + (uint32_t)((s % A) * w);
+                if (addr >= (uint32_t)lds_bytes) return fail(LL_ERR_INVALID_ARG, "internal: bad LDS write address in broadcast plan");
                 if (held[addr / w] >= 0) return fail(LL_ERR_INVALID_ARG, "internal: LDS writes overlap in broadcast plan");
                 held[addr / w] = (int64_t)off + s;
             }
@@ -64,8 +66,10 @@ static ll_status check_pull_block(const PullArgs &a, const mat &rext, int vs, in
             const uint32_t off = cd ^ lane_part(a.lane_dst, tid) ^ ob;
             if (off >= dst_group || (off & (uint32_t)(E - 1))) return fail(LL_ERR_INVALID_ARG, "internal: bad destination offset in broadcast plan");
             for (int s = 0; s < E; ++s) {
-                const uint32_t addr = cr ^ lane_part(a.lds_rd_lane, tid) ^ ib ^ a.lds_rd_sub[s];
-                if (addr >= (uint32_t)lds_bytes || addr % (uint32_t)w || held[addr / w] < 0)
+                const uint32_t base = cr ^ lane_part(a.lds_rd_lane, tid) ^ ib ^ a.lds_rd_sub[s / A];
+                if (base % (uint32_t)(w * A)) return fail(LL_ERR_INVALID_ARG, "internal: misaligned LDS read in broadcast plan");
+                const uint32_t addr = base + (uint32_t)((s % A) * w);
+                if (addr >= (uint32_t)lds_bytes || held[addr / w] < 0)
                     return fail(LL_ERR_INVALID_ARG, "internal: bad LDS read address in broadcast plan");
                 if ((vec)held[addr / w] != f2::apply(rext, (vec)off + s))
                     return fail(LL_ERR_INVALID_ARG, "internal: broadcast plan does not realise the conversion");
@@ -86,7 +90,12 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     vec pivots = 0;
     for (vec c : aplus) pivots |= c;
 
-    const unsigned max_block = env_bytes("LL_BLOCK_BYTES", 8192u);
+    // A destination that replicates 4x or more makes the conversion write-dominated: destination
+    // runs first, and 16 KiB blocks (four stores in flight per thread measured fastest on MI355X;
+    // read-dominated and balanced conversions do best at 8 KiB).
+    int mode = dB > dl + 1 ? 1 : 0;
+    if (const char *e = getenv("LL_PULL_MODE")) mode = atoi(e);
+    const unsigned max_block = env_bytes("LL_BLOCK_BYTES", mode == 1 ? 16384u : 8192u);
     const int n_max = std::max(vs + tb, ilog2p(max_block / (unsigned)w));
     const int g = std::max(0, n_max - std::min(dA, dB));        // bundle small tiles
     const int Ds = dA + g, Dd = dB + g;
@@ -109,19 +118,36 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
         *out = tag;
         return true;
     };
-    auto block_space = [&](int k) {
+    // Block = destination runs of 2^kd slots plus the destination slots that pull from source runs
+    // of 2^ks slots (pivot bits only).  Longer runs on a side mean longer contiguous pieces of HBM on
+    // that side; the side that moves more bytes gets its run bits first.
+    auto block_space = [&](int ks, int kd) {
         mat gens;
-        for (int j = 0; j < k; ++j) gens.push_back(vec(1) << j);
-        for (int j = 0; j < k && j < Ds; ++j) {
+        for (int j = 0; j < kd; ++j) gens.push_back(vec(1) << j);
+        for (int j = 0; j < ks && j < Ds; ++j) {
             vec pre;
             if (((pivots >> j) & 1) && preimage(vec(1) << j, &pre)) gens.push_back(pre);
         }
         return f2::extend({}, gens);
     };
-    int k = vs;
     if (vs > Ds || vs > Dd) return fail(LL_ERR_UNSUPPORTED, "tile smaller than one 16-byte vector");
-    while (k < Dd && (int)block_space(k + 1).size() <= n_max) ++k;
-    mat Ud = block_space(k);
+    int ks = vs, kd = vs;
+    auto fits = [&](int s_, int d_) { return (int)block_space(s_, d_).size() <= n_max; };
+    if (mode == 1) {
+        while (kd < Dd && fits(ks, kd + 1)) ++kd;
+        while (ks < Ds && fits(ks + 1, kd)) ++ks;
+    } else if (mode == 2) {
+        while (ks < Ds && fits(ks + 1, kd)) ++ks;
+        while (kd < Dd && fits(ks, kd + 1)) ++kd;
+    } else {
+        for (bool grew = true; grew;) {
+            grew = false;
+            if (kd < Dd && fits(ks, kd + 1)) { ++kd; grew = true; }
+            if (ks < Ds && fits(ks + 1, kd)) { ++ks; grew = true; }
+        }
+    }
+    const int k = kd;
+    mat Ud = block_space(ks, kd);
     // destination broadcast directions: keep replicas of one element in one block while it fits
     for (vec kv : kernel_r)
         if ((int)Ud.size() < n_max) Ud = f2::extend({}, cat(Ud, {kv}));
@@ -146,7 +172,7 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     for (int j = 0; j < vs; ++j) us.push_back(vec(1) << j);
     {
         mat cand;
-        for (int j = vs; j < k && j < Ds; ++j)
+        for (int j = vs; j < ks && j < Ds; ++j)
             if ((pivots >> j) & 1) cand.push_back(vec(1) << j);
         for (vec x : ud) cand.push_back(f2::apply(rext, x) & ~src_low);
         for (vec x : f2::extend(us, cand)) us.push_back(x);
@@ -168,14 +194,23 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     const int src_iters = std::max(1, 1 << std::max(0, src_vec_bits - tb));
     if (src_iters > 8) return fail(LL_ERR_UNSUPPORTED, "internal: source block too large");
 
-    // LDS layout over the source-local space, element-wide accesses
+    // LDS access width: 2^v elements where the conversion keeps the low v bits of a slot index in
+    // place (Sec. 5.3 "Generalized Vectorization"), element-wide otherwise
+    int v = vs;
+    if (const char *e = getenv("LL_PULL_VEC")) v = std::min(vs, std::max(0, atoi(e)));
+    for (int j = 0; j < nd; ++j)
+        while (v > 0 && (j < v ? rl[j] != (vec(1) << j) : (rl[j] & ((vec(1) << v) - 1)) != 0)) --v;
+    for (vec c : comp)
+        while (v > 0 && (f2::apply(rext, c) & ((vec(1) << v) - 1)) != 0) --v;
+    for (int j = 0; j < v; ++j)
+        if (rl[j] != (vec(1) << j)) return fail(LL_ERR_INVALID_ARG, "internal: vector bits of a broadcast plan");
     mat wr_lanes, rd_lanes;
     for (int b = 0; b < 6; ++b) {
         wr_lanes.push_back(vs + b < ns ? vec(1) << (vs + b) : 0);
         rd_lanes.push_back(rl[vs + b]);
     }
     int wfw = 1, wfr = 1;
-    const mat m = synthesize_swizzle(ns, 0, w, wr_lanes, rd_lanes, hw, &wfw, &wfr);
+    const mat m = synthesize_swizzle(ns, v, w, wr_lanes, rd_lanes, hw, &wfw, &wfr);
     mat sw;
     if (!f2::invert(m, ns, &sw)) return fail(LL_ERR_INVALID_ARG, "internal: swizzle not invertible");
     const mat swr = f2::compose(sw, rl);            // destination-local index -> LDS element offset
@@ -205,20 +240,21 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
         a.iter_dst_bit[b] = (uint32_t)ud[vs + tb + b];
         a.lds_rd_iter_bit[b] = (uint32_t)(swr[vs + tb + b] * (vec)w);
     }
-    for (int s = 0; s < (1 << vs); ++s) {
-        a.lds_wr_sub[s] = (uint32_t)(xor_sel(sw, 0, (unsigned)s) * (vec)w);
-        a.lds_rd_sub[s] = (uint32_t)(xor_sel(swr, 0, (unsigned)s) * (vec)w);
+    for (int s = 0; s < (1 << (vs - v)); ++s) {      // one entry per LDS access of 2^v elements
+        a.lds_wr_sub[s] = (uint32_t)(xor_sel(sw, v, (unsigned)s) * (vec)w);
+        a.lds_rd_sub[s] = (uint32_t)(xor_sel(swr, v, (unsigned)s) * (vec)w);
     }
     const int lds_bytes = (1 << ns) * w;
     plan->pull_src_iters = src_iters;
+    plan->pull_vec_bits = v;
     {
-        ll_status st = check_pull_block(a, rext, vs, w, src_iters, lds_bytes, 0, 0, 0);
+        ll_status st = check_pull_block(a, rext, vs, v, w, src_iters, lds_bytes, 0, 0, 0);
         uint32_t cs = 0, cd = 0, cr = 0;
         for (int c = 0; c < a.coset_bits && st == LL_OK; ++c) {
-            st = check_pull_block(a, rext, vs, w, src_iters, lds_bytes, a.coset_src[c], a.coset_dst[c], a.coset_lds_rd[c]);
+            st = check_pull_block(a, rext, vs, v, w, src_iters, lds_bytes, a.coset_src[c], a.coset_dst[c], a.coset_lds_rd[c]);
             cs ^= a.coset_src[c]; cd ^= a.coset_dst[c]; cr ^= a.coset_lds_rd[c];
         }
-        if (st == LL_OK && a.coset_bits > 1) st = check_pull_block(a, rext, vs, w, src_iters, lds_bytes, cs, cd, cr);
+        if (st == LL_OK && a.coset_bits > 1) st = check_pull_block(a, rext, vs, v, w, src_iters, lds_bytes, cs, cd, cr);
         if (st != LL_OK) return st;
     }
 
@@ -229,13 +265,13 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     desc.d_dst = dB;
     for (int j = 0; j < dB; ++j) desc.pull[j] = r[j];
     desc.global_vec_bytes = 16;
-    desc.lds_write_bytes = desc.lds_read_bytes = w;
+    desc.lds_write_bytes = desc.lds_read_bytes = w << v;
     desc.lds_bytes = lds_bytes;
     desc.threads = 256;
     desc.vectors_per_thread = a.dst_iters;
     desc.block_bits = nd; desc.group_bits = g; desc.segment_bits = k;
-    desc.lds_vec_bits = 0;
-    const int cls = lds_width_class(w);
+    desc.lds_vec_bits = v;
+    const int cls = lds_width_class(w << v);
     desc.lds_banks = hw.rd_banks[cls]; desc.lds_banks_write = hw.wr_banks[cls];
     desc.lds_phase_lanes_write = 1 << hw.wr_phase_dim[cls];
     desc.lds_phase_lanes_read = 1 << hw.rd_phase_dim[cls];
