@@ -202,3 +202,6 @@ def wavefronts(mem_bases: Sequence[int], dist_bases: Sequence[int], nreg: int, n
     if rc != OK:
         raise OracleError(rc, "wavefronts")
     return mx.value, tot.value, nph.value
+
+
+from .algebra import OLayout, contiguity, divide_left, divide_left_permuting, identity_tile, product  # noqa: E402
