@@ -47,7 +47,8 @@ typedef enum {
     LL_ERR_TILE_MIXED = 5,       /* the conversion would move data between tiles */
     LL_ERR_AXIS_NOT_IN_WAVE = 6, /* gather axis is not contained in one wave (Sec. 5.5) */
     LL_ERR_UNSUPPORTED = 7,      /* valid request outside what is implemented */
-    LL_ERR_DEVICE = 8            /* a HIP call failed; see ll_last_error() */
+    LL_ERR_DEVICE = 8,           /* a HIP call failed; see ll_last_error() */
+    LL_ERR_NOT_DIVISIBLE = 9     /* the layout does not have the tile as a left factor (Def. "Left Division") */
 } ll_status;
 
 typedef enum { LL_IN_REG = 0, LL_IN_LANE = 1, LL_IN_WAVE = 2, LL_IN_TILE = 3, LL_IN_OFFSET = 4 } ll_in_label;
@@ -90,6 +91,34 @@ ll_status ll_compose(const ll_layout *outer, const ll_layout *inner, ll_layout *
  * Input dims are merged label-wise (bits of `a` below bits of `b` inside one label); the output
  * dims of `b` are placed above (slower than) those of `a` in the flattened index. */
 ll_status ll_product(const ll_layout *a, const ll_layout *b, ll_layout **out);
+
+/* Product taken label-wise on BOTH sides (Def. "Product" as used for tiling, Sec. 5.1
+ * "Broadcasting"): a and b must have the same number of logical dims; inside every input label
+ * and inside every logical dim the bits of `a` sit below the bits of `b`.  Layout A of Sec. 4.1 is
+ * (2x2 registers) x (4x8 threads) x (2x1 warps) in this sense.  LL_ERR_DIM_MISMATCH if the numbers
+ * of logical dims differ. */
+ll_status ll_product_dimwise(const ll_layout *a, const ll_layout *b, ll_layout **out);
+
+/* Left division (Def. "Left Division"; Sec. 5.3: an instruction with tile T can lower a layout L
+ * if L / T exists).  Succeeds when layout = ll_product_dimwise(tile, Q) for some Q, which is
+ * returned: the tile must own the low input bits of each of its labels and the low bits of every
+ * logical dim, those inputs must map exactly as the tile does, and no other input may reach the
+ * tile's bits.  Q keeps the layout's input labels (possibly with zero bits).
+ * LL_ERR_NOT_DIVISIBLE otherwise (ll_last_error() names the first column that breaks the
+ * structure); LL_ERR_DIM_MISMATCH if the numbers of logical dims differ. */
+ll_status ll_divide_left(const ll_layout *layout, const ll_layout *tile, ll_layout **out);
+
+/* Generalized vectorization (Sec. 5.3): like ll_divide_left, but the input bits of `label` may be
+ * permuted first.  The tile's columns of that label are processed in order; each takes the first
+ * unused input bit that maps as it does.  perm (room for the layout's bits of `label`) receives
+ * the order: new bit k = old bit perm[k].  LL_ERR_NOT_DIVISIBLE if no permutation works. */
+ll_status ll_divide_left_permuted(const ll_layout *layout, const ll_layout *tile, int label, int32_t *perm,
+                                  ll_layout **out);
+
+/* Contiguous elements per thread (Sec. 5.1 "Contiguous elements"): the largest 2^u such that the
+ * inverse of the layout maps logical elements 0..2^u-1 by the identity onto registers 0..2^u-1,
+ * i.e. the widest vector one thread can load or store.  1 if the layout has no register bits. */
+ll_status ll_contiguity(const ll_layout *layout, int32_t *elems);
 
 /* Right inverse (Def. "Right Inverse") by Gaussian elimination over F2.  L must be surjective,
  * else LL_ERR_NOT_SURJECTIVE.  If L is not injective the free variables are set to zero, with

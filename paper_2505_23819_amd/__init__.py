@@ -16,7 +16,7 @@ from . import build as _build
 
 # ---- status codes and enums of ll.h ------------------------------------------------------------
 LL_OK, LL_ERR_INVALID_ARG, LL_ERR_DIM_MISMATCH, LL_ERR_NOT_SURJECTIVE, LL_ERR_NOT_INJECTIVE, \
-    LL_ERR_TILE_MIXED, LL_ERR_AXIS_NOT_IN_WAVE, LL_ERR_UNSUPPORTED, LL_ERR_DEVICE = range(9)
+    LL_ERR_TILE_MIXED, LL_ERR_AXIS_NOT_IN_WAVE, LL_ERR_UNSUPPORTED, LL_ERR_DEVICE, LL_ERR_NOT_DIVISIBLE = range(10)
 LL_IN_REG, LL_IN_LANE, LL_IN_WAVE, LL_IN_TILE, LL_IN_OFFSET = range(5)
 LL_KIND_NOOP, LL_KIND_REG_ONLY, LL_KIND_INTRA_WAVE, LL_KIND_LDS, LL_KIND_BROADCAST = range(5)
 LL_STRATEGY_COPY, LL_STRATEGY_REG_PERMUTE, LL_STRATEGY_WAVE_SHUFFLE, LL_STRATEGY_LDS_ELEM, \
@@ -29,7 +29,8 @@ STRATEGY_NAMES = ["copy", "reg_permute", "wave_shuffle", "lds_elem", "lds_vec", 
 EXPORTED_SYMBOLS = [
     "ll_layout_create", "ll_layout_destroy", "ll_layout_get", "ll_layout_apply", "ll_compose",
     "ll_product", "ll_invert", "ll_plan_convert", "ll_plan_info", "ll_plan_destroy", "ll_convert",
-    "ll_gather", "ll_copy", "ll_last_error",
+    "ll_gather", "ll_copy", "ll_last_error", "ll_product_dimwise", "ll_divide_left",
+    "ll_divide_left_permuted", "ll_contiguity",
 ]
 
 
@@ -199,6 +200,29 @@ def ll_compose(outer: Layout, inner: Layout) -> Layout:
 
 def ll_product(a: Layout, b: Layout) -> Layout:
     return _binary(_lib.ll_product, a, b)
+
+
+def ll_product_dimwise(a: Layout, b: Layout) -> Layout:
+    return _binary(_lib.ll_product_dimwise, a, b)
+
+
+def ll_divide_left(layout: Layout, tile: Layout) -> Layout:
+    return _binary(_lib.ll_divide_left, layout, tile)
+
+
+def ll_divide_left_permuted(layout: Layout, tile: Layout, label: int):
+    """Returns (perm, quotient): new input bit k of `label` = old bit perm[k]."""
+    n = dict(layout.in_dims).get(label, 0)
+    perm = (ctypes.c_int32 * max(n, 1))()
+    h = ctypes.c_void_p()
+    _check(_lib.ll_divide_left_permuted(layout._h, tile._h, int(label), perm, ctypes.byref(h)))
+    return list(perm)[:n], Layout(h.value)
+
+
+def ll_contiguity(layout: Layout) -> int:
+    out = ctypes.c_int32()
+    _check(_lib.ll_contiguity(layout._h, ctypes.byref(out)))
+    return out.value
 
 
 def ll_invert(layout: Layout) -> Layout:

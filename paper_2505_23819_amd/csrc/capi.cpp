@@ -22,8 +22,8 @@ ll_status fail(ll_status code, const char *fmt, ...)
 
 const char *last_error() { return g_error; }
 
-static ll_status make_layout(const ll_in_dim *in_dims, int n_in, const ll_out_dim *out_dims, int n_out,
-                             const f2::mat &bases, ll_layout **out)
+ll_status make_layout(const ll_in_dim *in_dims, int n_in, const ll_out_dim *out_dims, int n_out,
+                      const f2::mat &bases, ll_layout **out)
 {
     ll_layout *l = new (std::nothrow) ll_layout();
     if (!l) return fail(LL_ERR_INVALID_ARG, "out of host memory");

@@ -40,4 +40,8 @@ namespace ll {
 ll_status fail(ll_status code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 const char *last_error();
 
+// new layout object from dims and columns (no validation beyond allocation)
+ll_status make_layout(const ll_in_dim *in_dims, int n_in, const ll_out_dim *out_dims, int n_out,
+                      const f2::mat &bases, ll_layout **out);
+
 }  // namespace ll

@@ -122,3 +122,119 @@ def test_layout_create_argument_errors():
             ll.ll_layout_create(kw["in_dims"], kw["out_dims"], kw["bases"])
         assert e.value.status == ll.LL_ERR_INVALID_ARG
         assert ll.ll_last_error()
+
+
+# ---- label-wise product, left division, contiguity (Defs. "Product", "Left Division"; Sec. 5.1, 5.3)
+
+def _random_layout(rng, in_dims, out_dims):
+    d_out = sum(out_dims)
+    bases = [int(rng.integers(0, 1 << d_out)) if d_out else 0 for _ in range(sum(n for _, n in in_dims))]
+    return [d for d in in_dims], list(out_dims), bases
+
+
+def _mk(in_dims, out_dims, bases):
+    return ll.ll_layout_create(in_dims, out_dims, bases)
+
+
+def test_dimwise_product_and_left_division_match_the_oracle():
+    rng = np.random.default_rng(11)
+    done = 0
+    while done < 40:
+        t_in = [(ll.LL_IN_REG, int(rng.integers(0, 3))), (ll.LL_IN_LANE, int(rng.integers(0, 3)))]
+        m_in = [(ll.LL_IN_REG, int(rng.integers(0, 3))), (ll.LL_IN_LANE, int(rng.integers(1, 3))),
+                (ll.LL_IN_WAVE, int(rng.integers(0, 2)))]
+        t_out = [int(rng.integers(0, 3)), int(rng.integers(0, 3))]
+        m_out = [int(rng.integers(0, 3)), int(rng.integers(0, 3))]
+        t_in = [d for d in t_in if d[1]]
+        m_in = [d for d in m_in if d[1]]
+        if not t_in or sum(t_out) == 0 or sum(m_out) == 0:
+            continue
+        done += 1
+        ti, to, tb = _random_layout(rng, t_in, t_out)
+        mi, mo, mb = _random_layout(rng, m_in, m_out)
+        want = oracle.product(oracle.OLayout(ti, to, tb), oracle.OLayout(mi, mo, mb))
+        got = ll.ll_product_dimwise(_mk(ti, to, tb), _mk(mi, mo, mb))
+        assert got.in_dims == [d for d in want.in_dims] and got.out_dims == want.out_dims
+        assert got.bases == want.bases
+        q = ll.ll_divide_left(got, _mk(ti, to, tb))
+        assert q.bases == mb and q.out_dims == mo
+        # any layout: the library and the oracle agree on divisibility and on the quotient
+        li, lo, lb = _random_layout(rng, want.in_dims, want.out_dims)
+        if rng.integers(0, 2):                      # often keep the tile's own columns
+            pos = 0
+            for (label, n) in want.in_dims:
+                nt = dict(ti).get(label, 0)
+                lb[pos:pos + nt] = want.bases[pos:pos + nt]
+                pos += n
+        oq = oracle.divide_left(oracle.OLayout(li, lo, lb), oracle.OLayout(ti, to, tb))
+        try:
+            lq = ll.ll_divide_left(_mk(li, lo, lb), _mk(ti, to, tb))
+        except ll.LLError as e:
+            assert e.status == ll.LL_ERR_NOT_DIVISIBLE and oq is None
+        else:
+            assert oq is not None and lq.bases == oq.bases and lq.out_dims == oq.out_dims
+
+
+def test_layout_a_built_from_tiles_and_divided_again():
+    regs = _mk([(ll.LL_IN_REG, 2)], [1, 1], [1, 2])
+    thrs = _mk([(ll.LL_IN_LANE, 5)], [2, 3], [1, 2, 4, 8, 16])
+    warps = _mk([(ll.LL_IN_WAVE, 1)], [1, 0], [1])
+    a = ll.ll_product_dimwise(ll.ll_product_dimwise(regs, thrs), warps)
+    assert a.bases == wl.PAPER_LAYOUT_A and a.out_dims == [4, 4]
+    q = ll.ll_divide_left(a, regs)
+    assert q.bases == ll.ll_product_dimwise(thrs, warps).bases
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_divide_left(a, _mk([(ll.LL_IN_REG, 2)], [0, 2], [1, 2]))
+    assert e.value.status == ll.LL_ERR_NOT_DIVISIBLE
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_divide_left(a, _mk([(ll.LL_IN_REG, 2)], [2], [1, 2]))
+    assert e.value.status == ll.LL_ERR_DIM_MISMATCH
+
+
+def test_generalized_vectorization_matches_brute_force():
+    """Sec. 5.3: the register permutation found while dividing, against the oracle's search over
+    all permutations (any permutation that works gives the same quotient up to register order, so
+    divisibility and the tile part are compared)."""
+    rng = np.random.default_rng(12)
+    for trial in range(60):
+        nreg, d = int(rng.integers(1, 5)), 6
+        cols = [1 << int(p) for p in rng.permutation(d)]
+        in_dims, out_dims = [(ll.LL_IN_REG, nreg), (ll.LL_IN_LANE, d - nreg)], [3, 3]
+        n = int(rng.integers(1, nreg + 1))
+        tile_o = oracle.identity_tile(ll.LL_IN_REG, n, n_out_dims=2)
+        tile = _mk(tile_o.in_dims, tile_o.out_dims, tile_o.bases)
+        want = oracle.divide_left_permuting(oracle.OLayout(in_dims, out_dims, cols), tile_o, ll.LL_IN_REG)
+        try:
+            perm, q = ll.ll_divide_left_permuted(_mk(in_dims, out_dims, cols), tile, ll.LL_IN_REG)
+        except ll.LLError as e:
+            assert e.status == ll.LL_ERR_NOT_DIVISIBLE and want is None, (cols, n)
+            continue
+        assert want is not None
+        assert sorted(perm) == list(range(nreg))
+        assert [cols[perm[k]] for k in range(n)] == [1 << k for k in range(n)]
+        assert sorted(q.bases) == sorted(want[1].bases)
+    # the paper's example: column-major registers vectorize after swapping them
+    perm, q = ll.ll_divide_left_permuted(_mk([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 2)], [2, 2], [4, 1, 2, 8]),
+                                         _mk([(ll.LL_IN_REG, 1)], [0, 1], [1]), ll.LL_IN_REG)
+    assert perm == [1, 0] and q.bases == [2, 1, 4]
+
+
+def test_contiguity_matches_the_oracle():
+    rng = np.random.default_rng(13)
+    assert ll.ll_contiguity(_mk([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 5)], [7, 0], [1, 2, 4, 8, 16, 32, 64])) == 4
+    assert ll.ll_contiguity(_mk([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 5), (ll.LL_IN_WAVE, 1)], [4, 4], wl.PAPER_LAYOUT_A)) == 2
+    assert ll.ll_contiguity(_mk([(ll.LL_IN_LANE, 3)], [3], [1, 2, 4])) == 1
+    for trial in range(60):
+        d, nreg = 8, int(rng.integers(1, 5))
+        d_in = d + int(rng.integers(0, 2))                      # sometimes one replica bit
+        while True:
+            cols = [int(rng.integers(0, 1 << d)) for _ in range(d_in)]
+            for k in range(int(rng.integers(0, nreg + 1))):
+                cols[k] = 1 << k
+            seen = {0}
+            for c in cols:
+                seen |= {x ^ c for x in seen}
+            if len(seen) == 1 << d:
+                break
+        in_dims = [(ll.LL_IN_REG, nreg), (ll.LL_IN_LANE, d_in - nreg)]
+        assert ll.ll_contiguity(_mk(in_dims, [d], cols)) == oracle.contiguity(oracle.OLayout(in_dims, [d], cols)), cols
