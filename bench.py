@@ -211,6 +211,34 @@ def main() -> int:
             torch.cuda.empty_cache()
         result["broadcast_conversions"] = btable
 
+        # the 128 x 128 transpose of config 2 with 1-byte (float8-sized) and 2-byte elements through the
+        # transposing LDS loads of gfx950, next to the same conversion with plain LDS reads
+        ttable = []
+        c2 = wl.config(2)
+        for w_, dt_, force_ in ((1, torch.uint8, None), (1, torch.uint8, "3"), (2, torch.int16, "6"), (2, torch.int16, "4")):
+            if force_ is not None:
+                os.environ["LL_FORCE_STRATEGY"] = force_
+            a = ll.distributed_layout(c2.nreg, c2.nlane, c2.nwave, c2.out_dim_bits, c2.src_bases)
+            b = ll.distributed_layout(c2.nreg, c2.nlane, c2.nwave, c2.out_dim_bits, c2.dst_bases)
+            plan = ll.ll_plan_convert(a, b, w_)
+            os.environ.pop("LL_FORCE_STRATEGY", None)
+            if args.strategy is not None:
+                os.environ["LL_FORCE_STRATEGY"] = str(args.strategy)
+            inf = plan.info()
+            nt = (256 << 20) // (c2.tile_elems * w_)            # 256 MiB per side
+            x = wl.raw_bits(21, 0, nt * c2.tile_elems * w_ // 8, dev).view(dt_)
+            outs = [torch.empty_like(x) for _ in range(2)]
+            _, _, md_ms, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % 2], nt), args.table_steps, 3)
+            ab = 2 * nt * c2.tile_elems * w_
+            ttable.append({"name": "transpose 128x128, %d-byte elements, %d tiles" % (w_, nt), "kernel": inf["strategy_name"],
+                           "lds_access_bytes": [inf["lds_write_bytes"], inf["lds_read_bytes"]], "block_bytes": (1 << inf["block_bits"]) * w_,
+                           "algorithmic_bytes": ab, "us_median": round(md_ms * 1e3, 2), "GBps": round(ab / md_ms / 1e6, 1),
+                           "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                           "predicted_wavefronts": [inf["predicted_wavefronts_write"], inf["predicted_wavefronts_read"]]})
+            del x, outs
+            torch.cuda.empty_cache()
+        result["narrow_element_transposes"] = ttable
+
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(main_cfg)
 

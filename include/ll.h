@@ -142,7 +142,8 @@ typedef enum {
     LL_STRATEGY_WAVE_SHUFFLE = 2, /* wave64 exchange by cross-lane shuffles */
     LL_STRATEGY_LDS_ELEM = 3,  /* LDS staging, element-wide (or common-vector-wide) accesses, XOR swizzle */
     LL_STRATEGY_LDS_VEC = 4,   /* LDS staging with in-register transposes and 128-bit LDS accesses */
-    LL_STRATEGY_LDS_PULL = 5   /* broadcasting layouts: destination units pull from LDS-staged source runs */
+    LL_STRATEGY_LDS_PULL = 5,  /* broadcasting layouts: destination units pull from LDS-staged source runs */
+    LL_STRATEGY_LDS_TR = 6     /* LDS staging read back with transposing LDS loads (1- and 2-byte elements) */
 } ll_strategy;
 
 #define LL_PLAN_MAX_BLOCK_BITS 20

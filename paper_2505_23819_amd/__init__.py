@@ -20,11 +20,11 @@ LL_OK, LL_ERR_INVALID_ARG, LL_ERR_DIM_MISMATCH, LL_ERR_NOT_SURJECTIVE, LL_ERR_NO
 LL_IN_REG, LL_IN_LANE, LL_IN_WAVE, LL_IN_TILE, LL_IN_OFFSET = range(5)
 LL_KIND_NOOP, LL_KIND_REG_ONLY, LL_KIND_INTRA_WAVE, LL_KIND_LDS, LL_KIND_BROADCAST = range(5)
 LL_STRATEGY_COPY, LL_STRATEGY_REG_PERMUTE, LL_STRATEGY_WAVE_SHUFFLE, LL_STRATEGY_LDS_ELEM, \
-    LL_STRATEGY_LDS_VEC, LL_STRATEGY_LDS_PULL = range(6)
+    LL_STRATEGY_LDS_VEC, LL_STRATEGY_LDS_PULL, LL_STRATEGY_LDS_TR = range(7)
 LL_MAX_IN_DIMS, LL_MAX_OUT_DIMS, LL_MAX_BITS, LL_PLAN_MAX_BLOCK_BITS = 5, 8, 30, 20
 
 KIND_NAMES = ["noop", "reg_only", "intra_wave", "lds", "broadcast"]
-STRATEGY_NAMES = ["copy", "reg_permute", "wave_shuffle", "lds_elem", "lds_vec", "lds_pull"]
+STRATEGY_NAMES = ["copy", "reg_permute", "wave_shuffle", "lds_elem", "lds_vec", "lds_pull", "lds_tr"]
 
 EXPORTED_SYMBOLS = [
     "ll_layout_create", "ll_layout_destroy", "ll_layout_get", "ll_layout_apply", "ll_compose",

@@ -129,7 +129,28 @@ static __device__ __forceinline__ void lds_get(const unsigned char *lds, uint32_
 // takes vector t + 256 i of the block's source runs), LDS writes at swizzled offsets, barrier,
 // LDS reads of the elements of its destination vectors, coalesced 16-byte stores.  Every index
 // map is linear over F2, so an offset is the XOR of per-bit table entries.
-template <int W, int NV, int V>
+// Read one 8-byte LDS chunk with the transposing load: the address this lane passes is used by
+// OTHER lanes of its group of 16 (see plan_tr.cpp for the measured lane behaviour); the result is
+// half of this lane's destination vector.
+template <int W>
+static __device__ __forceinline__ void lds_get_tr(unsigned char *lds, uint32_t addr, uint32_t (&r)[4], int s)
+{
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    typedef int v2i __attribute__((ext_vector_type(2)));
+    if constexpr (W == 2) {
+        const v4s x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3))) *)(lds + addr));
+        const u32x2 y = __builtin_bit_cast(u32x2, x);
+        r[2 * s] = y.x; r[2 * s + 1] = y.y;
+    } else {
+        static_assert(W == 1 || W == 2, "transposing LDS loads exist for 1- and 2-byte elements");
+        const v2i x = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3))) *)(lds + addr));
+        r[2 * s] = (uint32_t)x.x; r[2 * s + 1] = (uint32_t)x.y;
+    }
+}
+
+// TR = 1: the LDS reads are transposing loads (ds_read_b64_tr_b16 / _tr_b8), V must make the
+// access 8 bytes wide; the read tables then hold the addresses a lane supplies for its group.
+template <int W, int NV, int V, int TR = 0>
 __global__ __launch_bounds__(256) void k_lds_elem(const LdsElemArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -186,7 +207,10 @@ __global__ __launch_bounds__(256) void k_lds_elem(const LdsElemArgs a)
     for (int i = 0; i < NV; ++i) {
         const uint32_t base = cr ^ lr ^ a.lds_rd_iter[i];
 #pragma unroll
-        for (int s = 0; s < NSUB; ++s) lds_get<AB>(lds, base ^ a.lds_rd_sub[s], r[i], s);
+        for (int s = 0; s < NSUB; ++s) {
+            if constexpr (TR) lds_get_tr<W>(lds, base ^ a.lds_rd_sub[s], r[i], s);
+            else lds_get<AB>(lds, base ^ a.lds_rd_sub[s], r[i], s);
+        }
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -247,6 +271,31 @@ ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int ld
     case 8: return launch_lds_elem_n<8>(a, nvec, lds_vec_bits, lds_bytes, s);
     default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
     }
+}
+
+template <int W>
+static ll_status launch_lds_tr_w(const LdsElemArgs &a, int nvec, int lds_bytes, hipStream_t stream)
+{
+    constexpr int V = (W == 1) ? 3 : 2;             // 8-byte chunks
+    const dim3 grid((unsigned)a.nblocks), block(256);
+    switch (nvec) {
+    case 1: hipLaunchKernelGGL((k_lds_elem<W, 1, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 2: hipLaunchKernelGGL((k_lds_elem<W, 2, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 4: hipLaunchKernelGGL((k_lds_elem<W, 4, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 8: hipLaunchKernelGGL((k_lds_elem<W, 8, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    default: return fail(LL_ERR_UNSUPPORTED, "no transposing-read kernel for %d vectors per thread", nvec);
+    }
+    return check_launch("transposing-read conversion kernel launch");
+}
+
+ll_status launch_lds_tr(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_bytes, void *stream)
+{
+    if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
+    if (lds_bytes <= 0 || lds_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "LDS block of %d bytes", lds_bytes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (elem_bytes == 1) return launch_lds_tr_w<1>(a, nvec, lds_bytes, s);
+    if (elem_bytes == 2) return launch_lds_tr_w<2>(a, nvec, lds_bytes, s);
+    return fail(LL_ERR_UNSUPPORTED, "transposing LDS loads exist for 1- and 2-byte elements");
 }
 
 // ---------------------------------------------------------------------------------------------

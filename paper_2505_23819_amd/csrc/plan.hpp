@@ -68,6 +68,8 @@ namespace ll {
 // untouched.
 ll_status plan_wave_shuffle(const f2::mat &p, int d, int w, ll_plan *plan, bool *applied);
 ll_status plan_lds_vec(const f2::mat &p, int d, int w, ll_plan *plan, bool *applied);
+// LDS staging read back with the transposing LDS loads of gfx950 (plan_tr.cpp), 1- and 2-byte elements.
+ll_status plan_lds_tr(const f2::mat &p, int d, int w, ll_plan *plan, bool *applied);
 // Broadcasting layouts (plan_pull.cpp): A, B surjective, possibly not injective.
 ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan);
 ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan);

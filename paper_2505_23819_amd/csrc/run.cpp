@@ -25,6 +25,15 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.nblocks = groups << a.coset_bits;
         return launch_lds_elem(a, desc.elem_bytes, plan->nvec, desc.lds_vec_bits, desc.threads, desc.lds_bytes, stream);
     }
+    case LL_STRATEGY_LDS_TR: {
+        LdsElemArgs a = plan->lds_elem;
+        a.src = src;
+        a.dst = dst;
+        a.ntiles = ntiles;
+        const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
+        a.nblocks = groups << a.coset_bits;
+        return launch_lds_tr(a, desc.elem_bytes, plan->nvec, desc.lds_bytes, stream);
+    }
     case LL_STRATEGY_REG_PERMUTE:
     case LL_STRATEGY_WAVE_SHUFFLE:
     case LL_STRATEGY_LDS_VEC: {

@@ -113,3 +113,28 @@ def test_broadcast_convert_full_size_sampled(case):
         assert np.array_equal(s_tile, wl.to_numpy_bits(case.gen_data(t, 1)))
         want = oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, s_tile)
         assert np.array_equal(wl.to_numpy_bits(dst[t << dd:(t + 1) << dd]), want), f"{case.name} tile {t}"
+
+
+@pytest.mark.parametrize("w,force", [(1, None), (2, "6")])
+def test_narrow_transpose_full_size_sampled(w, force, monkeypatch):
+    """The 128 x 128 transpose with 1- and 2-byte elements through the transposing LDS loads, at the
+    size bench.py times (256 MiB per side)."""
+    if force:
+        monkeypatch.setenv("LL_FORCE_STRATEGY", force)
+    cfg = wl.config(2)
+    a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+    b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
+    plan = ll.ll_plan_convert(a, b, w)
+    assert plan.info()["strategy_name"] == "lds_tr"
+    te = cfg.tile_elems
+    nt = (256 << 20) // (te * w)
+    src = wl.raw_bits(21, 0, nt * te * w // 8, "cuda").view({1: torch.uint8, 2: torch.int16}[w])
+    dst = torch.empty_like(src)
+    ll.ll_convert(plan, src, dst, nt)
+    torch.cuda.synchronize()
+    # a transpose of the logical 128 x 128 view, on the whole buffer, with torch
+    assert torch.equal(dst.view(nt, te).to(torch.int64).sum(dim=1), src.view(nt, te).to(torch.int64).sum(dim=1))
+    for t in sample_tiles(nt, 10, 20 + w):
+        s_tile = wl.to_numpy_bits(src[t * te:(t + 1) * te])
+        want = oracle.convert(cfg.src_bases, cfg.dst_bases, s_tile)
+        assert np.array_equal(wl.to_numpy_bits(dst[t * te:(t + 1) * te]), want), f"tile {t}"

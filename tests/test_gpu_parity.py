@@ -310,3 +310,46 @@ def test_convert_broadcast_workloads_small(case):
         src = wl.to_numpy_bits(case.gen_data(0, ntiles))
         got = run_convert_general(plan, src, case.d_src, case.d_dst)
         assert np.array_equal(got, oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, src))
+
+
+# ---------------------------------------------------------------------------------------------
+# LDS staging read back with the transposing LDS loads (Sec. 5.3 "Using SIMD Hardware Primitives")
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("w", [1, 2])
+def test_convert_transposing_lds_reads(w, monkeypatch):
+    """Transposes and other bit permutations of 1- and 2-byte elements through ds_read_b64_tr_b8 /
+    _tr_b16 (forced, so that 2-byte cases do not take the register path)."""
+    monkeypatch.setenv("LL_FORCE_STRATEGY", "6")
+    rng = np.random.default_rng(600 + w)
+    used = 0
+    cases = []
+    c2 = wl.config(2)
+    cases.append((c2.nreg, c2.nlane, c2.nwave, c2.out_dim_bits, c2.src_bases, c2.dst_bases))
+    cases.append((c2.nreg, c2.nlane, c2.nwave, c2.out_dim_bits, c2.dst_bases, c2.src_bases))
+    c3 = wl.config(3)
+    cases.append((c3.nreg, c3.nlane, c3.nwave, c3.out_dim_bits, c3.src_bases, c3.dst_bases))
+    for d, nreg in [(12, 4), (13, 5), (14, 6), (16, 6), (11, 4)]:
+        for _ in range(4):
+            ca = [1 << int(p) for p in rng.permutation(d)]
+            cb = [1 << int(p) for p in rng.permutation(d)]
+            cases.append((nreg, 6, d - nreg - 6, [d], ca, cb))
+    for nreg, nlane, nwave, dims, ca, cb in cases:
+        d = nreg + nlane + nwave
+        plan = ll.ll_plan_convert(ll.distributed_layout(nreg, nlane, nwave, dims, ca),
+                                  ll.distributed_layout(nreg, nlane, nwave, dims, cb), w)
+        used += plan.info()["strategy_name"] == "lds_tr"
+        ntiles = int(rng.integers(1, 12))
+        src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+        assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src)), plan.info()["strategy_name"]
+    assert used >= 3, "the transposing-read planner applied to %d cases only" % used
+
+
+def test_one_byte_transpose_takes_transposing_reads_by_default():
+    c2 = wl.config(2)
+    a, b = layouts_of(c2)
+    plan = ll.ll_plan_convert(a, b, 1)
+    info = plan.info()
+    assert info["strategy_name"] == "lds_tr" and info["lds_read_bytes"] == 8
+    src = np.random.default_rng(5).integers(0, 255, size=9 << c2.d, dtype=np.uint8)
+    assert np.array_equal(run_convert(plan, src, c2.d), oracle.convert(c2.src_bases, c2.dst_bases, src))
