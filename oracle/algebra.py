@@ -89,7 +89,8 @@ def product(a: OLayout, b: OLayout) -> OLayout:
                     for i in range(nb):
                         col[row_of(which, j, i)] = mat[out_shift(lay.out_dims, j) + i, c]
                 cols.append(col)
-    return from_matrix(np.stack(cols, axis=1), in_dims, out_dims)
+    full = np.stack(cols, axis=1) if cols else np.zeros((sum(out_dims), 0), dtype=np.uint8)
+    return from_matrix(full, in_dims, out_dims)
 
 
 def divide_left(lay: OLayout, tile: OLayout) -> Optional[OLayout]:
