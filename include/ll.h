@@ -120,6 +120,45 @@ ll_status ll_divide_left_permuted(const ll_layout *layout, const ll_layout *tile
  * i.e. the widest vector one thread can load or store.  1 if the layout has no register bits. */
 ll_status ll_contiguity(const ll_layout *layout, int32_t *elems);
 
+/* ---- layout families (paper Sec. 4.3, appendix) --------------------------------------------- */
+
+/* id_k^{label, dim} (appendix "Notation"): the first k bits of input `label` map identically onto
+ * the first k bits of logical dim `dim` (dims numbered slowest first) of an n_dims-dim tensor whose
+ * other dims have no bits.  Building block for ll_product_dimwise. */
+ll_status ll_layout_identity(int label, int dim, int k, int n_dims, ll_layout **out);
+
+/* Blocked layout (Proposition "Blocked layouts are linear layouts"): reg_bits / lane_bits /
+ * wave_bits give, per dim, the log2 number of registers, lanes and waves along it; order[i] is the
+ * i-th fastest dim.  The result is id_R^o x id_T^o x id_W^o; dim k has reg + lane + wave bits. */
+ll_status ll_layout_blocked(int n_dims, const int32_t *reg_bits, const int32_t *lane_bits, const int32_t *wave_bits,
+                            const int32_t *order, ll_layout **out);
+
+/* Result tile of a CDNA matrix instruction with a 16x16 (m_bits 4) or 32x32 (m_bits 5) fp32
+ * accumulator on 64 lanes, as the product id_2^{reg,0} x id_m^{lane,1} x id_{6-m}^{lane,0} x
+ * id_{2m-8}^{reg,0} (the pattern of the appendix's proof for `mma`): a lane holds groups of 4
+ * consecutive rows of one column.  Multiply by further identities (ll_product_dimwise) to cover
+ * a larger tensor with registers or waves. */
+ll_status ll_layout_mfma_accumulator(int m_bits, ll_layout **out);
+
+/* Left-operand tile (2^m_bits rows x K) of the same instructions: a lane holds 2^k_reg_bits
+ * consecutive elements along K of one row: id_kr^{reg,1} x id_m^{lane,0} x id_{6-m}^{lane,1}. */
+ll_status ll_layout_mfma_operand(int m_bits, int k_reg_bits, ll_layout **out);
+
+/* The legacy `mma` swizzle (Def. "mma swizzling") for a row-major 2^m_bits x 2^n_bits tensor as a
+ * memory layout (input label `offset`, logical dims (i, j)), built from the closed form of
+ * Sec. 4.3: [[I_n, C], [0, I_m]] with c_i = (vec * ((2^i / per_phase) mod max_phase)) mod 2^n.
+ * vec_elems, per_phase, max_phase: powers of two with vec_elems * max_phase <= 2^n_bits. */
+ll_status ll_layout_mma_swizzle(int m_bits, int n_bits, int vec_elems, int per_phase, int max_phase, ll_layout **out);
+
+/* Family tests: OR of the flags below.  DISTRIBUTED: Def. "Distributed Layout" (surjective, every
+ * column zero or a unit vector, no unit vector twice; register / lane / wave / tile inputs).
+ * MEMORY: Def. "Memory Layout" (invertible, every column has one or two non-zero bits). */
+#define LL_LAYOUT_SURJECTIVE 1u
+#define LL_LAYOUT_INJECTIVE 2u
+#define LL_LAYOUT_DISTRIBUTED 4u
+#define LL_LAYOUT_MEMORY 8u
+ll_status ll_layout_classify(const ll_layout *layout, uint32_t *flags);
+
 /* Right inverse (Def. "Right Inverse") by Gaussian elimination over F2.  L must be surjective,
  * else LL_ERR_NOT_SURJECTIVE.  If L is not injective the free variables are set to zero, with
  * input columns taken as pivots in order (register bits first).  The result maps one `offset`

@@ -30,8 +30,10 @@ EXPORTED_SYMBOLS = [
     "ll_layout_create", "ll_layout_destroy", "ll_layout_get", "ll_layout_apply", "ll_compose",
     "ll_product", "ll_invert", "ll_plan_convert", "ll_plan_info", "ll_plan_destroy", "ll_convert",
     "ll_gather", "ll_copy", "ll_last_error", "ll_product_dimwise", "ll_divide_left",
-    "ll_divide_left_permuted", "ll_contiguity",
+    "ll_divide_left_permuted", "ll_contiguity", "ll_layout_identity", "ll_layout_blocked",
+    "ll_layout_mfma_accumulator", "ll_layout_mfma_operand", "ll_layout_mma_swizzle", "ll_layout_classify",
 ]
+LL_LAYOUT_SURJECTIVE, LL_LAYOUT_INJECTIVE, LL_LAYOUT_DISTRIBUTED, LL_LAYOUT_MEMORY = 1, 2, 4, 8
 
 
 class ll_in_dim(ctypes.Structure):
@@ -223,6 +225,46 @@ def ll_contiguity(layout: Layout) -> int:
     out = ctypes.c_int32()
     _check(_lib.ll_contiguity(layout._h, ctypes.byref(out)))
     return out.value
+
+
+def _made(status, h) -> Layout:
+    _check(status)
+    return Layout(h.value)
+
+
+def ll_layout_identity(label: int, dim: int, k: int, n_dims: int) -> Layout:
+    h = ctypes.c_void_p()
+    return _made(_lib.ll_layout_identity(int(label), int(dim), int(k), int(n_dims), ctypes.byref(h)), h)
+
+
+def ll_layout_blocked(reg_bits: Sequence[int], lane_bits: Sequence[int], wave_bits: Sequence[int],
+                      order: Sequence[int]) -> Layout:
+    n = len(order)
+    arr = lambda xs: (ctypes.c_int32 * n)(*[int(x) for x in xs])
+    h = ctypes.c_void_p()
+    return _made(_lib.ll_layout_blocked(n, arr(reg_bits), arr(lane_bits), arr(wave_bits), arr(order), ctypes.byref(h)), h)
+
+
+def ll_layout_mfma_accumulator(m_bits: int) -> Layout:
+    h = ctypes.c_void_p()
+    return _made(_lib.ll_layout_mfma_accumulator(int(m_bits), ctypes.byref(h)), h)
+
+
+def ll_layout_mfma_operand(m_bits: int, k_reg_bits: int) -> Layout:
+    h = ctypes.c_void_p()
+    return _made(_lib.ll_layout_mfma_operand(int(m_bits), int(k_reg_bits), ctypes.byref(h)), h)
+
+
+def ll_layout_mma_swizzle(m_bits: int, n_bits: int, vec: int, per_phase: int, max_phase: int) -> Layout:
+    h = ctypes.c_void_p()
+    return _made(_lib.ll_layout_mma_swizzle(int(m_bits), int(n_bits), int(vec), int(per_phase), int(max_phase),
+                                            ctypes.byref(h)), h)
+
+
+def ll_layout_classify(layout: Layout) -> int:
+    flags = ctypes.c_uint32()
+    _check(_lib.ll_layout_classify(layout._h, ctypes.byref(flags)))
+    return flags.value
 
 
 def ll_invert(layout: Layout) -> Layout:

@@ -238,3 +238,96 @@ def test_contiguity_matches_the_oracle():
                 break
         in_dims = [(ll.LL_IN_REG, nreg), (ll.LL_IN_LANE, d_in - nreg)]
         assert ll.ll_contiguity(_mk(in_dims, [d], cols)) == oracle.contiguity(oracle.OLayout(in_dims, [d], cols)), cols
+
+
+# ---- layout families (Sec. 4.3, appendix) against the oracle's constructions
+
+def _same(lib_layout, o):
+    assert lib_layout.bases == o.bases, (lib_layout.bases, o.bases)
+    assert lib_layout.out_dims == o.out_dims
+    assert lib_layout.in_dims == [d for d in o.in_dims if d[1] > 0]
+
+
+def test_blocked_constructor_matches_the_oracle_and_layout_a():
+    assert ll.ll_layout_blocked([1, 1], [2, 3], [1, 0], [1, 0]).bases == wl.PAPER_LAYOUT_A
+    rng = np.random.default_rng(21)
+    for _ in range(40):
+        nd = int(rng.integers(1, 4))
+        r = [int(x) for x in rng.integers(0, 3, size=nd)]
+        t = [int(x) for x in rng.integers(0, 3, size=nd)]
+        w = [int(x) for x in rng.integers(0, 2, size=nd)]
+        order = [int(x) for x in rng.permutation(nd)]
+        if sum(r) + sum(t) + sum(w) == 0:
+            continue
+        _same(ll.ll_layout_blocked(r, t, w, order), oracle.blocked_layout(r, t, w, order))
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_layout_blocked([1, 1], [2, 3], [1, 0], [1, 1])
+    assert e.value.status == ll.LL_ERR_INVALID_ARG
+
+
+def test_matrix_instruction_tiles_match_the_oracle_and_the_configs():
+    for m in (4, 5):
+        _same(ll.ll_layout_mfma_accumulator(m), oracle.mfma_accumulator_tile(m))
+        for kr in (2, 3):
+            _same(ll.ll_layout_mfma_operand(m, kr), oracle.mfma_operand_tile(m, kr))
+    # config 1's destination and config 3's source built from tiles with ll_product_dimwise
+    c1, c3 = wl.config(1), wl.config(3)
+    acc32 = ll.ll_layout_mfma_accumulator(5)
+    full = ll.ll_product_dimwise(ll.ll_product_dimwise(acc32, ll.ll_layout_identity(ll.LL_IN_WAVE, 0, 1, 2)),
+                                 ll.ll_layout_identity(ll.LL_IN_WAVE, 1, 1, 2))
+    assert full.bases == c1.dst_bases
+    acc16 = ll.ll_layout_mfma_accumulator(4)
+    full = ll.ll_product_dimwise(ll.ll_product_dimwise(acc16, ll.ll_layout_identity(ll.LL_IN_REG, 0, 2, 2)),
+                                 ll.ll_layout_identity(ll.LL_IN_REG, 1, 2, 2))
+    assert full.bases == c3.src_bases
+    # and the accumulator tile divides config 1's destination layout again (Sec. 5.3)
+    c1_dst = ll.distributed_layout(c1.nreg, c1.nlane, c1.nwave, c1.out_dim_bits, c1.dst_bases)
+    q = ll.ll_divide_left(c1_dst, acc32)
+    assert q.bases == [1 << 1, 1 << 0] and q.out_dims == [1, 1]
+
+
+@pytest.mark.parametrize("m,n,vec,per_phase,max_phase", [(3, 3, 1, 1, 8), (4, 6, 8, 1, 8), (5, 5, 4, 2, 4),
+                                                         (6, 4, 2, 4, 8), (3, 6, 8, 2, 2), (4, 4, 4, 1, 1)])
+def test_mma_swizzle_closed_form_matches_the_definition(m, n, vec, per_phase, max_phase):
+    lay = ll.ll_layout_mma_swizzle(m, n, vec, per_phase, max_phase)
+    _same(lay, oracle.mma_swizzle_layout(m, n, vec, per_phase, max_phase))
+    inv = ll.ll_invert(lay)                                  # logical (i, j) -> offset: Def. "mma swizzling"
+    for i in range(1 << m):
+        for j in range(1 << n):
+            assert inv.apply((i << n) | j) == oracle.mma_swizzle_offset(i, j, n, vec, per_phase, max_phase)
+    assert ll.ll_layout_classify(lay) & ll.LL_LAYOUT_MEMORY
+
+
+def test_mma_swizzle_rejects_parameters_that_leave_the_row():
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_layout_mma_swizzle(4, 3, 4, 1, 4)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG
+    with pytest.raises(ll.LLError):
+        ll.ll_layout_mma_swizzle(4, 4, 3, 1, 4)
+
+
+def test_classify_matches_the_oracle_definitions():
+    rng = np.random.default_rng(22)
+    seen = set()
+    for trial in range(300):
+        d_out = int(rng.integers(1, 6))
+        d_in = d_out + int(rng.integers(-1, 2))
+        if d_in < 1:
+            continue
+        kind = trial % 3
+        if kind == 0:
+            cols = [int(rng.integers(0, 1 << d_out)) for _ in range(d_in)]
+        elif kind == 1:                                          # unit vectors and zeros
+            cols = [0 if rng.integers(0, 4) == 0 else 1 << int(rng.integers(0, d_out)) for _ in range(d_in)]
+        else:                                                    # one or two bits per column
+            cols = [(1 << int(rng.integers(0, d_out))) | (1 << int(rng.integers(0, d_out))) for _ in range(d_in)]
+        hw = [(ll.LL_IN_REG, d_in)]
+        flags = ll.ll_layout_classify(_mk(hw, [d_out], cols))
+        o = oracle.OLayout(hw, [d_out], cols)
+        images = {oracle.apply(cols, h) for h in range(1 << d_in)}
+        assert bool(flags & ll.LL_LAYOUT_SURJECTIVE) == (len(images) == 1 << d_out)
+        assert bool(flags & ll.LL_LAYOUT_INJECTIVE) == (len(images) == 1 << d_in)
+        assert bool(flags & ll.LL_LAYOUT_DISTRIBUTED) == oracle.is_distributed_layout(o), cols
+        assert bool(flags & ll.LL_LAYOUT_MEMORY) == oracle.is_memory_layout(o), cols
+        seen.add(flags)
+    assert len(seen) >= 5                                        # the cases really differ
