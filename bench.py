@@ -239,6 +239,33 @@ def main() -> int:
             torch.cuda.empty_cache()
         result["narrow_element_transposes"] = ttable
 
+        # gather variants on config 5's layout: rows (lane axis) with each of the three kernels, and
+        # columns (an axis on register and wave bits: 16 shuffle rounds in the paper's scheme)
+        gtable = []
+        c5 = wl.config(5)
+        lay5 = ll.distributed_layout(c5.nreg, c5.nlane, c5.nwave, c5.out_dim_bits, c5.src_bases)
+        x5 = c5.gen_data(0, c5.ntiles, dev)
+        out5 = torch.empty_like(x5)
+        for axis_, env_ in ((0, {}), (0, {"LL_GATHER_STAGED": "0"}), (0, {"LL_GATHER_GENERAL": "1"}), (1, {})):
+            for k_, v_ in env_.items():
+                os.environ[k_] = v_
+            ginfo = ll.ll_gather_info(lay5, axis_, c5.elem_bytes)
+            idx5 = wl.gen_index(51 + axis_, 0, c5.ntiles * c5.tile_elems, 1 << c5.out_dim_bits[axis_], dev)
+            _, _, md_ms, _ = time_launches(lambda k: ll.ll_gather(lay5, axis_, c5.elem_bytes, x5, idx5, out5, c5.ntiles),
+                                           args.table_steps, 3)
+            for k_ in env_:
+                del os.environ[k_]
+            ab = c5.algorithmic_bytes()
+            gtable.append({"name": "config 5 layout, gather along dim %d" % axis_, "kernel": ginfo["kernel_name"],
+                           "axis_bits_reg_lane_wave": [ginfo["axis_reg_bits"], ginfo["axis_lane_bits"], ginfo["axis_wave_bits"]],
+                           "paper_rounds": ginfo["paper_rounds"], "staged_bytes": ginfo["block_bytes"],
+                           "algorithmic_bytes": ab, "us_median": round(md_ms * 1e3, 2), "GBps": round(ab / md_ms / 1e6, 1),
+                           "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)})
+            del idx5
+        del x5, out5
+        torch.cuda.empty_cache()
+        result["gather_variants"] = gtable
+
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(main_cfg)
 

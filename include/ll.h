@@ -256,10 +256,33 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
 /* ---- gather (paper Sec. 5.5) ----------------------------------------------------------- */
 
 /* out[.., i, ..] = in[.., idx[.., i, ..], ..] along output dim `axis`, where in, idx (int32) and
- * out are images under the same bijective layout L.  The axis must lie inside one wave: moving
- * along it must change lane bits only (LL_ERR_AXIS_NOT_IN_WAVE if it changes wave bits,
- * LL_ERR_UNSUPPORTED if it changes register bits).  Indices are reduced modulo the axis
- * length.  Pointers are DEVICE pointers.  Asynchronous on hip_stream. */
+ * out are images under the same bijective layout L.  Indices are reduced modulo the axis length.
+ * Moving along the axis changes the hardware index by L^-1 of the axis bits:
+ *  - lane bits only (the paper's condition, Sec. 5.5, with one round): cross-lane shuffles, or
+ *    wave-private LDS staging when a lane holds more than 16 bytes;
+ *  - register and / or wave bits as well: the aligned block of image elements those bits span is
+ *    staged in workgroup LDS (at most 64 KiB).  If it does not fit: LL_ERR_AXIS_NOT_IN_WAVE when
+ *    the axis crosses waves, LL_ERR_UNSUPPORTED otherwise;
+ *  - tile bits: LL_ERR_TILE_MIXED.
+ * Pointers are DEVICE pointers.  Asynchronous on hip_stream. */
+typedef enum {
+    LL_GATHER_SHUFFLE = 0,       /* one ds_bpermute_b32 per 32-bit piece of an element */
+    LL_GATHER_WAVE_STAGED = 1,   /* coalesced access, source rows staged in wave-private LDS */
+    LL_GATHER_BLOCK_STAGED = 2   /* general: a block closed under the axis staged in workgroup LDS */
+} ll_gather_kernel;
+
+typedef struct {
+    int32_t kernel;              /* ll_gather_kernel */
+    int32_t axis_reg_bits;       /* hardware bits a move along the axis can flip, by label */
+    int32_t axis_lane_bits;
+    int32_t axis_wave_bits;
+    int32_t paper_rounds;        /* 2^axis_reg_bits: the shuffle rounds of Sec. 5.5 */
+    int32_t block_bytes;         /* bytes of `in` one wave (kernels 0, 1) or workgroup (kernel 2) stages */
+} ll_gather_desc;
+
+/* What ll_gather would do for this layout, axis and element size (same checks and errors). */
+ll_status ll_gather_info(const ll_layout *layout, int axis, int elem_bytes, ll_gather_desc *out);
+
 ll_status ll_gather(const ll_layout *layout, int axis, int elem_bytes, const void *in_dev,
                     const int32_t *idx_dev, void *out_dev, int64_t ntiles, void *hip_stream);
 

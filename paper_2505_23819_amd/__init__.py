@@ -32,7 +32,14 @@ EXPORTED_SYMBOLS = [
     "ll_gather", "ll_copy", "ll_last_error", "ll_product_dimwise", "ll_divide_left",
     "ll_divide_left_permuted", "ll_contiguity", "ll_layout_identity", "ll_layout_blocked",
     "ll_layout_mfma_accumulator", "ll_layout_mfma_operand", "ll_layout_mma_swizzle", "ll_layout_classify",
+    "ll_gather_info",
 ]
+GATHER_KERNEL_NAMES = ["shuffle", "wave_staged", "block_staged"]
+
+
+class ll_gather_desc(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("axis_reg_bits", ctypes.c_int32), ("axis_lane_bits", ctypes.c_int32),
+                ("axis_wave_bits", ctypes.c_int32), ("paper_rounds", ctypes.c_int32), ("block_bytes", ctypes.c_int32)]
 LL_LAYOUT_SURJECTIVE, LL_LAYOUT_INJECTIVE, LL_LAYOUT_DISTRIBUTED, LL_LAYOUT_MEMORY = 1, 2, 4, 8
 
 
@@ -259,6 +266,14 @@ def ll_layout_mma_swizzle(m_bits: int, n_bits: int, vec: int, per_phase: int, ma
     h = ctypes.c_void_p()
     return _made(_lib.ll_layout_mma_swizzle(int(m_bits), int(n_bits), int(vec), int(per_phase), int(max_phase),
                                             ctypes.byref(h)), h)
+
+
+def ll_gather_info(layout: Layout, axis: int, elem_bytes: int) -> dict:
+    d = ll_gather_desc()
+    _check(_lib.ll_gather_info(layout._h, int(axis), int(elem_bytes), ctypes.byref(d)))
+    out = {name: getattr(d, name) for name, _ in ll_gather_desc._fields_}
+    out["kernel_name"] = GATHER_KERNEL_NAMES[d.kernel]
+    return out
 
 
 def ll_layout_classify(layout: Layout) -> int:

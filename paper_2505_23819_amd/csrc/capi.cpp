@@ -232,6 +232,12 @@ ll_status ll_gather(const ll_layout *layout, int axis, int elem_bytes, const voi
     return st;
 }
 
+ll_status ll_gather_info(const ll_layout *layout, int axis, int elem_bytes, ll_gather_desc *out)
+{
+    if (!layout || !out) return fail(LL_ERR_INVALID_ARG, "null argument");
+    return ll::describe_gather(layout, axis, elem_bytes, out);
+}
+
 ll_status ll_copy(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream)
 {
     if (bytes < 0 || (bytes & 15)) return fail(LL_ERR_INVALID_ARG, "bytes must be a non-negative multiple of 16");

@@ -931,6 +931,167 @@ static ll_status launch_gather_w(const GatherArgs &a, hipStream_t stream)
     }
 }
 
+// General gather: any bijective layout, axis bits anywhere inside the block.  256 threads.
+//   stage   coalesced 16-byte loads of the block of `in`, written to LDS word by word (4-byte words,
+//           8-byte for 8-byte elements) at XOR-swizzled addresses;
+//   gather  a unit of work is 4 consecutive output elements (one coalesced 16-byte load of their
+//           indices).  For each element the XOR delta that moves its hardware index along the axis
+//           to the indexed coordinate (Sec. 5.5: the source is L^-1 of the element's logical
+//           position with the axis coordinate replaced) is linear in x = idx ^ own coordinate, and
+//           so is the swizzle: the LDS address of the source is (address of the element itself) ^
+//           T(x), with T read from tables of 32 entries per 5 bits of x that sit in LDS behind the
+//           block (32 consecutive words: any access pattern to one table is conflict free).
+// The swizzle moves higher address bits into the bank bits so that lanes reading the same register
+// slot of different layout lanes fall in different banks; reads are data dependent, so conflicts
+// cannot be excluded in general.  U: passes handled together (loads issued back to back).
+template <int W, int U>
+__global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
+    const uint32_t tid = threadIdx.x;
+    const long long first = (long long)blockIdx.x << a.block_bits;
+    const uint32_t block_elems = 1u << a.block_bits;
+    const long long left = a.total_elems - first;
+    const uint32_t valid = left >= (long long)block_elems ? block_elems : (uint32_t)left;
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(static_cast<const unsigned char *>(a.in) + (size_t)first * W, valid * W);
+    const __amdgpu_buffer_rsrc_t rix = make_rsrc(reinterpret_cast<const unsigned char *>(a.idx) + (size_t)first * 4, valid * 4);
+    const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (size_t)first * W, valid * W);
+    auto swz = [&](uint32_t addr) { return addr ^ (((addr >> a.swz_shift) & a.swz_mask) << a.swz_to); };
+    uint32_t *table = reinterpret_cast<uint32_t *>(lds + ((size_t)block_elems * W));
+    const int ntab = (a.na + 4) / 5;
+
+    // delta tables
+    if (tid < 32u * (uint32_t)ntab) {
+        const uint32_t x = (tid & 31u) << (5u * (tid >> 5));
+        uint32_t dl = 0;
+        for (int b = 0; b < a.na; ++b) dl ^= a.delta[b] & (0u - ((x >> b) & 1u));
+        table[tid] = swz(dl * W);
+    }
+    // stage the block
+    const uint32_t vec_passes = (block_elems >> VS) >> 8;        // 16-byte vectors per thread (a multiple of U)
+    for (uint32_t p = 0; p < vec_passes; p += U) {
+        u32x4 x[U];
+#pragma unroll
+        for (int q = 0; q < U; ++q) x[q] = buf_load16(rin, (tid + 256u * (p + q)) * 16u);
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const uint32_t at = (tid + 256u * (p + q)) * 16u;
+            if constexpr (W == 8) {
+                const u32x2 lo = {x[q].x, x[q].y}, hi = {x[q].z, x[q].w};
+                *reinterpret_cast<u32x2 *>(lds + swz(at)) = lo;
+                *reinterpret_cast<u32x2 *>(lds + swz(at + 8)) = hi;
+            } else {
+                *reinterpret_cast<uint32_t *>(lds + swz(at)) = x[q].x;
+                *reinterpret_cast<uint32_t *>(lds + swz(at + 4)) = x[q].y;
+                *reinterpret_cast<uint32_t *>(lds + swz(at + 8)) = x[q].z;
+                *reinterpret_cast<uint32_t *>(lds + swz(at + 12)) = x[q].w;
+            }
+        }
+    }
+    // axis coordinate of an element = XOR of the contributions of the set bits of its hardware
+    // index: the block's bits (uniform), this thread's bits, the pass's bits, the slot's bits
+    uint32_t own_t = 0;
+    {
+        const unsigned long long f = (unsigned long long)first;
+        for (int b = a.block_bits; b < 32; ++b) own_t ^= a.own_bit[b] & (0u - (uint32_t)((f >> b) & 1ull));
+#pragma unroll
+        for (int b = 0; b < 8; ++b) own_t ^= a.own_bit[2 + b] & (0u - ((tid >> b) & 1u));
+    }
+    const uint32_t own_s[4] = {0u, a.own_bit[0], a.own_bit[1], a.own_bit[0] ^ a.own_bit[1]};
+    const uint32_t unit_passes = (block_elems >> 2) >> 8;         // 4-element units per thread (a multiple of U)
+    __syncthreads();
+
+    for (uint32_t p = 0; p < unit_passes; p += U) {
+        u32x4 ix[U];
+#pragma unroll
+        for (int q = 0; q < U; ++q) ix[q] = buf_load16(rix, (tid + 256u * (p + q)) * 16u);
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const uint32_t pass = p + q;
+            const uint32_t unit = tid + 256u * pass;
+            uint32_t own_p = own_t;
+            for (int b = 0; (pass >> b) != 0; ++b) own_p ^= a.own_bit[10 + b] & (0u - ((pass >> b) & 1u));
+            const uint32_t self = swz(unit * (4u * W));           // LDS address of the unit's first element
+            const uint32_t idx4[4] = {ix[q].x, ix[q].y, ix[q].z, ix[q].w};
+            uint32_t o[(W == 8) ? 8 : 4] = {};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const uint32_t x = (idx4[s] ^ own_p ^ own_s[s]) & a.axis_mask;
+                uint32_t t = table[x & 31u];
+                if (ntab > 1) t ^= table[32u + ((x >> 5) & 31u)];
+                if (ntab > 2) t ^= table[64u + ((x >> 10) & 31u)];
+                if (ntab > 3) t ^= table[96u + (x >> 15)];
+                const uint32_t addr = self ^ ((uint32_t)s * W) ^ t;   // XOR, not add: the swizzle may have set bit 2 of self
+                if constexpr (W == 8) {
+                    const u32x2 v = *reinterpret_cast<const u32x2 *>(lds + addr);
+                    o[2 * s] = v.x; o[2 * s + 1] = v.y;
+                } else if constexpr (W == 4) {
+                    o[s] = *reinterpret_cast<const uint32_t *>(lds + addr);
+                } else if constexpr (W == 2) {
+                    o[s >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t *>(lds + addr) << ((s & 1) * 16);
+                } else {
+                    o[0] |= (uint32_t)*reinterpret_cast<const uint8_t *>(lds + addr) << (s * 8);
+                }
+            }
+            if constexpr (W == 8) {
+                const u32x4 lo = {o[0], o[1], o[2], o[3]}, hi = {o[4], o[5], o[6], o[7]};
+                buf_store16(rout, unit * 32u, lo);
+                buf_store16(rout, unit * 32u + 16u, hi);
+            } else if constexpr (W == 4) {
+                const u32x4 v = {o[0], o[1], o[2], o[3]};
+                buf_store16(rout, unit * 16u, v);
+            } else if constexpr (W == 2) {
+                const u32x2 v = {o[0], o[1]};
+                __builtin_amdgcn_raw_buffer_store_b64(v, rout, unit * 8u, 0, kStream);
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b32(o[0], rout, unit * 4u, 0, kStream);
+            }
+        }
+    }
+}
+
+template <int W>
+static ll_status launch_gather_general_w(const GatherGenArgs &a, hipStream_t s)
+{
+    constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
+    const long long block_bytes = (1ll << a.block_bits) * W;
+    const size_t lds_bytes = (size_t)block_bytes + 128u * (size_t)((a.na + 4) / 5);
+    const dim3 grid((unsigned)a.nblocks), block(256);
+    const int vec_passes = (int)((1ll << a.block_bits) >> VS >> 8), unit_passes = (int)((1ll << a.block_bits) >> 10);
+    if (vec_passes < 1 || unit_passes < 1) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than one pass");
+    const int together = vec_passes < unit_passes ? vec_passes : unit_passes;   // both are powers of two
+    if (together >= 4) {
+        if (lds_bytes > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gather_general<W, 4>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+            if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+        }
+        hipLaunchKernelGGL((k_gather_general<W, 4>), grid, block, lds_bytes, s, a);
+    } else if (together == 2) {
+        hipLaunchKernelGGL((k_gather_general<W, 2>), grid, block, lds_bytes, s, a);
+    } else {
+        hipLaunchKernelGGL((k_gather_general<W, 1>), grid, block, lds_bytes, s, a);
+    }
+    return check_launch("general gather kernel launch");
+}
+
+ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *stream)
+{
+    if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
+    const long long block_bytes = (1ll << a.block_bits) * elem_bytes;
+    if (block_bytes < 4096 || block_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "gather block of %lld bytes", block_bytes);
+    if (a.na < 0 || a.na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", a.na);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (elem_bytes) {
+    case 1: return launch_gather_general_w<1>(a, s);
+    case 2: return launch_gather_general_w<2>(a, s);
+    case 4: return launch_gather_general_w<4>(a, s);
+    case 8: return launch_gather_general_w<8>(a, s);
+    default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
+    }
+}
+
 ll_status launch_gather(const GatherArgs &a, int elem_bytes, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -108,6 +108,26 @@ struct GatherArgs {
     int staged;               // 1: coalesced global access with the source staged in wave-private LDS
 };
 
+// General gather (paper Sec. 5.5 extended): the axis may occupy register, lane and wave bits.  A
+// workgroup stages a block of 2^block_bits consecutive image elements (a block that is closed
+// under moves along the axis) in LDS and reads every output element's source from there.
+constexpr int kMaxAxisBits = 16;
+struct GatherGenArgs {
+    const void *in;
+    const int32_t *idx;
+    void *out;
+    long long nblocks;
+    long long total_elems;               // ntiles * 2^d
+    int block_bits;                      // log2 elements per workgroup block
+    int na;                              // axis bits
+    uint32_t axis_mask;
+    uint32_t delta[kMaxAxisBits];        // per axis bit: XOR on the block-local hardware index
+    uint32_t own_bit[32];                // per hardware-index bit (0 above the tile): axis coordinate contribution
+    int swz_shift, swz_to;               // LDS byte address ^= ((address >> swz_shift) & swz_mask) << swz_to
+    uint32_t swz_mask;
+};
+
+ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *stream);
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,
                           int lds_bytes, void *stream);
 ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose, int xchg, int threads, int lds_bytes,

@@ -74,6 +74,7 @@ ll_status plan_lds_tr(const f2::mat &p, int d, int w, ll_plan *plan, bool *appli
 ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan);
 ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan);
 ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long ntiles, void *stream);
+ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gather_desc *out);
 ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *in, const int32_t *idx,
                      void *out, long long ntiles, void *stream);
 }  // namespace ll

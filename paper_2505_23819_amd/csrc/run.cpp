@@ -1,5 +1,6 @@
 // Host side of the device entry points: pick the kernel a plan names, fill the per-call fields of
 // its argument block, validate the gather layout (paper Sec. 5.5) and launch.
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 
@@ -60,69 +61,150 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
     }
 }
 
-ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *in, const int32_t *idx, void *out,
-                     long long ntiles, void *stream)
+// What run_gather decides before it launches: which kernel, and the geometry of the general one.
+struct GatherChoice {
+    int kernel = 0;                    // ll_gather_desc.kernel
+    int axis_reg_bits = 0, axis_lane_bits = 0, axis_wave_bits = 0;
+    GatherArgs wave = {};              // shuffle / wave-staged kernels
+    GatherGenArgs gen = {};            // workgroup-staged kernel
+};
+
+static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, GatherChoice *c)
 {
     for (int i = 0; i < L->n_in; ++i)
         if (L->in_dims[i].label == LL_IN_OFFSET)
             return fail(LL_ERR_INVALID_ARG, "gather needs a distributed layout (register / lane / wave / tile inputs)");
+    if (axis < 0 || axis >= L->n_out) return fail(LL_ERR_INVALID_ARG, "axis %d of a %d-dim tensor", axis, L->n_out);
+    if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8)
+        return fail(LL_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8 (got %d)", elem_bytes);
     const int d = L->d_in;
     if (f2::rank(L->bases) < L->d_out) return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
     if (d > L->d_out) return fail(LL_ERR_NOT_INJECTIVE, "layouts with broadcasting are not supported");
     mat linv;
     if (!f2::invert(L->bases, d, &linv)) return fail(LL_ERR_NOT_INJECTIVE, "layout is not bijective");
     const int nreg = L->bits_of(LL_IN_REG), nlane = L->bits_of(LL_IN_LANE);
-    if (nlane != LL_WAVE_LANE_BITS) return fail(LL_ERR_UNSUPPORTED, "gather needs %d lane bits (wave64), layout has %d", LL_WAVE_LANE_BITS, nlane);
-    const int nhigh = d - nreg - nlane;              // wave (and tile) bits of the layout
-    if (nhigh > 16) return fail(LL_ERR_UNSUPPORTED, "gather supports at most 16 wave + tile bits");
-    if (nreg > 6) return fail(LL_ERR_UNSUPPORTED, "gather supports at most 6 register bits (got %d)", nreg);
-
+    const int lane0 = L->first_bit_of(LL_IN_LANE), wave0 = L->first_bit_of(LL_IN_WAVE), tile0 = L->first_bit_of(LL_IN_TILE);
     int axis_shift = 0;
     for (int k = L->n_out - 1; k > axis; --k) axis_shift += L->out_dims[k].nbits;
     const int na = L->out_dims[axis].nbits;
-    const vec reg_mask = (vec(1) << nreg) - 1;
-    const vec lane_mask = vec(63) << nreg;
+    const vec all = (vec(1) << d) - 1;
+    const vec reg_mask = (vec(1) << lane0) - 1;
+    const vec lane_mask = ((vec(1) << wave0) - 1) & ~reg_mask;
+    const vec wave_mask = ((vec(1) << tile0) - 1) & ~(reg_mask | lane_mask);
+    const vec tile_mask = all & ~((vec(1) << tile0) - 1);
 
-    GatherArgs a;
-    std::memset(&a, 0, sizeof(a));
-    // Moving one step along axis bit b moves the hardware index by L^-1(e_b): it must stay inside
-    // the wave (Sec. 5.5: the warp part of the layout restricted to the axis vanishes).
-    for (int b = 0; b < na; ++b)
-        if (linv[axis_shift + b] & ~(reg_mask | lane_mask))
-            return fail(LL_ERR_AXIS_NOT_IN_WAVE, "axis bit %d crosses waves: the gather axis must lie inside one wave", b);
-    for (int b = 0; b < na; ++b) {
-        const vec delta = linv[axis_shift + b];
-        if (delta & reg_mask)
-            return fail(LL_ERR_UNSUPPORTED, "axis bit %d lives in registers; only lane-resident axes are implemented", b);
-        a.lane_delta[b] = (uint32_t)((delta & lane_mask) >> nreg);
-    }
-    if (na > 6) return fail(LL_ERR_AXIS_NOT_IN_WAVE, "axis of 2^%d elements cannot fit in 64 lanes", na);
+    // Moving one step along axis bit b moves the hardware index by L^-1(e_b) (Sec. 5.5: the source
+    // of an element is L^-1 of its position with the axis coordinate replaced).
+    vec touched = 0;
+    for (int b = 0; b < na; ++b) touched |= linv[axis_shift + b];
+    if (touched & tile_mask) return fail(LL_ERR_TILE_MIXED, "the gather axis crosses tiles");
+    c->axis_reg_bits = f2::popcount(touched & reg_mask);
+    c->axis_lane_bits = f2::popcount(touched & lane_mask);
+    c->axis_wave_bits = f2::popcount(touched & wave_mask);
     auto axis_coord = [&](vec h) { return (uint32_t)((f2::apply(L->bases, h) >> axis_shift) & ((vec(1) << na) - 1)); };
-    for (int b = 0; b < 6; ++b) a.own_lane[b] = axis_coord(vec(1) << (nreg + b));
-    for (int r = 0; r < (1 << nreg); ++r) a.own_reg[r] = axis_coord((vec)r);
-    for (int b = 0; b < nhigh; ++b) a.own_wave[b] = axis_coord(vec(1) << (nreg + 6 + b));
-    for (int b = 0; b < nreg; ++b) a.own_regbit[b] = axis_coord(vec(1) << b);
-    a.nwave = nhigh;
-    a.nreg = nreg;
-    a.axis_mask = (1u << na) - 1;
-    // fast form: the axis is a contiguous field of the lane index holding the coordinate itself
-    a.fast = 0;
-    if (na > 0) {
-        int shift = __builtin_ctz(a.lane_delta[0]);
-        bool ok = true;
-        for (int b = 0; b < na; ++b) ok &= a.lane_delta[b] == (1u << (shift + b));
-        for (int b = 0; b < 6; ++b) {
-            const uint32_t want = (b >= shift && b < shift + na) ? (1u << (b - shift)) : 0u;
-            ok &= a.own_lane[b] == want;
+
+    const char *force = getenv("LL_GATHER_GENERAL");
+    const bool lane_only = !(touched & ~lane_mask) && nlane == LL_WAVE_LANE_BITS && nreg <= 6 && d - nreg - nlane <= 16 &&
+                           na <= 6 && (1 << nreg) * elem_bytes >= 4 && (1 << nreg) * elem_bytes <= 256;
+    if (lane_only && !(force && atoi(force))) {
+        GatherArgs &a = c->wave;
+        std::memset(&a, 0, sizeof(a));
+        const int nhigh = d - nreg - nlane;
+        for (int b = 0; b < na; ++b) a.lane_delta[b] = (uint32_t)((linv[axis_shift + b] & lane_mask) >> nreg);
+        for (int b = 0; b < 6; ++b) a.own_lane[b] = axis_coord(vec(1) << (nreg + b));
+        for (int r = 0; r < (1 << nreg); ++r) a.own_reg[r] = axis_coord((vec)r);
+        for (int b = 0; b < nhigh; ++b) a.own_wave[b] = axis_coord(vec(1) << (nreg + 6 + b));
+        for (int b = 0; b < nreg; ++b) a.own_regbit[b] = axis_coord(vec(1) << b);
+        a.nwave = nhigh;
+        a.nreg = nreg;
+        a.axis_mask = (1u << na) - 1;
+        // fast form: the axis is a contiguous field of the lane index holding the coordinate itself
+        a.fast = 0;
+        if (na > 0) {
+            int shift = __builtin_ctz(a.lane_delta[0]);
+            bool ok = true;
+            for (int b = 0; b < na; ++b) ok &= a.lane_delta[b] == (1u << (shift + b));
+            for (int b = 0; b < 6; ++b) {
+                const uint32_t want = (b >= shift && b < shift + na) ? (1u << (b - shift)) : 0u;
+                ok &= a.own_lane[b] == want;
+            }
+            for (int r = 0; r < (1 << nreg); ++r) ok &= a.own_reg[r] == 0;
+            for (int b = 0; b < nhigh; ++b) ok &= a.own_wave[b] == 0;
+            if (ok) {
+                a.fast = 1;
+                a.shift = shift;
+                a.keep_mask = 63u & ~(a.axis_mask << shift);
+            }
         }
-        for (int r = 0; r < (1 << nreg); ++r) ok &= a.own_reg[r] == 0;
-        for (int b = 0; b < nhigh; ++b) ok &= a.own_wave[b] == 0;
-        if (ok) {
-            a.fast = 1;
-            a.shift = shift;
-            a.keep_mask = 63u & ~(a.axis_mask << shift);
-        }
+        // Rows of 16 bytes are already one coalesced vector per lane: shuffle directly.  Wider rows would
+        // make every lane's accesses strided, so they are staged through wave-private LDS instead.
+        const int row_bytes = (1 << nreg) * elem_bytes;
+        a.staged = (row_bytes > 16 && row_bytes <= 256 && nreg >= 2) ? 1 : 0;
+        if (const char *st = getenv("LL_GATHER_STAGED")) a.staged = atoi(st) && row_bytes >= 16 && row_bytes <= 256 && nreg >= 2;
+        c->kernel = a.staged ? LL_GATHER_WAVE_STAGED : LL_GATHER_SHUFFLE;
+        return LL_OK;
     }
+
+    // General case: the axis occupies register and / or wave bits (or the layout is not wave64
+    // shaped).  The smallest block closed under moves along the axis is the aligned range of
+    // 2^top image elements, top = highest hardware bit any axis step can flip; one workgroup stages
+    // it in LDS.  The paper's shuffle rounds (2^|register bits of the axis| per element) are
+    // replaced by one LDS read per element: a round needs a register index chosen per lane at run
+    // time, and ds_bpermute_b32 goes through the same LDS crossbar anyway.
+    const int vs = 31 - __builtin_clz(16u / (unsigned)elem_bytes);
+    const int top = touched ? 64 - __builtin_clzll((unsigned long long)touched) : 0;
+    int block_bits = std::max(std::max(top, vs + 8), 10);     // at least one 16-byte vector and one 4-element unit per thread
+    if (const char *bb = getenv("LL_GATHER_BLOCK_BYTES")) {        // experiment knob: larger blocks
+        int want = 31 - __builtin_clz((unsigned)std::max(1, atoi(bb) / elem_bytes));
+        block_bits = std::max(block_bits, want);
+    }
+    if (((long long)elem_bytes << block_bits) > 64 * 1024) {
+        if (touched & wave_mask)
+            return fail(LL_ERR_AXIS_NOT_IN_WAVE, "the gather axis crosses waves and the %lld bytes it spans do not fit in LDS",
+                        (long long)elem_bytes << top);
+        return fail(LL_ERR_UNSUPPORTED, "the gather axis spans %lld bytes per lane group, more than LDS can stage", (long long)elem_bytes << top);
+    }
+    if (na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", na);
+    GatherGenArgs &g = c->gen;
+    std::memset(&g, 0, sizeof(g));
+    g.block_bits = block_bits;
+    g.na = na;
+    g.axis_mask = (uint32_t)((vec(1) << na) - 1);
+    for (int b = 0; b < na; ++b) g.delta[b] = (uint32_t)linv[axis_shift + b];
+    for (int b = 0; b < d && b < 32; ++b) g.own_bit[b] = axis_coord(vec(1) << b);
+    // LDS swizzle: the bank field is address bits [ub, ub + 5); bring layout-lane bits into it
+    const int ub = elem_bytes == 8 ? 3 : 2;
+    const int rb = 31 - __builtin_clz((unsigned)((1 << nreg) * elem_bytes));
+    const int t = std::min(std::max(rb, ub), ub + 5);
+    const int nx = std::min(5, t - ub);
+    g.swz_shift = std::max(ub + 5, rb);
+    g.swz_to = ub;
+    g.swz_mask = (1u << nx) - 1;
+    c->kernel = LL_GATHER_BLOCK_STAGED;
+    return LL_OK;
+}
+
+ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gather_desc *out)
+{
+    GatherChoice c;
+    if (ll_status st = choose_gather(L, axis, elem_bytes, &c); st != LL_OK) return st;
+    std::memset(out, 0, sizeof(*out));
+    out->kernel = c.kernel;
+    out->axis_reg_bits = c.axis_reg_bits;
+    out->axis_lane_bits = c.axis_lane_bits;
+    out->axis_wave_bits = c.axis_wave_bits;
+    out->paper_rounds = 1 << c.axis_reg_bits;
+    out->block_bytes = c.kernel == LL_GATHER_BLOCK_STAGED ? (elem_bytes << c.gen.block_bits)
+                                                          : 64 * (1 << L->bits_of(LL_IN_REG)) * elem_bytes;
+    return LL_OK;
+}
+
+ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *in, const int32_t *idx, void *out,
+                     long long ntiles, void *stream)
+{
+    GatherChoice c;
+    if (ll_status st = choose_gather(L, axis, elem_bytes, &c); st != LL_OK) return st;
+    const int d = L->d_in;
     if (ntiles == 0) return LL_OK;
     if (!in || !idx || !out) return fail(LL_ERR_INVALID_ARG, "null device pointer");
     if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(out)) & 15)
@@ -134,15 +216,20 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
     const unsigned long long ibytes = ((unsigned long long)ntiles << d) * 4;
     if ((pi < po + bytes && po < pi + bytes) || (px < po + bytes && po < px + ibytes))
         return fail(LL_ERR_INVALID_ARG, "the output buffer overlaps an input buffer");
+    if (c.kernel == LL_GATHER_BLOCK_STAGED) {
+        GatherGenArgs &g = c.gen;
+        g.in = in;
+        g.idx = idx;
+        g.out = out;
+        g.total_elems = ntiles << d;
+        g.nblocks = (g.total_elems + (1ll << g.block_bits) - 1) >> g.block_bits;
+        return launch_gather_general(g, elem_bytes, stream);
+    }
+    GatherArgs &a = c.wave;
     a.in = in;
     a.idx = idx;
     a.out = out;
-    a.nchunks = ntiles << nhigh;
-    // Rows of 16 bytes are already one coalesced vector per lane: shuffle directly.  Wider rows would
-    // make every lane's accesses strided, so they are staged through wave-private LDS instead.
-    const int row_bytes = (1 << nreg) * elem_bytes;
-    a.staged = (row_bytes > 16 && row_bytes <= 256 && nreg >= 2) ? 1 : 0;
-    if (const char *force = getenv("LL_GATHER_STAGED")) a.staged = atoi(force) && row_bytes >= 16 && row_bytes <= 256 && nreg >= 2;
+    a.nchunks = ntiles << a.nwave;
     return launch_gather(a, elem_bytes, stream);
 }
 

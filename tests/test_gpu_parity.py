@@ -372,3 +372,74 @@ def test_convert_between_constructed_layouts():
             plan = ll.ll_plan_convert(x, y, w)
             src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=5 << 14, dtype=NP_DTYPES[w])
             assert np.array_equal(run_convert(plan, src, 14), oracle.convert(x.bases, y.bases, src)), (w, plan.info()["strategy_name"])
+
+
+# ---------------------------------------------------------------------------------------------
+# general gather: axis on register and wave bits, arbitrary XOR layouts (Sec. 5.5 extended)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("axis,ntiles", [(1, 1), (1, 3), (0, 2)])
+def test_gather_config5_any_axis(axis, ntiles, monkeypatch):
+    """Config 5's layout gathered along its columns (registers and waves: the workgroup-staged
+    kernel) and along its rows with that kernel forced."""
+    cfg = wl.config(5)
+    layout, _ = layouts_of(cfg)
+    if axis == 0:
+        monkeypatch.setenv("LL_GATHER_GENERAL", "1")
+    assert ll.ll_gather_info(layout, axis, cfg.elem_bytes)["kernel_name"] == "block_staged"
+    rng = np.random.default_rng(axis + 10 * ntiles)
+    inp = wl.to_numpy_bits(cfg.gen_data(0, ntiles))
+    idx = rng.integers(0, 1 << cfg.out_dim_bits[axis], size=ntiles << cfg.d, dtype=np.int32)
+    idx[::13] += 1 << cfg.out_dim_bits[axis]                      # wraps
+    got = run_gather(layout, axis, inp, idx, cfg.d)
+    want = oracle.gather(cfg.src_bases, cfg.out_dim_bits, axis, inp, idx)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+@pytest.mark.parametrize("d,dims", [(8, [3, 5]), (10, [4, 3, 3]), (12, [6, 6]), (13, [2, 11]), (7, [7]), (11, [5, 6])])
+def test_gather_random_xor_layouts_any_axis(w, d, dims):
+    """Random invertible layouts (columns are arbitrary XOR combinations): every axis, so that its
+    hardware bits fall on registers, lanes and waves alike; tiles smaller and larger than a block;
+    ragged tile counts."""
+    if (w << d) > 64 * 1024:
+        pytest.skip("tile larger than LDS")
+    rng = np.random.default_rng(4000 + 17 * w + d)
+    nreg = int(rng.integers(0, min(4, d - 2) + 1))
+    nlane = min(6, d - nreg)
+    nwave = d - nreg - nlane
+    for axis in range(len(dims)):
+        cols = random_invertible(rng, d)
+        layout = ll.distributed_layout(nreg, nlane, nwave, dims, cols)
+        try:
+            info = ll.ll_gather_info(layout, axis, w)
+        except ll.LLError as e:
+            assert e.status in (ll.LL_ERR_UNSUPPORTED, ll.LL_ERR_AXIS_NOT_IN_WAVE)
+            continue
+        ntiles = int(rng.integers(1, 70))
+        inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+        idx = rng.integers(0, 1 << dims[axis], size=ntiles << d, dtype=np.int32)
+        idx[::7] -= 1 << dims[axis]                                # negative entries wrap too
+        got = run_gather(layout, axis, inp, idx, d)
+        want = oracle.gather(cols, dims, axis, inp, idx)
+        assert np.array_equal(got, want), (axis, info)
+
+
+def test_gather_register_axis_and_identity_property():
+    """Axis entirely on register bits (the paper's n = 2^bits rounds): idx[i, j] = i gives the
+    input back; a constant index broadcasts one row."""
+    nreg, d = 3, 11
+    dims = [3, 8]
+    bases = [1 << (8 + k) for k in range(3)] + [1 << k for k in range(8)]      # registers walk the axis
+    layout = ll.distributed_layout(nreg, 6, 2, dims, bases)
+    assert ll.ll_gather_info(layout, 0, 4)["paper_rounds"] == 8
+    rng = np.random.default_rng(8)
+    ntiles = 9
+    inp = rng.integers(0, 1 << 32, size=ntiles << d, dtype=np.uint32)
+    h = np.arange(ntiles << d) & ((1 << d) - 1)
+    own = (h & 7).astype(np.int32)                                  # register index = axis coordinate
+    assert np.array_equal(run_gather(layout, 0, inp, own, d), inp)
+    const = np.full(ntiles << d, 5, dtype=np.int32)
+    got = run_gather(layout, 0, inp, const, d)
+    assert np.array_equal(got, oracle.gather(bases, dims, 0, inp, const))
+    assert np.array_equal(got.reshape(-1, 8), np.repeat(inp.reshape(-1, 8)[:, 5:6], 8, axis=1))

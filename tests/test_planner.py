@@ -283,16 +283,38 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     lay = ll.distributed_layout(g.nreg, g.nlane, g.nwave, g.out_dim_bits, g.src_bases)
     ll.ll_gather(lay, 0, 2, 0, 0, 0, 0, stream=0)                  # valid layout, nothing to move
     with pytest.raises(ll.LLError) as e:
-        ll.ll_gather(lay, 1, 2, 0, 0, 0, 0, stream=0)              # columns live in registers and waves
-    assert e.value.status == ll.LL_ERR_AXIS_NOT_IN_WAVE
-    with pytest.raises(ll.LLError) as e:
         ll.ll_gather(lay, 2, 2, 0, 0, 0, 0, stream=0)
     assert e.value.status == ll.LL_ERR_INVALID_ARG
-    # axis on register bits only: inside the wave, but not implemented
-    regaxis = ll.distributed_layout(2, 6, 0, [2, 6], [1 << 6, 1 << 7] + [1 << k for k in range(6)])
+    # an axis that crosses waves over more data than LDS can stage: the paper's legality condition
+    big = ll.distributed_layout(4, 6, 6, [6, 10], [1 << k for k in range(4)] + [1 << (10 + k) for k in range(6)] +
+                                [1 << (4 + k) for k in range(6)])
     with pytest.raises(ll.LLError) as e:
-        ll.ll_gather(regaxis, 0, 4, 0, 0, 0, 0, stream=0)
-    assert e.value.status == ll.LL_ERR_UNSUPPORTED
+        ll.ll_gather(big, 1, 4, 0, 0, 0, 0, stream=0)              # columns: registers and all 6 wave bits, 256 KiB
+    assert e.value.status == ll.LL_ERR_AXIS_NOT_IN_WAVE
+    assert ll.ll_gather_info(big, 0, 4)["kernel_name"] == "wave_staged"
+    # a tile label on the axis
+    tiled = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 6), (ll.LL_IN_TILE, 2)], [2, 8],
+                                [1 << k for k in range(10)])
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_gather(tiled, 0, 4, 0, 0, 0, 0, stream=0)
+    assert e.value.status == ll.LL_ERR_TILE_MIXED
+
+
+def test_gather_kernel_choice():
+    """Sec. 5.5: an axis on lane bits needs one round of shuffles; register bits on the axis mean
+    2^bits rounds in the paper and workgroup-LDS staging here; so do wave bits (when they fit)."""
+    g = wl.config(5)
+    lay = ll.distributed_layout(g.nreg, g.nlane, g.nwave, g.out_dim_bits, g.src_bases)
+    info = ll.ll_gather_info(lay, 0, 2)
+    assert (info["kernel_name"], info["axis_lane_bits"], info["axis_reg_bits"], info["paper_rounds"]) == ("wave_staged", 6, 0, 1)
+    info = ll.ll_gather_info(lay, 1, 2)                            # columns live in registers and waves
+    assert (info["kernel_name"], info["axis_reg_bits"], info["axis_wave_bits"], info["paper_rounds"]) == ("block_staged", 4, 4, 16)
+    assert info["block_bytes"] == 2 << 14
+    regaxis = ll.distributed_layout(2, 6, 0, [2, 6], [1 << 6, 1 << 7] + [1 << k for k in range(6)])
+    info = ll.ll_gather_info(regaxis, 0, 4)
+    assert (info["kernel_name"], info["axis_reg_bits"], info["paper_rounds"]) == ("block_staged", 2, 4)
+    narrow = ll.distributed_layout(0, 6, 2, [6, 2], [1 << (2 + k) for k in range(6)] + [1, 2])
+    assert ll.ll_gather_info(narrow, 0, 4)["kernel_name"] == "shuffle"
 
 
 def test_paper_shuffle_schedule_invariants():
