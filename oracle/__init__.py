@@ -69,6 +69,12 @@ def _load():
         lib.oracle_convert_table.argtypes = [u64p, u64p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                              ctypes.c_void_p, ctypes.c_int64,
                                              ctypes.POINTER(ctypes.c_int)]
+        lib.oracle_convert_affine.restype = ctypes.c_int
+        lib.oracle_convert_affine.argtypes = [u64p, ctypes.c_uint64, u64p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        lib.oracle_gather_affine.restype = ctypes.c_int
+        lib.oracle_gather_affine.argtypes = [u64p, ctypes.c_uint64, ctypes.c_int, i32p, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_int, ctypes.c_void_p, i32p, ctypes.c_void_p, ctypes.c_int64]
         lib.oracle_gather.restype = ctypes.c_int
         lib.oracle_gather.argtypes = [u64p, ctypes.c_int, i32p, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_int, ctypes.c_void_p, i32p, ctypes.c_void_p,
@@ -183,6 +189,39 @@ def gather(bases_l: Sequence[int], out_dim_bits: Sequence[int], axis: int,
                                out.ctypes.data, ntiles)
     if rc != OK:
         raise OracleError(rc, "gather")
+    return out
+
+
+def convert_affine(bases_a: Sequence[int], off_a: int, bases_b: Sequence[int], off_b: int,
+                   src: np.ndarray) -> np.ndarray:
+    """Image under h -> A h ^ off_a to image under h -> B h ^ off_b (both bijective on the same bits)."""
+    d = len(bases_a)
+    if len(bases_b) != d:
+        raise ValueError("A and B must have the same number of input bits")
+    _check_img(src, d, "src")
+    dst = np.empty_like(src)
+    rc = _load().oracle_convert_affine(_u64(bases_a), int(off_a), _u64(bases_b), int(off_b), d, src.itemsize,
+                                       src.ctypes.data, dst.ctypes.data, src.size >> d)
+    if rc != OK:
+        raise OracleError(rc, "convert_affine")
+    return dst
+
+
+def gather_affine(bases_l: Sequence[int], off: int, out_dim_bits: Sequence[int], axis: int,
+                  inp: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """Gather along `axis` with in, idx and out under the affine layout h -> L h ^ off."""
+    d = len(bases_l)
+    _check_img(inp, d, "in")
+    _check_img(idx, d, "idx")
+    if idx.dtype != np.int32 or idx.size != inp.size:
+        raise ValueError("idx must be int32 with as many elements as in")
+    out = np.empty_like(inp)
+    dims = (ctypes.c_int32 * len(out_dim_bits))(*[int(b) for b in out_dim_bits])
+    rc = _load().oracle_gather_affine(_u64(bases_l), int(off), d, dims, len(out_dim_bits), int(axis), inp.itemsize,
+                                      inp.ctypes.data, idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                      out.ctypes.data, inp.size >> d)
+    if rc != OK:
+        raise OracleError(rc, "gather_affine")
     return out
 
 

@@ -36,6 +36,8 @@
  *                           and tiles are processed by all host threads
  *   oracle_gather           Sec. 5.5: out[.., i, ..] = in[.., idx[.., i, ..], ..]
  *                           along `axis`, all three tensors under layout L
+ *   oracle_convert_affine,
+ *   oracle_gather_affine    Conclusions: affine layouts y = A x xor b (flips, slices)
  *   oracle_wavefronts       Sec. 5.4 "Optimal Swizzling" + the wavefront lemma
  *                           of the appendix: exhaustive enumeration of the
  *                           shared-memory (LDS) wavefronts an access needs
@@ -334,6 +336,111 @@ int oracle_gather(const uint64_t *basesL, int d, const int32_t *out_dim_bits,
     }
     free(invL);
     return ORACLE_OK;
+}
+
+/*
+ * Affine layouts (Conclusions: flips and slices are y = A x xor b).  An affine
+ * layout is a bijective linear layout A on d bits plus a constant b < 2^d:
+ * hardware index h holds the logical element A h xor b.
+ *
+ * Conversion between two affine layouts, by the definition on images: the
+ * element at source index h is the logical element x = A h xor a; it goes to
+ * the destination index h' with B h' xor b = x.  The inverse of the affine map
+ * of the destination is tabulated (table[B h' xor b] = h'), never solved for.
+ */
+int oracle_convert_affine(const uint64_t *basesA, uint64_t offA, const uint64_t *basesB, uint64_t offB,
+                          int d, int elem_bytes, const void *src, void *dst, int64_t ntiles)
+{
+    if (!basesA || !basesB || d < 0 || d > 30 || elem_bytes <= 0 || ntiles < 0)
+        return ORACLE_ERR_ARG;
+    if (ntiles > 0 && (!src || !dst))
+        return ORACLE_ERR_ARG;
+    const uint64_t n = 1ull << d;
+    if (offA >= n || offB >= n) return ORACLE_ERR_ARG;
+    uint32_t *where = (uint32_t *)malloc(n * sizeof(uint32_t));      /* logical x -> destination index */
+    unsigned char *seen = (unsigned char *)calloc(n, 1);
+    if (!where || !seen) { free(where); free(seen); return ORACLE_ERR_ALLOC; }
+    int rc = ORACLE_OK;
+    for (uint64_t h = 0; h < n; ++h) {
+        uint64_t x = oracle_apply(basesB, d, h) ^ offB;
+        if (x >= n || seen[x]) { rc = ORACLE_ERR_NOT_BIJECTIVE; break; }
+        seen[x] = 1;
+        where[x] = (uint32_t)h;
+    }
+    if (rc == ORACLE_OK) {
+        memset(seen, 0, n);
+        for (uint64_t h = 0; h < n; ++h) {                             /* A must be a bijection as well */
+            uint64_t x = oracle_apply(basesA, d, h) ^ offA;
+            if (x >= n || seen[x]) { rc = ORACLE_ERR_NOT_BIJECTIVE; break; }
+            seen[x] = 1;
+        }
+    }
+    if (rc == ORACLE_OK) {
+        const unsigned char *s = (const unsigned char *)src;
+        unsigned char *o = (unsigned char *)dst;
+        for (int64_t t = 0; t < ntiles; ++t)
+            for (uint64_t h = 0; h < n; ++h) {
+                uint64_t x = oracle_apply(basesA, d, h) ^ offA;
+                uint64_t to = where[x];
+                memcpy(o + ((uint64_t)t * n + to) * (uint64_t)elem_bytes,
+                       s + ((uint64_t)t * n + h) * (uint64_t)elem_bytes, (size_t)elem_bytes);
+            }
+    }
+    free(where);
+    free(seen);
+    return rc;
+}
+
+/*
+ * Gather along `axis` (Sec. 5.5) with all three tensors under the same affine
+ * layout h -> L h xor off: for every hardware index h the logical position is
+ * x = L h xor off; its axis coordinate is replaced by the index; the source is
+ * the hardware index that holds that logical position (tabulated).
+ */
+int oracle_gather_affine(const uint64_t *basesL, uint64_t off, int d, const int32_t *out_dim_bits,
+                         int n_out_dims, int axis, int elem_bytes, const void *in,
+                         const int32_t *idx, void *out, int64_t ntiles)
+{
+    if (!basesL || !out_dim_bits || d < 0 || d > 30 || elem_bytes <= 0 || ntiles < 0 || n_out_dims <= 0)
+        return ORACLE_ERR_ARG;
+    if (axis < 0 || axis >= n_out_dims) return ORACLE_ERR_AXIS;
+    if (ntiles > 0 && (!in || !idx || !out)) return ORACLE_ERR_ARG;
+    int total = 0, axis_shift = 0;
+    for (int k = n_out_dims - 1; k >= 0; --k) {
+        if (k == axis) axis_shift = total;
+        total += out_dim_bits[k];
+    }
+    if (total != d) return ORACLE_ERR_ARG;
+    const uint64_t n = 1ull << d;
+    if (off >= n) return ORACLE_ERR_ARG;
+    const uint64_t axis_len_mask = (1ull << out_dim_bits[axis]) - 1;
+    uint32_t *where = (uint32_t *)malloc(n * sizeof(uint32_t));
+    unsigned char *seen = (unsigned char *)calloc(n, 1);
+    if (!where || !seen) { free(where); free(seen); return ORACLE_ERR_ALLOC; }
+    int rc = ORACLE_OK;
+    for (uint64_t h = 0; h < n; ++h) {
+        uint64_t x = oracle_apply(basesL, d, h) ^ off;
+        if (x >= n || seen[x]) { rc = ORACLE_ERR_NOT_BIJECTIVE; break; }
+        seen[x] = 1;
+        where[x] = (uint32_t)h;
+    }
+    if (rc == ORACLE_OK) {
+        const unsigned char *pi = (const unsigned char *)in;
+        unsigned char *po = (unsigned char *)out;
+        for (int64_t t = 0; t < ntiles; ++t) {
+            const uint64_t base = (uint64_t)t * n;
+            for (uint64_t h = 0; h < n; ++h) {
+                uint64_t x = oracle_apply(basesL, d, h) ^ off;
+                uint64_t s = (uint64_t)(uint32_t)idx[base + h] & axis_len_mask;
+                uint64_t xs = (x & ~(axis_len_mask << axis_shift)) | (s << axis_shift);
+                memcpy(po + (base + h) * (uint64_t)elem_bytes,
+                       pi + (base + where[xs]) * (uint64_t)elem_bytes, (size_t)elem_bytes);
+            }
+        }
+    }
+    free(where);
+    free(seen);
+    return rc;
 }
 
 /*

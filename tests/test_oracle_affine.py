@@ -1,0 +1,106 @@
+"""Pins of the oracle's affine conversion and gather (Conclusions: flips and slices as
+y = A x xor b) to numpy's flip / roll / take_along_axis and to brute force."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+
+def unit(d):
+    return [1 << k for k in range(d)]
+
+
+def dim_mask(dims, j, bits=None):
+    """Flattened mask of logical dim j (all of its bits, or the given ones)."""
+    shift = sum(dims[j + 1:])
+    m = (1 << dims[j]) - 1 if bits is None else bits
+    return m << shift
+
+
+def test_zero_offsets_reduce_to_the_linear_oracle():
+    rng = np.random.default_rng(0)
+    d = 9
+    a, b = wl.random_invertible_bases(11, d), wl.random_invertible_bases(12, d)
+    src = rng.integers(0, 1 << 32, size=3 << d, dtype=np.uint32)
+    assert np.array_equal(oracle.convert_affine(a, 0, b, 0, src), oracle.convert(a, b, src))
+    dims = [4, 5]
+    idx = rng.integers(0, 16, size=3 << d, dtype=np.int32)
+    assert np.array_equal(oracle.gather_affine(a, 0, dims, 0, src, idx), oracle.gather(a, dims, 0, src, idx))
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_flip_and_half_roll_on_the_identity_layout(w):
+    """With the identity layout an image is the flattened tensor itself.  Converting to the same
+    layout with offset = all ones of a dim stores the tensor flipped along that dim; offset = the
+    top bit of a dim stores it rolled by half that dim."""
+    rng = np.random.default_rng(w)
+    dims = [3, 4, 2]
+    d = sum(dims)
+    shape = [1 << b for b in dims]
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[w]
+    src = rng.integers(0, np.iinfo(dt).max, size=5 << d, dtype=dt)
+    t = src.reshape([5] + shape)
+    for j in range(3):
+        got = oracle.convert_affine(unit(d), 0, unit(d), dim_mask(dims, j), src)
+        assert np.array_equal(got.reshape(t.shape), np.flip(t, axis=1 + j))
+        got = oracle.convert_affine(unit(d), 0, unit(d), dim_mask(dims, j, 1 << (dims[j] - 1)), src)
+        assert np.array_equal(got.reshape(t.shape), np.roll(t, shape[j] // 2, axis=1 + j))
+    # all dims flipped: the flattened tile reversed
+    got = oracle.convert_affine(unit(d), 0, unit(d), (1 << d) - 1, src)
+    assert np.array_equal(got.reshape(5, -1), src.reshape(5, -1)[:, ::-1])
+    # the offset on the source side undoes it
+    assert np.array_equal(oracle.convert_affine(unit(d), (1 << d) - 1, unit(d), 0, got), src)
+
+
+def test_flip_under_a_distributed_layout_is_a_flip_of_the_logical_tensor():
+    """Layout A of Sec. 4.1 (16 x 16): image under A -> image under (A, rows flipped); read back
+    through plain A, the logical tensor is flipped along the rows."""
+    a = wl.PAPER_LAYOUT_A
+    rng = np.random.default_rng(3)
+    logical = rng.integers(0, 1 << 16, size=256, dtype=np.uint16)
+    img = oracle.convert(unit(8), a, logical)                     # logical tensor -> image under A
+    flipped_img = oracle.convert_affine(a, 0, a, dim_mask([4, 4], 0), img)
+    back = oracle.convert(a, unit(8), flipped_img)                 # image under A -> logical tensor
+    assert np.array_equal(back.reshape(16, 16), np.flip(logical.reshape(16, 16), axis=0))
+
+
+def test_affine_conversion_brute_force_and_round_trip():
+    rng = np.random.default_rng(4)
+    for d in (3, 6, 8):
+        a, b = wl.random_invertible_bases(20 + d, d), wl.random_invertible_bases(30 + d, d)
+        oa, ob = int(rng.integers(0, 1 << d)), int(rng.integers(0, 1 << d))
+        src = rng.integers(0, 1 << 32, size=2 << d, dtype=np.uint32)
+        got = oracle.convert_affine(a, oa, b, ob, src)
+        want = np.empty_like(src)
+        for t in range(2):
+            for h in range(1 << d):
+                x = oracle.apply(a, h) ^ oa
+                hb = next(k for k in range(1 << d) if oracle.apply(b, k) ^ ob == x)
+                want[(t << d) + hb] = src[(t << d) + h]
+        assert np.array_equal(got, want)
+        assert np.array_equal(oracle.convert_affine(b, ob, a, oa, got), src)
+    with pytest.raises(oracle.OracleError):
+        oracle.convert_affine([1, 2, 3], 0, [1, 2, 4], 0, np.zeros(8, dtype=np.uint8))   # A singular
+
+
+def test_gather_under_a_flipped_layout_is_take_along_axis_on_the_logical_tensor():
+    """Identity layout with both dims flipped: image index h holds logical element ~h, so the
+    logical tensors are the reversed images; the gather itself is numpy's take_along_axis."""
+    rng = np.random.default_rng(5)
+    dims = [5, 4]
+    d = 9
+    off = (1 << d) - 1
+    nt = 3
+    inp = rng.integers(0, 1 << 32, size=nt << d, dtype=np.uint32)
+    for axis in (0, 1):
+        idx = rng.integers(0, 1 << dims[axis], size=nt << d, dtype=np.int32)
+        out = oracle.gather_affine(unit(d), off, dims, axis, inp, idx)
+        rev = lambda a: a.reshape(nt, -1)[:, ::-1].reshape(nt, 32, 16)
+        want_logical = np.take_along_axis(rev(inp), rev(idx).astype(np.int64), axis=1 + axis)
+        assert np.array_equal(rev(out), want_logical)
+    # flipping only the axis: idx[h] = own coordinate still returns the input
+    off_rows = dim_mask(dims, 0)
+    h = np.arange(nt << d) & ((1 << d) - 1)
+    own = (((h ^ off_rows) >> 4) & 31).astype(np.int32)
+    assert np.array_equal(oracle.gather_affine(unit(d), off_rows, dims, 0, inp, own), inp)
