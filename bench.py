@@ -266,6 +266,26 @@ def main() -> int:
         torch.cuda.empty_cache()
         result["gather_variants"] = gtable
 
+        # affine layouts (y = A x xor b): config 2 with the destination flipped along both dims (element
+        # positions inside every 16-byte vector reverse as well) and config 4 with an arbitrary constant
+        atable = []
+        for cid_, off_ in ((2, (1 << 14) - 1), (4, 0xB46B)):
+            cfg = wl.config(cid_)
+            a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+            b = ll.ll_layout_with_offset(ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases), off_)
+            plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+            inf = plan.info()
+            x = cfg.gen_data(0, cfg.ntiles, dev)
+            outs = [torch.empty_like(x) for _ in range(2 if cid_ == 2 else 1)]
+            _, _, md_ms, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % len(outs)], cfg.ntiles), args.table_steps, 3)
+            ab = cfg.algorithmic_bytes()
+            atable.append({"name": "config %d, destination offset 0x%x" % (cid_, off_), "kernel": inf["strategy_name"],
+                           "conv_offset": inf["conv_offset"], "algorithmic_bytes": ab, "us_median": round(md_ms * 1e3, 2),
+                           "GBps": round(ab / md_ms / 1e6, 1), "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)})
+            del x, outs
+            torch.cuda.empty_cache()
+        result["affine_conversions"] = atable
+
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(main_cfg)
 

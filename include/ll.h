@@ -159,6 +159,14 @@ ll_status ll_layout_mma_swizzle(int m_bits, int n_bits, int vec_elems, int per_p
 #define LL_LAYOUT_MEMORY 8u
 ll_status ll_layout_classify(const ll_layout *layout, uint32_t *flags);
 
+/* Affine layouts (Conclusions: flips and slices are y = A x xor b).  A copy of `layout` in which
+ * index h holds the logical element (A h) xor offset; offset < 2^(output bits).  For a dim of 2^n
+ * elements, offset = all ones of that dim flips it, offset = its top bit rolls it by half.
+ * ll_layout_apply, ll_compose and ll_invert carry the offset along; ll_plan_convert and ll_gather
+ * accept affine layouts when both are bijective; products and divisions do not (LL_ERR_UNSUPPORTED). */
+ll_status ll_layout_with_offset(const ll_layout *layout, uint64_t offset, ll_layout **out);
+ll_status ll_layout_get_offset(const ll_layout *layout, uint64_t *offset);
+
 /* Right inverse (Def. "Right Inverse") by Gaussian elimination over F2.  L must be surjective,
  * else LL_ERR_NOT_SURJECTIVE.  If L is not injective the free variables are set to zero, with
  * input columns taken as pivots in order (register bits first).  The result maps one `offset`
@@ -194,6 +202,7 @@ typedef struct {
     int32_t d_dst;              /* index bits of one destination tile (= d unless a layout broadcasts) */
     int32_t elem_bytes;
     uint64_t conv[LL_MAX_BITS]; /* columns of B^-1 o A on the d hardware-index bits (bijective layouts) */
+    uint64_t conv_offset;       /* affine layouts: destination index = conv * h xor conv_offset */
     uint64_t pull[LL_MAX_BITS]; /* broadcasting layouts: columns of A^+ o B, destination index -> source index */
     int32_t global_vec_bytes;   /* width of every global load and store */
     int32_t lds_write_bytes;    /* width of one LDS write (0 if LDS unused) */

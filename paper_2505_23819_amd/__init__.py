@@ -32,7 +32,7 @@ EXPORTED_SYMBOLS = [
     "ll_gather", "ll_copy", "ll_last_error", "ll_product_dimwise", "ll_divide_left",
     "ll_divide_left_permuted", "ll_contiguity", "ll_layout_identity", "ll_layout_blocked",
     "ll_layout_mfma_accumulator", "ll_layout_mfma_operand", "ll_layout_mma_swizzle", "ll_layout_classify",
-    "ll_gather_info",
+    "ll_gather_info", "ll_layout_with_offset", "ll_layout_get_offset",
 ]
 GATHER_KERNEL_NAMES = ["shuffle", "wave_staged", "block_staged"]
 
@@ -55,7 +55,8 @@ class ll_plan_desc(ctypes.Structure):
     _fields_ = [
         ("kind", ctypes.c_int32), ("strategy", ctypes.c_int32), ("d", ctypes.c_int32), ("d_dst", ctypes.c_int32),
         ("elem_bytes", ctypes.c_int32),
-        ("conv", ctypes.c_uint64 * LL_MAX_BITS), ("pull", ctypes.c_uint64 * LL_MAX_BITS),
+        ("conv", ctypes.c_uint64 * LL_MAX_BITS), ("conv_offset", ctypes.c_uint64),
+        ("pull", ctypes.c_uint64 * LL_MAX_BITS),
         ("global_vec_bytes", ctypes.c_int32), ("lds_write_bytes", ctypes.c_int32),
         ("lds_read_bytes", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
         ("threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
@@ -274,6 +275,17 @@ def ll_gather_info(layout: Layout, axis: int, elem_bytes: int) -> dict:
     out = {name: getattr(d, name) for name, _ in ll_gather_desc._fields_}
     out["kernel_name"] = GATHER_KERNEL_NAMES[d.kernel]
     return out
+
+
+def ll_layout_with_offset(layout: Layout, offset: int) -> Layout:
+    h = ctypes.c_void_p()
+    return _made(_lib.ll_layout_with_offset(layout._h, ctypes.c_uint64(int(offset)), ctypes.byref(h)), h)
+
+
+def ll_layout_get_offset(layout: Layout) -> int:
+    off = ctypes.c_uint64()
+    _check(_lib.ll_layout_get_offset(layout._h, ctypes.byref(off)))
+    return off.value
 
 
 def ll_layout_classify(layout: Layout) -> int:

@@ -86,6 +86,7 @@ ll_status check_pair(const ll_layout *layout, const ll_layout *tile, ll_layout *
     if (!layout || !tile) return ll::fail(LL_ERR_INVALID_ARG, "null layout");
     if (layout->n_out != tile->n_out)
         return ll::fail(LL_ERR_DIM_MISMATCH, "layout and tile have %d and %d logical dims", layout->n_out, tile->n_out);
+    if (layout->offset || tile->offset) return ll::fail(LL_ERR_UNSUPPORTED, "division of affine layouts is not implemented");
     for (int i = 0; i < tile->n_in; ++i)
         if (tile->in_dims[i].nbits > 0 && !has_label(layout, tile->in_dims[i].label))
             return ll::fail(LL_ERR_NOT_DIVISIBLE, "the layout has no input label %d", tile->in_dims[i].label);
@@ -102,6 +103,7 @@ ll_status ll_product_dimwise(const ll_layout *a, const ll_layout *b, ll_layout *
     *out = nullptr;
     if (!a || !b) return ll::fail(LL_ERR_INVALID_ARG, "null layout");
     if (a->n_out != b->n_out) return ll::fail(LL_ERR_DIM_MISMATCH, "factors have %d and %d logical dims", a->n_out, b->n_out);
+    if (a->offset || b->offset) return ll::fail(LL_ERR_UNSUPPORTED, "products of affine layouts are not implemented");
     if (a->d_in + b->d_in > LL_MAX_BITS || a->d_out + b->d_out > LL_MAX_BITS)
         return ll::fail(LL_ERR_INVALID_ARG, "product exceeds %d bits", LL_MAX_BITS);
     const int r = a->n_out;

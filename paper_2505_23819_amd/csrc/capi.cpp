@@ -107,7 +107,7 @@ ll_status ll_layout_apply(const ll_layout *layout, uint64_t in_index, uint64_t *
     if (!layout || !out_index) return fail(LL_ERR_INVALID_ARG, "null argument");
     if (layout->d_in < 64 && (in_index >> layout->d_in))
         return fail(LL_ERR_INVALID_ARG, "in_index 0x%llx does not fit in %d input bits", (unsigned long long)in_index, layout->d_in);
-    *out_index = f2::apply(layout->bases, in_index);
+    *out_index = f2::apply(layout->bases, in_index) ^ layout->offset;
     return LL_OK;
 }
 
@@ -118,8 +118,30 @@ ll_status ll_compose(const ll_layout *outer, const ll_layout *inner, ll_layout *
     if (!outer || !inner) return fail(LL_ERR_INVALID_ARG, "null layout");
     if (inner->d_out != outer->d_in)
         return fail(LL_ERR_DIM_MISMATCH, "inner maps to %d bits but outer takes %d bits", inner->d_out, outer->d_in);
-    return ll::make_layout(inner->in_dims, inner->n_in, outer->out_dims, outer->n_out,
-                           f2::compose(outer->bases, inner->bases), out);
+    ll_status st = ll::make_layout(inner->in_dims, inner->n_in, outer->out_dims, outer->n_out,
+                                   f2::compose(outer->bases, inner->bases), out);
+    // affine parts: outer(inner(h)) = A1 (A2 h ^ b2) ^ b1
+    if (st == LL_OK) (*out)->offset = f2::apply(outer->bases, inner->offset) ^ outer->offset;
+    return st;
+}
+
+ll_status ll_layout_with_offset(const ll_layout *layout, uint64_t offset, ll_layout **out)
+{
+    if (!out) return fail(LL_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (!layout) return fail(LL_ERR_INVALID_ARG, "layout is null");
+    if (layout->d_out < 64 && (offset >> layout->d_out))
+        return fail(LL_ERR_INVALID_ARG, "offset 0x%llx does not fit in %d output bits", (unsigned long long)offset, layout->d_out);
+    ll_status st = ll::make_layout(layout->in_dims, layout->n_in, layout->out_dims, layout->n_out, layout->bases, out);
+    if (st == LL_OK) (*out)->offset = offset;
+    return st;
+}
+
+ll_status ll_layout_get_offset(const ll_layout *layout, uint64_t *offset)
+{
+    if (!layout || !offset) return fail(LL_ERR_INVALID_ARG, "null argument");
+    *offset = layout->offset;
+    return LL_OK;
 }
 
 ll_status ll_product(const ll_layout *a, const ll_layout *b, ll_layout **out)
@@ -130,6 +152,7 @@ ll_status ll_product(const ll_layout *a, const ll_layout *b, ll_layout **out)
     if (a->d_in + b->d_in > LL_MAX_BITS || a->d_out + b->d_out > LL_MAX_BITS)
         return fail(LL_ERR_INVALID_ARG, "product exceeds %d bits", LL_MAX_BITS);
     if (a->n_out + b->n_out > LL_MAX_OUT_DIMS) return fail(LL_ERR_INVALID_ARG, "product has too many output dims");
+    if (a->offset || b->offset) return fail(LL_ERR_UNSUPPORTED, "products of affine layouts are not implemented");
     // merged input dims, label by label: bits of `a` first, then bits of `b`
     ll_in_dim dims[LL_MAX_IN_DIMS];
     int n = 0;
@@ -169,7 +192,10 @@ ll_status ll_invert(const ll_layout *layout, ll_layout **out)
                     layout->d_out);
     ll_in_dim in = {LL_IN_OFFSET, layout->d_out};
     ll_out_dim o = {layout->d_in};
-    return ll::make_layout(&in, 1, &o, 1, inv, out);
+    ll_status st = ll::make_layout(&in, 1, &o, 1, inv, out);
+    // h = X (x ^ b) = X x ^ X b
+    if (st == LL_OK) (*out)->offset = f2::apply(inv, layout->offset);
+    return st;
 }
 
 ll_status ll_plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan **out)

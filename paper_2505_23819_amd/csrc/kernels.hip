@@ -39,6 +39,39 @@ static __device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, uin
     __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, kStream);
 }
 
+// Affine conversions (y = A x xor b): the destination index of every element carries a constant
+// XOR c.  Its bits above the vector move whole vectors (an XOR on the store offset); its low bits
+// move elements inside the 16-byte vector: element e goes to position e ^ c_low.
+template <int W>
+static __device__ __forceinline__ void store_vec_xor(__amdgpu_buffer_rsrc_t r, uint32_t elem_off, u32x4 v, uint32_t c)
+{
+    constexpr uint32_t kPos = 16u / W - 1u;            // position bits inside a vector
+    const uint32_t cl = c & kPos;                       // wave uniform
+    if (cl) {
+        uint32_t d[4] = {v.x, v.y, v.z, v.w};
+        uint32_t dsel;                                  // dword-index bits of cl
+        if constexpr (W == 1) {
+            if (cl & 1u)
+                for (int k = 0; k < 4; ++k) d[k] = ((d[k] & 0x00FF00FFu) << 8) | ((d[k] >> 8) & 0x00FF00FFu);
+            if (cl & 2u)
+                for (int k = 0; k < 4; ++k) d[k] = (d[k] << 16) | (d[k] >> 16);
+            dsel = cl >> 2;
+        } else if constexpr (W == 2) {
+            if (cl & 1u)
+                for (int k = 0; k < 4; ++k) d[k] = (d[k] << 16) | (d[k] >> 16);
+            dsel = cl >> 1;
+        } else if constexpr (W == 4) {
+            dsel = cl;
+        } else {
+            dsel = cl << 1;
+        }
+        if (dsel & 1u) { uint32_t t = d[0]; d[0] = d[1]; d[1] = t; t = d[2]; d[2] = d[3]; d[3] = t; }
+        if (dsel & 2u) { uint32_t t = d[0]; d[0] = d[2]; d[2] = t; t = d[1]; d[1] = d[3]; d[3] = t; }
+        v.x = d[0]; v.y = d[1]; v.z = d[2]; v.w = d[3];
+    }
+    buf_store16(r, (elem_off ^ (c & ~kPos)) * W, v);
+}
+
 static unsigned env_inflight_bytes()
 {
     const char *v = getenv("LL_INFLIGHT_BYTES");     // experiment knob
@@ -216,7 +249,7 @@ __global__ __launch_bounds__(256) void k_lds_elem(const LdsElemArgs a)
     for (int i = 0; i < NV; ++i) {
         const uint32_t off = cd ^ ld ^ a.iter_dst[i];
         const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
-        buf_store16(drsrc, off * W, v);
+        store_vec_xor<W>(drsrc, off, v, a.dst_xor);
     }
 }
 
@@ -438,7 +471,7 @@ __global__ __launch_bounds__(256) void k_vec(const VecArgs a)
     for (int i = 0; i < NV; ++i) {
         const uint32_t off = cd ^ ld ^ a.iter_dst[i];
         const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
-        buf_store16(drsrc, off * W, v);
+        store_vec_xor<W>(drsrc, off, v, a.dst_xor);
     }
 }
 
@@ -688,7 +721,7 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a)
         idx[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(ix));
     }
 
-    uint32_t own_lw = 0;        // own axis coordinate: lane and wave contributions
+    uint32_t own_lw = a.own_const;        // own axis coordinate: lane and wave contributions
     if (!a.fast) {
 #pragma unroll
         for (int b = 0; b < 6; ++b) own_lw ^= a.own_lane[b] & (0u - ((lane >> b) & 1u));
@@ -812,7 +845,7 @@ __global__ __launch_bounds__(256) void k_gather_staged(const GatherArgs a)
     }
     __syncthreads();
 
-    uint32_t own_w = 0;
+    uint32_t own_w = a.own_const;
     if (!a.fast) {
         const uint32_t wv = (uint32_t)(chunk & ((1ll << a.nwave) - 1));
         for (int b = 0; b < a.nwave; ++b) own_w ^= a.own_wave[b] & (0u - ((wv >> b) & 1u));
@@ -991,7 +1024,7 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
     }
     // axis coordinate of an element = XOR of the contributions of the set bits of its hardware
     // index: the block's bits (uniform), this thread's bits, the pass's bits, the slot's bits
-    uint32_t own_t = 0;
+    uint32_t own_t = a.own_const;
     {
         const unsigned long long f = (unsigned long long)first;
         for (int b = a.block_bits; b < 32; ++b) own_t ^= a.own_bit[b] & (0u - (uint32_t)((f >> b) & 1ull));

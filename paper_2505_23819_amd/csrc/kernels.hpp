@@ -38,6 +38,7 @@ struct LdsElemArgs {
     uint32_t lds_wr_lane[kMaxThreadBits], lds_rd_lane[kMaxThreadBits];
     uint32_t lds_wr_iter[kMaxIter], lds_rd_iter[kMaxIter];
     uint32_t lds_wr_sub[kMaxSub], lds_rd_sub[kMaxSub];              // per sub-access of a vector
+    uint32_t dst_xor;   // affine conversions: constant XORed onto every destination element index
 };
 
 // Vector-preserving conversion: every thread keeps whole 16-byte vectors, optionally transposes
@@ -58,6 +59,7 @@ struct VecArgs {
     uint32_t stage_mask[5];       // per iteration bit: lane XOR mask of the butterfly stage (0 = none)
     uint32_t lds_wr_lane[kMaxThreadBits], lds_rd_lane[kMaxThreadBits];
     uint32_t lds_wr_iter[kMaxIter], lds_rd_iter[kMaxIter];
+    uint32_t dst_xor;   // affine conversions: constant XORed onto every destination element index
 };
 
 // Conversion between layouts with broadcasting (paper Sec. 5.1 "Broadcasting", Sec. 5.4 rule 2):
@@ -105,6 +107,7 @@ struct GatherArgs {
     uint32_t own_wave[16];    // per wave-index bit
     uint32_t own_regbit[6];   // per register bit (own_reg is linear: own_reg[r] = XOR of these)
     int nwave;
+    uint32_t own_const;       // affine layouts: constant part of every element's axis coordinate
     int staged;               // 1: coalesced global access with the source staged in wave-private LDS
 };
 
@@ -123,6 +126,7 @@ struct GatherGenArgs {
     uint32_t axis_mask;
     uint32_t delta[kMaxAxisBits];        // per axis bit: XOR on the block-local hardware index
     uint32_t own_bit[32];                // per hardware-index bit (0 above the tile): axis coordinate contribution
+    uint32_t own_const;                  // affine layouts: constant part of every element's axis coordinate
     int swz_shift, swz_to;               // LDS byte address ^= ((address >> swz_shift) & swz_mask) << swz_to
     uint32_t swz_mask;
 };

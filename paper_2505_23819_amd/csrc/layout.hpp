@@ -16,6 +16,7 @@ struct ll_layout {
     int d_in = 0;
     int d_out = 0;
     f2::mat bases;   // d_in columns, each a d_out-bit flattened output index
+    f2::vec offset = 0;   // affine part: index h holds logical element (bases h) xor offset
 
     int bits_of(int label) const
     {

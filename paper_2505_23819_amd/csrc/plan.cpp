@@ -503,6 +503,7 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     if (d < 1 || dst->d_in < 1) return fail(LL_ERR_INVALID_ARG, "empty layout");
     if (d > src->d_out || dst->d_in > dst->d_out) {
         // broadcasting (Sec. 5.1, Sec. 5.4 rule 2): destination units pull from canonical source units
+        if (src->offset || dst->offset) return fail(LL_ERR_UNSUPPORTED, "affine layouts with broadcasting are not implemented");
         std::memset(&plan->desc, 0, sizeof(plan->desc));
         plan->desc.elem_bytes = elem_bytes;
         return plan_pull(src, dst, elem_bytes, plan);
@@ -529,7 +530,19 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     for (int k = 0; k < d; ++k) desc.conv[k] = p[k];
     desc.kind = classify(p, d, src->bits_of(LL_IN_REG), src->first_bit_of(LL_IN_WAVE));
     paper_shuffle_schedule(src, dst, elem_bytes, &desc);
-    if (desc.kind == LL_KIND_NOOP) {
+    // Affine layouts: x = A h ^ a = B h' ^ b gives h' = P h ^ c with c = B^-1 (a ^ b).  The planners
+    // below work on P alone; c is a constant XOR on every destination index, which the kernels
+    // apply when they store (whole vectors move by its upper bits, elements inside a vector by
+    // its low bits), so it changes neither blocks, nor LDS layouts, nor exchanges.
+    const vec c = f2::apply(binv, src->offset ^ dst->offset);
+    if (c & (((vec(1) << d) - 1) & ~((vec(1) << tile_first) - 1)))
+        return fail(LL_ERR_TILE_MIXED, "the offsets of the layouts would move data between tiles");
+    desc.conv_offset = c;
+    struct Fold {                       // set the constant in whichever argument block the plan uses
+        ll_plan *plan; vec c;
+        ~Fold() { plan->lds_elem.dst_xor = (uint32_t)c; plan->vec.dst_xor = (uint32_t)c; }
+    } fold{plan, c};
+    if (desc.kind == LL_KIND_NOOP && c == 0) {
         desc.strategy = LL_STRATEGY_COPY;
         desc.global_vec_bytes = 16;
         desc.threads = 256;

@@ -102,6 +102,9 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     c->axis_lane_bits = f2::popcount(touched & lane_mask);
     c->axis_wave_bits = f2::popcount(touched & wave_mask);
     auto axis_coord = [&](vec h) { return (uint32_t)((f2::apply(L->bases, h) >> axis_shift) & ((vec(1) << na) - 1)); };
+    // affine layouts: every element's axis coordinate carries the axis part of the offset; the
+    // moves along the axis (differences) do not change
+    const uint32_t own_const = (uint32_t)((L->offset >> axis_shift) & ((vec(1) << na) - 1));
 
     const char *force = getenv("LL_GATHER_GENERAL");
     const bool lane_only = !(touched & ~lane_mask) && nlane == LL_WAVE_LANE_BITS && nreg <= 6 && d - nreg - nlane <= 16 &&
@@ -118,6 +121,7 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         a.nwave = nhigh;
         a.nreg = nreg;
         a.axis_mask = (1u << na) - 1;
+        a.own_const = own_const;
         // fast form: the axis is a contiguous field of the lane index holding the coordinate itself
         a.fast = 0;
         if (na > 0) {
@@ -130,6 +134,7 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
             }
             for (int r = 0; r < (1 << nreg); ++r) ok &= a.own_reg[r] == 0;
             for (int b = 0; b < nhigh; ++b) ok &= a.own_wave[b] == 0;
+            ok &= own_const == 0;
             if (ok) {
                 a.fast = 1;
                 a.shift = shift;
@@ -172,6 +177,7 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     g.axis_mask = (uint32_t)((vec(1) << na) - 1);
     for (int b = 0; b < na; ++b) g.delta[b] = (uint32_t)linv[axis_shift + b];
     for (int b = 0; b < d && b < 32; ++b) g.own_bit[b] = axis_coord(vec(1) << b);
+    g.own_const = own_const;
     // LDS swizzle: the bank field is address bits [ub, ub + 5); bring layout-lane bits into it
     const int ub = elem_bytes == 8 ? 3 : 2;
     const int rb = 31 - __builtin_clz((unsigned)((1 << nreg) * elem_bytes));

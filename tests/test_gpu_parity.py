@@ -443,3 +443,74 @@ def test_gather_register_axis_and_identity_property():
     got = run_gather(layout, 0, inp, const, d)
     assert np.array_equal(got, oracle.gather(bases, dims, 0, inp, const))
     assert np.array_equal(got.reshape(-1, 8), np.repeat(inp.reshape(-1, 8)[:, 5:6], 8, axis=1))
+
+
+# ---------------------------------------------------------------------------------------------
+# affine layouts y = A x xor b: flips, half rolls, arbitrary constants (Conclusions)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_convert_configs_with_flips(cid):
+    """Each configuration with its destination flipped along the rows, along both dims, and with
+    an arbitrary constant on both sides (element positions inside the 16-byte vectors move too)."""
+    cfg = wl.config(cid)
+    a, b = layouts_of(cfg)
+    dims = cfg.out_dim_bits
+    rows = ((1 << dims[0]) - 1) << (cfg.d - dims[0])
+    rng = np.random.default_rng(70 + cid)
+    src = wl.to_numpy_bits(cfg.gen_data(0, 3))
+    for oa, ob in ((0, rows), (0, (1 << cfg.d) - 1), (int(rng.integers(1, 1 << cfg.d)), int(rng.integers(1, 1 << cfg.d)))):
+        plan = ll.ll_plan_convert(ll.ll_layout_with_offset(a, oa), ll.ll_layout_with_offset(b, ob), cfg.elem_bytes)
+        got = run_convert(plan, src, cfg.d)
+        want = oracle.convert_affine(cfg.src_bases, oa, cfg.dst_bases, ob, src)
+        assert np.array_equal(got, want), (cid, oa, ob, plan.info()["strategy_name"])
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_convert_random_affine_layouts(w, monkeypatch):
+    rng = np.random.default_rng(900 + w)
+    for d, nreg in [(9, 3), (12, 4), (14, 6)]:
+        for trial in range(6):
+            if trial % 3 == 0:       # same layout, offsets only: a pure XOR shuffle of the image
+                ca = cb = [1 << int(p) for p in rng.permutation(d)]
+            elif trial % 3 == 1:
+                ca, cb = [1 << int(p) for p in rng.permutation(d)], [1 << int(p) for p in rng.permutation(d)]
+            else:
+                ca, cb = random_invertible(rng, d), random_invertible(rng, d)
+            oa, ob = int(rng.integers(0, 1 << d)), int(rng.integers(0, 1 << d))
+            if trial == 5:
+                monkeypatch.setenv("LL_FORCE_STRATEGY", "3")
+            a = ll.ll_layout_with_offset(ll.distributed_layout(nreg, 6, d - nreg - 6, [d], ca), oa)
+            b = ll.ll_layout_with_offset(ll.distributed_layout(nreg, 6, d - nreg - 6, [d], cb), ob)
+            plan = ll.ll_plan_convert(a, b, w)
+            monkeypatch.delenv("LL_FORCE_STRATEGY", raising=False)
+            ntiles = int(rng.integers(1, 20))
+            src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+            got = run_convert(plan, src, d)
+            assert np.array_equal(got, oracle.convert_affine(ca, oa, cb, ob, src)), (d, trial, plan.info()["strategy_name"])
+
+
+def test_flip_of_the_identity_layout_is_numpy_flip():
+    d, dims = 13, [6, 7]
+    ident = ll.distributed_layout(3, 6, 4, dims, [1 << k for k in range(d)])
+    flipped = ll.ll_layout_with_offset(ident, ((1 << 6) - 1) << 7)          # rows reversed
+    plan = ll.ll_plan_convert(ident, flipped, 2)
+    src = np.random.default_rng(1).integers(0, 1 << 16, size=4 << d, dtype=np.uint16)
+    got = run_convert(plan, src, d)
+    assert np.array_equal(got.reshape(4, 64, 128), np.flip(src.reshape(4, 64, 128), axis=1))
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+def test_gather_under_affine_layouts(axis, monkeypatch):
+    cfg = wl.config(5)
+    base, _ = layouts_of(cfg)
+    rng = np.random.default_rng(40 + axis)
+    ntiles = 3
+    inp = wl.to_numpy_bits(cfg.gen_data(0, ntiles))
+    idx = rng.integers(0, 1 << cfg.out_dim_bits[axis], size=ntiles << cfg.d, dtype=np.int32)
+    for off in ((1 << cfg.d) - 1, int(rng.integers(1, 1 << cfg.d))):
+        layout = ll.ll_layout_with_offset(base, off)
+        for staged in ("0", "1"):
+            monkeypatch.setenv("LL_GATHER_STAGED", staged)
+            got = run_gather(layout, axis, inp, idx, cfg.d)
+            assert np.array_equal(got, oracle.gather_affine(cfg.src_bases, off, cfg.out_dim_bits, axis, inp, idx)), (off, staged)

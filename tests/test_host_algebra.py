@@ -331,3 +331,50 @@ def test_classify_matches_the_oracle_definitions():
         assert bool(flags & ll.LL_LAYOUT_MEMORY) == oracle.is_memory_layout(o), cols
         seen.add(flags)
     assert len(seen) >= 5                                        # the cases really differ
+
+
+# ---- affine layouts y = A x xor b (Conclusions)
+
+def test_affine_layout_apply_compose_invert():
+    rng = np.random.default_rng(31)
+    d = 8
+    cols = random_invertible(rng, d)
+    off = int(rng.integers(1, 1 << d))
+    lay = ll.ll_layout_with_offset(_mk([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 6)], [4, 4], cols), off)
+    assert ll.ll_layout_get_offset(lay) == off
+    for h in range(1 << d):
+        assert lay.apply(h) == oracle.apply(cols, h) ^ off
+    inv = ll.ll_invert(lay)
+    for h in range(1 << d):
+        assert inv.apply(lay.apply(h)) == h
+    # composition carries the offsets: outer(inner(h))
+    cols2, off2 = random_invertible(rng, d), int(rng.integers(1, 1 << d))
+    outer = ll.ll_layout_with_offset(_mk([(ll.LL_IN_OFFSET, d)], [d], cols2), off2)
+    both = ll.ll_compose(outer, lay)
+    for h in range(1 << d):
+        assert both.apply(h) == outer.apply(lay.apply(h))
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_layout_with_offset(lay, 1 << d)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_product_dimwise(lay, lay)
+    assert e.value.status == ll.LL_ERR_UNSUPPORTED
+
+
+def test_affine_plan_reports_the_constant():
+    """h' = P h xor c with c = B^-1 (a xor b): compare with the oracle on a few indices."""
+    rng = np.random.default_rng(32)
+    d = 10
+    ca, cb = random_invertible(rng, d), random_invertible(rng, d)
+    oa, ob = int(rng.integers(0, 1 << d)), int(rng.integers(0, 1 << d))
+    a = ll.ll_layout_with_offset(ll.distributed_layout(2, 6, 2, [d], ca), oa)
+    b = ll.ll_layout_with_offset(ll.distributed_layout(2, 6, 2, [d], cb), ob)
+    info = ll.ll_plan_convert(a, b, 4).info()
+    src = np.arange(1 << d, dtype=np.uint32)
+    want = oracle.convert_affine(ca, oa, cb, ob, src)                # want[h'] = h
+    for h in rng.integers(0, 1 << d, size=50):
+        hp = info["conv_offset"]
+        for k in range(d):
+            if (int(h) >> k) & 1:
+                hp ^= info["conv"][k]
+        assert want[hp] == h
