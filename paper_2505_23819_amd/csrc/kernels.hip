@@ -407,6 +407,9 @@ static __device__ __forceinline__ void shuffle_stages(uint32_t (&r)[NV][4], uint
     if constexpr (NVB > 4) { if (a.stage_mask[4]) shuffle_stage<NV, 4>(r, lane, a.stage_mask[4]); }
 }
 
+// A workgroup takes a.pipe consecutive blocks.  Without LDS exchange the blocks are software
+// pipelined: the loads of the next block are issued before the current block is transposed,
+// exchanged and stored, so that a wave always has loads in flight.
 template <int W, int NVB, int TPOSE, int XCHG>
 __global__ __launch_bounds__(256) void k_vec(const VecArgs a)
 {
@@ -425,53 +428,91 @@ __global__ __launch_bounds__(256) void k_vec(const VecArgs a)
             lr ^= a.lds_rd_lane[b] & m;
         }
     }
-    const long long blk = blockIdx.x;
-    const long long group = blk >> a.coset_bits;
-    const uint32_t c = (uint32_t)(blk & ((1ll << a.coset_bits) - 1));
-    uint32_t cs = 0, cd = 0, cr = 0;
-    for (int b = 0; b < a.coset_bits; ++b) {
-        const uint32_t m = 0u - ((c >> b) & 1u);
-        cs ^= a.coset_src[b] & m;
-        cd ^= a.coset_dst[b] & m;
-        cr ^= a.coset_lds_rd[b] & m;
-    }
-    const int gshift = a.d + a.group_bits;
-    const unsigned char *sbase = static_cast<const unsigned char *>(a.src) + (((size_t)group << gshift) * W);
-    unsigned char *dbase = static_cast<unsigned char *>(a.dst) + (((size_t)group << gshift) * W);
-    const long long left = a.ntiles - (group << a.group_bits);
-    const uint32_t tiles_here = left > (1ll << a.group_bits) ? (1u << a.group_bits) : (uint32_t)left;
-    const uint32_t valid_bytes = (tiles_here << a.d) * W;
-    const __amdgpu_buffer_rsrc_t srsrc = make_rsrc(sbase, valid_bytes);
-    const __amdgpu_buffer_rsrc_t drsrc = make_rsrc(dbase, valid_bytes);
-
-    uint32_t r[NV][4];
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const uint32_t off = cs ^ ls ^ a.iter_src[i];
-        const u32x4 v = buf_load16(srsrc, off * W);
-        r[i][0] = v.x; r[i][1] = v.y; r[i][2] = v.z; r[i][3] = v.w;
-    }
-    if constexpr (TPOSE == kTposeBefore) transpose_regs<W, NV>(r);
-    if constexpr (XCHG == kXchgShuffle) shuffle_stages<NV, NVB>(r, tid & 63, a);
-    if constexpr (XCHG == kXchgLds) {
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
-            *reinterpret_cast<u32x4 *>(lds + (lw ^ a.lds_wr_iter[i])) = v;
+    struct Ctx {
+        uint32_t cs, cd, cr;
+        __amdgpu_buffer_rsrc_t srsrc, drsrc;
+    };
+    auto context = [&](long long blk) {
+        Ctx x;
+        const long long group = blk >> a.coset_bits;
+        const uint32_t c = (uint32_t)(blk & ((1ll << a.coset_bits) - 1));
+        x.cs = 0; x.cd = 0; x.cr = 0;
+        for (int b = 0; b < a.coset_bits; ++b) {
+            const uint32_t m = 0u - ((c >> b) & 1u);
+            x.cs ^= a.coset_src[b] & m;
+            x.cd ^= a.coset_dst[b] & m;
+            x.cr ^= a.coset_lds_rd[b] & m;
         }
-        __syncthreads();
+        const int gshift = a.d + a.group_bits;
+        const unsigned char *sbase = static_cast<const unsigned char *>(a.src) + (((size_t)group << gshift) * W);
+        unsigned char *dbase = static_cast<unsigned char *>(a.dst) + (((size_t)group << gshift) * W);
+        const long long left = a.ntiles - (group << a.group_bits);
+        const uint32_t tiles_here = left > (1ll << a.group_bits) ? (1u << a.group_bits) : (uint32_t)left;
+        const uint32_t valid_bytes = (tiles_here << a.d) * W;
+        x.srsrc = make_rsrc(sbase, valid_bytes);
+        x.drsrc = make_rsrc(dbase, valid_bytes);
+        return x;
+    };
+    auto load = [&](const Ctx &x, uint32_t (&r)[NV][4]) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + (cr ^ lr ^ a.lds_rd_iter[i]));
+            const uint32_t off = x.cs ^ ls ^ a.iter_src[i];
+            const u32x4 v = buf_load16(x.srsrc, off * W);
             r[i][0] = v.x; r[i][1] = v.y; r[i][2] = v.z; r[i][3] = v.w;
         }
-    }
-    if constexpr (TPOSE == kTposeAfter) transpose_regs<W, NV>(r);
+    };
+    auto finish = [&](const Ctx &x, uint32_t (&r)[NV][4]) {
+        if constexpr (TPOSE == kTposeBefore) transpose_regs<W, NV>(r);
+        if constexpr (XCHG == kXchgShuffle) shuffle_stages<NV, NVB>(r, tid & 63, a);
+        if constexpr (XCHG == kXchgLds) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const uint32_t off = cd ^ ld ^ a.iter_dst[i];
-        const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
-        store_vec_xor<W>(drsrc, off, v, a.dst_xor);
+            for (int i = 0; i < NV; ++i) {
+                const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
+                *reinterpret_cast<u32x4 *>(lds + (lw ^ a.lds_wr_iter[i])) = v;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + (x.cr ^ lr ^ a.lds_rd_iter[i]));
+                r[i][0] = v.x; r[i][1] = v.y; r[i][2] = v.z; r[i][3] = v.w;
+            }
+        }
+        if constexpr (TPOSE == kTposeAfter) transpose_regs<W, NV>(r);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const uint32_t off = x.cd ^ ld ^ a.iter_dst[i];
+            const u32x4 v = {r[i][0], r[i][1], r[i][2], r[i][3]};
+            store_vec_xor<W>(x.drsrc, off, v, a.dst_xor);
+        }
+    };
+
+    if constexpr (XCHG == kXchgLds) {
+        // one block per workgroup (the LDS block is reused without a second barrier otherwise)
+        const Ctx x = context((long long)blockIdx.x);
+        uint32_t r[NV][4];
+        load(x, r);
+        finish(x, r);
+    } else {
+        const long long first = (long long)blockIdx.x * a.pipe;
+        const long long remaining = a.nblocks - first;
+        const int nb = remaining < a.pipe ? (int)remaining : a.pipe;      // >= 1 by the grid size
+        uint32_t ra[NV][4], rb[NV][4];
+        Ctx xa = context(first), xb = xa;
+        load(xa, ra);
+        for (int j = 0; j < nb; j += 2) {
+            const bool has_b = j + 1 < nb;
+            if (has_b) {
+                xb = context(first + j + 1);
+                load(xb, rb);
+            }
+            finish(xa, ra);
+            if (!has_b) break;
+            if (j + 2 < nb) {
+                xa = context(first + j + 2);
+                load(xa, ra);
+            }
+            finish(xb, rb);
+        }
     }
 }
 
@@ -486,13 +527,17 @@ static ll_status launch_vec_t(const VecArgs &a, int threads, int lds_bytes, hipS
         // loses bandwidth beyond that, so workgroups are kept to (in-flight budget / block bytes) per
         // CU by asking for a matching share of the 160 KiB LDS.
         static const unsigned budget = env_inflight_bytes();
-        const unsigned block_bytes = (unsigned)threads * (16u << NVB);
+        static const int pipe_env = getenv("LL_VEC_PIPE") ? atoi(getenv("LL_VEC_PIPE")) : 1;   // experiment knob
+        VecArgs b = a;
+        b.pipe = (XCHG == kXchgLds || pipe_env < 1) ? 1 : (pipe_env > 64 ? 64 : pipe_env);
+        const unsigned block_bytes = (unsigned)threads * (16u << NVB) * (b.pipe > 1 ? 2u : 1u);
         const unsigned per_cu = budget / block_bytes > 1 ? budget / block_bytes : 1;
         unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
         if (alloc > 64u * 1024u) alloc = 64u * 1024u;
         if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
-        hipLaunchKernelGGL((k_vec<W, NVB, TPOSE, XCHG>), dim3((unsigned)a.nblocks), dim3((unsigned)threads),
-                           (size_t)alloc, stream, a);
+        const long long grid = (a.nblocks + b.pipe - 1) / b.pipe;
+        hipLaunchKernelGGL((k_vec<W, NVB, TPOSE, XCHG>), dim3((unsigned)grid), dim3((unsigned)threads),
+                           (size_t)alloc, stream, b);
         return check_launch("vector conversion kernel launch");
     }
 }
