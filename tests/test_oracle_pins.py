@@ -540,3 +540,24 @@ def test_convert_general_paper_broadcast_example(golden_dir):
         assert wide[h] == src[(reg & 3) | (rest << 2)]                    # registers 4-7 alias 0-3
     back = oracle.convert_general(widened, a, 8, wide)
     assert np.array_equal(back, src)
+
+
+def test_convert_spot_values_of_the_configurations():
+    """tests/golden/config_spot_values.txt: hand-derived (source index, destination index) pairs of
+    configs 1-3 and the image of every source bit of config 1."""
+    rows = [l.split() for l in open("tests/golden/config_spot_values.txt") if l.strip() and not l.startswith("#")]
+    images = {}
+    for cid in (1, 2, 3):
+        cfg = wl.config(cid)
+        images[cid] = oracle.convert(cfg.src_bases, cfg.dst_bases, np.arange(1 << cfg.d, dtype=np.uint32))
+        assert int(images[cid][0]) == 0 and int(images[cid][-1]) == (1 << cfg.d) - 1
+    seen = 0
+    for r in rows:
+        if r[0] == "P":
+            for k, col in enumerate(r[1:]):
+                assert int(images[1][int(col, 16)]) == 1 << k
+            assert len(r) == 13
+        else:
+            assert int(images[int(r[0])][int(r[2], 16)]) == int(r[1], 16), r
+            seen += 1
+    assert seen == 12

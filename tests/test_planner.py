@@ -358,3 +358,10 @@ def test_paper_shuffle_schedule_invariants():
                         for xs in per_lane.values():
                             assert len(xs) == 1 << len(V)                     # exactly one vectorized element
                             assert {x ^ xs[0] for x in xs} == span(V)
+
+
+def test_plan_of_config1_reports_the_hand_derived_conversion_matrix():
+    """The columns of B^-1 o A for config 1, as derived by hand in tests/golden/config_spot_values.txt."""
+    row = [l.split() for l in open("tests/golden/config_spot_values.txt") if l.startswith("P")][0]
+    info = plan_of(wl.config(1)).info()
+    assert info["conv"] == [int(x, 16) for x in row[1:]]
