@@ -258,8 +258,10 @@ ll_status ll_plan_destroy(ll_plan *plan);
 
 /* Apply a plan: dst_dev[t * 2^d + (B^-1 o A)(h)] = src_dev[t * 2^d + h] for every tile t < ntiles
  * and every h (Sec. 5.4); for broadcasting plans dst_dev[t * 2^d_dst + hB] =
- * src_dev[t * 2^d + (A^+ o B)(hB)].  Pointers are DEVICE pointers.  Asynchronous on hip_stream.
- * ntiles == 0 is a no-op. */
+ * src_dev[t * 2^d + (A^+ o B)(hB)].  Pointers are DEVICE pointers, 16-byte aligned, not
+ * overlapping; both buffers must hold a whole number of 16-byte vectors (only tiles smaller than
+ * 16 bytes can violate that: pass a multiple of 16 / tile bytes tiles).  Asynchronous on
+ * hip_stream.  ntiles == 0 is a no-op.  Errors in the arguments are reported before any launch. */
 ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, int64_t ntiles, void *hip_stream);
 
 /* ---- gather (paper Sec. 5.5) ----------------------------------------------------------- */

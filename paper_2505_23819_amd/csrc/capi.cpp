@@ -240,6 +240,9 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
     if (ntiles > (1ll << 40) >> dmax) return fail(LL_ERR_INVALID_ARG, "ntiles is too large");
     const unsigned long long sbytes = (unsigned long long)ntiles * plan->desc.elem_bytes << plan->desc.d;
     const unsigned long long dbytes = (unsigned long long)ntiles * plan->desc.elem_bytes << plan->desc.d_dst;
+    // every access is a 16-byte vector: tiles smaller than that must come in whole vectors
+    if ((sbytes | dbytes) & 15)
+        return fail(LL_ERR_INVALID_ARG, "ntiles * tile bytes (%llu source, %llu destination) must be a multiple of 16", sbytes, dbytes);
     const char *s = static_cast<const char *>(src_dev), *t = static_cast<const char *>(dst_dev);
     if (s < t + dbytes && t < s + sbytes) return fail(LL_ERR_INVALID_ARG, "source and destination buffers overlap");
     return ll::run_convert(plan, src_dev, dst_dev, ntiles, hip_stream);

@@ -217,6 +217,7 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
         return fail(LL_ERR_INVALID_ARG, "device buffers must be 16-byte aligned");
     const unsigned long long bytes = ((unsigned long long)ntiles << d) * elem_bytes;
     if (ntiles > (1ll << 40) >> d) return fail(LL_ERR_INVALID_ARG, "ntiles is too large");
+    if (bytes & 15) return fail(LL_ERR_INVALID_ARG, "ntiles * tile bytes (%llu) must be a multiple of 16", bytes);
     const char *pi = static_cast<const char *>(in), *po = static_cast<const char *>(out);
     const char *px = reinterpret_cast<const char *>(idx);
     const unsigned long long ibytes = ((unsigned long long)ntiles << d) * 4;

@@ -514,3 +514,51 @@ def test_gather_under_affine_layouts(axis, monkeypatch):
             monkeypatch.setenv("LL_GATHER_STAGED", staged)
             got = run_gather(layout, axis, inp, idx, cfg.d)
             assert np.array_equal(got, oracle.gather_affine(cfg.src_bases, off, cfg.out_dim_bits, axis, inp, idx)), (off, staged)
+
+
+# ---------------------------------------------------------------------------------------------
+# extreme sizes
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_convert_tiny_tiles_are_bundled(w):
+    """Tiles of 2 .. 128 elements (down to 2 bytes): many tiles share one workgroup block; ragged
+    tile counts leave the last block partly empty."""
+    rng = np.random.default_rng(300 + w)
+    for d in range(1, 8):
+        nreg = min(2, d)
+        dims = [(ll.LL_IN_REG, nreg)] + ([(ll.LL_IN_LANE, d - nreg)] if d > nreg else [])
+        ca, cb = random_invertible(rng, d), random_invertible(rng, d)
+        plan = ll.ll_plan_convert(ll.ll_layout_create(dims, [d], ca), ll.ll_layout_create(dims, [d], cb), w)
+        per16 = max(1, 16 // (w << d))            # tiles per 16-byte vector: buffers hold whole vectors
+        for ntiles in (per16, 5 * per16, (1000 + int(rng.integers(0, 2000))) * per16):
+            src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+            assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src)), (d, ntiles)
+
+
+def test_convert_one_large_tile():
+    """A single tile of 2^25 four-byte elements (128 MiB, 65536 blocks of one tile)."""
+    d = 25
+    rng = np.random.default_rng(26)
+    ca = [1 << int(p) for p in rng.permutation(d)]
+    cb = [1 << int(p) for p in rng.permutation(d)]
+    a = ll.distributed_layout(6, 6, d - 12, [d], ca)
+    b = ll.distributed_layout(6, 6, d - 12, [d], cb)
+    plan = ll.ll_plan_convert(a, b, 4)
+    src = torch.randint(-2**31, 2**31 - 1, (1 << d,), dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    ll.ll_convert(plan, src, dst, 1)
+    torch.cuda.synchronize()
+    # sampled elements: destination index of h is the bit permutation cb^-1(ca(h))
+    pos_b = {c: k for k, c in enumerate(cb)}
+    hs = rng.integers(0, 1 << d, size=4096)
+    hs[:2] = (0, (1 << d) - 1)
+    to = np.zeros_like(hs)
+    for k in range(d):
+        to |= ((hs >> k) & 1) << pos_b[ca[k]]
+    got = dst[torch.from_numpy(to).cuda()].cpu().numpy()
+    want = src[torch.from_numpy(hs).cuda()].cpu().numpy()
+    assert np.array_equal(got, want)
+    # and the whole tile against the oracle's tabulated variant
+    full, _ = oracle.convert(ca, cb, src.cpu().numpy().view(np.uint32), table=True)
+    assert np.array_equal(dst.cpu().numpy().view(np.uint32), full)

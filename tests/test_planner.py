@@ -278,6 +278,11 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
         ll.ll_convert(plan, 4096, 1 << 20, -1, stream=0)
     assert e.value.status == ll.LL_ERR_INVALID_ARG
     ll.ll_convert(plan, 0, 0, 0, stream=0)                         # ntiles == 0: no-op
+    tiny = ll.ll_plan_convert(ll.ll_layout_create([(ll.LL_IN_REG, 2)], [2], [2, 1]),
+                              ll.ll_layout_create([(ll.LL_IN_REG, 2)], [2], [1, 2]), 1)
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_convert(tiny, 4096, 1 << 20, 3, stream=0)            # 12 bytes: not a whole 16-byte vector
+    assert e.value.status == ll.LL_ERR_INVALID_ARG
 
     g = wl.config(5)
     lay = ll.distributed_layout(g.nreg, g.nlane, g.nwave, g.out_dim_bits, g.src_bases)
