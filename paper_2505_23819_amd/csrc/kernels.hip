@@ -407,9 +407,6 @@ static __device__ __forceinline__ void shuffle_stages(uint32_t (&r)[NV][4], uint
     if constexpr (NVB > 4) { if (a.stage_mask[4]) shuffle_stage<NV, 4>(r, lane, a.stage_mask[4]); }
 }
 
-// A workgroup takes a.pipe consecutive blocks.  Without LDS exchange the blocks are software
-// pipelined: the loads of the next block are issued before the current block is transposed,
-// exchanged and stored, so that a wave always has loads in flight.
 template <int W, int NVB, int TPOSE, int XCHG>
 __global__ __launch_bounds__(256) void k_vec(const VecArgs a)
 {
@@ -486,34 +483,13 @@ __global__ __launch_bounds__(256) void k_vec(const VecArgs a)
         }
     };
 
-    if constexpr (XCHG == kXchgLds) {
-        // one block per workgroup (the LDS block is reused without a second barrier otherwise)
-        const Ctx x = context((long long)blockIdx.x);
-        uint32_t r[NV][4];
-        load(x, r);
-        finish(x, r);
-    } else {
-        const long long first = (long long)blockIdx.x * a.pipe;
-        const long long remaining = a.nblocks - first;
-        const int nb = remaining < a.pipe ? (int)remaining : a.pipe;      // >= 1 by the grid size
-        uint32_t ra[NV][4], rb[NV][4];
-        Ctx xa = context(first), xb = xa;
-        load(xa, ra);
-        for (int j = 0; j < nb; j += 2) {
-            const bool has_b = j + 1 < nb;
-            if (has_b) {
-                xb = context(first + j + 1);
-                load(xb, rb);
-            }
-            finish(xa, ra);
-            if (!has_b) break;
-            if (j + 2 < nb) {
-                xa = context(first + j + 2);
-                load(xa, ra);
-            }
-            finish(xb, rb);
-        }
-    }
+    // One block per workgroup.  (Letting a wave take several blocks and load the next while it
+    // finishes the current one was measured 5-20 % slower on MI355X at every occupancy: many
+    // short-lived waves stream better.)
+    const Ctx x = context((long long)blockIdx.x);
+    uint32_t r[NV][4];
+    load(x, r);
+    finish(x, r);
 }
 
 template <int W, int NVB, int TPOSE, int XCHG>
@@ -527,17 +503,13 @@ static ll_status launch_vec_t(const VecArgs &a, int threads, int lds_bytes, hipS
         // loses bandwidth beyond that, so workgroups are kept to (in-flight budget / block bytes) per
         // CU by asking for a matching share of the 160 KiB LDS.
         static const unsigned budget = env_inflight_bytes();
-        static const int pipe_env = getenv("LL_VEC_PIPE") ? atoi(getenv("LL_VEC_PIPE")) : 1;   // experiment knob
-        VecArgs b = a;
-        b.pipe = (XCHG == kXchgLds || pipe_env < 1) ? 1 : (pipe_env > 64 ? 64 : pipe_env);
-        const unsigned block_bytes = (unsigned)threads * (16u << NVB) * (b.pipe > 1 ? 2u : 1u);
+        const unsigned block_bytes = (unsigned)threads * (16u << NVB);
         const unsigned per_cu = budget / block_bytes > 1 ? budget / block_bytes : 1;
         unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
         if (alloc > 64u * 1024u) alloc = 64u * 1024u;
         if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
-        const long long grid = (a.nblocks + b.pipe - 1) / b.pipe;
-        hipLaunchKernelGGL((k_vec<W, NVB, TPOSE, XCHG>), dim3((unsigned)grid), dim3((unsigned)threads),
-                           (size_t)alloc, stream, b);
+        hipLaunchKernelGGL((k_vec<W, NVB, TPOSE, XCHG>), dim3((unsigned)a.nblocks), dim3((unsigned)threads),
+                           (size_t)alloc, stream, a);
         return check_launch("vector conversion kernel launch");
     }
 }

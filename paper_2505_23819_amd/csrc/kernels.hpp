@@ -60,7 +60,6 @@ struct VecArgs {
     uint32_t lds_wr_lane[kMaxThreadBits], lds_rd_lane[kMaxThreadBits];
     uint32_t lds_wr_iter[kMaxIter], lds_rd_iter[kMaxIter];
     uint32_t dst_xor;   // affine conversions: constant XORed onto every destination element index
-    int pipe;           // consecutive blocks one workgroup takes (set at launch)
 };
 
 // Conversion between layouts with broadcasting (paper Sec. 5.1 "Broadcasting", Sec. 5.4 rule 2):

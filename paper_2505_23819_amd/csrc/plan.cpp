@@ -485,6 +485,33 @@ static void paper_shuffle_schedule(const ll_layout *a, const ll_layout *b, int w
     desc->sched_valid = 1;
 }
 
+// Strategy, cheapest exchange first.  The kernel's lanes are not the layout's lanes (only the
+// conversion and the image order are observable), so even a conversion that moves data between
+// the layout's waves may need no exchange between the KERNEL's lanes once small blocks with the
+// right run selectors as lanes are used: the register / shuffle planner is tried for every
+// class.  What its structure does not cover is staged through LDS, with 128-bit accesses when
+// the in-register transpose applies and element-wide accesses otherwise (always possible).
+static ll_status choose_strategy(const mat &p, int d, int elem_bytes, ll_plan *plan)
+{
+    const char *force = getenv("LL_FORCE_STRATEGY");
+    bool applied = false;
+    // Transposing LDS loads: the planner's choice for 1-byte elements (which have no in-register
+    // transpose path); for 2-byte elements only on request (LL_FORCE_STRATEGY=6).
+    if ((force && atoi(force) == LL_STRATEGY_LDS_TR) || (!force && elem_bytes == 1)) {
+        if (ll_status st = plan_lds_tr(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
+        if (applied) return LL_OK;
+    }
+    if (!(force && atoi(force) >= LL_STRATEGY_LDS_ELEM)) {
+        if (ll_status st = plan_wave_shuffle(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
+        if (applied) return LL_OK;
+    }
+    if (!(force && atoi(force) == LL_STRATEGY_LDS_ELEM)) {
+        if (ll_status st = plan_lds_vec(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
+        if (applied) return LL_OK;
+    }
+    return plan_lds_elem(p, d, elem_bytes, plan);
+}
+
 ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan)
 {
     if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8)
@@ -538,39 +565,16 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     if (c & (((vec(1) << d) - 1) & ~((vec(1) << tile_first) - 1)))
         return fail(LL_ERR_TILE_MIXED, "the offsets of the layouts would move data between tiles");
     desc.conv_offset = c;
-    struct Fold {                       // set the constant in whichever argument block the plan uses
-        ll_plan *plan; vec c;
-        ~Fold() { plan->lds_elem.dst_xor = (uint32_t)c; plan->vec.dst_xor = (uint32_t)c; }
-    } fold{plan, c};
     if (desc.kind == LL_KIND_NOOP && c == 0) {
         desc.strategy = LL_STRATEGY_COPY;
         desc.global_vec_bytes = 16;
         desc.threads = 256;
         return LL_OK;
     }
-    // Strategy, cheapest exchange first.  The kernel's lanes are not the layout's lanes (only the
-    // conversion and the image order are observable), so even a conversion that moves data between
-    // the layout's waves may need no exchange between the KERNEL's lanes once small blocks with the
-    // right run selectors as lanes are used: the register / shuffle planner is tried for every
-    // class.  What its structure does not cover is staged through LDS, with 128-bit accesses when
-    // the in-register transpose applies and element-wide accesses otherwise (always possible).
-    const char *force = getenv("LL_FORCE_STRATEGY");
-    bool applied = false;
-    // Transposing LDS loads: the planner's choice for 1-byte elements (which have no in-register
-    // transpose path); for 2-byte elements only on request (LL_FORCE_STRATEGY=6).
-    if ((force && atoi(force) == LL_STRATEGY_LDS_TR) || (!force && elem_bytes == 1)) {
-        if (ll_status st = plan_lds_tr(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
-        if (applied) return LL_OK;
-    }
-    if (!(force && atoi(force) >= LL_STRATEGY_LDS_ELEM)) {
-        if (ll_status st = plan_wave_shuffle(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
-        if (applied) return LL_OK;
-    }
-    if (!(force && atoi(force) == LL_STRATEGY_LDS_ELEM)) {
-        if (ll_status st = plan_lds_vec(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
-        if (applied) return LL_OK;
-    }
-    return plan_lds_elem(p, d, elem_bytes, plan);
+    if (ll_status st = choose_strategy(p, d, elem_bytes, plan); st != LL_OK) return st;
+    plan->lds_elem.dst_xor = (uint32_t)c;      // whichever argument block the strategy uses
+    plan->vec.dst_xor = (uint32_t)c;
+    return LL_OK;
 }
 
 }  // namespace ll

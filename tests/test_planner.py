@@ -172,11 +172,10 @@ def test_common_vector_is_kept_wide(monkeypatch):
     monkeypatch.setenv("LL_FORCE_STRATEGY", "3")
     info = ll.ll_plan_convert(a, b, 4).info()
     assert info["strategy_name"] == "lds_elem"
-    if True:
-        assert info["lds_vec_bits"] == 2 and info["lds_write_bytes"] == 16
-        for side in ("lds_write", "lds_read"):
-            assert oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6, 4, 2,
-                                     banks_of(info, side), gfx950_phases(16, side))[0] == 1
+    assert info["lds_vec_bits"] == 2 and info["lds_write_bytes"] == 16
+    for side in ("lds_write", "lds_read"):
+        assert oracle.wavefronts(info["lds_mem"], info[side], info["lds_write_reg_bits"], 6, 4, 2,
+                                 banks_of(info, side), gfx950_phases(16, side))[0] == 1
 
 
 def test_plan_errors():
