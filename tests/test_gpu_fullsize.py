@@ -10,7 +10,7 @@ import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-ll = pytest.importorskip("paper_2505_23819_amd")
+import paper_2505_23819_amd as ll  # noqa: E402  (a missing library must fail loudly, not skip)
 
 
 def sample_tiles(ntiles, count, seed):

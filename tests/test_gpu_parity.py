@@ -8,7 +8,7 @@ import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-ll = pytest.importorskip("paper_2505_23819_amd")
+import paper_2505_23819_amd as ll  # noqa: E402  (a missing library must fail loudly, not skip)
 
 DTYPES = {1: torch.uint8, 2: torch.int16, 4: torch.int32, 8: torch.int64}
 NP_DTYPES = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}
