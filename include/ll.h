@@ -245,6 +245,10 @@ typedef struct {
  * wave [/ tile] inputs onto output spaces of equal size).  Computes B^-1 o A (Sec. 5.4),
  * classifies it (intra-thread / intra-warp / shared memory), and picks the kernel, its vector
  * widths and, for LDS paths, the XOR swizzle.  elem_bytes is 1, 2, 4 or 8.
+ * Either side may instead be a memory layout (one `offset` input dim, Sec. 4.3: unswizzled,
+ * ll_layout_mma_swizzle, ...): its image is the buffer indexed by memory offset, and the plan is
+ * the register <-> memory mapping of Sec. 5.3; the input bit counts must match and no tile label
+ * may be present.
  * Both layouts must be surjective (LL_ERR_NOT_SURJECTIVE otherwise).  If both are bijective they
  * must have the same input dims (LL_ERR_DIM_MISMATCH), and a `tile` input dim, if present, must
  * map identically in both (LL_ERR_TILE_MIXED).  If a layout is not injective (broadcasting:

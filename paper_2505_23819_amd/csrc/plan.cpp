@@ -518,12 +518,12 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
         return fail(LL_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8 (got %d)", elem_bytes);
     if (src->d_out != dst->d_out)
         return fail(LL_ERR_DIM_MISMATCH, "source and destination map to output spaces of %d and %d bits", src->d_out, dst->d_out);
-    for (int i = 0; i < src->n_in; ++i)
-        if (src->in_dims[i].label == LL_IN_OFFSET)
-            return fail(LL_ERR_INVALID_ARG, "conversion needs distributed layouts (register / lane / wave / tile inputs)");
-    for (int i = 0; i < dst->n_in; ++i)
-        if (dst->in_dims[i].label == LL_IN_OFFSET)
-            return fail(LL_ERR_INVALID_ARG, "conversion needs distributed layouts (register / lane / wave / tile inputs)");
+    // A memory layout (input label `offset`, Sec. 4.3) may stand on either side: its image is the
+    // buffer indexed by memory offset, and the conversion is then the A^-1 o B of Sec. 5.3 "Shared
+    // Memory Load and Store" between a memory image and a register image (or two memory images).
+    bool memory_side = false;
+    for (int i = 0; i < src->n_in; ++i) memory_side |= src->in_dims[i].label == LL_IN_OFFSET;
+    for (int i = 0; i < dst->n_in; ++i) memory_side |= dst->in_dims[i].label == LL_IN_OFFSET;
     const int d = src->d_in;
     if (f2::rank(src->bases) < src->d_out || f2::rank(dst->bases) < dst->d_out)
         return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
@@ -535,7 +535,14 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
         plan->desc.elem_bytes = elem_bytes;
         return plan_pull(src, dst, elem_bytes, plan);
     }
-    if (!same_inputs(src, dst)) return fail(LL_ERR_DIM_MISMATCH, "source and destination layouts have different input dims");
+    if (memory_side) {
+        if (src->d_in != dst->d_in)
+            return fail(LL_ERR_DIM_MISMATCH, "source and destination layouts have %d and %d input bits", src->d_in, dst->d_in);
+        if (src->bits_of(LL_IN_TILE) || dst->bits_of(LL_IN_TILE))
+            return fail(LL_ERR_DIM_MISMATCH, "a memory layout cannot be converted to or from a layout with a tile label");
+    } else if (!same_inputs(src, dst)) {
+        return fail(LL_ERR_DIM_MISMATCH, "source and destination layouts have different input dims");
+    }
 
     // B^-1 o A (Sec. 5.4)
     mat binv;
@@ -543,7 +550,7 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     const mat p = f2::compose(binv, src->bases);
 
     // a tile label must pass through untouched
-    const int tile_first = src->first_bit_of(LL_IN_TILE);
+    const int tile_first = memory_side ? d : src->first_bit_of(LL_IN_TILE);
     for (int k = 0; k < d; ++k) {
         const vec tile_mask = ((vec(1) << d) - 1) & ~((vec(1) << tile_first) - 1);
         if (k >= tile_first ? p[k] != (vec(1) << k) : (p[k] & tile_mask) != 0)
@@ -556,6 +563,7 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     desc.elem_bytes = elem_bytes;
     for (int k = 0; k < d; ++k) desc.conv[k] = p[k];
     desc.kind = classify(p, d, src->bits_of(LL_IN_REG), src->first_bit_of(LL_IN_WAVE));
+    if (memory_side && desc.kind != LL_KIND_NOOP) desc.kind = LL_KIND_LDS;      // no register / lane / wave classes to compare
     paper_shuffle_schedule(src, dst, elem_bytes, &desc);
     // Affine layouts: x = A h ^ a = B h' ^ b gives h' = P h ^ c with c = B^-1 (a ^ b).  The planners
     // below work on P alone; c is a constant XOR on every destination index, which the kernels

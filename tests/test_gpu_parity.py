@@ -562,3 +562,36 @@ def test_convert_one_large_tile():
     # and the whole tile against the oracle's tabulated variant
     full, _ = oracle.convert(ca, cb, src.cpu().numpy().view(np.uint32), table=True)
     assert np.array_equal(dst.cpu().numpy().view(np.uint32), full)
+
+
+# ---------------------------------------------------------------------------------------------
+# memory layouts on one side (Sec. 5.3 "Shared Memory Load and Store": A^-1 o B)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("w", [1, 2, 4])
+def test_convert_between_memory_and_register_images(w):
+    """Row-major and mma-swizzled memory images <-> the 32x32 accumulator layout over a 64 x 64 tile,
+    and memory image <-> memory image (un-swizzling)."""
+    plain = ll.ll_layout_mma_swizzle(6, 6, 1, 1, 1)                       # offset = row-major position
+    swz = ll.ll_layout_mma_swizzle(6, 6, 8 // w if w < 8 else 1, 1, 8)
+    acc = ll.ll_layout_mfma_accumulator(5)
+    for label, dim in ((ll.LL_IN_WAVE, 0), (ll.LL_IN_WAVE, 1)):
+        acc = ll.ll_product_dimwise(acc, ll.ll_layout_identity(label, dim, 1, 2))
+    assert plain.in_dims == [(ll.LL_IN_OFFSET, 12)] and acc.in_dims == [(ll.LL_IN_REG, 4), (ll.LL_IN_LANE, 6), (ll.LL_IN_WAVE, 2)]
+    rng = np.random.default_rng(50 + w)
+    for x, y in ((plain, acc), (acc, plain), (swz, acc), (acc, swz), (swz, plain), (plain, swz)):
+        plan = ll.ll_plan_convert(x, y, w)
+        info = plan.info()
+        assert info["kind_name"] == "lds"
+        src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=7 << 12, dtype=NP_DTYPES[w])
+        got = run_convert(plan, src, 12)
+        assert np.array_equal(got, oracle.convert(x.bases, y.bases, src)), info["strategy_name"]
+    # a row-major image converted to the swizzled layout and read with the swizzle formula
+    plan = ll.ll_plan_convert(plain, swz, w)
+    src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=1 << 12, dtype=NP_DTYPES[w])
+    got = run_convert(plan, src, 12)
+    vec = 8 // w
+    for i, j in rng.integers(0, 64, size=(50, 2)):
+        off = oracle.mma_swizzle_offset(int(i), int(j), 6, vec, 1, 8)
+        assert got[off] == src[(int(i) << 6) | int(j)]
+    assert ll.ll_plan_convert(plain, plain, w).info()["kind_name"] == "noop"
