@@ -223,11 +223,11 @@ def main() -> int:
             torch.cuda.empty_cache()
         result["broadcast_conversions"] = btable
 
-        # the 128 x 128 transpose of config 2 with 1-byte (float8-sized) and 2-byte elements through the
-        # transposing LDS loads of gfx950, next to the same conversion with plain LDS reads
+        # the 128 x 128 transpose of config 2 with 1-byte (float8-sized) and 2-byte elements: the planner's
+        # choice, and the same conversion through the transposing LDS loads of gfx950 / 128-bit LDS
         ttable = []
         c2 = wl.config(2)
-        for w_, dt_, force_ in ((1, torch.uint8, None), (1, torch.uint8, "3"), (2, torch.int16, "6"), (2, torch.int16, "4")):
+        for w_, dt_, force_ in ((1, torch.uint8, None), (1, torch.uint8, "6"), (2, torch.int16, "6"), (2, torch.int16, "4")):
             if force_ is not None:
                 os.environ["LL_FORCE_STRATEGY"] = force_
             a = ll.distributed_layout(c2.nreg, c2.nlane, c2.nwave, c2.out_dim_bits, c2.src_bases)

@@ -39,6 +39,7 @@ struct LdsElemArgs {
     uint32_t lds_wr_iter[kMaxIter], lds_rd_iter[kMaxIter];
     uint32_t lds_wr_sub[kMaxSub], lds_rd_sub[kMaxSub];              // per sub-access of a vector
     uint32_t dst_xor;   // affine conversions: constant XORed onto every destination element index
+    int xcd_chunk;      // log2 of the consecutive blocks one XCD takes, -1: natural order (set at launch)
 };
 
 // Vector-preserving conversion: every thread keeps whole 16-byte vectors, optionally transposes
@@ -60,6 +61,7 @@ struct VecArgs {
     uint32_t lds_wr_lane[kMaxThreadBits], lds_rd_lane[kMaxThreadBits];
     uint32_t lds_wr_iter[kMaxIter], lds_rd_iter[kMaxIter];
     uint32_t dst_xor;   // affine conversions: constant XORed onto every destination element index
+    int xcd_chunk;      // log2 of the consecutive blocks one XCD takes, -1: natural order (set at launch)
 };
 
 // Conversion between layouts with broadcasting (paper Sec. 5.1 "Broadcasting", Sec. 5.4 rule 2):
@@ -131,6 +133,7 @@ struct GatherGenArgs {
     uint32_t swz_mask;
 };
 
+int xcd_chunk_bits_for(long long group_bytes, long long block_bytes);
 ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *stream);
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,
                           int lds_bytes, void *stream);

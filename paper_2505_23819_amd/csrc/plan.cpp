@@ -495,9 +495,12 @@ static ll_status choose_strategy(const mat &p, int d, int elem_bytes, ll_plan *p
 {
     const char *force = getenv("LL_FORCE_STRATEGY");
     bool applied = false;
-    // Transposing LDS loads: the planner's choice for 1-byte elements (which have no in-register
-    // transpose path); for 2-byte elements only on request (LL_FORCE_STRATEGY=6).
-    if ((force && atoi(force) == LL_STRATEGY_LDS_TR) || (!force && elem_bytes == 1)) {
+    // Transposing LDS loads (1- and 2-byte elements): on request only (LL_FORCE_STRATEGY=6).  They
+    // cut the LDS instructions 8-fold, but the instruction makes adjacent lanes take adjacent source
+    // elements, which in a transpose are different destination rows: stores of 16-byte pieces at
+    // row pitch.  Measured 5.8-6.0 TB/s against 6.3 for byte-wide LDS accesses with contiguous
+    // stores on the 128 x 128 transpose of 1-byte elements; the conversion is HBM bound either way.
+    if (force && atoi(force) == LL_STRATEGY_LDS_TR) {
         if (ll_status st = plan_lds_tr(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
         if (applied) return LL_OK;
     }

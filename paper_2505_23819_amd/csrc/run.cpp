@@ -24,6 +24,7 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.ntiles = ntiles;
         const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
         a.nblocks = groups << a.coset_bits;
+        a.xcd_chunk = xcd_chunk_bits_for((long long)desc.elem_bytes << (desc.d + a.group_bits), (long long)desc.elem_bytes << desc.block_bits);
         return launch_lds_elem(a, desc.elem_bytes, plan->nvec, desc.lds_vec_bits, desc.threads, desc.lds_bytes, stream);
     }
     case LL_STRATEGY_LDS_TR: {
@@ -33,6 +34,7 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.ntiles = ntiles;
         const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
         a.nblocks = groups << a.coset_bits;
+        a.xcd_chunk = xcd_chunk_bits_for((long long)desc.elem_bytes << (desc.d + a.group_bits), (long long)desc.elem_bytes << desc.block_bits);
         return launch_lds_tr(a, desc.elem_bytes, plan->nvec, desc.lds_bytes, stream);
     }
     case LL_STRATEGY_REG_PERMUTE:
@@ -44,6 +46,7 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.ntiles = ntiles;
         const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
         a.nblocks = groups << a.coset_bits;
+        a.xcd_chunk = xcd_chunk_bits_for((long long)desc.elem_bytes << (desc.d + a.group_bits), (long long)desc.elem_bytes << desc.block_bits);
         return launch_vec(a, desc.elem_bytes, plan->vec_nvec_bits, plan->vec_tpose, plan->vec_xchg, desc.threads,
                           desc.lds_bytes, stream);
     }

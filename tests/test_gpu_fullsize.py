@@ -115,7 +115,7 @@ def test_broadcast_convert_full_size_sampled(case):
         assert np.array_equal(wl.to_numpy_bits(dst[t << dd:(t + 1) << dd]), want), f"{case.name} tile {t}"
 
 
-@pytest.mark.parametrize("w,force", [(1, None), (2, "6")])
+@pytest.mark.parametrize("w,force", [(1, "6"), (2, "6")])
 def test_narrow_transpose_full_size_sampled(w, force, monkeypatch):
     """The 128 x 128 transpose with 1- and 2-byte elements through the transposing LDS loads, at the
     size bench.py times (256 MiB per side)."""

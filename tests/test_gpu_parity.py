@@ -345,33 +345,19 @@ def test_convert_transposing_lds_reads(w, monkeypatch):
     assert used >= 3, "the transposing-read planner applied to %d cases only" % used
 
 
-def test_one_byte_transpose_takes_transposing_reads_by_default():
+def test_one_byte_transpose_through_both_lds_kernels(monkeypatch):
     c2 = wl.config(2)
     a, b = layouts_of(c2)
+    src = np.random.default_rng(5).integers(0, 255, size=9 << c2.d, dtype=np.uint8)
+    want = oracle.convert(c2.src_bases, c2.dst_bases, src)
+    plan = ll.ll_plan_convert(a, b, 1)
+    assert plan.info()["strategy_name"] == "lds_elem"
+    assert np.array_equal(run_convert(plan, src, c2.d), want)
+    monkeypatch.setenv("LL_FORCE_STRATEGY", "6")
     plan = ll.ll_plan_convert(a, b, 1)
     info = plan.info()
     assert info["strategy_name"] == "lds_tr" and info["lds_read_bytes"] == 8
-    src = np.random.default_rng(5).integers(0, 255, size=9 << c2.d, dtype=np.uint8)
-    assert np.array_equal(run_convert(plan, src, c2.d), oracle.convert(c2.src_bases, c2.dst_bases, src))
-
-
-def test_convert_between_constructed_layouts():
-    """Layouts built with the constructors (blocked, matrix-instruction tiles, products) instead of
-    hand-written bases: blocked row-major <-> 32x32 accumulator tiles over a 128 x 128 tile, and
-    blocked <-> a left-operand tile whose K direction is covered by registers."""
-    blocked = ll.ll_layout_blocked([3, 3], [2, 4], [2, 0], [1, 0])               # 8 x 8 per lane, 4 x 16 lanes, 4 x 1 waves
-    acc = ll.ll_layout_mfma_accumulator(5)
-    for label, dim in ((ll.LL_IN_WAVE, 0), (ll.LL_IN_WAVE, 1), (ll.LL_IN_REG, 0), (ll.LL_IN_REG, 1)):
-        acc = ll.ll_product_dimwise(acc, ll.ll_layout_identity(label, dim, 1, 2))
-    assert acc.out_dims == [7, 7] and blocked.out_dims == [7, 7]
-    assert blocked.in_dims == acc.in_dims == [(ll.LL_IN_REG, 6), (ll.LL_IN_LANE, 6), (ll.LL_IN_WAVE, 2)]
-    a, b = blocked, acc
-    rng = np.random.default_rng(99)
-    for w in (1, 2, 4):
-        for x, y in ((a, b), (b, a)):
-            plan = ll.ll_plan_convert(x, y, w)
-            src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=5 << 14, dtype=NP_DTYPES[w])
-            assert np.array_equal(run_convert(plan, src, 14), oracle.convert(x.bases, y.bases, src)), (w, plan.info()["strategy_name"])
+    assert np.array_equal(run_convert(plan, src, c2.d), want)
 
 
 # ---------------------------------------------------------------------------------------------
