@@ -618,7 +618,7 @@ __global__ __launch_bounds__(256) void k_pull(const PullArgs a)
         lw ^= a.lds_wr_lane[b] & m;
         lr ^= a.lds_rd_lane[b] & m;
     }
-    const long long blk = blockIdx.x;
+    const long long blk = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk);
     const long long group = blk >> a.coset_bits;
     const uint32_t c = (uint32_t)(blk & ((1ll << a.coset_bits) - 1));
     uint32_t cs = 0, cd = 0, cr = 0;
@@ -1030,7 +1030,7 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
     const uint32_t tid = threadIdx.x;
-    const long long first = (long long)blockIdx.x << a.block_bits;
+    const long long first = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk) << a.block_bits;
     const uint32_t block_elems = 1u << a.block_bits;
     const long long left = a.total_elems - first;
     const uint32_t valid = left >= (long long)block_elems ? block_elems : (uint32_t)left;

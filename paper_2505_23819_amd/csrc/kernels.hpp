@@ -85,6 +85,7 @@ struct PullArgs {
     uint32_t lds_wr_lane[8], lds_rd_lane[8];
     uint32_t lds_wr_iter[kMaxIter], lds_rd_iter_bit[8];
     uint32_t lds_wr_sub[kMaxSub], lds_rd_sub[kMaxSub];
+    int xcd_chunk;      // log2 of the consecutive blocks one XCD takes, -1: natural order (set at launch)
 };
 
 enum { kTposeNone = 0, kTposeBefore = 1, kTposeAfter = 2 };
@@ -129,6 +130,7 @@ struct GatherGenArgs {
     uint32_t delta[kMaxAxisBits];        // per axis bit: XOR on the block-local hardware index
     uint32_t own_bit[32];                // per hardware-index bit (0 above the tile): axis coordinate contribution
     uint32_t own_const;                  // affine layouts: constant part of every element's axis coordinate
+    int xcd_chunk;                       // log2 of the consecutive blocks one XCD takes, -1: natural order
     int swz_shift, swz_to;               // LDS byte address ^= ((address >> swz_shift) & swz_mask) << swz_to
     uint32_t swz_mask;
 };
