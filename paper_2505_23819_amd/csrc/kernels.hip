@@ -740,7 +740,7 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a)
     constexpr int PL = NE * W;                    // data bytes per lane
     constexpr int DW = (PL + 3) / 4;              // data dwords per lane
     const uint32_t lane = threadIdx.x & 63;
-    const long long chunk = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long chunk = block_of_workgroup((long long)blockIdx.x, (a.nchunks + 3) / 4, a.xcd_chunk) * 4 + (threadIdx.x >> 6);
     if (chunk >= a.nchunks) return;               // whole wave leaves together
     const unsigned char *in = static_cast<const unsigned char *>(a.in) + ((size_t)chunk * 64 + lane) * PL;
     const unsigned char *ix = reinterpret_cast<const unsigned char *>(a.idx) + ((size_t)chunk * 64 + lane) * (NE * 4);
@@ -848,7 +848,7 @@ __global__ __launch_bounds__(256) void k_gather_staged(const GatherArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long chunk0 = (long long)blockIdx.x * 4;
+    const long long chunk0 = block_of_workgroup((long long)blockIdx.x, (a.nchunks + 3) / 4, a.xcd_chunk) * 4;
     const long long chunk = chunk0 + wave;
     const long long left = a.nchunks - chunk0;
     const uint32_t chunks_here = left >= 4 ? 4u : (left > 0 ? (uint32_t)left : 0u);

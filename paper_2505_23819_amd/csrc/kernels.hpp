@@ -111,6 +111,7 @@ struct GatherArgs {
     uint32_t own_regbit[6];   // per register bit (own_reg is linear: own_reg[r] = XOR of these)
     int nwave;
     uint32_t own_const;       // affine layouts: constant part of every element's axis coordinate
+    int xcd_chunk;            // log2 of the consecutive workgroups' worth of chunks one XCD takes, -1: natural order
     int staged;               // 1: coalesced global access with the source staged in wave-private LDS
 };
 

@@ -258,6 +258,11 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
     a.idx = idx;
     a.out = out;
     a.nchunks = ntiles << a.nwave;
+    {
+        const char *e = getenv("LL_GATHER_XCD_CHUNK");            // experiment knob: workgroups (power of two), 0 = off
+        const long long v = e ? atoi(e) : 0;
+        a.xcd_chunk = v > 1 ? 63 - __builtin_clzll((unsigned long long)v) : -1;
+    }
     return launch_gather(a, elem_bytes, stream);
 }
 
