@@ -99,87 +99,103 @@ extern "C" {
 
 ll_status ll_product_dimwise(const ll_layout *a, const ll_layout *b, ll_layout **out)
 {
-    if (!out) return ll::fail(LL_ERR_INVALID_ARG, "out is null");
-    *out = nullptr;
-    if (!a || !b) return ll::fail(LL_ERR_INVALID_ARG, "null layout");
-    if (a->n_out != b->n_out) return ll::fail(LL_ERR_DIM_MISMATCH, "factors have %d and %d logical dims", a->n_out, b->n_out);
-    if (a->offset || b->offset) return ll::fail(LL_ERR_UNSUPPORTED, "products of affine layouts are not implemented");
-    if (a->d_in + b->d_in > LL_MAX_BITS || a->d_out + b->d_out > LL_MAX_BITS)
-        return ll::fail(LL_ERR_INVALID_ARG, "product exceeds %d bits", LL_MAX_BITS);
-    const int r = a->n_out;
-    ll_out_dim odims[LL_MAX_OUT_DIMS];
-    int zero[LL_MAX_OUT_DIMS] = {}, above[LL_MAX_OUT_DIMS];
-    for (int j = 0; j < r; ++j) {
-        odims[j].nbits = a->out_dims[j].nbits + b->out_dims[j].nbits;
-        above[j] = a->out_dims[j].nbits;                 // b's bits of a dim sit above a's
+    try {
+        if (!out) return ll::fail(LL_ERR_INVALID_ARG, "out is null");
+        *out = nullptr;
+        if (!a || !b) return ll::fail(LL_ERR_INVALID_ARG, "null layout");
+        if (a->n_out != b->n_out) return ll::fail(LL_ERR_DIM_MISMATCH, "factors have %d and %d logical dims", a->n_out, b->n_out);
+        if (a->offset || b->offset) return ll::fail(LL_ERR_UNSUPPORTED, "products of affine layouts are not implemented");
+        if (a->d_in + b->d_in > LL_MAX_BITS || a->d_out + b->d_out > LL_MAX_BITS)
+            return ll::fail(LL_ERR_INVALID_ARG, "product exceeds %d bits", LL_MAX_BITS);
+        const int r = a->n_out;
+        ll_out_dim odims[LL_MAX_OUT_DIMS];
+        int zero[LL_MAX_OUT_DIMS] = {}, above[LL_MAX_OUT_DIMS];
+        for (int j = 0; j < r; ++j) {
+            odims[j].nbits = a->out_dims[j].nbits + b->out_dims[j].nbits;
+            above[j] = a->out_dims[j].nbits;                 // b's bits of a dim sit above a's
+        }
+        ll_in_dim dims[LL_MAX_IN_DIMS];
+        int n = 0;
+        bool has_offset = false, has_hw = false;
+        mat cols;
+        for (int label = LL_IN_REG; label <= LL_IN_OFFSET; ++label) {
+            if (!has_label(a, label) && !has_label(b, label)) continue;
+            (label == LL_IN_OFFSET ? has_offset : has_hw) = true;
+            const int na = a->bits_of(label), nb = b->bits_of(label);
+            dims[n].label = label;
+            dims[n].nbits = na + nb;
+            ++n;
+            for (int k = 0; k < na; ++k) cols.push_back(repack(a->bases[a->first_bit_of(label) + k], a->out_dims, odims, r, zero));
+            for (int k = 0; k < nb; ++k) cols.push_back(repack(b->bases[b->first_bit_of(label) + k], b->out_dims, odims, r, above));
+        }
+        if (has_offset && has_hw) return ll::fail(LL_ERR_DIM_MISMATCH, "cannot multiply a memory layout with a distributed layout");
+        return ll::make_layout(dims, n, odims, r, cols, out);
+    } catch (...) {   // nothing may propagate across the C ABI
+        return ll::fail(LL_ERR_INVALID_ARG, "ll_product_dimwise: out of host memory");
     }
-    ll_in_dim dims[LL_MAX_IN_DIMS];
-    int n = 0;
-    bool has_offset = false, has_hw = false;
-    mat cols;
-    for (int label = LL_IN_REG; label <= LL_IN_OFFSET; ++label) {
-        if (!has_label(a, label) && !has_label(b, label)) continue;
-        (label == LL_IN_OFFSET ? has_offset : has_hw) = true;
-        const int na = a->bits_of(label), nb = b->bits_of(label);
-        dims[n].label = label;
-        dims[n].nbits = na + nb;
-        ++n;
-        for (int k = 0; k < na; ++k) cols.push_back(repack(a->bases[a->first_bit_of(label) + k], a->out_dims, odims, r, zero));
-        for (int k = 0; k < nb; ++k) cols.push_back(repack(b->bases[b->first_bit_of(label) + k], b->out_dims, odims, r, above));
-    }
-    if (has_offset && has_hw) return ll::fail(LL_ERR_DIM_MISMATCH, "cannot multiply a memory layout with a distributed layout");
-    return ll::make_layout(dims, n, odims, r, cols, out);
 }
 
 ll_status ll_divide_left(const ll_layout *layout, const ll_layout *tile, ll_layout **out)
 {
-    if (ll_status st = check_pair(layout, tile, out); st != LL_OK) return st;
-    return divide(layout, layout->bases, tile, out);
+    try {
+        if (ll_status st = check_pair(layout, tile, out); st != LL_OK) return st;
+        return divide(layout, layout->bases, tile, out);
+    } catch (...) {   // nothing may propagate across the C ABI
+        return ll::fail(LL_ERR_INVALID_ARG, "ll_divide_left: out of host memory");
+    }
 }
 
 ll_status ll_divide_left_permuted(const ll_layout *layout, const ll_layout *tile, int label, int32_t *perm, ll_layout **out)
 {
-    if (ll_status st = check_pair(layout, tile, out); st != LL_OK) return st;
-    if (!perm) return ll::fail(LL_ERR_INVALID_ARG, "perm is null");
-    const int n = layout->bits_of(label), nt = tile->bits_of(label);
-    if (nt > n) return ll::fail(LL_ERR_NOT_DIVISIBLE, "the tile has %d bits of input label %d, the layout %d", nt, label, n);
-    const int first = layout->first_bit_of(label), tfirst = tile->first_bit_of(label);
-    int zero[LL_MAX_OUT_DIMS] = {};
-    // The tile's columns are taken in order; each claims the first unused input bit of `label`
-    // that maps as it does.  The unclaimed bits follow in their old order.
-    std::vector<int> order;
-    std::vector<bool> used((size_t)n, false);
-    for (int k = 0; k < nt; ++k) {
-        const vec want = repack(tile->bases[tfirst + k], tile->out_dims, layout->out_dims, layout->n_out, zero);
-        int found = -1;
-        for (int c = 0; c < n && found < 0; ++c)
-            if (!used[(size_t)c] && layout->bases[first + c] == want) found = c;
-        if (found < 0)
-            return ll::fail(LL_ERR_NOT_DIVISIBLE, "no input bit of label %d maps as bit %d of the tile does", label, k);
-        used[(size_t)found] = true;
-        order.push_back(found);
+    try {
+        if (ll_status st = check_pair(layout, tile, out); st != LL_OK) return st;
+        if (!perm) return ll::fail(LL_ERR_INVALID_ARG, "perm is null");
+        const int n = layout->bits_of(label), nt = tile->bits_of(label);
+        if (nt > n) return ll::fail(LL_ERR_NOT_DIVISIBLE, "the tile has %d bits of input label %d, the layout %d", nt, label, n);
+        const int first = layout->first_bit_of(label), tfirst = tile->first_bit_of(label);
+        int zero[LL_MAX_OUT_DIMS] = {};
+        // The tile's columns are taken in order; each claims the first unused input bit of `label`
+        // that maps as it does.  The unclaimed bits follow in their old order.
+        std::vector<int> order;
+        std::vector<bool> used((size_t)n, false);
+        for (int k = 0; k < nt; ++k) {
+            const vec want = repack(tile->bases[tfirst + k], tile->out_dims, layout->out_dims, layout->n_out, zero);
+            int found = -1;
+            for (int c = 0; c < n && found < 0; ++c)
+                if (!used[(size_t)c] && layout->bases[first + c] == want) found = c;
+            if (found < 0)
+                return ll::fail(LL_ERR_NOT_DIVISIBLE, "no input bit of label %d maps as bit %d of the tile does", label, k);
+            used[(size_t)found] = true;
+            order.push_back(found);
+        }
+        for (int c = 0; c < n; ++c)
+            if (!used[(size_t)c]) order.push_back(c);
+        mat cols = layout->bases;
+        for (int k = 0; k < n; ++k) {
+            cols[first + k] = layout->bases[first + order[(size_t)k]];
+            perm[k] = order[(size_t)k];
+        }
+        return divide(layout, cols, tile, out);
+    } catch (...) {   // nothing may propagate across the C ABI
+        return ll::fail(LL_ERR_INVALID_ARG, "ll_divide_left_permuted: out of host memory");
     }
-    for (int c = 0; c < n; ++c)
-        if (!used[(size_t)c]) order.push_back(c);
-    mat cols = layout->bases;
-    for (int k = 0; k < n; ++k) {
-        cols[first + k] = layout->bases[first + order[(size_t)k]];
-        perm[k] = order[(size_t)k];
-    }
-    return divide(layout, cols, tile, out);
 }
 
 ll_status ll_contiguity(const ll_layout *layout, int32_t *elems)
 {
-    if (!layout || !elems) return ll::fail(LL_ERR_INVALID_ARG, "null argument");
-    *elems = 1;
-    if (layout->n_in == 0 || layout->in_dims[0].label != LL_IN_REG) return LL_OK;
-    // Logical elements 0..2^u-1 sit in registers 0..2^u-1 of one thread exactly when register bit
-    // i maps to logical bit i for every i < u (the inverse is then the identity on that block).
-    int u = 0;
-    while (u < layout->in_dims[0].nbits && u < layout->d_out && layout->bases[(size_t)u] == (vec(1) << u)) ++u;
-    *elems = 1 << u;
-    return LL_OK;
+    try {
+        if (!layout || !elems) return ll::fail(LL_ERR_INVALID_ARG, "null argument");
+        *elems = 1;
+        if (layout->n_in == 0 || layout->in_dims[0].label != LL_IN_REG) return LL_OK;
+        // Logical elements 0..2^u-1 sit in registers 0..2^u-1 of one thread exactly when register bit
+        // i maps to logical bit i for every i < u (the inverse is then the identity on that block).
+        int u = 0;
+        while (u < layout->in_dims[0].nbits && u < layout->d_out && layout->bases[(size_t)u] == (vec(1) << u)) ++u;
+        *elems = 1 << u;
+        return LL_OK;
+    } catch (...) {   // nothing may propagate across the C ABI
+        return ll::fail(LL_ERR_INVALID_ARG, "ll_contiguity: out of host memory");
+    }
 }
 
 }  // extern "C"
