@@ -201,6 +201,24 @@ def main() -> int:
             table.append(entry)
         result["per_config"] = table
 
+        # config 1 is launch bound: the same launch recorded 100 times into a HIP graph and replayed
+        c1 = wl.config(1)
+        l1, inf1, s1 = make_case(c1, 2)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            l1(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for k in range(100):
+                l1(k)
+        _, g_ms, _, _ = time_launches(lambda k: graph.replay(), 20, 2)
+        result["config1_graph_replay"] = {"launches_per_graph": 100, "us_per_launch": round(g_ms * 1e3 / 100, 3),
+                                          "kernel": inf1["strategy_name"]}
+        del graph, l1, s1
+
         # conversions between layouts that replicate data (zero columns): one copy of every logical
         # element read, every destination slot written
         btable = []

@@ -581,3 +581,47 @@ def test_convert_between_memory_and_register_images(w):
         off = oracle.mma_swizzle_offset(int(i), int(j), 6, vec, 1, 8)
         assert got[off] == src[(int(i) << 6) | int(j)]
     assert ll.ll_plan_convert(plain, plain, w).info()["kind_name"] == "noop"
+
+
+# ---------------------------------------------------------------------------------------------
+# HIP graph capture: the entry points allocate nothing and never synchronize
+# ---------------------------------------------------------------------------------------------
+
+def test_entry_points_can_be_captured_in_a_hip_graph():
+    """A conversion (config 1, launch bound) and a gather recorded into one graph and replayed with
+    new inputs between replays; every replay must equal the eager result and the oracle."""
+    c1, c5 = wl.config(1), wl.config(5)
+    a, b = layouts_of(c1)
+    plan = ll.ll_plan_convert(a, b, c1.elem_bytes)
+    lay5, _ = layouts_of(c5)
+    nt1, nt5 = 4, 2
+    src = torch.zeros(nt1 << c1.d, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    inp = torch.zeros(nt5 << c5.d, dtype=torch.float16, device="cuda")
+    idx = torch.zeros(nt5 << c5.d, dtype=torch.int32, device="cuda")
+    out = torch.zeros_like(inp)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside capture
+        ll.ll_convert(plan, src, dst, nt1)
+        ll.ll_gather(lay5, c5.axis, c5.elem_bytes, inp, idx, out, nt5)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ll.ll_convert(plan, src, dst, nt1)
+        ll.ll_gather(lay5, c5.axis, c5.elem_bytes, inp, idx, out, nt5)
+    for rep in range(4):
+        new_src = c1.gen_data(rep, nt1)
+        new_inp, new_idx = c5.gen_data(rep, nt5), c5.gen_idx(rep, nt5)
+        src.copy_(new_src.cuda())
+        inp.copy_(new_inp.cuda())
+        idx.copy_(new_idx.cuda())
+        dst.zero_()
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(wl.to_numpy_bits(dst), oracle.convert(c1.src_bases, c1.dst_bases, wl.to_numpy_bits(new_src))), rep
+        assert np.array_equal(wl.to_numpy_bits(out), oracle.gather(c5.src_bases, c5.out_dim_bits, c5.axis,
+                                                                   wl.to_numpy_bits(new_inp), new_idx.numpy())), rep
