@@ -149,8 +149,8 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": {1: "u8", 2: "u16", 4: "u32", 8: "u64"}[main_cfg.elem_bytes] + " (raw bits moved; elements are "
-                 + str(main_cfg.dtype).replace("torch.", "") + ")",
+        "dtype": {1: "u8", 2: "u16", 4: "u32", 8: "u64"}[main_cfg.elem_bytes],      # raw bits are moved, no arithmetic
+        "element_type": str(main_cfg.dtype).replace("torch.", ""),
         "data": "synthetic",
         "config": {"workload": "config %d: %s, %d tiles of 2^%d elements x %d B" %
                                (main_cfg.cid, main_cfg.name, main_cfg.ntiles, main_cfg.d, main_cfg.elem_bytes),
