@@ -369,3 +369,32 @@ def test_plan_of_config1_reports_the_hand_derived_conversion_matrix():
     row = [l.split() for l in open("tests/golden/config_spot_values.txt") if l.startswith("P")][0]
     info = plan_of(wl.config(1)).info()
     assert info["conv"] == [int(x, 16) for x in row[1:]]
+
+
+def test_planning_from_several_threads():
+    """Layouts and plans are immutable after creation and the library keeps no shared mutable state:
+    concurrent planning (ctypes releases the GIL) gives the same plans, and ll_last_error is per thread."""
+    import threading
+    cfgs = [wl.config(c) for c in (1, 2, 3, 4)]
+    want = [plan_of(c).info() for c in cfgs]
+    errors = []
+
+    def work(k):
+        try:
+            for rep in range(5):
+                for c, w in zip(cfgs, want):
+                    got = plan_of(c).info()
+                    assert got["conv"] == w["conv"] and got["strategy"] == w["strategy"] and got["lds_mem"] == w["lds_mem"]
+                if k % 2:                                   # provoke an error on this thread only
+                    with pytest.raises(ll.LLError) as e:
+                        ll.ll_layout_create([(ll.LL_IN_REG, 2)], [1], [1, 7])
+                    assert "does not fit" in str(e.value)
+        except Exception as exc:                            # noqa: BLE001
+            errors.append((k, exc))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
