@@ -1018,8 +1018,8 @@ static ll_status launch_gather_w(const GatherArgs &a, hipStream_t stream)
 // General gather: any bijective layout, axis bits anywhere inside the block.  256 threads.
 //   stage   coalesced 16-byte loads of the block of `in`, written to LDS word by word (4-byte words,
 //           8-byte for 8-byte elements) at XOR-swizzled addresses;
-//   gather  a unit of work is 4 consecutive output elements (one coalesced 16-byte load of their
-//           indices).  For each element the XOR delta that moves its hardware index along the axis
+//   gather  a unit of work is 4 consecutive output elements (2 for 8-byte elements): one coalesced
+//           load of their indices, at most 16 bytes stored.  For each element the XOR delta that moves its hardware index along the axis
 //           to the indexed coordinate (Sec. 5.5: the source is L^-1 of the element's logical
 //           position with the axis coordinate replaced) is linear in x = idx ^ own coordinate, and
 //           so is the swizzle: the LDS address of the source is (address of the element itself) ^
@@ -1075,33 +1075,42 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
     }
     // axis coordinate of an element = XOR of the contributions of the set bits of its hardware
     // index: the block's bits (uniform), this thread's bits, the pass's bits, the slot's bits
+    constexpr int UB = (W == 8) ? 1 : 2;             // log2 elements per unit: one 16-byte (8-byte) index load
+    constexpr int UE = 1 << UB;
     uint32_t own_t = a.own_const;
     {
         const unsigned long long f = (unsigned long long)first;
         for (int b = a.block_bits; b < 32; ++b) own_t ^= a.own_bit[b] & (0u - (uint32_t)((f >> b) & 1ull));
 #pragma unroll
-        for (int b = 0; b < 8; ++b) own_t ^= a.own_bit[2 + b] & (0u - ((tid >> b) & 1u));
+        for (int b = 0; b < 8; ++b) own_t ^= a.own_bit[UB + b] & (0u - ((tid >> b) & 1u));
     }
     const uint32_t own_s[4] = {0u, a.own_bit[0], a.own_bit[1], a.own_bit[0] ^ a.own_bit[1]};
-    const uint32_t unit_passes = (block_elems >> 2) >> 8;         // 4-element units per thread (a multiple of U)
+    const uint32_t unit_passes = (block_elems >> UB) >> 8;        // units per thread (a multiple of U)
     __syncthreads();
 
     for (uint32_t p = 0; p < unit_passes; p += U) {
-        u32x4 ix[U];
+        uint32_t ix[U][UE];
 #pragma unroll
-        for (int q = 0; q < U; ++q) ix[q] = buf_load16(rix, (tid + 256u * (p + q)) * 16u);
+        for (int q = 0; q < U; ++q) {
+            if constexpr (UE == 4) {
+                const u32x4 t = buf_load16(rix, (tid + 256u * (p + q)) * 16u);
+                ix[q][0] = t.x; ix[q][1] = t.y; ix[q][2] = t.z; ix[q][3] = t.w;
+            } else {
+                const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rix, (tid + 256u * (p + q)) * 8u, 0, kStream);
+                ix[q][0] = t.x; ix[q][1] = t.y;
+            }
+        }
 #pragma unroll
         for (int q = 0; q < U; ++q) {
             const uint32_t pass = p + q;
             const uint32_t unit = tid + 256u * pass;
             uint32_t own_p = own_t;
-            for (int b = 0; (pass >> b) != 0; ++b) own_p ^= a.own_bit[10 + b] & (0u - ((pass >> b) & 1u));
-            const uint32_t self = swz(unit * (4u * W));           // LDS address of the unit's first element
-            const uint32_t idx4[4] = {ix[q].x, ix[q].y, ix[q].z, ix[q].w};
-            uint32_t o[(W == 8) ? 8 : 4] = {};
+            for (int b = 0; (pass >> b) != 0; ++b) own_p ^= a.own_bit[UB + 8 + b] & (0u - ((pass >> b) & 1u));
+            const uint32_t self = swz(unit * (uint32_t)(UE * W));  // LDS address of the unit's first element
+            uint32_t o[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const uint32_t x = (idx4[s] ^ own_p ^ own_s[s]) & a.axis_mask;
+            for (int s = 0; s < UE; ++s) {
+                const uint32_t x = (ix[q][s] ^ own_p ^ own_s[s]) & a.axis_mask;
                 uint32_t t = table[x & 31u];
                 if (ntab > 1) t ^= table[32u + ((x >> 5) & 31u)];
                 if (ntab > 2) t ^= table[64u + ((x >> 10) & 31u)];
@@ -1118,11 +1127,7 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
                     o[0] |= (uint32_t)*reinterpret_cast<const uint8_t *>(lds + addr) << (s * 8);
                 }
             }
-            if constexpr (W == 8) {
-                const u32x4 lo = {o[0], o[1], o[2], o[3]}, hi = {o[4], o[5], o[6], o[7]};
-                buf_store16(rout, unit * 32u, lo);
-                buf_store16(rout, unit * 32u + 16u, hi);
-            } else if constexpr (W == 4) {
+            if constexpr (W >= 4) {
                 const u32x4 v = {o[0], o[1], o[2], o[3]};
                 buf_store16(rout, unit * 16u, v);
             } else if constexpr (W == 2) {
@@ -1142,7 +1147,7 @@ static ll_status launch_gather_general_w(const GatherGenArgs &a, hipStream_t s)
     const long long block_bytes = (1ll << a.block_bits) * W;
     const size_t lds_bytes = (size_t)block_bytes + 128u * (size_t)((a.na + 4) / 5);
     const dim3 grid((unsigned)a.nblocks), block(256);
-    const int vec_passes = (int)((1ll << a.block_bits) >> VS >> 8), unit_passes = (int)((1ll << a.block_bits) >> 10);
+    const int vec_passes = (int)((1ll << a.block_bits) >> VS >> 8), unit_passes = (int)((1ll << a.block_bits) >> (W == 8 ? 9 : 10));
     if (vec_passes < 1 || unit_passes < 1) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than one pass");
     const int together = vec_passes < unit_passes ? vec_passes : unit_passes;   // both are powers of two
     if (together >= 4) {

@@ -121,7 +121,12 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     const char *force = getenv("LL_GATHER_GENERAL");
     const bool lane_only = !(touched & ~lane_mask) && nlane == LL_WAVE_LANE_BITS && nreg <= 6 && d - nreg - nlane <= 16 &&
                            na <= 6 && (1 << nreg) * elem_bytes >= 4 && (1 << nreg) * elem_bytes <= 256;
-    if (lane_only && !(force && atoi(force))) {
+    // Lanes that hold fewer than 16 bytes make the shuffle kernel's global accesses narrow (measured
+    // 4.6-5.5 TB/s against 6.4-6.5 for the workgroup-staged kernel), so those layouts take the general
+    // kernel unless LL_GATHER_GENERAL=0 asks for the wave kernels.
+    const bool narrow = (1 << nreg) * elem_bytes < 16;
+    const bool want_general = force ? atoi(force) != 0 : narrow;
+    if (lane_only && !want_general) {
         GatherArgs &a = c->wave;
         std::memset(&a, 0, sizeof(a));
         const int nhigh = d - nreg - nlane;

@@ -120,7 +120,7 @@ def test_gather_config5_small(ntiles):
 
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 @pytest.mark.parametrize("nreg,nwave,axis_bits", [(2, 0, 6), (3, 1, 4), (4, 2, 6), (5, 1, 3), (1, 3, 5)])
-def test_gather_random_lane_axis(w, nreg, nwave, axis_bits):
+def test_gather_random_lane_axis(w, nreg, nwave, axis_bits, monkeypatch):
     """Axis bits live on an arbitrary subset of the lane bits, mixed by XOR with other lane bits;
     the other logical bits are spread over registers, the remaining lanes and waves."""
     if (1 << nreg) * w < 4:
@@ -149,9 +149,13 @@ def test_gather_random_lane_axis(w, nreg, nwave, axis_bits):
     inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
     idx = rng.integers(0, 1 << axis_bits, size=ntiles << d, dtype=np.int32)
     idx[::17] += 1 << axis_bits                        # out-of-range entries wrap
-    got = run_gather(layout, 0, inp, idx, d)
     want = oracle.gather(bases, dims, 0, inp, idx)
-    assert np.array_equal(got, want)
+    for general in ("0", "1"):                         # the wave kernels (shuffle / wave-staged) and the workgroup-staged one
+        monkeypatch.setenv("LL_GATHER_GENERAL", general)
+        assert ll.ll_gather_info(layout, 0, w)["kernel_name"] == ("block_staged" if general == "1" else
+                                                                 ll.ll_gather_info(layout, 0, w)["kernel_name"])
+        got = run_gather(layout, 0, inp, idx, d)
+        assert np.array_equal(got, want), general
 
 
 @pytest.mark.parametrize("cid", [1, 2, 3, 4])

@@ -318,7 +318,9 @@ def test_gather_kernel_choice():
     info = ll.ll_gather_info(regaxis, 0, 4)
     assert (info["kernel_name"], info["axis_reg_bits"], info["paper_rounds"]) == ("block_staged", 2, 4)
     narrow = ll.distributed_layout(0, 6, 2, [6, 2], [1 << (2 + k) for k in range(6)] + [1, 2])
-    assert ll.ll_gather_info(narrow, 0, 4)["kernel_name"] == "shuffle"
+    assert ll.ll_gather_info(narrow, 0, 4)["kernel_name"] == "block_staged"       # 4 bytes per lane: staged
+    rows16 = ll.distributed_layout(2, 6, 2, [6, 4], [1, 2] + [1 << (4 + k) for k in range(6)] + [4, 8])
+    assert ll.ll_gather_info(rows16, 0, 4)["kernel_name"] == "shuffle"            # 16 bytes per lane: one shuffle round
 
 
 def test_paper_shuffle_schedule_invariants():
