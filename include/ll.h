@@ -205,6 +205,8 @@ typedef struct {
     uint64_t conv_offset;       /* affine layouts: destination index = conv * h xor conv_offset */
     uint64_t pull[LL_MAX_BITS]; /* broadcasting layouts: columns of A^+ o B, destination index -> source index */
     int32_t global_vec_bytes;   /* width of every global load and store */
+    int32_t src_lines_per_access; /* distinct 128-byte lines one wave-wide load (64 x 16 bytes) touches; 8 = fully coalesced */
+    int32_t dst_lines_per_access; /* the same for one wave-wide store */
     int32_t lds_write_bytes;    /* width of one LDS write (0 if LDS unused) */
     int32_t lds_read_bytes;     /* width of one LDS read  (0 if LDS unused) */
     int32_t lds_bytes;          /* LDS bytes per workgroup */

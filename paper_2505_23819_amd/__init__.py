@@ -57,7 +57,8 @@ class ll_plan_desc(ctypes.Structure):
         ("elem_bytes", ctypes.c_int32),
         ("conv", ctypes.c_uint64 * LL_MAX_BITS), ("conv_offset", ctypes.c_uint64),
         ("pull", ctypes.c_uint64 * LL_MAX_BITS),
-        ("global_vec_bytes", ctypes.c_int32), ("lds_write_bytes", ctypes.c_int32),
+        ("global_vec_bytes", ctypes.c_int32), ("src_lines_per_access", ctypes.c_int32),
+        ("dst_lines_per_access", ctypes.c_int32), ("lds_write_bytes", ctypes.c_int32),
         ("lds_read_bytes", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
         ("threads", ctypes.c_int32), ("vectors_per_thread", ctypes.c_int32),
         ("block_bits", ctypes.c_int32), ("group_bits", ctypes.c_int32),

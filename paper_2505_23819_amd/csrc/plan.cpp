@@ -20,6 +20,14 @@ unsigned env_bytes(const char *name, unsigned fallback)
     return (x >= 16 && x <= (1 << 20) && (x & (x - 1)) == 0) ? (unsigned)x : fallback;
 }
 
+int wave_access_lines(const uint32_t *lane_table, int w)
+{
+    const int line_shift = ilog2(128u / (unsigned)w);       // element-offset bits inside one 128-byte line
+    mat high;
+    for (int b = 0; b < 6; ++b) high.push_back((vec)(lane_table[b] >> line_shift));
+    return 1 << f2::rank(high);
+}
+
 int lds_width_class(int access_bytes) { return access_bytes <= 4 ? 0 : (access_bytes == 8 ? 1 : 2); }
 
 static vec lane_image(const mat &lanes, uint32_t lane_vec)
@@ -583,6 +591,11 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
         return LL_OK;
     }
     if (ll_status st = choose_strategy(p, d, elem_bytes, plan); st != LL_OK) return st;
+    {
+        const bool elem = desc.strategy == LL_STRATEGY_LDS_ELEM || desc.strategy == LL_STRATEGY_LDS_TR;
+        desc.src_lines_per_access = wave_access_lines(elem ? plan->lds_elem.lane_src : plan->vec.lane_src, elem_bytes);
+        desc.dst_lines_per_access = wave_access_lines(elem ? plan->lds_elem.lane_dst : plan->vec.lane_dst, elem_bytes);
+    }
     plan->lds_elem.dst_xor = (uint32_t)c;      // whichever argument block the strategy uses
     plan->vec.dst_xor = (uint32_t)c;
     return LL_OK;

@@ -49,6 +49,9 @@ struct BlockGeom {
 };
 ll_status build_blocks(const f2::mat &p, int d, int w, int min_bits, unsigned max_bytes, unsigned pref_bytes, BlockGeom *out);
 unsigned env_bytes(const char *name, unsigned fallback);
+// Distinct 128-byte lines touched by one wave-wide access of 16-byte vectors whose element offsets are
+// XOR combinations of lane_table[0..5] (8 when the 64 vectors are contiguous).
+int wave_access_lines(const uint32_t *lane_table, int w);
 
 }  // namespace ll
 

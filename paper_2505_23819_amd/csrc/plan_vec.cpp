@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <utility>
 #include <vector>
 
 #include "plan.hpp"
@@ -376,12 +377,17 @@ ll_status plan_lds_vec(const mat &p, int d, int w, ll_plan *plan, bool *applied)
     }
     const mat zspace = f2::intersect(h_src, h_pre, n);
     if ((int)zspace.size() != n - 2 * vs) return LL_OK;
-    f2::Basis zb;
-    for (vec x : zspace) zb.add(x);
+    // Lanes first: take the directions of Z in the order of the source offsets they stand for, so
+    // that the 64 vectors of a wave-wide load lie in as few 128-byte lines as Z allows.
+    if (zspace.size() > 12) return LL_OK;
+    std::vector<std::pair<vec, vec>> by_offset;       // (source offset, direction)
+    for (unsigned sel = 1; sel < (1u << zspace.size()); ++sel) {
+        const vec x = xor_bits(zspace, sel);
+        by_offset.push_back({f2::apply(g.us, x), x});
+    }
+    std::sort(by_offset.begin(), by_offset.end());
     mat zcand;
-    for (int b = vs; b < n; ++b)
-        if (zb.contains(vec(1) << b)) zcand.push_back(vec(1) << b);
-    zcand.insert(zcand.end(), zspace.begin(), zspace.end());
+    for (const auto &e : by_offset) zcand.push_back(e.second);
     const mat z = f2::extend({}, zcand);
     if ((int)z.size() != n - 2 * vs) return LL_OK;
     {
@@ -436,6 +442,10 @@ ll_status plan_lds_vec(const mat &p, int d, int w, ll_plan *plan, bool *applied)
         a.iter_dst[i] = (uint32_t)dl;
         a.lds_rd_iter[i] = (uint32_t)(rl * (vec)w);
     }
+    // A wave-wide load that is spread over more than 8 lines costs more than the narrower LDS
+    // accesses of the element-wide kernel, whose global accesses are always contiguous (measured:
+    // 16 lines 5.6 TB/s, 32 lines 3.9-5.2, element-wide kernel 6.2).
+    if (wave_access_lines(a.lane_src, w) > 8 || wave_access_lines(a.lane_dst, w) > 8) return LL_OK;
     const int lds_bytes = (1 << n) * w;
     if (ll_status st = check_vec_tables(a, g.pext, vs, w, nvb, kTposeBefore, kXchgLds, lds_bytes); st != LL_OK) return st;
 

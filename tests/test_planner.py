@@ -400,3 +400,31 @@ def test_planning_from_several_threads():
     for t in threads:
         t.join()
     assert not errors, errors
+
+
+def test_every_plan_keeps_wave_accesses_in_eight_lines():
+    """D1 / D5: a wave-wide 16-byte access (1 KiB) must touch exactly 8 lines of 128 bytes on both
+    sides, whatever the strategy (plans whose lanes would spread further are rejected in favour of
+    the element-wide LDS kernel)."""
+    rng = np.random.default_rng(77)
+    seen = set()
+    for trial in range(150):
+        d = int(rng.integers(8, 17))
+        w = int(rng.choice([1, 2, 4, 8]))
+        nreg = int(rng.integers(0, 7))
+        nlane = min(6, d - nreg)
+        nwave = d - nreg - nlane
+        if trial % 2:
+            ca, cb = [1 << int(p) for p in rng.permutation(d)], [1 << int(p) for p in rng.permutation(d)]
+        else:
+            ca, cb = wl.random_invertible_bases(5000 + trial, d), wl.random_invertible_bases(6000 + trial, d)
+        info = ll.ll_plan_convert(ll.distributed_layout(nreg, nlane, nwave, [d], ca),
+                                  ll.distributed_layout(nreg, nlane, nwave, [d], cb), w).info()
+        if info["kind_name"] == "noop":
+            continue
+        assert info["src_lines_per_access"] == 8 and info["dst_lines_per_access"] == 8, (trial, info["strategy_name"])
+        seen.add(info["strategy_name"])
+    for cid in (1, 2, 3, 4):
+        info = plan_of(wl.config(cid)).info()
+        assert info["src_lines_per_access"] == 8 and info["dst_lines_per_access"] == 8
+    assert len(seen) >= 3
