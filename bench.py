@@ -3,8 +3,8 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--only-main] [--strategy N]
 
-A step is one pass of the headline workload (benchmark configs[1]: 8192 tiles of
-128x128 bf16 transposed through LDS) with inputs already resident in HBM.  The
+A step is one pass of the headline workload (benchmark configuration 2: 8192 tiles of
+128x128 bf16 transposed) with inputs already resident in HBM.  The
 JSON line printed at the end carries the whole-job GB/s (read + write algorithmic
 bytes), a roofline object for the dominant kernel, the CPU oracle timed on a
 bounded sample, and per-config figures for all five configurations next to a
