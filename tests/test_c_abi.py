@@ -1,0 +1,19 @@
+"""The boundary is a C ABI: a plain C99 program includes include/ll.h, links the shared library and
+uses the host entry points (no GPU needed)."""
+import os
+import subprocess
+
+import paper_2505_23819_amd as ll
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_c99_client_builds_and_runs(tmp_path):
+    exe = str(tmp_path / "abi_check")
+    libdir = os.path.dirname(ll.LIBRARY_PATH)
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c", "abi_check.c"), "-o", exe, "-L", libdir, "-lll355", "-Wl,-rpath," + libdir]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, res.stderr
+    assert res.stdout.strip() == "ok"
