@@ -12,6 +12,12 @@ import ctypes
 import os
 from typing import List, Optional, Sequence, Tuple
 
+# PyTorch-ROCm ships its own copy of the HIP runtime.  A process must end up with ONE runtime: if this
+# library were loaded first it would bring in the system copy, PyTorch would then load its own next to
+# it, and launches into the second runtime fail with "no ROCm-capable device is detected".  Importing
+# torch first makes the dynamic linker satisfy this library's dependency with the copy torch loaded.
+import torch  # noqa: F401
+
 from . import build as _build
 
 # ---- status codes and enums of ll.h ------------------------------------------------------------

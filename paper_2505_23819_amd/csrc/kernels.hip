@@ -109,10 +109,24 @@ static unsigned env_inflight_bytes()
     return x >= 4096 ? (unsigned)x : 49152u;   // 32 KiB is as good for the register paths, 128-bit LDS staging needs 48 (5.2 vs 6.15 TB/s)
 }
 
+// Launches go through hipLaunchKernel, whose return value is the status of THIS launch.  (The
+// thread's "last error" is shared with every other user of the runtime in the process: an error
+// left behind by someone else's call would otherwise be reported as ours.)
+static thread_local hipError_t g_launch_status = hipSuccess;
+
+template <typename... P, typename... A>
+static void launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, A &&...args)
+{
+    auto with_params = [&](P... p) {
+        void *ptrs[] = {static_cast<void *>(&p)...};
+        return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds_bytes, stream);
+    };
+    g_launch_status = with_params(static_cast<P>(args)...);
+}
+
 static ll_status check_launch(const char *what)
 {
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(LL_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    if (g_launch_status != hipSuccess) return fail(LL_ERR_DEVICE, "%s: %s", what, hipGetErrorString(g_launch_status));
     return LL_OK;
 }
 
@@ -145,7 +159,7 @@ ll_status launch_copy(const void *src, void *dst, long long bytes, void *stream)
     // 1 MiB of consecutive 4 KiB blocks per XCD: 2 % above the natural round robin (6.77 against 6.62 TB/s at 1 GiB)
     static const int chunk = getenv("LL_COPY_XCD_CHUNK") ? atoi(getenv("LL_COPY_XCD_CHUNK")) : 256;   // experiment knob
     const int bits = chunk > 1 ? 31 - __builtin_clz((unsigned)chunk) : -1;
-    hipLaunchKernelGGL(k_copy, dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(stream), src, dst, nvec, grid, bits);
+    launch(k_copy, dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(stream), src, dst, nvec, grid, bits);
     return check_launch("copy kernel launch");
 }
 
@@ -296,7 +310,7 @@ static ll_status launch_lds_elem_t(const LdsElemArgs &a, int lds_bytes, hipStrea
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
     }
-    hipLaunchKernelGGL((k_lds_elem<W, NV, V>), dim3((unsigned)a.nblocks), dim3(256), (size_t)(lds_bytes + pad), stream, a);
+    launch((k_lds_elem<W, NV, V>), dim3((unsigned)a.nblocks), dim3(256), (size_t)(lds_bytes + pad), stream, a);
     return check_launch("LDS conversion kernel launch");
 }
 
@@ -346,10 +360,10 @@ static ll_status launch_lds_tr_w(const LdsElemArgs &a, int nvec, int lds_bytes, 
     constexpr int V = (W == 1) ? 3 : 2;             // 8-byte chunks
     const dim3 grid((unsigned)a.nblocks), block(256);
     switch (nvec) {
-    case 1: hipLaunchKernelGGL((k_lds_elem<W, 1, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 2: hipLaunchKernelGGL((k_lds_elem<W, 2, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 4: hipLaunchKernelGGL((k_lds_elem<W, 4, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 8: hipLaunchKernelGGL((k_lds_elem<W, 8, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 1: launch((k_lds_elem<W, 1, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 2: launch((k_lds_elem<W, 2, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 4: launch((k_lds_elem<W, 4, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 8: launch((k_lds_elem<W, 8, V, 1>), grid, block, (size_t)lds_bytes, stream, a); break;
     default: return fail(LL_ERR_UNSUPPORTED, "no transposing-read kernel for %d vectors per thread", nvec);
     }
     return check_launch("transposing-read conversion kernel launch");
@@ -542,7 +556,7 @@ static ll_status launch_vec_t(const VecArgs &a, int threads, int lds_bytes, hipS
         unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
         if (alloc > 64u * 1024u) alloc = 64u * 1024u;
         if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
-        hipLaunchKernelGGL((k_vec<W, NVB, TPOSE, XCHG>), dim3((unsigned)a.nblocks), dim3((unsigned)threads),
+        launch((k_vec<W, NVB, TPOSE, XCHG>), dim3((unsigned)a.nblocks), dim3((unsigned)threads),
                            (size_t)alloc, stream, a);
         return check_launch("vector conversion kernel launch");
     }
@@ -687,10 +701,10 @@ static ll_status launch_pull_wv(const PullArgs &a, int src_iters, int lds_bytes,
         if (alloc > (unsigned)lds_bytes) lds_bytes = (int)alloc;
     }
     switch (src_iters) {
-    case 1: hipLaunchKernelGGL((k_pull<W, 1, V>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 2: hipLaunchKernelGGL((k_pull<W, 2, V>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 4: hipLaunchKernelGGL((k_pull<W, 4, V>), grid, block, (size_t)lds_bytes, stream, a); break;
-    case 8: hipLaunchKernelGGL((k_pull<W, 8, V>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 1: launch((k_pull<W, 1, V>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 2: launch((k_pull<W, 2, V>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 4: launch((k_pull<W, 4, V>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 8: launch((k_pull<W, 8, V>), grid, block, (size_t)lds_bytes, stream, a); break;
     default: return fail(LL_ERR_UNSUPPORTED, "no broadcast kernel for %d source vectors per thread", src_iters);
     }
     return check_launch("broadcast conversion kernel launch");
@@ -972,7 +986,7 @@ static ll_status launch_gather_staged_t(const GatherArgs &a, hipStream_t stream)
         unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
         if (alloc > 64u * 1024u) alloc = 64u * 1024u;
         if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
-        hipLaunchKernelGGL((k_gather_staged<W, NREG>), dim3((unsigned)grid), dim3(256), alloc, stream, a);
+        launch((k_gather_staged<W, NREG>), dim3((unsigned)grid), dim3(256), alloc, stream, a);
         return check_launch("gather kernel launch");
     }
 }
@@ -985,7 +999,7 @@ static ll_status launch_gather_t(const GatherArgs &a, hipStream_t stream)
     } else {
         const long long grid = (a.nchunks + 3) / 4;
         if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", grid);
-        hipLaunchKernelGGL((k_gather<W, NREG>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+        launch((k_gather<W, NREG>), dim3((unsigned)grid), dim3(256), 0, stream, a);
         return check_launch("gather kernel launch");
     }
 }
@@ -1156,11 +1170,11 @@ static ll_status launch_gather_general_w(const GatherGenArgs &a, hipStream_t s)
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
             if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
         }
-        hipLaunchKernelGGL((k_gather_general<W, 4>), grid, block, lds_bytes, s, a);
+        launch((k_gather_general<W, 4>), grid, block, lds_bytes, s, a);
     } else if (together == 2) {
-        hipLaunchKernelGGL((k_gather_general<W, 2>), grid, block, lds_bytes, s, a);
+        launch((k_gather_general<W, 2>), grid, block, lds_bytes, s, a);
     } else {
-        hipLaunchKernelGGL((k_gather_general<W, 1>), grid, block, lds_bytes, s, a);
+        launch((k_gather_general<W, 1>), grid, block, lds_bytes, s, a);
     }
     return check_launch("general gather kernel launch");
 }

@@ -629,3 +629,27 @@ def test_entry_points_can_be_captured_in_a_hip_graph():
         assert np.array_equal(wl.to_numpy_bits(dst), oracle.convert(c1.src_bases, c1.dst_bases, wl.to_numpy_bits(new_src))), rep
         assert np.array_equal(wl.to_numpy_bits(out), oracle.gather(c5.src_bases, c5.out_dim_bits, c5.axis,
                                                                    wl.to_numpy_bits(new_inp), new_idx.numpy())), rep
+
+
+def test_layouts_with_a_tile_label():
+    """A `tile` input dim passes through conversions untouched (the tile index is the workgroup
+    dimension) and may not lie on a gather axis; everything else behaves as without it."""
+    rng = np.random.default_rng(123)
+    d_in, nt_bits = 10, 2
+    d = d_in + nt_bits
+    ca = [1 << int(p) for p in rng.permutation(d_in)] + [1 << (d_in + k) for k in range(nt_bits)]
+    cb = [1 << int(p) for p in rng.permutation(d_in)] + [1 << (d_in + k) for k in range(nt_bits)]
+    dims = [(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 6), (ll.LL_IN_WAVE, 2), (ll.LL_IN_TILE, nt_bits)]
+    a, b = ll.ll_layout_create(dims, [2, 5, 5], ca), ll.ll_layout_create(dims, [2, 5, 5], cb)
+    for w in (2, 4):
+        plan = ll.ll_plan_convert(a, b, w)
+        src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=6 << d, dtype=NP_DTYPES[w])
+        assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src))
+    inp = rng.integers(0, 1 << 32, size=3 << d, dtype=np.uint32)
+    for axis in (1, 2):
+        idx = rng.integers(0, 32, size=3 << d, dtype=np.int32)
+        got = run_gather(a, axis, inp, idx, d)
+        assert np.array_equal(got, oracle.gather(ca, [2, 5, 5], axis, inp, idx))
+    with pytest.raises(ll.LLError) as e:
+        run_gather(a, 0, inp, np.zeros(3 << d, dtype=np.int32), d)          # dim 0 is the tile dim
+    assert e.value.status == ll.LL_ERR_TILE_MIXED
