@@ -653,3 +653,21 @@ def test_layouts_with_a_tile_label():
     with pytest.raises(ll.LLError) as e:
         run_gather(a, 0, inp, np.zeros(3 << d, dtype=np.int32), d)          # dim 0 is the tile dim
     assert e.value.status == ll.LL_ERR_TILE_MIXED
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_convert_tiny_broadcast_tiles(w):
+    """Broadcasting conversions of tiles of 2 .. 64 slots (bundled into blocks), ragged tile counts."""
+    rng = np.random.default_rng(800 + w)
+    for dl in range(1, 6):
+        for extra_a, extra_b in ((0, 2), (2, 0), (1, 3), (3, 1)):
+            da, db = dl + extra_a, dl + extra_b
+            ca, cb = surjective_bases(rng, da, dl), surjective_bases(rng, db, dl)
+            plan = ll.ll_plan_convert(ll.ll_layout_create([(ll.LL_IN_REG, da)], [dl], ca),
+                                      ll.ll_layout_create([(ll.LL_IN_REG, db)], [dl], cb), w)
+            assert plan.info()["strategy_name"] == "lds_pull"
+            per16 = max(1, 16 // (w << min(da, db)))
+            for ntiles in (per16, 37 * per16):
+                src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << da, dtype=NP_DTYPES[w])
+                got = run_convert_general(plan, src, da, db)
+                assert np.array_equal(got, oracle.convert_general(ca, cb, dl, src)), (dl, da, db, ntiles)
