@@ -163,7 +163,7 @@ ll_status ll_layout_classify(const ll_layout *layout, uint32_t *flags);
  * index h holds the logical element (A h) xor offset; offset < 2^(output bits).  For a dim of 2^n
  * elements, offset = all ones of that dim flips it, offset = its top bit rolls it by half.
  * ll_layout_apply, ll_compose and ll_invert carry the offset along; ll_plan_convert and ll_gather
- * accept affine layouts when both are bijective; products and divisions do not (LL_ERR_UNSUPPORTED). */
+ * accept affine layouts (gather: bijective ones); products and divisions do not (LL_ERR_UNSUPPORTED). */
 ll_status ll_layout_with_offset(const ll_layout *layout, uint64_t offset, ll_layout **out);
 ll_status ll_layout_get_offset(const ll_layout *layout, uint64_t *offset);
 
@@ -202,7 +202,8 @@ typedef struct {
     int32_t d_dst;              /* index bits of one destination tile (= d unless a layout broadcasts) */
     int32_t elem_bytes;
     uint64_t conv[LL_MAX_BITS]; /* columns of B^-1 o A on the d hardware-index bits (bijective layouts) */
-    uint64_t conv_offset;       /* affine layouts: destination index = conv * h xor conv_offset */
+    uint64_t conv_offset;       /* affine layouts: destination index = conv * h xor conv_offset
+                                 * (broadcasting plans: source index = pull * hB xor conv_offset) */
     uint64_t pull[LL_MAX_BITS]; /* broadcasting layouts: columns of A^+ o B, destination index -> source index */
     int32_t global_vec_bytes;   /* width of every global load and store */
     int32_t src_lines_per_access; /* distinct 128-byte lines one wave-wide load (64 x 16 bytes) touches; 8 = fully coalesced */

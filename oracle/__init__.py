@@ -62,6 +62,9 @@ def _load():
         lib.oracle_convert_general.restype = ctypes.c_int
         lib.oracle_convert_general.argtypes = [u64p, ctypes.c_int, u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        lib.oracle_convert_general_affine.restype = ctypes.c_int
+        lib.oracle_convert_general_affine.argtypes = [u64p, ctypes.c_uint64, ctypes.c_int, u64p, ctypes.c_uint64, ctypes.c_int,
+                                                      ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
         lib.oracle_convert.restype = ctypes.c_int
         lib.oracle_convert.argtypes = [u64p, u64p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                        ctypes.c_void_p, ctypes.c_int64]
@@ -137,6 +140,20 @@ def convert_general(bases_a: Sequence[int], bases_b: Sequence[int], d_out: int, 
                                         src.ctypes.data, dst.ctypes.data, ntiles)
     if rc != OK:
         raise OracleError(rc, "convert_general")
+    return dst
+
+
+def convert_general_affine(bases_a: Sequence[int], off_a: int, bases_b: Sequence[int], off_b: int, d_out: int,
+                           src: np.ndarray) -> np.ndarray:
+    """Broadcasting conversion between affine layouts: dst[hB] = src[A^+(B hB ^ off_b ^ off_a)]."""
+    da, db = len(bases_a), len(bases_b)
+    _check_img(src, da, "src")
+    ntiles = src.size >> da
+    dst = np.empty(ntiles << db, dtype=src.dtype)
+    rc = _load().oracle_convert_general_affine(_u64(bases_a), int(off_a), da, _u64(bases_b), int(off_b), db, d_out,
+                                               src.itemsize, src.ctypes.data, dst.ctypes.data, ntiles)
+    if rc != OK:
+        raise OracleError(rc, "convert_general_affine")
     return dst
 
 

@@ -194,6 +194,44 @@ int oracle_convert_general(const uint64_t *basesA, int dA, const uint64_t *bases
 }
 
 /*
+ * The same with affine layouts (Conclusions: y = A x xor b): slot hA of the
+ * source holds the logical element A(hA) xor offA, slot hB of the destination
+ * must hold B(hB) xor offB; the canonical source slot of a logical element x is
+ * A^+(x xor offA).
+ */
+int oracle_convert_general_affine(const uint64_t *basesA, uint64_t offA, int dA, const uint64_t *basesB,
+                                  uint64_t offB, int dB, int d_out, int elem_bytes, const void *src,
+                                  void *dst, int64_t ntiles)
+{
+    if (!basesA || !basesB || dA < 0 || dA > 30 || dB < 0 || dB > 30 || d_out < 0 || d_out > 30 ||
+        elem_bytes <= 0 || ntiles < 0 || (offA >> d_out) || (offB >> d_out))
+        return ORACLE_ERR_ARG;
+    if (ntiles > 0 && (!src || !dst))
+        return ORACLE_ERR_ARG;
+    uint32_t *invA = (uint32_t *)malloc((1ull << d_out) * sizeof(uint32_t));
+    uint32_t *invB = (uint32_t *)malloc((1ull << d_out) * sizeof(uint32_t));
+    if (!invA || !invB) { free(invA); free(invB); return ORACLE_ERR_ALLOC; }
+    int rc = oracle_right_inverse_table(basesA, dA, d_out, invA);
+    if (rc == ORACLE_OK)
+        rc = oracle_right_inverse_table(basesB, dB, d_out, invB);   /* only to check that B is surjective */
+    if (rc != ORACLE_OK) { free(invA); free(invB); return rc; }
+    const unsigned char *s = (const unsigned char *)src;
+    unsigned char *o = (unsigned char *)dst;
+    const uint64_t nA = 1ull << dA, nB = 1ull << dB;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        for (uint64_t hB = 0; hB < nB; ++hB) {
+            const uint64_t x = oracle_apply(basesB, dB, hB) ^ offB;     /* logical element of slot hB */
+            const uint64_t hA = invA[x ^ offA];                          /* A(hA) xor offA = x */
+            memcpy(o + ((uint64_t)t * nB + hB) * (uint64_t)elem_bytes,
+                   s + ((uint64_t)t * nA + hA) * (uint64_t)elem_bytes, (size_t)elem_bytes);
+        }
+    }
+    free(invA);
+    free(invB);
+    return ORACLE_OK;
+}
+
+/*
  * Layout conversion A -> B on images (Sec. 5.4: the conversion is B^-1 o A).
  * For every tile t and every source hardware index hA:
  *     x  = A(hA)                      (logical element held at hA)

@@ -639,7 +639,7 @@ __global__ __launch_bounds__(256) void k_pull(const PullArgs a)
     const long long blk = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk);
     const long long group = blk >> a.coset_bits;
     const uint32_t c = (uint32_t)(blk & ((1ll << a.coset_bits) - 1));
-    uint32_t cs = 0, cd = 0, cr = 0;
+    uint32_t cs = a.src_xor, cd = 0, cr = a.lds_rd_xor;   // affine layouts: constants of the pull map
     for (int b = 0; b < a.coset_bits; ++b) {
         const uint32_t m = 0u - ((c >> b) & 1u);
         cs ^= a.coset_src[b] & m;

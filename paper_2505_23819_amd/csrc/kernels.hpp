@@ -85,6 +85,7 @@ struct PullArgs {
     uint32_t lds_wr_lane[8], lds_rd_lane[8];
     uint32_t lds_wr_iter[kMaxIter], lds_rd_iter_bit[8];
     uint32_t lds_wr_sub[kMaxSub], lds_rd_sub[kMaxSub];
+    uint32_t src_xor, lds_rd_xor;   // affine layouts: constant on every source index (vector part / in-vector part via LDS)
     int xcd_chunk;      // log2 of the consecutive blocks one XCD takes, -1: natural order (set at launch)
 };
 

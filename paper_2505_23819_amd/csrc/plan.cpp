@@ -541,7 +541,6 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     if (d < 1 || dst->d_in < 1) return fail(LL_ERR_INVALID_ARG, "empty layout");
     if (d > src->d_out || dst->d_in > dst->d_out) {
         // broadcasting (Sec. 5.1, Sec. 5.4 rule 2): destination units pull from canonical source units
-        if (src->offset || dst->offset) return fail(LL_ERR_UNSUPPORTED, "affine layouts with broadcasting are not implemented");
         std::memset(&plan->desc, 0, sizeof(plan->desc));
         plan->desc.elem_bytes = elem_bytes;
         return plan_pull(src, dst, elem_bytes, plan);

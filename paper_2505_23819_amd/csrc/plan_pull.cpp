@@ -32,7 +32,7 @@ static vec xor_sel(const mat &cols, int first, unsigned idx)
 }
 
 // Host-side walk of one block, as the kernel indexes it.
-static ll_status check_pull_block(const PullArgs &a, const mat &rext, int vs, int v, int w, int src_iters, int lds_bytes,
+static ll_status check_pull_block(const PullArgs &a, const mat &rext, vec cconst, int vs, int v, int w, int src_iters, int lds_bytes,
                                   uint32_t cs, uint32_t cd, uint32_t cr)
 {
     const int E = 1 << vs, A = 1 << v;                // elements per global vector / per LDS access
@@ -71,7 +71,7 @@ static ll_status check_pull_block(const PullArgs &a, const mat &rext, int vs, in
                 const uint32_t addr = base + (uint32_t)((s % A) * w);
                 if (addr >= (uint32_t)lds_bytes || held[addr / w] < 0)
                     return fail(LL_ERR_INVALID_ARG, "internal: bad LDS read address in broadcast plan");
-                if ((vec)held[addr / w] != f2::apply(rext, (vec)off + s))
+                if ((vec)held[addr / w] != (f2::apply(rext, (vec)off + s) ^ cconst))
                     return fail(LL_ERR_INVALID_ARG, "internal: broadcast plan does not realise the conversion");
             }
         }
@@ -86,6 +86,8 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     mat aplus;
     if (!f2::right_inverse(A->bases, dl, &aplus)) return fail(LL_ERR_NOT_SURJECTIVE, "source layout does not cover the whole logical tensor");
     const mat r = f2::compose(aplus, B->bases);                 // dB columns in F2^dA
+    // affine layouts: x = B hB ^ b is held by the source slot A^+ (x ^ a) = R hB ^ A^+ (a ^ b)
+    const vec cconst = f2::apply(aplus, A->offset ^ B->offset);
     // pivots of A: the source bits the right inverse may use
     vec pivots = 0;
     for (vec c : aplus) pivots |= c;
@@ -202,6 +204,7 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
         while (v > 0 && (j < v ? rl[j] != (vec(1) << j) : (rl[j] & ((vec(1) << v) - 1)) != 0)) --v;
     for (vec c : comp)
         while (v > 0 && (f2::apply(rext, c) & ((vec(1) << v) - 1)) != 0) --v;
+    while (v > 0 && (cconst & ((vec(1) << v) - 1)) != 0) --v;
     for (int j = 0; j < v; ++j)
         if (rl[j] != (vec(1) << j)) return fail(LL_ERR_INVALID_ARG, "internal: vector bits of a broadcast plan");
     mat wr_lanes, rd_lanes;
@@ -220,6 +223,8 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     a.d_src = dA; a.d_dst = dB; a.group_bits = g; a.coset_bits = (int)comp.size();
     a.src_vec_bits = src_vec_bits;
     a.dst_iters = 1 << (nd - vs - tb);
+    a.src_xor = (uint32_t)(cconst & ~src_low);
+    a.lds_rd_xor = (uint32_t)(f2::apply(sw, cconst & src_low) * (vec)w);
     for (size_t c = 0; c < comp.size(); ++c) {
         const vec sc = f2::apply(rext, comp[c]);
         a.coset_dst[c] = (uint32_t)comp[c];
@@ -248,13 +253,14 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     plan->pull_src_iters = src_iters;
     plan->pull_vec_bits = v;
     {
-        ll_status st = check_pull_block(a, rext, vs, v, w, src_iters, lds_bytes, 0, 0, 0);
-        uint32_t cs = 0, cd = 0, cr = 0;
+        ll_status st = check_pull_block(a, rext, cconst, vs, v, w, src_iters, lds_bytes, a.src_xor, 0, a.lds_rd_xor);
+        const uint32_t cs0 = a.src_xor, cr0 = a.lds_rd_xor;
+        uint32_t cs = cs0, cd = 0, cr = cr0;
         for (int c = 0; c < a.coset_bits && st == LL_OK; ++c) {
-            st = check_pull_block(a, rext, vs, v, w, src_iters, lds_bytes, a.coset_src[c], a.coset_dst[c], a.coset_lds_rd[c]);
+            st = check_pull_block(a, rext, cconst, vs, v, w, src_iters, lds_bytes, cs0 ^ a.coset_src[c], a.coset_dst[c], cr0 ^ a.coset_lds_rd[c]);
             cs ^= a.coset_src[c]; cd ^= a.coset_dst[c]; cr ^= a.coset_lds_rd[c];
         }
-        if (st == LL_OK && a.coset_bits > 1) st = check_pull_block(a, rext, vs, v, w, src_iters, lds_bytes, cs, cd, cr);
+        if (st == LL_OK && a.coset_bits > 1) st = check_pull_block(a, rext, cconst, vs, v, w, src_iters, lds_bytes, cs, cd, cr);
         if (st != LL_OK) return st;
     }
 
@@ -264,6 +270,7 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     desc.d = dA;
     desc.d_dst = dB;
     for (int j = 0; j < dB; ++j) desc.pull[j] = r[j];
+    desc.conv_offset = cconst;       // source index = pull * hB xor conv_offset
     desc.global_vec_bytes = 16;
     desc.lds_write_bytes = desc.lds_read_bytes = w << v;
     desc.lds_bytes = lds_bytes;

@@ -671,3 +671,21 @@ def test_convert_tiny_broadcast_tiles(w):
                 src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << da, dtype=NP_DTYPES[w])
                 got = run_convert_general(plan, src, da, db)
                 assert np.array_equal(got, oracle.convert_general(ca, cb, dl, src)), (dl, da, db, ntiles)
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_convert_broadcast_affine_layouts(w):
+    """Broadcasting and affine at once: the pull map carries a constant, whose low bits move elements
+    inside the staged source vectors."""
+    rng = np.random.default_rng(950 + w)
+    for da, db, dl in [(9, 8, 8), (8, 10, 8), (12, 12, 10), (13, 11, 11), (7, 9, 6)]:
+        for trial in range(2):
+            ca, cb = surjective_bases(rng, da, dl), surjective_bases(rng, db, dl)
+            oa, ob = int(rng.integers(0, 1 << dl)), int(rng.integers(0, 1 << dl))
+            a = ll.ll_layout_with_offset(ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, da - 2)], [dl], ca), oa)
+            b = ll.ll_layout_with_offset(ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, db - 2)], [dl], cb), ob)
+            plan = ll.ll_plan_convert(a, b, w)
+            ntiles = int(rng.integers(1, 30))
+            src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << da, dtype=NP_DTYPES[w])
+            got = run_convert_general(plan, src, da, db)
+            assert np.array_equal(got, oracle.convert_general_affine(ca, oa, cb, ob, dl, src)), (da, db, trial)

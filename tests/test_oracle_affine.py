@@ -104,3 +104,28 @@ def test_gather_under_a_flipped_layout_is_take_along_axis_on_the_logical_tensor(
     h = np.arange(nt << d) & ((1 << d) - 1)
     own = (((h ^ off_rows) >> 4) & 31).astype(np.int32)
     assert np.array_equal(oracle.gather_affine(unit(d), off_rows, dims, 0, inp, own), inp)
+
+
+def test_broadcasting_affine_conversion_pins():
+    rng = np.random.default_rng(6)
+    # zero offsets: the linear broadcasting conversion; bijective layouts: the affine conversion
+    base = wl.PAPER_LAYOUT_A
+    wide = base[:2] + [0] + base[2:]
+    src = rng.integers(0, 1 << 32, size=3 << 9, dtype=np.uint32)
+    assert np.array_equal(oracle.convert_general_affine(wide, 0, base, 0, 8, src), oracle.convert_general(wide, base, 8, src))
+    a, b = wl.random_invertible_bases(51, 8), wl.random_invertible_bases(52, 8)
+    s8 = rng.integers(0, 1 << 32, size=2 << 8, dtype=np.uint32)
+    assert np.array_equal(oracle.convert_general_affine(a, 0x35, b, 0xC1, 8, s8), oracle.convert_affine(a, 0x35, b, 0xC1, s8))
+    # identity layout expanded by one replica bit (a zero column on top) and flipped: every logical
+    # element appears twice, in reversed order
+    d = 6
+    ident = unit(d)
+    flipped_wide = ident + [0]
+    t = rng.integers(0, 1 << 16, size=4 << d, dtype=np.uint16)
+    got = oracle.convert_general_affine(ident, 0, flipped_wide, (1 << d) - 1, d, t)
+    rev = t.reshape(4, 1 << d)[:, ::-1]
+    assert np.array_equal(got.reshape(4, 2, 1 << d), np.stack([rev, rev], axis=1))
+    # collapsing a replicated, flipped source reads the replica whose free bit is zero
+    src_wide = rng.integers(0, 1 << 16, size=4 << (d + 1), dtype=np.uint16)
+    got = oracle.convert_general_affine(flipped_wide, (1 << d) - 1, ident, 0, d, src_wide)
+    assert np.array_equal(got.reshape(4, 1 << d), src_wide.reshape(4, 2, 1 << d)[:, 0, ::-1])
