@@ -1057,7 +1057,7 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
     const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (size_t)first * W, valid * W);
     auto swz = [&](uint32_t addr) { return addr ^ (((addr >> a.swz_shift) & a.swz_mask) << a.swz_to); };
     uint32_t *table = reinterpret_cast<uint32_t *>(lds + ((size_t)block_elems * W));
-    const int ntab = (a.na + 4) / 5;
+    const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;      // an axis of one element still reads table 0 (all zero)
 
     // delta tables
     if (tid < 32u * (uint32_t)ntab) {
@@ -1159,7 +1159,7 @@ static ll_status launch_gather_general_w(const GatherGenArgs &a, hipStream_t s)
 {
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
     const long long block_bytes = (1ll << a.block_bits) * W;
-    const size_t lds_bytes = (size_t)block_bytes + 128u * (size_t)((a.na + 4) / 5);
+    const size_t lds_bytes = (size_t)block_bytes + 128u * (size_t)(a.na > 0 ? (a.na + 4) / 5 : 1);
     const dim3 grid((unsigned)a.nblocks), block(256);
     const int vec_passes = (int)((1ll << a.block_bits) >> VS >> 8), unit_passes = (int)((1ll << a.block_bits) >> (W == 8 ? 9 : 10));
     if (vec_passes < 1 || unit_passes < 1) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than one pass");

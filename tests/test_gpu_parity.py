@@ -689,3 +689,17 @@ def test_convert_broadcast_affine_layouts(w):
             src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << da, dtype=NP_DTYPES[w])
             got = run_convert_general(plan, src, da, db)
             assert np.array_equal(got, oracle.convert_general_affine(ca, oa, cb, ob, dl, src)), (da, db, trial)
+
+
+def test_gather_along_an_axis_of_one_element():
+    """A logical dim of size 1 as the gather axis: every index wraps to 0 and the output equals the input,
+    through the wave kernels and through the workgroup-staged one (narrow lanes)."""
+    rng = np.random.default_rng(11)
+    for nreg, w in ((2, 4), (0, 4), (1, 2)):
+        d = nreg + 6 + 2
+        bases = [1 << k for k in range(d)]
+        layout = ll.distributed_layout(nreg, 6, 2, [0, d], bases)
+        inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=5 << d, dtype=NP_DTYPES[w])
+        idx = rng.integers(-5, 5, size=5 << d, dtype=np.int32)
+        got = run_gather(layout, 0, inp, idx, d)
+        assert np.array_equal(got, inp) and np.array_equal(got, oracle.gather(bases, [0, d], 0, inp, idx))
