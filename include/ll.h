@@ -159,6 +159,13 @@ ll_status ll_layout_mma_swizzle(int m_bits, int n_bits, int vec_elems, int per_p
 #define LL_LAYOUT_MEMORY 8u
 ll_status ll_layout_classify(const ll_layout *layout, uint32_t *flags);
 
+/* Sliced layout (Sec. 4.3 "Sliced Layouts"): the layout of the result of a reduction along logical
+ * dim `dim` (numbered slowest first).  The rows of that dim are removed from the matrix: inputs keep
+ * their labels and sizes, columns that ran along the dim become zero (the result is replicated over
+ * them), an affine constant loses the same bits.  The layout must have at least two logical dims.
+ * A surjective layout stays surjective; ll_plan_convert treats the zero columns as broadcasting. */
+ll_status ll_layout_slice(const ll_layout *layout, int dim, ll_layout **out);
+
 /* Affine layouts (Conclusions: flips and slices are y = A x xor b).  A copy of `layout` in which
  * index h holds the logical element (A h) xor offset; offset < 2^(output bits).  For a dim of 2^n
  * elements, offset = all ones of that dim flips it, offset = its top bit rolls it by half.
@@ -253,8 +260,10 @@ typedef struct {
  * the register <-> memory mapping of Sec. 5.3; the input bit counts must match and no tile label
  * may be present.
  * Both layouts must be surjective (LL_ERR_NOT_SURJECTIVE otherwise).  If both are bijective they
- * must have the same input dims (LL_ERR_DIM_MISMATCH), and a `tile` input dim, if present, must
- * map identically in both (LL_ERR_TILE_MIXED).  If a layout is not injective (broadcasting:
+ * must have the same number of input bits and the same `tile` bits (LL_ERR_DIM_MISMATCH), and the
+ * tile bits must map identically in both (LL_ERR_TILE_MIXED); the split of the remaining bits over
+ * registers, lanes and waves may differ (the images are flat per tile; such a plan is classified
+ * as a shared-memory conversion, since the register / lane classes do not line up).  If a layout is not injective (broadcasting:
  * zero or dependent columns, Sec. 5.1) the two may have different input dims; the plan then
  * pulls every destination unit's logical element from the source unit given by the right
  * inverse with free variables zero (Sec. 5.4 rule 2), source tiles hold 2^d and destination

@@ -263,4 +263,4 @@ def wavefronts(mem_bases: Sequence[int], dist_bases: Sequence[int], nreg: int, n
 from .algebra import OLayout, contiguity, divide_left, divide_left_permuting, identity_tile, product  # noqa: E402
 from .families import (blocked_layout, identity_map, is_distributed_layout, is_memory_layout,  # noqa: E402
                        mfma_accumulator_tile, mfma_operand_tile, mma_swizzle_layout, mma_swizzle_offset,
-                       product_of)
+                       product_of, slice_layout)

@@ -95,6 +95,21 @@ def mma_swizzle_layout(m_bits: int, n_bits: int, vec: int, per_phase: int, max_p
     return OLayout([(4, m_bits + n_bits)], [m_bits, n_bits], bases)
 
 
+def slice_layout(lay: OLayout, dim: int) -> OLayout:
+    """Sec. 4.3 "Sliced Layouts" (the layout of the result of a reduction along `dim`): removing a
+    logical dim is the linear map that deletes that dim's rows of the matrix.  Inputs keep their
+    labels and sizes; columns that ran along the removed dim become zero (the result is broadcast
+    over them), and a surjective layout stays surjective."""
+    if not 0 <= dim < len(lay.out_dims) or len(lay.out_dims) < 2:
+        raise ValueError("slice needs a layout of at least two dims and a dim inside it")
+    m = to_matrix(lay)
+    lo = sum(lay.out_dims[dim + 1:])                 # flat position of bit 0 of `dim`
+    keep = [r for r in range(lay.d_out) if not lo <= r < lo + lay.out_dims[dim]]
+    out_dims = [n for j, n in enumerate(lay.out_dims) if j != dim]
+    bases = [int(sum(int(m[r, c]) << i for i, r in enumerate(keep))) for c in range(lay.d_in)]
+    return OLayout(list(lay.in_dims), out_dims, bases)
+
+
 def is_distributed_layout(lay: OLayout) -> bool:
     """Def. "Distributed Layout": surjective, every column has at most one non-zero bit, and no
     non-zero column is repeated (a permutation matrix with zero columns interleaved)."""

@@ -38,7 +38,7 @@ EXPORTED_SYMBOLS = [
     "ll_gather", "ll_copy", "ll_last_error", "ll_product_dimwise", "ll_divide_left",
     "ll_divide_left_permuted", "ll_contiguity", "ll_layout_identity", "ll_layout_blocked",
     "ll_layout_mfma_accumulator", "ll_layout_mfma_operand", "ll_layout_mma_swizzle", "ll_layout_classify",
-    "ll_gather_info", "ll_layout_with_offset", "ll_layout_get_offset",
+    "ll_gather_info", "ll_layout_with_offset", "ll_layout_get_offset", "ll_layout_slice",
 ]
 GATHER_KERNEL_NAMES = ["shuffle", "wave_staged", "block_staged"]
 
@@ -287,6 +287,11 @@ def ll_gather_info(layout: Layout, axis: int, elem_bytes: int) -> dict:
 def ll_layout_with_offset(layout: Layout, offset: int) -> Layout:
     h = ctypes.c_void_p()
     return _made(_lib.ll_layout_with_offset(layout._h, ctypes.c_uint64(int(offset)), ctypes.byref(h)), h)
+
+
+def ll_layout_slice(layout: Layout, dim: int) -> Layout:
+    h = ctypes.c_void_p()
+    return _made(_lib.ll_layout_slice(layout._h, ctypes.c_int(int(dim)), ctypes.byref(h)), h)
 
 
 def ll_layout_get_offset(layout: Layout) -> int:

@@ -161,6 +161,34 @@ ll_status ll_layout_with_offset(const ll_layout *layout, uint64_t offset, ll_lay
     }
 }
 
+ll_status ll_layout_slice(const ll_layout *layout, int dim, ll_layout **out)
+{
+    try {
+        if (!out) return fail(LL_ERR_INVALID_ARG, "out is null");
+        *out = nullptr;
+        if (!layout) return fail(LL_ERR_INVALID_ARG, "layout is null");
+        if (layout->n_out < 2) return fail(LL_ERR_INVALID_ARG, "a slice needs at least two logical dims");
+        if (dim < 0 || dim >= layout->n_out) return fail(LL_ERR_INVALID_ARG, "dim %d is not one of the %d logical dims", dim, layout->n_out);
+        // flat output bits [lo, lo + nb) belong to `dim` (last dim fastest): squeeze them out
+        int lo = 0;
+        for (int j = dim + 1; j < layout->n_out; ++j) lo += layout->out_dims[j].nbits;
+        const int nb = layout->out_dims[dim].nbits;
+        const f2::vec low = (f2::vec(1) << lo) - 1;
+        auto squeeze = [&](f2::vec x) { return (x & low) | ((x >> (lo + nb)) << lo); };
+        ll_out_dim dims[LL_MAX_OUT_DIMS];
+        int n = 0;
+        for (int j = 0; j < layout->n_out; ++j)
+            if (j != dim) dims[n++] = layout->out_dims[j];
+        f2::mat cols;
+        for (f2::vec c : layout->bases) cols.push_back(squeeze(c));
+        ll_status st = ll::make_layout(layout->in_dims, layout->n_in, dims, n, cols, out);
+        if (st == LL_OK) (*out)->offset = squeeze(layout->offset);
+        return st;
+    } catch (...) {   // nothing may propagate across the C ABI
+        return ll::fail(LL_ERR_INVALID_ARG, "ll_layout_slice: out of host memory");
+    }
+}
+
 ll_status ll_layout_get_offset(const ll_layout *layout, uint64_t *offset)
 {
     try {

@@ -705,6 +705,7 @@ static ll_status launch_pull_wv(const PullArgs &a, int src_iters, int lds_bytes,
     case 2: launch((k_pull<W, 2, V>), grid, block, (size_t)lds_bytes, stream, a); break;
     case 4: launch((k_pull<W, 4, V>), grid, block, (size_t)lds_bytes, stream, a); break;
     case 8: launch((k_pull<W, 8, V>), grid, block, (size_t)lds_bytes, stream, a); break;
+    case 16: launch((k_pull<W, 16, V>), grid, block, (size_t)lds_bytes, stream, a); break;
     default: return fail(LL_ERR_UNSUPPORTED, "no broadcast kernel for %d source vectors per thread", src_iters);
     }
     return check_launch("broadcast conversion kernel launch");

@@ -14,6 +14,7 @@ constexpr int kMaxThreadBits = 10;   // up to 1024 threads per workgroup
 constexpr int kMaxIter = 32;         // 16-byte vectors per thread
 constexpr int kMaxSub = 16;          // LDS accesses per 16-byte vector (1-byte elements: 16)
 constexpr int kMaxCosetBits = 24;
+constexpr int kPullMaxSrcIters = 16; // source vectors one thread of the broadcast kernel stages
 
 // LDS-staged conversion with element-wide (or common-vector-wide) LDS accesses
 // (paper Sec. 5.4 "Optimal Swizzling"; vector width = the common contiguous elements).

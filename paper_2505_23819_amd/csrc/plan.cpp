@@ -535,6 +535,7 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     bool memory_side = false;
     for (int i = 0; i < src->n_in; ++i) memory_side |= src->in_dims[i].label == LL_IN_OFFSET;
     for (int i = 0; i < dst->n_in; ++i) memory_side |= dst->in_dims[i].label == LL_IN_OFFSET;
+    const bool memory_image = memory_side;
     const int d = src->d_in;
     if (f2::rank(src->bases) < src->d_out || f2::rank(dst->bases) < dst->d_out)
         return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
@@ -551,7 +552,13 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
         if (src->bits_of(LL_IN_TILE) || dst->bits_of(LL_IN_TILE))
             return fail(LL_ERR_DIM_MISMATCH, "a memory layout cannot be converted to or from a layout with a tile label");
     } else if (!same_inputs(src, dst)) {
-        return fail(LL_ERR_DIM_MISMATCH, "source and destination layouts have different input dims");
+        // The same tile split differently over registers, lanes and waves: the images are still
+        // 2^d slots per tile, so the conversion is the same B^-1 o A on flat indices.  The register /
+        // lane / wave classes of the two sides do not line up, so no class-based shortcut applies
+        // (handled like a memory image).  Tiles must agree.
+        if (src->d_in != dst->d_in || src->bits_of(LL_IN_TILE) != dst->bits_of(LL_IN_TILE))
+            return fail(LL_ERR_DIM_MISMATCH, "source and destination layouts have different input dims");
+        memory_side = true;
     }
 
     // B^-1 o A (Sec. 5.4)
@@ -560,7 +567,7 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     const mat p = f2::compose(binv, src->bases);
 
     // a tile label must pass through untouched
-    const int tile_first = memory_side ? d : src->first_bit_of(LL_IN_TILE);
+    const int tile_first = memory_image ? d : src->first_bit_of(LL_IN_TILE);
     for (int k = 0; k < d; ++k) {
         const vec tile_mask = ((vec(1) << d) - 1) & ~((vec(1) << tile_first) - 1);
         if (k >= tile_first ? p[k] != (vec(1) << k) : (p[k] & tile_mask) != 0)

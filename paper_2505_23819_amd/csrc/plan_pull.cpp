@@ -78,7 +78,9 @@ static ll_status check_pull_block(const PullArgs &a, const mat &rext, vec cconst
     return LL_OK;
 }
 
-ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan)
+// One attempt with blocks of at most 2^n_max elements.  *too_large: the source vectors behind such a
+// block exceed what one workgroup stages (a source whose 16-byte vectors hold few canonical slots).
+static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int mode, int n_max, ll_plan *plan, bool *too_large)
 {
     const LdsModel hw;
     const int dA = A->d_in, dB = B->d_in, dl = A->d_out;
@@ -92,13 +94,6 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     vec pivots = 0;
     for (vec c : aplus) pivots |= c;
 
-    // A destination that replicates 4x or more makes the conversion write-dominated: destination
-    // runs first, and 16 KiB blocks (four stores in flight per thread measured fastest on MI355X;
-    // read-dominated and balanced conversions do best at 8 KiB).
-    int mode = dB > dl + 1 ? 1 : 0;
-    if (const char *e = getenv("LL_PULL_MODE")) mode = atoi(e);
-    const unsigned max_block = env_bytes("LL_BLOCK_BYTES", mode == 1 ? 16384u : 8192u);
-    const int n_max = std::max(vs + tb, ilog2p(max_block / (unsigned)w));
     const int g = std::max(0, n_max - std::min(dA, dB));        // bundle small tiles
     const int Ds = dA + g, Dd = dB + g;
     if (std::max(Ds, Dd) + ilog2p((unsigned)w) > 31) return fail(LL_ERR_UNSUPPORTED, "tile too large");
@@ -194,7 +189,10 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     if ((int)comp.size() > kMaxCosetBits) return fail(LL_ERR_UNSUPPORTED, "internal: too many blocks per tile");
     const int src_vec_bits = ns - vs;
     const int src_iters = std::max(1, 1 << std::max(0, src_vec_bits - tb));
-    if (src_iters > 8) return fail(LL_ERR_UNSUPPORTED, "internal: source block too large");
+    if (src_iters > kPullMaxSrcIters) {
+        *too_large = true;
+        return fail(LL_ERR_UNSUPPORTED, "internal: source block too large");
+    }
 
     // LDS access width: 2^v elements where the conversion keeps the low v bits of a slot index in
     // place (Sec. 5.3 "Generalized Vectorization"), element-wide otherwise
@@ -287,4 +285,25 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     return LL_OK;
 }
 
+ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan)
+{
+    const int vs = ilog2p(16u / (unsigned)w), tb = 8;
+    // A destination that replicates 4x or more makes the conversion write-dominated: destination
+    // runs first, and 16 KiB blocks (four stores in flight per thread measured fastest on MI355X;
+    // read-dominated and balanced conversions do best at 8 KiB).
+    int mode = B->d_in > A->d_out + 1 ? 1 : 0;
+    if (const char *e = getenv("LL_PULL_MODE")) mode = atoi(e);
+    const unsigned max_block = env_bytes("LL_BLOCK_BYTES", mode == 1 ? 16384u : 8192u);
+    // A sparse source (few canonical slots per 16-byte vector, as in the slice left by a reduction
+    // along the register-fastest dim) needs many vectors per destination element: shrink the block
+    // until they fit.  At one vector per thread on the destination side a block needs at most one
+    // source vector per element, 2^vs per thread, which the kernel covers.
+    for (int n_max = std::max(vs + tb, ilog2p(max_block / (unsigned)w));; --n_max) {
+        bool too_large = false;
+        const ll_status st = plan_pull_at(A, B, w, mode, n_max, plan, &too_large);
+        if (st == LL_OK || !too_large || n_max == vs + tb) return st;
+    }
+}
+
 }  // namespace ll
+

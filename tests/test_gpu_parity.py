@@ -703,3 +703,74 @@ def test_gather_along_an_axis_of_one_element():
         idx = rng.integers(-5, 5, size=5 << d, dtype=np.int32)
         got = run_gather(layout, 0, inp, idx, d)
         assert np.array_equal(got, inp) and np.array_equal(got, oracle.gather(bases, [0, d], 0, inp, idx))
+
+
+# ---------------------------------------------------------------------------------------------
+# Sliced layouts (Sec. 4.3): the result of a reduction, converted to compact and to other slices
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_convert_sliced_layouts(w):
+    """A 2-D and a 3-D blocked tensor reduced along each dim: the slice built by the library must
+    equal the oracle's, and its data must convert into a compact blocked layout of what is left,
+    and into the slice of a differently blocked parent."""
+    parents = [
+        ([1, 2], [3, 3], [1, 1], [1, 0]),             # 32 x 64, rows fastest within lanes
+        ([2, 1], [2, 4], [0, 2], [0, 1]),             # 16 x 128
+        ([1, 1, 1], [2, 2, 2], [1, 0, 1], [2, 0, 1]),  # 16 x 8 x 16
+    ]
+    others = [
+        ([2, 1], [3, 3], [0, 2], [0, 1]),
+        ([1, 2], [2, 4], [1, 1], [1, 0]),
+        ([0, 2, 1], [3, 1, 2], [1, 0, 1], [1, 2, 0]),
+    ]
+    rng = np.random.default_rng(8800 + w)
+    for (r, t, wv, order), (r2, t2, wv2, order2) in zip(parents, others):
+        parent = ll.ll_layout_blocked(r, t, wv, order)
+        oparent = oracle.blocked_layout(r, t, wv, order)
+        other = ll.ll_layout_blocked(r2, t2, wv2, order2)
+        oother = oracle.blocked_layout(r2, t2, wv2, order2)
+        assert oparent.out_dims == oother.out_dims
+        d_in = oparent.d_in
+        for dim in range(len(order)):
+            s, os_ = ll.ll_layout_slice(parent, dim), oracle.slice_layout(oparent, dim)
+            assert s.bases == os_.bases and s.out_dims == os_.out_dims
+            rest = os_.out_dims
+            dl = sum(rest)
+            # compact destination: every remaining element once, 2 registers, then lanes, then waves
+            nl = min(6, dl - 1)
+            compact = ll.ll_layout_create([(ll.LL_IN_REG, 1), (ll.LL_IN_LANE, nl), (ll.LL_IN_WAVE, dl - 1 - nl)],
+                                          rest, [1 << k for k in range(dl)])
+            ntiles = int(rng.integers(1, 9)) * 16
+            src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d_in, dtype=NP_DTYPES[w])
+            plan = ll.ll_plan_convert(s, compact, w)
+            assert plan.info()["kind_name"] == "broadcast"
+            got = run_convert_general(plan, src, d_in, dl)
+            assert np.array_equal(got, oracle.convert_general(os_.bases, [1 << k for k in range(dl)], dl, src)), (order, dim)
+            # slice of another blocking of the same tensor
+            s2, os2 = ll.ll_layout_slice(other, dim), oracle.slice_layout(oother, dim)
+            assert s2.bases == os2.bases
+            plan = ll.ll_plan_convert(s, s2, w)
+            got = run_convert_general(plan, src, d_in, oother.d_in)
+            assert np.array_equal(got, oracle.convert_general(os_.bases, os2.bases, dl, src)), (order, dim, "slice")
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_convert_between_different_register_lane_wave_splits(w):
+    """Bijective layouts of one tile that split its 2^d slots differently over registers, lanes and
+    waves: the images are flat per tile, so the conversion is B^-1 o A on flat indices."""
+    rng = np.random.default_rng(9100 + w)
+    for d, (ra, la, wa), (rb, lb, wb) in [(10, (2, 6, 2), (4, 6, 0)), (12, (3, 6, 3), (5, 5, 2)), (9, (0, 6, 3), (3, 6, 0))]:
+        ca, cb = random_invertible(rng, d), random_invertible(rng, d)
+        a = ll.distributed_layout(ra, la, wa, [d], ca)
+        b = ll.distributed_layout(rb, lb, wb, [d], cb)
+        plan = ll.ll_plan_convert(a, b, w)
+        ntiles = int(rng.integers(1, 20))
+        src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+        assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src))
+    # blocked layouts of a 64 x 64 tile with 4 and with 16 registers per lane
+    a = ll.ll_layout_blocked([0, 2], [3, 3], [3, 1], [1, 0])
+    b = ll.ll_layout_blocked([2, 2], [2, 4], [2, 0], [0, 1])
+    oa, ob = oracle.blocked_layout([0, 2], [3, 3], [3, 1], [1, 0]), oracle.blocked_layout([2, 2], [2, 4], [2, 0], [0, 1])
+    plan = ll.ll_plan_convert(a, b, w)
+    src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=7 << 12, dtype=NP_DTYPES[w])
+    assert np.array_equal(run_convert(plan, src, 12), oracle.convert(oa.bases, ob.bases, src))

@@ -378,3 +378,33 @@ def test_affine_plan_reports_the_constant():
             if (int(h) >> k) & 1:
                 hp ^= info["conv"][k]
         assert want[hp] == h
+
+
+def test_slice_matches_the_oracle():
+    rng = np.random.default_rng(31)
+    for _ in range(40):
+        nd = int(rng.integers(2, 4))
+        r = [int(x) for x in rng.integers(0, 3, size=nd)]
+        t = [int(x) for x in rng.integers(0, 3, size=nd)]
+        w = [int(x) for x in rng.integers(0, 2, size=nd)]
+        order = [int(x) for x in rng.permutation(nd)]
+        if sum(r) + sum(t) + sum(w) == 0:
+            continue
+        dim = int(rng.integers(0, nd))
+        _same(ll.ll_layout_slice(ll.ll_layout_blocked(r, t, w, order), dim),
+              oracle.slice_layout(oracle.blocked_layout(r, t, w, order), dim))
+    # a general (non-permutation) layout and an affine constant
+    c4 = wl.config(4)
+    lay = ll.ll_layout_create([(ll.LL_IN_REG, 6), (ll.LL_IN_LANE, 6), (ll.LL_IN_WAVE, 4)], [5, 5, 6], c4.src_bases)
+    ref = oracle.OLayout([(0, 6), (1, 6), (2, 4)], [5, 5, 6], list(c4.src_bases))
+    for dim in range(3):
+        _same(ll.ll_layout_slice(lay, dim), oracle.slice_layout(ref, dim))
+    flipped = ll.ll_layout_with_offset(lay, 0b10110_01101_110011)
+    assert ll.ll_layout_get_offset(ll.ll_layout_slice(flipped, 1)) == 0b10110_110011
+    for bad in (-1, 3):
+        with pytest.raises(ll.LLError) as e:
+            ll.ll_layout_slice(lay, bad)
+        assert e.value.status == ll.LL_ERR_INVALID_ARG
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_layout_slice(ll.ll_layout_identity(ll.LL_IN_REG, 0, 3, 1), 0)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG

@@ -151,3 +151,48 @@ def test_family_definitions():
     assert not oracle.is_memory_layout(OLayout([(OFFSET, 4)], [2, 2], [1, 2, 3, 3]))   # singular
     assert oracle.is_memory_layout(OLayout([(OFFSET, 8)], [4, 4], a.bases))             # a permutation matrix qualifies
     assert not oracle.is_memory_layout(wide)                        # not square
+
+
+def coords_of(x, dims):
+    out = []
+    for b in reversed(dims):
+        out.append(x & ((1 << b) - 1))
+        x >>= b
+    return out[::-1]
+
+
+def test_slice_drops_the_coordinate_of_the_reduced_dim():
+    """Sec. 4.3 "Sliced Layouts" by its meaning: wherever the layout put element (c_0, .., c_n), the
+    slice along dim j puts (c_0, .., c_n) without c_j; checked for every hardware index of random
+    blocked layouts.  The Remark's two facts: still surjective, and exactly the input bits that ran
+    along the reduced dim turn into zero columns."""
+    rng = np.random.default_rng(77)
+    for _ in range(30):
+        nd = int(rng.integers(2, 4))
+        r = [int(x) for x in rng.integers(0, 3, size=nd)]
+        t = [int(x) for x in rng.integers(0, 3, size=nd)]
+        w = [int(x) for x in rng.integers(0, 2, size=nd)]
+        order = [int(x) for x in rng.permutation(nd)]
+        lay = oracle.blocked_layout(r, t, w, order)
+        for dim in range(nd):
+            s = oracle.slice_layout(lay, dim)
+            rest = [b for j, b in enumerate(lay.out_dims) if j != dim]
+            assert s.out_dims == rest and s.in_dims == lay.in_dims
+            images = set()
+            for h in range(1 << lay.d_in):
+                c = coords_of(oracle.apply(lay.bases, h), lay.out_dims)
+                del c[dim]
+                assert oracle.apply(s.bases, h) == flat(c, rest)
+                images.add(flat(c, rest))
+            assert len(images) == 1 << sum(rest)                      # surjective
+            assert sum(1 for b in s.bases if b == 0) == lay.out_dims[dim]
+            assert oracle.is_distributed_layout(s)
+
+
+def test_slice_of_layout_a_along_each_dim():
+    """Layout A (Sec. 4.1, 16 x 16): along dim 1 (j) the slice keeps the i bits, along dim 0 the j bits."""
+    a = OLayout([(REG, 2), (LANE, 5), (WAVE, 1)], [4, 4], wl.PAPER_LAYOUT_A)
+    assert oracle.slice_layout(a, 1).bases == [b >> 4 for b in wl.PAPER_LAYOUT_A]
+    assert oracle.slice_layout(a, 0).bases == [b & 15 for b in wl.PAPER_LAYOUT_A]
+    with pytest.raises(ValueError):
+        oracle.slice_layout(oracle.slice_layout(a, 0), 0)

@@ -183,8 +183,14 @@ def test_plan_errors():
     ident = [1 << k for k in range(d)]
     a = ll.distributed_layout(2, 5, 1, [d], ident)
     with pytest.raises(ll.LLError) as e:
-        ll.ll_plan_convert(a, ll.distributed_layout(3, 5, 0, [d], ident), 4)
-    assert e.value.status == ll.LL_ERR_DIM_MISMATCH
+        ll.ll_plan_convert(a, ll.distributed_layout(3, 5, 1, [d + 1], ident + [1 << d]), 4)
+    assert e.value.status == ll.LL_ERR_DIM_MISMATCH                  # output spaces differ
+    tiled = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 5), (ll.LL_IN_TILE, 1)], [d], ident)
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_plan_convert(a, tiled, 4)
+    assert e.value.status == ll.LL_ERR_DIM_MISMATCH                  # tile bits differ
+    # the same tile split differently over registers, lanes and waves is a flat re-indexing
+    assert ll.ll_plan_convert(a, ll.distributed_layout(3, 5, 0, [d], ident), 4).info()["strategy_name"] == "copy"
     with pytest.raises(ll.LLError) as e:
         ll.ll_plan_convert(a, a, 3)
     assert e.value.status == ll.LL_ERR_INVALID_ARG
@@ -428,3 +434,20 @@ def test_every_plan_keeps_wave_accesses_in_eight_lines():
         info = plan_of(wl.config(cid)).info()
         assert info["src_lines_per_access"] == 8 and info["dst_lines_per_access"] == 8
     assert len(seen) >= 3
+
+
+def test_sparse_sliced_sources_plan():
+    """The slice left by a reduction along the dim the registers run along keeps one element in 2^r
+    slots: for 1-byte elements and 16 registers per lane every 16-byte source vector holds a single
+    useful byte.  The planner shrinks the destination block until the source vectors behind it fit
+    one workgroup (LDS within 64 KiB), for every element size."""
+    for regs_along_reduced in (2, 3, 4):
+        parent = ll.ll_layout_blocked([1, regs_along_reduced], [3, 3], [1, 1], [1, 0])
+        s = ll.ll_layout_slice(parent, 1)
+        dl = sum(s.out_dims)
+        compact = ll.ll_layout_create([(ll.LL_IN_REG, 1), (ll.LL_IN_LANE, dl - 1)], s.out_dims, [1 << k for k in range(dl)])
+        for w in (1, 2, 4, 8):
+            for a, b in ((s, compact), (compact, s), (s, s)):
+                info = ll.ll_plan_convert(a, b, w).info()
+                assert info["kind_name"] == "broadcast" and 0 < info["lds_bytes"] <= 65536
+                assert info["predicted_wavefronts_write"] >= 1
