@@ -45,7 +45,8 @@ typedef enum {
     LL_ERR_NOT_SURJECTIVE = 3,   /* a right inverse was requested of a non-surjective layout */
     LL_ERR_NOT_INJECTIVE = 4,    /* the operation needs an injective layout (gather; inversion) */
     LL_ERR_TILE_MIXED = 5,       /* the conversion would move data between tiles */
-    LL_ERR_AXIS_NOT_IN_WAVE = 6, /* gather axis is not contained in one wave (Sec. 5.5) */
+    LL_ERR_AXIS_NOT_IN_WAVE = 6, /* gather axis is not contained in one wave (Sec. 5.5); kept for ABI stability,
+                                    no longer returned: see ll_gather */
     LL_ERR_UNSUPPORTED = 7,      /* valid request outside what is implemented */
     LL_ERR_DEVICE = 8,           /* a HIP call failed; see ll_last_error() */
     LL_ERR_NOT_DIVISIBLE = 9     /* the layout does not have the tile as a left factor (Def. "Left Division") */
@@ -288,14 +289,17 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
  *  - lane bits only (the paper's condition, Sec. 5.5, with one round): cross-lane shuffles, or
  *    wave-private LDS staging when a lane holds more than 16 bytes;
  *  - register and / or wave bits as well: the aligned block of image elements those bits span is
- *    staged in workgroup LDS (at most 64 KiB).  If it does not fit: LL_ERR_AXIS_NOT_IN_WAVE when
- *    the axis crosses waves, LL_ERR_UNSUPPORTED otherwise;
+ *    staged in workgroup LDS when it is at most 64 KiB; a larger block is gathered straight from
+ *    memory, element by element, inside that block (slower: every element is its own access).
+ *    Sec. 5.5's condition (no wave bits on the axis) is reported by ll_gather_info
+ *    (axis_wave_bits == 0) and is not an error here;
  *  - tile bits: LL_ERR_TILE_MIXED.
  * Pointers are DEVICE pointers.  Asynchronous on hip_stream. */
 typedef enum {
     LL_GATHER_SHUFFLE = 0,       /* one ds_bpermute_b32 per 32-bit piece of an element */
     LL_GATHER_WAVE_STAGED = 1,   /* coalesced access, source rows staged in wave-private LDS */
-    LL_GATHER_BLOCK_STAGED = 2   /* general: a block closed under the axis staged in workgroup LDS */
+    LL_GATHER_BLOCK_STAGED = 2,  /* general: a block closed under the axis staged in workgroup LDS */
+    LL_GATHER_GLOBAL = 3         /* the block exceeds LDS: element-wide reads from memory inside the block */
 } ll_gather_kernel;
 
 typedef struct {
@@ -304,7 +308,8 @@ typedef struct {
     int32_t axis_lane_bits;
     int32_t axis_wave_bits;
     int32_t paper_rounds;        /* 2^axis_reg_bits: the shuffle rounds of Sec. 5.5 */
-    int32_t block_bytes;         /* bytes of `in` one wave (kernels 0, 1) or workgroup (kernel 2) stages */
+    int32_t block_bytes;         /* bytes of `in` one wave (kernels 0, 1) or workgroup (kernel 2) stages; kernel 3:
+                                    the aligned block a source lies in (saturates at 2^31 - 1) */
 } ll_gather_desc;
 
 /* What ll_gather would do for this layout, axis and element size (same checks and errors). */

@@ -1185,7 +1185,7 @@ ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *st
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     const long long block_bytes = (1ll << a.block_bits) * elem_bytes;
     if (block_bytes < 4096 || block_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "gather block of %lld bytes", block_bytes);
-    if (a.na < 0 || a.na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", a.na);
+    if (a.na < 0 || a.na > 16) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", a.na);   // four delta tables
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {
     case 1: return launch_gather_general_w<1>(a, s);
@@ -1194,6 +1194,118 @@ ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *st
     case 8: return launch_gather_general_w<8>(a, s);
     default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
     }
+}
+
+// Gather for axes whose block does not fit LDS: the source element is read straight from memory at
+// (own index) ^ delta(x), with the same linear delta tables as above (element units here, up to 6
+// tables of 32 entries for an axis of 2^30).  A workgroup takes kGlobalPasses * 256 units of
+// consecutive output elements: coalesced index loads and output stores, element-wide source loads
+// that stay inside the aligned block of 2^block_bits elements around the element (L2 / MALL serve
+// the re-reads when the block order keeps one block on one XCD).
+constexpr int kGlobalPasses = 4;
+template <int W>
+__global__ __launch_bounds__(256) void k_gather_global(const GatherGenArgs a)
+{
+    __shared__ uint32_t table[6 * 32];
+    constexpr int UB = (W == 8) ? 1 : 2;
+    constexpr int UE = 1 << UB;
+    constexpr int CB = UB + 8 + 2;                    // log2 elements per workgroup (4 passes)
+    static_assert(kGlobalPasses == 4, "CB assumes four passes");
+    const uint32_t tid = threadIdx.x;
+    const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;
+    if (tid < 32u * (uint32_t)ntab) {
+        const uint32_t x = (tid & 31u) << (5u * (tid >> 5));
+        uint32_t dl = 0;
+        for (int b = 0; b < a.na; ++b) dl ^= a.delta[b] & (0u - ((x >> b) & 1u));
+        table[tid] = dl;
+    }
+    const long long first = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk) << CB;
+    const long long left = a.total_elems - first;
+    const uint32_t valid = left >= (1ll << CB) ? (1u << CB) : (uint32_t)left;     // a multiple of UE
+    const __amdgpu_buffer_rsrc_t rix = make_rsrc(reinterpret_cast<const unsigned char *>(a.idx) + (size_t)first * 4, valid * 4);
+    const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (size_t)first * W, valid * W);
+    const unsigned char *in = static_cast<const unsigned char *>(a.in);
+
+    uint32_t own_t = a.own_const;
+    {
+        const unsigned long long f = (unsigned long long)first;
+        for (int b = CB; b < 32; ++b) own_t ^= a.own_bit[b] & (0u - (uint32_t)((f >> b) & 1ull));
+#pragma unroll
+        for (int b = 0; b < 8; ++b) own_t ^= a.own_bit[UB + b] & (0u - ((tid >> b) & 1u));
+    }
+    const uint32_t own_s[4] = {0u, a.own_bit[0], a.own_bit[1], a.own_bit[0] ^ a.own_bit[1]};
+    const uint32_t own_q[4] = {0u, a.own_bit[UB + 8], a.own_bit[UB + 9], a.own_bit[UB + 8] ^ a.own_bit[UB + 9]};
+
+    uint32_t ix[kGlobalPasses][UE];
+#pragma unroll
+    for (int q = 0; q < kGlobalPasses; ++q) {
+        if constexpr (UE == 4) {
+            const u32x4 t = buf_load16(rix, (tid + 256u * q) * 16u);
+            ix[q][0] = t.x; ix[q][1] = t.y; ix[q][2] = t.z; ix[q][3] = t.w;
+        } else {
+            const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rix, (tid + 256u * q) * 8u, 0, kStream);
+            ix[q][0] = t.x; ix[q][1] = t.y;
+        }
+    }
+    __syncthreads();
+    uint32_t o[kGlobalPasses][4];
+#pragma unroll
+    for (int q = 0; q < kGlobalPasses; ++q) {
+        const uint32_t unit = tid + 256u * q;
+        o[q][0] = o[q][1] = o[q][2] = o[q][3] = 0u;
+        if (unit * UE < valid) {                      // the source of a valid element is valid: same tile
+#pragma unroll
+            for (int s = 0; s < UE; ++s) {
+                const uint32_t x = (ix[q][s] ^ own_t ^ own_q[q] ^ own_s[s]) & a.axis_mask;
+                uint32_t t = table[x & 31u];
+                for (int k = 1; k < ntab; ++k) t ^= table[32u * k + ((x >> (5 * k)) & 31u)];
+                const unsigned long long src = ((unsigned long long)first + unit * UE + s) ^ (unsigned long long)t;
+                const unsigned char *p = in + src * W;
+                if constexpr (W == 8) {
+                    const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+                    o[q][2 * s] = v.x; o[q][2 * s + 1] = v.y;
+                } else if constexpr (W == 4) {
+                    o[q][s] = *reinterpret_cast<const uint32_t *>(p);
+                } else if constexpr (W == 2) {
+                    o[q][s >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t *>(p) << ((s & 1) * 16);
+                } else {
+                    o[q][0] |= (uint32_t)*p << (s * 8);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kGlobalPasses; ++q) {
+        const uint32_t unit = tid + 256u * q;
+        if constexpr (W >= 4) {
+            const u32x4 v = {o[q][0], o[q][1], o[q][2], o[q][3]};
+            buf_store16(rout, unit * 16u, v);
+        } else if constexpr (W == 2) {
+            const u32x2 v = {o[q][0], o[q][1]};
+            __builtin_amdgcn_raw_buffer_store_b64(v, rout, unit * 8u, 0, kStream);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b32(o[q][0], rout, unit * 4u, 0, kStream);
+        }
+    }
+}
+
+int gather_global_chunk_bits(int elem_bytes) { return (elem_bytes == 8 ? 1 : 2) + 8 + 2; }
+
+ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *stream)
+{
+    if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
+    if (a.na < 0 || a.na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", a.na);
+    if (a.block_bits < gather_global_chunk_bits(elem_bytes)) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than a workgroup's share");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)a.nblocks), block(256);
+    switch (elem_bytes) {
+    case 1: launch((k_gather_global<1>), grid, block, 0, s, a); break;
+    case 2: launch((k_gather_global<2>), grid, block, 0, s, a); break;
+    case 4: launch((k_gather_global<4>), grid, block, 0, s, a); break;
+    case 8: launch((k_gather_global<8>), grid, block, 0, s, a); break;
+    default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
+    }
+    return check_launch("global gather kernel launch");
 }
 
 ll_status launch_gather(const GatherArgs &a, int elem_bytes, void *stream)

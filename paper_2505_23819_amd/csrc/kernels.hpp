@@ -120,7 +120,7 @@ struct GatherArgs {
 // General gather (paper Sec. 5.5 extended): the axis may occupy register, lane and wave bits.  A
 // workgroup stages a block of 2^block_bits consecutive image elements (a block that is closed
 // under moves along the axis) in LDS and reads every output element's source from there.
-constexpr int kMaxAxisBits = 16;
+constexpr int kMaxAxisBits = 30;
 struct GatherGenArgs {
     const void *in;
     const int32_t *idx;
@@ -140,6 +140,8 @@ struct GatherGenArgs {
 
 int xcd_chunk_bits_for(long long group_bytes, long long block_bytes);
 ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *stream);
+int gather_global_chunk_bits(int elem_bytes);       // log2 elements one workgroup of the global gather takes
+ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *stream);
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,
                           int lds_bytes, void *stream);
 ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose, int xchg, int threads, int lds_bytes,

@@ -183,12 +183,10 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         const int want = 31 - __builtin_clz((unsigned)std::max(1, bytes / elem_bytes));
         block_bits = std::max(block_bits, want);
     }
-    if (((long long)elem_bytes << block_bits) > 64 * 1024) {
-        if (touched & wave_mask)
-            return fail(LL_ERR_AXIS_NOT_IN_WAVE, "the gather axis crosses waves and the %lld bytes it spans do not fit in LDS",
-                        (long long)elem_bytes << top);
-        return fail(LL_ERR_UNSUPPORTED, "the gather axis spans %lld bytes per lane group, more than LDS can stage", (long long)elem_bytes << top);
-    }
+    // A block beyond LDS (the axis reaches high register or wave bits of a large tile): the source
+    // elements are read straight from memory inside the aligned 2^top block around each element.
+    const bool global = ((long long)elem_bytes << block_bits) > 64 * 1024;
+    if (global) block_bits = top;
     if (na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", na);
     GatherGenArgs &g = c->gen;
     std::memset(&g, 0, sizeof(g));
@@ -206,7 +204,7 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     g.swz_shift = std::max(ub + 5, rb);
     g.swz_to = ub;
     g.swz_mask = (1u << nx) - 1;
-    c->kernel = LL_GATHER_BLOCK_STAGED;
+    c->kernel = global ? LL_GATHER_GLOBAL : LL_GATHER_BLOCK_STAGED;
     return LL_OK;
 }
 
@@ -220,8 +218,10 @@ ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gathe
     out->axis_lane_bits = c.axis_lane_bits;
     out->axis_wave_bits = c.axis_wave_bits;
     out->paper_rounds = 1 << c.axis_reg_bits;
-    out->block_bytes = c.kernel == LL_GATHER_BLOCK_STAGED ? (elem_bytes << c.gen.block_bits)
-                                                          : 64 * (1 << L->bits_of(LL_IN_REG)) * elem_bytes;
+    const long long gen_bytes = (long long)elem_bytes << c.gen.block_bits;
+    out->block_bytes = c.kernel == LL_GATHER_BLOCK_STAGED || c.kernel == LL_GATHER_GLOBAL
+                           ? (int32_t)std::min(gen_bytes, (long long)INT32_MAX)
+                           : 64 * (1 << L->bits_of(LL_IN_REG)) * elem_bytes;
     return LL_OK;
 }
 
@@ -243,6 +243,23 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
     const unsigned long long ibytes = ((unsigned long long)ntiles << d) * 4;
     if ((pi < po + bytes && po < pi + bytes) || (px < po + bytes && po < px + ibytes))
         return fail(LL_ERR_INVALID_ARG, "the output buffer overlaps an input buffer");
+    if (c.kernel == LL_GATHER_GLOBAL) {
+        GatherGenArgs &g = c.gen;
+        g.in = in;
+        g.idx = idx;
+        g.out = out;
+        g.total_elems = ntiles << d;
+        const int cb = gather_global_chunk_bits(elem_bytes);
+        g.nblocks = (g.total_elems + (1ll << cb) - 1) >> cb;
+        {
+            // XCD-aware order: one XCD works through a whole axis block (up to 2 MiB) so that the
+            // re-reads of the block hit that XCD's L2
+            const char *e = getenv("LL_GATHER_XCD_CHUNK");        // experiment knob: workgroups (power of two), 0 = off
+            const int block_chunks = std::min(g.block_bits, 21 - (31 - __builtin_clz((unsigned)elem_bytes))) - cb;
+            g.xcd_chunk = e ? (atoi(e) > 1 ? 31 - __builtin_clz((unsigned)atoi(e)) : -1) : (block_chunks > 0 ? block_chunks : -1);
+        }
+        return launch_gather_global(g, elem_bytes, stream);
+    }
     if (c.kernel == LL_GATHER_BLOCK_STAGED) {
         GatherGenArgs &g = c.gen;
         g.in = in;

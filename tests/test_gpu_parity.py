@@ -392,8 +392,6 @@ def test_gather_random_xor_layouts_any_axis(w, d, dims):
     """Random invertible layouts (columns are arbitrary XOR combinations): every axis, so that its
     hardware bits fall on registers, lanes and waves alike; tiles smaller and larger than a block;
     ragged tile counts."""
-    if (w << d) > 64 * 1024:
-        pytest.skip("tile larger than LDS")
     rng = np.random.default_rng(4000 + 17 * w + d)
     nreg = int(rng.integers(0, min(4, d - 2) + 1))
     nlane = min(6, d - nreg)
@@ -401,11 +399,7 @@ def test_gather_random_xor_layouts_any_axis(w, d, dims):
     for axis in range(len(dims)):
         cols = random_invertible(rng, d)
         layout = ll.distributed_layout(nreg, nlane, nwave, dims, cols)
-        try:
-            info = ll.ll_gather_info(layout, axis, w)
-        except ll.LLError as e:
-            assert e.status in (ll.LL_ERR_UNSUPPORTED, ll.LL_ERR_AXIS_NOT_IN_WAVE)
-            continue
+        info = ll.ll_gather_info(layout, axis, w)
         ntiles = int(rng.integers(1, 70))
         inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
         idx = rng.integers(0, 1 << dims[axis], size=ntiles << d, dtype=np.int32)
@@ -774,3 +768,36 @@ def test_convert_between_different_register_lane_wave_splits(w):
     plan = ll.ll_plan_convert(a, b, w)
     src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=7 << 12, dtype=NP_DTYPES[w])
     assert np.array_equal(run_convert(plan, src, 12), oracle.convert(oa.bases, ob.bases, src))
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_gather_along_axes_larger_than_lds(w, monkeypatch):
+    """Axes whose aligned block exceeds 64 KiB are gathered straight from memory: random XOR layouts
+    of 2^16 .. 2^18 elements (every axis then reaches the top bits), a ragged number of tiles, and
+    a permutation layout whose axis 0 is exactly the wave bits of a 2^17-element tile."""
+    rng = np.random.default_rng(9300 + w)
+    cases = [(16, [7, 9]), (17, [17]), (18, [6, 6, 6])]
+    seen = set()
+    for d, dims in cases:
+        if w == 1 and d == 16:
+            d, dims = 17, [8, 9]                                    # 64 KiB of bytes would still fit LDS
+        nreg, nlane = 4, 6
+        cols = random_invertible(rng, d)
+        layout = ll.distributed_layout(nreg, nlane, d - 10, dims, cols)
+        for axis in range(len(dims)):
+            info = ll.ll_gather_info(layout, axis, w)
+            seen.add(info["kernel_name"])
+            ntiles = int(rng.integers(1, 4))
+            inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
+            idx = rng.integers(0, 1 << dims[axis], size=ntiles << d, dtype=np.int32)
+            idx[::5] -= 1 << dims[axis]
+            got = run_gather(layout, axis, inp, idx, d)
+            assert np.array_equal(got, oracle.gather(cols, dims, axis, inp, idx)), (d, dims, axis, info)
+    assert "global" in seen
+    d, dims = 17, [7, 10]
+    cols = [1 << k for k in range(10)] + [1 << (10 + k) for k in range(7)]     # rows = the 7 wave bits
+    layout = ll.distributed_layout(4, 6, 7, dims, cols)
+    assert ll.ll_gather_info(layout, 0, w)["kernel_name"] == ("global" if (w << 17) > 65536 else "block_staged")
+    inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=3 << d, dtype=NP_DTYPES[w])
+    idx = rng.integers(0, 1 << 7, size=3 << d, dtype=np.int32)
+    assert np.array_equal(run_gather(layout, 0, inp, idx, d), oracle.gather(cols, dims, 0, inp, idx))

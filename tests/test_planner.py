@@ -295,12 +295,12 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     with pytest.raises(ll.LLError) as e:
         ll.ll_gather(lay, 2, 2, 0, 0, 0, 0, stream=0)
     assert e.value.status == ll.LL_ERR_INVALID_ARG
-    # an axis that crosses waves over more data than LDS can stage: the paper's legality condition
+    # an axis that crosses waves over more data than LDS can stage: outside the paper's legality
+    # condition (reported, not an error); gathered from memory inside the 256 KiB block
     big = ll.distributed_layout(4, 6, 6, [6, 10], [1 << k for k in range(4)] + [1 << (10 + k) for k in range(6)] +
                                 [1 << (4 + k) for k in range(6)])
-    with pytest.raises(ll.LLError) as e:
-        ll.ll_gather(big, 1, 4, 0, 0, 0, 0, stream=0)              # columns: registers and all 6 wave bits, 256 KiB
-    assert e.value.status == ll.LL_ERR_AXIS_NOT_IN_WAVE
+    info = ll.ll_gather_info(big, 1, 4)                            # columns: registers and all 6 wave bits
+    assert info["kernel_name"] == "global" and info["axis_wave_bits"] == 6 and info["block_bytes"] == 256 * 1024
     assert ll.ll_gather_info(big, 0, 4)["kernel_name"] == "wave_staged"
     # a tile label on the axis
     tiled = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 6), (ll.LL_IN_TILE, 2)], [2, 8],
