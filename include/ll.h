@@ -43,7 +43,7 @@ typedef enum {
     LL_ERR_INVALID_ARG = 1,      /* null pointer, size out of range, bad label order, misaligned buffer */
     LL_ERR_DIM_MISMATCH = 2,     /* input/output spaces of the operands do not match */
     LL_ERR_NOT_SURJECTIVE = 3,   /* a right inverse was requested of a non-surjective layout */
-    LL_ERR_NOT_INJECTIVE = 4,    /* the operation needs an injective layout (gather; inversion) */
+    LL_ERR_NOT_INJECTIVE = 4,    /* the operation needs an injective layout */
     LL_ERR_TILE_MIXED = 5,       /* the conversion would move data between tiles */
     LL_ERR_AXIS_NOT_IN_WAVE = 6, /* gather axis is not contained in one wave (Sec. 5.5); kept for ABI stability,
                                     no longer returned: see ll_gather */
@@ -284,8 +284,11 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
 /* ---- gather (paper Sec. 5.5) ----------------------------------------------------------- */
 
 /* out[.., i, ..] = in[.., idx[.., i, ..], ..] along output dim `axis`, where in, idx (int32) and
- * out are images under the same bijective layout L.  Indices are reduced modulo the axis length.
- * Moving along the axis changes the hardware index by L^-1 of the axis bits:
+ * out are images under the same surjective layout L.  Indices are reduced modulo the axis length.
+ * L may broadcast (Sec. 5.1; 2^d slots per tile for fewer logical elements): every slot of out is
+ * written, from its own slot of idx, and of the replicas of the wanted element it reads the one at
+ * (own slot) xor L^+(coordinate difference), L^+ the right inverse with free variables zero.
+ * Moving along the axis changes the hardware index by L^-1 (L^+) of the axis bits:
  *  - lane bits only (the paper's condition, Sec. 5.5, with one round): cross-lane shuffles, or
  *    wave-private LDS staging when a lane holds more than 16 bytes;
  *  - register and / or wave bits as well: the aligned block of image elements those bits span is

@@ -242,6 +242,40 @@ def gather_affine(bases_l: Sequence[int], off: int, out_dim_bits: Sequence[int],
     return out
 
 
+def gather_general(bases_l: Sequence[int], out_dim_bits: Sequence[int], axis: int,
+                   inp: np.ndarray, idx: np.ndarray, off: int = 0) -> np.ndarray:
+    """Gather (Sec. 5.5) under a surjective layout that may broadcast (Sec. 5.1), optionally affine.
+    Slot h of a tile holds the logical element x = L h ^ off.  It receives the element whose axis
+    coordinate is idx[h] (mod the axis length) and whose other coordinates are those of x, i.e. the
+    logical element x ^ delta with delta = (own axis coordinate ^ idx[h]) on the axis bits.  Of the
+    replicas of that element it takes the one at slot h ^ L^+(delta), L^+ the right inverse with
+    free variables zero (Def. "Right Inverse"): L(h ^ L^+ delta) = L h ^ delta.  For a bijective
+    layout this is the plain gather."""
+    d, d_out = len(bases_l), int(sum(out_dim_bits))
+    _check_img(inp, d, "in")
+    _check_img(idx, d, "idx")
+    if idx.dtype != np.int32 or idx.size != inp.size:
+        raise ValueError("idx must be int32 with as many elements as in")
+    if not 0 <= axis < len(out_dim_bits):
+        raise ValueError("axis")
+    shift = int(sum(out_dim_bits[axis + 1:]))
+    mask = (1 << int(out_dim_bits[axis])) - 1
+    lplus = right_inverse_table(bases_l, d_out).astype(np.int64)     # x -> slot, free variables zero
+    h = np.arange(1 << d, dtype=np.int64)
+    x = np.zeros(1 << d, dtype=np.int64)
+    for k, col in enumerate(bases_l):
+        x ^= ((h >> k) & 1) * int(col)
+    x ^= int(off)
+    own = (x >> shift) & mask
+    out = np.empty_like(inp)
+    src_img, idx_img, out_img = inp.reshape(-1, 1 << d), idx.reshape(-1, 1 << d), out.reshape(-1, 1 << d)
+    for t in range(src_img.shape[0]):
+        want = idx_img[t].astype(np.int64) & mask
+        delta = (own ^ want) << shift
+        out_img[t] = src_img[t][h ^ lplus[delta]]
+    return out
+
+
 def wavefronts(mem_bases: Sequence[int], dist_bases: Sequence[int], nreg: int, nlane: int,
                elem_bytes: int, vec_bits: int, nbanks: int, phase_of_lane: Sequence[int]):
     """Exhaustive wavefront count: returns (max per phase, total, conflict-free total)."""

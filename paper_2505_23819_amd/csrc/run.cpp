@@ -91,9 +91,11 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         return fail(LL_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8 (got %d)", elem_bytes);
     const int d = L->d_in;
     if (f2::rank(L->bases) < L->d_out) return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
-    if (d > L->d_out) return fail(LL_ERR_NOT_INJECTIVE, "layouts with broadcasting are not supported");
+    // Right inverse with free variables zero (Def. "Right Inverse"); the inverse when L is bijective.
+    // Under a broadcasting layout an element is taken from the replica that differs from the
+    // receiving slot by L^+ of the coordinate difference: L(h ^ L^+(delta)) = L(h) ^ delta.
     mat linv;
-    if (!f2::invert(L->bases, d, &linv)) return fail(LL_ERR_NOT_INJECTIVE, "layout is not bijective");
+    if (!f2::right_inverse(L->bases, L->d_out, &linv)) return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
     const int nreg = L->bits_of(LL_IN_REG), nlane = L->bits_of(LL_IN_LANE);
     const int lane0 = L->first_bit_of(LL_IN_LANE), wave0 = L->first_bit_of(LL_IN_WAVE), tile0 = L->first_bit_of(LL_IN_TILE);
     int axis_shift = 0;

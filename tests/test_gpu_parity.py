@@ -801,3 +801,42 @@ def test_gather_along_axes_larger_than_lds(w, monkeypatch):
     inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=3 << d, dtype=NP_DTYPES[w])
     idx = rng.integers(0, 1 << 7, size=3 << d, dtype=np.int32)
     assert np.array_equal(run_gather(layout, 0, inp, idx, d), oracle.gather(cols, dims, 0, inp, idx))
+
+
+# ---------------------------------------------------------------------------------------------
+# Gather under broadcasting layouts (Sec. 5.5 with Sec. 5.1): replicas receive and supply data
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_gather_under_broadcasting_layouts(w, monkeypatch):
+    """Random surjective layouts with zero and dependent columns, every axis, replicas of `in` and
+    `idx` deliberately unequal (which replica is read is part of the definition); a sliced blocked
+    layout; an affine constant on top."""
+    rng = np.random.default_rng(9500 + w)
+    seen = set()
+    for d_in, dims, nreg in [(10, [4, 4], 2), (12, [3, 6], 4), (13, [5, 2, 3], 3), (9, [7], 2), (16, [6, 7], 4)]:
+        d_out = sum(dims)
+        cols = surjective_bases(rng, d_in, d_out)
+        nlane = min(6, d_in - nreg)
+        layout = ll.ll_layout_create([(ll.LL_IN_REG, nreg), (ll.LL_IN_LANE, nlane), (ll.LL_IN_WAVE, d_in - nreg - nlane)], dims, cols)
+        off = int(rng.integers(0, 1 << d_out))
+        for axis in range(len(dims)):
+            for lay, o in ((layout, 0), (ll.ll_layout_with_offset(layout, off), off)):
+                seen.add(ll.ll_gather_info(lay, axis, w)["kernel_name"])
+                ntiles = int(rng.integers(1, 6)) * 16
+                inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d_in, dtype=NP_DTYPES[w])
+                idx = rng.integers(-(1 << dims[axis]), 1 << dims[axis], size=ntiles << d_in, dtype=np.int32)
+                got = run_gather(lay, axis, inp, idx, d_in)
+                assert np.array_equal(got, oracle.gather_general(cols, dims, axis, inp, idx, o)), (d_in, dims, axis, o)
+    # the result of a reduction: a 64 x 64 blocked tile sliced along its rows, gathered along what is left
+    parent = ll.ll_layout_blocked([1, 2], [3, 3], [2, 1], [1, 0])
+    s = ll.ll_layout_slice(parent, 0)
+    os_ = oracle.slice_layout(oracle.blocked_layout([1, 2], [3, 3], [2, 1], [1, 0]), 0)
+    assert s.bases == os_.bases
+    for env in ({}, {"LL_GATHER_GENERAL": "1"}):
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        seen.add(ll.ll_gather_info(s, 0, w)["kernel_name"])
+        inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=32 << 12, dtype=NP_DTYPES[w])
+        idx = rng.integers(0, 64, size=32 << 12, dtype=np.int32)
+        assert np.array_equal(run_gather(s, 0, inp, idx, 12), oracle.gather_general(os_.bases, [6], 0, inp, idx))
+    assert "block_staged" in seen
