@@ -171,7 +171,9 @@ ll_status ll_layout_slice(const ll_layout *layout, int dim, ll_layout **out);
  * index h holds the logical element (A h) xor offset; offset < 2^(output bits).  For a dim of 2^n
  * elements, offset = all ones of that dim flips it, offset = its top bit rolls it by half.
  * ll_layout_apply, ll_compose and ll_invert carry the offset along; ll_plan_convert and ll_gather
- * accept affine layouts (gather: bijective ones); products and divisions do not (LL_ERR_UNSUPPORTED). */
+ * accept affine layouts; products combine the constants of their factors dim by dim, a division
+ * needs the layout's constant to contain the tile's (LL_ERR_NOT_DIVISIBLE otherwise) and gives the
+ * quotient the rest; ll_contiguity counts the run that starts at register 0's element. */
 ll_status ll_layout_with_offset(const ll_layout *layout, uint64_t offset, ll_layout **out);
 ll_status ll_layout_get_offset(const ll_layout *layout, uint64_t *offset);
 

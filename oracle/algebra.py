@@ -26,6 +26,7 @@ class OLayout:
     in_dims: List[Tuple[int, int]]      # (label, bits), in input-bit order
     out_dims: List[int]                 # bits per logical dim, slowest first
     bases: List[int]                    # image of every input bit, flattened (last dim fastest)
+    offset: int = 0                     # affine layouts (Conclusions): index h holds element (bases h) xor offset
 
     @property
     def d_in(self) -> int:
@@ -48,6 +49,15 @@ def to_matrix(lay: OLayout) -> np.ndarray:
         for r in range(lay.d_out):
             m[r, c] = (b >> r) & 1
     return m
+
+
+def split_dims(x: int, out_dims: Sequence[int]) -> List[int]:
+    """Per-dim coordinates of a flattened index (slowest dim first)."""
+    return [(x >> out_shift(out_dims, j)) & ((1 << n) - 1) for j, n in enumerate(out_dims)]
+
+
+def join_dims(coords: Sequence[int], out_dims: Sequence[int]) -> int:
+    return sum(c << out_shift(out_dims, j) for j, c in enumerate(coords))
 
 
 def from_matrix(m: np.ndarray, in_dims, out_dims) -> OLayout:
@@ -90,7 +100,11 @@ def product(a: OLayout, b: OLayout) -> OLayout:
                         col[row_of(which, j, i)] = mat[out_shift(lay.out_dims, j) + i, c]
                 cols.append(col)
     full = np.stack(cols, axis=1) if cols else np.zeros((sum(out_dims), 0), dtype=np.uint8)
-    return from_matrix(full, in_dims, out_dims)
+    res = from_matrix(full, in_dims, out_dims)
+    # affine factors: element (x1 ^ b1, x2 ^ b2) per dim, a's bits below b's
+    res.offset = join_dims([ca | (cb << a.out_dims[j]) for j, (ca, cb) in
+                            enumerate(zip(split_dims(a.offset, a.out_dims), split_dims(b.offset, b.out_dims)))], out_dims)
+    return res
 
 
 def divide_left(lay: OLayout, tile: OLayout) -> Optional[OLayout]:
@@ -139,7 +153,13 @@ def divide_left(lay: OLayout, tile: OLayout) -> Optional[OLayout]:
     if top_right.any() or bottom_left.any():
         return None
     q_out = [l - t for l, t in zip(lay.out_dims, tile.out_dims)]
-    return from_matrix(bottom_right, q_in, q_out)
+    q = from_matrix(bottom_right, q_in, q_out)
+    # affine layouts: lay = tile x q also for the constants, dim by dim
+    lo, to = split_dims(lay.offset, lay.out_dims), split_dims(tile.offset, tile.out_dims)
+    if any((l & ((1 << tb) - 1)) != t for l, t, tb in zip(lo, to, tile.out_dims)):
+        return None
+    q.offset = join_dims([l >> tb for l, tb in zip(lo, tile.out_dims)], q_out)
+    return q
 
 
 def divide_left_permuting(lay: OLayout, tile: OLayout, label: int):
@@ -151,24 +171,27 @@ def divide_left_permuting(lay: OLayout, tile: OLayout, label: int):
         bases = list(lay.bases)
         for k, src in enumerate(perm):
             bases[pos[k]] = lay.bases[pos[src]]
-        q = divide_left(OLayout(lay.in_dims, lay.out_dims, bases), tile)
+        q = divide_left(OLayout(lay.in_dims, lay.out_dims, bases, lay.offset), tile)
         if q is not None:
             return list(perm), q
     return None
 
 
 def contiguity(lay: OLayout, reg_label: int = 0) -> int:
-    """Sec. 5.1 "Contiguous elements": the number c of leading logical elements 0..c-1 that the
+    """Sec. 5.1 "Contiguous elements": the number c of leading logical elements x0..x0+c-1 that the
     inverse of the layout sends, by the identity map, onto registers 0..c-1 (of thread 0, wave 0):
     the largest block that one thread can move with a single vector access.  Taken literally on
-    the tabulated inverse; the register bits must be the first input bits."""
+    the tabulated inverse; the register bits must be the first input bits.  x0 is the element of
+    register 0: 0 for a linear layout, the constant for an affine one (slot h holds L h ^ offset, so
+    element x sits at the inverse of x ^ offset)."""
     from . import right_inverse_table
     if not lay.in_dims or lay.in_dims[0][0] != reg_label:
         return 1
     nreg = lay.in_dims[0][1]
     table = right_inverse_table(lay.bases, lay.d_out)
     c = 0
-    while c < min(1 << nreg, 1 << lay.d_out) and int(table[c]) == c:
+    x0 = lay.offset
+    while c < min(1 << nreg, 1 << lay.d_out) and x0 + c < (1 << lay.d_out) and int(table[(x0 + c) ^ lay.offset]) == c:
         c += 1
     return max(c, 1)
 

@@ -107,7 +107,8 @@ def slice_layout(lay: OLayout, dim: int) -> OLayout:
     keep = [r for r in range(lay.d_out) if not lo <= r < lo + lay.out_dims[dim]]
     out_dims = [n for j, n in enumerate(lay.out_dims) if j != dim]
     bases = [int(sum(int(m[r, c]) << i for i, r in enumerate(keep))) for c in range(lay.d_in)]
-    return OLayout(list(lay.in_dims), out_dims, bases)
+    offset = sum(((lay.offset >> r) & 1) << i for i, r in enumerate(keep))      # the constant loses the same rows
+    return OLayout(list(lay.in_dims), out_dims, bases, offset)
 
 
 def is_distributed_layout(lay: OLayout) -> bool:

@@ -76,7 +76,15 @@ ll_status divide(const ll_layout *layout, const mat &cols, const ll_layout *tile
         qin[i].label = label;
         qin[i].nbits = n - nt;
     }
-    return ll::make_layout(qin, layout->n_in, qdims, r, qcols, out);
+    // affine layouts: the constant splits like a column does; its tile part must be the tile's own
+    if ((layout->offset & tile_rows) != repack(tile->offset, tile->out_dims, layout->out_dims, r, zero))
+        return ll::fail(LL_ERR_NOT_DIVISIBLE, "the constant of the layout does not contain the constant of the tile");
+    vec qoff = 0;
+    for (int j = 0; j < r; ++j)
+        qoff |= field(layout->offset, shift_of(layout->out_dims, r, j) + tile->out_dims[j].nbits, qdims[j].nbits) << shift_of(qdims, r, j);
+    const ll_status st = ll::make_layout(qin, layout->n_in, qdims, r, qcols, out);
+    if (st == LL_OK) (*out)->offset = qoff;
+    return st;
 }
 
 ll_status check_pair(const ll_layout *layout, const ll_layout *tile, ll_layout **out)
@@ -86,7 +94,6 @@ ll_status check_pair(const ll_layout *layout, const ll_layout *tile, ll_layout *
     if (!layout || !tile) return ll::fail(LL_ERR_INVALID_ARG, "null layout");
     if (layout->n_out != tile->n_out)
         return ll::fail(LL_ERR_DIM_MISMATCH, "layout and tile have %d and %d logical dims", layout->n_out, tile->n_out);
-    if (layout->offset || tile->offset) return ll::fail(LL_ERR_UNSUPPORTED, "division of affine layouts is not implemented");
     for (int i = 0; i < tile->n_in; ++i)
         if (tile->in_dims[i].nbits > 0 && !has_label(layout, tile->in_dims[i].label))
             return ll::fail(LL_ERR_NOT_DIVISIBLE, "the layout has no input label %d", tile->in_dims[i].label);
@@ -104,7 +111,6 @@ ll_status ll_product_dimwise(const ll_layout *a, const ll_layout *b, ll_layout *
         *out = nullptr;
         if (!a || !b) return ll::fail(LL_ERR_INVALID_ARG, "null layout");
         if (a->n_out != b->n_out) return ll::fail(LL_ERR_DIM_MISMATCH, "factors have %d and %d logical dims", a->n_out, b->n_out);
-        if (a->offset || b->offset) return ll::fail(LL_ERR_UNSUPPORTED, "products of affine layouts are not implemented");
         if (a->d_in + b->d_in > LL_MAX_BITS || a->d_out + b->d_out > LL_MAX_BITS)
             return ll::fail(LL_ERR_INVALID_ARG, "product exceeds %d bits", LL_MAX_BITS);
         const int r = a->n_out;
@@ -129,7 +135,10 @@ ll_status ll_product_dimwise(const ll_layout *a, const ll_layout *b, ll_layout *
             for (int k = 0; k < nb; ++k) cols.push_back(repack(b->bases[b->first_bit_of(label) + k], b->out_dims, odims, r, above));
         }
         if (has_offset && has_hw) return ll::fail(LL_ERR_DIM_MISMATCH, "cannot multiply a memory layout with a distributed layout");
-        return ll::make_layout(dims, n, odims, r, cols, out);
+        const ll_status st = ll::make_layout(dims, n, odims, r, cols, out);
+        // affine factors: the constants combine dim by dim exactly as the images do
+        if (st == LL_OK) (*out)->offset = repack(a->offset, a->out_dims, odims, r, zero) | repack(b->offset, b->out_dims, odims, r, above);
+        return st;
     } catch (...) {   // nothing may propagate across the C ABI
         return ll::fail(LL_ERR_INVALID_ARG, "ll_product_dimwise: out of host memory");
     }
@@ -191,6 +200,8 @@ ll_status ll_contiguity(const ll_layout *layout, int32_t *elems)
         // i maps to logical bit i for every i < u (the inverse is then the identity on that block).
         int u = 0;
         while (u < layout->in_dims[0].nbits && u < layout->d_out && layout->bases[(size_t)u] == (vec(1) << u)) ++u;
+        // an affine constant with low bits set reverses or swaps elements inside such a block
+        while (u > 0 && (layout->offset & ((vec(1) << u) - 1))) --u;
         *elems = 1 << u;
         return LL_OK;
     } catch (...) {   // nothing may propagate across the C ABI

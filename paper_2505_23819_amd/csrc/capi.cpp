@@ -209,7 +209,6 @@ ll_status ll_product(const ll_layout *a, const ll_layout *b, ll_layout **out)
         if (a->d_in + b->d_in > LL_MAX_BITS || a->d_out + b->d_out > LL_MAX_BITS)
             return fail(LL_ERR_INVALID_ARG, "product exceeds %d bits", LL_MAX_BITS);
         if (a->n_out + b->n_out > LL_MAX_OUT_DIMS) return fail(LL_ERR_INVALID_ARG, "product has too many output dims");
-        if (a->offset || b->offset) return fail(LL_ERR_UNSUPPORTED, "products of affine layouts are not implemented");
         // merged input dims, label by label: bits of `a` first, then bits of `b`
         ll_in_dim dims[LL_MAX_IN_DIMS];
         int n = 0;
@@ -235,7 +234,10 @@ ll_status ll_product(const ll_layout *a, const ll_layout *b, ll_layout **out)
         int m = 0;
         for (int i = 0; i < b->n_out; ++i) odims[m++] = b->out_dims[i];
         for (int i = 0; i < a->n_out; ++i) odims[m++] = a->out_dims[i];
-        return ll::make_layout(dims, n, odims, m, cols, out);
+        const ll_status st = ll::make_layout(dims, n, odims, m, cols, out);
+        // affine factors: (A1 h1 ^ b1, A2 h2 ^ b2) = (A1 x A2)(h1, h2) ^ (b1, b2)
+        if (st == LL_OK) (*out)->offset = a->offset | (b->offset << a->d_out);
+        return st;
     } catch (...) {   // nothing may propagate across the C ABI
         return ll::fail(LL_ERR_INVALID_ARG, "ll_product: out of host memory");
     }

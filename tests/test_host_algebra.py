@@ -245,7 +245,7 @@ def test_contiguity_matches_the_oracle():
 def _same(lib_layout, o):
     assert lib_layout.bases == o.bases, (lib_layout.bases, o.bases)
     assert lib_layout.out_dims == o.out_dims
-    assert lib_layout.in_dims == [d for d in o.in_dims if d[1] > 0]
+    assert [d for d in lib_layout.in_dims if d[1] > 0] == [d for d in o.in_dims if d[1] > 0]
 
 
 def test_blocked_constructor_matches_the_oracle_and_layout_a():
@@ -356,9 +356,6 @@ def test_affine_layout_apply_compose_invert():
     with pytest.raises(ll.LLError) as e:
         ll.ll_layout_with_offset(lay, 1 << d)
     assert e.value.status == ll.LL_ERR_INVALID_ARG
-    with pytest.raises(ll.LLError) as e:
-        ll.ll_product_dimwise(lay, lay)
-    assert e.value.status == ll.LL_ERR_UNSUPPORTED
 
 
 def test_affine_plan_reports_the_constant():
@@ -408,3 +405,36 @@ def test_slice_matches_the_oracle():
     with pytest.raises(ll.LLError) as e:
         ll.ll_layout_slice(ll.ll_layout_identity(ll.LL_IN_REG, 0, 3, 1), 0)
     assert e.value.status == ll.LL_ERR_INVALID_ARG
+
+
+def test_affine_products_divisions_and_contiguity_match_the_oracle():
+    rng = np.random.default_rng(33)
+    for _ in range(40):
+        nd = int(rng.integers(1, 4))
+        fa = [[int(x) for x in rng.integers(0, 3, size=nd)] for _ in range(3)]
+        fb = [[int(x) for x in rng.integers(0, 3, size=nd)] for _ in range(3)]
+        order = [int(x) for x in rng.permutation(nd)]
+        if sum(map(sum, fa)) == 0 or sum(map(sum, fb)) == 0:
+            continue
+        a, oa = ll.ll_layout_blocked(*fa, order), oracle.blocked_layout(*fa, order)
+        b, ob = ll.ll_layout_blocked(*fb, order), oracle.blocked_layout(*fb, order)
+        oa.offset, ob.offset = int(rng.integers(0, 1 << oa.d_out)), int(rng.integers(0, 1 << ob.d_out))
+        a, b = ll.ll_layout_with_offset(a, oa.offset), ll.ll_layout_with_offset(b, ob.offset)
+        prod, oprod = ll.ll_product_dimwise(a, b), oracle.product(oa, ob)
+        _same(prod, oprod)
+        assert ll.ll_layout_get_offset(prod) == oprod.offset
+        q, oq = ll.ll_divide_left(prod, a), oracle.divide_left(oprod, oa)
+        _same(q, oq)
+        assert ll.ll_layout_get_offset(q) == oq.offset == ob.offset
+        assert ll.ll_contiguity(prod) == oracle.contiguity(oprod)
+        if oa.d_out:                                               # a tile with another constant does not divide
+            wrong = ll.ll_layout_with_offset(a, oa.offset ^ 1)
+            with pytest.raises(ll.LLError) as e:
+                ll.ll_divide_left(prod, wrong)
+            assert e.value.status == ll.LL_ERR_NOT_DIVISIBLE
+            owrong = oracle.OLayout(oa.in_dims, oa.out_dims, oa.bases, oa.offset ^ 1)
+            assert oracle.divide_left(oprod, owrong) is None
+    # the plain product stacks the output spaces: constants side by side
+    x = ll.ll_layout_with_offset(ll.ll_layout_identity(ll.LL_IN_REG, 0, 3, 1), 0b101)
+    y = ll.ll_layout_with_offset(ll.ll_layout_identity(ll.LL_IN_LANE, 0, 2, 1), 0b10)
+    assert ll.ll_layout_get_offset(ll.ll_product(x, y)) == 0b10_101

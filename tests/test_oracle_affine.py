@@ -129,3 +129,52 @@ def test_broadcasting_affine_conversion_pins():
     src_wide = rng.integers(0, 1 << 16, size=4 << (d + 1), dtype=np.uint16)
     got = oracle.convert_general_affine(flipped_wide, (1 << d) - 1, ident, 0, d, src_wide)
     assert np.array_equal(got.reshape(4, 1 << d), src_wide.reshape(4, 2, 1 << d)[:, 0, ::-1])
+
+
+def test_affine_product_division_and_contiguity():
+    """Def. "Product" / "Left Division" with constants: the product of two affine layouts applied to
+    (h1, h2) is, per logical dim, the pair of coordinates the factors give, the first factor's bits
+    below the second's; division undoes it and refuses a tile with another constant.  Contiguity
+    under a constant: the run of ascending consecutive elements in registers 0, 1, .. of thread 0,
+    read off the elements directly."""
+    from oracle.algebra import OLayout
+    rng = np.random.default_rng(71)
+
+    def coords(x, dims):
+        out = []
+        for n in reversed(dims):
+            out.append(x & ((1 << n) - 1))
+            x >>= n
+        return out[::-1]
+
+    for _ in range(30):
+        nd = int(rng.integers(1, 4))
+        fa = [[int(x) for x in rng.integers(0, 3, size=nd)] for _ in range(3)]
+        fb = [[int(x) for x in rng.integers(0, 3, size=nd)] for _ in range(3)]
+        order = [int(x) for x in rng.permutation(nd)]
+        a, b = oracle.blocked_layout(*fa, order), oracle.blocked_layout(*fb, order)
+        a.offset, b.offset = int(rng.integers(0, 1 << a.d_out)), int(rng.integers(0, 1 << b.d_out))
+        p = oracle.product(a, b)
+        # walk all (h1, h2): input bits are merged label by label, a's bits first
+        for h1 in range(1 << a.d_in):
+            for h2 in range(0, 1 << b.d_in, max(1, (1 << b.d_in) // 8)):
+                h, pos, p1, p2 = 0, 0, 0, 0
+                for (_, na), (_, nb) in zip(a.in_dims, b.in_dims):
+                    h |= ((h1 >> p1) & ((1 << na) - 1)) << pos
+                    h |= ((h2 >> p2) & ((1 << nb) - 1)) << (pos + na)
+                    pos, p1, p2 = pos + na + nb, p1 + na, p2 + nb
+                ca = coords(oracle.apply(a.bases, h1) ^ a.offset, a.out_dims)
+                cb = coords(oracle.apply(b.bases, h2) ^ b.offset, b.out_dims)
+                got = coords(oracle.apply(p.bases, h) ^ p.offset, p.out_dims)
+                assert got == [x | (y << n) for x, y, n in zip(ca, cb, a.out_dims)]
+        q = oracle.divide_left(p, a)
+        assert q is not None and q.bases == b.bases and q.offset == b.offset
+        if a.d_out:
+            assert oracle.divide_left(p, OLayout(a.in_dims, a.out_dims, a.bases, a.offset ^ (1 << int(rng.integers(0, a.d_out))))) is None
+    for off, want in ((0, 8), (4, 4), (6, 2), (2, 2), (1, 1), (0b1000, 8), (0b1100, 4)):
+        lay = OLayout([(0, 3), (1, 2)], [5], [1, 2, 4, 8, 16], off)
+        held = np.array([oracle.apply(lay.bases, r) ^ off for r in range(8)])
+        run = 1
+        while run < 8 and held[run] == held[0] + run:
+            run += 1
+        assert oracle.contiguity(lay) == run == want
