@@ -325,8 +325,9 @@ ll_status ll_gather(const ll_layout *layout, int axis, int elem_bytes, const voi
 
 /* ---- misc -------------------------------------------------------------------------------- */
 
-/* Plain 16-byte-vector device copy of `bytes` bytes (a multiple of 16): the achievable-bandwidth
- * yardstick the benchmark prints next to each conversion.  Asynchronous on hip_stream. */
+/* Plain 16-byte-vector device copy of `bytes` bytes (a multiple of 16) between buffers that do not
+ * overlap: the achievable-bandwidth yardstick the benchmark prints next to each conversion.
+ * Asynchronous on hip_stream. */
 ll_status ll_copy(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream);
 
 const char *ll_last_error(void);

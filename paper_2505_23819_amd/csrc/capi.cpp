@@ -364,6 +364,8 @@ ll_status ll_copy(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_s
         if (bytes == 0) return LL_OK;
         if (!src_dev || !dst_dev) return fail(LL_ERR_INVALID_ARG, "null device pointer");
         if (misaligned(src_dev) || misaligned(dst_dev)) return fail(LL_ERR_INVALID_ARG, "device buffers must be 16-byte aligned");
+        const char *ps = static_cast<const char *>(src_dev), *pd = static_cast<const char *>(dst_dev);
+        if (ps < pd + bytes && pd < ps + bytes) return fail(LL_ERR_INVALID_ARG, "source and destination buffers overlap");
         return ll::launch_copy(src_dev, dst_dev, bytes, hip_stream);
     } catch (...) {   // nothing may propagate across the C ABI
         return ll::fail(LL_ERR_INVALID_ARG, "ll_copy: out of host memory");

@@ -289,6 +289,9 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
         ll.ll_convert(tiny, 4096, 1 << 20, 3, stream=0)            # 12 bytes: not a whole 16-byte vector
     assert e.value.status == ll.LL_ERR_INVALID_ARG
 
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_copy(4096, 4096 + 32, 64, stream=0)                  # overlapping buffers
+    assert e.value.status == ll.LL_ERR_INVALID_ARG
     g = wl.config(5)
     lay = ll.distributed_layout(g.nreg, g.nlane, g.nwave, g.out_dim_bits, g.src_bases)
     ll.ll_gather(lay, 0, 2, 0, 0, 0, 0, stream=0)                  # valid layout, nothing to move
