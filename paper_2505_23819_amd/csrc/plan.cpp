@@ -339,6 +339,18 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
 
     BlockGeom geom;
     if (ll_status st = build_blocks(p, d, w, vs + tb, max_block, pref_block, &geom); st != LL_OK) return st;
+    if (geom.n == vs + tb && ((long long)w << d) > 256 * 1024 && !getenv("LL_BLOCK_BYTES")) {
+        // One vector per thread and a large tile cut into many such blocks: the runs are as short as
+        // the limit allows (4-byte elements: 128 bytes on each side, 32 of them scattered over the
+        // tile).  Runs grow on both sides at once, so the next size is four times the block.  Measured
+        // on random XOR layouts of 4-byte elements: tiles up to 256 KiB are as fast or faster with the
+        // small block (16 KiB tiles: 6.36 against 6.09 TB/s), larger ones much faster with the wide
+        // one (2^18 elements: 5.7 -> 6.2, 2^20: 5.0 -> 6.2, 2^22: 4.5 -> 5.9).
+        BlockGeom wider;
+        if (build_blocks(p, d, w, vs + tb, 2 * max_block, pref_block, &wider) == LL_OK && wider.k > geom.k &&
+            ((unsigned)w << wider.n) <= 2 * max_block)
+            geom = wider;
+    }
     const int g = geom.g, k = geom.k, n = geom.n;
     const mat &pext = geom.pext, &us = geom.us, &ud = geom.ud, &q = geom.q, &qinv = geom.qinv, &comp = geom.comp;
     const int nco = (int)comp.size();
