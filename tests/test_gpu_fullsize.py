@@ -138,3 +138,27 @@ def test_narrow_transpose_full_size_sampled(w, force, monkeypatch):
         s_tile = wl.to_numpy_bits(src[t * te:(t + 1) * te])
         want = oracle.convert(cfg.src_bases, cfg.dst_bases, s_tile)
         assert np.array_equal(wl.to_numpy_bits(dst[t * te:(t + 1) * te]), want), f"tile {t}"
+
+
+def test_gather_beyond_lds_full_size_sampled():
+    """The memory-direct gather in the configuration bench.py times: 512 row-major 512 x 512 tiles of
+    two-byte elements, gather along the rows (the axis block is the whole 512 KiB tile)."""
+    d, ntiles = 18, 512
+    bases = [1 << k for k in range(d)]
+    layout = ll.distributed_layout(4, 6, 8, [9, 9], bases)
+    assert ll.ll_gather_info(layout, 0, 2)["kernel_name"] == "global"
+    inp = wl.raw_bits(23, 0, (ntiles << d) * 2 // 8, "cuda").view(torch.int16)
+    idx = wl.gen_index(53, 0, ntiles << d, 1 << 9, "cuda")
+    out = torch.empty_like(inp)
+    out.fill_(0x5A5A)
+    ll.ll_gather(layout, 0, 2, inp, idx, out, ntiles)
+    torch.cuda.synchronize()
+    te = 1 << d
+    for t in sample_tiles(ntiles, 6, 18):
+        i_tile = inp[t * te:(t + 1) * te].cpu().numpy().view(np.uint16)
+        x_tile = idx[t * te:(t + 1) * te].cpu().numpy()
+        want = oracle.gather(bases, [9, 9], 0, i_tile, x_tile)
+        assert np.array_equal(out[t * te:(t + 1) * te].cpu().numpy().view(np.uint16), want), f"tile {t}"
+    # at full size: the layout is the identity, so the definition is torch.gather on the logical view
+    ref = torch.gather(inp.view(ntiles, 512, 512), 1, idx.view(ntiles, 512, 512).to(torch.int64))
+    assert torch.equal(out.view(ntiles, 512, 512), ref)
