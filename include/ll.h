@@ -294,7 +294,7 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
  *  - lane bits only (the paper's condition, Sec. 5.5, with one round): cross-lane shuffles, or
  *    wave-private LDS staging when a lane holds more than 16 bytes;
  *  - register and / or wave bits as well: the aligned block of image elements those bits span is
- *    staged in workgroup LDS when it is at most 64 KiB; a larger block is gathered straight from
+ *    staged in workgroup LDS when it is at most 128 KiB; a larger block is gathered straight from
  *    memory, element by element, inside that block (slower: every element is its own access).
  *    Sec. 5.5's condition (no wave bits on the axis) is reported by ll_gather_info
  *    (axis_wave_bits == 0) and is not an error here;

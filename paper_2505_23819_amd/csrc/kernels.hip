@@ -1043,11 +1043,12 @@ static ll_status launch_gather_w(const GatherArgs &a, hipStream_t stream)
 // The swizzle moves higher address bits into the bank bits so that lanes reading the same register
 // slot of different layout lanes fall in different banks; reads are data dependent, so conflicts
 // cannot be excluded in general.  U: passes handled together (loads issued back to back).
-template <int W, int U>
-__global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
+template <int W, int U, int TB>
+__global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
+    constexpr uint32_t T = 1u << TB;                 // threads per workgroup
     const uint32_t tid = threadIdx.x;
     const long long first = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk) << a.block_bits;
     const uint32_t block_elems = 1u << a.block_bits;
@@ -1068,14 +1069,14 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
         table[tid] = swz(dl * W);
     }
     // stage the block
-    const uint32_t vec_passes = (block_elems >> VS) >> 8;        // 16-byte vectors per thread (a multiple of U)
+    const uint32_t vec_passes = (block_elems >> VS) >> TB;        // 16-byte vectors per thread (a multiple of U)
     for (uint32_t p = 0; p < vec_passes; p += U) {
         u32x4 x[U];
 #pragma unroll
-        for (int q = 0; q < U; ++q) x[q] = buf_load16(rin, (tid + 256u * (p + q)) * 16u);
+        for (int q = 0; q < U; ++q) x[q] = buf_load16(rin, (tid + T * (p + q)) * 16u);
 #pragma unroll
         for (int q = 0; q < U; ++q) {
-            const uint32_t at = (tid + 256u * (p + q)) * 16u;
+            const uint32_t at = (tid + T * (p + q)) * 16u;
             if constexpr (W == 8) {
                 const u32x2 lo = {x[q].x, x[q].y}, hi = {x[q].z, x[q].w};
                 *reinterpret_cast<u32x2 *>(lds + swz(at)) = lo;
@@ -1097,10 +1098,10 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
         const unsigned long long f = (unsigned long long)first;
         for (int b = a.block_bits; b < 32; ++b) own_t ^= a.own_bit[b] & (0u - (uint32_t)((f >> b) & 1ull));
 #pragma unroll
-        for (int b = 0; b < 8; ++b) own_t ^= a.own_bit[UB + b] & (0u - ((tid >> b) & 1u));
+        for (int b = 0; b < TB; ++b) own_t ^= a.own_bit[UB + b] & (0u - ((tid >> b) & 1u));
     }
     const uint32_t own_s[4] = {0u, a.own_bit[0], a.own_bit[1], a.own_bit[0] ^ a.own_bit[1]};
-    const uint32_t unit_passes = (block_elems >> UB) >> 8;        // units per thread (a multiple of U)
+    const uint32_t unit_passes = (block_elems >> UB) >> TB;        // units per thread (a multiple of U)
     __syncthreads();
 
     for (uint32_t p = 0; p < unit_passes; p += U) {
@@ -1108,19 +1109,19 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
 #pragma unroll
         for (int q = 0; q < U; ++q) {
             if constexpr (UE == 4) {
-                const u32x4 t = buf_load16(rix, (tid + 256u * (p + q)) * 16u);
+                const u32x4 t = buf_load16(rix, (tid + T * (p + q)) * 16u);
                 ix[q][0] = t.x; ix[q][1] = t.y; ix[q][2] = t.z; ix[q][3] = t.w;
             } else {
-                const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rix, (tid + 256u * (p + q)) * 8u, 0, kStream);
+                const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rix, (tid + T * (p + q)) * 8u, 0, kStream);
                 ix[q][0] = t.x; ix[q][1] = t.y;
             }
         }
 #pragma unroll
         for (int q = 0; q < U; ++q) {
             const uint32_t pass = p + q;
-            const uint32_t unit = tid + 256u * pass;
+            const uint32_t unit = tid + T * pass;
             uint32_t own_p = own_t;
-            for (int b = 0; (pass >> b) != 0; ++b) own_p ^= a.own_bit[UB + 8 + b] & (0u - ((pass >> b) & 1u));
+            for (int b = 0; (pass >> b) != 0; ++b) own_p ^= a.own_bit[UB + TB + b] & (0u - ((pass >> b) & 1u));
             const uint32_t self = swz(unit * (uint32_t)(UE * W));  // LDS address of the unit's first element
             uint32_t o[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -1155,36 +1156,50 @@ __global__ __launch_bounds__(256) void k_gather_general(const GatherGenArgs a)
     }
 }
 
-template <int W>
-static ll_status launch_gather_general_w(const GatherGenArgs &a, hipStream_t s)
+template <int W, int TB>
+static ll_status launch_gather_general_wt(const GatherGenArgs &a, hipStream_t s)
 {
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
     const long long block_bytes = (1ll << a.block_bits) * W;
     const size_t lds_bytes = (size_t)block_bytes + 128u * (size_t)(a.na > 0 ? (a.na + 4) / 5 : 1);
-    const dim3 grid((unsigned)a.nblocks), block(256);
-    const int vec_passes = (int)((1ll << a.block_bits) >> VS >> 8), unit_passes = (int)((1ll << a.block_bits) >> (W == 8 ? 9 : 10));
+    const dim3 grid((unsigned)a.nblocks), block(1u << TB);
+    const int vec_passes = (int)((1ll << a.block_bits) >> VS >> TB), unit_passes = (int)((1ll << a.block_bits) >> ((W == 8 ? 1 : 2) + TB));
     if (vec_passes < 1 || unit_passes < 1) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than one pass");
     const int together = vec_passes < unit_passes ? vec_passes : unit_passes;   // both are powers of two
     if (together >= 4) {
         if (lds_bytes > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gather_general<W, 4>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gather_general<W, 4, TB>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 136 * 1024);
             if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
         }
-        launch((k_gather_general<W, 4>), grid, block, lds_bytes, s, a);
+        launch((k_gather_general<W, 4, TB>), grid, block, lds_bytes, s, a);
     } else if (together == 2) {
-        launch((k_gather_general<W, 2>), grid, block, lds_bytes, s, a);
+        launch((k_gather_general<W, 2, TB>), grid, block, lds_bytes, s, a);
     } else {
-        launch((k_gather_general<W, 1>), grid, block, lds_bytes, s, a);
+        launch((k_gather_general<W, 1, TB>), grid, block, lds_bytes, s, a);
     }
     return check_launch("general gather kernel launch");
+}
+
+// Threads per workgroup.  A block is staged, then gathered from, with a barrier between: what hides
+// memory latency is other workgroups on the CU, and a large block leaves room for few of them, so it
+// gets more threads.  Measured on MI355X (TB/s, 256 / 512 / 1024 threads): 128 KiB blocks 3.3-3.5 /
+// 5.2-5.3 / 5.7-5.96; 64 KiB 5.5-5.6 / 6.0 / 6.05-6.16; 32 KiB 5.8-6.0 / 6.0-6.26 / 6.07-6.35; 16 KiB
+// 5.7-6.2 / 5.9-6.36 / 4.8-5.6; 8 KiB 6.3 / 5.5-6.3 / -.
+template <int W>
+static ll_status launch_gather_general_w(const GatherGenArgs &a, hipStream_t s)
+{
+    const long long block_bytes = (1ll << a.block_bits) * W;
+    if (block_bytes >= 32 * 1024) return launch_gather_general_wt<W, 10>(a, s);
+    if (block_bytes >= 16 * 1024) return launch_gather_general_wt<W, 9>(a, s);
+    return launch_gather_general_wt<W, 8>(a, s);
 }
 
 ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *stream)
 {
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     const long long block_bytes = (1ll << a.block_bits) * elem_bytes;
-    if (block_bytes < 4096 || block_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "gather block of %lld bytes", block_bytes);
+    if (block_bytes < 4096 || block_bytes > 128 * 1024) return fail(LL_ERR_UNSUPPORTED, "gather block of %lld bytes", block_bytes);
     if (a.na < 0 || a.na > 16) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", a.na);   // four delta tables
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {

@@ -126,7 +126,9 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     // Lanes that hold fewer than 16 bytes make the shuffle kernel's global accesses narrow (measured
     // 4.6-5.5 TB/s against 6.4-6.5 for the workgroup-staged kernel), so those layouts take the general
     // kernel unless LL_GATHER_GENERAL=0 asks for the wave kernels.
-    const bool narrow = (1 << nreg) * elem_bytes < 16;
+    // One-byte elements need one shuffle each however many a lane holds (measured 4.8 TB/s with 16 per
+    // lane against 5.7-5.9 staged), so they take the general kernel as well.
+    const bool narrow = (1 << nreg) * elem_bytes < 16 || elem_bytes == 1;
     const bool want_general = force ? atoi(force) != 0 : narrow;
     if (lane_only && !want_general) {
         GatherArgs &a = c->wave;
@@ -187,7 +189,9 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     }
     // A block beyond LDS (the axis reaches high register or wave bits of a large tile): the source
     // elements are read straight from memory inside the aligned 2^top block around each element.
-    const bool global = ((long long)elem_bytes << block_bits) > 64 * 1024;
+    // gfx950 has 160 KiB of LDS per CU: blocks up to 128 KiB (plus the delta tables) are staged
+    static const long long lds_max = getenv("LL_GATHER_LDS_MAX") ? atoll(getenv("LL_GATHER_LDS_MAX")) : 128 * 1024;   // experiment knob
+    const bool global = ((long long)elem_bytes << block_bits) > lds_max;
     if (global) block_bits = top;
     if (na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", na);
     GatherGenArgs &g = c->gen;

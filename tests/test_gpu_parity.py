@@ -786,15 +786,15 @@ def test_convert_between_different_register_lane_wave_splits(w):
 
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 def test_gather_along_axes_larger_than_lds(w, monkeypatch):
-    """Axes whose aligned block exceeds 64 KiB are gathered straight from memory: random XOR layouts
-    of 2^16 .. 2^18 elements (every axis then reaches the top bits), a ragged number of tiles, and
-    a permutation layout whose axis 0 is exactly the wave bits of a 2^17-element tile."""
+    """Axes whose aligned block exceeds what LDS stages (128 KiB) are gathered straight from memory;
+    blocks of 64 and 128 KiB are staged by 1024-thread workgroups.  Random XOR layouts on tiles of 64,
+    128 and 256 KiB and of 2^18 elements (every axis then reaches the top bits), a ragged number of
+    tiles, and a permutation layout whose axis 0 is exactly the wave bits of a 2^17-element tile."""
     rng = np.random.default_rng(9300 + w)
-    cases = [(16, [7, 9]), (17, [17]), (18, [6, 6, 6])]
+    d128 = 17 - {1: 0, 2: 1, 4: 2, 8: 3}[w]                          # a tile of 128 KiB
+    cases = [(d128 - 1, [d128 - 1]), (d128, [d128 // 2, d128 - d128 // 2]), (d128 + 1, [d128 + 1]), (18, [6, 6, 6])]
     seen = set()
     for d, dims in cases:
-        if w == 1 and d == 16:
-            d, dims = 17, [8, 9]                                    # 64 KiB of bytes would still fit LDS
         nreg, nlane = 4, 6
         cols = random_invertible(rng, d)
         layout = ll.distributed_layout(nreg, nlane, d - 10, dims, cols)
@@ -807,11 +807,11 @@ def test_gather_along_axes_larger_than_lds(w, monkeypatch):
             idx[::5] -= 1 << dims[axis]
             got = run_gather(layout, axis, inp, idx, d)
             assert np.array_equal(got, oracle.gather(cols, dims, axis, inp, idx)), (d, dims, axis, info)
-    assert "global" in seen
+    assert "global" in seen and "block_staged" in seen
     d, dims = 17, [7, 10]
     cols = [1 << k for k in range(10)] + [1 << (10 + k) for k in range(7)]     # rows = the 7 wave bits
     layout = ll.distributed_layout(4, 6, 7, dims, cols)
-    assert ll.ll_gather_info(layout, 0, w)["kernel_name"] == ("global" if (w << 17) > 65536 else "block_staged")
+    assert ll.ll_gather_info(layout, 0, w)["kernel_name"] == ("global" if (w << 17) > 131072 else "block_staged")
     inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=3 << d, dtype=NP_DTYPES[w])
     idx = rng.integers(0, 1 << 7, size=3 << d, dtype=np.int32)
     assert np.array_equal(run_gather(layout, 0, inp, idx, d), oracle.gather(cols, dims, 0, inp, idx))
