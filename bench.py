@@ -26,15 +26,18 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
 
 
+TABLE_WARMUP = 10      # untimed launches before each table entry (on fresh buffers the first launches run slower)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--only-main", action="store_true", help="skip the per-config table")
     ap.add_argument("--workload", type=int, default=2, help="config id timed as the main line (default 2)")
-    ap.add_argument("--table-steps", type=int, default=30, help="launches per config in the per-config table")
+    ap.add_argument("--table-steps", type=int, default=100, help="launches per config in the per-config table")
     ap.add_argument("--strategy", type=int, default=None,
                     help="force a conversion strategy for every plan (3: element-wide LDS, 4: 128-bit LDS "
                          "where it applies); default: the planner's choice")
@@ -115,12 +118,13 @@ def main() -> int:
         per = [evs[k].elapsed_time(evs[k + 1]) for k in range(steps)]
         return wall_ms, mean_ms, statistics.median(per), min(per)
 
-    def copy_ceiling(nbytes_each, steps=20):
+    def copy_ceiling(nbytes_each, steps=None):
+        steps = steps or max(20, args.table_steps)
         """Plain 16-byte vector copy moving the same read + write footprint."""
         n = max(16, (nbytes_each // 16) * 16)
         src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
         dsts = [torch.empty_like(src) for _ in range(2)]
-        _, mean_ms, _, _ = time_launches(lambda k: ll.ll_copy(src, dsts[k % 2], n), steps, 3)
+        _, mean_ms, _, _ = time_launches(lambda k: ll.ll_copy(src, dsts[k % 2], n), steps, TABLE_WARMUP)
         return 2.0 * n / mean_ms / 1e6
 
     main_cfg = wl.config(args.workload)
@@ -174,7 +178,7 @@ def main() -> int:
             nsets = 2 if cfg.algorithmic_bytes() < (1 << 30) else 1
             l, inf, s = make_case(cfg, nsets)
             steps = args.table_steps if cfg.cid != 1 else max(args.table_steps, 200 if args.table_steps >= 30 else 0)
-            w_ms, m_ms, md_ms, mn_ms = time_launches(l, steps, 3)
+            w_ms, m_ms, md_ms, mn_ms = time_launches(l, steps, TABLE_WARMUP)
             ab = cfg.algorithmic_bytes()
             entry = {"config": cfg.cid, "name": cfg.name, "kernel": inf["strategy_name"], "class": inf["kind_name"],
                      "algorithmic_bytes": ab, "us_mean": round(m_ms * 1e3, 2), "us_median_with_events": round(md_ms * 1e3, 2),
@@ -192,7 +196,7 @@ def main() -> int:
                 os.environ["LL_FORCE_STRATEGY"] = "4"
                 l2, inf2, s2 = make_case(cfg, nsets)
                 del os.environ["LL_FORCE_STRATEGY"]
-                _, md2, _, _ = time_launches(l2, steps, 3)
+                _, md2, _, _ = time_launches(l2, steps, TABLE_WARMUP)
                 entry["through_lds"] = {"kernel": inf2["strategy_name"], "lds_access_bytes": inf2["lds_write_bytes"],
                                         "GBps": round(ab / md2 / 1e6, 1),
                                         "predicted_wavefronts": [inf2["predicted_wavefronts_write"], inf2["predicted_wavefronts_read"]]}
@@ -230,7 +234,7 @@ def main() -> int:
             x = case.gen_data(0, case.ntiles, dev)
             outs = [torch.empty(case.ntiles << case.d_dst, dtype=x.dtype, device=dev) for _ in range(2)]
             _, md_ms, _, mn_ms = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % 2], case.ntiles),
-                                               args.table_steps, 3)
+                                               args.table_steps, TABLE_WARMUP)
             ab = case.algorithmic_bytes()
             btable.append({"name": case.name, "kernel": inf["strategy_name"], "src_tile_bits": case.d_src,
                            "dst_tile_bits": case.d_dst, "logical_bits": case.d_out, "algorithmic_bytes": ab,
@@ -258,7 +262,7 @@ def main() -> int:
             nt = (256 << 20) // (c2.tile_elems * w_)            # 256 MiB per side
             x = wl.raw_bits(21, 0, nt * c2.tile_elems * w_ // 8, dev).view(dt_)
             outs = [torch.empty_like(x) for _ in range(2)]
-            _, md_ms, _, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % 2], nt), args.table_steps, 3)
+            _, md_ms, _, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % 2], nt), args.table_steps, TABLE_WARMUP)
             ab = 2 * nt * c2.tile_elems * w_
             ttable.append({"name": "transpose 128x128, %d-byte elements, %d tiles" % (w_, nt), "kernel": inf["strategy_name"],
                            "lds_access_bytes": [inf["lds_write_bytes"], inf["lds_read_bytes"]], "block_bytes": (1 << inf["block_bits"]) * w_,
@@ -282,7 +286,7 @@ def main() -> int:
             ginfo = ll.ll_gather_info(lay5, axis_, c5.elem_bytes)
             idx5 = wl.gen_index(51 + axis_, 0, c5.ntiles * c5.tile_elems, 1 << c5.out_dim_bits[axis_], dev)
             _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(lay5, axis_, c5.elem_bytes, x5, idx5, out5, c5.ntiles),
-                                           args.table_steps, 3)
+                                           args.table_steps, TABLE_WARMUP)
             for k_ in env_:
                 del os.environ[k_]
             ab = c5.algorithmic_bytes()
@@ -302,7 +306,7 @@ def main() -> int:
         ob = torch.empty_like(xb)
         ib = wl.gen_index(53, 0, ntb << 18, 1 << 9, dev)
         ginfo = ll.ll_gather_info(big, 0, 2)
-        _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(big, 0, 2, xb, ib, ob, ntb), args.table_steps, 3)
+        _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(big, 0, 2, xb, ib, ob, ntb), args.table_steps, TABLE_WARMUP)
         ab = (ntb << 18) * (2 + 2 + 4)
         gtable.append({"name": "row-major 512x512 tile, 2-byte elements, gather along dim 0", "kernel": ginfo["kernel_name"],
                        "axis_bits_reg_lane_wave": [ginfo["axis_reg_bits"], ginfo["axis_lane_bits"], ginfo["axis_wave_bits"]],
@@ -324,7 +328,7 @@ def main() -> int:
             inf = plan.info()
             x = cfg.gen_data(0, cfg.ntiles, dev)
             outs = [torch.empty_like(x) for _ in range(2 if cid_ == 2 else 1)]
-            _, md_ms, _, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % len(outs)], cfg.ntiles), args.table_steps, 3)
+            _, md_ms, _, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % len(outs)], cfg.ntiles), args.table_steps, TABLE_WARMUP)
             ab = cfg.algorithmic_bytes()
             atable.append({"name": "config %d, destination offset 0x%x" % (cid_, off_), "kernel": inf["strategy_name"],
                            "conv_offset": inf["conv_offset"], "algorithmic_bytes": ab, "us_mean": round(md_ms * 1e3, 2),
@@ -353,7 +357,7 @@ def cpu_baseline(cfg):
         return {"value": round(cfg.algorithmic_bytes(nt) / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                 "sample": "oracle_gather on the first %d of %d tiles, single thread" % (nt, cfg.ntiles)}
     nt_table = min(cfg.ntiles, max(1, (512 << 20) // (cfg.tile_elems * cfg.elem_bytes)))   # at most 512 MiB of input
-    nt_plain = min(cfg.ntiles, max(1, (48 << 20) // (cfg.tile_elems * cfg.elem_bytes)))    # about 48 MiB of input
+    nt_plain = min(cfg.ntiles, max(1, (256 << 20) // (cfg.tile_elems * cfg.elem_bytes)))   # about 256 MiB of input: 5 s or so
     src = wl.to_numpy_bits(cfg.gen_data(0, nt_table))
     oracle.convert(cfg.src_bases, cfg.dst_bases, src[: cfg.tile_elems])                    # builds / loads the C library
     best, threads = None, 1

@@ -231,8 +231,8 @@ static __device__ __forceinline__ void lds_get_tr(unsigned char *lds, uint32_t a
 
 // TR = 1: the LDS reads are transposing loads (ds_read_b64_tr_b16 / _tr_b8), V must make the
 // access 8 bytes wide; the read tables then hold the addresses a lane supplies for its group.
-template <int W, int NV, int V, int TR = 0>
-__global__ __launch_bounds__(256) void k_lds_elem(const LdsElemArgs a)
+template <int W, int NV, int V, int TR = 0, int TB = 8>
+__global__ __launch_bounds__(1 << TB) void k_lds_elem(const LdsElemArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) void k_lds_elem(const LdsElemArgs a)
 
     uint32_t ls = 0, ld = 0, lw = 0, lr = 0;
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
+    for (int b = 0; b < TB; ++b) {
         const uint32_t m = 0u - ((tid >> b) & 1u);
         ls ^= a.lane_src[b] & m;
         ld ^= a.lane_dst[b] & m;
@@ -301,17 +301,29 @@ __global__ __launch_bounds__(256) void k_lds_elem(const LdsElemArgs a)
     }
 }
 
-template <int W, int NV, int V>
-static ll_status launch_lds_elem_t(const LdsElemArgs &a, int lds_bytes, hipStream_t stream)
+template <int W, int NV, int V, int TB>
+static ll_status launch_lds_elem_tb(const LdsElemArgs &a, int lds_bytes, hipStream_t stream)
 {
     static const int pad = getenv("LL_LDS_PAD") ? atoi(getenv("LL_LDS_PAD")) : 0;   // experiment knob: caps occupancy
     if (lds_bytes + pad > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lds_elem<W, NV, V>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lds_elem<W, NV, V, 0, TB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
     }
-    launch((k_lds_elem<W, NV, V>), dim3((unsigned)a.nblocks), dim3(256), (size_t)(lds_bytes + pad), stream, a);
+    launch((k_lds_elem<W, NV, V, 0, TB>), dim3((unsigned)a.nblocks), dim3(1u << TB), (size_t)(lds_bytes + pad), stream, a);
     return check_launch("LDS conversion kernel launch");
+}
+
+template <int W, int NV, int V>
+static ll_status launch_lds_elem_t(const LdsElemArgs &a, int lds_bytes, hipStream_t stream)
+{
+    switch (a.thread_bits) {
+    case 8: return launch_lds_elem_tb<W, NV, V, 8>(a, lds_bytes, stream);
+    case 9: if constexpr (NV <= 4) return launch_lds_elem_tb<W, NV, V, 9>(a, lds_bytes, stream); break;
+    case 10: if constexpr (NV <= 4) return launch_lds_elem_tb<W, NV, V, 10>(a, lds_bytes, stream); break;
+    default: break;
+    }
+    return fail(LL_ERR_UNSUPPORTED, "no LDS kernel for 2^%d threads and %d vectors per thread", a.thread_bits, NV);
 }
 
 template <int W, int NV>
@@ -341,7 +353,8 @@ static ll_status launch_lds_elem_n(const LdsElemArgs &a, int nvec, int v, int ld
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads, int lds_bytes,
                           void *stream)
 {
-    if (threads != 256) return fail(LL_ERR_UNSUPPORTED, "LDS kernel runs 256 threads per workgroup");
+    if (threads != (1 << a.thread_bits) || a.thread_bits < 8 || a.thread_bits > 10)
+        return fail(LL_ERR_UNSUPPORTED, "LDS kernel runs 256, 512 or 1024 threads per workgroup");
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     if (lds_bytes <= 0 || lds_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "LDS block of %d bytes", lds_bytes);
     hipStream_t s = static_cast<hipStream_t>(stream);

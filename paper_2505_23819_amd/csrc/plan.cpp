@@ -330,7 +330,8 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     ll_plan_desc &desc = plan->desc;
     LdsElemArgs &a = plan->lds_elem;
     const int vs = ilog2(16u / (unsigned)w);          // elements per 16-byte vector (log2)
-    const int tb = 8;                                 // 256 threads
+    int tb = 8;                                       // 256 threads
+    if (const char *e = getenv("LL_ELEM_THREADS_LOG2")) tb = std::min(10, std::max(8, atoi(e)));     // experiment knob
     // experiment knobs (bytes, powers of two): largest staged block, and the size small tiles are bundled to
     // Small blocks measured best on MI355X (more, shorter-lived workgroups keep about 32-64 KiB in
     // flight per CU, which is where a plain copy also peaks).
@@ -339,13 +340,13 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
 
     BlockGeom geom;
     if (ll_status st = build_blocks(p, d, w, vs + tb, max_block, pref_block, &geom); st != LL_OK) return st;
-    if (geom.n == vs + tb && ((long long)w << d) > 256 * 1024 && !getenv("LL_BLOCK_BYTES")) {
+    if (geom.n == vs + tb && ((long long)w << d) > 1024 * 1024 && !getenv("LL_BLOCK_BYTES")) {
         // One vector per thread and a large tile cut into many such blocks: the runs are as short as
         // the limit allows (4-byte elements: 128 bytes on each side, 32 of them scattered over the
         // tile).  Runs grow on both sides at once, so the next size is four times the block.  Measured
-        // on random XOR layouts of 4-byte elements: tiles up to 256 KiB are as fast or faster with the
-        // small block (16 KiB tiles: 6.36 against 6.09 TB/s), larger ones much faster with the wide
-        // one (2^18 elements: 5.7 -> 6.2, 2^20: 5.0 -> 6.2, 2^22: 4.5 -> 5.9).
+        // on random XOR layouts of 4-byte elements, interleaved runs of both block sizes on 1 GiB of
+        // data (TB/s, 4 KiB against 16 KiB blocks): tiles of 2^12..2^17 elements 6.1-6.4 against 5.9-6.2,
+        // 2^18 6.1 / 6.1, 2^19 5.9 / 6.05, 2^20 5.55 / 6.0, 2^21 5.26 / 6.05, 2^22 4.94 / 5.65, 2^24 4.44 / 5.3-5.5.
         BlockGeom wider;
         if (build_blocks(p, d, w, vs + tb, 2 * max_block, pref_block, &wider) == LL_OK && wider.k > geom.k &&
             ((unsigned)w << wider.n) <= 2 * max_block)
