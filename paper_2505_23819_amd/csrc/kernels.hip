@@ -1198,13 +1198,16 @@ static ll_status launch_gather_general_wt(const GatherGenArgs &a, hipStream_t s)
 // memory latency is other workgroups on the CU, and a large block leaves room for few of them, so it
 // gets more threads.  Measured on MI355X (TB/s, 256 / 512 / 1024 threads): 128 KiB blocks 3.3-3.5 /
 // 5.2-5.3 / 5.7-5.96; 64 KiB 5.5-5.6 / 6.0 / 6.05-6.16; 32 KiB 5.8-6.0 / 6.0-6.26 / 6.07-6.35; 16 KiB
-// 5.7-6.2 / 5.9-6.36 / 4.8-5.6; 8 KiB 6.3 / 5.5-6.3 / -.
+// 5.7-6.2 / 5.9-6.5 / 4.9-5.7; 8 KiB 6.3-6.5 / 4.1-5.7 / - (one-byte elements, whose units are a quarter
+// of the bytes: 5.96 / 6.08 / -).  Interleaved repeats on 512 MiB of data.
 template <int W>
 static ll_status launch_gather_general_w(const GatherGenArgs &a, hipStream_t s)
 {
     const long long block_bytes = (1ll << a.block_bits) * W;
-    if (block_bytes >= 32 * 1024) return launch_gather_general_wt<W, 10>(a, s);
-    if (block_bytes >= 16 * 1024) return launch_gather_general_wt<W, 9>(a, s);
+    int tb = block_bytes >= 32 * 1024 ? 10 : (block_bytes >= 16 * 1024 || (W == 1 && block_bytes >= 8 * 1024)) ? 9 : 8;
+    if (const char *e = getenv("LL_GATHER_THREADS_LOG2")) tb = atoi(e);      // experiment knob
+    if (tb == 10) return launch_gather_general_wt<W, 10>(a, s);
+    if (tb == 9) return launch_gather_general_wt<W, 9>(a, s);
     return launch_gather_general_wt<W, 8>(a, s);
 }
 
