@@ -206,8 +206,9 @@ static __device__ __forceinline__ void lds_get(const unsigned char *lds, uint32_
 }
 
 // W: element bytes, NV: 16-byte vectors per thread, V: log2 elements per LDS access.
-// One workgroup of 256 threads stages one block: coalesced 16-byte loads (thread t, iteration i
-// takes vector t + 256 i of the block's source runs), LDS writes at swizzled offsets, barrier,
+// One workgroup of T = 2^TB threads (256 unless the experiment knob says otherwise) stages one block:
+// coalesced 16-byte loads (thread t, iteration i takes vector t + T i of the block's source runs), LDS
+// writes at swizzled offsets, barrier,
 // LDS reads of the elements of its destination vectors, coalesced 16-byte stores.  Every index
 // map is linear over F2, so an offset is the XOR of per-bit table entries.
 // Read one 8-byte LDS chunk with the transposing load: the address this lane passes is used by
@@ -1043,7 +1044,8 @@ static ll_status launch_gather_w(const GatherArgs &a, hipStream_t stream)
     }
 }
 
-// General gather: any bijective layout, axis bits anywhere inside the block.  256 threads.
+// General gather: any surjective layout (replicas included), axis bits anywhere inside the block.
+// 2^TB threads (256, 512 or 1024: see launch_gather_general_w).
 //   stage   coalesced 16-byte loads of the block of `in`, written to LDS word by word (4-byte words,
 //           8-byte for 8-byte elements) at XOR-swizzled addresses;
 //   gather  a unit of work is 4 consecutive output elements (2 for 8-byte elements): one coalesced
