@@ -299,6 +299,8 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
  *    Sec. 5.5's condition (no wave bits on the axis) is reported by ll_gather_info
  *    (axis_wave_bits == 0) and is not an error here;
  *  - tile bits: LL_ERR_TILE_MIXED.
+ * L may also be a memory layout (one `offset` input dim): in, idx and out are then buffers indexed by
+ * memory offset (a row-major tensor is the identity memory layout) and every bit counts as a register bit.
  * Pointers are DEVICE pointers.  Asynchronous on hip_stream. */
 typedef enum {
     LL_GATHER_SHUFFLE = 0,       /* one ds_bpermute_b32 per 32-bit piece of an element */
@@ -312,7 +314,7 @@ typedef struct {
     int32_t axis_reg_bits;       /* hardware bits a move along the axis can flip, by label */
     int32_t axis_lane_bits;
     int32_t axis_wave_bits;
-    int32_t paper_rounds;        /* 2^axis_reg_bits: the shuffle rounds of Sec. 5.5 */
+    int32_t paper_rounds;        /* 2^axis_reg_bits: the shuffle rounds of Sec. 5.5 (0 for a memory layout) */
     int32_t block_bytes;         /* bytes of `in` one wave (kernels 0, 1) or workgroup (kernel 2) stages; kernel 3:
                                     the aligned block a source lies in (saturates at 2^31 - 1) */
 } ll_gather_desc;

@@ -77,15 +77,18 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
 struct GatherChoice {
     int kernel = 0;                    // ll_gather_desc.kernel
     int axis_reg_bits = 0, axis_lane_bits = 0, axis_wave_bits = 0;
+    bool memory = false;               // memory layout: no registers, lanes or waves
     GatherArgs wave = {};              // shuffle / wave-staged kernels
     GatherGenArgs gen = {};            // workgroup-staged kernel
 };
 
 static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, GatherChoice *c)
 {
-    for (int i = 0; i < L->n_in; ++i)
-        if (L->in_dims[i].label == LL_IN_OFFSET)
-            return fail(LL_ERR_INVALID_ARG, "gather needs a distributed layout (register / lane / wave / tile inputs)");
+    // A memory layout (one `offset` input, Sec. 4.3) is a buffer indexed by memory offset: no lanes or
+    // waves to shuffle between, every bit counts as a register bit and the staged kernels serve it.
+    bool memory = false;
+    for (int i = 0; i < L->n_in; ++i) memory |= L->in_dims[i].label == LL_IN_OFFSET;
+    c->memory = memory;
     if (axis < 0 || axis >= L->n_out) return fail(LL_ERR_INVALID_ARG, "axis %d of a %d-dim tensor", axis, L->n_out);
     if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8)
         return fail(LL_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8 (got %d)", elem_bytes);
@@ -97,7 +100,8 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     mat linv;
     if (!f2::right_inverse(L->bases, L->d_out, &linv)) return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
     const int nreg = L->bits_of(LL_IN_REG), nlane = L->bits_of(LL_IN_LANE);
-    const int lane0 = L->first_bit_of(LL_IN_LANE), wave0 = L->first_bit_of(LL_IN_WAVE), tile0 = L->first_bit_of(LL_IN_TILE);
+    const int lane0 = memory ? d : L->first_bit_of(LL_IN_LANE), wave0 = memory ? d : L->first_bit_of(LL_IN_WAVE);
+    const int tile0 = memory ? d : L->first_bit_of(LL_IN_TILE);
     int axis_shift = 0;
     for (int k = L->n_out - 1; k > axis; --k) axis_shift += L->out_dims[k].nbits;
     const int na = L->out_dims[axis].nbits;
@@ -223,7 +227,7 @@ ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gathe
     out->axis_reg_bits = c.axis_reg_bits;
     out->axis_lane_bits = c.axis_lane_bits;
     out->axis_wave_bits = c.axis_wave_bits;
-    out->paper_rounds = 1 << c.axis_reg_bits;
+    out->paper_rounds = c.memory ? 0 : 1 << c.axis_reg_bits;
     const long long gen_bytes = (long long)elem_bytes << c.gen.block_bits;
     out->block_bytes = c.kernel == LL_GATHER_BLOCK_STAGED || c.kernel == LL_GATHER_GLOBAL
                            ? (int32_t)std::min(gen_bytes, (long long)INT32_MAX)

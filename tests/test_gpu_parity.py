@@ -854,3 +854,28 @@ def test_gather_under_broadcasting_layouts(w, monkeypatch):
         idx = rng.integers(0, 64, size=32 << 12, dtype=np.int32)
         assert np.array_equal(run_gather(s, 0, inp, idx, 12), oracle.gather_general(os_.bases, [6], 0, inp, idx))
     assert "block_staged" in seen
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_gather_on_memory_layouts(w):
+    """in, idx and out as buffers indexed by memory offset: a row-major tensor (the identity memory
+    layout) against torch.gather on the logical view, and an mma-swizzled buffer against the oracle."""
+    rng = np.random.default_rng(9800 + w)
+    shape = (5, 64, 128)
+    ident = ll.ll_layout_create([(ll.LL_IN_OFFSET, 13)], [6, 7], [1 << k for k in range(13)])
+    tdt = {1: torch.uint8, 2: torch.int16, 4: torch.int32, 8: torch.int64}[w]
+    for axis in (0, 1):
+        assert ll.ll_gather_info(ident, axis, w)["paper_rounds"] == 0
+        x = torch.from_numpy(rng.integers(0, 127, size=shape).astype(NP_DTYPES[w]).view({1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}[w])).cuda()
+        idx = torch.from_numpy(rng.integers(0, shape[1 + axis], size=shape).astype(np.int32)).cuda()
+        out = torch.full_like(x, 0x5A)
+        ll.ll_gather(ident, axis, w, x, idx, out, shape[0])
+        torch.cuda.synchronize()
+        assert torch.equal(out, torch.gather(x, 1 + axis, idx.to(torch.int64))), axis
+    sw = ll.ll_layout_mma_swizzle(6, 6, 8 // w if w < 8 else 1, 1, 8)
+    osw = oracle.mma_swizzle_layout(6, 6, 8 // w if w < 8 else 1, 1, 8)
+    assert sw.bases == osw.bases
+    inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=6 << 12, dtype=NP_DTYPES[w])
+    for axis in (0, 1):
+        idx = rng.integers(0, 64, size=6 << 12, dtype=np.int32)
+        assert np.array_equal(run_gather(sw, axis, inp, idx, 12), oracle.gather(osw.bases, [6, 6], axis, inp, idx)), axis
