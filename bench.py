@@ -298,22 +298,26 @@ def main() -> int:
             del idx5
         del x5, out5
         torch.cuda.empty_cache()
-        # an axis whose block exceeds LDS: rows of a row-major 512 x 512 two-byte tile (512 KiB) held 16
-        # elements per lane; every element comes from another row, read straight from memory
-        big = ll.distributed_layout(4, 6, 8, [9, 9], [1 << k for k in range(18)])
+        # axes whose aligned block exceeds LDS, row-major two-byte tiles of 2^18 elements (512 KiB), gather along
+        # the rows: 512 x 512 is staged as 512 rows x 128-byte runs; 8192 x 32 has no closed block with runs of
+        # 64 bytes that fits LDS and is read straight from memory
         ntb = 512
         xb = wl.raw_bits(23, 0, (ntb << 18) * 2 // 8, dev).view(torch.int16)
         ob = torch.empty_like(xb)
-        ib = wl.gen_index(53, 0, ntb << 18, 1 << 9, dev)
-        ginfo = ll.ll_gather_info(big, 0, 2)
-        _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(big, 0, 2, xb, ib, ob, ntb), args.table_steps, TABLE_WARMUP)
-        ab = (ntb << 18) * (2 + 2 + 4)
-        gtable.append({"name": "row-major 512x512 tile, 2-byte elements, gather along dim 0", "kernel": ginfo["kernel_name"],
-                       "axis_bits_reg_lane_wave": [ginfo["axis_reg_bits"], ginfo["axis_lane_bits"], ginfo["axis_wave_bits"]],
-                       "paper_rounds": ginfo["paper_rounds"], "staged_bytes": ginfo["block_bytes"],
-                       "algorithmic_bytes": ab, "us_mean": round(md_ms * 1e3, 2), "GBps": round(ab / md_ms / 1e6, 1),
-                       "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)})
-        del xb, ob, ib
+        for rows_b, cols_b in ((9, 9), (13, 5)):
+            big = ll.distributed_layout(4, 6, 8, [rows_b, cols_b], [1 << k for k in range(18)])
+            ib = wl.gen_index(53, 0, ntb << 18, 1 << rows_b, dev)
+            ginfo = ll.ll_gather_info(big, 0, 2)
+            _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(big, 0, 2, xb, ib, ob, ntb), args.table_steps, TABLE_WARMUP)
+            ab = (ntb << 18) * (2 + 2 + 4)
+            gtable.append({"name": "row-major %dx%d tile, 2-byte elements, gather along dim 0" % (1 << rows_b, 1 << cols_b),
+                           "kernel": ginfo["kernel_name"],
+                           "axis_bits_reg_lane_wave": [ginfo["axis_reg_bits"], ginfo["axis_lane_bits"], ginfo["axis_wave_bits"]],
+                           "paper_rounds": ginfo["paper_rounds"], "staged_bytes": ginfo["block_bytes"],
+                           "algorithmic_bytes": ab, "us_mean": round(md_ms * 1e3, 2), "GBps": round(ab / md_ms / 1e6, 1),
+                           "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)})
+            del ib
+        del xb, ob
         torch.cuda.empty_cache()
         result["gather_variants"] = gtable
 

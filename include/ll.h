@@ -293,9 +293,10 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
  * Moving along the axis changes the hardware index by L^-1 (L^+) of the axis bits:
  *  - lane bits only (the paper's condition, Sec. 5.5, with one round): cross-lane shuffles, or
  *    wave-private LDS staging when a lane holds more than 16 bytes;
- *  - register and / or wave bits as well: the aligned block of image elements those bits span is
- *    staged in workgroup LDS when it is at most 128 KiB; a larger block is gathered straight from
- *    memory, element by element, inside that block (slower: every element is its own access).
+ *  - register and / or wave bits as well: a block of image elements closed under moves along the axis
+ *    (the span of those index changes plus contiguous runs of 128 bytes where the size allows) is
+ *    staged in workgroup LDS, at most 128 KiB; if no such block with runs of at least 64 bytes fits,
+ *    every element is gathered straight from memory (slower: every element is its own access).
  *    Sec. 5.5's condition (no wave bits on the axis) is reported by ll_gather_info
  *    (axis_wave_bits == 0) and is not an error here;
  *  - tile bits: LL_ERR_TILE_MIXED.
@@ -306,7 +307,7 @@ typedef enum {
     LL_GATHER_SHUFFLE = 0,       /* one ds_bpermute_b32 per 32-bit piece of an element */
     LL_GATHER_WAVE_STAGED = 1,   /* coalesced access, source rows staged in wave-private LDS */
     LL_GATHER_BLOCK_STAGED = 2,  /* general: a block closed under the axis staged in workgroup LDS */
-    LL_GATHER_GLOBAL = 3         /* the block exceeds LDS: element-wide reads from memory inside the block */
+    LL_GATHER_GLOBAL = 3         /* no closed block fits LDS: element-wide reads from memory */
 } ll_gather_kernel;
 
 typedef struct {
@@ -316,7 +317,7 @@ typedef struct {
     int32_t axis_wave_bits;
     int32_t paper_rounds;        /* 2^axis_reg_bits: the shuffle rounds of Sec. 5.5 (0 for a memory layout) */
     int32_t block_bytes;         /* bytes of `in` one wave (kernels 0, 1) or workgroup (kernel 2) stages; kernel 3:
-                                    the aligned block a source lies in (saturates at 2^31 - 1) */
+                                    the aligned range a source lies in (saturates at 2^31 - 1) */
 } ll_gather_desc;
 
 /* What ll_gather would do for this layout, axis and element size (same checks and errors). */

@@ -1064,14 +1064,27 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
     constexpr uint32_t T = 1u << TB;                 // threads per workgroup
+    constexpr int UB = (W == 8) ? 1 : 2;             // log2 elements per unit: one 16-byte (8-byte) index load
+    constexpr int UE = 1 << UB;
     const uint32_t tid = threadIdx.x;
-    const long long first = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk) << a.block_bits;
     const uint32_t block_elems = 1u << a.block_bits;
-    const long long left = a.total_elems - first;
-    const uint32_t valid = left >= (long long)block_elems ? block_elems : (uint32_t)left;
-    const __amdgpu_buffer_rsrc_t rin = make_rsrc(static_cast<const unsigned char *>(a.in) + (size_t)first * W, valid * W);
-    const __amdgpu_buffer_rsrc_t rix = make_rsrc(reinterpret_cast<const unsigned char *>(a.idx) + (size_t)first * 4, valid * 4);
-    const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (size_t)first * W, valid * W);
+    // which block of which tile group: the block is a coset of the subspace spanned by `embed`
+    const long long blk = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk);
+    const long long group = blk >> a.coset_bits;
+    const uint32_t cidx = (uint32_t)(blk & ((1ll << a.coset_bits) - 1));
+    uint32_t cbase = 0, own_c = a.own_const;
+    for (int b = 0; b < a.coset_bits; ++b) {
+        const uint32_t m = 0u - ((cidx >> b) & 1u);
+        cbase ^= a.coset[b] & m;
+        own_c ^= a.own_coset[b] & m;
+    }
+    const int gshift = a.d + a.group_bits;
+    const long long left = a.ntiles - (group << a.group_bits);
+    const uint32_t tiles_here = left > (1ll << a.group_bits) ? (1u << a.group_bits) : (uint32_t)left;
+    const uint32_t valid = tiles_here << a.d;        // elements of this group that exist (a prefix)
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(static_cast<const unsigned char *>(a.in) + (((size_t)group << gshift) * W), valid * W);
+    const __amdgpu_buffer_rsrc_t rix = make_rsrc(reinterpret_cast<const unsigned char *>(a.idx) + (((size_t)group << gshift) * 4), valid * 4);
+    const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (((size_t)group << gshift) * W), valid * W);
     auto swz = [&](uint32_t addr) { return addr ^ (((addr >> a.swz_shift) & a.swz_mask) << a.swz_to); };
     uint32_t *table = reinterpret_cast<uint32_t *>(lds + ((size_t)block_elems * W));
     const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;      // an axis of one element still reads table 0 (all zero)
@@ -1083,12 +1096,26 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
         for (int b = 0; b < a.na; ++b) dl ^= a.delta[b] & (0u - ((x >> b) & 1u));
         table[tid] = swz(dl * W);
     }
+    // Group-relative element offsets of this thread's vectors and units: block-local index -> image
+    // index is linear (XOR of `embed` entries), identity inside a run.
+    uint32_t vec_t = cbase, unit_t = cbase, own_t = own_c;
+#pragma unroll
+    for (int b = 0; b < TB; ++b) {
+        const uint32_t m = 0u - ((tid >> b) & 1u);
+        vec_t ^= a.embed[VS + b] & m;
+        unit_t ^= a.embed[UB + b] & m;
+        own_t ^= a.own_bit[UB + b] & m;
+    }
     // stage the block
     const uint32_t vec_passes = (block_elems >> VS) >> TB;        // 16-byte vectors per thread (a multiple of U)
     for (uint32_t p = 0; p < vec_passes; p += U) {
         u32x4 x[U];
 #pragma unroll
-        for (int q = 0; q < U; ++q) x[q] = buf_load16(rin, (tid + T * (p + q)) * 16u);
+        for (int q = 0; q < U; ++q) {
+            uint32_t off = vec_t;
+            for (int b = 0; ((p + q) >> b) != 0; ++b) off ^= a.embed[VS + TB + b] & (0u - (((p + q) >> b) & 1u));
+            x[q] = buf_load16(rin, off * W);
+        }
 #pragma unroll
         for (int q = 0; q < U; ++q) {
             const uint32_t at = (tid + T * (p + q)) * 16u;
@@ -1104,44 +1131,40 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
             }
         }
     }
-    // axis coordinate of an element = XOR of the contributions of the set bits of its hardware
-    // index: the block's bits (uniform), this thread's bits, the pass's bits, the slot's bits
-    constexpr int UB = (W == 8) ? 1 : 2;             // log2 elements per unit: one 16-byte (8-byte) index load
-    constexpr int UE = 1 << UB;
-    uint32_t own_t = a.own_const;
-    {
-        const unsigned long long f = (unsigned long long)first;
-        for (int b = a.block_bits; b < 32; ++b) own_t ^= a.own_bit[b] & (0u - (uint32_t)((f >> b) & 1ull));
-#pragma unroll
-        for (int b = 0; b < TB; ++b) own_t ^= a.own_bit[UB + b] & (0u - ((tid >> b) & 1u));
-    }
+    // axis coordinate of an element = XOR of the contributions of the set bits of its block-local
+    // index (thread bits, pass bits, slot bits) and of the block's own offset
     const uint32_t own_s[4] = {0u, a.own_bit[0], a.own_bit[1], a.own_bit[0] ^ a.own_bit[1]};
     const uint32_t unit_passes = (block_elems >> UB) >> TB;        // units per thread (a multiple of U)
     __syncthreads();
 
     for (uint32_t p = 0; p < unit_passes; p += U) {
-        uint32_t ix[U][UE];
+        uint32_t ix[U][UE], uoff[U], own_p[U];
 #pragma unroll
         for (int q = 0; q < U; ++q) {
+            const uint32_t pass = p + q;
+            uoff[q] = unit_t;
+            own_p[q] = own_t;
+            for (int b = 0; (pass >> b) != 0; ++b) {
+                const uint32_t m = 0u - ((pass >> b) & 1u);
+                uoff[q] ^= a.embed[UB + TB + b] & m;
+                own_p[q] ^= a.own_bit[UB + TB + b] & m;
+            }
             if constexpr (UE == 4) {
-                const u32x4 t = buf_load16(rix, (tid + T * (p + q)) * 16u);
+                const u32x4 t = buf_load16(rix, uoff[q] * 4u);
                 ix[q][0] = t.x; ix[q][1] = t.y; ix[q][2] = t.z; ix[q][3] = t.w;
             } else {
-                const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rix, (tid + T * (p + q)) * 8u, 0, kStream);
+                const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rix, uoff[q] * 4u, 0, kStream);
                 ix[q][0] = t.x; ix[q][1] = t.y;
             }
         }
 #pragma unroll
         for (int q = 0; q < U; ++q) {
-            const uint32_t pass = p + q;
-            const uint32_t unit = tid + T * pass;
-            uint32_t own_p = own_t;
-            for (int b = 0; (pass >> b) != 0; ++b) own_p ^= a.own_bit[UB + TB + b] & (0u - ((pass >> b) & 1u));
+            const uint32_t unit = tid + T * (p + q);
             const uint32_t self = swz(unit * (uint32_t)(UE * W));  // LDS address of the unit's first element
             uint32_t o[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int s = 0; s < UE; ++s) {
-                const uint32_t x = (ix[q][s] ^ own_p ^ own_s[s]) & a.axis_mask;
+                const uint32_t x = (ix[q][s] ^ own_p[q] ^ own_s[s]) & a.axis_mask;
                 uint32_t t = table[x & 31u];
                 if (ntab > 1) t ^= table[32u + ((x >> 5) & 31u)];
                 if (ntab > 2) t ^= table[64u + ((x >> 10) & 31u)];
@@ -1160,12 +1183,12 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
             }
             if constexpr (W >= 4) {
                 const u32x4 v = {o[0], o[1], o[2], o[3]};
-                buf_store16(rout, unit * 16u, v);
+                buf_store16(rout, uoff[q] * W, v);
             } else if constexpr (W == 2) {
                 const u32x2 v = {o[0], o[1]};
-                __builtin_amdgcn_raw_buffer_store_b64(v, rout, unit * 8u, 0, kStream);
+                __builtin_amdgcn_raw_buffer_store_b64(v, rout, uoff[q] * W, 0, kStream);
             } else {
-                __builtin_amdgcn_raw_buffer_store_b32(o[0], rout, unit * 4u, 0, kStream);
+                __builtin_amdgcn_raw_buffer_store_b32(o[0], rout, uoff[q] * W, 0, kStream);
             }
         }
     }
@@ -1218,7 +1241,8 @@ ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *st
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     const long long block_bytes = (1ll << a.block_bits) * elem_bytes;
     if (block_bytes < 4096 || block_bytes > 128 * 1024) return fail(LL_ERR_UNSUPPORTED, "gather block of %lld bytes", block_bytes);
-    if (a.na < 0 || a.na > 16) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", a.na);   // four delta tables
+    if (a.na < 0 || a.na > 20) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", a.na);   // four delta tables of five bits
+    if (a.block_bits > 31 || a.coset_bits < 0 || a.coset_bits > kMaxCosetBits) return fail(LL_ERR_INVALID_ARG, "internal: gather block geometry");
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {
     case 1: return launch_gather_general_w<1>(a, s);

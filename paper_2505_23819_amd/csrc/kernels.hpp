@@ -126,12 +126,20 @@ struct GatherGenArgs {
     const int32_t *idx;
     void *out;
     long long nblocks;
+    long long ntiles;
     long long total_elems;               // ntiles * 2^d
-    int block_bits;                      // log2 elements per workgroup block
+    int d;                               // index bits of one tile
+    int group_bits;                      // staged kernel: log2 tiles bundled into a group
+    int coset_bits;                      // staged kernel: log2 blocks per group
+    int block_bits;                      // log2 elements per block (staged: dimension of the block's subspace;
+                                         // memory-direct: the aligned range a source lies in)
     int na;                              // axis bits
     uint32_t axis_mask;
-    uint32_t delta[kMaxAxisBits];        // per axis bit: XOR on the block-local hardware index
-    uint32_t own_bit[32];                // per hardware-index bit (0 above the tile): axis coordinate contribution
+    uint32_t delta[kMaxAxisBits];        // per axis bit: XOR on the block-local index (staged) / the element index (memory-direct)
+    uint32_t embed[32];                  // staged: group-relative element offset of block-local bit j (1 << j inside a run)
+    uint32_t coset[kMaxCosetBits];       // staged: group-relative element offset per block-index bit
+    uint32_t own_bit[32];                // axis coordinate contribution per block-local bit (staged) / element-index bit
+    uint32_t own_coset[kMaxCosetBits];   // staged: ... per block-index bit
     uint32_t own_const;                  // affine layouts: constant part of every element's axis coordinate
     int xcd_chunk;                       // log2 of the consecutive blocks one XCD takes, -1: natural order
     int swz_shift, swz_to;               // LDS byte address ^= ((address >> swz_shift) & swz_mask) << swz_to

@@ -176,45 +176,95 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     }
 
     // General case: the axis occupies register and / or wave bits (or the layout is not wave64
-    // shaped).  The smallest block closed under moves along the axis is the aligned range of
-    // 2^top image elements, top = highest hardware bit any axis step can flip; one workgroup stages
-    // it in LDS.  The paper's shuffle rounds (2^|register bits of the axis| per element) are
-    // replaced by one LDS read per element: a round needs a register index chosen per lane at run
-    // time, and ds_bpermute_b32 goes through the same LDS crossbar anyway.
+    // shaped).  A set of image elements closed under moves along the axis is a coset of any
+    // subspace U that contains the deltas; one workgroup stages one coset in LDS.  The paper's
+    // shuffle rounds (2^|register bits of the axis| per element) are replaced by one LDS read per
+    // element: a round needs a register index chosen per lane at run time, and ds_bpermute_b32 goes
+    // through the same LDS crossbar anyway.
+    //   U = span(e_0 .. e_{c-1}) + span(deltas): the low c index bits give contiguous runs of 2^c
+    //   elements (coalesced global access: 128 bytes where the block allows), the deltas close it.
+    //   Bits between the runs and the deltas (the columns of a row gather in a row-major tile)
+    //   select the coset, so the block need not be the aligned range up to the highest delta bit.
+    if (na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", na);
     const int vs = 31 - __builtin_clz(16u / (unsigned)elem_bytes);
+    const int ubits = elem_bytes == 8 ? 1 : 2;                        // log2 elements per unit of the gather phase
+    const int wlog = 31 - __builtin_clz((unsigned)elem_bytes);
     const int top = touched ? 64 - __builtin_clzll((unsigned long long)touched) : 0;
-    int block_bits = std::max(std::max(top, vs + 8), 10);     // at least one 16-byte vector and one 4-element unit per thread
+    // gfx950 has 160 KiB of LDS per CU: blocks up to 128 KiB (plus the delta tables) are staged
+    static const long long lds_max = getenv("LL_GATHER_LDS_MAX") ? atoll(getenv("LL_GATHER_LDS_MAX")) : 128 * 1024;   // experiment knob
+    const int max_bits = 63 - __builtin_clzll((unsigned long long)std::max(1ll, lds_max / elem_bytes));
+    int min_bits = std::max(vs + 8, 10);                               // one 16-byte vector and one unit per thread
     {
         // 8 KiB blocks measured best on MI355X when the axis leaves the choice (4 KiB: -5 %, 32 KiB: -4 %)
         const char *bb = getenv("LL_GATHER_BLOCK_BYTES");          // experiment knob
         const int bytes = bb ? atoi(bb) : 8192;
-        const int want = 31 - __builtin_clz((unsigned)std::max(1, bytes / elem_bytes));
-        block_bits = std::max(block_bits, want);
+        min_bits = std::max(min_bits, 31 - __builtin_clz((unsigned)std::max(1, bytes / elem_bytes)));
     }
-    // A block beyond LDS (the axis reaches high register or wave bits of a large tile): the source
-    // elements are read straight from memory inside the aligned 2^top block around each element.
-    // gfx950 has 160 KiB of LDS per CU: blocks up to 128 KiB (plus the delta tables) are staged
-    static const long long lds_max = getenv("LL_GATHER_LDS_MAX") ? atoll(getenv("LL_GATHER_LDS_MAX")) : 128 * 1024;   // experiment knob
-    const bool global = ((long long)elem_bytes << block_bits) > lds_max;
-    if (global) block_bits = top;
-    if (na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", na);
+    const int gb = std::max(0, min_bits - d);                          // small tiles are bundled
+    const int D = d + gb;
+    auto dim_u = [&](int cc, mat *basis) {
+        mat us, cand;
+        for (int j = 0; j < cc; ++j) us.push_back(vec(1) << j);
+        const vec low = (vec(1) << cc) - 1;
+        for (int b = 0; b < na; ++b) cand.push_back(linv[axis_shift + b] & ~low);
+        for (vec x : f2::extend(us, cand)) us.push_back(x);
+        if (basis) *basis = us;
+        return (int)us.size();
+    };
+    const int cmin = std::max(vs, ubits);
+    int cb = std::min(D, std::max(cmin, 7 - wlog));                    // runs of 128 bytes to start with
+    while (cb > cmin && dim_u(cb, nullptr) > max_bits) --cb;           // shorter runs if the block would not fit LDS
+    while (cb < D && dim_u(cb, nullptr) < min_bits) ++cb;              // longer runs up to the preferred block size
+    mat us;
+    const int n = dim_u(cb, &us);
+    // A block beyond LDS even with the shortest runs, or runs under 64 bytes (every line would be
+    // fetched by several blocks): the source elements are read straight from memory inside the
+    // aligned 2^top block around each element.
+    // (the staged kernel addresses a tile group through 32-bit buffer offsets)
+    const bool global = n > max_bits || (elem_bytes << cb) < 64 || D + wlog > 31;
     GatherGenArgs &g = c->gen;
     std::memset(&g, 0, sizeof(g));
-    g.block_bits = block_bits;
     g.na = na;
     g.axis_mask = (uint32_t)((vec(1) << na) - 1);
-    for (int b = 0; b < na; ++b) g.delta[b] = (uint32_t)linv[axis_shift + b];
-    for (int b = 0; b < d && b < 32; ++b) g.own_bit[b] = axis_coord(vec(1) << b);
     g.own_const = own_const;
+    g.d = d;
+    if (global) {
+        g.block_bits = top;
+        for (int b = 0; b < na; ++b) g.delta[b] = (uint32_t)linv[axis_shift + b];
+        for (int b = 0; b < d && b < 32; ++b) g.own_bit[b] = axis_coord(vec(1) << b);
+        c->kernel = LL_GATHER_GLOBAL;
+        return LL_OK;
+    }
+    if (n < min_bits) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than the kernel's unit of work");
+    g.block_bits = n;
+    g.group_bits = gb;
+    f2::Basis ub;
+    for (int j = 0; j < n; ++j) ub.add(us[j], vec(1) << j);
+    for (int b = 0; b < na; ++b) {
+        vec tag = 0;
+        if (ub.reduce(linv[axis_shift + b], &tag) != 0) return fail(LL_ERR_INVALID_ARG, "internal: gather block not closed under the axis");
+        g.delta[b] = (uint32_t)tag;                                    // in block-local coordinates
+    }
+    for (int j = 0; j < n; ++j) {
+        g.embed[j] = (uint32_t)us[j];
+        g.own_bit[j] = (us[j] >> d) ? 0u : axis_coord(us[j]);          // bundled-tile bits carry no coordinate
+    }
+    const mat comp = f2::complement(us, D);
+    if ((int)comp.size() > kMaxCosetBits) return fail(LL_ERR_UNSUPPORTED, "internal: too many gather blocks per tile");
+    g.coset_bits = (int)comp.size();
+    for (size_t k = 0; k < comp.size(); ++k) {
+        g.coset[k] = (uint32_t)comp[k];
+        g.own_coset[k] = (comp[k] >> d) ? 0u : axis_coord(comp[k] & all);
+    }
     // LDS swizzle: the bank field is address bits [ub, ub + 5); bring layout-lane bits into it
-    const int ub = elem_bytes == 8 ? 3 : 2;
+    const int ubk = elem_bytes == 8 ? 3 : 2;
     const int rb = 31 - __builtin_clz((unsigned)((1 << nreg) * elem_bytes));
-    const int t = std::min(std::max(rb, ub), ub + 5);
-    const int nx = std::min(5, t - ub);
-    g.swz_shift = std::max(ub + 5, rb);
-    g.swz_to = ub;
+    const int t = std::min(std::max(rb, ubk), ubk + 5);
+    const int nx = std::min(5, t - ubk);
+    g.swz_shift = std::max(ubk + 5, rb);
+    g.swz_to = ubk;
     g.swz_mask = (1u << nx) - 1;
-    c->kernel = global ? LL_GATHER_GLOBAL : LL_GATHER_BLOCK_STAGED;
+    c->kernel = LL_GATHER_BLOCK_STAGED;
     return LL_OK;
 }
 
@@ -275,8 +325,10 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
         g.in = in;
         g.idx = idx;
         g.out = out;
+        g.ntiles = ntiles;
         g.total_elems = ntiles << d;
-        g.nblocks = (g.total_elems + (1ll << g.block_bits) - 1) >> g.block_bits;
+        const long long ngroups = (ntiles + (1ll << g.group_bits) - 1) >> g.group_bits;
+        g.nblocks = ngroups << g.coset_bits;
         {
             // XCD-aware block order: 512 KiB of consecutive blocks per XCD (rows of config 5: 5.99 -> 6.36 TB/s)
             const char *e = getenv("LL_GATHER_XCD_CHUNK");        // experiment knob: blocks (power of two), 0 = off

@@ -141,12 +141,12 @@ def test_narrow_transpose_full_size_sampled(w, force, monkeypatch):
 
 
 def test_gather_beyond_lds_full_size_sampled():
-    """The memory-direct gather in the configuration bench.py times: 512 row-major 512 x 512 tiles of
-    two-byte elements, gather along the rows (the axis block is the whole 512 KiB tile)."""
+    """A gather whose aligned axis block exceeds LDS, in the configuration bench.py times: 512 row-major
+    512 x 512 tiles of two-byte elements, gather along the rows (staged as 512 rows x 128-byte runs)."""
     d, ntiles = 18, 512
     bases = [1 << k for k in range(d)]
     layout = ll.distributed_layout(4, 6, 8, [9, 9], bases)
-    assert ll.ll_gather_info(layout, 0, 2)["kernel_name"] == "global"
+    assert ll.ll_gather_info(layout, 0, 2)["block_bytes"] == 65536
     inp = wl.raw_bits(23, 0, (ntiles << d) * 2 // 8, "cuda").view(torch.int16)
     idx = wl.gen_index(53, 0, ntiles << d, 1 << 9, "cuda")
     out = torch.empty_like(inp)
@@ -162,3 +162,25 @@ def test_gather_beyond_lds_full_size_sampled():
     # at full size: the layout is the identity, so the definition is torch.gather on the logical view
     ref = torch.gather(inp.view(ntiles, 512, 512), 1, idx.view(ntiles, 512, 512).to(torch.int64))
     assert torch.equal(out.view(ntiles, 512, 512), ref)
+
+
+def test_gather_memory_direct_full_size():
+    """The memory-direct kernel at size: 256 MiB of 8192 x 32 two-byte tiles gathered along the rows
+    (no block closed under the rows fits LDS with runs of 64 bytes), against torch.gather on the
+    logical view and sampled tiles against the oracle."""
+    d, ntiles = 18, 512
+    bases = [1 << k for k in range(d)]
+    layout = ll.distributed_layout(4, 6, 8, [13, 5], bases)
+    assert ll.ll_gather_info(layout, 0, 2)["kernel_name"] == "global"
+    inp = wl.raw_bits(24, 0, (ntiles << d) * 2 // 8, "cuda").view(torch.int16)
+    idx = wl.gen_index(54, 0, ntiles << d, 1 << 13, "cuda")
+    out = torch.empty_like(inp)
+    out.fill_(0x5A5A)
+    ll.ll_gather(layout, 0, 2, inp, idx, out, ntiles)
+    torch.cuda.synchronize()
+    ref = torch.gather(inp.view(ntiles, 8192, 32), 1, idx.view(ntiles, 8192, 32).to(torch.int64))
+    assert torch.equal(out.view(ntiles, 8192, 32), ref)
+    te = 1 << d
+    for t in sample_tiles(ntiles, 3, 19):
+        want = oracle.gather(bases, [13, 5], 0, inp[t * te:(t + 1) * te].cpu().numpy().view(np.uint16), idx[t * te:(t + 1) * te].cpu().numpy())
+        assert np.array_equal(out[t * te:(t + 1) * te].cpu().numpy().view(np.uint16), want), f"tile {t}"

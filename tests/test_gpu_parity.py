@@ -811,7 +811,8 @@ def test_gather_along_axes_larger_than_lds(w, monkeypatch):
     d, dims = 17, [7, 10]
     cols = [1 << k for k in range(10)] + [1 << (10 + k) for k in range(7)]     # rows = the 7 wave bits
     layout = ll.distributed_layout(4, 6, 7, dims, cols)
-    assert ll.ll_gather_info(layout, 0, w)["kernel_name"] == ("global" if (w << 17) > 131072 else "block_staged")
+    # closed under the 7 wave bits with 128-byte runs: 2^7 rows of runs, far smaller than the aligned range
+    assert ll.ll_gather_info(layout, 0, w)["block_bytes"] == 128 * 128
     inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=3 << d, dtype=NP_DTYPES[w])
     idx = rng.integers(0, 1 << 7, size=3 << d, dtype=np.int32)
     assert np.array_equal(run_gather(layout, 0, inp, idx, d), oracle.gather(cols, dims, 0, inp, idx))

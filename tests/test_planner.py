@@ -298,13 +298,19 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     with pytest.raises(ll.LLError) as e:
         ll.ll_gather(lay, 2, 2, 0, 0, 0, 0, stream=0)
     assert e.value.status == ll.LL_ERR_INVALID_ARG
-    # an axis that crosses waves over more data than LDS can stage: outside the paper's legality
-    # condition (reported, not an error); gathered from memory inside the 256 KiB block
+    # an axis that crosses waves: outside the paper's legality condition (reported, not an error).  The
+    # columns of `big` live on 4 register and all 6 wave bits; the block closed under them is those
+    # 10 bits plus 128-byte runs, not the aligned 256 KiB range: staged in LDS
     big = ll.distributed_layout(4, 6, 6, [6, 10], [1 << k for k in range(4)] + [1 << (10 + k) for k in range(6)] +
                                 [1 << (4 + k) for k in range(6)])
-    info = ll.ll_gather_info(big, 1, 4)                            # columns: registers and all 6 wave bits
-    assert info["kernel_name"] == "global" and info["axis_wave_bits"] == 6 and info["block_bytes"] == 256 * 1024
+    info = ll.ll_gather_info(big, 1, 4)
+    assert info["kernel_name"] == "block_staged" and info["axis_wave_bits"] == 6 and info["block_bytes"] == 8192
     assert ll.ll_gather_info(big, 0, 4)["kernel_name"] == "wave_staged"
+    # 8192 rows of 32 two-byte elements: a block closed under the rows would need runs under 64 bytes
+    # to fit LDS, so the rows are gathered straight from memory
+    tall = ll.distributed_layout(4, 6, 8, [13, 5], [1 << k for k in range(18)])
+    info = ll.ll_gather_info(tall, 0, 2)
+    assert info["kernel_name"] == "global" and info["block_bytes"] == 512 * 1024
     # a tile label on the axis
     tiled = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 6), (ll.LL_IN_TILE, 2)], [2, 8],
                                 [1 << k for k in range(10)])
@@ -322,7 +328,7 @@ def test_gather_kernel_choice():
     assert (info["kernel_name"], info["axis_lane_bits"], info["axis_reg_bits"], info["paper_rounds"]) == ("wave_staged", 6, 0, 1)
     info = ll.ll_gather_info(lay, 1, 2)                            # columns live in registers and waves
     assert (info["kernel_name"], info["axis_reg_bits"], info["axis_wave_bits"], info["paper_rounds"]) == ("block_staged", 4, 4, 16)
-    assert info["block_bytes"] == 2 << 14
+    assert info["block_bytes"] == 8192          # 4 register + 4 wave bits and runs of 2^8 elements, not the aligned 32 KiB
     regaxis = ll.distributed_layout(2, 6, 0, [2, 6], [1 << 6, 1 << 7] + [1 << k for k in range(6)])
     info = ll.ll_gather_info(regaxis, 0, 4)
     assert (info["kernel_name"], info["axis_reg_bits"], info["paper_rounds"]) == ("block_staged", 2, 4)
