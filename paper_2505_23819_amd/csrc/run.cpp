@@ -221,7 +221,13 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     // fetched by several blocks): the source elements are read straight from memory inside the
     // aligned 2^top block around each element.
     // (the staged kernel addresses a tile group through 32-bit buffer offsets)
-    const bool global = n > max_bits || (elem_bytes << cb) < 64 || D + wlog > 31;
+    // Runs under 64 bytes make several blocks fetch every 128-byte line (consecutive blocks, which the
+    // XCD-aware order keeps on one L2).  Measured against the memory-direct kernel: worth it only when
+    // the aligned range is beyond an XCD's 4 MiB L2 (4096 x 4096 two-byte rows, 32-byte runs: 2.0
+    // against 0.51 TB/s; four-byte: 1.44 / 0.68), not below (4096 x 256 eight-byte: 1.44 / 1.71).
+    static const int min_run_env = getenv("LL_GATHER_MIN_RUN") ? atoi(getenv("LL_GATHER_MIN_RUN")) : 0;       // experiment knob (bytes)
+    const int min_run = min_run_env ? min_run_env : (((long long)elem_bytes << top) > (4ll << 20) ? 32 : 64);
+    const bool global = n > max_bits || (elem_bytes << cb) < min_run || D + wlog > 31;
     GatherGenArgs &g = c->gen;
     std::memset(&g, 0, sizeof(g));
     g.na = na;
