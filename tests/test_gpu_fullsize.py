@@ -184,3 +184,24 @@ def test_gather_memory_direct_full_size():
     for t in sample_tiles(ntiles, 3, 19):
         want = oracle.gather(bases, [13, 5], 0, inp[t * te:(t + 1) * te].cpu().numpy().view(np.uint16), idx[t * te:(t + 1) * te].cpu().numpy())
         assert np.array_equal(out[t * te:(t + 1) * te].cpu().numpy().view(np.uint16), want), f"tile {t}"
+
+
+def test_gather_short_runs_beyond_l2():
+    """Rows of 4096 x 1024 four-byte row-major tiles (16 MiB each: beyond an XCD's L2): staged in 128 KiB
+    blocks of 4096 rows x 32-byte runs.  Against the oracle on one tile and torch.gather on all."""
+    d, ntiles = 22, 3
+    bases = [1 << k for k in range(d)]
+    layout = ll.ll_layout_create([(ll.LL_IN_OFFSET, d)], [12, 10], bases)
+    info = ll.ll_gather_info(layout, 0, 4)
+    assert info["kernel_name"] == "block_staged" and info["block_bytes"] == 128 * 1024
+    inp = wl.raw_bits(25, 0, (ntiles << d) * 4 // 8, "cuda").view(torch.int32)
+    idx = wl.gen_index(55, 0, ntiles << d, 1 << 12, "cuda")
+    out = torch.empty_like(inp)
+    out.fill_(0x5A5A5A5A)
+    ll.ll_gather(layout, 0, 4, inp, idx, out, ntiles)
+    torch.cuda.synchronize()
+    ref = torch.gather(inp.view(ntiles, 4096, 1024), 1, idx.view(ntiles, 4096, 1024).to(torch.int64))
+    assert torch.equal(out.view(ntiles, 4096, 1024), ref)
+    te = 1 << d
+    want = oracle.gather(bases, [12, 10], 0, inp[te:2 * te].cpu().numpy().view(np.uint32), idx[te:2 * te].cpu().numpy())
+    assert np.array_equal(out[te:2 * te].cpu().numpy().view(np.uint32), want)
