@@ -92,7 +92,7 @@ static __device__ __forceinline__ long long block_of_workgroup(long long wg, lon
 // large tile are scattered cosets (config 4) it is 2 % slower, so the natural order stays.
 int xcd_chunk_bits_for(long long group_bytes, long long block_bytes)
 {
-    static const char *env = getenv("LL_XCD_CHUNK");          // experiment knob: blocks (power of two), 0 = off
+    const char *env = getenv("LL_XCD_CHUNK");                 // experiment knob: blocks (power of two), 0 = off
     if (env) {
         const int v = atoi(env);
         return v > 0 ? 31 - __builtin_clz((unsigned)v) : -1;
