@@ -168,6 +168,13 @@ class Layout:
     def out_dims(self):
         return self.get()[1]
 
+    @property
+    def d_in(self) -> int:
+        """Input bits (index bits of one tile image), read once: layouts are immutable."""
+        if getattr(self, "_d_in", None) is None:
+            self._d_in = sum(b for _, b in self.get()[0])
+        return self._d_in
+
     def apply(self, index: int) -> int:
         return ll_layout_apply(self, index)
 
@@ -185,6 +192,13 @@ class Plan:
 
     def info(self) -> dict:
         return ll_plan_info(self)
+
+    def sizes(self) -> Tuple[int, int, int]:
+        """(index bits of a source tile, of a destination tile, element bytes), read once."""
+        if getattr(self, "_sizes", None) is None:
+            i = ll_plan_info(self)
+            self._sizes = (i["d"], i["d_dst"], i["elem_bytes"])
+        return self._sizes
 
 
 # ---- the calls of ll.h, same names --------------------------------------------------------------
@@ -336,9 +350,20 @@ def ll_plan_info(plan: Plan) -> dict:
     return out
 
 
-def _ptr(x) -> int:
-    """Device pointer of a torch tensor (or a raw integer address)."""
-    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+def _ptr(x, need_bytes: int = 0, what: str = "buffer") -> int:
+    """Device pointer of a torch tensor (or a raw integer address, taken on trust).  A tensor must
+    live on the GPU, be contiguous and hold at least `need_bytes`: a host pointer or a short buffer
+    handed to a kernel would be a memory fault on the device, not an exception."""
+    if not hasattr(x, "data_ptr"):
+        return int(x)
+    if not getattr(x, "is_cuda", False):
+        raise LLError(LL_ERR_INVALID_ARG, f"{what} is not a GPU tensor")
+    if not x.is_contiguous():
+        raise LLError(LL_ERR_INVALID_ARG, f"{what} is not contiguous")
+    have = x.numel() * x.element_size()
+    if have < need_bytes:
+        raise LLError(LL_ERR_INVALID_ARG, f"{what} holds {have} bytes, the call needs {need_bytes}")
+    return int(x.data_ptr())
 
 
 def _stream(stream) -> int:
@@ -350,16 +375,22 @@ def _stream(stream) -> int:
 
 def ll_convert(plan: Plan, src, dst, ntiles: int, stream=None) -> None:
     """Enqueue the conversion on `stream` (default: torch's current stream)."""
-    _check(_lib.ll_convert(plan._h, _ptr(src), _ptr(dst), int(ntiles), _stream(stream)))
+    d, d_dst, w = plan.sizes()
+    n = max(0, int(ntiles))
+    _check(_lib.ll_convert(plan._h, _ptr(src, (n << d) * w, "src"), _ptr(dst, (n << d_dst) * w, "dst"), int(ntiles),
+                           _stream(stream)))
 
 
 def ll_gather(layout: Layout, axis: int, elem_bytes: int, inp, idx, out, ntiles: int, stream=None) -> None:
-    _check(_lib.ll_gather(layout._h, int(axis), int(elem_bytes), _ptr(inp), _ptr(idx), _ptr(out),
-                          int(ntiles), _stream(stream)))
+    n = max(0, int(ntiles)) << layout.d_in
+    if hasattr(idx, "element_size") and idx.element_size() != 4:
+        raise LLError(LL_ERR_INVALID_ARG, "idx must hold 32-bit integers")
+    _check(_lib.ll_gather(layout._h, int(axis), int(elem_bytes), _ptr(inp, n * int(elem_bytes), "in"), _ptr(idx, n * 4, "idx"),
+                          _ptr(out, n * int(elem_bytes), "out"), int(ntiles), _stream(stream)))
 
 
 def ll_copy(src, dst, nbytes: int, stream=None) -> None:
-    _check(_lib.ll_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)))
+    _check(_lib.ll_copy(_ptr(src, int(nbytes), "src"), _ptr(dst, int(nbytes), "dst"), int(nbytes), _stream(stream)))
 
 
 # ---- small conveniences --------------------------------------------------------------------------

@@ -880,3 +880,19 @@ def test_gather_on_memory_layouts(w):
     for axis in (0, 1):
         idx = rng.integers(0, 64, size=6 << 12, dtype=np.int32)
         assert np.array_equal(run_gather(sw, axis, inp, idx, 12), oracle.gather(osw.bases, [6, 6], axis, inp, idx)), axis
+
+
+def test_binding_rejects_short_and_strided_gpu_tensors():
+    cfg = wl.config(2)
+    a, b = layouts_of(cfg)
+    plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+    src = cfg.gen_data(0, 2, "cuda")
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_convert(plan, src, torch.empty(src.numel() - 8, dtype=src.dtype, device="cuda"), 2)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG and "dst holds" in e.value.message
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_convert(plan, torch.empty(2 * src.numel(), dtype=src.dtype, device="cuda")[::2], torch.empty_like(src), 2)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG and "contiguous" in e.value.message
+    with pytest.raises(ll.LLError) as e:
+        ll.ll_gather(a, 0, 2, src, torch.zeros(src.numel(), dtype=torch.int64, device="cuda"), torch.empty_like(src), 2)
+    assert e.value.status == ll.LL_ERR_INVALID_ARG and "32-bit" in e.value.message

@@ -460,3 +460,21 @@ def test_sparse_sliced_sources_plan():
                 info = ll.ll_plan_convert(a, b, w).info()
                 assert info["kind_name"] == "broadcast" and 0 < info["lds_bytes"] <= 65536
                 assert info["predicted_wavefronts_write"] >= 1
+
+
+def test_binding_rejects_host_and_short_tensors():
+    """A tensor handed to a device entry point must be on the GPU and large enough: the binding checks
+    before anything is launched (raw integer addresses are taken on trust)."""
+    import torch
+    c = wl.config(2)
+    a = ll.distributed_layout(c.nreg, c.nlane, c.nwave, c.out_dim_bits, c.src_bases)
+    b = ll.distributed_layout(c.nreg, c.nlane, c.nwave, c.out_dim_bits, c.dst_bases)
+    plan = ll.ll_plan_convert(a, b, 2)
+    host = torch.zeros(1 << 14, dtype=torch.int16)
+    for call in (lambda: ll.ll_convert(plan, host, host.clone(), 1, stream=0),
+                 lambda: ll.ll_copy(host, host.clone(), 1 << 15, stream=0),
+                 lambda: ll.ll_gather(a, 0, 2, host, torch.zeros(1 << 14, dtype=torch.int32), host.clone(), 1, stream=0)):
+        with pytest.raises(ll.LLError) as e:
+            call()
+        assert e.value.status == ll.LL_ERR_INVALID_ARG and "GPU tensor" in e.value.message
+    assert plan.sizes() == (14, 14, 2) and a.d_in == 14
