@@ -205,3 +205,47 @@ def test_gather_short_runs_beyond_l2():
     te = 1 << d
     want = oracle.gather(bases, [12, 10], 0, inp[te:2 * te].cpu().numpy().view(np.uint32), idx[te:2 * te].cpu().numpy())
     assert np.array_equal(out[te:2 * te].cpu().numpy().view(np.uint32), want)
+
+
+@pytest.mark.parametrize("cid", [3, 4, 5])
+def test_buffers_beyond_four_gib(cid):
+    """Images larger than 4 GiB (64-bit offsets in every kernel family: register path, LDS staging,
+    gather), with a ragged tile count; tiles from both ends and from just past the 4 GiB mark are
+    compared with the oracle, and every tile's checksum is preserved (conversions permute a tile)."""
+    cfg = wl.config(cid)
+    te, w = cfg.tile_elems, cfg.elem_bytes
+    ntiles = (4 << 30) // (te * w) + 257 + 3
+    step = max(1, (256 << 20) // (te * w))
+    src = torch.empty(ntiles * te, dtype=cfg.dtype, device="cuda")
+    for t0 in range(0, ntiles, step):
+        n = min(step, ntiles - t0)
+        src[t0 * te:(t0 + n) * te] = cfg.gen_data(t0, n, "cuda")
+    dst = torch.empty_like(src)
+    past = (4 << 30) // (te * w)
+    picks = [0, 1, past - 1, past, past + 1, ntiles - 2, ntiles - 1]
+    if cfg.kind == "gather":
+        idx = torch.empty(ntiles * te, dtype=torch.int32, device="cuda")
+        for t0 in range(0, ntiles, step):
+            n = min(step, ntiles - t0)
+            idx[t0 * te:(t0 + n) * te] = cfg.gen_idx(t0, n, "cuda")
+        layout = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+        ll.ll_gather(layout, cfg.axis, w, src, idx, dst, ntiles)
+        torch.cuda.synchronize()
+        for t in picks:
+            want = oracle.gather(cfg.src_bases, cfg.out_dim_bits, cfg.axis, wl.to_numpy_bits(src[t * te:(t + 1) * te]),
+                                 idx[t * te:(t + 1) * te].cpu().numpy())
+            assert np.array_equal(wl.to_numpy_bits(dst[t * te:(t + 1) * te]), want), f"tile {t}"
+        return
+    a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+    b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
+    plan = ll.ll_plan_convert(a, b, w)
+    ll.ll_convert(plan, src, dst, ntiles)
+    torch.cuda.synchronize()
+    for t in picks:
+        want = oracle.convert(cfg.src_bases, cfg.dst_bases, wl.to_numpy_bits(src[t * te:(t + 1) * te]))
+        assert np.array_equal(wl.to_numpy_bits(dst[t * te:(t + 1) * te]), want), f"config {cid} tile {t}"
+    for t0 in range(0, ntiles, step):
+        n = min(step, ntiles - t0)
+        s_sum = wl.bits_view(src[t0 * te:(t0 + n) * te]).view(n, te).to(torch.int64).sum(dim=1)
+        d_sum = wl.bits_view(dst[t0 * te:(t0 + n) * te]).view(n, te).to(torch.int64).sum(dim=1)
+        assert torch.equal(s_sum, d_sum), f"tiles {t0}.."
