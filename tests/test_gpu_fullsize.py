@@ -249,3 +249,21 @@ def test_buffers_beyond_four_gib(cid):
         s_sum = wl.bits_view(src[t0 * te:(t0 + n) * te]).view(n, te).to(torch.int64).sum(dim=1)
         d_sum = wl.bits_view(dst[t0 * te:(t0 + n) * te]).view(n, te).to(torch.int64).sum(dim=1)
         assert torch.equal(s_sum, d_sum), f"tiles {t0}.."
+
+
+def test_broadcast_destination_beyond_four_gib():
+    """The broadcasting kernel with a destination image past 4 GiB (expand 16x, 64 KiB per tile)."""
+    case = wl.broadcast_cases()[1]
+    a = ll.distributed_layout(*case.src_in, case.out_dim_bits, case.src_bases)
+    b = ll.distributed_layout(*case.dst_in, case.out_dim_bits, case.dst_bases)
+    plan = ll.ll_plan_convert(a, b, case.elem_bytes)
+    ts, td = 1 << case.d_src, 1 << case.d_dst
+    ntiles = (4 << 30) // (td * case.elem_bytes) + 1029
+    src = case.gen_data(0, ntiles, "cuda")
+    dst = torch.empty(ntiles * td, dtype=src.dtype, device="cuda")
+    ll.ll_convert(plan, src, dst, ntiles)
+    torch.cuda.synchronize()
+    past = (4 << 30) // (td * case.elem_bytes)
+    for t in (0, past - 1, past, past + 1, ntiles - 1):
+        want = oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, wl.to_numpy_bits(src[t * ts:(t + 1) * ts]))
+        assert np.array_equal(wl.to_numpy_bits(dst[t * td:(t + 1) * td]), want), f"tile {t}"
