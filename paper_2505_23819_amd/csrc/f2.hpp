@@ -3,6 +3,7 @@
 // A matrix is stored by columns: cols[k] is the image of input bit k, a bit vector packed in a
 // 64-bit word (bit i = row i).  Subspaces are stored as lists of spanning vectors.
 #pragma once
+#include <cstddef>
 #include <cstdint>
 #include <vector>
 
