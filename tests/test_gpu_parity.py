@@ -896,3 +896,43 @@ def test_binding_rejects_short_and_strided_gpu_tensors():
     with pytest.raises(ll.LLError) as e:
         ll.ll_gather(a, 0, 2, src, torch.zeros(src.numel(), dtype=torch.int64, device="cuda"), torch.empty_like(src), 2)
     assert e.value.status == ll.LL_ERR_INVALID_ARG and "32-bit" in e.value.message
+
+
+def test_entry_points_from_several_threads_and_streams():
+    """Plans and layouts are immutable and the library keeps no global launch state: four host threads,
+    each with its own stream, convert and gather concurrently through the same plan and layout."""
+    import threading
+    cfg, g = wl.config(2), wl.config(5)
+    a, b = layouts_of(cfg)
+    plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+    lay5, _ = layouts_of(g)
+    nt = 64
+    src = cfg.gen_data(0, nt, "cuda")
+    inp, idx = g.gen_data(0, nt, "cuda"), g.gen_idx(0, nt, "cuda")
+    want_c = oracle.convert(cfg.src_bases, cfg.dst_bases, wl.to_numpy_bits(src))
+    want_g = oracle.gather(g.src_bases, g.out_dim_bits, g.axis, wl.to_numpy_bits(inp), idx.cpu().numpy())
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(k):
+        try:
+            stream = torch.cuda.Stream()
+            outs_c = [torch.empty_like(src) for _ in range(4)]
+            outs_g = [torch.empty_like(inp) for _ in range(4)]
+            for rep in range(25):
+                ll.ll_convert(plan, src, outs_c[rep % 4], nt, stream=stream)
+                ll.ll_gather(lay5, g.axis, g.elem_bytes, inp, idx, outs_g[rep % 4], nt, stream=stream)
+            stream.synchronize()
+            for o in outs_c:
+                assert np.array_equal(wl.to_numpy_bits(o), want_c)
+            for o in outs_g:
+                assert np.array_equal(wl.to_numpy_bits(o), want_g)
+        except Exception as e:  # noqa: BLE001  (reported to the main thread)
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
