@@ -936,3 +936,30 @@ def test_entry_points_from_several_threads_and_streams():
     for t in threads:
         t.join()
     assert not errors, errors
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_degenerate_layouts(w):
+    """The smallest cases the method has: a scalar replicated over the slots of a tile (no logical bits
+    at all), a two-element tile, and tiles of a single element under gather."""
+    rng = np.random.default_rng(9900 + w)
+    n = 64
+    # a scalar held 8 times -> held 4 times: every destination slot copies source slot 0 of its tile
+    a = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_WAVE, 1)], [0], [0, 0, 0])
+    b = ll.ll_layout_create([(ll.LL_IN_REG, 2)], [0], [0, 0])
+    src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=n << 3, dtype=NP_DTYPES[w])
+    got = run_convert_general(ll.ll_plan_convert(a, b, w), src, 3, 2)
+    assert np.array_equal(got, oracle.convert_general([0, 0, 0], [0, 0], 0, src))
+    assert np.array_equal(got.reshape(n, 4), np.repeat(src.reshape(n, 8)[:, :1], 4, axis=1))
+    # two elements per tile, swapped
+    two, swp = ll.ll_layout_create([(ll.LL_IN_REG, 1)], [1], [1]), ll.ll_layout_with_offset(ll.ll_layout_create([(ll.LL_IN_REG, 1)], [1], [1]), 1)
+    src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=n << 1, dtype=NP_DTYPES[w])
+    got = run_convert(ll.ll_plan_convert(two, swp, w), src, 1)
+    assert np.array_equal(got.reshape(n, 2), src.reshape(n, 2)[:, ::-1])
+    # gather on two-element tiles and on single-element tiles (an axis of one element: identity)
+    idx = rng.integers(0, 2, size=n << 1, dtype=np.int32)
+    assert np.array_equal(run_gather(two, 0, src, idx, 1), oracle.gather([1], [1], 0, src, idx))
+    one = ll.ll_layout_create([(ll.LL_IN_REG, 0)], [0], [])
+    src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=n, dtype=NP_DTYPES[w])
+    idx = rng.integers(-5, 5, size=n, dtype=np.int32)
+    assert np.array_equal(run_gather(one, 0, src, idx, 0), src)
