@@ -270,6 +270,17 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     g.swz_shift = std::max(ubk + 5, rb);
     g.swz_to = ubk;
     g.swz_mask = (1u << nx) - 1;
+    {
+        // When no move along the axis changes the bank bits of an LDS address (a row gather in a
+        // row-major tile: the deltas sit above the runs), every lane reads in the bank of its own
+        // unit and consecutive units already spread over the banks: a swizzle would only scatter them.
+        vec moved = 0;
+        for (int b = 0; b < na; ++b) moved |= g.delta[b];
+        const int lo = std::max(0, ubk - wlog), hi = ubk + 5 - wlog;      // element bits that form the bank field
+        const vec bank_bits = hi > lo ? ((vec(1) << hi) - 1) & ~((vec(1) << lo) - 1) : 0;
+        static const bool always = getenv("LL_GATHER_SWIZZLE_ALWAYS") != nullptr;      // experiment knob
+        if (!(moved & bank_bits) && !always) g.swz_mask = 0;
+    }
     c->kernel = LL_GATHER_BLOCK_STAGED;
     return LL_OK;
 }
