@@ -366,10 +366,25 @@ def _ptr(x, need_bytes: int = 0, what: str = "buffer") -> int:
     return int(x.data_ptr())
 
 
+def _current_stream_fn():
+    """torch's current raw stream handle.  The public path (building a Stream object) costs about
+    3 us per call, as much as the launch itself; torch's own kernels use the raw-handle query."""
+    import torch
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+    if raw is None:
+        return lambda: int(torch.cuda.current_stream().cuda_stream)
+    return lambda: int(raw(torch.cuda.current_device()))
+
+
+_current_stream = None
+
+
 def _stream(stream) -> int:
+    global _current_stream
     if stream is None:
-        import torch
-        return int(torch.cuda.current_stream().cuda_stream)
+        if _current_stream is None:
+            _current_stream = _current_stream_fn()
+        return _current_stream()
     return int(getattr(stream, "cuda_stream", stream))
 
 
