@@ -223,6 +223,30 @@ def main() -> int:
                                           "kernel": inf1["strategy_name"]}
         del graph, l1, s1
 
+        # config 1's layouts on many tiles: the lane <-> register butterfly kernel (Sec. 5.4 "Intra-warp Data
+        # Exchange") at a size where bandwidth, not the launch, is what is measured; and the same through LDS
+        nt1 = 32768
+        a1 = ll.distributed_layout(c1.nreg, c1.nlane, c1.nwave, c1.out_dim_bits, c1.src_bases)
+        b1 = ll.distributed_layout(c1.nreg, c1.nlane, c1.nwave, c1.out_dim_bits, c1.dst_bases)
+        x1 = wl.gen_int32(11, 0, nt1 * c1.tile_elems, dev)
+        o1 = [torch.empty_like(x1) for _ in range(2)]
+        ab1 = 2 * nt1 * c1.tile_elems * c1.elem_bytes
+        many = []
+        for force in (None, "4", "3"):
+            if force is not None:
+                os.environ["LL_FORCE_STRATEGY"] = force
+            p1 = ll.ll_plan_convert(a1, b1, c1.elem_bytes)
+            if force is not None:
+                del os.environ["LL_FORCE_STRATEGY"]
+            i1 = p1.info()
+            _, m_ms, _, _ = time_launches(lambda k: ll.ll_convert(p1, x1, o1[k % 2], nt1), args.table_steps, TABLE_WARMUP)
+            many.append({"kernel": i1["strategy_name"], "shuffle_stages": i1["shuffle_rounds"], "lds_bytes": i1["lds_bytes"],
+                         "us_mean": round(m_ms * 1e3, 2), "GBps": round(ab1 / m_ms / 1e6, 1),
+                         "frac_hbm_peak": round(ab1 / m_ms / 1e6 / HBM_PEAK_GBPS, 4)})
+        result["config1_layouts_32768_tiles"] = {"algorithmic_bytes": ab1, "kernels": many}
+        del x1, o1
+        torch.cuda.empty_cache()
+
         # conversions between layouts that replicate data (zero columns): one copy of every logical
         # element read, every destination slot written
         btable = []

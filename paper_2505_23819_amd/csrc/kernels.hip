@@ -446,15 +446,20 @@ static __device__ __forceinline__ void shuffle_stage(uint32_t (&r)[NV][4], uint3
 {
     const bool upper = (lane & mask) != 0;
     const int partner = (int)((lane ^ mask) << 2);
+    constexpr int bit = 1 << B;
+    // Pairs (lo, hi = lo | bit) by their index among the vectors with iteration bit B clear.  Both
+    // registers of a pair are rewritten with selects (no conditional stores into the array and no
+    // skipped iterations: with those, one instantiation was compiled into compare-and-select chains
+    // over all 32 registers, 14 times the vector instructions).
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        if ((i >> B) & 1) continue;
-        constexpr int bit = 1 << B;
+    for (int k = 0; k < NV / 2; ++k) {
+        const int lo = ((k >> B) << (B + 1)) | (k & (bit - 1)), hi = lo | bit;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const uint32_t send = upper ? r[i][c] : r[i | bit][c];
-            const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute(partner, (int)send);
-            if (upper) r[i][c] = got; else r[i | bit][c] = got;
+            const uint32_t x = r[lo][c], y = r[hi][c];
+            const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute(partner, (int)(upper ? x : y));
+            r[lo][c] = upper ? got : x;
+            r[hi][c] = upper ? y : got;
         }
     }
 }
