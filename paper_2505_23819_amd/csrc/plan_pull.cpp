@@ -118,9 +118,11 @@ static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int
     // Block = destination runs of 2^kd slots plus the destination slots that pull from source runs
     // of 2^ks slots (pivot bits only).  Longer runs on a side mean longer contiguous pieces of HBM on
     // that side; the side that moves more bytes gets its run bits first.
+    int nrep = 0;                                    // destination broadcast directions taken into the block first
     auto block_space = [&](int ks, int kd) {
         mat gens;
         for (int j = 0; j < kd; ++j) gens.push_back(vec(1) << j);
+        for (int j = 0; j < nrep; ++j) gens.push_back(kernel_r[(size_t)j]);
         for (int j = 0; j < ks && j < Ds; ++j) {
             vec pre;
             if (((pivots >> j) & 1) && preimage(vec(1) << j, &pre)) gens.push_back(pre);
@@ -131,6 +133,17 @@ static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int
     int ks = vs, kd = vs;
     auto fits = [&](int s_, int d_) { return (int)block_space(s_, d_).size() <= n_max; };
     if (mode == 1) {
+        // destination runs first, but not at the price of 16-byte source pieces: the source side gets
+        // runs of a 128-byte line before the destination takes the rest (random bit correspondences
+        // between the two sides otherwise leave every source line fetched by eight blocks)
+        const int line = std::max(vs, ilog2p(128u / (unsigned)w));
+        while (ks < Ds && ks < line && fits(ks + 1, kd)) ++ks;
+        // ... and the replicas of an element stay in one block while destination runs of 1 KiB remain,
+        // so that every source element is fetched by one block instead of one per replica
+        for (const int run = std::max(vs, ilog2p(1024u / (unsigned)w)); nrep < (int)kernel_r.size();) {
+            ++nrep;
+            if (!fits(ks, std::min(Dd, run))) { --nrep; break; }
+        }
         while (kd < Dd && fits(ks, kd + 1)) ++kd;
         while (ks < Ds && fits(ks + 1, kd)) ++ks;
     } else if (mode == 2) {
