@@ -146,12 +146,46 @@ static ll_status check_vec_tables(const VecArgs &a, const mat &pext, int vs, int
 // in-register transpose with the low iteration bits before or after the stages.
 // Built for conversions that are bit permutations inside a block.
 // ---------------------------------------------------------------------------------------------
+static ll_status plan_wave_shuffle_at(const mat &p, int d, int w, unsigned max_block, ll_plan *plan, bool *applied);
+
+// Blocks of 4 KiB (a wave with 4 vectors per lane) unless their runs are only one 128-byte line
+// long or the block comes out smaller: then 8 KiB blocks are tried and taken if they apply and
+// lengthen the runs.  Interleaved A/B on 30 random bit permutations of 2^12..2^18 elements (TB/s, 4 / 8
+// KiB): short-run cases 5.6-6.3 -> 6.4-6.7, the others equal within 1 %; configs 1 and 3 (runs of 512
+// and 256 bytes) are 1-2 % faster with 4 KiB and keep it; 16 KiB (16 vectors per lane) drops to 3.7-5.3.
 ll_status plan_wave_shuffle(const mat &p, int d, int w, ll_plan *plan, bool *applied)
 {
     *applied = false;
     if (w != 2 && w != 4 && w != 8) return dbg_na(1);
+    if (getenv("LL_SHUFFLE_BLOCK_BYTES"))      // experiment knob: one fixed block size
+        return plan_wave_shuffle_at(p, d, w, env_bytes("LL_SHUFFLE_BLOCK_BYTES", 4096u), plan, applied);
+    ll_plan small = *plan;
+    bool small_ok = false;
+    if (ll_status st = plan_wave_shuffle_at(p, d, w, 4096u, &small, &small_ok); st != LL_OK) return st;
+    // (8-byte elements: a 4 KiB block is 4 vectors per lane of 2 elements each, and 8 KiB measured 2-10 % faster throughout)
+    const bool short_runs = small_ok && (w == 8 || ((unsigned)w << small.desc.segment_bits) <= 128u || ((unsigned)w << small.desc.block_bits) < 4096u);
+    if (small_ok && !short_runs) {
+        *plan = small;
+        *applied = true;
+        return LL_OK;
+    }
+    ll_plan wide = *plan;
+    bool wide_ok = false;
+    if (ll_status st = plan_wave_shuffle_at(p, d, w, 8192u, &wide, &wide_ok); st != LL_OK) return st;
+    if (wide_ok && (!small_ok || wide.desc.segment_bits > small.desc.segment_bits)) {
+        *plan = wide;
+        *applied = true;
+    } else if (small_ok) {
+        *plan = small;
+        *applied = true;
+    }
+    return LL_OK;
+}
+
+static ll_status plan_wave_shuffle_at(const mat &p, int d, int w, unsigned max_block, ll_plan *plan, bool *applied)
+{
+    *applied = false;
     const int vs = ilog2u(16u / (unsigned)w), tb = 6;
-    const unsigned max_block = env_bytes("LL_SHUFFLE_BLOCK_BYTES", 4096u);
     BlockGeom g;
     // a transposing plan needs 2^vs vectors per lane
     if (build_blocks(p, d, w, 2 * vs + tb, max_block, max_block, &g) != LL_OK) return dbg_na(2);
