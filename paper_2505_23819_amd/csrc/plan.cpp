@@ -340,13 +340,18 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
 
     BlockGeom geom;
     if (ll_status st = build_blocks(p, d, w, vs + tb, max_block, pref_block, &geom); st != LL_OK) return st;
-    if (geom.n == vs + tb && ((long long)w << d) > 1024 * 1024 && !getenv("LL_BLOCK_BYTES")) {
-        // One vector per thread and a large tile cut into many such blocks: the runs are as short as
-        // the limit allows (4-byte elements: 128 bytes on each side, 32 of them scattered over the
-        // tile).  Runs grow on both sides at once, so the next size is four times the block.  Measured
-        // on random XOR layouts of 4-byte elements, interleaved runs of both block sizes on 1 GiB of
-        // data (TB/s, 4 KiB against 16 KiB blocks): tiles of 2^12..2^17 elements 6.1-6.4 against 5.9-6.2,
-        // 2^18 6.1 / 6.1, 2^19 5.9 / 6.05, 2^20 5.55 / 6.0, 2^21 5.26 / 6.05, 2^22 4.94 / 5.65, 2^24 4.44 / 5.3-5.5.
+    if (geom.n == vs + tb && (w == 1 || d >= 17) && !getenv("LL_BLOCK_BYTES")) {
+        // One vector per thread and a tile cut into many such blocks: the runs are as short as the
+        // limit allows (4-byte elements: 128 bytes on each side, 32 of them scattered over the tile).
+        // Runs grow on both sides at once, so the next size is four times the block.  Measured with
+        // interleaved runs of both block sizes (TB/s, 4 KiB against 16 KiB blocks).  Random XOR layouts
+        // of 4-byte elements on 1 GiB: tiles of 2^12..2^17 elements 6.1-6.4 against 5.9-6.2, 2^18
+        // 6.1 / 6.1, 2^19 5.9 / 6.05, 2^20 5.55 / 6.0, 2^21 5.26 / 6.05, 2^22 4.94 / 5.65, 2^24
+        // 4.44 / 5.3-5.5.  Random bit permutations on 256 MiB: 2-byte elements 2^13..2^16 6.2-6.5
+        // against 5.8-6.2, 2^17 5.9-6.0 / 6.1-6.2, 2^18 5.3-5.9 / 6.1-6.2, 2^19 5.5-5.9 / 6.0-6.2;
+        // 4-byte 2^17 6.1 / 6.25, 2^18 5.8 / 6.3; 8-byte 2^13..2^15 6.5 / 5.8-6.2, 2^17 6.1 / 6.3.
+        // Byte elements pay one LDS instruction per byte, and a workgroup that holds only 4 KiB
+        // cannot hide that: 2^14..2^20 4.2-5.8 against 6.1-6.5 at every tile size.
         BlockGeom wider;
         if (build_blocks(p, d, w, vs + tb, 2 * max_block, pref_block, &wider) == LL_OK && wider.k > geom.k &&
             ((unsigned)w << wider.n) <= 2 * max_block)

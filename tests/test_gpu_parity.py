@@ -548,16 +548,16 @@ def test_convert_one_large_tile():
     assert np.array_equal(dst.cpu().numpy().view(np.uint32), full)
 
 
-@pytest.mark.parametrize("w,d", [(4, 17), (4, 20), (2, 19), (8, 18)])
+@pytest.mark.parametrize("w,d", [(4, 16), (4, 17), (4, 20), (2, 19), (8, 18), (1, 15)])
 def test_convert_large_tiles_random_xor(w, d):
-    """Large tiles under random XOR layouts (above 1 MiB the planner stages wider blocks for 4-byte
-    elements), a ragged number of tiles."""
+    """Large tiles under random XOR layouts (from 2^17 elements on the planner stages wider blocks
+    where the narrow one holds a single vector per thread), a ragged number of tiles."""
     rng = np.random.default_rng(9700 + 10 * w + d)
     ca, cb = wl.random_invertible_bases(500 + d, d), wl.random_invertible_bases(600 + d, d)
     a, b = ll.distributed_layout(4, 6, d - 10, [d], ca), ll.distributed_layout(4, 6, d - 10, [d], cb)
     plan = ll.ll_plan_convert(a, b, w)
     if w == 4:
-        assert plan.info()["vectors_per_thread"] == (4 if d > 18 else 1)
+        assert plan.info()["vectors_per_thread"] == (4 if d >= 17 else 1)
     src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=3 << d, dtype=NP_DTYPES[w])
     assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src))
 
