@@ -267,3 +267,35 @@ def test_broadcast_destination_beyond_four_gib():
     for t in (0, past - 1, past, past + 1, ntiles - 1):
         want = oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, wl.to_numpy_bits(src[t * ts:(t + 1) * ts]))
         assert np.array_equal(wl.to_numpy_bits(dst[t * td:(t + 1) * td]), want), f"tile {t}"
+
+
+@pytest.mark.parametrize("kernel", ["block_staged", "global"])
+def test_gather_general_kernels_beyond_four_gib(kernel):
+    """The workgroup-staged and the memory-direct gather with images past 4 GiB (4-byte elements, a ragged
+    tile count): tiles from both ends and around the 4 GiB mark against the oracle."""
+    if kernel == "block_staged":
+        cfg = wl.config(5)
+        bases, dims, axis, split = cfg.src_bases, cfg.out_dim_bits, 1, (cfg.nreg, cfg.nlane, cfg.nwave)
+    else:
+        bases, dims, axis, split = [1 << k for k in range(18)], [13, 5], 0, (4, 6, 8)
+    layout = ll.distributed_layout(*split, dims, bases)
+    assert ll.ll_gather_info(layout, axis, 4)["kernel_name"] == kernel
+    d = sum(dims)
+    te = 1 << d
+    past = (4 << 30) // (te * 4)
+    ntiles = past + 5
+    n = ntiles * te
+    inp = torch.empty(n, dtype=torch.int32, device="cuda")
+    idx = torch.empty(n, dtype=torch.int32, device="cuda")
+    step = 1 << 26
+    for e0 in range(0, n, step):
+        m = min(step, n - e0)
+        inp[e0:e0 + m] = wl.raw_bits(26, e0 // 2, m // 2, "cuda").view(torch.int32)
+        idx[e0:e0 + m] = wl.gen_index(56, e0, m, 1 << dims[axis], "cuda")
+    out = torch.empty_like(inp)
+    out.fill_(0x5A5A5A5A)
+    ll.ll_gather(layout, axis, 4, inp, idx, out, ntiles)
+    torch.cuda.synchronize()
+    for t in (0, 1, past - 1, past, past + 1, ntiles - 1):
+        want = oracle.gather(bases, dims, axis, inp[t * te:(t + 1) * te].cpu().numpy().view(np.uint32), idx[t * te:(t + 1) * te].cpu().numpy())
+        assert np.array_equal(out[t * te:(t + 1) * te].cpu().numpy().view(np.uint32), want), f"tile {t}"
