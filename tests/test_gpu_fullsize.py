@@ -207,11 +207,15 @@ def test_gather_short_runs_beyond_l2():
     assert np.array_equal(out[te:2 * te].cpu().numpy().view(np.uint32), want)
 
 
-@pytest.mark.parametrize("cid", [3, 4, 5])
-def test_buffers_beyond_four_gib(cid):
-    """Images larger than 4 GiB (64-bit offsets in every kernel family: register path, LDS staging,
-    gather), with a ragged tile count; tiles from both ends and from just past the 4 GiB mark are
-    compared with the oracle, and every tile's checksum is preserved (conversions permute a tile)."""
+@pytest.mark.parametrize("cid,force", [(1, None), (3, None), (4, None), (5, None), (2, "4"), (2, "6")])
+def test_buffers_beyond_four_gib(cid, force, monkeypatch):
+    """Images larger than 4 GiB (64-bit offsets in every kernel family: lane-register butterflies,
+    register path, element-wide LDS staging, gather, and config 2 forced through the 128-bit LDS
+    kernel and the transposing LDS loads), with a ragged tile count; tiles from both ends and from
+    just past the 4 GiB mark are compared with the oracle, and every tile's checksum is preserved
+    (conversions permute a tile)."""
+    if force:
+        monkeypatch.setenv("LL_FORCE_STRATEGY", force)
     cfg = wl.config(cid)
     te, w = cfg.tile_elems, cfg.elem_bytes
     ntiles = (4 << 30) // (te * w) + 257 + 3
@@ -239,6 +243,8 @@ def test_buffers_beyond_four_gib(cid):
     a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
     b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
     plan = ll.ll_plan_convert(a, b, w)
+    want_kernel = {(1, None): "wave_shuffle", (3, None): "reg_permute", (4, None): "lds_elem", (2, "4"): "lds_vec", (2, "6"): "lds_tr"}
+    assert plan.info()["strategy_name"] == want_kernel[(cid, force)]
     ll.ll_convert(plan, src, dst, ntiles)
     torch.cuda.synchronize()
     for t in picks:
@@ -251,29 +257,33 @@ def test_buffers_beyond_four_gib(cid):
         assert torch.equal(s_sum, d_sum), f"tiles {t0}.."
 
 
-def test_broadcast_destination_beyond_four_gib():
-    """The broadcasting kernel with a destination image past 4 GiB (expand 16x, 64 KiB per tile)."""
-    case = wl.broadcast_cases()[1]
+@pytest.mark.parametrize("which", [1, 0], ids=["destination", "source"])
+def test_broadcast_images_beyond_four_gib(which):
+    """The broadcasting kernel with a destination image past 4 GiB (expand 16x, 64 KiB per destination
+    tile) and with a source image past 4 GiB (collapse 16x, 64 KiB per source tile)."""
+    case = wl.broadcast_cases()[which]
     a = ll.distributed_layout(*case.src_in, case.out_dim_bits, case.src_bases)
     b = ll.distributed_layout(*case.dst_in, case.out_dim_bits, case.dst_bases)
     plan = ll.ll_plan_convert(a, b, case.elem_bytes)
     ts, td = 1 << case.d_src, 1 << case.d_dst
-    ntiles = (4 << 30) // (td * case.elem_bytes) + 1029
+    past = (4 << 30) // (max(ts, td) * case.elem_bytes)
+    ntiles = past + 1029
     src = case.gen_data(0, ntiles, "cuda")
     dst = torch.empty(ntiles * td, dtype=src.dtype, device="cuda")
     ll.ll_convert(plan, src, dst, ntiles)
     torch.cuda.synchronize()
-    past = (4 << 30) // (td * case.elem_bytes)
     for t in (0, past - 1, past, past + 1, ntiles - 1):
         want = oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, wl.to_numpy_bits(src[t * ts:(t + 1) * ts]))
         assert np.array_equal(wl.to_numpy_bits(dst[t * td:(t + 1) * td]), want), f"tile {t}"
 
 
-@pytest.mark.parametrize("kernel", ["block_staged", "global"])
+@pytest.mark.parametrize("kernel", ["block_staged", "global", "shuffle"])
 def test_gather_general_kernels_beyond_four_gib(kernel):
-    """The workgroup-staged and the memory-direct gather with images past 4 GiB (4-byte elements, a ragged
-    tile count): tiles from both ends and around the 4 GiB mark against the oracle."""
-    if kernel == "block_staged":
+    """The workgroup-staged, the memory-direct and the lane-shuffle gather with images past 4 GiB (4-byte
+    elements, a ragged tile count): tiles from both ends and around the 4 GiB mark against the oracle."""
+    if kernel == "shuffle":
+        bases, dims, axis, split = [1 << k for k in range(8)], [6, 2], 0, (2, 6, 0)
+    elif kernel == "block_staged":
         cfg = wl.config(5)
         bases, dims, axis, split = cfg.src_bases, cfg.out_dim_bits, 1, (cfg.nreg, cfg.nlane, cfg.nwave)
     else:
