@@ -362,7 +362,9 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     const int nco = (int)comp.size();
     const vec low_mask = (vec(1) << k) - 1;
     const int nvec_bits = n - vs - tb;
-    if ((1 << nvec_bits) > kMaxIter) return fail(LL_ERR_UNSUPPORTED, "internal: too many vectors per thread");
+    // what the launcher instantiates: up to 8 vectors per thread with 256 threads, up to 4 with more
+    if ((1 << nvec_bits) > (tb == 8 ? 8 : 4))
+        return fail(LL_ERR_UNSUPPORTED, "staged block of %d bytes needs %d vectors per thread", (1 << n) * w, 1 << nvec_bits);
 
     // common contiguous run: Q e_b = e_b for b < v
     // (the low v bits of the destination index must be the low v bits of the source index: column
