@@ -2,11 +2,24 @@
 #pragma once
 #include <cstdarg>
 #include <cstdint>
+#include <memory>
 #include <string>
 #include <vector>
 
 #include "../../include/ll.h"
 #include "f2.hpp"
+
+namespace ll {
+struct GatherCache;   // kernel choices ll_gather has already made for one layout (run.cpp)
+// Holder that does not travel with copies: a layout copied and then changed must not inherit the
+// choices made for the original.  Read and replaced only through std::atomic_load / atomic_store.
+struct GatherCacheSlot {
+    std::shared_ptr<const GatherCache> p;
+    GatherCacheSlot() = default;
+    GatherCacheSlot(const GatherCacheSlot &) {}
+    GatherCacheSlot &operator=(const GatherCacheSlot &) { p.reset(); return *this; }
+};
+}   // namespace ll
 
 struct ll_layout {
     int n_in = 0;
@@ -17,6 +30,7 @@ struct ll_layout {
     int d_out = 0;
     f2::mat bases;   // d_in columns, each a d_out-bit flattened output index
     f2::vec offset = 0;   // affine part: index h holds logical element (bases h) xor offset
+    mutable ll::GatherCacheSlot gather_cache;   // not part of the layout's value
 
     int bits_of(int label) const
     {

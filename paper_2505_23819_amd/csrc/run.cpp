@@ -3,6 +3,9 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
 
 #include "plan.hpp"
 
@@ -285,10 +288,53 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     return LL_OK;
 }
 
+// choose_gather costs about 3 us of host time (a right inverse, a few subspace bases), most of a small
+// gather's launch cost, and a layout is immutable: the choices are kept with the layout, keyed by
+// axis, element size and the values of the experiment knobs that choose_gather reads on every call.
+// The list is replaced as a whole (copy, append, atomic store), so concurrent callers need no lock;
+// two threads that miss at the same time both compute the same entry and one list wins.
+struct GatherCache {
+    struct Entry {
+        int axis, elem_bytes;
+        std::string knobs;
+        GatherChoice choice;
+    };
+    std::vector<Entry> entries;
+};
+
+static std::string gather_knobs()
+{
+    std::string s;
+    for (const char *name : {"LL_GATHER_GENERAL", "LL_GATHER_STAGED", "LL_GATHER_BLOCK_BYTES"}) {
+        const char *v = getenv(name);
+        s += v ? v : "";
+        s += '|';
+    }
+    return s;
+}
+
+static ll_status choose_gather_cached(const ll_layout *L, int axis, int elem_bytes, GatherChoice *c)
+{
+    const std::string knobs = gather_knobs();
+    std::shared_ptr<const GatherCache> have = std::atomic_load(&L->gather_cache.p);
+    if (have)
+        for (const GatherCache::Entry &e : have->entries)
+            if (e.axis == axis && e.elem_bytes == elem_bytes && e.knobs == knobs) {
+                *c = e.choice;
+                return LL_OK;
+            }
+    if (ll_status st = choose_gather(L, axis, elem_bytes, c); st != LL_OK) return st;
+    auto next = std::make_shared<GatherCache>();
+    if (have && have->entries.size() < 32) next->entries = have->entries;     // bounded: start over when full
+    next->entries.push_back({axis, elem_bytes, knobs, *c});
+    std::atomic_store(&L->gather_cache.p, std::shared_ptr<const GatherCache>(next));
+    return LL_OK;
+}
+
 ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gather_desc *out)
 {
     GatherChoice c;
-    if (ll_status st = choose_gather(L, axis, elem_bytes, &c); st != LL_OK) return st;
+    if (ll_status st = choose_gather_cached(L, axis, elem_bytes, &c); st != LL_OK) return st;
     std::memset(out, 0, sizeof(*out));
     out->kernel = c.kernel;
     out->axis_reg_bits = c.axis_reg_bits;
@@ -306,7 +352,7 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
                      long long ntiles, void *stream)
 {
     GatherChoice c;
-    if (ll_status st = choose_gather(L, axis, elem_bytes, &c); st != LL_OK) return st;
+    if (ll_status st = choose_gather_cached(L, axis, elem_bytes, &c); st != LL_OK) return st;
     const int d = L->d_in;
     if (ntiles == 0) return LL_OK;
     if (!in || !idx || !out) return fail(LL_ERR_INVALID_ARG, "null device pointer");

@@ -478,3 +478,32 @@ def test_binding_rejects_host_and_short_tensors():
             call()
         assert e.value.status == ll.LL_ERR_INVALID_ARG and "GPU tensor" in e.value.message
     assert plan.sizes() == (14, 14, 2) and a.d_in == 14
+
+
+def test_gather_choice_is_remembered_per_layout_and_follows_the_knobs(monkeypatch):
+    """The kernel choice of a gather is kept with the layout; a repeated query returns the same
+    description, other axes and element sizes get their own, and the experiment knobs that influence
+    the choice are part of the key."""
+    cfg = wl.config(5)
+    layout = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+    monkeypatch.delenv("LL_GATHER_GENERAL", raising=False)
+    first = ll.ll_gather_info(layout, 0, 2)
+    assert first["kernel_name"] == "wave_staged"
+    assert ll.ll_gather_info(layout, 0, 2) == first
+    assert ll.ll_gather_info(layout, 1, 2)["kernel_name"] == "block_staged"
+    assert ll.ll_gather_info(layout, 0, 1)["kernel_name"] == "block_staged"       # one-byte elements
+    monkeypatch.setenv("LL_GATHER_GENERAL", "1")
+    assert ll.ll_gather_info(layout, 0, 2)["kernel_name"] == "block_staged"
+    monkeypatch.delenv("LL_GATHER_GENERAL")
+    assert ll.ll_gather_info(layout, 0, 2) == first
+    # many distinct queries on one layout (the list is bounded) still answer correctly
+    for rep in range(3):
+        for w in (1, 2, 4, 8):
+            for axis in (0, 1):
+                for knob in (None, "0", "1"):
+                    if knob is None:
+                        monkeypatch.delenv("LL_GATHER_GENERAL", raising=False)
+                    else:
+                        monkeypatch.setenv("LL_GATHER_GENERAL", knob)
+                    fresh = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+                    assert ll.ll_gather_info(layout, axis, w) == ll.ll_gather_info(fresh, axis, w)
