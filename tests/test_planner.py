@@ -507,3 +507,37 @@ def test_gather_choice_is_remembered_per_layout_and_follows_the_knobs(monkeypatc
                         monkeypatch.setenv("LL_GATHER_GENERAL", knob)
                     fresh = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
                     assert ll.ll_gather_info(layout, axis, w) == ll.ll_gather_info(fresh, axis, w)
+
+
+def test_planning_from_many_threads_gives_the_single_thread_answer():
+    """Layouts are immutable and planning keeps no shared state besides the per-layout gather choices:
+    eight threads planning conversions and querying gathers on the SAME layout objects (ctypes drops
+    the interpreter lock during the calls) get what one thread gets."""
+    import threading
+    cfg2, cfg5 = wl.config(2), wl.config(5)
+    a = ll.distributed_layout(cfg2.nreg, cfg2.nlane, cfg2.nwave, cfg2.out_dim_bits, cfg2.src_bases)
+    b = ll.distributed_layout(cfg2.nreg, cfg2.nlane, cfg2.nwave, cfg2.out_dim_bits, cfg2.dst_bases)
+    g = ll.distributed_layout(cfg5.nreg, cfg5.nlane, cfg5.nwave, cfg5.out_dim_bits, cfg5.src_bases)
+    want_plan = {w: ll.ll_plan_convert(a, b, w).info() for w in (1, 2, 4, 8)}
+    fresh = ll.distributed_layout(cfg5.nreg, cfg5.nlane, cfg5.nwave, cfg5.out_dim_bits, cfg5.src_bases)
+    want_gather = {(axis, w): ll.ll_gather_info(fresh, axis, w) for axis in (0, 1) for w in (1, 2, 4, 8)}
+    errors = []
+
+    def work(t):
+        try:
+            for i in range(12):
+                w = 1 << ((i + t) & 3)
+                if ll.ll_plan_convert(a, b, w).info() != want_plan[w]:
+                    errors.append(("plan", t, i))
+                axis = (i >> 2) & 1
+                if ll.ll_gather_info(g, axis, w) != want_gather[(axis, w)]:
+                    errors.append(("gather", t, i))
+        except Exception as e:                      # noqa: BLE001 - report whatever a thread hit
+            errors.append((t, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(8)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors
