@@ -324,16 +324,18 @@ def main() -> int:
         torch.cuda.empty_cache()
         # axes whose aligned block exceeds LDS, row-major two-byte tiles of 2^18 elements (512 KiB), gather along
         # the rows: 512 x 512 is staged as 512 rows x 128-byte runs; 8192 x 32 has no closed block with runs of
-        # 64 bytes that fits LDS and is read straight from memory
-        ntb = 512
-        xb = wl.raw_bits(23, 0, (ntb << 18) * 2 // 8, dev).view(torch.int16)
+        # 64 bytes that fits LDS, its 512 KiB range is walked through LDS in chunks; 16384 x 32 (1 MiB) is read
+        # straight from memory
+        xb = wl.raw_bits(23, 0, (512 << 18) * 2 // 8, dev).view(torch.int16)
         ob = torch.empty_like(xb)
-        for rows_b, cols_b in ((9, 9), (13, 5)):
-            big = ll.distributed_layout(4, 6, 8, [rows_b, cols_b], [1 << k for k in range(18)])
-            ib = wl.gen_index(53, 0, ntb << 18, 1 << rows_b, dev)
+        for rows_b, cols_b in ((9, 9), (13, 5), (14, 5)):
+            db = rows_b + cols_b
+            ntb = (512 << 18) >> db
+            big = ll.distributed_layout(4, 6, db - 10, [rows_b, cols_b], [1 << k for k in range(db)])
+            ib = wl.gen_index(53, 0, ntb << db, 1 << rows_b, dev)
             ginfo = ll.ll_gather_info(big, 0, 2)
             _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(big, 0, 2, xb, ib, ob, ntb), args.table_steps, TABLE_WARMUP)
-            ab = (ntb << 18) * (2 + 2 + 4)
+            ab = (ntb << db) * (2 + 2 + 4)
             gtable.append({"name": "row-major %dx%d tile, 2-byte elements, gather along dim 0" % (1 << rows_b, 1 << cols_b),
                            "kernel": ginfo["kernel_name"],
                            "axis_bits_reg_lane_wave": [ginfo["axis_reg_bits"], ginfo["axis_lane_bits"], ginfo["axis_wave_bits"]],

@@ -296,7 +296,10 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
  *  - register and / or wave bits as well: a block of image elements closed under moves along the axis
  *    (the span of those index changes plus contiguous runs of 128 bytes where the size allows) is
  *    staged in workgroup LDS, at most 128 KiB; if no such block with runs of at least 64 bytes fits,
- *    every element is gathered straight from memory (slower: every element is its own access).
+ *    the aligned power-of-two range around an element that holds all its possible sources is either
+ *    walked through LDS in 64 KiB chunks by every workgroup with elements in it (ranges up to
+ *    512 KiB), or every element is gathered straight from memory (slower: every element is its own
+ *    access).
  *    Sec. 5.5's condition (no wave bits on the axis) is reported by ll_gather_info
  *    (axis_wave_bits == 0) and is not an error here;
  *  - tile bits: LL_ERR_TILE_MIXED.
@@ -307,7 +310,9 @@ typedef enum {
     LL_GATHER_SHUFFLE = 0,       /* one ds_bpermute_b32 per 32-bit piece of an element */
     LL_GATHER_WAVE_STAGED = 1,   /* coalesced access, source rows staged in wave-private LDS */
     LL_GATHER_BLOCK_STAGED = 2,  /* general: a block closed under the axis staged in workgroup LDS */
-    LL_GATHER_GLOBAL = 3         /* no closed block fits LDS: element-wide reads from memory */
+    LL_GATHER_GLOBAL = 3,        /* no closed block fits LDS: element-wide reads from memory */
+    LL_GATHER_PHASED = 4         /* no closed block fits LDS, but the aligned range around an element is a few
+                                    LDS sizes: every workgroup walks the range through LDS in 64 KiB chunks */
 } ll_gather_kernel;
 
 typedef struct {

@@ -40,7 +40,7 @@ EXPORTED_SYMBOLS = [
     "ll_layout_mfma_accumulator", "ll_layout_mfma_operand", "ll_layout_mma_swizzle", "ll_layout_classify",
     "ll_gather_info", "ll_layout_with_offset", "ll_layout_get_offset", "ll_layout_slice",
 ]
-GATHER_KERNEL_NAMES = ["shuffle", "wave_staged", "block_staged", "global"]
+GATHER_KERNEL_NAMES = ["shuffle", "wave_staged", "block_staged", "global", "lds_phased"]
 
 
 class ll_gather_desc(ctypes.Structure):

@@ -1370,6 +1370,176 @@ ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *str
     return check_launch("global gather kernel launch");
 }
 
+// Gather for aligned blocks a few times the size of LDS (the axis leaves LDS, but the block still
+// sits in an XCD's L2).  A workgroup of 1024 threads owns 8 units per thread of consecutive output
+// elements: it loads their indices once (coalesced), turns them into block-relative source indices
+// with the delta tables of the kernels above, then walks through the whole aligned block in chunks
+// of 64 KiB: stage a chunk in LDS with coalesced 16-byte loads (the next chunk's loads are in
+// flight while the current one is read), and every element whose source lies in the chunk picks
+// it up.  Every workgroup reads the whole block, so the block is fetched from L2
+// (block elements) / (workgroup elements) times - in full lines, against one line per ELEMENT in the
+// memory-direct kernel.  Two workgroups fit a CU.
+constexpr int kPhasedThreadBits = 10;
+constexpr int kPhasedUnits = 8;                       // units per thread
+constexpr int kPhasedChunkBytes = 64 * 1024;
+template <int W>
+__global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const GatherGenArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int UB = (W == 8) ? 1 : 2;
+    constexpr int UE = 1 << UB;
+    constexpr int TB = kPhasedThreadBits;
+    constexpr uint32_t T = 1u << TB;
+    constexpr int P = kPhasedUnits;
+    constexpr int CB = UB + TB + 3;                   // log2 elements per workgroup
+    static_assert(kPhasedUnits == 8, "CB assumes eight units per thread");
+    constexpr int WL = (W == 1) ? 0 : (W == 2) ? 1 : (W == 4) ? 2 : 3;
+    constexpr int SB = 16 - WL;                       // log2 elements per chunk
+    constexpr int VPT = kPhasedChunkBytes / 16 / (int)T;   // 16-byte vectors per thread and chunk
+    uint32_t *table = reinterpret_cast<uint32_t *>(lds + kPhasedChunkBytes);
+    const uint32_t tid = threadIdx.x;
+    const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;
+    if (tid < 32u * (uint32_t)ntab) {
+        const uint32_t x = (tid & 31u) << (5u * (tid >> 5));
+        uint32_t dl = 0;
+        for (int b = 0; b < a.na; ++b) dl ^= a.delta[b] & (0u - ((x >> b) & 1u));
+        table[tid] = dl;
+    }
+    const long long first = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk) << CB;
+    const long long left = a.total_elems - first;
+    const uint32_t valid = left >= (1ll << CB) ? (1u << CB) : (uint32_t)left;     // a multiple of UE
+    const __amdgpu_buffer_rsrc_t rix = make_rsrc(reinterpret_cast<const unsigned char *>(a.idx) + (size_t)first * 4, valid * 4);
+    const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (size_t)first * W, valid * W);
+    // the aligned block around this workgroup's elements; what lies beyond the last tile reads as zero
+    const uint32_t block_mask = (1u << a.block_bits) - 1u;
+    const long long block_base = first & ~(long long)block_mask;
+    const long long block_left = a.total_elems - block_base;
+    const uint32_t block_valid = block_left >= (1ll << a.block_bits) ? (1u << a.block_bits) : (uint32_t)block_left;
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(static_cast<const unsigned char *>(a.in) + (size_t)block_base * W, block_valid * W);
+    const uint32_t nchunks = 1u << (a.block_bits - SB);
+
+    u32x4 stage[VPT];
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) stage[i] = buf_load16(rin, (tid + T * i) * 16u);
+
+    uint32_t own_t = a.own_const;
+    {
+        const unsigned long long f = (unsigned long long)first;
+        for (int b = CB; b < 32; ++b) own_t ^= a.own_bit[b] & (0u - (uint32_t)((f >> b) & 1ull));
+#pragma unroll
+        for (int b = 0; b < TB; ++b) own_t ^= a.own_bit[UB + b] & (0u - ((tid >> b) & 1u));
+    }
+    const uint32_t own_s[4] = {0u, a.own_bit[0], a.own_bit[1], a.own_bit[0] ^ a.own_bit[1]};
+    uint32_t ix[P][UE];
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+        if constexpr (UE == 4) {
+            const u32x4 t = buf_load16(rix, (tid + T * q) * 16u);
+            ix[q][0] = t.x; ix[q][1] = t.y; ix[q][2] = t.z; ix[q][3] = t.w;
+        } else {
+            const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rix, (tid + T * q) * 8u, 0, kStream);
+            ix[q][0] = t.x; ix[q][1] = t.y;
+        }
+    }
+    __syncthreads();                                  // delta tables
+    // block-relative source index of every element (it replaces the index in ix)
+    const uint32_t rel = (uint32_t)(first - block_base);
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+        uint32_t own_q = own_t;
+#pragma unroll
+        for (int b = 0; b < 3; ++b) own_q ^= a.own_bit[UB + TB + b] & (0u - (((uint32_t)q >> b) & 1u));
+        const uint32_t unit = tid + T * q;
+#pragma unroll
+        for (int s = 0; s < UE; ++s) {
+            const uint32_t x = (ix[q][s] ^ own_q ^ own_s[s]) & a.axis_mask;
+            uint32_t t = table[x & 31u];
+            for (int k = 1; k < ntab; ++k) t ^= table[32u * k + ((x >> (5 * k)) & 31u)];
+            ix[q][s] = ((rel + unit * UE + s) ^ t) & block_mask;
+        }
+    }
+    uint32_t o[P][4];
+#pragma unroll
+    for (int q = 0; q < P; ++q) o[q][0] = o[q][1] = o[q][2] = o[q][3] = 0u;
+
+    for (uint32_t c = 0; c < nchunks; ++c) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) *reinterpret_cast<u32x4 *>(lds + (tid + T * i) * 16u) = stage[i];
+        __syncthreads();
+        if (c + 1 < nchunks) {
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) stage[i] = buf_load16(rin, (c + 1) * (uint32_t)kPhasedChunkBytes + (tid + T * i) * 16u);
+        }
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+#pragma unroll
+            for (int s = 0; s < UE; ++s) {
+                if ((ix[q][s] >> SB) == c) {
+                    const unsigned char *p = lds + (ix[q][s] & ((1u << SB) - 1u)) * W;
+                    if constexpr (W == 8) {
+                        const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+                        o[q][2 * s] = v.x; o[q][2 * s + 1] = v.y;
+                    } else if constexpr (W == 4) {
+                        o[q][s] = *reinterpret_cast<const uint32_t *>(p);
+                    } else if constexpr (W == 2) {
+                        o[q][s >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t *>(p) << ((s & 1) * 16);
+                    } else {
+                        o[q][0] |= (uint32_t)*p << (s * 8);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+        const uint32_t unit = tid + T * q;
+        if constexpr (W >= 4) {
+            const u32x4 v = {o[q][0], o[q][1], o[q][2], o[q][3]};
+            buf_store16(rout, unit * 16u, v);
+        } else if constexpr (W == 2) {
+            const u32x2 v = {o[q][0], o[q][1]};
+            __builtin_amdgcn_raw_buffer_store_b64(v, rout, unit * 8u, 0, kStream);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b32(o[q][0], rout, unit * 4u, 0, kStream);
+        }
+    }
+}
+
+int gather_phased_chunk_bits(int elem_bytes) { return (elem_bytes == 8 ? 1 : 2) + kPhasedThreadBits + 3; }
+int gather_phased_lds_chunk_bytes() { return kPhasedChunkBytes; }
+
+template <int W>
+static ll_status launch_gather_phased_w(const GatherGenArgs &a, hipStream_t s)
+{
+    const size_t lds_bytes = (size_t)kPhasedChunkBytes + 6 * 32 * sizeof(uint32_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gather_phased<W>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds_bytes);
+    if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    const dim3 grid((unsigned)a.nblocks), block(1u << kPhasedThreadBits);
+    launch((k_gather_phased<W>), grid, block, lds_bytes, s, a);
+    return check_launch("phased gather kernel launch");
+}
+
+ll_status launch_gather_phased(const GatherGenArgs &a, int elem_bytes, void *stream)
+{
+    if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
+    if (a.na < 0 || a.na > kMaxAxisBits) return fail(LL_ERR_UNSUPPORTED, "gather axis of 2^%d elements", a.na);
+    const int wl = elem_bytes == 1 ? 0 : elem_bytes == 2 ? 1 : elem_bytes == 4 ? 2 : 3;
+    // a workgroup's elements lie in one aligned block, the block is a whole number of chunks and its
+    // bytes fit a buffer descriptor
+    if (a.block_bits < gather_phased_chunk_bits(elem_bytes) || a.block_bits < 16 - wl || a.block_bits + wl > 31)
+        return fail(LL_ERR_INVALID_ARG, "internal: gather block of 2^%d elements does not suit the phased kernel", a.block_bits);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (elem_bytes) {
+    case 1: return launch_gather_phased_w<1>(a, s);
+    case 2: return launch_gather_phased_w<2>(a, s);
+    case 4: return launch_gather_phased_w<4>(a, s);
+    case 8: return launch_gather_phased_w<8>(a, s);
+    default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
+    }
+}
+
 ll_status launch_gather(const GatherArgs &a, int elem_bytes, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -150,6 +150,9 @@ int xcd_chunk_bits_for(long long group_bytes, long long block_bytes);
 ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *stream);
 int gather_global_chunk_bits(int elem_bytes);       // log2 elements one workgroup of the global gather takes
 ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *stream);
+int gather_phased_chunk_bits(int elem_bytes);       // log2 elements one workgroup of the phased gather takes
+int gather_phased_lds_chunk_bytes();                // bytes of the aligned block staged at a time
+ll_status launch_gather_phased(const GatherGenArgs &a, int elem_bytes, void *stream);
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,
                           int lds_bytes, void *stream);
 ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose, int xchg, int threads, int lds_bytes,

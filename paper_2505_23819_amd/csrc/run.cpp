@@ -241,7 +241,19 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         g.block_bits = top;
         for (int b = 0; b < na; ++b) g.delta[b] = (uint32_t)linv[axis_shift + b];
         for (int b = 0; b < d && b < 32; ++b) g.own_bit[b] = axis_coord(vec(1) << b);
-        c->kernel = LL_GATHER_GLOBAL;
+        // An aligned block of a few LDS sizes is walked through LDS chunk by chunk by every workgroup
+        // that has elements in it (k_gather_phased): the block is then read from L2 once per workgroup,
+        // in full lines, instead of one line per element.  Measured on MI355X (row gathers in row-major
+        // tiles, ps per element): phased 1.9 + 0.1 x (block bytes / elements per workgroup), memory-direct
+        // 4.1 / 4.5 / 5.0 / 7.0 for 1- / 2- / 4- / 8-byte elements whatever the block; phased wins up to
+        // blocks of 512 KiB (8192 x 32 one-byte 2.33 against 1.46 TB/s, two-byte 1.95 / 1.76, 8192 x 8
+        // four-byte 3.85 / 2.48, eight-byte 3.40 / 3.08) and loses beyond (1 MiB four-byte 2.13 / 2.39,
+        // 2 MiB eight-byte 1.39 / 2.85).
+        const int pcb = gather_phased_chunk_bits(elem_bytes);
+        static const long long phased_max = getenv("LL_GATHER_PHASED_MAX_BYTES") ? atoll(getenv("LL_GATHER_PHASED_MAX_BYTES")) : 512 * 1024;   // experiment knob
+        const long long block_bytes = (long long)elem_bytes << top;
+        const bool phased = top >= pcb && block_bytes >= 2 * gather_phased_lds_chunk_bytes() && block_bytes <= phased_max && top + wlog <= 31;
+        c->kernel = phased ? LL_GATHER_PHASED : LL_GATHER_GLOBAL;
         return LL_OK;
     }
     if (n < min_bits) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than the kernel's unit of work");
@@ -342,7 +354,7 @@ ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gathe
     out->axis_wave_bits = c.axis_wave_bits;
     out->paper_rounds = c.memory ? 0 : 1 << c.axis_reg_bits;
     const long long gen_bytes = (long long)elem_bytes << c.gen.block_bits;
-    out->block_bytes = c.kernel == LL_GATHER_BLOCK_STAGED || c.kernel == LL_GATHER_GLOBAL
+    out->block_bytes = c.kernel == LL_GATHER_BLOCK_STAGED || c.kernel == LL_GATHER_GLOBAL || c.kernel == LL_GATHER_PHASED
                            ? (int32_t)std::min(gen_bytes, (long long)INT32_MAX)
                            : 64 * (1 << L->bits_of(LL_IN_REG)) * elem_bytes;
     return LL_OK;
@@ -366,6 +378,23 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
     const unsigned long long ibytes = ((unsigned long long)ntiles << d) * 4;
     if ((pi < po + bytes && po < pi + bytes) || (px < po + bytes && po < px + ibytes))
         return fail(LL_ERR_INVALID_ARG, "the output buffer overlaps an input buffer");
+    if (c.kernel == LL_GATHER_PHASED) {
+        GatherGenArgs &g = c.gen;
+        g.in = in;
+        g.idx = idx;
+        g.out = out;
+        g.total_elems = ntiles << d;
+        const int cb = gather_phased_chunk_bits(elem_bytes);
+        g.nblocks = (g.total_elems + (1ll << cb) - 1) >> cb;
+        {
+            // XCD-aware order: the workgroups of one aligned block run on one XCD, whose L2 serves
+            // their repeated reads of the block
+            const char *e = getenv("LL_GATHER_XCD_CHUNK");        // experiment knob: workgroups (power of two), 0 = off
+            const int block_chunks = g.block_bits - cb;
+            g.xcd_chunk = e ? (atoi(e) > 1 ? 31 - __builtin_clz((unsigned)atoi(e)) : -1) : (block_chunks > 0 ? block_chunks : -1);
+        }
+        return launch_gather_phased(g, elem_bytes, stream);
+    }
     if (c.kernel == LL_GATHER_GLOBAL) {
         GatherGenArgs &g = c.gen;
         g.in = in;

@@ -164,25 +164,29 @@ def test_gather_beyond_lds_full_size_sampled():
     assert torch.equal(out.view(ntiles, 512, 512), ref)
 
 
-def test_gather_memory_direct_full_size():
-    """The memory-direct kernel at size: 256 MiB of 8192 x 32 two-byte tiles gathered along the rows
-    (no block closed under the rows fits LDS with runs of 64 bytes), against torch.gather on the
+@pytest.mark.parametrize("rows_bits,kernel", [(13, "lds_phased"), (14, "global")])
+def test_gather_beyond_lds_without_long_runs_full_size(rows_bits, kernel):
+    """256 MiB of 8192 x 32 (16384 x 32) two-byte tiles gathered along the rows: no block closed under
+    the rows fits LDS with runs of 64 bytes.  The aligned 512 KiB range is walked through LDS in
+    chunks; the 1 MiB range is read from memory element by element.  Against torch.gather on the
     logical view and sampled tiles against the oracle."""
-    d, ntiles = 18, 512
+    d = rows_bits + 5
+    ntiles = (256 << 20) // (2 << d)
+    rows = 1 << rows_bits
     bases = [1 << k for k in range(d)]
-    layout = ll.distributed_layout(4, 6, 8, [13, 5], bases)
-    assert ll.ll_gather_info(layout, 0, 2)["kernel_name"] == "global"
+    layout = ll.distributed_layout(4, 6, d - 10, [rows_bits, 5], bases)
+    assert ll.ll_gather_info(layout, 0, 2)["kernel_name"] == kernel
     inp = wl.raw_bits(24, 0, (ntiles << d) * 2 // 8, "cuda").view(torch.int16)
-    idx = wl.gen_index(54, 0, ntiles << d, 1 << 13, "cuda")
+    idx = wl.gen_index(54, 0, ntiles << d, rows, "cuda")
     out = torch.empty_like(inp)
     out.fill_(0x5A5A)
     ll.ll_gather(layout, 0, 2, inp, idx, out, ntiles)
     torch.cuda.synchronize()
-    ref = torch.gather(inp.view(ntiles, 8192, 32), 1, idx.view(ntiles, 8192, 32).to(torch.int64))
-    assert torch.equal(out.view(ntiles, 8192, 32), ref)
+    ref = torch.gather(inp.view(ntiles, rows, 32), 1, idx.view(ntiles, rows, 32).to(torch.int64))
+    assert torch.equal(out.view(ntiles, rows, 32), ref)
     te = 1 << d
     for t in sample_tiles(ntiles, 3, 19):
-        want = oracle.gather(bases, [13, 5], 0, inp[t * te:(t + 1) * te].cpu().numpy().view(np.uint16), idx[t * te:(t + 1) * te].cpu().numpy())
+        want = oracle.gather(bases, [rows_bits, 5], 0, inp[t * te:(t + 1) * te].cpu().numpy().view(np.uint16), idx[t * te:(t + 1) * te].cpu().numpy())
         assert np.array_equal(out[t * te:(t + 1) * te].cpu().numpy().view(np.uint16), want), f"tile {t}"
 
 
@@ -277,12 +281,14 @@ def test_broadcast_images_beyond_four_gib(which):
         assert np.array_equal(wl.to_numpy_bits(dst[t * td:(t + 1) * td]), want), f"tile {t}"
 
 
-@pytest.mark.parametrize("kernel", ["block_staged", "global", "shuffle"])
+@pytest.mark.parametrize("kernel", ["block_staged", "global", "lds_phased", "shuffle"])
 def test_gather_general_kernels_beyond_four_gib(kernel):
-    """The workgroup-staged, the memory-direct and the lane-shuffle gather with images past 4 GiB (4-byte
+    """The workgroup-staged, the memory-direct, the chunk-walking and the lane-shuffle gather with images past 4 GiB (4-byte
     elements, a ragged tile count): tiles from both ends and around the 4 GiB mark against the oracle."""
     if kernel == "shuffle":
         bases, dims, axis, split = [1 << k for k in range(8)], [6, 2], 0, (2, 6, 0)
+    elif kernel == "lds_phased":
+        bases, dims, axis, split = [1 << k for k in range(17)], [13, 4], 0, (4, 6, 7)
     elif kernel == "block_staged":
         cfg = wl.config(5)
         bases, dims, axis, split = cfg.src_bases, cfg.out_dim_bits, 1, (cfg.nreg, cfg.nlane, cfg.nwave)

@@ -786,13 +786,15 @@ def test_convert_between_different_register_lane_wave_splits(w):
 
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 def test_gather_along_axes_larger_than_lds(w, monkeypatch):
-    """Axes whose aligned block exceeds what LDS stages (128 KiB) are gathered straight from memory;
-    blocks of 64 and 128 KiB are staged by 1024-thread workgroups.  Random XOR layouts on tiles of 64,
-    128 and 256 KiB and of 2^18 elements (every axis then reaches the top bits), a ragged number of
-    tiles, and a permutation layout whose axis 0 is exactly the wave bits of a 2^17-element tile."""
+    """Axes whose aligned block exceeds what LDS stages (128 KiB) are walked through LDS in chunks
+    (up to 512 KiB) or gathered straight from memory; blocks of 64 and 128 KiB are staged by
+    1024-thread workgroups.  Random XOR layouts on tiles of 64, 128, 256 KiB and 1 MiB and of 2^18
+    elements (every axis then reaches the top bits), a ragged number of tiles, and a permutation
+    layout whose axis 0 is exactly the wave bits of a 2^17-element tile."""
     rng = np.random.default_rng(9300 + w)
     d128 = 17 - {1: 0, 2: 1, 4: 2, 8: 3}[w]                          # a tile of 128 KiB
-    cases = [(d128 - 1, [d128 - 1]), (d128, [d128 // 2, d128 - d128 // 2]), (d128 + 1, [d128 + 1]), (18, [6, 6, 6])]
+    cases = [(d128 - 1, [d128 - 1]), (d128, [d128 // 2, d128 - d128 // 2]), (d128 + 1, [d128 + 1]), (18, [6, 6, 6]),
+             (d128 + 3, [d128 + 3])]
     seen = set()
     for d, dims in cases:
         nreg, nlane = 4, 6
@@ -807,7 +809,7 @@ def test_gather_along_axes_larger_than_lds(w, monkeypatch):
             idx[::5] -= 1 << dims[axis]
             got = run_gather(layout, axis, inp, idx, d)
             assert np.array_equal(got, oracle.gather(cols, dims, axis, inp, idx)), (d, dims, axis, info)
-    assert "global" in seen and "block_staged" in seen
+    assert {"global", "lds_phased", "block_staged"} <= seen
     d, dims = 17, [7, 10]
     cols = [1 << k for k in range(10)] + [1 << (10 + k) for k in range(7)]     # rows = the 7 wave bits
     layout = ll.distributed_layout(4, 6, 7, dims, cols)
