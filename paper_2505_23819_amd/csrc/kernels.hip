@@ -1370,18 +1370,19 @@ ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *str
     return check_launch("global gather kernel launch");
 }
 
-// Gather for aligned blocks a few times the size of LDS (the axis leaves LDS, but the block still
+// Gather for aligned ranges a few times the size of LDS (the axis leaves LDS, but the range still
 // sits in an XCD's L2).  A workgroup of 1024 threads owns 8 units per thread of consecutive output
-// elements: it loads their indices once (coalesced), turns them into block-relative source indices
-// with the delta tables of the kernels above, then walks through the whole aligned block in chunks
-// of 64 KiB: stage a chunk in LDS with coalesced 16-byte loads (the next chunk's loads are in
-// flight while the current one is read), and every element whose source lies in the chunk picks
-// it up.  Every workgroup reads the whole block, so the block is fetched from L2
-// (block elements) / (workgroup elements) times - in full lines, against one line per ELEMENT in the
-// memory-direct kernel.  Two workgroups fit a CU.
+// elements: it loads their indices once (coalesced), turns them into byte offsets of the sources
+// inside the aligned range (delta tables as in the kernels above), then walks through the WHOLE
+// range in chunks of 128 KiB: the chunk is stored to LDS from registers filled by coalesced 16-byte
+// loads one phase earlier, and every element reads LDS once per phase - at its source when that
+// lies in the chunk, else at 16 bytes of zeros behind the chunk - and ORs the value into its output.
+// Every workgroup reads the whole range, so the range comes from L2
+// (range elements / workgroup elements) times, in full lines, against one line per ELEMENT in the
+// memory-direct kernel.  One workgroup fits a CU.
 constexpr int kPhasedThreadBits = 10;
 constexpr int kPhasedUnits = 8;                       // units per thread
-constexpr int kPhasedChunkBytes = 64 * 1024;
+constexpr int kPhasedChunkBytes = 128 * 1024;
 template <int W>
 __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const GatherGenArgs a)
 {
@@ -1394,9 +1395,11 @@ __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const 
     constexpr int CB = UB + TB + 3;                   // log2 elements per workgroup
     static_assert(kPhasedUnits == 8, "CB assumes eight units per thread");
     constexpr int WL = (W == 1) ? 0 : (W == 2) ? 1 : (W == 4) ? 2 : 3;
-    constexpr int SB = 16 - WL;                       // log2 elements per chunk
+    constexpr int SB = (kPhasedChunkBytes == 128 * 1024 ? 17 : 16) - WL;   // log2 elements per chunk
     constexpr int VPT = kPhasedChunkBytes / 16 / (int)T;   // 16-byte vectors per thread and chunk
-    uint32_t *table = reinterpret_cast<uint32_t *>(lds + kPhasedChunkBytes);
+    // LDS: the chunk, then 16 bytes of zeros (where every element whose source is NOT in the current
+    // chunk reads), then the delta tables
+    uint32_t *table = reinterpret_cast<uint32_t *>(lds + kPhasedChunkBytes + 16);
     const uint32_t tid = threadIdx.x;
     const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;
     if (tid < 32u * (uint32_t)ntab) {
@@ -1405,6 +1408,7 @@ __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const 
         for (int b = 0; b < a.na; ++b) dl ^= a.delta[b] & (0u - ((x >> b) & 1u));
         table[tid] = dl;
     }
+    if (tid < 4u) reinterpret_cast<uint32_t *>(lds + kPhasedChunkBytes)[tid] = 0u;
     const long long first = block_of_workgroup((long long)blockIdx.x, a.nblocks, a.xcd_chunk) << CB;
     const long long left = a.total_elems - first;
     const uint32_t valid = left >= (1ll << CB) ? (1u << CB) : (uint32_t)left;     // a multiple of UE
@@ -1455,7 +1459,7 @@ __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const 
             const uint32_t x = (ix[q][s] ^ own_q ^ own_s[s]) & a.axis_mask;
             uint32_t t = table[x & 31u];
             for (int k = 1; k < ntab; ++k) t ^= table[32u * k + ((x >> (5 * k)) & 31u)];
-            ix[q][s] = ((rel + unit * UE + s) ^ t) & block_mask;
+            ix[q][s] = (((rel + unit * UE + s) ^ t) & block_mask) * W;    // byte offset of the source in the range
         }
     }
     uint32_t o[P][4];
@@ -1470,22 +1474,28 @@ __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const 
 #pragma unroll
             for (int i = 0; i < VPT; ++i) stage[i] = buf_load16(rin, (c + 1) * (uint32_t)kPhasedChunkBytes + (tid + T * i) * 16u);
         }
+        // Every element reads in every phase: at its source when that lies in this chunk, otherwise at
+        // the zeros behind the chunk (offsets below the chunk wrap to huge values, so one unsigned
+        // minimum sends both kinds of miss there), and ORs what it read into its output, which starts
+        // as zero.  Three vector instructions and one LDS read per element and phase; the reads of a
+        // unit are independent and issue back to back.
+        const uint32_t cbytes = c * (uint32_t)kPhasedChunkBytes;
 #pragma unroll
         for (int q = 0; q < P; ++q) {
 #pragma unroll
             for (int s = 0; s < UE; ++s) {
-                if ((ix[q][s] >> SB) == c) {
-                    const unsigned char *p = lds + (ix[q][s] & ((1u << SB) - 1u)) * W;
-                    if constexpr (W == 8) {
-                        const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
-                        o[q][2 * s] = v.x; o[q][2 * s + 1] = v.y;
-                    } else if constexpr (W == 4) {
-                        o[q][s] = *reinterpret_cast<const uint32_t *>(p);
-                    } else if constexpr (W == 2) {
-                        o[q][s >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t *>(p) << ((s & 1) * 16);
-                    } else {
-                        o[q][0] |= (uint32_t)*p << (s * 8);
-                    }
+                const uint32_t at = ix[q][s] - cbytes;
+                const unsigned char *p = lds + (at < (uint32_t)kPhasedChunkBytes ? at : (uint32_t)kPhasedChunkBytes);
+                if constexpr (W == 8) {
+                    const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+                    o[q][2 * s] |= v.x;
+                    o[q][2 * s + 1] |= v.y;
+                } else if constexpr (W == 4) {
+                    o[q][s] |= *reinterpret_cast<const uint32_t *>(p);
+                } else if constexpr (W == 2) {
+                    o[q][s >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t *>(p) << ((s & 1) * 16);
+                } else {
+                    o[q][0] |= (uint32_t)*p << (s * 8);
                 }
             }
         }
@@ -1512,7 +1522,7 @@ int gather_phased_lds_chunk_bytes() { return kPhasedChunkBytes; }
 template <int W>
 static ll_status launch_gather_phased_w(const GatherGenArgs &a, hipStream_t s)
 {
-    const size_t lds_bytes = (size_t)kPhasedChunkBytes + 6 * 32 * sizeof(uint32_t);
+    const size_t lds_bytes = (size_t)kPhasedChunkBytes + 16 + 6 * 32 * sizeof(uint32_t);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gather_phased<W>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds_bytes);
     if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
@@ -1528,7 +1538,7 @@ ll_status launch_gather_phased(const GatherGenArgs &a, int elem_bytes, void *str
     const int wl = elem_bytes == 1 ? 0 : elem_bytes == 2 ? 1 : elem_bytes == 4 ? 2 : 3;
     // a workgroup's elements lie in one aligned block, the block is a whole number of chunks and its
     // bytes fit a buffer descriptor
-    if (a.block_bits < gather_phased_chunk_bits(elem_bytes) || a.block_bits < 16 - wl || a.block_bits + wl > 31)
+    if (a.block_bits < gather_phased_chunk_bits(elem_bytes) || (1ll << (a.block_bits + wl)) < kPhasedChunkBytes || a.block_bits + wl > 31)
         return fail(LL_ERR_INVALID_ARG, "internal: gather block of 2^%d elements does not suit the phased kernel", a.block_bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {

@@ -244,11 +244,10 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         // An aligned block of a few LDS sizes is walked through LDS chunk by chunk by every workgroup
         // that has elements in it (k_gather_phased): the block is then read from L2 once per workgroup,
         // in full lines, instead of one line per element.  Measured on MI355X (row gathers in row-major
-        // tiles, ps per element): phased 1.9 + 0.1 x (block bytes / elements per workgroup), memory-direct
-        // 4.1 / 4.5 / 5.0 / 7.0 for 1- / 2- / 4- / 8-byte elements whatever the block; phased wins up to
-        // blocks of 512 KiB (8192 x 32 one-byte 2.33 against 1.46 TB/s, two-byte 1.95 / 1.76, 8192 x 8
-        // four-byte 3.85 / 2.48, eight-byte 3.40 / 3.08) and loses beyond (1 MiB four-byte 2.13 / 2.39,
-        // 2 MiB eight-byte 1.39 / 2.85).
+        // tiles, TB/s, chunk walk against memory-direct): ranges of 256 KiB: one-byte elements 2.82 / 1.46,
+        // four-byte 3.92 / 2.48; 512 KiB: two-byte 2.58 / 1.76, eight-byte 3.39 / 3.08; 1 MiB: one-byte
+        // 1.50 / 1.39, four-byte 2.39 / 2.39; 2 MiB: two-byte 1.13 / 1.68, eight-byte 1.53 / 2.85.  The
+        // cost grows with range bytes per workgroup element, the memory-direct kernel's does not.
         const int pcb = gather_phased_chunk_bits(elem_bytes);
         static const long long phased_max = getenv("LL_GATHER_PHASED_MAX_BYTES") ? atoll(getenv("LL_GATHER_PHASED_MAX_BYTES")) : 512 * 1024;   // experiment knob
         const long long block_bytes = (long long)elem_bytes << top;
