@@ -860,6 +860,32 @@ def test_gather_under_broadcasting_layouts(w, monkeypatch):
 
 
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
+def test_gather_through_lds_chunks_broadcasting_and_affine(w):
+    """The chunk-walking kernel (aligned range of 256 or 512 KiB that no closed block with long runs
+    covers) under random XOR layouts that broadcast (one slot bit more than logical bits, replicas of
+    `in` and `idx` unequal) and carry an affine constant, indices partly out of range (they wrap)."""
+    rng = np.random.default_rng(9900 + w)
+    wl2 = {1: 0, 2: 1, 4: 2, 8: 3}[w]
+    seen = set()
+    for range_bytes_log2 in (18, 19):
+        d_in = range_bytes_log2 - wl2                 # slots per tile: the tile is the aligned range
+        d_out = d_in - 1
+        dims = [d_out - 3, 3]
+        cols = surjective_bases(rng, d_in, d_out)
+        layout = ll.ll_layout_create([(ll.LL_IN_REG, 4), (ll.LL_IN_LANE, 6), (ll.LL_IN_WAVE, d_in - 10)], dims, cols)
+        off = int(rng.integers(1, 1 << d_out))
+        for lay, o in ((layout, 0), (ll.ll_layout_with_offset(layout, off), off)):
+            info = ll.ll_gather_info(lay, 0, w)
+            seen.add(info["kernel_name"])
+            ntiles = 3
+            inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d_in, dtype=NP_DTYPES[w])
+            idx = rng.integers(-(1 << dims[0]), 1 << dims[0], size=ntiles << d_in, dtype=np.int32)
+            got = run_gather(lay, 0, inp, idx, d_in)
+            assert np.array_equal(got, oracle.gather_general(cols, dims, 0, inp, idx, o)), (d_in, dims, o, info)
+    assert "lds_phased" in seen
+
+
+@pytest.mark.parametrize("w", [1, 2, 4, 8])
 def test_gather_on_memory_layouts(w):
     """in, idx and out as buffers indexed by memory offset: a row-major tensor (the identity memory
     layout) against torch.gather on the logical view, and an mma-swizzled buffer against the oracle."""
