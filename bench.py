@@ -324,11 +324,11 @@ def main() -> int:
         torch.cuda.empty_cache()
         # axes whose aligned block exceeds LDS, row-major two-byte tiles of 2^18 elements (512 KiB), gather along
         # the rows: 512 x 512 is staged as 512 rows x 128-byte runs; 8192 x 32 has no closed block with runs of
-        # 64 bytes that fits LDS, its 512 KiB range is walked through LDS in chunks; 16384 x 32 (1 MiB) is read
+        # 64 bytes that fits LDS, its 512 KiB range is walked through LDS in chunks; 32768 x 32 (2 MiB) is read
         # straight from memory
         xb = wl.raw_bits(23, 0, (512 << 18) * 2 // 8, dev).view(torch.int16)
         ob = torch.empty_like(xb)
-        for rows_b, cols_b in ((9, 9), (13, 5), (14, 5)):
+        for rows_b, cols_b in ((9, 9), (13, 5), (15, 5)):
             db = rows_b + cols_b
             ntb = (512 << 18) >> db
             big = ll.distributed_layout(4, 6, db - 10, [rows_b, cols_b], [1 << k for k in range(db)])

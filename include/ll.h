@@ -297,8 +297,8 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
  *    (the span of those index changes plus contiguous runs of 128 bytes where the size allows) is
  *    staged in workgroup LDS, at most 128 KiB; if no such block with runs of at least 64 bytes fits,
  *    the aligned power-of-two range around an element that holds all its possible sources is either
- *    walked through LDS in 64 KiB chunks by every workgroup with elements in it (ranges up to
- *    512 KiB), or every element is gathered straight from memory (slower: every element is its own
+ *    walked through LDS in 128 KiB chunks by every workgroup with elements in it (ranges up to
+ *    1 MiB), or every element is gathered straight from memory (slower: every element is its own
  *    access).
  *    Sec. 5.5's condition (no wave bits on the axis) is reported by ll_gather_info
  *    (axis_wave_bits == 0) and is not an error here;
@@ -312,7 +312,7 @@ typedef enum {
     LL_GATHER_BLOCK_STAGED = 2,  /* general: a block closed under the axis staged in workgroup LDS */
     LL_GATHER_GLOBAL = 3,        /* no closed block fits LDS: element-wide reads from memory */
     LL_GATHER_PHASED = 4         /* no closed block fits LDS, but the aligned range around an element is a few
-                                    LDS sizes: every workgroup walks the range through LDS in 64 KiB chunks */
+                                    LDS sizes: every workgroup walks the range through LDS in 128 KiB chunks */
 } ll_gather_kernel;
 
 typedef struct {

@@ -1275,7 +1275,9 @@ __global__ __launch_bounds__(256) void k_gather_global(const GatherGenArgs a)
     static_assert(kGlobalPasses == 4, "CB assumes four passes");
     const uint32_t tid = threadIdx.x;
     const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;
-    if (tid < 32u * (uint32_t)ntab) {
+    // at least four tables are filled (those beyond the axis bits with zeros) so that the first four
+    // lookups of an element need no condition and issue together
+    if (tid < 32u * (uint32_t)(ntab > 4 ? ntab : 4)) {
         const uint32_t x = (tid & 31u) << (5u * (tid >> 5));
         uint32_t dl = 0;
         for (int b = 0; b < a.na; ++b) dl ^= a.delta[b] & (0u - ((x >> b) & 1u));
@@ -1319,8 +1321,8 @@ __global__ __launch_bounds__(256) void k_gather_global(const GatherGenArgs a)
 #pragma unroll
             for (int s = 0; s < UE; ++s) {
                 const uint32_t x = (ix[q][s] ^ own_t ^ own_q[q] ^ own_s[s]) & a.axis_mask;
-                uint32_t t = table[x & 31u];
-                for (int k = 1; k < ntab; ++k) t ^= table[32u * k + ((x >> (5 * k)) & 31u)];
+                uint32_t t = table[x & 31u] ^ table[32u + ((x >> 5) & 31u)] ^ table[64u + ((x >> 10) & 31u)] ^ table[96u + ((x >> 15) & 31u)];
+                for (int k = 4; k < ntab; ++k) t ^= table[32u * k + ((x >> (5 * k)) & 31u)];
                 const unsigned long long src = ((unsigned long long)first + unit * UE + s) ^ (unsigned long long)t;
                 const unsigned char *p = in + src * W;
                 if constexpr (W == 8) {
@@ -1383,7 +1385,7 @@ ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *str
 constexpr int kPhasedThreadBits = 10;
 constexpr int kPhasedUnits = 8;                       // units per thread
 constexpr int kPhasedChunkBytes = 128 * 1024;
-template <int W>
+template <int W, bool FIELD>
 __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const GatherGenArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -1402,7 +1404,9 @@ __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const 
     uint32_t *table = reinterpret_cast<uint32_t *>(lds + kPhasedChunkBytes + 16);
     const uint32_t tid = threadIdx.x;
     const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;
-    if (tid < 32u * (uint32_t)ntab) {
+    // at least four tables are filled (those beyond the axis bits with zeros) so that the first four
+    // lookups of an element need no condition and issue together
+    if (tid < 32u * (uint32_t)(ntab > 4 ? ntab : 4)) {
         const uint32_t x = (tid & 31u) << (5u * (tid >> 5));
         uint32_t dl = 0;
         for (int b = 0; b < a.na; ++b) dl ^= a.delta[b] & (0u - ((x >> b) & 1u));
@@ -1456,10 +1460,17 @@ __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const 
         const uint32_t unit = tid + T * q;
 #pragma unroll
         for (int s = 0; s < UE; ++s) {
-            const uint32_t x = (ix[q][s] ^ own_q ^ own_s[s]) & a.axis_mask;
-            uint32_t t = table[x & 31u];
-            for (int k = 1; k < ntab; ++k) t ^= table[32u * k + ((x >> (5 * k)) & 31u)];
-            ix[q][s] = (((rel + unit * UE + s) ^ t) & block_mask) * W;    // byte offset of the source in the range
+            if constexpr (FIELD) {
+                // the axis coordinate is a bit field of the element index: the source is the element's
+                // own index with that field replaced by the gather index
+                const uint32_t field = a.axis_mask << a.field_shift;
+                ix[q][s] = ((((rel + unit * UE + s) & ~field) | ((ix[q][s] & a.axis_mask) << a.field_shift)) & block_mask) * W;
+            } else {
+                const uint32_t x = (ix[q][s] ^ own_q ^ own_s[s]) & a.axis_mask;
+                uint32_t t = table[x & 31u] ^ table[32u + ((x >> 5) & 31u)] ^ table[64u + ((x >> 10) & 31u)] ^ table[96u + ((x >> 15) & 31u)];
+                for (int k = 4; k < ntab; ++k) t ^= table[32u * k + ((x >> (5 * k)) & 31u)];
+                ix[q][s] = (((rel + unit * UE + s) ^ t) & block_mask) * W;    // byte offset of the source in the range
+            }
         }
     }
     uint32_t o[P][4];
@@ -1523,11 +1534,16 @@ template <int W>
 static ll_status launch_gather_phased_w(const GatherGenArgs &a, hipStream_t s)
 {
     const size_t lds_bytes = (size_t)kPhasedChunkBytes + 16 + 6 * 32 * sizeof(uint32_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gather_phased<W>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds_bytes);
+    const bool field = a.field_shift >= 0;
+    hipError_t e = hipFuncSetAttribute(field ? reinterpret_cast<const void *>(k_gather_phased<W, true>)
+                                             : reinterpret_cast<const void *>(k_gather_phased<W, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
     const dim3 grid((unsigned)a.nblocks), block(1u << kPhasedThreadBits);
-    launch((k_gather_phased<W>), grid, block, lds_bytes, s, a);
+    if (field)
+        launch((k_gather_phased<W, true>), grid, block, lds_bytes, s, a);
+    else
+        launch((k_gather_phased<W, false>), grid, block, lds_bytes, s, a);
     return check_launch("phased gather kernel launch");
 }
 
@@ -1538,6 +1554,7 @@ ll_status launch_gather_phased(const GatherGenArgs &a, int elem_bytes, void *str
     const int wl = elem_bytes == 1 ? 0 : elem_bytes == 2 ? 1 : elem_bytes == 4 ? 2 : 3;
     // a workgroup's elements lie in one aligned block, the block is a whole number of chunks and its
     // bytes fit a buffer descriptor
+    if (a.field_shift >= 0 && a.field_shift + a.na > 32) return fail(LL_ERR_INVALID_ARG, "internal: gather axis field out of range");
     if (a.block_bits < gather_phased_chunk_bits(elem_bytes) || (1ll << (a.block_bits + wl)) < kPhasedChunkBytes || a.block_bits + wl > 31)
         return fail(LL_ERR_INVALID_ARG, "internal: gather block of 2^%d elements does not suit the phased kernel", a.block_bits);
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -244,15 +244,28 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         // An aligned block of a few LDS sizes is walked through LDS chunk by chunk by every workgroup
         // that has elements in it (k_gather_phased): the block is then read from L2 once per workgroup,
         // in full lines, instead of one line per element.  Measured on MI355X (row gathers in row-major
-        // tiles, TB/s, chunk walk against memory-direct): ranges of 256 KiB: one-byte elements 2.82 / 1.46,
-        // four-byte 3.92 / 2.48; 512 KiB: two-byte 2.58 / 1.76, eight-byte 3.39 / 3.08; 1 MiB: one-byte
-        // 1.50 / 1.39, four-byte 2.39 / 2.39; 2 MiB: two-byte 1.13 / 1.68, eight-byte 1.53 / 2.85.  The
-        // cost grows with range bytes per workgroup element, the memory-direct kernel's does not.
+        // tiles, where the source index needs no tables; TB/s, chunk walk against memory-direct): ranges of
+        // 256 KiB: one-byte elements 3.99 / 1.46, four-byte 5.11 / 2.48; 512 KiB: two-byte 3.35 / 1.76,
+        // eight-byte 3.85 / 3.08; 1 MiB: one-byte 1.80 / 1.39, four-byte 2.85 / 2.40; 2 MiB: two-byte
+        // 1.27 / 1.66, eight-byte 1.63 / 2.86.  Random XOR layouts (table lookups), 512 KiB: 2.5 / 2.9 / 3.5
+        // for 1- / 2- / 4-byte elements.  The cost grows with range bytes per workgroup element, the
+        // memory-direct kernel's does not.
         const int pcb = gather_phased_chunk_bits(elem_bytes);
-        static const long long phased_max = getenv("LL_GATHER_PHASED_MAX_BYTES") ? atoll(getenv("LL_GATHER_PHASED_MAX_BYTES")) : 512 * 1024;   // experiment knob
+        static const long long phased_max = getenv("LL_GATHER_PHASED_MAX_BYTES") ? atoll(getenv("LL_GATHER_PHASED_MAX_BYTES")) : 1024 * 1024;   // experiment knob
         const long long block_bytes = (long long)elem_bytes << top;
         const bool phased = top >= pcb && block_bytes >= 2 * gather_phased_lds_chunk_bytes() && block_bytes <= phased_max && top + wlog <= 31;
         c->kernel = phased ? LL_GATHER_PHASED : LL_GATHER_GLOBAL;
+        // The axis coordinate of an element may simply be a bit field of its index (row-major memory
+        // layouts, blocked layouts): then the source is the element's own index with that field
+        // replaced by the gather index, no tables needed.
+        g.field_shift = -1;
+        if (na > 0 && own_const == 0 && g.delta[0] != 0 && !(g.delta[0] & (g.delta[0] - 1))) {
+            const int shift = __builtin_ctz(g.delta[0]);
+            bool field = shift + na <= 32;
+            for (int b = 0; b < na && field; ++b) field = g.delta[b] == (1u << (shift + b));
+            for (int j = 0; j < 32 && field; ++j) field = g.own_bit[j] == ((j >= shift && j < shift + na) ? (1u << (j - shift)) : 0u);
+            if (field) g.field_shift = shift;
+        }
         return LL_OK;
     }
     if (n < min_bits) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than the kernel's unit of work");

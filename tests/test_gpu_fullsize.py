@@ -164,12 +164,12 @@ def test_gather_beyond_lds_full_size_sampled():
     assert torch.equal(out.view(ntiles, 512, 512), ref)
 
 
-@pytest.mark.parametrize("rows_bits,kernel", [(13, "lds_phased"), (14, "global")])
+@pytest.mark.parametrize("rows_bits,kernel", [(13, "lds_phased"), (14, "lds_phased"), (15, "global")])
 def test_gather_beyond_lds_without_long_runs_full_size(rows_bits, kernel):
-    """256 MiB of 8192 x 32 (16384 x 32) two-byte tiles gathered along the rows: no block closed under
-    the rows fits LDS with runs of 64 bytes.  The aligned 512 KiB range is walked through LDS in
-    chunks; the 1 MiB range is read from memory element by element.  Against torch.gather on the
-    logical view and sampled tiles against the oracle."""
+    """256 MiB of 8192 x 32 (16384 x 32, 32768 x 32) two-byte tiles gathered along the rows: no block
+    closed under the rows fits LDS with runs of 64 bytes.  Aligned ranges of 512 KiB and 1 MiB are
+    walked through LDS in chunks; the 2 MiB range is read from memory element by element.  Against
+    torch.gather on the logical view and sampled tiles against the oracle."""
     d = rows_bits + 5
     ntiles = (256 << 20) // (2 << d)
     rows = 1 << rows_bits
@@ -293,7 +293,7 @@ def test_gather_general_kernels_beyond_four_gib(kernel):
         cfg = wl.config(5)
         bases, dims, axis, split = cfg.src_bases, cfg.out_dim_bits, 1, (cfg.nreg, cfg.nlane, cfg.nwave)
     else:
-        bases, dims, axis, split = [1 << k for k in range(18)], [13, 5], 0, (4, 6, 8)
+        bases, dims, axis, split = [1 << k for k in range(19)], [14, 5], 0, (4, 6, 9)
     layout = ll.distributed_layout(*split, dims, bases)
     assert ll.ll_gather_info(layout, axis, 4)["kernel_name"] == kernel
     d = sum(dims)

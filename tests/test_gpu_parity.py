@@ -787,14 +787,14 @@ def test_convert_between_different_register_lane_wave_splits(w):
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 def test_gather_along_axes_larger_than_lds(w, monkeypatch):
     """Axes whose aligned block exceeds what LDS stages (128 KiB) are walked through LDS in chunks
-    (up to 512 KiB) or gathered straight from memory; blocks of 64 and 128 KiB are staged by
-    1024-thread workgroups.  Random XOR layouts on tiles of 64, 128, 256 KiB and 1 MiB and of 2^18
+    (up to 1 MiB) or gathered straight from memory; blocks of 64 and 128 KiB are staged by
+    1024-thread workgroups.  Random XOR layouts on tiles of 64, 128, 256 KiB and 2 MiB and of 2^18
     elements (every axis then reaches the top bits), a ragged number of tiles, and a permutation
     layout whose axis 0 is exactly the wave bits of a 2^17-element tile."""
     rng = np.random.default_rng(9300 + w)
     d128 = 17 - {1: 0, 2: 1, 4: 2, 8: 3}[w]                          # a tile of 128 KiB
     cases = [(d128 - 1, [d128 - 1]), (d128, [d128 // 2, d128 - d128 // 2]), (d128 + 1, [d128 + 1]), (18, [6, 6, 6]),
-             (d128 + 3, [d128 + 3])]
+             (d128 + 4, [d128 + 4])]
     seen = set()
     for d, dims in cases:
         nreg, nlane = 4, 6
@@ -861,13 +861,13 @@ def test_gather_under_broadcasting_layouts(w, monkeypatch):
 
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 def test_gather_through_lds_chunks_broadcasting_and_affine(w):
-    """The chunk-walking kernel (aligned range of 256 or 512 KiB that no closed block with long runs
+    """The chunk-walking kernel (aligned range of 256 KiB to 1 MiB that no closed block with long runs
     covers) under random XOR layouts that broadcast (one slot bit more than logical bits, replicas of
     `in` and `idx` unequal) and carry an affine constant, indices partly out of range (they wrap)."""
     rng = np.random.default_rng(9900 + w)
     wl2 = {1: 0, 2: 1, 4: 2, 8: 3}[w]
     seen = set()
-    for range_bytes_log2 in (18, 19):
+    for range_bytes_log2 in (18, 19, 20):
         d_in = range_bytes_log2 - wl2                 # slots per tile: the tile is the aligned range
         d_out = d_in - 1
         dims = [d_out - 3, 3]

@@ -307,14 +307,14 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     assert info["kernel_name"] == "block_staged" and info["axis_wave_bits"] == 6 and info["block_bytes"] == 8192
     assert ll.ll_gather_info(big, 0, 4)["kernel_name"] == "wave_staged"
     # 8192 rows of 32 two-byte elements: a block closed under the rows would need runs under 64 bytes
-    # to fit LDS; the aligned 512 KiB range is walked through LDS in chunks.  Twice the rows: the range
-    # is 1 MiB and the rows are gathered straight from memory
+    # to fit LDS; the aligned 512 KiB range is walked through LDS in chunks.  Four times the rows: the
+    # range is 2 MiB and the rows are gathered straight from memory
     tall = ll.distributed_layout(4, 6, 8, [13, 5], [1 << k for k in range(18)])
     info = ll.ll_gather_info(tall, 0, 2)
     assert info["kernel_name"] == "lds_phased" and info["block_bytes"] == 512 * 1024
-    taller = ll.distributed_layout(4, 6, 9, [14, 5], [1 << k for k in range(19)])
+    taller = ll.distributed_layout(4, 6, 10, [15, 5], [1 << k for k in range(20)])
     info = ll.ll_gather_info(taller, 0, 2)
-    assert info["kernel_name"] == "global" and info["block_bytes"] == 1024 * 1024
+    assert info["kernel_name"] == "global" and info["block_bytes"] == 2048 * 1024
     # a tile label on the axis
     tiled = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, 6), (ll.LL_IN_TILE, 2)], [2, 8],
                                 [1 << k for k in range(10)])
