@@ -1095,7 +1095,7 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
     const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;      // an axis of one element still reads table 0 (all zero)
 
     // delta tables
-    if (tid < 32u * (uint32_t)ntab) {
+    if (tid < 128u) {                                    // four tables, those beyond the axis bits all zero
         const uint32_t x = (tid & 31u) << (5u * (tid >> 5));
         uint32_t dl = 0;
         for (int b = 0; b < a.na; ++b) dl ^= a.delta[b] & (0u - ((x >> b) & 1u));
@@ -1171,9 +1171,7 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
             for (int s = 0; s < UE; ++s) {
                 const uint32_t x = (ix[q][s] ^ own_p[q] ^ own_s[s]) & a.axis_mask;
                 uint32_t t = table[x & 31u];
-                if (ntab > 1) t ^= table[32u + ((x >> 5) & 31u)];
-                if (ntab > 2) t ^= table[64u + ((x >> 10) & 31u)];
-                if (ntab > 3) t ^= table[96u + (x >> 15)];
+                t ^= table[32u + ((x >> 5) & 31u)] ^ table[64u + ((x >> 10) & 31u)] ^ table[96u + (x >> 15)];
                 const uint32_t addr = self ^ ((uint32_t)s * W) ^ t;   // XOR, not add: the swizzle may have set bit 2 of self
                 if constexpr (W == 8) {
                     const u32x2 v = *reinterpret_cast<const u32x2 *>(lds + addr);
@@ -1204,7 +1202,7 @@ static ll_status launch_gather_general_wt(const GatherGenArgs &a, hipStream_t s)
 {
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
     const long long block_bytes = (1ll << a.block_bits) * W;
-    const size_t lds_bytes = (size_t)block_bytes + 128u * (size_t)(a.na > 0 ? (a.na + 4) / 5 : 1);
+    const size_t lds_bytes = (size_t)block_bytes + 4u * 128u;      // the block and four delta tables
     const dim3 grid((unsigned)a.nblocks), block(1u << TB);
     const int vec_passes = (int)((1ll << a.block_bits) >> VS >> TB), unit_passes = (int)((1ll << a.block_bits) >> ((W == 8 ? 1 : 2) + TB));
     if (vec_passes < 1 || unit_passes < 1) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than one pass");
