@@ -1,6 +1,7 @@
 // HIP kernels for gfx950 (CDNA4, wave64).  Pure data movement: 16-byte global loads and stores,
 // LDS staging or cross-lane shuffles in between, no MFMA.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include <cstdlib>
 
@@ -1162,6 +1163,10 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
                 ix[q][0] = t.x; ix[q][1] = t.y;
             }
         }
+        // When the deltas are consecutive single bits of the block-local index and nothing is swizzled
+        // (a row gather in a row-major tile), the LDS offset of a move is the coordinate difference
+        // shifted into place: no table lookups.  The choice is uniform and made per pass.
+        auto gather_units = [&](auto shifted) {
 #pragma unroll
         for (int q = 0; q < U; ++q) {
             const uint32_t unit = tid + T * (p + q);
@@ -1170,8 +1175,13 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
 #pragma unroll
             for (int s = 0; s < UE; ++s) {
                 const uint32_t x = (ix[q][s] ^ own_p[q] ^ own_s[s]) & a.axis_mask;
-                uint32_t t = table[x & 31u];
-                t ^= table[32u + ((x >> 5) & 31u)] ^ table[64u + ((x >> 10) & 31u)] ^ table[96u + (x >> 15)];
+                uint32_t t;
+                if constexpr (decltype(shifted)::value) {
+                    t = x << a.field_shift;
+                } else {
+                    t = table[x & 31u];
+                    t ^= table[32u + ((x >> 5) & 31u)] ^ table[64u + ((x >> 10) & 31u)] ^ table[96u + (x >> 15)];
+                }
                 const uint32_t addr = self ^ ((uint32_t)s * W) ^ t;   // XOR, not add: the swizzle may have set bit 2 of self
                 if constexpr (W == 8) {
                     const u32x2 v = *reinterpret_cast<const u32x2 *>(lds + addr);
@@ -1194,6 +1204,11 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
                 __builtin_amdgcn_raw_buffer_store_b32(o[0], rout, uoff[q] * W, 0, kStream);
             }
         }
+        };
+        if (a.field_shift >= 0)
+            gather_units(std::true_type{});
+        else
+            gather_units(std::false_type{});
     }
 }
 

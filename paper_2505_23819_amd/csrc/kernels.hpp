@@ -145,7 +145,8 @@ struct GatherGenArgs {
     int swz_shift, swz_to;               // LDS byte address ^= ((address >> swz_shift) & swz_mask) << swz_to
     uint32_t swz_mask;
     int field_shift;                     // chunk-walking kernel: >= 0 when the axis coordinate is the bit field [field_shift, field_shift + na)
-                                         // of the element index itself (a row-major tile, a blocked layout), else -1
+                                         // of the element index itself (a row-major tile, a blocked layout), else -1;
+                                         // staged kernel: >= 0 when the LDS byte offset of a move is (coordinate difference) << field_shift
 };
 
 int xcd_chunk_bits_for(long long group_bytes, long long block_bytes);

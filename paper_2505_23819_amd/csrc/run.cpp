@@ -308,6 +308,15 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         static const bool always = getenv("LL_GATHER_SWIZZLE_ALWAYS") != nullptr;      // experiment knob
         if (!(moved & bank_bits) && !always) g.swz_mask = 0;
     }
+    // deltas that are consecutive single bits of the block-local index, nothing swizzled: the LDS byte
+    // offset of a move is (coordinate difference) << field_shift
+    g.field_shift = -1;
+    if (g.swz_mask == 0 && na > 0 && g.delta[0] != 0 && !(g.delta[0] & (g.delta[0] - 1))) {
+        const int shift = __builtin_ctz(g.delta[0]);
+        bool field = true;
+        for (int b = 0; b < na && field; ++b) field = g.delta[b] == (1u << (shift + b));
+        if (field) g.field_shift = shift + wlog;
+    }
     c->kernel = LL_GATHER_BLOCK_STAGED;
     return LL_OK;
 }
