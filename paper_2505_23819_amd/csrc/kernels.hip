@@ -1093,7 +1093,6 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
     const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (((size_t)group << gshift) * W), valid * W);
     auto swz = [&](uint32_t addr) { return addr ^ (((addr >> a.swz_shift) & a.swz_mask) << a.swz_to); };
     uint32_t *table = reinterpret_cast<uint32_t *>(lds + ((size_t)block_elems * W));
-    const int ntab = a.na > 0 ? (a.na + 4) / 5 : 1;      // an axis of one element still reads table 0 (all zero)
 
     // delta tables
     if (tid < 128u) {                                    // four tables, those beyond the axis bits all zero
@@ -1410,7 +1409,8 @@ __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const 
     constexpr int CB = UB + TB + 3;                   // log2 elements per workgroup
     static_assert(kPhasedUnits == 8, "CB assumes eight units per thread");
     constexpr int WL = (W == 1) ? 0 : (W == 2) ? 1 : (W == 4) ? 2 : 3;
-    constexpr int SB = (kPhasedChunkBytes == 128 * 1024 ? 17 : 16) - WL;   // log2 elements per chunk
+    static_assert(kPhasedChunkBytes == 128 * 1024, "SB assumes 128 KiB chunks");
+    constexpr int SB = 17 - WL;                       // log2 elements per chunk
     constexpr int VPT = kPhasedChunkBytes / 16 / (int)T;   // 16-byte vectors per thread and chunk
     // LDS: the chunk, then 16 bytes of zeros (where every element whose source is NOT in the current
     // chunk reads), then the delta tables
