@@ -639,6 +639,46 @@ def test_entry_points_can_be_captured_in_a_hip_graph():
                                                                    wl.to_numpy_bits(new_inp), new_idx.numpy())), rep
 
 
+def test_large_lds_gathers_can_be_captured_in_a_hip_graph():
+    """The gather kernels that ask for more than 64 KiB of LDS (a 64 KiB closed block plus tables; the
+    128 KiB chunks of the chunk-walking kernel) set a function attribute before every launch: that
+    must be harmless under stream capture.  Two tiles each, replayed with new inputs, against
+    torch.gather on the logical view."""
+    d = 18
+    staged = ll.distributed_layout(4, 6, 8, [9, 9], [1 << k for k in range(d)])
+    walked = ll.distributed_layout(4, 6, 8, [13, 5], [1 << k for k in range(d)])
+    assert ll.ll_gather_info(staged, 0, 2)["kernel_name"] == "block_staged"
+    assert ll.ll_gather_info(walked, 0, 2)["kernel_name"] == "lds_phased"
+    nt = 2
+    inp = torch.zeros(nt << d, dtype=torch.int16, device="cuda")
+    idx_s = torch.zeros(nt << d, dtype=torch.int32, device="cuda")
+    idx_w = torch.zeros(nt << d, dtype=torch.int32, device="cuda")
+    out_s, out_w = torch.zeros_like(inp), torch.zeros_like(inp)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside capture
+        ll.ll_gather(staged, 0, 2, inp, idx_s, out_s, nt)
+        ll.ll_gather(walked, 0, 2, inp, idx_w, out_w, nt)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ll.ll_gather(staged, 0, 2, inp, idx_s, out_s, nt)
+        ll.ll_gather(walked, 0, 2, inp, idx_w, out_w, nt)
+    gen = torch.Generator(device="cpu").manual_seed(77)
+    for rep in range(3):
+        inp.copy_(torch.randint(-2**15, 2**15 - 1, (nt << d,), dtype=torch.int16, generator=gen).cuda())
+        idx_s.copy_(torch.randint(0, 512, (nt << d,), dtype=torch.int32, generator=gen).cuda())
+        idx_w.copy_(torch.randint(0, 8192, (nt << d,), dtype=torch.int32, generator=gen).cuda())
+        out_s.zero_()
+        out_w.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_s.view(nt, 512, 512), torch.gather(inp.view(nt, 512, 512), 1, idx_s.view(nt, 512, 512).long())), rep
+        assert torch.equal(out_w.view(nt, 8192, 32), torch.gather(inp.view(nt, 8192, 32), 1, idx_w.view(nt, 8192, 32).long())), rep
+
+
 def test_layouts_with_a_tile_label():
     """A `tile` input dim passes through conversions untouched (the tile index is the workgroup
     dimension) and may not lie on a gather axis; everything else behaves as without it."""
