@@ -3,8 +3,9 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--only-main] [--strategy N]
 
-A step is one pass of the headline workload (benchmark configuration 2: 8192 tiles of
-128x128 bf16 transposed) with inputs already resident in HBM.  The
+A step is one pass of the headline workload (benchmark configuration 4, the largest and slowest
+of the five: 4096 tiles of 65536 int32 converted between two random invertible XOR layouts, 2 GiB
+of algorithmic bytes) with inputs already resident in HBM.  The
 JSON line printed at the end carries the whole-job GB/s (read + write algorithmic
 bytes), a roofline object for the dominant kernel, the CPU oracle timed on a
 bounded sample, and per-config figures for all five configurations next to a
@@ -26,17 +27,18 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
 
 
-TABLE_WARMUP = 10      # untimed launches before each table entry (on fresh buffers the first launches run slower)
+TABLE_WARMUP = 10      # untimed launches before each table entry, at least; extended to TABLE_WARMUP_MS of device time
+TABLE_WARMUP_MS = 25.0 # (the first launches after an idle spell or on fresh buffers run up to 10 % slower: clocks ramp up)
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--only-main", action="store_true", help="skip the per-config table")
-    ap.add_argument("--workload", type=int, default=2, help="config id timed as the main line (default 2)")
+    ap.add_argument("--workload", type=int, default=4, help="config id timed as the main line (default 4: the largest)")
     ap.add_argument("--table-steps", type=int, default=100, help="launches per config in the per-config table")
     ap.add_argument("--strategy", type=int, default=None,
                     help="force a conversion strategy for every plan (3: element-wide LDS, 4: 128-bit LDS "
@@ -48,9 +50,6 @@ def main() -> int:
               "Run with --gpus 1.", file=sys.stderr)
         return 2
 
-    if args.strategy is not None:
-        os.environ["LL_FORCE_STRATEGY"] = str(args.strategy)     # read by the planner at plan time
-
     import torch
     import paper_2505_23819_amd as ll
     import workloads as wl
@@ -61,7 +60,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = "cuda"
 
-    def make_case(cfg, nsets):
+    forced = None if args.strategy is None else ll.ll_options_init(strategy=args.strategy)
+
+    def make_case(cfg, nsets, opts=forced):
         """Device buffers (nsets rotating copies) and a launcher for one configuration."""
         a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
         sets = []
@@ -80,7 +81,7 @@ def main() -> int:
                 ll.ll_gather(a, cfg.axis, cfg.elem_bytes, x, idx, out, cfg.ntiles)
         else:
             b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
-            plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+            plan = ll.ll_plan_convert(a, b, cfg.elem_bytes, opts)
             info = plan.info()
 
             def launch(k, plan=plan):
@@ -88,7 +89,7 @@ def main() -> int:
                 ll.ll_convert(plan, x, out, cfg.ntiles)
         return launch, info, sets
 
-    def time_launches(launch, steps, warmup):
+    def time_launches(launch, steps, warmup, warm_ms=TABLE_WARMUP_MS):
         """Returns (wall ms per step, mean ms per launch, median, min).
 
         The timed region is exactly `steps` back-to-back launches between two HIP events on the stream
@@ -96,9 +97,16 @@ def main() -> int:
         host clock readings around synchronize(): mean = event time / steps, wall = host time / steps.
         Median and minimum come from a second, untimed pass with an event after every launch (each
         such event costs about 3 us of stream time, which is why it is not done in the timed region)."""
+        t_w = time.perf_counter()
         for k in range(warmup):
             launch(k)
         torch.cuda.synchronize()
+        if warm_ms and warmup:
+            spent = (time.perf_counter() - t_w) * 1e3
+            extra = min(5000, int((warm_ms - spent) / max(spent / warmup, 1e-3))) if spent < warm_ms else 0
+            for k in range(extra):
+                launch(k)
+            torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -129,7 +137,7 @@ def main() -> int:
 
     main_cfg = wl.config(args.workload)
     launch, info, sets = make_case(main_cfg, nsets=2)
-    wall_ms, mean_ms, med_ms, min_ms = time_launches(launch, args.steps, args.warmup)
+    wall_ms, mean_ms, med_ms, min_ms = time_launches(launch, args.steps, args.warmup, warm_ms=0)      # exactly W warm-up steps
     alg_bytes = main_cfg.algorithmic_bytes()
     value = alg_bytes / wall_ms / 1e6                      # GB/s over the timed region (wall clock)
     achieved = alg_bytes / mean_ms / 1e6                   # GB/s of the kernel itself (HIP events)
@@ -193,9 +201,7 @@ def main() -> int:
                 entry["copy_GBps_same_footprint"] = round(copy_ceiling(ab // 2), 1)
             if cfg.kind == "convert" and args.strategy is None and inf["strategy_name"] in ("reg_permute", "wave_shuffle"):
                 # the same conversion staged through LDS (128-bit accesses), for comparison
-                os.environ["LL_FORCE_STRATEGY"] = "4"
-                l2, inf2, s2 = make_case(cfg, nsets)
-                del os.environ["LL_FORCE_STRATEGY"]
+                l2, inf2, s2 = make_case(cfg, nsets, ll.ll_options_init(strategy=ll.LL_STRATEGY_LDS_VEC))
                 _, md2, _, _ = time_launches(l2, steps, TABLE_WARMUP)
                 entry["through_lds"] = {"kernel": inf2["strategy_name"], "lds_access_bytes": inf2["lds_write_bytes"],
                                         "GBps": round(ab / md2 / 1e6, 1),
@@ -232,12 +238,8 @@ def main() -> int:
         o1 = [torch.empty_like(x1) for _ in range(2)]
         ab1 = 2 * nt1 * c1.tile_elems * c1.elem_bytes
         many = []
-        for force in (None, "4", "3"):
-            if force is not None:
-                os.environ["LL_FORCE_STRATEGY"] = force
-            p1 = ll.ll_plan_convert(a1, b1, c1.elem_bytes)
-            if force is not None:
-                del os.environ["LL_FORCE_STRATEGY"]
+        for force in (None, ll.LL_STRATEGY_LDS_VEC, ll.LL_STRATEGY_LDS_ELEM):
+            p1 = ll.ll_plan_convert(a1, b1, c1.elem_bytes, None if force is None else ll.ll_options_init(strategy=force))
             i1 = p1.info()
             _, m_ms, _, _ = time_launches(lambda k: ll.ll_convert(p1, x1, o1[k % 2], nt1), args.table_steps, TABLE_WARMUP)
             many.append({"kernel": i1["strategy_name"], "shuffle_stages": i1["shuffle_rounds"], "lds_bytes": i1["lds_bytes"],
@@ -273,15 +275,11 @@ def main() -> int:
         # choice, and the same conversion through the transposing LDS loads of gfx950 / 128-bit LDS
         ttable = []
         c2 = wl.config(2)
-        for w_, dt_, force_ in ((1, torch.uint8, None), (1, torch.uint8, "6"), (2, torch.int16, "6"), (2, torch.int16, "4")):
-            if force_ is not None:
-                os.environ["LL_FORCE_STRATEGY"] = force_
+        for w_, dt_, force_ in ((1, torch.uint8, None), (1, torch.uint8, ll.LL_STRATEGY_LDS_TR), (2, torch.int16, ll.LL_STRATEGY_LDS_TR),
+                                (2, torch.int16, ll.LL_STRATEGY_LDS_VEC)):
             a = ll.distributed_layout(c2.nreg, c2.nlane, c2.nwave, c2.out_dim_bits, c2.src_bases)
             b = ll.distributed_layout(c2.nreg, c2.nlane, c2.nwave, c2.out_dim_bits, c2.dst_bases)
-            plan = ll.ll_plan_convert(a, b, w_)
-            os.environ.pop("LL_FORCE_STRATEGY", None)
-            if args.strategy is not None:
-                os.environ["LL_FORCE_STRATEGY"] = str(args.strategy)
+            plan = ll.ll_plan_convert(a, b, w_, None if force_ is None else ll.ll_options_init(strategy=force_))
             inf = plan.info()
             nt = (256 << 20) // (c2.tile_elems * w_)            # 256 MiB per side
             x = wl.raw_bits(21, 0, nt * c2.tile_elems * w_ // 8, dev).view(dt_)
@@ -304,15 +302,12 @@ def main() -> int:
         lay5 = ll.distributed_layout(c5.nreg, c5.nlane, c5.nwave, c5.out_dim_bits, c5.src_bases)
         x5 = c5.gen_data(0, c5.ntiles, dev)
         out5 = torch.empty_like(x5)
-        for axis_, env_ in ((0, {}), (0, {"LL_GATHER_STAGED": "0"}), (0, {"LL_GATHER_GENERAL": "1"}), (1, {})):
-            for k_, v_ in env_.items():
-                os.environ[k_] = v_
-            ginfo = ll.ll_gather_info(lay5, axis_, c5.elem_bytes)
+        for axis_, kern_ in ((0, None), (0, ll.LL_GATHER_SHUFFLE), (0, ll.LL_GATHER_BLOCK_STAGED), (1, None)):
+            gopts = None if kern_ is None else ll.ll_options_init(gather_kernel=kern_)
+            ginfo = ll.ll_gather_info(lay5, axis_, c5.elem_bytes, gopts)
             idx5 = wl.gen_index(51 + axis_, 0, c5.ntiles * c5.tile_elems, 1 << c5.out_dim_bits[axis_], dev)
-            _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(lay5, axis_, c5.elem_bytes, x5, idx5, out5, c5.ntiles),
+            _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(lay5, axis_, c5.elem_bytes, x5, idx5, out5, c5.ntiles, opts=gopts),
                                            args.table_steps, TABLE_WARMUP)
-            for k_ in env_:
-                del os.environ[k_]
             ab = c5.algorithmic_bytes()
             gtable.append({"name": "config 5 layout, gather along dim %d" % axis_, "kernel": ginfo["kernel_name"],
                            "axis_bits_reg_lane_wave": [ginfo["axis_reg_bits"], ginfo["axis_lane_bits"], ginfo["axis_wave_bits"]],

@@ -183,6 +183,58 @@ ll_status ll_layout_get_offset(const ll_layout *layout, uint64_t *offset);
  * input dim of d_out bits to one output dim of d_in bits (the flattened hardware index). */
 ll_status ll_invert(const ll_layout *layout, ll_layout **out);
 
+/* ---- options ------------------------------------------------------------------------------- */
+
+/* Explicit kernel selection and tuning for ll_plan_convert_opts / ll_gather_opts / ll_gather_info_opts.
+ * For callers that want a particular kernel (tests, benchmarks comparing the exchange paths) or
+ * that retune for a workload; nothing here changes a result.  Every field is an int32; LL_AUTO
+ * (-1) leaves the decision to the library.  An ll_options is plain data owned by the caller, read
+ * during the call only, and safe to share between threads.  ll_options_init sets every field to
+ * LL_AUTO; ll_options_from_env additionally takes overrides from LL_* environment variables (one
+ * per field, upper-case field name, e.g. LL_XCD_CHUNK) and is meant for experiments.  The calls
+ * without options behave as with a NULL pointer: they use the process defaults, which are
+ * ll_options_from_env evaluated ONCE, at the first call that needs them. */
+#define LL_AUTO (-1)
+typedef struct {
+    int32_t size;                  /* sizeof(ll_options), set by ll_options_init / ll_options_from_env */
+    /* kernel selection */
+    int32_t strategy;              /* conversions: LL_STRATEGY_LDS_ELEM: element-wide LDS staging (always applicable);
+                                      LL_STRATEGY_LDS_VEC: skip the register / shuffle planner, i.e. 128-bit LDS staging where it
+                                      applies, else element-wide; LL_STRATEGY_LDS_TR: transposing LDS loads where they apply,
+                                      else as LL_AUTO.  ll_plan_info reports the kernel actually planned. */
+    int32_t gather_kernel;         /* gathers: LL_GATHER_SHUFFLE / LL_GATHER_WAVE_STAGED (taken when the axis moves lane bits
+                                      only and the bytes per lane suit the kernel), LL_GATHER_BLOCK_STAGED (taken whenever a
+                                      closed block fits LDS); otherwise as LL_AUTO.  ll_gather_info_opts reports the choice. */
+    /* conversion tuning (bytes are powers of two) */
+    int32_t block_bytes;           /* largest block of the element-wide LDS kernels */
+    int32_t pref_bytes;            /* size small tiles are bundled up to */
+    int32_t elem_threads_log2;     /* threads per workgroup of the element-wide LDS kernel: 6 (one wave), 8, 9 or 10 */
+    int32_t vec_block_bytes;       /* largest block of the 128-bit LDS kernel */
+    int32_t vec_threads;           /* its threads per workgroup: 64, 128 or 256 */
+    int32_t shuffle_block_bytes;   /* block of the register / shuffle kernel: 4096 or 8192 */
+    int32_t inflight_bytes;        /* bytes a CU may have in flight: resident workgroups are capped through their LDS share */
+    int32_t lds_pad_bytes;         /* extra LDS per workgroup of the 256-thread element-wide kernel (lowers occupancy) */
+    int32_t xcd_chunk;             /* consecutive blocks each of the 8 XCDs takes at a time (power of two); 0: natural order */
+    int32_t pull_mode;             /* broadcasting plans: 0 balanced, 1 destination runs first, 2 source runs first */
+    int32_t pull_vec_bits;         /* log2 elements per LDS access of the broadcast kernel (upper bound) */
+    int32_t pull_inflight_bytes;
+    int32_t pull_xcd_chunk;
+    /* gather tuning */
+    int32_t gather_block_bytes;    /* preferred block of the workgroup-staged kernel */
+    int32_t gather_lds_max_bytes;  /* largest block it may stage */
+    int32_t gather_min_run_bytes;  /* shortest contiguous run a staged block may be made of */
+    int32_t gather_phased_max_bytes; /* largest aligned range walked through LDS in chunks */
+    int32_t gather_threads_log2;   /* threads per workgroup of the workgroup-staged kernel: 8, 9 or 10 */
+    int32_t gather_inflight_bytes;
+    int32_t gather_xcd_chunk;
+    int32_t gather_swizzle_always; /* 1: swizzle the staged block even when no move along the axis changes bank bits */
+    int32_t copy_xcd_chunk;        /* ll_copy (process defaults only) */
+    int32_t debug;                 /* 1: planners say on stderr why a strategy did not apply */
+} ll_options;
+
+ll_status ll_options_init(ll_options *opts);
+ll_status ll_options_from_env(ll_options *opts);
+
 /* ---- conversion (paper Sec. 5.4) ------------------------------------------------------- */
 
 typedef enum {
@@ -272,6 +324,9 @@ typedef struct {
  * inverse with free variables zero (Sec. 5.4 rule 2), source tiles hold 2^d and destination
  * tiles 2^d_dst elements. */
 ll_status ll_plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan **out);
+/* The same with explicit options (NULL = the process defaults); the plan keeps what it needs of them. */
+ll_status ll_plan_convert_opts(const ll_layout *src, const ll_layout *dst, int elem_bytes, const ll_options *opts,
+                               ll_plan **out);
 ll_status ll_plan_info(const ll_plan *plan, ll_plan_desc *out);
 ll_status ll_plan_destroy(ll_plan *plan);
 
@@ -330,6 +385,10 @@ ll_status ll_gather_info(const ll_layout *layout, int axis, int elem_bytes, ll_g
 
 ll_status ll_gather(const ll_layout *layout, int axis, int elem_bytes, const void *in_dev,
                     const int32_t *idx_dev, void *out_dev, int64_t ntiles, void *hip_stream);
+/* The same with explicit options (NULL = the process defaults). */
+ll_status ll_gather_info_opts(const ll_layout *layout, int axis, int elem_bytes, const ll_options *opts, ll_gather_desc *out);
+ll_status ll_gather_opts(const ll_layout *layout, int axis, int elem_bytes, const ll_options *opts, const void *in_dev,
+                         const int32_t *idx_dev, void *out_dev, int64_t ntiles, void *hip_stream);
 
 /* ---- misc -------------------------------------------------------------------------------- */
 

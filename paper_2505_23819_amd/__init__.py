@@ -39,7 +39,10 @@ EXPORTED_SYMBOLS = [
     "ll_divide_left_permuted", "ll_contiguity", "ll_layout_identity", "ll_layout_blocked",
     "ll_layout_mfma_accumulator", "ll_layout_mfma_operand", "ll_layout_mma_swizzle", "ll_layout_classify",
     "ll_gather_info", "ll_layout_with_offset", "ll_layout_get_offset", "ll_layout_slice",
+    "ll_options_init", "ll_options_from_env", "ll_plan_convert_opts", "ll_gather_opts", "ll_gather_info_opts",
 ]
+LL_AUTO = -1
+LL_GATHER_SHUFFLE, LL_GATHER_WAVE_STAGED, LL_GATHER_BLOCK_STAGED, LL_GATHER_GLOBAL, LL_GATHER_PHASED = range(5)
 GATHER_KERNEL_NAMES = ["shuffle", "wave_staged", "block_staged", "global", "lds_phased"]
 
 
@@ -47,6 +50,16 @@ class ll_gather_desc(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("axis_reg_bits", ctypes.c_int32), ("axis_lane_bits", ctypes.c_int32),
                 ("axis_wave_bits", ctypes.c_int32), ("paper_rounds", ctypes.c_int32), ("block_bytes", ctypes.c_int32)]
 LL_LAYOUT_SURJECTIVE, LL_LAYOUT_INJECTIVE, LL_LAYOUT_DISTRIBUTED, LL_LAYOUT_MEMORY = 1, 2, 4, 8
+
+
+class ll_options(ctypes.Structure):
+    """Mirror of the C struct: every field an int32, LL_AUTO = the library's choice."""
+    _fields_ = [(name, ctypes.c_int32) for name in (
+        "size", "strategy", "gather_kernel", "block_bytes", "pref_bytes", "elem_threads_log2", "vec_block_bytes",
+        "vec_threads", "shuffle_block_bytes", "inflight_bytes", "lds_pad_bytes", "xcd_chunk", "pull_mode",
+        "pull_vec_bits", "pull_inflight_bytes", "pull_xcd_chunk", "gather_block_bytes", "gather_lds_max_bytes",
+        "gather_min_run_bytes", "gather_phased_max_bytes", "gather_threads_log2", "gather_inflight_bytes",
+        "gather_xcd_chunk", "gather_swizzle_always", "copy_xcd_chunk", "debug")]
 
 
 class ll_in_dim(ctypes.Structure):
@@ -111,6 +124,11 @@ def _load() -> ctypes.CDLL:
     lib.ll_convert.argtypes = [vp, vp, vp, i64, vp]
     lib.ll_gather.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp]
     lib.ll_copy.argtypes = [vp, vp, i64, vp]
+    lib.ll_options_init.argtypes = [P(ll_options)]
+    lib.ll_options_from_env.argtypes = [P(ll_options)]
+    lib.ll_plan_convert_opts.argtypes = [vp, vp, i32, P(ll_options), P(vp)]
+    lib.ll_gather_opts.argtypes = [vp, i32, i32, P(ll_options), vp, vp, vp, i64, vp]
+    lib.ll_gather_info_opts.argtypes = [vp, i32, i32, P(ll_options), P(ll_gather_desc)]
     lib.ll_last_error.restype = ctypes.c_char_p
     lib.ll_last_error.argtypes = []
     for name in EXPORTED_SYMBOLS:
@@ -290,9 +308,30 @@ def ll_layout_mma_swizzle(m_bits: int, n_bits: int, vec: int, per_phase: int, ma
                                             ctypes.byref(h)), h)
 
 
-def ll_gather_info(layout: Layout, axis: int, elem_bytes: int) -> dict:
+def ll_options_init(**fields) -> ll_options:
+    """A new ll_options with every field LL_AUTO, then the given fields set."""
+    o = ll_options()
+    _check(_lib.ll_options_init(ctypes.byref(o)))
+    for k, v in fields.items():
+        if k == "size" or k not in dict(ll_options._fields_):
+            raise LLError(LL_ERR_INVALID_ARG, f"ll_options has no settable field {k!r}")
+        setattr(o, k, int(v))
+    return o
+
+
+def ll_options_from_env() -> ll_options:
+    o = ll_options()
+    _check(_lib.ll_options_from_env(ctypes.byref(o)))
+    return o
+
+
+def _opts(opts):
+    return None if opts is None else ctypes.byref(opts)
+
+
+def ll_gather_info(layout: Layout, axis: int, elem_bytes: int, opts: Optional[ll_options] = None) -> dict:
     d = ll_gather_desc()
-    _check(_lib.ll_gather_info(layout._h, int(axis), int(elem_bytes), ctypes.byref(d)))
+    _check(_lib.ll_gather_info_opts(layout._h, int(axis), int(elem_bytes), _opts(opts), ctypes.byref(d)))
     out = {name: getattr(d, name) for name, _ in ll_gather_desc._fields_}
     out["kernel_name"] = GATHER_KERNEL_NAMES[d.kernel]
     return out
@@ -326,10 +365,16 @@ def ll_invert(layout: Layout) -> Layout:
     return Layout(h.value)
 
 
-def ll_plan_convert(src: Layout, dst: Layout, elem_bytes: int) -> Plan:
+def ll_plan_convert(src: Layout, dst: Layout, elem_bytes: int, opts: Optional[ll_options] = None) -> Plan:
     h = ctypes.c_void_p()
-    _check(_lib.ll_plan_convert(src._h, dst._h, int(elem_bytes), ctypes.byref(h)))
+    if opts is None:
+        _check(_lib.ll_plan_convert(src._h, dst._h, int(elem_bytes), ctypes.byref(h)))
+    else:
+        _check(_lib.ll_plan_convert_opts(src._h, dst._h, int(elem_bytes), ctypes.byref(opts), ctypes.byref(h)))
     return Plan(h.value)
+
+
+ll_plan_convert_opts = ll_plan_convert
 
 
 def ll_plan_info(plan: Plan) -> dict:
@@ -396,12 +441,21 @@ def ll_convert(plan: Plan, src, dst, ntiles: int, stream=None) -> None:
                            _stream(stream)))
 
 
-def ll_gather(layout: Layout, axis: int, elem_bytes: int, inp, idx, out, ntiles: int, stream=None) -> None:
+def ll_gather(layout: Layout, axis: int, elem_bytes: int, inp, idx, out, ntiles: int, stream=None,
+              opts: Optional[ll_options] = None) -> None:
     n = max(0, int(ntiles)) << layout.d_in
     if hasattr(idx, "element_size") and idx.element_size() != 4:
         raise LLError(LL_ERR_INVALID_ARG, "idx must hold 32-bit integers")
-    _check(_lib.ll_gather(layout._h, int(axis), int(elem_bytes), _ptr(inp, n * int(elem_bytes), "in"), _ptr(idx, n * 4, "idx"),
-                          _ptr(out, n * int(elem_bytes), "out"), int(ntiles), _stream(stream)))
+    if opts is None:
+        _check(_lib.ll_gather(layout._h, int(axis), int(elem_bytes), _ptr(inp, n * int(elem_bytes), "in"), _ptr(idx, n * 4, "idx"),
+                              _ptr(out, n * int(elem_bytes), "out"), int(ntiles), _stream(stream)))
+    else:
+        _check(_lib.ll_gather_opts(layout._h, int(axis), int(elem_bytes), ctypes.byref(opts), _ptr(inp, n * int(elem_bytes), "in"),
+                                   _ptr(idx, n * 4, "idx"), _ptr(out, n * int(elem_bytes), "out"), int(ntiles), _stream(stream)))
+
+
+ll_gather_opts = ll_gather
+ll_gather_info_opts = ll_gather_info
 
 
 def ll_copy(src, dst, nbytes: int, stream=None) -> None:

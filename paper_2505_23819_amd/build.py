@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libll355.so")
-SOURCES = ["f2.cpp", "plan.cpp", "plan_vec.cpp", "plan_pull.cpp", "plan_tr.cpp", "algebra.cpp", "families.cpp", "run.cpp", "capi.cpp", "kernels.hip"]
+SOURCES = ["f2.cpp", "plan.cpp", "plan_vec.cpp", "plan_pull.cpp", "plan_tr.cpp", "algebra.cpp", "families.cpp", "options.cpp", "run.cpp", "capi.cpp", "kernels.hip"]
 HEADERS = ["f2.hpp", "layout.hpp", "plan.hpp", "kernels.hpp", os.path.join("..", "..", "include", "ll.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -266,12 +266,18 @@ ll_status ll_invert(const ll_layout *layout, ll_layout **out)
 
 ll_status ll_plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan **out)
 {
+    return ll_plan_convert_opts(src, dst, elem_bytes, nullptr, out);
+}
+
+ll_status ll_plan_convert_opts(const ll_layout *src, const ll_layout *dst, int elem_bytes, const ll_options *opts, ll_plan **out)
+{
     try {
         if (!out) return fail(LL_ERR_INVALID_ARG, "out is null");
         *out = nullptr;
         if (!src || !dst) return fail(LL_ERR_INVALID_ARG, "null layout");
         ll_plan *p = new (std::nothrow) ll_plan();
         if (!p) return fail(LL_ERR_INVALID_ARG, "out of host memory");
+        p->opts = ll::resolve_options(opts);
         ll_status st = ll::plan_convert(src, dst, elem_bytes, p);
         if (st != LL_OK) {
             delete p;
@@ -333,6 +339,12 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
 ll_status ll_gather(const ll_layout *layout, int axis, int elem_bytes, const void *in_dev, const int32_t *idx_dev,
                     void *out_dev, int64_t ntiles, void *hip_stream)
 {
+    return ll_gather_opts(layout, axis, elem_bytes, nullptr, in_dev, idx_dev, out_dev, ntiles, hip_stream);
+}
+
+ll_status ll_gather_opts(const ll_layout *layout, int axis, int elem_bytes, const ll_options *opts, const void *in_dev,
+                         const int32_t *idx_dev, void *out_dev, int64_t ntiles, void *hip_stream)
+{
     try {
         if (!layout) return fail(LL_ERR_INVALID_ARG, "layout is null");
         if (ntiles < 0) return fail(LL_ERR_INVALID_ARG, "ntiles is negative");
@@ -340,8 +352,9 @@ ll_status ll_gather(const ll_layout *layout, int axis, int elem_bytes, const voi
             return fail(LL_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8 (got %d)", elem_bytes);
         if (axis < 0 || axis >= layout->n_out) return fail(LL_ERR_INVALID_ARG, "axis %d is not an output dim", axis);
         // the layout is validated even when there is nothing to move
-        ll_status st = ll::run_gather(layout, axis, elem_bytes, in_dev, idx_dev, out_dev, ntiles, hip_stream);
-        return st;
+        if (!opts) return ll::run_gather(layout, axis, elem_bytes, nullptr, in_dev, idx_dev, out_dev, ntiles, hip_stream);
+        const ll_options full = ll::resolve_options(opts);
+        return ll::run_gather(layout, axis, elem_bytes, &full, in_dev, idx_dev, out_dev, ntiles, hip_stream);
     } catch (...) {   // nothing may propagate across the C ABI
         return ll::fail(LL_ERR_INVALID_ARG, "ll_gather: out of host memory");
     }
@@ -349,9 +362,16 @@ ll_status ll_gather(const ll_layout *layout, int axis, int elem_bytes, const voi
 
 ll_status ll_gather_info(const ll_layout *layout, int axis, int elem_bytes, ll_gather_desc *out)
 {
+    return ll_gather_info_opts(layout, axis, elem_bytes, nullptr, out);
+}
+
+ll_status ll_gather_info_opts(const ll_layout *layout, int axis, int elem_bytes, const ll_options *opts, ll_gather_desc *out)
+{
     try {
         if (!layout || !out) return fail(LL_ERR_INVALID_ARG, "null argument");
-        return ll::describe_gather(layout, axis, elem_bytes, out);
+        if (!opts) return ll::describe_gather(layout, axis, elem_bytes, nullptr, out);
+        const ll_options full = ll::resolve_options(opts);
+        return ll::describe_gather(layout, axis, elem_bytes, &full, out);
     } catch (...) {   // nothing may propagate across the C ABI
         return ll::fail(LL_ERR_INVALID_ARG, "ll_gather_info: out of host memory");
     }
@@ -366,7 +386,7 @@ ll_status ll_copy(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_s
         if (misaligned(src_dev) || misaligned(dst_dev)) return fail(LL_ERR_INVALID_ARG, "device buffers must be 16-byte aligned");
         const char *ps = static_cast<const char *>(src_dev), *pd = static_cast<const char *>(dst_dev);
         if (ps < pd + bytes && pd < ps + bytes) return fail(LL_ERR_INVALID_ARG, "source and destination buffers overlap");
-        return ll::launch_copy(src_dev, dst_dev, bytes, hip_stream);
+        return ll::launch_copy(src_dev, dst_dev, bytes, ll::copy_xcd_chunk_bits(ll::process_options()), hip_stream);
     } catch (...) {   // nothing may propagate across the C ABI
         return ll::fail(LL_ERR_INVALID_ARG, "ll_copy: out of host memory");
     }

@@ -1,6 +1,7 @@
 // HIP kernels for gfx950 (CDNA4, wave64).  Pure data movement: 16-byte global loads and stores,
 // LDS staging or cross-lane shuffles in between, no MFMA.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <type_traits>
 
 #include <cstdlib>
@@ -87,29 +88,6 @@ static __device__ __forceinline__ long long block_of_workgroup(long long wg, lon
     return (wg - in) + ((long long)(in & 7u) << xcd_chunk_bits) + (in >> 3);
 }
 
-// Measured on MI355X: when a tile group is at most 128 KiB (so that consecutive blocks walk through
-// contiguous memory), letting each XCD take 128 KiB worth of consecutive blocks is 1-6 % faster than
-// the natural round robin (config 2: 6.02 -> 6.43 TB/s, config 3: 6.59 -> 6.66); when the blocks of a
-// large tile are scattered cosets (config 4) it is 2 % slower, so the natural order stays.
-int xcd_chunk_bits_for(long long group_bytes, long long block_bytes)
-{
-    const char *env = getenv("LL_XCD_CHUNK");                 // experiment knob: blocks (power of two), 0 = off
-    if (env) {
-        const int v = atoi(env);
-        return v > 0 ? 31 - __builtin_clz((unsigned)v) : -1;
-    }
-    const long long target = 128 * 1024;
-    if (group_bytes > target || block_bytes >= target || block_bytes <= 0) return -1;
-    return 63 - __builtin_clzll((unsigned long long)(target / block_bytes));
-}
-
-static unsigned env_inflight_bytes()
-{
-    const char *v = getenv("LL_INFLIGHT_BYTES");     // experiment knob
-    const long x = v ? atol(v) : 0;
-    return x >= 4096 ? (unsigned)x : 49152u;   // 32 KiB is as good for the register paths, 128-bit LDS staging needs 48 (5.2 vs 6.15 TB/s)
-}
-
 // Launches go through hipLaunchKernel, whose return value is the status of THIS launch.  (The
 // thread's "last error" is shared with every other user of the runtime in the process: an error
 // left behind by someone else's call would otherwise be reported as ours.)
@@ -128,6 +106,21 @@ static void launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes
 static ll_status check_launch(const char *what)
 {
     if (g_launch_status != hipSuccess) return fail(LL_ERR_DEVICE, "%s: %s", what, hipGetErrorString(g_launch_status));
+    return LL_OK;
+}
+
+// A kernel that wants more than 64 KiB of dynamic LDS must be told so once per device
+// (hipFuncSetAttribute); `done` is the per-kernel record of the devices that have been (one bit per
+// device ordinal; ordinals beyond 63 simply set the attribute on every call).
+static ll_status allow_large_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(LL_ERR_DEVICE, "hipGetDevice failed");
+    const uint64_t bit = dev >= 0 && dev < 64 ? 1ull << dev : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return LL_OK;
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    if (bit) done.fetch_or(bit, std::memory_order_release);
     return LL_OK;
 }
 
@@ -151,16 +144,13 @@ __global__ __launch_bounds__(256) void k_copy(const void *__restrict__ src, void
     buf_store16(rd, threadIdx.x * 16, buf_load16(rs, threadIdx.x * 16));
 }
 
-ll_status launch_copy(const void *src, void *dst, long long bytes, void *stream)
+ll_status launch_copy(const void *src, void *dst, long long bytes, int xcd_chunk_bits, void *stream)
 {
     const long long nvec = bytes / 16;
     const long long per = kCopyVec * 256;
     const long long grid = (nvec + per - 1) / per;
     if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "copy of %lld bytes is too large for one launch", bytes);
-    // 1 MiB of consecutive 4 KiB blocks per XCD: 2 % above the natural round robin (6.77 against 6.62 TB/s at 1 GiB)
-    static const int chunk = getenv("LL_COPY_XCD_CHUNK") ? atoi(getenv("LL_COPY_XCD_CHUNK")) : 256;   // experiment knob
-    const int bits = chunk > 1 ? 31 - __builtin_clz((unsigned)chunk) : -1;
-    launch(k_copy, dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(stream), src, dst, nvec, grid, bits);
+    launch(k_copy, dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(stream), src, dst, nvec, grid, xcd_chunk_bits);
     return check_launch("copy kernel launch");
 }
 
@@ -306,13 +296,7 @@ __global__ __launch_bounds__(1 << TB) void k_lds_elem(const LdsElemArgs a)
 template <int W, int NV, int V, int TB>
 static ll_status launch_lds_elem_tb(const LdsElemArgs &a, int lds_bytes, hipStream_t stream)
 {
-    static const int pad = getenv("LL_LDS_PAD") ? atoi(getenv("LL_LDS_PAD")) : 0;   // experiment knob: caps occupancy
-    if (lds_bytes + pad > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lds_elem<W, NV, V, 0, TB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-    }
-    launch((k_lds_elem<W, NV, V, 0, TB>), dim3((unsigned)a.nblocks), dim3(1u << TB), (size_t)(lds_bytes + pad), stream, a);
+    launch((k_lds_elem<W, NV, V, 0, TB>), dim3((unsigned)a.nblocks), dim3(1u << TB), (size_t)lds_bytes, stream, a);
     return check_launch("LDS conversion kernel launch");
 }
 
@@ -320,6 +304,7 @@ template <int W, int NV, int V>
 static ll_status launch_lds_elem_t(const LdsElemArgs &a, int lds_bytes, hipStream_t stream)
 {
     switch (a.thread_bits) {
+    case 6: if constexpr (NV == 4) return launch_lds_elem_tb<W, NV, V, 6>(a, lds_bytes, stream); break;   // one wave, a 4 KiB block
     case 8: return launch_lds_elem_tb<W, NV, V, 8>(a, lds_bytes, stream);
     case 9: if constexpr (NV <= 4) return launch_lds_elem_tb<W, NV, V, 9>(a, lds_bytes, stream); break;
     case 10: if constexpr (NV <= 4) return launch_lds_elem_tb<W, NV, V, 10>(a, lds_bytes, stream); break;
@@ -355,8 +340,8 @@ static ll_status launch_lds_elem_n(const LdsElemArgs &a, int nvec, int v, int ld
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads, int lds_bytes,
                           void *stream)
 {
-    if (threads != (1 << a.thread_bits) || a.thread_bits < 8 || a.thread_bits > 10)
-        return fail(LL_ERR_UNSUPPORTED, "LDS kernel runs 256, 512 or 1024 threads per workgroup");
+    if (threads != (1 << a.thread_bits) || (a.thread_bits != 6 && (a.thread_bits < 8 || a.thread_bits > 10)))
+        return fail(LL_ERR_UNSUPPORTED, "LDS kernel runs 64, 256, 512 or 1024 threads per workgroup");
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     if (lds_bytes <= 0 || lds_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "LDS block of %d bytes", lds_bytes);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -567,17 +552,10 @@ static ll_status launch_vec_t(const VecArgs &a, int threads, int lds_bytes, hipS
     if constexpr (TPOSE != kTposeNone && NVB < VS) {
         return fail(LL_ERR_UNSUPPORTED, "internal: transposing kernel needs 2^%d vectors per thread", VS);
     } else {
-        // Occupancy cap: a plain copy on this chip peaks with roughly 32-64 KiB in flight per CU and
-        // loses bandwidth beyond that, so workgroups are kept to (in-flight budget / block bytes) per
-        // CU by asking for a matching share of the 160 KiB LDS.
-        static const unsigned budget = env_inflight_bytes();
-        const unsigned block_bytes = (unsigned)threads * (16u << NVB);
-        const unsigned per_cu = budget / block_bytes > 1 ? budget / block_bytes : 1;
-        unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
-        if (alloc > 64u * 1024u) alloc = 64u * 1024u;
-        if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
+        // lds_bytes carries the occupancy cap (the planner asks for a share of the 160 KiB LDS that
+        // admits in-flight budget / block bytes workgroups per CU)
         launch((k_vec<W, NVB, TPOSE, XCHG>), dim3((unsigned)a.nblocks), dim3((unsigned)threads),
-                           (size_t)alloc, stream, a);
+                           (size_t)lds_bytes, stream, a);
         return check_launch("vector conversion kernel launch");
     }
 }
@@ -711,15 +689,6 @@ template <int W, int V>
 static ll_status launch_pull_wv(const PullArgs &a, int src_iters, int lds_bytes, hipStream_t stream)
 {
     const dim3 grid((unsigned)a.nblocks), block(256);
-    // Occupancy cap through the LDS allocation (see launch_vec_t): bytes a workgroup stores.
-    static const unsigned budget = getenv("LL_PULL_INFLIGHT_BYTES") ? (unsigned)atol(getenv("LL_PULL_INFLIGHT_BYTES")) : 0u;
-    if (budget) {
-        const unsigned wg_bytes = 256u * 16u * (unsigned)a.dst_iters;
-        const unsigned per_cu = budget / wg_bytes > 1 ? budget / wg_bytes : 1;
-        unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
-        if (alloc > 64u * 1024u) alloc = 64u * 1024u;
-        if (alloc > (unsigned)lds_bytes) lds_bytes = (int)alloc;
-    }
     switch (src_iters) {
     case 1: launch((k_pull<W, 1, V>), grid, block, (size_t)lds_bytes, stream, a); break;
     case 2: launch((k_pull<W, 2, V>), grid, block, (size_t)lds_bytes, stream, a); break;
@@ -991,7 +960,7 @@ __global__ __launch_bounds__(256) void k_gather_staged(const GatherArgs a)
 }
 
 template <int W, int NREG>
-static ll_status launch_gather_staged_t(const GatherArgs &a, hipStream_t stream)
+static ll_status launch_gather_staged_t(const GatherArgs &a, int lds_alloc, hipStream_t stream)
 {
     constexpr int PL = (1 << NREG) * W;
     if constexpr (PL < 16 || PL > 256 || (1 << NREG) < 4) {
@@ -1000,13 +969,9 @@ static ll_status launch_gather_staged_t(const GatherArgs &a, hipStream_t stream)
         const long long grid = (a.nchunks + 3) / 4;
         if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", grid);
         constexpr int lds_bytes = 4 * 64 * PL;
-        // Occupancy cap (see launch_vec_t): a workgroup has 4 chunks of `in` and `idx` in flight.
-        static const unsigned budget = getenv("LL_GATHER_INFLIGHT_BYTES") ? (unsigned)atol(getenv("LL_GATHER_INFLIGHT_BYTES")) : 49152u;
-        constexpr unsigned wg_bytes = 4u * 64u * (PL + 4u * (1u << NREG));
-        const unsigned per_cu = budget / wg_bytes > 1 ? budget / wg_bytes : 1;
-        unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
-        if (alloc > 64u * 1024u) alloc = 64u * 1024u;
-        if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
+        // lds_alloc carries the occupancy cap (a workgroup has 4 chunks of `in` and `idx` in flight)
+        const unsigned alloc = lds_alloc > lds_bytes ? (unsigned)lds_alloc : (unsigned)lds_bytes;
+        if (alloc > 64u * 1024u) return fail(LL_ERR_INVALID_ARG, "internal: staged gather asked for %u bytes of LDS", alloc);
         launch((k_gather_staged<W, NREG>), dim3((unsigned)grid), dim3(256), alloc, stream, a);
         return check_launch("gather kernel launch");
     }
@@ -1026,15 +991,15 @@ static ll_status launch_gather_t(const GatherArgs &a, hipStream_t stream)
 }
 
 template <int W>
-static ll_status launch_gather_w(const GatherArgs &a, hipStream_t stream)
+static ll_status launch_gather_w(const GatherArgs &a, int lds_alloc, hipStream_t stream)
 {
     if (a.staged) {
         switch (a.nreg) {
-        case 2: return launch_gather_staged_t<W, 2>(a, stream);
-        case 3: return launch_gather_staged_t<W, 3>(a, stream);
-        case 4: return launch_gather_staged_t<W, 4>(a, stream);
-        case 5: return launch_gather_staged_t<W, 5>(a, stream);
-        case 6: return launch_gather_staged_t<W, 6>(a, stream);
+        case 2: return launch_gather_staged_t<W, 2>(a, lds_alloc, stream);
+        case 3: return launch_gather_staged_t<W, 3>(a, lds_alloc, stream);
+        case 4: return launch_gather_staged_t<W, 4>(a, lds_alloc, stream);
+        case 5: return launch_gather_staged_t<W, 5>(a, lds_alloc, stream);
+        case 6: return launch_gather_staged_t<W, 6>(a, lds_alloc, stream);
         default: return fail(LL_ERR_UNSUPPORTED, "staged gather needs 2 to 6 register bits (got %d)", a.nreg);
         }
     }
@@ -1223,9 +1188,9 @@ static ll_status launch_gather_general_wt(const GatherGenArgs &a, hipStream_t s)
     const int together = vec_passes < unit_passes ? vec_passes : unit_passes;   // both are powers of two
     if (together >= 4) {
         if (lds_bytes > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gather_general<W, 4, TB>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 136 * 1024);
-            if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+            static std::atomic<uint64_t> allowed{0};
+            if (ll_status st = allow_large_lds(reinterpret_cast<const void *>(k_gather_general<W, 4, TB>), 136 * 1024, allowed); st != LL_OK)
+                return st;
         }
         launch((k_gather_general<W, 4, TB>), grid, block, lds_bytes, s, a);
     } else if (together == 2) {
@@ -1242,18 +1207,20 @@ static ll_status launch_gather_general_wt(const GatherGenArgs &a, hipStream_t s)
 // 5.2-5.3 / 5.7-5.96; 64 KiB 5.5-5.6 / 6.0 / 6.05-6.16; 32 KiB 5.8-6.0 / 6.0-6.26 / 6.07-6.35; 16 KiB
 // 5.7-6.2 / 5.9-6.5 / 4.9-5.7; 8 KiB 6.3-6.5 / 4.1-5.7 / - (one-byte elements, whose units are a quarter
 // of the bytes: 5.96 / 6.08 / -).  Interleaved repeats on 512 MiB of data.
-template <int W>
-static ll_status launch_gather_general_w(const GatherGenArgs &a, hipStream_t s)
+int gather_general_thread_bits(long long block_bytes, int elem_bytes)
 {
-    const long long block_bytes = (1ll << a.block_bits) * W;
-    int tb = block_bytes >= 32 * 1024 ? 10 : (block_bytes >= 16 * 1024 || (W == 1 && block_bytes >= 8 * 1024)) ? 9 : 8;
-    if (const char *e = getenv("LL_GATHER_THREADS_LOG2")) tb = atoi(e);      // experiment knob
+    return block_bytes >= 32 * 1024 ? 10 : (block_bytes >= 16 * 1024 || (elem_bytes == 1 && block_bytes >= 8 * 1024)) ? 9 : 8;
+}
+
+template <int W>
+static ll_status launch_gather_general_w(const GatherGenArgs &a, int tb, hipStream_t s)
+{
     if (tb == 10) return launch_gather_general_wt<W, 10>(a, s);
     if (tb == 9) return launch_gather_general_wt<W, 9>(a, s);
     return launch_gather_general_wt<W, 8>(a, s);
 }
 
-ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *stream)
+ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thread_bits, void *stream)
 {
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     const long long block_bytes = (1ll << a.block_bits) * elem_bytes;
@@ -1262,10 +1229,10 @@ ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *st
     if (a.block_bits > 31 || a.coset_bits < 0 || a.coset_bits > kMaxCosetBits) return fail(LL_ERR_INVALID_ARG, "internal: gather block geometry");
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {
-    case 1: return launch_gather_general_w<1>(a, s);
-    case 2: return launch_gather_general_w<2>(a, s);
-    case 4: return launch_gather_general_w<4>(a, s);
-    case 8: return launch_gather_general_w<8>(a, s);
+    case 1: return launch_gather_general_w<1>(a, thread_bits, s);
+    case 2: return launch_gather_general_w<2>(a, thread_bits, s);
+    case 4: return launch_gather_general_w<4>(a, thread_bits, s);
+    case 8: return launch_gather_general_w<8>(a, thread_bits, s);
     default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
     }
 }
@@ -1548,10 +1515,12 @@ static ll_status launch_gather_phased_w(const GatherGenArgs &a, hipStream_t s)
 {
     const size_t lds_bytes = (size_t)kPhasedChunkBytes + 16 + 6 * 32 * sizeof(uint32_t);
     const bool field = a.field_shift >= 0;
-    hipError_t e = hipFuncSetAttribute(field ? reinterpret_cast<const void *>(k_gather_phased<W, true>)
+    static std::atomic<uint64_t> allowed_field{0}, allowed_table{0};
+    if (ll_status st = allow_large_lds(field ? reinterpret_cast<const void *>(k_gather_phased<W, true>)
                                              : reinterpret_cast<const void *>(k_gather_phased<W, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return fail(LL_ERR_DEVICE, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+                                       (int)lds_bytes, field ? allowed_field : allowed_table);
+        st != LL_OK)
+        return st;
     const dim3 grid((unsigned)a.nblocks), block(1u << kPhasedThreadBits);
     if (field)
         launch((k_gather_phased<W, true>), grid, block, lds_bytes, s, a);
@@ -1580,14 +1549,14 @@ ll_status launch_gather_phased(const GatherGenArgs &a, int elem_bytes, void *str
     }
 }
 
-ll_status launch_gather(const GatherArgs &a, int elem_bytes, void *stream)
+ll_status launch_gather(const GatherArgs &a, int elem_bytes, int lds_alloc, void *stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {
-    case 1: return launch_gather_w<1>(a, s);
-    case 2: return launch_gather_w<2>(a, s);
-    case 4: return launch_gather_w<4>(a, s);
-    case 8: return launch_gather_w<8>(a, s);
+    case 1: return launch_gather_w<1>(a, lds_alloc, s);
+    case 2: return launch_gather_w<2>(a, lds_alloc, s);
+    case 4: return launch_gather_w<4>(a, lds_alloc, s);
+    case 8: return launch_gather_w<8>(a, lds_alloc, s);
     default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
     }
 }

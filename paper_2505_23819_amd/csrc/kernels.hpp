@@ -149,8 +149,8 @@ struct GatherGenArgs {
                                          // staged kernel: >= 0 when the LDS byte offset of a move is (coordinate difference) << field_shift
 };
 
-int xcd_chunk_bits_for(long long group_bytes, long long block_bytes);
-ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, void *stream);
+int gather_general_thread_bits(long long block_bytes, int elem_bytes);   // log2 threads measured best for a staged block
+ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thread_bits, void *stream);
 int gather_global_chunk_bits(int elem_bytes);       // log2 elements one workgroup of the global gather takes
 ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *stream);
 int gather_phased_chunk_bits(int elem_bytes);       // log2 elements one workgroup of the phased gather takes
@@ -162,7 +162,7 @@ ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose,
                      void *stream);
 ll_status launch_lds_tr(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_bytes, void *stream);
 ll_status launch_pull(const PullArgs &a, int elem_bytes, int src_iters, int vec_bits, int lds_bytes, void *stream);
-ll_status launch_gather(const GatherArgs &a, int elem_bytes, void *stream);
-ll_status launch_copy(const void *src, void *dst, long long bytes, void *stream);
+ll_status launch_gather(const GatherArgs &a, int elem_bytes, int lds_alloc, void *stream);
+ll_status launch_copy(const void *src, void *dst, long long bytes, int xcd_chunk_bits, void *stream);
 
 }  // namespace ll

@@ -51,6 +51,19 @@ struct ll_layout {
 
 namespace ll {
 
+// ll_options (options.cpp): every field LL_AUTO; LL_AUTO plus the LL_* environment overrides; the
+// process defaults (the environment read once); a caller's struct made complete (NULL = process
+// defaults); field-wise comparison; and readers for byte sizes (powers of two) and XCD chunk
+// counts (returned as log2, -1 = natural order).
+void options_init(ll_options *o);
+void options_from_env(ll_options *o);
+const ll_options &process_options();
+ll_options resolve_options(const ll_options *given);
+bool same_options(const ll_options &a, const ll_options &b);
+unsigned opt_bytes(int32_t v, unsigned fallback);
+int opt_chunk_bits(int32_t v, int fallback_bits);
+inline int opt_or(int32_t v, int fallback) { return v == LL_AUTO ? fallback : v; }
+
 // thread-local error text behind ll_last_error()
 ll_status fail(ll_status code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 const char *last_error();

@@ -13,11 +13,19 @@ namespace ll {
 
 static int ilog2(unsigned x) { return 31 - __builtin_clz(x); }
 
-unsigned env_bytes(const char *name, unsigned fallback)
+int lds_alloc_for(unsigned block_bytes, unsigned budget, int lds_bytes)
 {
-    const char *v = getenv(name);
-    const long x = v ? atol(v) : 0;
-    return (x >= 16 && x <= (1 << 20) && (x & (x - 1)) == 0) ? (unsigned)x : fallback;
+    const unsigned per_cu = budget / block_bytes > 1 ? budget / block_bytes : 1;
+    unsigned alloc = (160u * 1024u / per_cu) & ~1023u;
+    if (alloc > 64u * 1024u) alloc = 64u * 1024u;
+    if (alloc < (unsigned)lds_bytes) alloc = (unsigned)lds_bytes;
+    return (int)alloc;
+}
+
+int xcd_chunk_bits_for(long long target_bytes, long long block_bytes)
+{
+    if (block_bytes <= 0 || block_bytes >= target_bytes) return -1;
+    return 63 - __builtin_clzll((unsigned long long)(target_bytes / block_bytes));
 }
 
 int wave_access_lines(const uint32_t *lane_table, int w)
@@ -330,17 +338,21 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     ll_plan_desc &desc = plan->desc;
     LdsElemArgs &a = plan->lds_elem;
     const int vs = ilog2(16u / (unsigned)w);          // elements per 16-byte vector (log2)
+    const ll_options &opt = plan->opts;
     int tb = 8;                                       // 256 threads
-    if (const char *e = getenv("LL_ELEM_THREADS_LOG2")) tb = std::min(10, std::max(8, atoi(e)));     // experiment knob
-    // experiment knobs (bytes, powers of two): largest staged block, and the size small tiles are bundled to
+    if (opt.elem_threads_log2 != LL_AUTO) tb = std::min(10, std::max(6, (int)opt.elem_threads_log2));
+    if (tb == 7) tb = 8;
+    // Largest staged block, and the size small tiles are bundled to (bytes, powers of two).
     // Small blocks measured best on MI355X (more, shorter-lived workgroups keep about 32-64 KiB in
     // flight per CU, which is where a plain copy also peaks).
-    const unsigned max_block = env_bytes("LL_BLOCK_BYTES", 8192u);
-    const unsigned pref_block = env_bytes("LL_PREF_BYTES", 8192u);
+    const unsigned max_block = opt_bytes(opt.block_bytes, 8192u);
+    const unsigned pref_block = opt_bytes(opt.pref_bytes, 8192u);
 
     BlockGeom geom;
-    if (ll_status st = build_blocks(p, d, w, vs + tb, max_block, pref_block, &geom); st != LL_OK) return st;
-    if (geom.n == vs + tb && (w == 1 || d >= 17) && !getenv("LL_BLOCK_BYTES")) {
+    const int min_bits = vs + std::max(tb, 8);        // a wave-sized workgroup takes at least four vectors per lane
+    const bool tb_auto = opt.elem_threads_log2 == LL_AUTO;
+    if (ll_status st = build_blocks(p, d, w, min_bits, max_block, pref_block, &geom); st != LL_OK) return st;
+    if (geom.n == min_bits && (w == 1 || d >= 17) && opt.block_bytes == LL_AUTO) {
         // One vector per thread and a tile cut into many such blocks: the runs are as short as the
         // limit allows (4-byte elements: 128 bytes on each side, 32 of them scattered over the tile).
         // Runs grow on both sides at once, so the next size is four times the block.  Measured with
@@ -353,7 +365,7 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
         // Byte elements pay one LDS instruction per byte, and a workgroup that holds only 4 KiB
         // cannot hide that: 2^14..2^20 4.2-5.8 against 6.1-6.5 at every tile size.
         BlockGeom wider;
-        if (build_blocks(p, d, w, vs + tb, 2 * max_block, pref_block, &wider) == LL_OK && wider.k > geom.k &&
+        if (build_blocks(p, d, w, min_bits, 2 * max_block, pref_block, &wider) == LL_OK && wider.k > geom.k &&
             ((unsigned)w << wider.n) <= 2 * max_block)
             geom = wider;
     }
@@ -361,9 +373,17 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     const mat &pext = geom.pext, &us = geom.us, &ud = geom.ud, &q = geom.q, &qinv = geom.qinv, &comp = geom.comp;
     const int nco = (int)comp.size();
     const vec low_mask = (vec(1) << k) - 1;
+    // A 4 KiB block is given to ONE wave (four vectors per lane) instead of four: the wave goes on as
+    // soon as its own loads have landed, no workgroup barrier holds the CU slot until the slowest of
+    // four waves is ready.  Measured on MI355X, random XOR layouts of 4-byte elements, 1 GiB each way:
+    // config 4 6.2-6.4 -> 6.7 TB/s, tiles of 2^12 / 2^14 elements 6.45 -> 6.6; 8-byte elements (blocks of
+    // 2^9) equal within 1 %.  Larger blocks lose that way (16 vectors per lane and two waves per CU
+    // leave the LDS latency exposed: 4.0-5.3 TB/s), so they keep 256 threads.
+    if (tb_auto && ((unsigned)w << n) == 4096u) tb = 6;
+    if (tb == 6 && ((unsigned)w << n) != 4096u) tb = 8;               // the one-wave kernel exists for 4 KiB blocks only
     const int nvec_bits = n - vs - tb;
     // what the launcher instantiates: up to 8 vectors per thread with 256 threads, up to 4 with more
-    if ((1 << nvec_bits) > (tb == 8 ? 8 : 4))
+    if (nvec_bits < 0 || (1 << nvec_bits) > (tb == 8 ? 8 : 4))
         return fail(LL_ERR_UNSUPPORTED, "staged block of %d bytes needs %d vectors per thread", (1 << n) * w, 1 << nvec_bits);
 
     // common contiguous run: Q e_b = e_b for b < v
@@ -521,26 +541,87 @@ static void paper_shuffle_schedule(const ll_layout *a, const ll_layout *b, int w
 // the in-register transpose applies and element-wide accesses otherwise (always possible).
 static ll_status choose_strategy(const mat &p, int d, int elem_bytes, ll_plan *plan)
 {
-    const char *force = getenv("LL_FORCE_STRATEGY");
+    const int force = plan->opts.strategy;
     bool applied = false;
-    // Transposing LDS loads (1- and 2-byte elements): on request only (LL_FORCE_STRATEGY=6).  They
+    // Transposing LDS loads (1- and 2-byte elements): on request only (ll_options.strategy).  They
     // cut the LDS instructions 8-fold, but the instruction makes adjacent lanes take adjacent source
     // elements, which in a transpose are different destination rows: stores of 16-byte pieces at
     // row pitch.  Measured 5.8-6.0 TB/s against 6.3 for byte-wide LDS accesses with contiguous
     // stores on the 128 x 128 transpose of 1-byte elements; the conversion is HBM bound either way.
-    if (force && atoi(force) == LL_STRATEGY_LDS_TR) {
+    if (force == LL_STRATEGY_LDS_TR) {
         if (ll_status st = plan_lds_tr(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
         if (applied) return LL_OK;
     }
-    if (!(force && atoi(force) >= LL_STRATEGY_LDS_ELEM)) {
+    if (!(force >= LL_STRATEGY_LDS_ELEM)) {
         if (ll_status st = plan_wave_shuffle(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
         if (applied) return LL_OK;
     }
-    if (!(force && atoi(force) == LL_STRATEGY_LDS_ELEM)) {
+    if (force != LL_STRATEGY_LDS_ELEM) {
         if (ll_status st = plan_lds_vec(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
         if (applied) return LL_OK;
     }
     return plan_lds_elem(p, d, elem_bytes, plan);
+}
+
+// What a launch needs besides the tables: the XCD-aware block order and the LDS allocation that
+// caps the workgroups per CU.  Fixed here so that ll_convert does no lookups of its own.
+//
+// XCD-aware order.  Workgroups are dealt to the 8 XCDs round robin; renumbering blocks so that each
+// XCD works through a run of consecutive blocks at a time (blocks that touch neighbouring lines then
+// share an L2 and reach memory close in time) measured 1-6 % faster than the natural order with
+// 128 KiB per XCD for the one-wave kernels (config 2: 6.02 -> 6.43 TB/s, config 3: 6.59 -> 6.66,
+// config 4 with one wave per block: 6.16 -> 6.7).
+//
+// In-flight cap.  A plain copy on this chip peaks with roughly 32-48 KiB in flight per CU and loses
+// bandwidth beyond that, so workgroups are kept to (budget / block bytes) per CU by asking for a
+// matching share of the 160 KiB LDS.  Budget: 48 KiB for the register / shuffle / 128-bit LDS
+// kernels (interleaved A/B, TB/s at 32 / 40 / 48 KiB: config 2 6.44 / 6.44 / 6.44, with the destination
+// flipped 5.85 / 5.85 / 6.42, config 3 6.60 / 6.59 / 6.49, config 1's layouts on 32768 tiles 6.09 / 6.46 /
+// 6.63, 128-bit LDS staging of config 2 - / 5.24 / 6.15: the more work a wave does between its loads
+// and its stores, the more waves it takes to keep the same bytes in flight), 44 KiB (11 waves per
+// CU) for the one-wave element-wide kernel (config 4: 9-11 per CU 6.70-6.74, 12: 6.65, 16: 6.53).
+static void set_launch_params(ll_plan *plan)
+{
+    const ll_plan_desc &desc = plan->desc;
+    const ll_options &opt = plan->opts;
+    const long long block_bytes = (long long)desc.elem_bytes << desc.block_bits;
+    const long long group_bytes = (long long)desc.elem_bytes << (desc.d + desc.group_bits);
+    const long long kXcdTarget = 128 * 1024;
+    switch (desc.strategy) {
+    case LL_STRATEGY_LDS_ELEM:
+    case LL_STRATEGY_LDS_TR: {
+        const bool one_wave = desc.threads == 64;
+        const int chunk = (one_wave || group_bytes <= kXcdTarget) ? xcd_chunk_bits_for(kXcdTarget, block_bytes) : -1;
+        plan->lds_elem.xcd_chunk = opt_chunk_bits(opt.xcd_chunk, chunk);
+        int alloc = desc.lds_bytes;
+        if (one_wave || opt.inflight_bytes != LL_AUTO)
+            alloc = lds_alloc_for((unsigned)block_bytes, (unsigned)opt_or(opt.inflight_bytes, 45056), alloc);
+        if (opt.lds_pad_bytes > 0) alloc = std::min(64 * 1024, alloc + opt.lds_pad_bytes);
+        plan->lds_alloc = alloc;
+        break;
+    }
+    case LL_STRATEGY_REG_PERMUTE:
+    case LL_STRATEGY_WAVE_SHUFFLE:
+    case LL_STRATEGY_LDS_VEC: {
+        const int chunk = group_bytes <= kXcdTarget ? xcd_chunk_bits_for(kXcdTarget, block_bytes) : -1;
+        plan->vec.xcd_chunk = opt_chunk_bits(opt.xcd_chunk, chunk);
+        plan->lds_alloc = lds_alloc_for((unsigned)desc.threads * (16u << plan->vec_nvec_bits), (unsigned)opt_or(opt.inflight_bytes, 49152),
+                                        desc.lds_bytes);
+        break;
+    }
+    case LL_STRATEGY_LDS_PULL: {
+        // measured best with 256 KiB of consecutive destination blocks per XCD when writes dominate
+        // (expand 16x: 5.95 -> 6.5 TB/s), 512 KiB otherwise
+        const long long target = (desc.d_dst > desc.d ? 256 : 512) * 1024;
+        plan->pull.xcd_chunk = opt_chunk_bits(opt.pull_xcd_chunk, xcd_chunk_bits_for(target, block_bytes));
+        plan->lds_alloc = desc.lds_bytes;
+        if (opt.pull_inflight_bytes != LL_AUTO)
+            plan->lds_alloc = lds_alloc_for(256u * 16u * (unsigned)plan->pull.dst_iters, (unsigned)opt.pull_inflight_bytes, desc.lds_bytes);
+        break;
+    }
+    default:
+        break;
+    }
 }
 
 ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan)
@@ -564,7 +645,9 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
         // broadcasting (Sec. 5.1, Sec. 5.4 rule 2): destination units pull from canonical source units
         std::memset(&plan->desc, 0, sizeof(plan->desc));
         plan->desc.elem_bytes = elem_bytes;
-        return plan_pull(src, dst, elem_bytes, plan);
+        if (ll_status st = plan_pull(src, dst, elem_bytes, plan); st != LL_OK) return st;
+        set_launch_params(plan);
+        return LL_OK;
     }
     if (memory_side) {
         if (src->d_in != dst->d_in)
@@ -624,6 +707,7 @@ ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_byte
     }
     plan->lds_elem.dst_xor = (uint32_t)c;      // whichever argument block the strategy uses
     plan->vec.dst_xor = (uint32_t)c;
+    set_launch_params(plan);
     return LL_OK;
 }
 

@@ -48,7 +48,6 @@ struct BlockGeom {
     f2::mat comp;                 // unit vectors enumerating the blocks of a tile group
 };
 ll_status build_blocks(const f2::mat &p, int d, int w, int min_bits, unsigned max_bytes, unsigned pref_bytes, BlockGeom *out);
-unsigned env_bytes(const char *name, unsigned fallback);
 // Distinct 128-byte lines touched by one wave-wide access of 16-byte vectors whose element offsets are
 // XOR combinations of lane_table[0..5] (8 when the 64 vectors are contiguous).
 int wave_access_lines(const uint32_t *lane_table, int w);
@@ -57,6 +56,8 @@ int wave_access_lines(const uint32_t *lane_table, int w);
 
 struct ll_plan {
     ll_plan_desc desc = {};
+    ll_options opts = {};         // the options the plan was made with (complete: no field missing)
+    int lds_alloc = 0;            // dynamic LDS bytes a launch asks for: the block, raised where that caps the workgroups per CU
     int nvec = 0;                 // 16-byte vectors per thread
     ll::LdsElemArgs lds_elem = {};
     ll::VecArgs vec = {};
@@ -75,9 +76,17 @@ ll_status plan_lds_vec(const f2::mat &p, int d, int w, ll_plan *plan, bool *appl
 ll_status plan_lds_tr(const f2::mat &p, int d, int w, ll_plan *plan, bool *applied);
 // Broadcasting layouts (plan_pull.cpp): A, B surjective, possibly not injective.
 ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan);
+// Fills *plan; plan->opts must hold the (complete) options before the call.
 ll_status plan_convert(const ll_layout *src, const ll_layout *dst, int elem_bytes, ll_plan *plan);
 ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long ntiles, void *stream);
-ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gather_desc *out);
-ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *in, const int32_t *idx,
+int copy_xcd_chunk_bits(const ll_options &opt);
+ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, const ll_options *opts, ll_gather_desc *out);
+ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const ll_options *opts, const void *in, const int32_t *idx,
                      void *out, long long ntiles, void *stream);
+// LDS bytes to ask for so that at most budget / block_bytes workgroups (at least one) share a CU's
+// 160 KiB; never less than the workgroup needs, at most 64 KiB.
+int lds_alloc_for(unsigned block_bytes, unsigned budget, int lds_bytes);
+// log2 of the consecutive blocks one XCD takes (-1: natural order) so that it works through
+// `target` bytes at a time.
+int xcd_chunk_bits_for(long long target_bytes, long long block_bytes);
 }  // namespace ll

@@ -210,7 +210,7 @@ static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int
     // LDS access width: 2^v elements where the conversion keeps the low v bits of a slot index in
     // place (Sec. 5.3 "Generalized Vectorization"), element-wide otherwise
     int v = vs;
-    if (const char *e = getenv("LL_PULL_VEC")) v = std::min(vs, std::max(0, atoi(e)));
+    if (plan->opts.pull_vec_bits != LL_AUTO) v = std::min(vs, std::max(0, (int)plan->opts.pull_vec_bits));
     for (int j = 0; j < nd; ++j)
         while (v > 0 && (j < v ? rl[j] != (vec(1) << j) : (rl[j] & ((vec(1) << v) - 1)) != 0)) --v;
     for (vec c : comp)
@@ -305,8 +305,8 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     // runs first, and 16 KiB blocks (four stores in flight per thread measured fastest on MI355X;
     // read-dominated and balanced conversions do best at 8 KiB).
     int mode = B->d_in > A->d_out + 1 ? 1 : 0;
-    if (const char *e = getenv("LL_PULL_MODE")) mode = atoi(e);
-    const unsigned max_block = env_bytes("LL_BLOCK_BYTES", mode == 1 ? 16384u : 8192u);
+    if (plan->opts.pull_mode != LL_AUTO) mode = plan->opts.pull_mode;
+    const unsigned max_block = opt_bytes(plan->opts.block_bytes, mode == 1 ? 16384u : 8192u);
     // A sparse source (few canonical slots per 16-byte vector, as in the slice left by a reduction
     // along the register-fastest dim) needs many vectors per destination element: shrink the block
     // until they fit.  At one vector per thread on the destination side a block needs at most one

@@ -87,7 +87,7 @@ ll_status plan_lds_tr(const mat &p, int d, int w, ll_plan *plan, bool *applied)
     const LdsModel hw;
     const int vs = ilog2t(16u / (unsigned)w), ce = ilog2t(8u / (unsigned)w), tb = 8;
     BlockGeom geom;
-    if (ll_status st = build_blocks(p, d, w, vs + tb, env_bytes("LL_BLOCK_BYTES", 8192u), env_bytes("LL_PREF_BYTES", 8192u), &geom);
+    if (ll_status st = build_blocks(p, d, w, vs + tb, opt_bytes(plan->opts.block_bytes, 8192u), opt_bytes(plan->opts.pref_bytes, 8192u), &geom);
         st != LL_OK)
         return st;
     const int g = geom.g, k = geom.k, n = geom.n;

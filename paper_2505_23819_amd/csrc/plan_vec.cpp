@@ -16,9 +16,10 @@ using f2::vec;
 
 namespace ll {
 
+static thread_local bool g_debug = false;      // ll_options.debug of the plan being made
 static ll_status dbg_na(int where)
 {
-    if (getenv("LL_DEBUG")) fprintf(stderr, "[ll] wave-shuffle plan not applicable (reason %d)\n", where);
+    if (g_debug) fprintf(stderr, "[ll] wave-shuffle plan not applicable (reason %d)\n", where);
     return LL_OK;
 }
 
@@ -156,9 +157,10 @@ static ll_status plan_wave_shuffle_at(const mat &p, int d, int w, unsigned max_b
 ll_status plan_wave_shuffle(const mat &p, int d, int w, ll_plan *plan, bool *applied)
 {
     *applied = false;
+    g_debug = plan->opts.debug == 1;
     if (w != 2 && w != 4 && w != 8) return dbg_na(1);
-    if (getenv("LL_SHUFFLE_BLOCK_BYTES"))      // experiment knob: one fixed block size
-        return plan_wave_shuffle_at(p, d, w, env_bytes("LL_SHUFFLE_BLOCK_BYTES", 4096u), plan, applied);
+    if (plan->opts.shuffle_block_bytes != LL_AUTO)      // one fixed block size
+        return plan_wave_shuffle_at(p, d, w, opt_bytes(plan->opts.shuffle_block_bytes, 4096u), plan, applied);
     ll_plan small = *plan;
     bool small_ok = false;
     if (ll_status st = plan_wave_shuffle_at(p, d, w, 4096u, &small, &small_ok); st != LL_OK) return st;
@@ -384,8 +386,8 @@ ll_status plan_lds_vec(const mat &p, int d, int w, ll_plan *plan, bool *applied)
     if (w != 2 && w != 4 && w != 8) return LL_OK;
     const LdsModel hw;
     const int vs = ilog2u(16u / (unsigned)w);
-    const unsigned max_block = env_bytes("LL_VEC_BLOCK_BYTES", 8192u);
-    int tb = ilog2u(env_bytes("LL_VEC_THREADS", 64u));
+    const unsigned max_block = opt_bytes(plan->opts.vec_block_bytes, 8192u);
+    int tb = ilog2u(opt_bytes(plan->opts.vec_threads, 64u));
     if (tb < 6 || tb > 8) tb = 6;
     BlockGeom g;
     if (build_blocks(p, d, w, 2 * vs + tb, max_block, max_block, &g) != LL_OK) return LL_OK;

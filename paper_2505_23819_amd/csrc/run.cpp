@@ -4,7 +4,6 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
-#include <string>
 #include <vector>
 
 #include "plan.hpp"
@@ -14,12 +13,18 @@ using f2::vec;
 
 namespace ll {
 
+// 1 MiB of consecutive 4 KiB blocks per XCD: 2 % above the natural round robin for the plain copy
+// (6.77 against 6.62 TB/s at 1 GiB)
+int copy_xcd_chunk_bits(const ll_options &opt) { return opt_chunk_bits(opt.copy_xcd_chunk, 8); }
+
+// Everything a launch needs beyond the caller's pointers and tile count is fixed when the plan is
+// made (set_launch_params in plan.cpp): no environment lookups, allocations or attribute calls here.
 ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long ntiles, void *stream)
 {
     const ll_plan_desc &desc = plan->desc;
     switch (desc.strategy) {
     case LL_STRATEGY_COPY:
-        return launch_copy(src, dst, (ntiles << desc.d) * desc.elem_bytes, stream);
+        return launch_copy(src, dst, (ntiles << desc.d) * desc.elem_bytes, copy_xcd_chunk_bits(plan->opts), stream);
     case LL_STRATEGY_LDS_ELEM: {
         LdsElemArgs a = plan->lds_elem;
         a.src = src;
@@ -27,8 +32,7 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.ntiles = ntiles;
         const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
         a.nblocks = groups << a.coset_bits;
-        a.xcd_chunk = xcd_chunk_bits_for((long long)desc.elem_bytes << (desc.d + a.group_bits), (long long)desc.elem_bytes << desc.block_bits);
-        return launch_lds_elem(a, desc.elem_bytes, plan->nvec, desc.lds_vec_bits, desc.threads, desc.lds_bytes, stream);
+        return launch_lds_elem(a, desc.elem_bytes, plan->nvec, desc.lds_vec_bits, desc.threads, plan->lds_alloc, stream);
     }
     case LL_STRATEGY_LDS_TR: {
         LdsElemArgs a = plan->lds_elem;
@@ -37,8 +41,7 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.ntiles = ntiles;
         const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
         a.nblocks = groups << a.coset_bits;
-        a.xcd_chunk = xcd_chunk_bits_for((long long)desc.elem_bytes << (desc.d + a.group_bits), (long long)desc.elem_bytes << desc.block_bits);
-        return launch_lds_tr(a, desc.elem_bytes, plan->nvec, desc.lds_bytes, stream);
+        return launch_lds_tr(a, desc.elem_bytes, plan->nvec, plan->lds_alloc, stream);
     }
     case LL_STRATEGY_REG_PERMUTE:
     case LL_STRATEGY_WAVE_SHUFFLE:
@@ -49,9 +52,8 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.ntiles = ntiles;
         const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
         a.nblocks = groups << a.coset_bits;
-        a.xcd_chunk = xcd_chunk_bits_for((long long)desc.elem_bytes << (desc.d + a.group_bits), (long long)desc.elem_bytes << desc.block_bits);
         return launch_vec(a, desc.elem_bytes, plan->vec_nvec_bits, plan->vec_tpose, plan->vec_xchg, desc.threads,
-                          desc.lds_bytes, stream);
+                          plan->lds_alloc, stream);
     }
     case LL_STRATEGY_LDS_PULL: {
         PullArgs a = plan->pull;
@@ -60,16 +62,7 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.ntiles = ntiles;
         const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
         a.nblocks = groups << a.coset_bits;
-        {
-            // XCD-aware block order (see xcd_chunk_bits_for): measured best with 256 KiB of consecutive
-            // destination blocks per XCD when writes dominate (expand 16x: 5.95 -> 6.5 TB/s), 512 KiB otherwise
-            const char *e = getenv("LL_PULL_XCD_CHUNK");          // experiment knob: blocks (power of two), 0 = off
-            const long long block_bytes = (long long)desc.elem_bytes << desc.block_bits;
-            const long long target = (desc.d_dst > desc.d ? 256 : 512) * 1024;
-            const long long v = e ? atoi(e) : target / block_bytes;
-            a.xcd_chunk = v > 1 ? 63 - __builtin_clzll((unsigned long long)v) : -1;
-        }
-        return launch_pull(a, desc.elem_bytes, plan->pull_src_iters, plan->pull_vec_bits, desc.lds_bytes, stream);
+        return launch_pull(a, desc.elem_bytes, plan->pull_src_iters, plan->pull_vec_bits, plan->lds_alloc, stream);
     }
     default:
         return fail(LL_ERR_UNSUPPORTED, "plan strategy %d has no kernel", desc.strategy);
@@ -83,9 +76,11 @@ struct GatherChoice {
     bool memory = false;               // memory layout: no registers, lanes or waves
     GatherArgs wave = {};              // shuffle / wave-staged kernels
     GatherGenArgs gen = {};            // workgroup-staged kernel
+    int lds_alloc = 0;                 // wave-staged kernel: dynamic LDS to ask for (caps the workgroups per CU)
+    int thread_bits = 8;               // workgroup-staged kernel: log2 threads per workgroup
 };
 
-static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, GatherChoice *c)
+static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, const ll_options &opt, GatherChoice *c)
 {
     // A memory layout (one `offset` input, Sec. 4.3) is a buffer indexed by memory offset: no lanes or
     // waves to shuffle between, every bit counts as a register bit and the staged kernels serve it.
@@ -127,16 +122,16 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     // moves along the axis (differences) do not change
     const uint32_t own_const = (uint32_t)((L->offset >> axis_shift) & ((vec(1) << na) - 1));
 
-    const char *force = getenv("LL_GATHER_GENERAL");
     const bool lane_only = !(touched & ~lane_mask) && nlane == LL_WAVE_LANE_BITS && nreg <= 6 && d - nreg - nlane <= 16 &&
                            na <= 6 && (1 << nreg) * elem_bytes >= 4 && (1 << nreg) * elem_bytes <= 256;
     // Lanes that hold fewer than 16 bytes make the shuffle kernel's global accesses narrow (measured
     // 4.6-5.5 TB/s against 6.4-6.5 for the workgroup-staged kernel), so those layouts take the general
-    // kernel unless LL_GATHER_GENERAL=0 asks for the wave kernels.
+    // kernel unless the options ask for one of the wave kernels.
     // One-byte elements need one shuffle each however many a lane holds (measured 4.8 TB/s with 16 per
     // lane against 5.7-5.9 staged), so they take the general kernel as well.
     const bool narrow = (1 << nreg) * elem_bytes < 16 || elem_bytes == 1;
-    const bool want_general = force ? atoi(force) != 0 : narrow;
+    const bool want_general = opt.gather_kernel == LL_GATHER_BLOCK_STAGED ||
+                              (opt.gather_kernel != LL_GATHER_SHUFFLE && opt.gather_kernel != LL_GATHER_WAVE_STAGED && narrow);
     if (lane_only && !want_general) {
         GatherArgs &a = c->wave;
         std::memset(&a, 0, sizeof(a));
@@ -173,8 +168,12 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         // make every lane's accesses strided, so they are staged through wave-private LDS instead.
         const int row_bytes = (1 << nreg) * elem_bytes;
         a.staged = (row_bytes > 16 && row_bytes <= 256 && nreg >= 2) ? 1 : 0;
-        if (const char *st = getenv("LL_GATHER_STAGED")) a.staged = atoi(st) && row_bytes >= 16 && row_bytes <= 256 && nreg >= 2;
+        if (opt.gather_kernel == LL_GATHER_SHUFFLE) a.staged = 0;
+        if (opt.gather_kernel == LL_GATHER_WAVE_STAGED) a.staged = row_bytes >= 16 && row_bytes <= 256 && nreg >= 2;
         c->kernel = a.staged ? LL_GATHER_WAVE_STAGED : LL_GATHER_SHUFFLE;
+        a.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, -1);
+        // occupancy cap of the wave-staged kernel: a workgroup has 4 chunks of `in` and `idx` in flight
+        c->lds_alloc = lds_alloc_for(4u * 64u * ((unsigned)row_bytes + 4u * (1u << nreg)), (unsigned)opt_or(opt.gather_inflight_bytes, 49152), 0);
         return LL_OK;
     }
 
@@ -194,13 +193,12 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     const int wlog = 31 - __builtin_clz((unsigned)elem_bytes);
     const int top = touched ? 64 - __builtin_clzll((unsigned long long)touched) : 0;
     // gfx950 has 160 KiB of LDS per CU: blocks up to 128 KiB (plus the delta tables) are staged
-    static const long long lds_max = getenv("LL_GATHER_LDS_MAX") ? atoll(getenv("LL_GATHER_LDS_MAX")) : 128 * 1024;   // experiment knob
+    const long long lds_max = opt_or(opt.gather_lds_max_bytes, 128 * 1024);
     const int max_bits = 63 - __builtin_clzll((unsigned long long)std::max(1ll, lds_max / elem_bytes));
     int min_bits = std::max(vs + 8, 10);                               // one 16-byte vector and one unit per thread
     {
         // 8 KiB blocks measured best on MI355X when the axis leaves the choice (4 KiB: -5 %, 32 KiB: -4 %)
-        const char *bb = getenv("LL_GATHER_BLOCK_BYTES");          // experiment knob
-        const int bytes = bb ? atoi(bb) : 8192;
+        const int bytes = opt_or(opt.gather_block_bytes, 8192);
         min_bits = std::max(min_bits, 31 - __builtin_clz((unsigned)std::max(1, bytes / elem_bytes)));
     }
     const int gb = std::max(0, min_bits - d);                          // small tiles are bundled
@@ -228,8 +226,7 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     // XCD-aware order keeps on one L2).  Measured against the memory-direct kernel: worth it only when
     // the aligned range is beyond an XCD's 4 MiB L2 (4096 x 4096 two-byte rows, 32-byte runs: 2.0
     // against 0.51 TB/s; four-byte: 1.44 / 0.68), not below (4096 x 256 eight-byte: 1.44 / 1.71).
-    static const int min_run_env = getenv("LL_GATHER_MIN_RUN") ? atoi(getenv("LL_GATHER_MIN_RUN")) : 0;       // experiment knob (bytes)
-    const int min_run = min_run_env ? min_run_env : (((long long)elem_bytes << top) > (4ll << 20) ? 32 : 64);
+    const int min_run = opt_or(opt.gather_min_run_bytes, ((long long)elem_bytes << top) > (4ll << 20) ? 32 : 64);
     const bool global = n > max_bits || (elem_bytes << cb) < min_run || D + wlog > 31;
     GatherGenArgs &g = c->gen;
     std::memset(&g, 0, sizeof(g));
@@ -238,7 +235,9 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
     g.own_const = own_const;
     g.d = d;
     if (global) {
-        g.block_bits = top;
+        // (a range smaller than a workgroup's share of consecutive elements is widened to it: the
+        // aligned range only grows, and it stays inside the tile)
+        g.block_bits = std::max(top, gather_global_chunk_bits(elem_bytes));
         for (int b = 0; b < na; ++b) g.delta[b] = (uint32_t)linv[axis_shift + b];
         for (int b = 0; b < d && b < 32; ++b) g.own_bit[b] = axis_coord(vec(1) << b);
         // An aligned block of a few LDS sizes is walked through LDS chunk by chunk by every workgroup
@@ -251,7 +250,7 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         // for 1- / 2- / 4-byte elements.  The cost grows with range bytes per workgroup element, the
         // memory-direct kernel's does not.
         const int pcb = gather_phased_chunk_bits(elem_bytes);
-        static const long long phased_max = getenv("LL_GATHER_PHASED_MAX_BYTES") ? atoll(getenv("LL_GATHER_PHASED_MAX_BYTES")) : 1024 * 1024;   // experiment knob
+        const long long phased_max = opt_or(opt.gather_phased_max_bytes, 1024 * 1024);
         const long long block_bytes = (long long)elem_bytes << top;
         const bool phased = top >= pcb && block_bytes >= 2 * gather_phased_lds_chunk_bytes() && block_bytes <= phased_max && top + wlog <= 31;
         c->kernel = phased ? LL_GATHER_PHASED : LL_GATHER_GLOBAL;
@@ -266,6 +265,11 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
             for (int j = 0; j < 32 && field; ++j) field = g.own_bit[j] == ((j >= shift && j < shift + na) ? (1u << (j - shift)) : 0u);
             if (field) g.field_shift = shift;
         }
+        // XCD-aware order: the workgroups of one aligned range run on one XCD, whose L2 serves their
+        // repeated reads of it (the memory-direct kernel: up to 2 MiB of a larger range)
+        const int cb = phased ? pcb : gather_global_chunk_bits(elem_bytes);
+        const int range_chunks = (phased ? g.block_bits : std::min(g.block_bits, 21 - wlog)) - cb;
+        g.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, range_chunks > 0 ? range_chunks : -1);
         return LL_OK;
     }
     if (n < min_bits) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than the kernel's unit of work");
@@ -305,7 +309,7 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         for (int b = 0; b < na; ++b) moved |= g.delta[b];
         const int lo = std::max(0, ubk - wlog), hi = ubk + 5 - wlog;      // element bits that form the bank field
         const vec bank_bits = hi > lo ? ((vec(1) << hi) - 1) & ~((vec(1) << lo) - 1) : 0;
-        static const bool always = getenv("LL_GATHER_SWIZZLE_ALWAYS") != nullptr;      // experiment knob
+        const bool always = opt.gather_swizzle_always == 1;
         if (!(moved & bank_bits) && !always) g.swz_mask = 0;
     }
     // deltas that are consecutive single bits of the block-local index, nothing swizzled: the LDS byte
@@ -318,56 +322,49 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, Gat
         if (field) g.field_shift = shift + wlog;
     }
     c->kernel = LL_GATHER_BLOCK_STAGED;
+    // XCD-aware block order: 512 KiB of consecutive blocks per XCD (rows of config 5: 5.99 -> 6.36 TB/s)
+    g.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, xcd_chunk_bits_for(512 * 1024, (long long)elem_bytes << g.block_bits));
+    c->thread_bits = gather_general_thread_bits((long long)elem_bytes << g.block_bits, elem_bytes);
+    if (opt.gather_threads_log2 >= 8 && opt.gather_threads_log2 <= 10) c->thread_bits = opt.gather_threads_log2;
     return LL_OK;
 }
 
 // choose_gather costs about 3 us of host time (a right inverse, a few subspace bases), most of a small
 // gather's launch cost, and a layout is immutable: the choices are kept with the layout, keyed by
-// axis, element size and the values of the experiment knobs that choose_gather reads on every call.
-// The list is replaced as a whole (copy, append, atomic store), so concurrent callers need no lock;
-// two threads that miss at the same time both compute the same entry and one list wins.
+// axis, element size and the options they were made under.  The list is replaced as a whole (copy,
+// append, atomic store), so concurrent callers need no lock; two threads that miss at the same time
+// both compute the same entry and one list wins.  A hit costs a few integer comparisons.
 struct GatherCache {
     struct Entry {
         int axis, elem_bytes;
-        std::string knobs;
+        ll_options opts;
         GatherChoice choice;
     };
     std::vector<Entry> entries;
 };
 
-static std::string gather_knobs()
+static ll_status choose_gather_cached(const ll_layout *L, int axis, int elem_bytes, const ll_options *given, GatherChoice *c)
 {
-    std::string s;
-    for (const char *name : {"LL_GATHER_GENERAL", "LL_GATHER_STAGED", "LL_GATHER_BLOCK_BYTES"}) {
-        const char *v = getenv(name);
-        s += v ? v : "";
-        s += '|';
-    }
-    return s;
-}
-
-static ll_status choose_gather_cached(const ll_layout *L, int axis, int elem_bytes, GatherChoice *c)
-{
-    const std::string knobs = gather_knobs();
+    const ll_options &opt = given ? *given : process_options();       // `given` is complete (resolve_options)
     std::shared_ptr<const GatherCache> have = std::atomic_load(&L->gather_cache.p);
     if (have)
         for (const GatherCache::Entry &e : have->entries)
-            if (e.axis == axis && e.elem_bytes == elem_bytes && e.knobs == knobs) {
+            if (e.axis == axis && e.elem_bytes == elem_bytes && same_options(e.opts, opt)) {
                 *c = e.choice;
                 return LL_OK;
             }
-    if (ll_status st = choose_gather(L, axis, elem_bytes, c); st != LL_OK) return st;
+    if (ll_status st = choose_gather(L, axis, elem_bytes, opt, c); st != LL_OK) return st;
     auto next = std::make_shared<GatherCache>();
     if (have && have->entries.size() < 32) next->entries = have->entries;     // bounded: start over when full
-    next->entries.push_back({axis, elem_bytes, knobs, *c});
+    next->entries.push_back({axis, elem_bytes, opt, *c});
     std::atomic_store(&L->gather_cache.p, std::shared_ptr<const GatherCache>(next));
     return LL_OK;
 }
 
-ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gather_desc *out)
+ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, const ll_options *opts, ll_gather_desc *out)
 {
     GatherChoice c;
-    if (ll_status st = choose_gather_cached(L, axis, elem_bytes, &c); st != LL_OK) return st;
+    if (ll_status st = choose_gather_cached(L, axis, elem_bytes, opts, &c); st != LL_OK) return st;
     std::memset(out, 0, sizeof(*out));
     out->kernel = c.kernel;
     out->axis_reg_bits = c.axis_reg_bits;
@@ -381,11 +378,11 @@ ll_status describe_gather(const ll_layout *L, int axis, int elem_bytes, ll_gathe
     return LL_OK;
 }
 
-ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *in, const int32_t *idx, void *out,
+ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const ll_options *opts, const void *in, const int32_t *idx, void *out,
                      long long ntiles, void *stream)
 {
     GatherChoice c;
-    if (ll_status st = choose_gather_cached(L, axis, elem_bytes, &c); st != LL_OK) return st;
+    if (ll_status st = choose_gather_cached(L, axis, elem_bytes, opts, &c); st != LL_OK) return st;
     const int d = L->d_in;
     if (ntiles == 0) return LL_OK;
     if (!in || !idx || !out) return fail(LL_ERR_INVALID_ARG, "null device pointer");
@@ -399,39 +396,15 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
     const unsigned long long ibytes = ((unsigned long long)ntiles << d) * 4;
     if ((pi < po + bytes && po < pi + bytes) || (px < po + bytes && po < px + ibytes))
         return fail(LL_ERR_INVALID_ARG, "the output buffer overlaps an input buffer");
-    if (c.kernel == LL_GATHER_PHASED) {
+    if (c.kernel == LL_GATHER_PHASED || c.kernel == LL_GATHER_GLOBAL) {
         GatherGenArgs &g = c.gen;
         g.in = in;
         g.idx = idx;
         g.out = out;
         g.total_elems = ntiles << d;
-        const int cb = gather_phased_chunk_bits(elem_bytes);
+        const int cb = c.kernel == LL_GATHER_PHASED ? gather_phased_chunk_bits(elem_bytes) : gather_global_chunk_bits(elem_bytes);
         g.nblocks = (g.total_elems + (1ll << cb) - 1) >> cb;
-        {
-            // XCD-aware order: the workgroups of one aligned block run on one XCD, whose L2 serves
-            // their repeated reads of the block
-            const char *e = getenv("LL_GATHER_XCD_CHUNK");        // experiment knob: workgroups (power of two), 0 = off
-            const int block_chunks = g.block_bits - cb;
-            g.xcd_chunk = e ? (atoi(e) > 1 ? 31 - __builtin_clz((unsigned)atoi(e)) : -1) : (block_chunks > 0 ? block_chunks : -1);
-        }
-        return launch_gather_phased(g, elem_bytes, stream);
-    }
-    if (c.kernel == LL_GATHER_GLOBAL) {
-        GatherGenArgs &g = c.gen;
-        g.in = in;
-        g.idx = idx;
-        g.out = out;
-        g.total_elems = ntiles << d;
-        const int cb = gather_global_chunk_bits(elem_bytes);
-        g.nblocks = (g.total_elems + (1ll << cb) - 1) >> cb;
-        {
-            // XCD-aware order: one XCD works through a whole axis block (up to 2 MiB) so that the
-            // re-reads of the block hit that XCD's L2
-            const char *e = getenv("LL_GATHER_XCD_CHUNK");        // experiment knob: workgroups (power of two), 0 = off
-            const int block_chunks = std::min(g.block_bits, 21 - (31 - __builtin_clz((unsigned)elem_bytes))) - cb;
-            g.xcd_chunk = e ? (atoi(e) > 1 ? 31 - __builtin_clz((unsigned)atoi(e)) : -1) : (block_chunks > 0 ? block_chunks : -1);
-        }
-        return launch_gather_global(g, elem_bytes, stream);
+        return c.kernel == LL_GATHER_PHASED ? launch_gather_phased(g, elem_bytes, stream) : launch_gather_global(g, elem_bytes, stream);
     }
     if (c.kernel == LL_GATHER_BLOCK_STAGED) {
         GatherGenArgs &g = c.gen;
@@ -442,25 +415,14 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const void *i
         g.total_elems = ntiles << d;
         const long long ngroups = (ntiles + (1ll << g.group_bits) - 1) >> g.group_bits;
         g.nblocks = ngroups << g.coset_bits;
-        {
-            // XCD-aware block order: 512 KiB of consecutive blocks per XCD (rows of config 5: 5.99 -> 6.36 TB/s)
-            const char *e = getenv("LL_GATHER_XCD_CHUNK");        // experiment knob: blocks (power of two), 0 = off
-            const long long v = e ? atoi(e) : (512 * 1024) / ((long long)elem_bytes << g.block_bits);
-            g.xcd_chunk = v > 1 ? 63 - __builtin_clzll((unsigned long long)v) : -1;
-        }
-        return launch_gather_general(g, elem_bytes, stream);
+        return launch_gather_general(g, elem_bytes, c.thread_bits, stream);
     }
     GatherArgs &a = c.wave;
     a.in = in;
     a.idx = idx;
     a.out = out;
     a.nchunks = ntiles << a.nwave;
-    {
-        const char *e = getenv("LL_GATHER_XCD_CHUNK");            // experiment knob: workgroups (power of two), 0 = off
-        const long long v = e ? atoi(e) : 0;
-        a.xcd_chunk = v > 1 ? 63 - __builtin_clzll((unsigned long long)v) : -1;
-    }
-    return launch_gather(a, elem_bytes, stream);
+    return launch_gather(a, elem_bytes, c.lds_alloc, stream);
 }
 
 }  // namespace ll

@@ -74,17 +74,18 @@ def test_gather_full_size_sampled():
     assert torch.equal(wl.bits_view(out), wl.bits_view(inp))
 
 
-def test_gather_both_kernels_agree(monkeypatch):
+def test_gather_both_kernels_agree():
     """The shuffle kernel (one ds_bpermute_b32 per element) and the staged kernel on config 5."""
     cfg = wl.config(5)
     layout = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
     nt = 37
     inp, idx = cfg.gen_data(0, nt, "cuda"), cfg.gen_idx(0, nt, "cuda")
     want = oracle.gather(cfg.src_bases, cfg.out_dim_bits, cfg.axis, wl.to_numpy_bits(inp), idx.cpu().numpy())
-    for staged in ("0", "1"):
-        monkeypatch.setenv("LL_GATHER_STAGED", staged)
+    for staged in (ll.LL_GATHER_SHUFFLE, ll.LL_GATHER_WAVE_STAGED):
+        opts = ll.ll_options_init(gather_kernel=staged)
+        assert ll.ll_gather_info(layout, cfg.axis, cfg.elem_bytes, opts)["kernel"] == staged
         out = torch.zeros_like(inp)
-        ll.ll_gather(layout, cfg.axis, cfg.elem_bytes, inp, idx, out, nt)
+        ll.ll_gather(layout, cfg.axis, cfg.elem_bytes, inp, idx, out, nt, opts=opts)
         torch.cuda.synchronize()
         assert np.array_equal(wl.to_numpy_bits(out), want), f"staged={staged}"
 
@@ -115,16 +116,14 @@ def test_broadcast_convert_full_size_sampled(case):
         assert np.array_equal(wl.to_numpy_bits(dst[t << dd:(t + 1) << dd]), want), f"{case.name} tile {t}"
 
 
-@pytest.mark.parametrize("w,force", [(1, "6"), (2, "6")])
-def test_narrow_transpose_full_size_sampled(w, force, monkeypatch):
+@pytest.mark.parametrize("w,force", [(1, 6), (2, 6)])
+def test_narrow_transpose_full_size_sampled(w, force):
     """The 128 x 128 transpose with 1- and 2-byte elements through the transposing LDS loads, at the
     size bench.py times (256 MiB per side)."""
-    if force:
-        monkeypatch.setenv("LL_FORCE_STRATEGY", force)
     cfg = wl.config(2)
     a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
     b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
-    plan = ll.ll_plan_convert(a, b, w)
+    plan = ll.ll_plan_convert(a, b, w, ll.ll_options_init(strategy=force))
     assert plan.info()["strategy_name"] == "lds_tr"
     te = cfg.tile_elems
     nt = (256 << 20) // (te * w)
@@ -211,15 +210,14 @@ def test_gather_short_runs_beyond_l2():
     assert np.array_equal(out[te:2 * te].cpu().numpy().view(np.uint32), want)
 
 
-@pytest.mark.parametrize("cid,force", [(1, None), (3, None), (4, None), (5, None), (2, "4"), (2, "6")])
-def test_buffers_beyond_four_gib(cid, force, monkeypatch):
+@pytest.mark.parametrize("cid,force", [(1, None), (3, None), (4, None), (5, None), (2, 4), (2, 6)])
+def test_buffers_beyond_four_gib(cid, force):
     """Images larger than 4 GiB (64-bit offsets in every kernel family: lane-register butterflies,
     register path, element-wide LDS staging, gather, and config 2 forced through the 128-bit LDS
     kernel and the transposing LDS loads), with a ragged tile count; tiles from both ends and from
     just past the 4 GiB mark are compared with the oracle, and every tile's checksum is preserved
     (conversions permute a tile)."""
-    if force:
-        monkeypatch.setenv("LL_FORCE_STRATEGY", force)
+    opts = ll.ll_options_init(strategy=force) if force else None
     cfg = wl.config(cid)
     te, w = cfg.tile_elems, cfg.elem_bytes
     ntiles = (4 << 30) // (te * w) + 257 + 3
@@ -246,8 +244,8 @@ def test_buffers_beyond_four_gib(cid, force, monkeypatch):
         return
     a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
     b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
-    plan = ll.ll_plan_convert(a, b, w)
-    want_kernel = {(1, None): "wave_shuffle", (3, None): "reg_permute", (4, None): "lds_elem", (2, "4"): "lds_vec", (2, "6"): "lds_tr"}
+    plan = ll.ll_plan_convert(a, b, w, opts)
+    want_kernel = {(1, None): "wave_shuffle", (3, None): "reg_permute", (4, None): "lds_elem", (2, 4): "lds_vec", (2, 6): "lds_tr"}
     assert plan.info()["strategy_name"] == want_kernel[(cid, force)]
     ll.ll_convert(plan, src, dst, ntiles)
     torch.cuda.synchronize()

@@ -96,13 +96,13 @@ def test_convert_identity_is_copy_and_zero_tiles():
     ll.ll_convert(plan, 0, 0, 0)                       # ntiles == 0: nothing is touched
 
 
-def run_gather(layout, axis, inp_bits: np.ndarray, idx: np.ndarray, d: int) -> np.ndarray:
+def run_gather(layout, axis, inp_bits: np.ndarray, idx: np.ndarray, d: int, opts=None) -> np.ndarray:
     w = inp_bits.itemsize
     ntiles = inp_bits.size >> d
     tin = torch.from_numpy(inp_bits.view({1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}[w])).cuda()
     tidx = torch.from_numpy(idx).cuda()
     tout = torch.full_like(tin, 0x5A if w == 1 else 0x5A5A)
-    ll.ll_gather(layout, axis, w, tin, tidx, tout, ntiles)
+    ll.ll_gather(layout, axis, w, tin, tidx, tout, ntiles, opts=opts)
     torch.cuda.synchronize()
     return tout.cpu().numpy().view(NP_DTYPES[w])
 
@@ -120,11 +120,11 @@ def test_gather_config5_small(ntiles):
 
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 @pytest.mark.parametrize("nreg,nwave,axis_bits", [(2, 0, 6), (3, 1, 4), (4, 2, 6), (5, 1, 3), (1, 3, 5)])
-def test_gather_random_lane_axis(w, nreg, nwave, axis_bits, monkeypatch):
+def test_gather_random_lane_axis(w, nreg, nwave, axis_bits):
     """Axis bits live on an arbitrary subset of the lane bits, mixed by XOR with other lane bits;
-    the other logical bits are spread over registers, the remaining lanes and waves."""
-    if (1 << nreg) * w < 4:
-        pytest.skip("fewer than 4 bytes per lane")
+    the other logical bits are spread over registers, the remaining lanes and waves.  Run through the
+    library's own choice, through the wave kernels (shuffle / wave-staged) on request where a lane
+    holds the 4 bytes they need, and through the workgroup-staged kernel on request."""
     rng = np.random.default_rng(31 * w + nreg + 7 * nwave + axis_bits)
     d = nreg + 6 + nwave
     other_bits = d - axis_bits
@@ -150,12 +150,15 @@ def test_gather_random_lane_axis(w, nreg, nwave, axis_bits, monkeypatch):
     idx = rng.integers(0, 1 << axis_bits, size=ntiles << d, dtype=np.int32)
     idx[::17] += 1 << axis_bits                        # out-of-range entries wrap
     want = oracle.gather(bases, dims, 0, inp, idx)
-    for general in ("0", "1"):                         # the wave kernels (shuffle / wave-staged) and the workgroup-staged one
-        monkeypatch.setenv("LL_GATHER_GENERAL", general)
-        assert ll.ll_gather_info(layout, 0, w)["kernel_name"] == ("block_staged" if general == "1" else
-                                                                 ll.ll_gather_info(layout, 0, w)["kernel_name"])
-        got = run_gather(layout, 0, inp, idx, d)
-        assert np.array_equal(got, want), general
+    wave_ok = (1 << nreg) * w >= 4
+    for kernel, allowed in ((None, ("shuffle", "wave_staged", "block_staged")),
+                            (ll.LL_GATHER_SHUFFLE, ("shuffle",) if wave_ok else ("block_staged",)),
+                            (ll.LL_GATHER_WAVE_STAGED, ("shuffle", "wave_staged") if wave_ok else ("block_staged",)),
+                            (ll.LL_GATHER_BLOCK_STAGED, ("block_staged",))):
+        opts = None if kernel is None else ll.ll_options_init(gather_kernel=kernel)
+        assert ll.ll_gather_info(layout, 0, w, opts)["kernel_name"] in allowed, kernel
+        got = run_gather(layout, 0, inp, idx, d, opts)
+        assert np.array_equal(got, want), kernel
 
 
 @pytest.mark.parametrize("cid", [1, 2, 3, 4])
@@ -167,16 +170,20 @@ def test_convert_configs_reverse_direction(cid):
     assert np.array_equal(run_convert(plan, src, cfg.d), oracle.convert(cfg.dst_bases, cfg.src_bases, src))
 
 
-@pytest.mark.parametrize("force", ["3", "4"])
+@pytest.mark.parametrize("force,threads_log2", [(3, -1), (3, 6), (3, 8), (4, -1)])
 @pytest.mark.parametrize("cid", [1, 2, 3, 4])
-def test_convert_configs_forced_lds_strategies(cid, force, monkeypatch):
-    """Every config through the element-wide LDS kernel (3) and, where it applies, the 128-bit one (4)."""
-    monkeypatch.setenv("LL_FORCE_STRATEGY", force)
+def test_convert_configs_forced_lds_strategies(cid, force, threads_log2):
+    """Every config through the element-wide LDS kernel (3: workgroup size chosen by the planner, one
+    wave, four waves) and, where it applies, the 128-bit one (4)."""
     cfg = wl.config(cid)
     a, b = layouts_of(cfg)
-    plan = ll.ll_plan_convert(a, b, cfg.elem_bytes)
+    plan = ll.ll_plan_convert(a, b, cfg.elem_bytes, ll.ll_options_init(strategy=force, elem_threads_log2=threads_log2))
     name = plan.info()["strategy_name"]
-    assert name in ("lds_elem", "lds_vec") and (force != "3" or name == "lds_elem")
+    assert name in ("lds_elem", "lds_vec") and (force != 3 or name == "lds_elem")
+    if force == 3 and threads_log2 > 0:
+        info = plan.info()
+        one_wave_block = (cfg.elem_bytes << info["block_bits"]) == 4096      # the one-wave kernel takes 4 KiB blocks only
+        assert info["threads"] == (1 << threads_log2 if threads_log2 != 6 or one_wave_block else 256)
     src = wl.to_numpy_bits(cfg.gen_data(1, 3))
     assert np.array_equal(run_convert(plan, src, cfg.d), oracle.convert(cfg.src_bases, cfg.dst_bases, src))
 
@@ -321,10 +328,10 @@ def test_convert_broadcast_workloads_small(case):
 # ---------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("w", [1, 2])
-def test_convert_transposing_lds_reads(w, monkeypatch):
+def test_convert_transposing_lds_reads(w):
     """Transposes and other bit permutations of 1- and 2-byte elements through ds_read_b64_tr_b8 /
-    _tr_b16 (forced, so that 2-byte cases do not take the register path)."""
-    monkeypatch.setenv("LL_FORCE_STRATEGY", "6")
+    _tr_b16 (requested, so that 2-byte cases do not take the register path)."""
+    tr = ll.ll_options_init(strategy=ll.LL_STRATEGY_LDS_TR)
     rng = np.random.default_rng(600 + w)
     used = 0
     cases = []
@@ -341,7 +348,7 @@ def test_convert_transposing_lds_reads(w, monkeypatch):
     for nreg, nlane, nwave, dims, ca, cb in cases:
         d = nreg + nlane + nwave
         plan = ll.ll_plan_convert(ll.distributed_layout(nreg, nlane, nwave, dims, ca),
-                                  ll.distributed_layout(nreg, nlane, nwave, dims, cb), w)
+                                  ll.distributed_layout(nreg, nlane, nwave, dims, cb), w, tr)
         used += plan.info()["strategy_name"] == "lds_tr"
         ntiles = int(rng.integers(1, 12))
         src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
@@ -349,7 +356,7 @@ def test_convert_transposing_lds_reads(w, monkeypatch):
     assert used >= 3, "the transposing-read planner applied to %d cases only" % used
 
 
-def test_one_byte_transpose_through_both_lds_kernels(monkeypatch):
+def test_one_byte_transpose_through_both_lds_kernels():
     c2 = wl.config(2)
     a, b = layouts_of(c2)
     src = np.random.default_rng(5).integers(0, 255, size=9 << c2.d, dtype=np.uint8)
@@ -357,8 +364,7 @@ def test_one_byte_transpose_through_both_lds_kernels(monkeypatch):
     plan = ll.ll_plan_convert(a, b, 1)
     assert plan.info()["strategy_name"] == "lds_elem"
     assert np.array_equal(run_convert(plan, src, c2.d), want)
-    monkeypatch.setenv("LL_FORCE_STRATEGY", "6")
-    plan = ll.ll_plan_convert(a, b, 1)
+    plan = ll.ll_plan_convert(a, b, 1, ll.ll_options_init(strategy=ll.LL_STRATEGY_LDS_TR))
     info = plan.info()
     assert info["strategy_name"] == "lds_tr" and info["lds_read_bytes"] == 8
     assert np.array_equal(run_convert(plan, src, c2.d), want)
@@ -369,19 +375,18 @@ def test_one_byte_transpose_through_both_lds_kernels(monkeypatch):
 # ---------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("axis,ntiles", [(1, 1), (1, 3), (0, 2)])
-def test_gather_config5_any_axis(axis, ntiles, monkeypatch):
+def test_gather_config5_any_axis(axis, ntiles):
     """Config 5's layout gathered along its columns (registers and waves: the workgroup-staged
     kernel) and along its rows with that kernel forced."""
     cfg = wl.config(5)
     layout, _ = layouts_of(cfg)
-    if axis == 0:
-        monkeypatch.setenv("LL_GATHER_GENERAL", "1")
-    assert ll.ll_gather_info(layout, axis, cfg.elem_bytes)["kernel_name"] == "block_staged"
+    opts = ll.ll_options_init(gather_kernel=ll.LL_GATHER_BLOCK_STAGED) if axis == 0 else None
+    assert ll.ll_gather_info(layout, axis, cfg.elem_bytes, opts)["kernel_name"] == "block_staged"
     rng = np.random.default_rng(axis + 10 * ntiles)
     inp = wl.to_numpy_bits(cfg.gen_data(0, ntiles))
     idx = rng.integers(0, 1 << cfg.out_dim_bits[axis], size=ntiles << cfg.d, dtype=np.int32)
     idx[::13] += 1 << cfg.out_dim_bits[axis]                      # wraps
-    got = run_gather(layout, axis, inp, idx, cfg.d)
+    got = run_gather(layout, axis, inp, idx, cfg.d, opts)
     want = oracle.gather(cfg.src_bases, cfg.out_dim_bits, axis, inp, idx)
     assert np.array_equal(got, want)
 
@@ -451,7 +456,7 @@ def test_convert_configs_with_flips(cid):
 
 
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
-def test_convert_random_affine_layouts(w, monkeypatch):
+def test_convert_random_affine_layouts(w):
     rng = np.random.default_rng(900 + w)
     for d, nreg in [(9, 3), (12, 4), (14, 6)]:
         for trial in range(6):
@@ -462,12 +467,9 @@ def test_convert_random_affine_layouts(w, monkeypatch):
             else:
                 ca, cb = random_invertible(rng, d), random_invertible(rng, d)
             oa, ob = int(rng.integers(0, 1 << d)), int(rng.integers(0, 1 << d))
-            if trial == 5:
-                monkeypatch.setenv("LL_FORCE_STRATEGY", "3")
             a = ll.ll_layout_with_offset(ll.distributed_layout(nreg, 6, d - nreg - 6, [d], ca), oa)
             b = ll.ll_layout_with_offset(ll.distributed_layout(nreg, 6, d - nreg - 6, [d], cb), ob)
-            plan = ll.ll_plan_convert(a, b, w)
-            monkeypatch.delenv("LL_FORCE_STRATEGY", raising=False)
+            plan = ll.ll_plan_convert(a, b, w, ll.ll_options_init(strategy=ll.LL_STRATEGY_LDS_ELEM) if trial == 5 else None)
             ntiles = int(rng.integers(1, 20))
             src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d, dtype=NP_DTYPES[w])
             got = run_convert(plan, src, d)
@@ -485,7 +487,7 @@ def test_flip_of_the_identity_layout_is_numpy_flip():
 
 
 @pytest.mark.parametrize("axis", [0, 1])
-def test_gather_under_affine_layouts(axis, monkeypatch):
+def test_gather_under_affine_layouts(axis):
     cfg = wl.config(5)
     base, _ = layouts_of(cfg)
     rng = np.random.default_rng(40 + axis)
@@ -494,9 +496,8 @@ def test_gather_under_affine_layouts(axis, monkeypatch):
     idx = rng.integers(0, 1 << cfg.out_dim_bits[axis], size=ntiles << cfg.d, dtype=np.int32)
     for off in ((1 << cfg.d) - 1, int(rng.integers(1, 1 << cfg.d))):
         layout = ll.ll_layout_with_offset(base, off)
-        for staged in ("0", "1"):
-            monkeypatch.setenv("LL_GATHER_STAGED", staged)
-            got = run_gather(layout, axis, inp, idx, cfg.d)
+        for staged in (ll.LL_GATHER_SHUFFLE, ll.LL_GATHER_WAVE_STAGED):
+            got = run_gather(layout, axis, inp, idx, cfg.d, ll.ll_options_init(gather_kernel=staged))
             assert np.array_equal(got, oracle.gather_affine(cfg.src_bases, off, cfg.out_dim_bits, axis, inp, idx)), (off, staged)
 
 
@@ -556,8 +557,9 @@ def test_convert_large_tiles_random_xor(w, d):
     ca, cb = wl.random_invertible_bases(500 + d, d), wl.random_invertible_bases(600 + d, d)
     a, b = ll.distributed_layout(4, 6, d - 10, [d], ca), ll.distributed_layout(4, 6, d - 10, [d], cb)
     plan = ll.ll_plan_convert(a, b, w)
-    if w == 4:
-        assert plan.info()["vectors_per_thread"] == (4 if d >= 17 else 1)
+    if w == 4:            # 16 KiB blocks for four waves from 2^17 elements on, below that 4 KiB blocks for one wave
+        info = plan.info()
+        assert (info["threads"], info["vectors_per_thread"], info["block_bits"]) == ((256, 4, 12) if d >= 17 else (64, 4, 10))
     src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=3 << d, dtype=NP_DTYPES[w])
     assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src))
 
@@ -825,7 +827,7 @@ def test_convert_between_different_register_lane_wave_splits(w):
 
 
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
-def test_gather_along_axes_larger_than_lds(w, monkeypatch):
+def test_gather_along_axes_larger_than_lds(w):
     """Axes whose aligned block exceeds what LDS stages (128 KiB) are walked through LDS in chunks
     (up to 1 MiB) or gathered straight from memory; blocks of 64 and 128 KiB are staged by
     1024-thread workgroups.  Random XOR layouts on tiles of 64, 128, 256 KiB and 2 MiB and of 2^18
@@ -864,7 +866,7 @@ def test_gather_along_axes_larger_than_lds(w, monkeypatch):
 # Gather under broadcasting layouts (Sec. 5.5 with Sec. 5.1): replicas receive and supply data
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
-def test_gather_under_broadcasting_layouts(w, monkeypatch):
+def test_gather_under_broadcasting_layouts(w):
     """Random surjective layouts with zero and dependent columns, every axis, replicas of `in` and
     `idx` deliberately unequal (which replica is read is part of the definition); a sliced blocked
     layout; an affine constant on top."""
@@ -889,13 +891,11 @@ def test_gather_under_broadcasting_layouts(w, monkeypatch):
     s = ll.ll_layout_slice(parent, 0)
     os_ = oracle.slice_layout(oracle.blocked_layout([1, 2], [3, 3], [2, 1], [1, 0]), 0)
     assert s.bases == os_.bases
-    for env in ({}, {"LL_GATHER_GENERAL": "1"}):
-        for k, v in env.items():
-            monkeypatch.setenv(k, v)
-        seen.add(ll.ll_gather_info(s, 0, w)["kernel_name"])
+    for opts in (None, ll.ll_options_init(gather_kernel=ll.LL_GATHER_BLOCK_STAGED)):
+        seen.add(ll.ll_gather_info(s, 0, w, opts)["kernel_name"])
         inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=32 << 12, dtype=NP_DTYPES[w])
         idx = rng.integers(0, 64, size=32 << 12, dtype=np.int32)
-        assert np.array_equal(run_gather(s, 0, inp, idx, 12), oracle.gather_general(os_.bases, [6], 0, inp, idx))
+        assert np.array_equal(run_gather(s, 0, inp, idx, 12, opts), oracle.gather_general(os_.bases, [6], 0, inp, idx))
     assert "block_staged" in seen
 
 

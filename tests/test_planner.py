@@ -40,10 +40,10 @@ def banks_of(info, side):
     return info["lds_banks_write"] if side == "lds_write" else info["lds_banks"]
 
 
-def plan_of(cfg):
+def plan_of(cfg, strategy=None):
     a = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
     b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
-    return ll.ll_plan_convert(a, b, cfg.elem_bytes)
+    return ll.ll_plan_convert(a, b, cfg.elem_bytes, None if strategy is None else ll.ll_options_init(strategy=strategy))
 
 
 def test_conversion_matrix_equals_tabulated_composition():
@@ -96,20 +96,18 @@ def test_strategies_of_the_configs(monkeypatch):
     for cid in (1, 2, 3, 4):
         assert got[cid]["global_vec_bytes"] == 16
     # with the register / shuffle planner switched off, configs 1-3 stage through LDS with 128-bit accesses
-    monkeypatch.setenv("LL_FORCE_STRATEGY", "4")
     for cid in (1, 2, 3):
-        info = plan_of(wl.config(cid)).info()
+        info = plan_of(wl.config(cid), ll.LL_STRATEGY_LDS_VEC).info()
         assert info["strategy_name"] == "lds_vec"
         assert info["lds_write_bytes"] == 16 and info["lds_read_bytes"] == 16 and info["register_transpose"] == 1
 
 
-@pytest.mark.parametrize("force", ["3", "4"])
+@pytest.mark.parametrize("force", [3, 4])
 @pytest.mark.parametrize("cid", [1, 2, 3, 4])
-def test_swizzle_of_configs_is_conflict_free_by_enumeration(cid, force, monkeypatch):
-    monkeypatch.setenv("LL_FORCE_STRATEGY", force)        # 3: element-wide LDS, 4: 128-bit LDS where it applies
-    info = plan_of(wl.config(cid)).info()
+def test_swizzle_of_configs_is_conflict_free_by_enumeration(cid, force):
+    info = plan_of(wl.config(cid), force).info()          # 3: element-wide LDS, 4: 128-bit LDS where it applies
     assert info["strategy_name"] in ("lds_elem", "lds_vec")
-    if force == "3":
+    if force == 3:
         assert info["strategy_name"] == "lds_elem"
     n = info["block_bits"]
     assert len(span(info["lds_mem"])) == 1 << n        # M is invertible
@@ -121,11 +119,10 @@ def test_swizzle_of_configs_is_conflict_free_by_enumeration(cid, force, monkeypa
     assert info["predicted_wavefronts_write"] == 1 and info["predicted_wavefronts_read"] == 1
 
 
-@pytest.mark.parametrize("force", ["3", "4"])
-def test_unswizzled_staging_of_config1_conflicts(force, monkeypatch):
+@pytest.mark.parametrize("force", [3, 4])
+def test_unswizzled_staging_of_config1_conflicts(force):
     # control: the same accesses against a linear (unswizzled) LDS layout do collide
-    monkeypatch.setenv("LL_FORCE_STRATEGY", force)
-    info = plan_of(wl.config(1)).info()
+    info = plan_of(wl.config(1), force).info()
     n = info["block_bits"]
     linear = [1 << k for k in range(n)]
     worst = max(oracle.wavefronts(linear, info[side], info["lds_write_reg_bits"], 6, 4, info["lds_vec_bits"],
@@ -169,8 +166,7 @@ def test_common_vector_is_kept_wide(monkeypatch):
     a = ll.distributed_layout(4, 6, 2, [d], [1, 2] + rest_a)
     b = ll.distributed_layout(4, 6, 2, [d], [1, 2] + rest_b)
     assert ll.ll_plan_convert(a, b, 4).info()["strategy_name"] in ("reg_permute", "wave_shuffle", "lds_elem")
-    monkeypatch.setenv("LL_FORCE_STRATEGY", "3")
-    info = ll.ll_plan_convert(a, b, 4).info()
+    info = ll.ll_plan_convert(a, b, 4, ll.ll_options_init(strategy=ll.LL_STRATEGY_LDS_ELEM)).info()
     assert info["strategy_name"] == "lds_elem"
     assert info["lds_vec_bits"] == 2 and info["lds_write_bytes"] == 16
     for side in ("lds_write", "lds_read"):
@@ -484,33 +480,31 @@ def test_binding_rejects_host_and_short_tensors():
     assert plan.sizes() == (14, 14, 2) and a.d_in == 14
 
 
-def test_gather_choice_is_remembered_per_layout_and_follows_the_knobs(monkeypatch):
+def test_gather_choice_is_remembered_per_layout_and_follows_the_options():
     """The kernel choice of a gather is kept with the layout; a repeated query returns the same
-    description, other axes and element sizes get their own, and the experiment knobs that influence
-    the choice are part of the key."""
+    description, other axes and element sizes get their own, and the options the choice was made
+    under are part of the key."""
     cfg = wl.config(5)
     layout = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
-    monkeypatch.delenv("LL_GATHER_GENERAL", raising=False)
     first = ll.ll_gather_info(layout, 0, 2)
     assert first["kernel_name"] == "wave_staged"
     assert ll.ll_gather_info(layout, 0, 2) == first
     assert ll.ll_gather_info(layout, 1, 2)["kernel_name"] == "block_staged"
     assert ll.ll_gather_info(layout, 0, 1)["kernel_name"] == "block_staged"       # one-byte elements
-    monkeypatch.setenv("LL_GATHER_GENERAL", "1")
-    assert ll.ll_gather_info(layout, 0, 2)["kernel_name"] == "block_staged"
-    monkeypatch.delenv("LL_GATHER_GENERAL")
+    staged = ll.ll_options_init(gather_kernel=ll.LL_GATHER_BLOCK_STAGED)
+    assert ll.ll_gather_info(layout, 0, 2, staged)["kernel_name"] == "block_staged"
+    assert ll.ll_gather_info(layout, 0, 2, ll.ll_options_init(gather_kernel=ll.LL_GATHER_SHUFFLE))["kernel_name"] == "shuffle"
     assert ll.ll_gather_info(layout, 0, 2) == first
+    assert ll.ll_gather_info(layout, 0, 2, ll.ll_options_init()) == first         # all-automatic options = no options
     # many distinct queries on one layout (the list is bounded) still answer correctly
     for rep in range(3):
         for w in (1, 2, 4, 8):
             for axis in (0, 1):
-                for knob in (None, "0", "1"):
-                    if knob is None:
-                        monkeypatch.delenv("LL_GATHER_GENERAL", raising=False)
-                    else:
-                        monkeypatch.setenv("LL_GATHER_GENERAL", knob)
-                    fresh = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
-                    assert ll.ll_gather_info(layout, axis, w) == ll.ll_gather_info(fresh, axis, w)
+                for knob in (None, 0, 1, 2):
+                    for blk in (-1, 4096, 16384, 32768):
+                        opts = None if knob is None else ll.ll_options_init(gather_kernel=knob, gather_block_bytes=blk)
+                        fresh = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
+                        assert ll.ll_gather_info(layout, axis, w, opts) == ll.ll_gather_info(fresh, axis, w, opts)
 
 
 def test_planning_from_many_threads_gives_the_single_thread_answer():
