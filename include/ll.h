@@ -202,9 +202,10 @@ typedef struct {
                                       LL_STRATEGY_LDS_VEC: skip the register / shuffle planner, i.e. 128-bit LDS staging where it
                                       applies, else element-wide; LL_STRATEGY_LDS_TR: transposing LDS loads where they apply,
                                       else as LL_AUTO.  ll_plan_info reports the kernel actually planned. */
-    int32_t gather_kernel;         /* gathers: LL_GATHER_SHUFFLE / LL_GATHER_WAVE_STAGED (taken when the axis moves lane bits
-                                      only and the bytes per lane suit the kernel), LL_GATHER_BLOCK_STAGED (taken whenever a
-                                      closed block fits LDS); otherwise as LL_AUTO.  ll_gather_info_opts reports the choice. */
+    int32_t gather_kernel;         /* gathers: LL_GATHER_SHUFFLE / LL_GATHER_SHUFFLE_ROWS / LL_GATHER_WAVE_STAGED (taken when the
+                                      axis moves lane bits only and the bytes per lane suit the kernel),
+                                      LL_GATHER_BLOCK_STAGED (taken whenever a closed block fits LDS); otherwise as LL_AUTO.
+                                      ll_gather_info_opts reports the choice. */
     /* conversion tuning (bytes are powers of two) */
     int32_t block_bytes;           /* largest block of the element-wide LDS kernels */
     int32_t pref_bytes;            /* size small tiles are bundled up to */
@@ -230,6 +231,7 @@ typedef struct {
     int32_t gather_swizzle_always; /* 1: swizzle the staged block even when no move along the axis changes bank bits */
     int32_t copy_xcd_chunk;        /* ll_copy (process defaults only) */
     int32_t debug;                 /* 1: planners say on stderr why a strategy did not apply */
+    int32_t gather_waves;          /* waves per workgroup of the wave-level gather kernels (one chunk each): 1, 2 or 4 */
 } ll_options;
 
 ll_status ll_options_init(ll_options *opts);
@@ -366,8 +368,11 @@ typedef enum {
     LL_GATHER_WAVE_STAGED = 1,   /* coalesced access, source rows staged in wave-private LDS */
     LL_GATHER_BLOCK_STAGED = 2,  /* general: a block closed under the axis staged in workgroup LDS */
     LL_GATHER_GLOBAL = 3,        /* no closed block fits LDS: element-wide reads from memory */
-    LL_GATHER_PHASED = 4         /* no closed block fits LDS, but the aligned range around an element is a few
+    LL_GATHER_PHASED = 4,        /* no closed block fits LDS, but the aligned range around an element is a few
                                     LDS sizes: every workgroup walks the range through LDS in 128 KiB chunks */
+    LL_GATHER_SHUFFLE_ROWS = 5   /* as LL_GATHER_SHUFFLE for lanes that hold 32 to 256 bytes: global accesses in coalesced
+                                    16-byte pieces, converted to and from "one layout row per lane" by lane <-> register
+                                    butterflies (ds_bpermute_b32), the gather itself by ds_bpermute_b32 */
 } ll_gather_kernel;
 
 typedef struct {

@@ -42,8 +42,9 @@ EXPORTED_SYMBOLS = [
     "ll_options_init", "ll_options_from_env", "ll_plan_convert_opts", "ll_gather_opts", "ll_gather_info_opts",
 ]
 LL_AUTO = -1
-LL_GATHER_SHUFFLE, LL_GATHER_WAVE_STAGED, LL_GATHER_BLOCK_STAGED, LL_GATHER_GLOBAL, LL_GATHER_PHASED = range(5)
-GATHER_KERNEL_NAMES = ["shuffle", "wave_staged", "block_staged", "global", "lds_phased"]
+LL_GATHER_SHUFFLE, LL_GATHER_WAVE_STAGED, LL_GATHER_BLOCK_STAGED, LL_GATHER_GLOBAL, LL_GATHER_PHASED, \
+    LL_GATHER_SHUFFLE_ROWS = range(6)
+GATHER_KERNEL_NAMES = ["shuffle", "wave_staged", "block_staged", "global", "lds_phased", "shuffle_rows"]
 
 
 class ll_gather_desc(ctypes.Structure):
@@ -59,7 +60,7 @@ class ll_options(ctypes.Structure):
         "vec_threads", "shuffle_block_bytes", "inflight_bytes", "lds_pad_bytes", "xcd_chunk", "pull_mode",
         "pull_vec_bits", "pull_inflight_bytes", "pull_xcd_chunk", "gather_block_bytes", "gather_lds_max_bytes",
         "gather_min_run_bytes", "gather_phased_max_bytes", "gather_threads_log2", "gather_inflight_bytes",
-        "gather_xcd_chunk", "gather_swizzle_always", "copy_xcd_chunk", "debug")]
+        "gather_xcd_chunk", "gather_swizzle_always", "copy_xcd_chunk", "debug", "gather_waves")]
 
 
 class ll_in_dim(ctypes.Structure):

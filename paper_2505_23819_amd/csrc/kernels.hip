@@ -744,7 +744,8 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a)
     constexpr int PL = NE * W;                    // data bytes per lane
     constexpr int DW = (PL + 3) / 4;              // data dwords per lane
     const uint32_t lane = threadIdx.x & 63;
-    const long long chunk = block_of_workgroup((long long)blockIdx.x, (a.nchunks + 3) / 4, a.xcd_chunk) * 4 + (threadIdx.x >> 6);
+    const uint32_t wpg = blockDim.x >> 6;         // waves (chunks) per workgroup
+    const long long chunk = block_of_workgroup((long long)blockIdx.x, (a.nchunks + wpg - 1) / wpg, a.xcd_chunk) * wpg + (threadIdx.x >> 6);
     if (chunk >= a.nchunks) return;               // whole wave leaves together
     const unsigned char *in = static_cast<const unsigned char *>(a.in) + ((size_t)chunk * 64 + lane) * PL;
     const unsigned char *ix = reinterpret_cast<const unsigned char *>(a.idx) + ((size_t)chunk * 64 + lane) * (NE * 4);
@@ -825,6 +826,105 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a)
     }
 }
 
+// The shuffle gather of Sec. 5.5 for rows wider than one 16-byte vector, with every global access
+// coalesced.  Loads and stores move 16-byte pieces (lane m of instruction j takes piece
+// j * 64 + rotl6(m, A) of the wave's chunk, a lane permutation inside a contiguous KiB), and lane <->
+// register butterfly stages (shuffle_stage: one lane bit traded for one register bit, 32-bit payload
+// per ds_bpermute_b32) convert between "a piece per lane" and "a layout row per lane": A stages on
+// the data (2^A pieces per row), B stages on the indices (2^B pieces of four indices per row), A
+// stages back on the result.  In between, lane = layout lane and the gather is the one of k_gather:
+// one ds_bpermute_b32 per 32-bit piece of an element, the source register being the element's own.
+//   stage s trades register (piece-in-row) bit s with lane bit 6 - A + s; afterwards lane k holds,
+//   as register j', the piece that lane (j' << (6 - A)) | (k & low) loaded as register k >> (6 - A):
+//   chunk piece (k >> (6-A)) * 64 + rotl6(that lane, A) = k * 2^A + j', piece j' of row k.
+template <int NV, int NVB>
+static __device__ __forceinline__ void row_stages(uint32_t (&r)[NV][4], uint32_t lane)
+{
+    if constexpr (NVB > 0) shuffle_stage<NV, 0>(r, lane, 1u << (6 - NVB));
+    if constexpr (NVB > 1) shuffle_stage<NV, 1>(r, lane, 1u << (7 - NVB));
+    if constexpr (NVB > 2) shuffle_stage<NV, 2>(r, lane, 1u << (8 - NVB));
+    if constexpr (NVB > 3) shuffle_stage<NV, 3>(r, lane, 1u << (9 - NVB));
+}
+
+template <int W, int NREG>
+__global__ __launch_bounds__(256) void k_gather_rows(const GatherArgs a)
+{
+    constexpr int NE = 1 << NREG;                 // elements per layout lane
+    constexpr int PL = NE * W;                    // bytes per layout lane (row): 32 .. 256
+    constexpr int M = PL / 16;                    // data pieces per row
+    constexpr int IQ = NE / 4;                    // index pieces per row
+    constexpr int A = (M == 2) ? 1 : (M == 4) ? 2 : (M == 8) ? 3 : 4;
+    constexpr int B = (IQ == 1) ? 0 : (IQ == 2) ? 1 : (IQ == 4) ? 2 : (IQ == 8) ? 3 : 4;
+    constexpr int DW = PL / 4;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wpg = blockDim.x >> 6;         // waves (chunks) per workgroup
+    const long long chunk = block_of_workgroup((long long)blockIdx.x, (a.nchunks + wpg - 1) / wpg, a.xcd_chunk) * wpg + (threadIdx.x >> 6);
+    if (chunk >= a.nchunks) return;               // whole wave leaves together
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(static_cast<const unsigned char *>(a.in) + (size_t)chunk * 64 * PL, 64 * PL);
+    const __amdgpu_buffer_rsrc_t rix = make_rsrc(reinterpret_cast<const unsigned char *>(a.idx) + (size_t)chunk * 64 * NE * 4, 64 * NE * 4);
+    const __amdgpu_buffer_rsrc_t rout = make_rsrc(static_cast<unsigned char *>(a.out) + (size_t)chunk * 64 * PL, 64 * PL);
+    const uint32_t piece_d = ((lane << A) | (lane >> (6 - A))) & 63u;      // rotl6(lane, A)
+    const uint32_t piece_i = B ? (((lane << B) | (lane >> (6 - B))) & 63u) : lane;
+
+    uint32_t dv[M][4], iv[IQ][4];
+#pragma unroll
+    for (int j = 0; j < M; ++j) {
+        const u32x4 v = buf_load16(rin, (j * 64 + piece_d) * 16);
+        dv[j][0] = v.x; dv[j][1] = v.y; dv[j][2] = v.z; dv[j][3] = v.w;
+    }
+#pragma unroll
+    for (int j = 0; j < IQ; ++j) {
+        const u32x4 v = buf_load16(rix, (j * 64 + piece_i) * 16);
+        iv[j][0] = v.x; iv[j][1] = v.y; iv[j][2] = v.z; iv[j][3] = v.w;
+    }
+    row_stages<M, A>(dv, lane);
+    row_stages<IQ, B>(iv, lane);
+
+    uint32_t own_lw = a.own_const;        // own axis coordinate: lane and wave contributions
+    if (!a.fast) {
+#pragma unroll
+        for (int b = 0; b < 6; ++b) own_lw ^= a.own_lane[b] & (0u - ((lane >> b) & 1u));
+        const uint32_t wv = (uint32_t)(chunk & ((1ll << a.nwave) - 1));
+        for (int b = 0; b < a.nwave; ++b) own_lw ^= a.own_wave[b] & (0u - ((wv >> b) & 1u));
+    }
+    uint32_t rv[M][4];
+#pragma unroll
+    for (int k = 0; k < DW; ++k) rv[k >> 2][k & 3] = 0;
+#pragma unroll
+    for (int r = 0; r < NE; ++r) {
+        const uint32_t s = iv[r >> 2][r & 3] & a.axis_mask;
+        uint32_t src_lane;
+        if (a.fast) {
+            src_lane = (lane & a.keep_mask) | (s << a.shift);
+        } else {
+            const uint32_t x = (s ^ own_lw ^ a.own_reg[r]) & a.axis_mask;
+            src_lane = lane;
+#pragma unroll
+            for (int b = 0; b < 6; ++b) src_lane ^= a.lane_delta[b] & (0u - ((x >> b) & 1u));
+        }
+        const int addr = (int)(src_lane << 2);
+        if constexpr (W == 8) {
+            rv[(2 * r) >> 2][(2 * r) & 3] = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)dv[(2 * r) >> 2][(2 * r) & 3]);
+            rv[(2 * r + 1) >> 2][(2 * r + 1) & 3] = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)dv[(2 * r + 1) >> 2][(2 * r + 1) & 3]);
+        } else if constexpr (W == 4) {
+            rv[r >> 2][r & 3] = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)dv[r >> 2][r & 3]);
+        } else {
+            constexpr int PER = 4 / W;            // elements per dword
+            const int q = r / PER;
+            const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)dv[q >> 2][q & 3]);
+            constexpr uint32_t EM = (W == 2) ? 0xffffu : 0xffu;
+            const int sh = (r % PER) * W * 8;
+            rv[q >> 2][q & 3] |= got & (EM << sh);
+        }
+    }
+    row_stages<M, A>(rv, lane);           // back to a piece per lane: the stages are their own inverses and commute
+#pragma unroll
+    for (int j = 0; j < M; ++j) {
+        const u32x4 v = {rv[j][0], rv[j][1], rv[j][2], rv[j][3]};
+        buf_store16(rout, (j * 64 + piece_d) * 16, v);
+    }
+}
+
 // Same gather with every global access fully coalesced.  A lane no longer stands for a layout lane:
 // lane k of a load or store instruction takes the k-th 16-byte (or 8-byte) piece of the chunk.  The
 // source values of the wave's chunk are staged in a wave-private LDS region, one row per layout
@@ -852,11 +952,12 @@ __global__ __launch_bounds__(256) void k_gather_staged(const GatherArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long chunk0 = block_of_workgroup((long long)blockIdx.x, (a.nchunks + 3) / 4, a.xcd_chunk) * 4;
+    const uint32_t wpg = blockDim.x >> 6;         // waves (chunks) per workgroup
+    const long long chunk0 = block_of_workgroup((long long)blockIdx.x, (a.nchunks + wpg - 1) / wpg, a.xcd_chunk) * wpg;
     const long long chunk = chunk0 + wave;
     const long long left = a.nchunks - chunk0;
-    const uint32_t chunks_here = left >= 4 ? 4u : (left > 0 ? (uint32_t)left : 0u);
-    // descriptors cover the (up to four) chunks of this workgroup: out-of-range lanes read zero and
+    const uint32_t chunks_here = left >= (long long)wpg ? wpg : (left > 0 ? (uint32_t)left : 0u);
+    // descriptors cover the chunks of this workgroup (one per wave): out-of-range lanes read zero and
     // write nothing
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(static_cast<const unsigned char *>(a.in) + (size_t)chunk0 * 64 * PL, chunks_here * 64 * PL);
     const __amdgpu_buffer_rsrc_t rix = make_rsrc(reinterpret_cast<const unsigned char *>(a.idx) + (size_t)chunk0 * 64 * NE * 4, chunks_here * 64 * NE * 4);
@@ -959,58 +1060,84 @@ __global__ __launch_bounds__(256) void k_gather_staged(const GatherArgs a)
     }
 }
 
+// `waves`: chunks (one per wave) a workgroup takes: 1, 2 or 4.
 template <int W, int NREG>
-static ll_status launch_gather_staged_t(const GatherArgs &a, int lds_alloc, hipStream_t stream)
+static ll_status launch_gather_staged_t(const GatherArgs &a, int waves, int lds_alloc, hipStream_t stream)
 {
     constexpr int PL = (1 << NREG) * W;
     if constexpr (PL < 16 || PL > 256 || (1 << NREG) < 4) {
         return fail(LL_ERR_UNSUPPORTED, "staged gather needs 16 to 256 bytes and at least 4 elements per lane");
     } else {
-        const long long grid = (a.nchunks + 3) / 4;
+        const long long grid = (a.nchunks + waves - 1) / waves;
         if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", grid);
-        constexpr int lds_bytes = 4 * 64 * PL;
-        // lds_alloc carries the occupancy cap (a workgroup has 4 chunks of `in` and `idx` in flight)
+        const int lds_bytes = waves * 64 * PL;
+        // lds_alloc carries the occupancy cap (every wave has a chunk of `in` and of `idx` in flight)
         const unsigned alloc = lds_alloc > lds_bytes ? (unsigned)lds_alloc : (unsigned)lds_bytes;
         if (alloc > 64u * 1024u) return fail(LL_ERR_INVALID_ARG, "internal: staged gather asked for %u bytes of LDS", alloc);
-        launch((k_gather_staged<W, NREG>), dim3((unsigned)grid), dim3(256), alloc, stream, a);
+        launch((k_gather_staged<W, NREG>), dim3((unsigned)grid), dim3(64u * (unsigned)waves), alloc, stream, a);
         return check_launch("gather kernel launch");
     }
 }
 
 template <int W, int NREG>
-static ll_status launch_gather_t(const GatherArgs &a, hipStream_t stream)
+static ll_status launch_gather_rows_t(const GatherArgs &a, int waves, int lds_alloc, hipStream_t stream)
+{
+    constexpr int PL = (1 << NREG) * W;
+    if constexpr (PL < 32 || PL > 256 || (1 << NREG) < 4) {
+        return fail(LL_ERR_UNSUPPORTED, "row-shuffle gather needs 32 to 256 bytes and at least 4 elements per lane");
+    } else {
+        const long long grid = (a.nchunks + waves - 1) / waves;
+        if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", grid);
+        if (lds_alloc < 0 || lds_alloc > 64 * 1024) return fail(LL_ERR_INVALID_ARG, "internal: row-shuffle gather asked for %d bytes of LDS", lds_alloc);
+        launch((k_gather_rows<W, NREG>), dim3((unsigned)grid), dim3(64u * (unsigned)waves), (size_t)lds_alloc, stream, a);   // LDS only as the occupancy cap
+        return check_launch("gather kernel launch");
+    }
+}
+
+template <int W, int NREG>
+static ll_status launch_gather_t(const GatherArgs &a, int waves, hipStream_t stream)
 {
     if constexpr ((1 << NREG) * W < 4 || (1 << NREG) * W > 256) {
         return fail(LL_ERR_UNSUPPORTED, "gather needs 4 to 256 bytes per lane (got %d)", (1 << NREG) * W);
     } else {
-        const long long grid = (a.nchunks + 3) / 4;
+        const long long grid = (a.nchunks + waves - 1) / waves;
         if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", grid);
-        launch((k_gather<W, NREG>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+        launch((k_gather<W, NREG>), dim3((unsigned)grid), dim3(64u * (unsigned)waves), 0, stream, a);
         return check_launch("gather kernel launch");
     }
 }
 
 template <int W>
-static ll_status launch_gather_w(const GatherArgs &a, int lds_alloc, hipStream_t stream)
+static ll_status launch_gather_w(const GatherArgs &a, int waves, int lds_alloc, hipStream_t stream)
 {
+    if (a.staged == 2) {
+        switch (a.nreg) {
+        case 2: return launch_gather_rows_t<W, 2>(a, waves, lds_alloc, stream);
+        case 3: return launch_gather_rows_t<W, 3>(a, waves, lds_alloc, stream);
+        case 4: return launch_gather_rows_t<W, 4>(a, waves, lds_alloc, stream);
+        case 5: return launch_gather_rows_t<W, 5>(a, waves, lds_alloc, stream);
+        case 6: return launch_gather_rows_t<W, 6>(a, waves, lds_alloc, stream);
+        default: return fail(LL_ERR_UNSUPPORTED, "row-shuffle gather needs 2 to 6 register bits (got %d)", a.nreg);
+        }
+    }
     if (a.staged) {
         switch (a.nreg) {
-        case 2: return launch_gather_staged_t<W, 2>(a, lds_alloc, stream);
-        case 3: return launch_gather_staged_t<W, 3>(a, lds_alloc, stream);
-        case 4: return launch_gather_staged_t<W, 4>(a, lds_alloc, stream);
-        case 5: return launch_gather_staged_t<W, 5>(a, lds_alloc, stream);
-        case 6: return launch_gather_staged_t<W, 6>(a, lds_alloc, stream);
+        case 2: return launch_gather_staged_t<W, 2>(a, waves, lds_alloc, stream);
+        case 3: return launch_gather_staged_t<W, 3>(a, waves, lds_alloc, stream);
+        case 4: return launch_gather_staged_t<W, 4>(a, waves, lds_alloc, stream);
+        case 5: return launch_gather_staged_t<W, 5>(a, waves, lds_alloc, stream);
+        case 6: return launch_gather_staged_t<W, 6>(a, waves, lds_alloc, stream);
         default: return fail(LL_ERR_UNSUPPORTED, "staged gather needs 2 to 6 register bits (got %d)", a.nreg);
         }
     }
     switch (a.nreg) {
-    case 0: return launch_gather_t<W, 0>(a, stream);
-    case 1: return launch_gather_t<W, 1>(a, stream);
-    case 2: return launch_gather_t<W, 2>(a, stream);
-    case 3: return launch_gather_t<W, 3>(a, stream);
-    case 4: return launch_gather_t<W, 4>(a, stream);
-    case 5: return launch_gather_t<W, 5>(a, stream);
-    case 6: return launch_gather_t<W, 6>(a, stream);
+    case 0: return launch_gather_t<W, 0>(a, waves, stream);
+    case 1: return launch_gather_t<W, 1>(a, waves, stream);
+    case 2: return launch_gather_t<W, 2>(a, waves, stream);
+    case 3: return launch_gather_t<W, 3>(a, waves, stream);
+    case 4: return launch_gather_t<W, 4>(a, waves, stream);
+    case 5: return launch_gather_t<W, 5>(a, waves, stream);
+    case 6: return launch_gather_t<W, 6>(a, waves, stream);
     default: return fail(LL_ERR_UNSUPPORTED, "gather supports at most 6 register bits (got %d)", a.nreg);
     }
 }
@@ -1549,14 +1676,15 @@ ll_status launch_gather_phased(const GatherGenArgs &a, int elem_bytes, void *str
     }
 }
 
-ll_status launch_gather(const GatherArgs &a, int elem_bytes, int lds_alloc, void *stream)
+ll_status launch_gather(const GatherArgs &a, int elem_bytes, int waves, int lds_alloc, void *stream)
 {
+    if (waves != 1 && waves != 2 && waves != 4) return fail(LL_ERR_INVALID_ARG, "internal: %d waves per gather workgroup", waves);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {
-    case 1: return launch_gather_w<1>(a, lds_alloc, s);
-    case 2: return launch_gather_w<2>(a, lds_alloc, s);
-    case 4: return launch_gather_w<4>(a, lds_alloc, s);
-    case 8: return launch_gather_w<8>(a, lds_alloc, s);
+    case 1: return launch_gather_w<1>(a, waves, lds_alloc, s);
+    case 2: return launch_gather_w<2>(a, waves, lds_alloc, s);
+    case 4: return launch_gather_w<4>(a, waves, lds_alloc, s);
+    case 8: return launch_gather_w<8>(a, waves, lds_alloc, s);
     default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
     }
 }

@@ -114,7 +114,9 @@ struct GatherArgs {
     int nwave;
     uint32_t own_const;       // affine layouts: constant part of every element's axis coordinate
     int xcd_chunk;            // log2 of the consecutive workgroups' worth of chunks one XCD takes, -1: natural order
-    int staged;               // 1: coalesced global access with the source staged in wave-private LDS
+    int staged;               // 0: lane = layout lane from the start (a lane's elements are one global access);
+                              // 1: coalesced 16-byte pieces, source rows staged in wave-private LDS;
+                              // 2: coalesced 16-byte pieces, lane <-> register butterflies, then as 0
 };
 
 // General gather (paper Sec. 5.5 extended): the axis may occupy register, lane and wave bits.  A
@@ -162,7 +164,7 @@ ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose,
                      void *stream);
 ll_status launch_lds_tr(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_bytes, void *stream);
 ll_status launch_pull(const PullArgs &a, int elem_bytes, int src_iters, int vec_bits, int lds_bytes, void *stream);
-ll_status launch_gather(const GatherArgs &a, int elem_bytes, int lds_alloc, void *stream);
+ll_status launch_gather(const GatherArgs &a, int elem_bytes, int waves, int lds_alloc, void *stream);
 ll_status launch_copy(const void *src, void *dst, long long bytes, int xcd_chunk_bits, void *stream);
 
 }  // namespace ll

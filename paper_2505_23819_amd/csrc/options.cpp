@@ -40,6 +40,7 @@ const Field kFields[] = {
     LL_FIELD(gather_swizzle_always, "LL_GATHER_SWIZZLE_ALWAYS"),
     LL_FIELD(copy_xcd_chunk, "LL_COPY_XCD_CHUNK"),
     LL_FIELD(debug, "LL_DEBUG"),
+    LL_FIELD(gather_waves, "LL_GATHER_WAVES"),
 };
 #undef LL_FIELD
 int32_t &field(ll_options *o, size_t offset) { return *reinterpret_cast<int32_t *>(reinterpret_cast<char *>(o) + offset); }

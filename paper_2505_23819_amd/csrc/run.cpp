@@ -76,7 +76,8 @@ struct GatherChoice {
     bool memory = false;               // memory layout: no registers, lanes or waves
     GatherArgs wave = {};              // shuffle / wave-staged kernels
     GatherGenArgs gen = {};            // workgroup-staged kernel
-    int lds_alloc = 0;                 // wave-staged kernel: dynamic LDS to ask for (caps the workgroups per CU)
+    int lds_alloc = 0;                 // wave-level kernels: dynamic LDS to ask for (caps the workgroups per CU)
+    int waves = 4;                     // wave-level kernels: waves (chunks) per workgroup
     int thread_bits = 8;               // workgroup-staged kernel: log2 threads per workgroup
 };
 
@@ -129,9 +130,12 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, con
     // kernel unless the options ask for one of the wave kernels.
     // One-byte elements need one shuffle each however many a lane holds (measured 4.8 TB/s with 16 per
     // lane against 5.7-5.9 staged), so they take the general kernel as well.
-    const bool narrow = (1 << nreg) * elem_bytes < 16 || elem_bytes == 1;
-    const bool want_general = opt.gather_kernel == LL_GATHER_BLOCK_STAGED ||
-                              (opt.gather_kernel != LL_GATHER_SHUFFLE && opt.gather_kernel != LL_GATHER_WAVE_STAGED && narrow);
+    // Lanes that hold 128 bytes or more: the wave kernels need 32 to 64 registers each for data, indices
+    // and results; measured 5.8-6.4 TB/s for them against 6.3-6.6 for the workgroup-staged kernel.
+    const bool narrow = (1 << nreg) * elem_bytes < 16 || elem_bytes == 1 || (1 << nreg) * elem_bytes >= 128;
+    const bool wave_kernel_asked = opt.gather_kernel == LL_GATHER_SHUFFLE || opt.gather_kernel == LL_GATHER_WAVE_STAGED ||
+                                   opt.gather_kernel == LL_GATHER_SHUFFLE_ROWS;
+    const bool want_general = opt.gather_kernel == LL_GATHER_BLOCK_STAGED || (!wave_kernel_asked && narrow);
     if (lane_only && !want_general) {
         GatherArgs &a = c->wave;
         std::memset(&a, 0, sizeof(a));
@@ -165,15 +169,37 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, con
             }
         }
         // Rows of 16 bytes are already one coalesced vector per lane: shuffle directly.  Wider rows would
-        // make every lane's accesses strided, so they are staged through wave-private LDS instead.
+        // make every lane's accesses strided (measured 4.58 TB/s on config 5), so they are moved in
+        // coalesced 16-byte pieces and either staged through wave-private LDS or brought into "one row
+        // per lane" by lane <-> register butterflies and gathered with ds_bpermute_b32 as Sec. 5.5 does.
+        // Measured (TB/s, staged / butterflies, each with one wave per workgroup): rows of 32 bytes
+        // 6.83 / 6.51 (config 5), 6.60 / 6.62, 6.56 / 6.54; 64 bytes 6.37 / 6.56, 6.59 / 6.75, 6.67 / 6.82;
+        // 128 bytes 5.81 / 6.38, 5.95 / 6.39, 5.98 / 6.35 (workgroup-staged kernel: 6.3, 6.6, 6.5); 256 bytes
+        // 5.68 / 5.70 and 5.70 / 5.50, against 5.89 and 6.17 staged by four waves per workgroup (workgroup-
+        // staged kernel: 6.28, 6.16).  Hence 32 bytes: staged, 64: butterflies, more: not here at all.
         const int row_bytes = (1 << nreg) * elem_bytes;
-        a.staged = (row_bytes > 16 && row_bytes <= 256 && nreg >= 2) ? 1 : 0;
+        a.staged = (row_bytes > 16 && row_bytes <= 256 && nreg >= 2) ? ((row_bytes == 64 || row_bytes == 128) ? 2 : 1) : 0;
         if (opt.gather_kernel == LL_GATHER_SHUFFLE) a.staged = 0;
         if (opt.gather_kernel == LL_GATHER_WAVE_STAGED) a.staged = row_bytes >= 16 && row_bytes <= 256 && nreg >= 2;
-        c->kernel = a.staged ? LL_GATHER_WAVE_STAGED : LL_GATHER_SHUFFLE;
-        a.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, -1);
-        // occupancy cap of the wave-staged kernel: a workgroup has 4 chunks of `in` and `idx` in flight
-        c->lds_alloc = lds_alloc_for(4u * 64u * ((unsigned)row_bytes + 4u * (1u << nreg)), (unsigned)opt_or(opt.gather_inflight_bytes, 49152), 0);
+        if (opt.gather_kernel == LL_GATHER_SHUFFLE_ROWS) a.staged = (row_bytes >= 32 && row_bytes <= 256 && nreg >= 2) ? 2 : 0;
+        c->kernel = a.staged == 2 ? LL_GATHER_SHUFFLE_ROWS : a.staged ? LL_GATHER_WAVE_STAGED : LL_GATHER_SHUFFLE;
+        // The kernels with coalesced pieces run ONE wave per workgroup (a wave's chunk is its own: it goes
+        // on as soon as its loads have landed), a number of waves per CU set through the LDS share, and an
+        // XCD-aware order.  Measured on MI355X (64 x 256 tiles and relatives, 512 MiB of `in`, TB/s):
+        // config 5 four waves per workgroup 6.59, one wave 6.68, with 32 consecutive chunks per XCD 6.84;
+        // 5 waves per CU 5.0, 8: 6.35-6.8, 10: 6.84 (6 KiB loaded per wave), 16: 6.55 (4 KiB per wave).
+        const bool one_wave = a.staged && row_bytes < 256;
+        c->waves = (opt.gather_waves == 1 || opt.gather_waves == 2 || opt.gather_waves == 4) ? opt.gather_waves : (one_wave ? 1 : 4);
+        const unsigned load_bytes = 64u * ((unsigned)row_bytes + 4u * (1u << nreg));           // per wave: `in` and `idx`
+        const unsigned wave_bytes = load_bytes + 64u * (unsigned)row_bytes;                       // ... and `out`
+        // 256 KiB of consecutive chunks (in + idx + out) per XCD; 64 KiB of loads in flight per CU, but 8 to 16 waves
+        a.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, one_wave ? xcd_chunk_bits_for(256 * 1024, (long long)wave_bytes * c->waves) : -1);
+        c->lds_alloc = 0;
+        if (a.staged) {
+            unsigned groups = (unsigned)opt_or(opt.gather_inflight_bytes, one_wave ? 65536 : 49152) / (load_bytes * (unsigned)c->waves);
+            if (opt.gather_inflight_bytes == LL_AUTO && one_wave) groups = std::min(std::max(groups, 8u / (unsigned)c->waves), 16u);
+            c->lds_alloc = lds_alloc_for(1u, std::max(groups, 1u), 0);
+        }
         return LL_OK;
     }
 
@@ -422,7 +448,7 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const ll_opti
     a.idx = idx;
     a.out = out;
     a.nchunks = ntiles << a.nwave;
-    return launch_gather(a, elem_bytes, c.lds_alloc, stream);
+    return launch_gather(a, elem_bytes, c.waves, c.lds_alloc, stream);
 }
 
 }  // namespace ll

@@ -75,19 +75,22 @@ def test_gather_full_size_sampled():
 
 
 def test_gather_both_kernels_agree():
-    """The shuffle kernel (one ds_bpermute_b32 per element) and the staged kernel on config 5."""
+    """The shuffle kernels (one ds_bpermute_b32 per element; a lane's row as it lies in memory, or
+    coalesced pieces and lane <-> register butterflies) and the staged kernel on config 5, with one,
+    two and four waves per workgroup."""
     cfg = wl.config(5)
     layout = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.src_bases)
     nt = 37
     inp, idx = cfg.gen_data(0, nt, "cuda"), cfg.gen_idx(0, nt, "cuda")
     want = oracle.gather(cfg.src_bases, cfg.out_dim_bits, cfg.axis, wl.to_numpy_bits(inp), idx.cpu().numpy())
-    for staged in (ll.LL_GATHER_SHUFFLE, ll.LL_GATHER_WAVE_STAGED):
-        opts = ll.ll_options_init(gather_kernel=staged)
-        assert ll.ll_gather_info(layout, cfg.axis, cfg.elem_bytes, opts)["kernel"] == staged
-        out = torch.zeros_like(inp)
-        ll.ll_gather(layout, cfg.axis, cfg.elem_bytes, inp, idx, out, nt, opts=opts)
-        torch.cuda.synchronize()
-        assert np.array_equal(wl.to_numpy_bits(out), want), f"staged={staged}"
+    for staged in (ll.LL_GATHER_SHUFFLE, ll.LL_GATHER_WAVE_STAGED, ll.LL_GATHER_SHUFFLE_ROWS):
+        for waves in (-1, 1, 2, 4):
+            opts = ll.ll_options_init(gather_kernel=staged, gather_waves=waves)
+            assert ll.ll_gather_info(layout, cfg.axis, cfg.elem_bytes, opts)["kernel"] == staged
+            out = torch.zeros_like(inp)
+            ll.ll_gather(layout, cfg.axis, cfg.elem_bytes, inp, idx, out, nt, opts=opts)
+            torch.cuda.synchronize()
+            assert np.array_equal(wl.to_numpy_bits(out), want), f"kernel={staged} waves={waves}"
 
 
 @pytest.mark.parametrize("case", wl.broadcast_cases(), ids=lambda c: c.name.split(" (")[0].replace(" ", "_"))

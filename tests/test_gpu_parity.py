@@ -151,12 +151,15 @@ def test_gather_random_lane_axis(w, nreg, nwave, axis_bits):
     idx[::17] += 1 << axis_bits                        # out-of-range entries wrap
     want = oracle.gather(bases, dims, 0, inp, idx)
     wave_ok = (1 << nreg) * w >= 4
-    for kernel, allowed in ((None, ("shuffle", "wave_staged", "block_staged")),
+    for kernel, allowed in ((None, ("shuffle", "wave_staged", "shuffle_rows", "block_staged")),
                             (ll.LL_GATHER_SHUFFLE, ("shuffle",) if wave_ok else ("block_staged",)),
                             (ll.LL_GATHER_WAVE_STAGED, ("shuffle", "wave_staged") if wave_ok else ("block_staged",)),
+                            (ll.LL_GATHER_SHUFFLE_ROWS, ("shuffle", "shuffle_rows") if wave_ok else ("block_staged",)),
                             (ll.LL_GATHER_BLOCK_STAGED, ("block_staged",))):
-        opts = None if kernel is None else ll.ll_options_init(gather_kernel=kernel)
+        opts = None if kernel is None else ll.ll_options_init(gather_kernel=kernel, gather_waves=int(rng.choice([-1, 1, 2, 4])))
         assert ll.ll_gather_info(layout, 0, w, opts)["kernel_name"] in allowed, kernel
+        if kernel == ll.LL_GATHER_SHUFFLE_ROWS and wave_ok and 32 <= (1 << nreg) * w <= 256:
+            assert ll.ll_gather_info(layout, 0, w, opts)["kernel_name"] == "shuffle_rows"
         got = run_gather(layout, 0, inp, idx, d, opts)
         assert np.array_equal(got, want), kernel
 
@@ -496,7 +499,7 @@ def test_gather_under_affine_layouts(axis):
     idx = rng.integers(0, 1 << cfg.out_dim_bits[axis], size=ntiles << cfg.d, dtype=np.int32)
     for off in ((1 << cfg.d) - 1, int(rng.integers(1, 1 << cfg.d))):
         layout = ll.ll_layout_with_offset(base, off)
-        for staged in (ll.LL_GATHER_SHUFFLE, ll.LL_GATHER_WAVE_STAGED):
+        for staged in (ll.LL_GATHER_SHUFFLE, ll.LL_GATHER_WAVE_STAGED, ll.LL_GATHER_SHUFFLE_ROWS):
             got = run_gather(layout, axis, inp, idx, cfg.d, ll.ll_options_init(gather_kernel=staged))
             assert np.array_equal(got, oracle.gather_affine(cfg.src_bases, off, cfg.out_dim_bits, axis, inp, idx)), (off, staged)
 

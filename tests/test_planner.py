@@ -301,7 +301,7 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
                                 [1 << (4 + k) for k in range(6)])
     info = ll.ll_gather_info(big, 1, 4)
     assert info["kernel_name"] == "block_staged" and info["axis_wave_bits"] == 6 and info["block_bytes"] == 8192
-    assert ll.ll_gather_info(big, 0, 4)["kernel_name"] == "wave_staged"
+    assert ll.ll_gather_info(big, 0, 4)["kernel_name"] == "shuffle_rows"      # 64 bytes per lane, axis on lane bits
     # 8192 rows of 32 two-byte elements: a block closed under the rows would need runs under 64 bytes
     # to fit LDS; the aligned 512 KiB range is walked through LDS in chunks.  Four times the rows: the
     # range is 2 MiB and the rows are gathered straight from memory
