@@ -82,6 +82,10 @@ def _load():
         lib.oracle_gather.argtypes = [u64p, ctypes.c_int, i32p, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_int, ctypes.c_void_p, i32p, ctypes.c_void_p,
                                       ctypes.c_int64]
+        lib.oracle_gather_table.restype = ctypes.c_int
+        lib.oracle_gather_table.argtypes = lib.oracle_gather.argtypes
+        lib.oracle_convert_general_table.restype = ctypes.c_int
+        lib.oracle_convert_general_table.argtypes = lib.oracle_convert_general.argtypes
         lib.oracle_wavefronts.restype = ctypes.c_int
         lib.oracle_wavefronts.argtypes = [u64p, u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                           ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p,
@@ -130,14 +134,16 @@ def right_inverse_table(bases: Sequence[int], d_out: int) -> np.ndarray:
     return table
 
 
-def convert_general(bases_a: Sequence[int], bases_b: Sequence[int], d_out: int, src: np.ndarray) -> np.ndarray:
-    """Conversion with broadcasting: dst[hB] = src[A^+(B hB)]; src holds ntiles * 2^len(A) elements."""
+def convert_general(bases_a: Sequence[int], bases_b: Sequence[int], d_out: int, src: np.ndarray,
+                    table: bool = False) -> np.ndarray:
+    """Conversion with broadcasting: dst[hB] = src[A^+(B hB)]; src holds ntiles * 2^len(A) elements.
+    table=True: the same with the pull map tabulated once and tiles on all host threads."""
     da, db = len(bases_a), len(bases_b)
     _check_img(src, da, "src")
     ntiles = src.size >> da
     dst = np.empty(ntiles << db, dtype=src.dtype)
-    rc = _load().oracle_convert_general(_u64(bases_a), da, _u64(bases_b), db, d_out, src.itemsize,
-                                        src.ctypes.data, dst.ctypes.data, ntiles)
+    fn = _load().oracle_convert_general_table if table else _load().oracle_convert_general
+    rc = fn(_u64(bases_a), da, _u64(bases_b), db, d_out, src.itemsize, src.ctypes.data, dst.ctypes.data, ntiles)
     if rc != OK:
         raise OracleError(rc, "convert_general")
     return dst
@@ -190,8 +196,9 @@ def convert(bases_a: Sequence[int], bases_b: Sequence[int], src: np.ndarray,
 
 
 def gather(bases_l: Sequence[int], out_dim_bits: Sequence[int], axis: int,
-           inp: np.ndarray, idx: np.ndarray) -> np.ndarray:
-    """out[.., i, ..] = in[.., idx[.., i, ..], ..] along `axis`, all images under L."""
+           inp: np.ndarray, idx: np.ndarray, table: bool = False) -> np.ndarray:
+    """out[.., i, ..] = in[.., idx[.., i, ..], ..] along `axis`, all images under L.
+    table=True: the same with L and its inverse tabulated once and tiles on all host threads."""
     d = len(bases_l)
     _check_img(inp, d, "in")
     _check_img(idx, d, "idx")
@@ -200,10 +207,9 @@ def gather(bases_l: Sequence[int], out_dim_bits: Sequence[int], axis: int,
     ntiles = inp.size >> d
     out = np.empty_like(inp)
     dims = (ctypes.c_int32 * len(out_dim_bits))(*[int(b) for b in out_dim_bits])
-    rc = _load().oracle_gather(_u64(bases_l), d, dims, len(out_dim_bits), int(axis),
-                               inp.itemsize, inp.ctypes.data,
-                               idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                               out.ctypes.data, ntiles)
+    fn = _load().oracle_gather_table if table else _load().oracle_gather
+    rc = fn(_u64(bases_l), d, dims, len(out_dim_bits), int(axis), inp.itemsize, inp.ctypes.data,
+            idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), out.ctypes.data, ntiles)
     if rc != OK:
         raise OracleError(rc, "gather")
     return out

@@ -194,6 +194,49 @@ int oracle_convert_general(const uint64_t *basesA, int dA, const uint64_t *bases
 }
 
 /*
+ * Same result as oracle_convert_general.  The pull map hB -> A^+(B(hB)) does not
+ * depend on the tile: it is tabulated once with the very statements of the plain
+ * function, and the tile loop runs on all host threads.  For checking whole
+ * full-size images, where the plain function would take minutes.
+ */
+int oracle_convert_general_table(const uint64_t *basesA, int dA, const uint64_t *basesB, int dB, int d_out,
+                                 int elem_bytes, const void *src, void *dst, int64_t ntiles)
+{
+    if (!basesA || !basesB || dA < 0 || dA > 30 || dB < 0 || dB > 30 || d_out < 0 || d_out > 30 ||
+        elem_bytes <= 0 || ntiles < 0)
+        return ORACLE_ERR_ARG;
+    if (ntiles > 0 && (!src || !dst))
+        return ORACLE_ERR_ARG;
+    const uint64_t nA = 1ull << dA, nB = 1ull << dB;
+    uint32_t *invA = (uint32_t *)malloc((1ull << d_out) * sizeof(uint32_t));
+    uint32_t *invB = (uint32_t *)malloc((1ull << d_out) * sizeof(uint32_t));
+    uint32_t *pull = (uint32_t *)malloc(nB * sizeof(uint32_t));
+    if (!invA || !invB || !pull) { free(invA); free(invB); free(pull); return ORACLE_ERR_ALLOC; }
+    int rc = oracle_right_inverse_table(basesA, dA, d_out, invA);
+    if (rc == ORACLE_OK)
+        rc = oracle_right_inverse_table(basesB, dB, d_out, invB);   /* only to check that B is surjective */
+    if (rc != ORACLE_OK) { free(invA); free(invB); free(pull); return rc; }
+    for (uint64_t hB = 0; hB < nB; ++hB) {
+        const uint64_t x = oracle_apply(basesB, dB, hB);
+        pull[hB] = invA[x];
+    }
+    const unsigned char *s = (const unsigned char *)src;
+    unsigned char *o = (unsigned char *)dst;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t t = 0; t < ntiles; ++t) {
+        for (uint64_t hB = 0; hB < nB; ++hB)
+            memcpy(o + ((uint64_t)t * nB + hB) * (uint64_t)elem_bytes,
+                   s + ((uint64_t)t * nA + pull[hB]) * (uint64_t)elem_bytes, (size_t)elem_bytes);
+    }
+    free(invA);
+    free(invB);
+    free(pull);
+    return ORACLE_OK;
+}
+
+/*
  * The same with affine layouts (Conclusions: y = A x xor b): slot hA of the
  * source holds the logical element A(hA) xor offA, slot hB of the destination
  * must hold B(hB) xor offB; the canonical source slot of a logical element x is
@@ -373,6 +416,60 @@ int oracle_gather(const uint64_t *basesL, int d, const int32_t *out_dim_bits,
         }
     }
     free(invL);
+    return ORACLE_OK;
+}
+
+/*
+ * Same result as oracle_gather.  L(h) and L^-1 are tabulated once (L(h) with the
+ * very statement of the plain function) and the tile loop runs on all host
+ * threads.  For checking whole full-size images.
+ */
+int oracle_gather_table(const uint64_t *basesL, int d, const int32_t *out_dim_bits,
+                        int n_out_dims, int axis, int elem_bytes, const void *in,
+                        const int32_t *idx, void *out, int64_t ntiles)
+{
+    if (!basesL || !out_dim_bits || d < 0 || d > 30 || elem_bytes <= 0 ||
+        ntiles < 0 || n_out_dims <= 0)
+        return ORACLE_ERR_ARG;
+    if (axis < 0 || axis >= n_out_dims)
+        return ORACLE_ERR_AXIS;
+    if (ntiles > 0 && (!in || !idx || !out))
+        return ORACLE_ERR_ARG;
+    int total = 0, axis_shift = 0;
+    for (int k = n_out_dims - 1; k >= 0; --k) { /* last dim sits lowest */
+        if (k == axis) axis_shift = total;
+        total += out_dim_bits[k];
+    }
+    if (total != d)
+        return ORACLE_ERR_ARG;
+    const int axis_bits = out_dim_bits[axis];
+    const uint64_t axis_len_mask = (1ull << axis_bits) - 1;
+    const uint64_t n = 1ull << d;
+    uint32_t *invL = (uint32_t *)malloc(n * sizeof(uint32_t));
+    uint32_t *fwdL = (uint32_t *)malloc(n * sizeof(uint32_t));
+    if (!invL || !fwdL) { free(invL); free(fwdL); return ORACLE_ERR_ALLOC; }
+    int rc = oracle_inverse_table(basesL, d, invL);
+    if (rc != ORACLE_OK) { free(invL); free(fwdL); return rc; }
+    for (uint64_t h = 0; h < n; ++h)
+        fwdL[h] = (uint32_t)oracle_apply(basesL, d, h);
+    const unsigned char *pi = (const unsigned char *)in;
+    unsigned char *po = (unsigned char *)out;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const uint64_t base = (uint64_t)t * n;
+        for (uint64_t h = 0; h < n; ++h) {
+            uint64_t x = fwdL[h];
+            uint64_t s = (uint64_t)(uint32_t)idx[base + h] & axis_len_mask;
+            uint64_t xs = (x & ~(axis_len_mask << axis_shift)) | (s << axis_shift);
+            uint64_t hs = invL[xs];
+            memcpy(po + (base + h) * (uint64_t)elem_bytes,
+                   pi + (base + hs) * (uint64_t)elem_bytes, (size_t)elem_bytes);
+        }
+    }
+    free(invL);
+    free(fwdL);
     return ORACLE_OK;
 }
 

@@ -542,10 +542,10 @@ def test_convert_general_paper_broadcast_example(golden_dir):
     assert np.array_equal(back, src)
 
 
-def test_convert_spot_values_of_the_configurations():
+def test_convert_spot_values_of_the_configurations(golden_dir):
     """tests/golden/config_spot_values.txt: hand-derived (source index, destination index) pairs of
     configs 1-3 and the image of every source bit of config 1."""
-    rows = [l.split() for l in open("tests/golden/config_spot_values.txt") if l.strip() and not l.startswith("#")]
+    rows = [l.split() for l in open(os.path.join(golden_dir, "config_spot_values.txt")) if l.strip() and not l.startswith("#")]
     images = {}
     for cid in (1, 2, 3):
         cfg = wl.config(cid)
@@ -561,3 +561,57 @@ def test_convert_spot_values_of_the_configurations():
             assert int(images[int(r[0])][int(r[2], 16)]) == int(r[1], 16), r
             seen += 1
     assert seen == 12
+
+
+# ----------------------------------------------------------------------------
+# table variants used to check whole full-size images: the same results as the plain functions
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("axis", [0, 1])
+def test_gather_table_matches_take_along_axis_and_the_plain_function(axis):
+    rng = np.random.default_rng(180 + axis)
+    for dims, dtype, ntiles in (([3, 4], np.uint16, 1), ([5, 2], np.uint8, 37), ([4, 6], np.uint32, 5), ([6, 8], np.uint64, 3)):
+        d = sum(dims)
+        bases = random_invertible(rng, d)
+        inp = rng.integers(0, np.iinfo(dtype).max, size=ntiles << d, dtype=dtype)
+        idx = rng.integers(-(1 << dims[axis]), 2 << dims[axis], size=ntiles << d, dtype=np.int32)     # out of range: wraps
+        out = oracle.gather(bases, dims, axis, inp, idx, table=True)
+        assert np.array_equal(out, oracle.gather(bases, dims, axis, inp, idx))
+        shape = (1 << dims[0], 1 << dims[1])
+        for t in range(ntiles):                       # and against numpy on the logical views, tile by tile
+            sl = slice(t << d, (t + 1) << d)
+            in_log, _ = logical_views(bases, d, inp[sl])
+            idx_log, _ = logical_views(bases, d, idx[sl])
+            out_log, _ = logical_views(bases, d, out[sl])
+            want = np.take_along_axis(in_log.reshape(shape), (idx_log.reshape(shape) & ((1 << dims[axis]) - 1)).astype(np.int64), axis=axis)
+            assert np.array_equal(out_log.reshape(shape), want)
+
+
+def test_gather_table_rejects_what_the_plain_function_rejects():
+    singular = [1, 2, 3, 8]
+    img = np.zeros(16, dtype=np.uint16)
+    idx = np.zeros(16, dtype=np.int32)
+    for table in (False, True):
+        with pytest.raises(oracle.OracleError):
+            oracle.gather(singular, [2, 2], 0, img, idx, table=table)
+        with pytest.raises(oracle.OracleError):
+            oracle.gather([1, 2, 4, 8], [2, 2], 2, img, idx, table=table)
+
+
+def test_convert_general_table_matches_the_plain_function_and_the_logical_element():
+    rng = np.random.default_rng(250)
+    for da, db, d_out, ntiles in [(5, 4, 4, 1), (4, 6, 4, 19), (7, 7, 5, 3), (10, 9, 8, 6), (8, 8, 8, 2)]:
+        for dtype in (np.uint8, np.uint32, np.uint64):
+            a, b = random_surjective(rng, da, d_out), random_surjective(rng, db, d_out)
+            src = rng.integers(0, np.iinfo(dtype).max, size=ntiles << da, dtype=dtype)      # replicas differ
+            got = oracle.convert_general(a, b, d_out, src, table=True)
+            assert np.array_equal(got, oracle.convert_general(a, b, d_out, src))
+            # independent of the plain function: from a consistent source, slot hB receives X[B hB]
+            x_log = rng.integers(0, np.iinfo(dtype).max, size=ntiles << d_out, dtype=dtype).reshape(ntiles, -1)
+            img_a = np.array([np_apply(a, d_out, h) for h in range(1 << da)])
+            img_b = np.array([np_apply(b, d_out, h) for h in range(1 << db)])
+            src2 = np.stack([x_log[t][img_a] for t in range(ntiles)]).reshape(-1)
+            want = np.stack([x_log[t][img_b] for t in range(ntiles)]).reshape(-1)
+            assert np.array_equal(oracle.convert_general(a, b, d_out, src2, table=True), want)
+    with pytest.raises(oracle.OracleError):
+        oracle.convert_general([1, 1], [1, 2], 2, np.zeros(4, dtype=np.uint8), table=True)      # A misses part of the tensor

@@ -147,18 +147,28 @@ def _swap_rc(spec: Sequence[str]) -> List[str]:
     return [("row" if s.startswith("col") else "col") + s[3:] for s in spec]
 
 
+def _rank_gf2(cols: Sequence[int]) -> int:
+    """Rank over GF(2) of integers read as bit vectors (plain XOR elimination on the leading bit).
+    An acceptance test for the sampler below: no layout is applied, composed or inverted here."""
+    pivots = {}                                  # leading bit -> reduced vector
+    for c in cols:
+        while c:
+            top = c.bit_length() - 1
+            if top not in pivots:
+                pivots[top] = c
+                break
+            c ^= pivots[top]
+    return len(pivots)
+
+
 def random_invertible_bases(seed: int, d: int) -> List[int]:
-    """d columns drawn uniformly from d-bit values; the whole matrix is redrawn until
-    the 2**d images are all distinct (rejection sampling of an invertible matrix)."""
+    """d columns drawn uniformly from d-bit values; the whole matrix is redrawn until it has
+    rank d (rejection sampling of an invertible matrix)."""
     attempt = 0
-    h = np.arange(1 << d, dtype=np.uint64)
     while True:
         raw = raw_bits(seed, attempt * d, d).numpy().view(np.uint64)
         cols = [int(x) & ((1 << d) - 1) for x in raw]
-        img = np.zeros(1 << d, dtype=np.uint64)
-        for k, c in enumerate(cols):
-            img ^= ((h >> np.uint64(k)) & np.uint64(1)) * np.uint64(c)
-        if np.unique(img).size == (1 << d):
+        if _rank_gf2(cols) == d:
             return cols
         attempt += 1
 
