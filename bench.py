@@ -43,6 +43,9 @@ def main() -> int:
     ap.add_argument("--strategy", type=int, default=None,
                     help="force a conversion strategy for every plan (3: element-wide LDS, 4: 128-bit LDS "
                          "where it applies); default: the planner's choice")
+    ap.add_argument("--opt", action="append", default=[], metavar="FIELD=VALUE",
+                    help="set a field of ll_options for the main workload and the per-config table (repeatable), "
+                         "e.g. --opt elem_threads_log2=8 --opt xcd_chunk=0")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; tiles are independent, so more GPUs would each "
@@ -60,7 +63,10 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = "cuda"
 
-    forced = None if args.strategy is None else ll.ll_options_init(strategy=args.strategy)
+    fields = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.opt}
+    if args.strategy is not None:
+        fields["strategy"] = args.strategy
+    forced = ll.ll_options_init(**fields) if fields else None
 
     def make_case(cfg, nsets, opts=forced):
         """Device buffers (nsets rotating copies) and a launcher for one configuration."""
@@ -74,11 +80,11 @@ def main() -> int:
             else:
                 sets.append((x, None, torch.empty_like(x)))
         if cfg.kind == "gather":
-            info = {"strategy_name": "gather", "kind_name": "gather"}
+            info = {"strategy_name": ll.ll_gather_info(a, cfg.axis, cfg.elem_bytes, opts)["kernel_name"], "kind_name": "gather"}
 
             def launch(k):
                 x, idx, out = sets[k % nsets]
-                ll.ll_gather(a, cfg.axis, cfg.elem_bytes, x, idx, out, cfg.ntiles)
+                ll.ll_gather(a, cfg.axis, cfg.elem_bytes, x, idx, out, cfg.ntiles, opts=opts)
         else:
             b = ll.distributed_layout(cfg.nreg, cfg.nlane, cfg.nwave, cfg.out_dim_bits, cfg.dst_bases)
             plan = ll.ll_plan_convert(a, b, cfg.elem_bytes, opts)
@@ -167,7 +173,8 @@ def main() -> int:
         "config": {"workload": "config %d: %s, %d tiles of 2^%d elements x %d B" %
                                (main_cfg.cid, main_cfg.name, main_cfg.ntiles, main_cfg.d, main_cfg.elem_bytes),
                    "kernel": info["strategy_name"], "class": info["kind_name"],
-                   "buffer_sets_rotated": 2},
+                   "threads_per_workgroup": info.get("threads"), "vectors_per_thread": info.get("vectors_per_thread"),
+                   "options": fields or None, "buffer_sets_rotated": 2},
         "fraction_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "copy_kernel_ceiling_GBps": round(ceiling, 1),
         "fraction_of_copy_ceiling": round(achieved / ceiling, 4),
@@ -302,7 +309,7 @@ def main() -> int:
         lay5 = ll.distributed_layout(c5.nreg, c5.nlane, c5.nwave, c5.out_dim_bits, c5.src_bases)
         x5 = c5.gen_data(0, c5.ntiles, dev)
         out5 = torch.empty_like(x5)
-        for axis_, kern_ in ((0, None), (0, ll.LL_GATHER_SHUFFLE), (0, ll.LL_GATHER_BLOCK_STAGED), (1, None)):
+        for axis_, kern_ in ((0, None), (0, ll.LL_GATHER_SHUFFLE_ROWS), (0, ll.LL_GATHER_SHUFFLE), (0, ll.LL_GATHER_BLOCK_STAGED), (1, None)):
             gopts = None if kern_ is None else ll.ll_options_init(gather_kernel=kern_)
             ginfo = ll.ll_gather_info(lay5, axis_, c5.elem_bytes, gopts)
             idx5 = wl.gen_index(51 + axis_, 0, c5.ntiles * c5.tile_elems, 1 << c5.out_dim_bits[axis_], dev)
