@@ -369,11 +369,41 @@ def main() -> int:
             torch.cuda.empty_cache()
         result["affine_conversions"] = atable
 
+    if not args.only_main:
+        result["c_abi_eager_calls"] = c_abi_call_cost()
+
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(main_cfg)
 
     print(json.dumps(result))
     return 0
+
+
+def c_abi_call_cost():
+    """Host cost of an eager ll_convert / ll_gather call through the C ABI, measured by the plain C
+    client (tests/c/gpu_client.c --time: 20000 calls back to back on one stream, one tile each,
+    configuration 1's layouts), which is compiled here with gcc and run as a child process."""
+    import subprocess
+    import tempfile
+    import paper_2505_23819_amd as ll
+    import oracle
+    libdir, odir = os.path.dirname(ll.LIBRARY_PATH), os.path.dirname(oracle.build())
+    with tempfile.TemporaryDirectory() as tmp:
+        exe = os.path.join(tmp, "gpu_client")
+        cmd = ["gcc", "-std=c99", "-O1", "-I", os.path.join(ROOT, "include"), "-I", "/opt/rocm/include",
+               os.path.join(ROOT, "tests", "c", "gpu_client.c"), "-o", exe,
+               "-L", libdir, "-lll355", "-L", odir, "-lll_oracle", "-L", "/opt/rocm/lib", "-lamdhip64",
+               "-Wl,-rpath," + libdir, "-Wl,-rpath," + odir, "-Wl,-rpath,/opt/rocm/lib"]
+        try:
+            subprocess.run(cmd, check=True, capture_output=True, text=True, timeout=120)
+            res = subprocess.run([exe, "--time"], capture_output=True, text=True, timeout=120)
+        except (OSError, subprocess.SubprocessError) as e:
+            return {"error": str(e)[:200]}
+    if res.returncode != 0:
+        return {"error": res.stderr[-200:]}
+    f = res.stdout.split()
+    return {"us_per_ll_convert_config1": float(f[1]), "us_per_ll_gather_one_tile": float(f[3]), "calls": int(f[5]),
+            "how": "plain C client, back-to-back eager calls on one stream, host clock around the loop and one synchronize"}
 
 
 def cpu_baseline(cfg):

@@ -1334,11 +1334,6 @@ static ll_status launch_gather_general_wt(const GatherGenArgs &a, hipStream_t s)
 // 5.2-5.3 / 5.7-5.96; 64 KiB 5.5-5.6 / 6.0 / 6.05-6.16; 32 KiB 5.8-6.0 / 6.0-6.26 / 6.07-6.35; 16 KiB
 // 5.7-6.2 / 5.9-6.5 / 4.9-5.7; 8 KiB 6.3-6.5 / 4.1-5.7 / - (one-byte elements, whose units are a quarter
 // of the bytes: 5.96 / 6.08 / -).  Interleaved repeats on 512 MiB of data.
-int gather_general_thread_bits(long long block_bytes, int elem_bytes)
-{
-    return block_bytes >= 32 * 1024 ? 10 : (block_bytes >= 16 * 1024 || (elem_bytes == 1 && block_bytes >= 8 * 1024)) ? 9 : 8;
-}
-
 template <int W>
 static ll_status launch_gather_general_w(const GatherGenArgs &a, int tb, hipStream_t s)
 {
@@ -1370,7 +1365,6 @@ ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thre
 // consecutive output elements: coalesced index loads and output stores, element-wide source loads
 // that stay inside the aligned block of 2^block_bits elements around the element (L2 / MALL serve
 // the re-reads when the block order keeps one block on one XCD).
-constexpr int kGlobalPasses = 4;
 template <int W>
 __global__ __launch_bounds__(256) void k_gather_global(const GatherGenArgs a)
 {
@@ -1459,8 +1453,6 @@ __global__ __launch_bounds__(256) void k_gather_global(const GatherGenArgs a)
     }
 }
 
-int gather_global_chunk_bits(int elem_bytes) { return (elem_bytes == 8 ? 1 : 2) + 8 + 2; }
-
 ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *stream)
 {
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
@@ -1488,9 +1480,6 @@ ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *str
 // Every workgroup reads the whole range, so the range comes from L2
 // (range elements / workgroup elements) times, in full lines, against one line per ELEMENT in the
 // memory-direct kernel.  One workgroup fits a CU.
-constexpr int kPhasedThreadBits = 10;
-constexpr int kPhasedUnits = 8;                       // units per thread
-constexpr int kPhasedChunkBytes = 128 * 1024;
 template <int W, bool FIELD>
 __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const GatherGenArgs a)
 {
@@ -1633,9 +1622,6 @@ __global__ __launch_bounds__(1 << kPhasedThreadBits) void k_gather_phased(const 
         }
     }
 }
-
-int gather_phased_chunk_bits(int elem_bytes) { return (elem_bytes == 8 ? 1 : 2) + kPhasedThreadBits + 3; }
-int gather_phased_lds_chunk_bytes() { return kPhasedChunkBytes; }
 
 template <int W>
 static ll_status launch_gather_phased_w(const GatherGenArgs &a, hipStream_t s)

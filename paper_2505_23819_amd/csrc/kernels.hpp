@@ -151,12 +151,22 @@ struct GatherGenArgs {
                                          // staged kernel: >= 0 when the LDS byte offset of a move is (coordinate difference) << field_shift
 };
 
-int gather_general_thread_bits(long long block_bytes, int elem_bytes);   // log2 threads measured best for a staged block
+// Work geometry of the gather kernels, shared by the kernels and by the host code that sizes their grids.
+constexpr int kGlobalPasses = 4;                      // memory-direct kernel: passes of 256 units per workgroup
+constexpr int kPhasedThreadBits = 10;                 // chunk-walking kernel: 1024 threads,
+constexpr int kPhasedUnits = 8;                       //   8 units per thread,
+constexpr int kPhasedChunkBytes = 128 * 1024;         //   the aligned range staged 128 KiB at a time
+// log2 threads measured best for a block staged by the workgroup-staged kernel (see launch_gather_general_w)
+inline int gather_general_thread_bits(long long block_bytes, int elem_bytes)
+{
+    return block_bytes >= 32 * 1024 ? 10 : (block_bytes >= 16 * 1024 || (elem_bytes == 1 && block_bytes >= 8 * 1024)) ? 9 : 8;
+}
+// log2 elements one workgroup takes: units of 4 elements (2 of 8 bytes) x 256 threads x 4 passes / x 1024 threads x 8 units
+inline int gather_global_chunk_bits(int elem_bytes) { return (elem_bytes == 8 ? 1 : 2) + 8 + 2; }
+inline int gather_phased_chunk_bits(int elem_bytes) { return (elem_bytes == 8 ? 1 : 2) + kPhasedThreadBits + 3; }
+inline int gather_phased_lds_chunk_bytes() { return kPhasedChunkBytes; }
 ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thread_bits, void *stream);
-int gather_global_chunk_bits(int elem_bytes);       // log2 elements one workgroup of the global gather takes
 ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *stream);
-int gather_phased_chunk_bits(int elem_bytes);       // log2 elements one workgroup of the phased gather takes
-int gather_phased_lds_chunk_bytes();                // bytes of the aligned block staged at a time
 ll_status launch_gather_phased(const GatherGenArgs &a, int elem_bytes, void *stream);
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,
                           int lds_bytes, void *stream);

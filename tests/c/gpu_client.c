@@ -1,13 +1,18 @@
 /* Plain C client of the whole boundary on a GPU: layouts, a plan, device buffers from the HIP
  * runtime's C API, ll_convert and ll_gather on the null stream, results compared bit for bit with the
  * CPU oracle's C functions (linked from oracle/, test infrastructure).  No Python, no C++.
- * Prints "ok" and returns 0 on success. */
+ * Prints "ok" and returns 0 on success.
+ * With the argument --time it instead times eager calls through the C ABI (no Python in the way) on
+ * the one-tile configuration 1 (64 x 64 int32, blocked -> 32x32 accumulator layout) and a one-tile
+ * gather, and prints one line: "us_per_convert <x> us_per_gather <y> calls <n>". */
 #define __HIP_PLATFORM_AMD__ 1
+#define _POSIX_C_SOURCE 199309L     /* clock_gettime under -std=c99 */
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <time.h>
 
 #include "ll.h"
 
@@ -23,8 +28,67 @@ int oracle_gather(const uint64_t *basesL, int d, const int32_t *out_dim_bits, in
 
 enum { D = 12, NTILES = 37 };
 
-int main(void)
+static double now_us(void)
 {
+    struct timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return ts.tv_sec * 1e6 + ts.tv_nsec * 1e-3;
+}
+
+/* Host cost of an eager call: n calls back to back on one stream, one synchronisation at the end. */
+static int time_calls(void)
+{
+    enum { COL = 0, ROW = 6, CALLS = 20000 };
+    /* configuration 1: registers, lanes, waves of the source and of the destination layout */
+    const uint64_t src_bases[D] = {1ull << (COL + 0), 1ull << (COL + 1), 1ull << (ROW + 4), 1ull << (ROW + 5),
+                                   1ull << (COL + 2), 1ull << (COL + 3), 1ull << (COL + 4), 1ull << (COL + 5), 1ull << (ROW + 0), 1ull << (ROW + 1),
+                                   1ull << (ROW + 2), 1ull << (ROW + 3)};
+    const uint64_t dst_bases[D] = {1ull << (ROW + 0), 1ull << (ROW + 1), 1ull << (ROW + 3), 1ull << (ROW + 4),
+                                   1ull << (COL + 0), 1ull << (COL + 1), 1ull << (COL + 2), 1ull << (COL + 3), 1ull << (COL + 4), 1ull << (ROW + 2),
+                                   1ull << (ROW + 5), 1ull << (COL + 5)};
+    const ll_in_dim in_dims[3] = {{LL_IN_REG, 4}, {LL_IN_LANE, 6}, {LL_IN_WAVE, 2}};
+    const ll_out_dim out_dims[2] = {{6}, {6}};
+    ll_layout *a = NULL, *b = NULL;
+    ll_plan *plan = NULL;
+    CHECK(ll_layout_create(in_dims, 3, out_dims, 2, src_bases, &a));
+    CHECK(ll_layout_create(in_dims, 3, out_dims, 2, dst_bases, &b));
+    CHECK(ll_plan_convert(a, b, 4, &plan));
+    void *dsrc = NULL, *ddst = NULL, *didx = NULL;
+    const size_t bytes = (size_t)4 << D;
+    HIP(hipMalloc(&dsrc, bytes));
+    HIP(hipMalloc(&ddst, bytes));
+    HIP(hipMalloc(&didx, bytes));
+    HIP(hipMemset(dsrc, 1, bytes));
+    HIP(hipMemset(didx, 0, bytes));
+    hipStream_t stream;
+    HIP(hipStreamCreate(&stream));
+    double us[2];
+    for (int what = 0; what < 2; ++what) {
+        for (int rep = 0; rep < 2; ++rep) {            /* the first round warms up */
+            HIP(hipStreamSynchronize(stream));
+            const double t0 = now_us();
+            for (int i = 0; i < CALLS; ++i) {
+                if (what == 0) CHECK(ll_convert(plan, dsrc, ddst, 1, stream));
+                else CHECK(ll_gather(b, 0, 4, dsrc, (const int32_t *)didx, ddst, 1, stream));
+            }
+            HIP(hipStreamSynchronize(stream));
+            us[what] = (now_us() - t0) / CALLS;
+        }
+    }
+    printf("us_per_convert %.3f us_per_gather %.3f calls %d\n", us[0], us[1], (int)CALLS);
+    HIP(hipStreamDestroy(stream));
+    HIP(hipFree(dsrc));
+    HIP(hipFree(ddst));
+    HIP(hipFree(didx));
+    CHECK(ll_plan_destroy(plan));
+    CHECK(ll_layout_destroy(a));
+    CHECK(ll_layout_destroy(b));
+    return 0;
+}
+
+int main(int argc, char **argv)
+{
+    if (argc > 1 && strcmp(argv[1], "--time") == 0) return time_calls();
     /* a 64 x 64 tile, 16 registers x 64 lanes x 4 waves: A row-major, B a bit permutation with XOR terms
      * (every column is one unit vector plus the unit vector of the column before it: invertible) */
     const int perm[D] = {7, 2, 9, 0, 11, 4, 1, 8, 5, 10, 3, 6};
