@@ -251,12 +251,14 @@ def gather_affine(bases_l: Sequence[int], off: int, out_dim_bits: Sequence[int],
 def gather_general(bases_l: Sequence[int], out_dim_bits: Sequence[int], axis: int,
                    inp: np.ndarray, idx: np.ndarray, off: int = 0) -> np.ndarray:
     """Gather (Sec. 5.5) under a surjective layout that may broadcast (Sec. 5.1), optionally affine.
-    Slot h of a tile holds the logical element x = L h ^ off.  It receives the element whose axis
-    coordinate is idx[h] (mod the axis length) and whose other coordinates are those of x, i.e. the
-    logical element x ^ delta with delta = (own axis coordinate ^ idx[h]) on the axis bits.  Of the
-    replicas of that element it takes the one at slot h ^ L^+(delta), L^+ the right inverse with
-    free variables zero (Def. "Right Inverse"): L(h ^ L^+ delta) = L h ^ delta.  For a bijective
-    layout this is the plain gather."""
+    Slot h of a tile holds the logical element x = L h ^ off; `in` must be the image of a logical
+    tensor X, i.e. all replicas of an element hold the same value (ValueError otherwise: the paper
+    does not say which replica a gather would read, and the library leaves it unspecified).  Every
+    slot of `out` is written, from its own slot of `idx` (replicas of idx may differ):
+        out[h] = X[x with the axis coordinate replaced by idx[h] mod the axis length].
+    X is read off the canonical slots, X[x] = in[L^+(x ^ off)] with L^+ the right inverse with free
+    variables zero (Def. "Right Inverse"; Sec. 5.4 rule 2).  For a bijective layout this is the
+    plain gather."""
     d, d_out = len(bases_l), int(sum(out_dim_bits))
     _check_img(inp, d, "in")
     _check_img(idx, d, "idx")
@@ -266,20 +268,35 @@ def gather_general(bases_l: Sequence[int], out_dim_bits: Sequence[int], axis: in
         raise ValueError("axis")
     shift = int(sum(out_dim_bits[axis + 1:]))
     mask = (1 << int(out_dim_bits[axis])) - 1
-    lplus = right_inverse_table(bases_l, d_out).astype(np.int64)     # x -> slot, free variables zero
+    lplus = right_inverse_table(bases_l, d_out).astype(np.int64)     # logical index -> canonical slot
     h = np.arange(1 << d, dtype=np.int64)
-    x = np.zeros(1 << d, dtype=np.int64)
+    lh = np.zeros(1 << d, dtype=np.int64)
     for k, col in enumerate(bases_l):
-        x ^= ((h >> k) & 1) * int(col)
-    x ^= int(off)
-    own = (x >> shift) & mask
+        lh ^= ((h >> k) & 1) * int(col)
+    x = lh ^ int(off)                                                 # logical element of every slot
+    canon = lplus[np.arange(1 << d_out, dtype=np.int64) ^ int(off)]   # X[x] sits at slot canon[x]
     out = np.empty_like(inp)
     src_img, idx_img, out_img = inp.reshape(-1, 1 << d), idx.reshape(-1, 1 << d), out.reshape(-1, 1 << d)
     for t in range(src_img.shape[0]):
+        logical = src_img[t][canon]                                   # the logical tensor X of this tile
+        if not np.array_equal(src_img[t], logical[x]):
+            raise ValueError("replicas of `in` differ in tile %d: the gather is defined for images of a logical tensor" % t)
         want = idx_img[t].astype(np.int64) & mask
-        delta = (own ^ want) << shift
-        out_img[t] = src_img[t][h ^ lplus[delta]]
+        out_img[t] = logical[(x & ~(mask << shift)) | (want << shift)]
     return out
+
+
+def consistent_image(bases_l: Sequence[int], d_out: int, img: np.ndarray, off: int = 0) -> np.ndarray:
+    """Copy of `img` (tiles of 2^len(bases) slots) in which every replica holds the value of the
+    canonical slot of its logical element: the image of a logical tensor."""
+    d = len(bases_l)
+    _check_img(img, d, "img")
+    lplus = right_inverse_table(bases_l, d_out).astype(np.int64)
+    h = np.arange(1 << d, dtype=np.int64)
+    lh = np.zeros(1 << d, dtype=np.int64)
+    for k, col in enumerate(bases_l):
+        lh ^= ((h >> k) & 1) * int(col)
+    return np.ascontiguousarray(img.reshape(-1, 1 << d)[:, lplus[lh]]).reshape(-1)
 
 
 def wavefronts(mem_bases: Sequence[int], dist_bases: Sequence[int], nreg: int, nlane: int,

@@ -1,7 +1,7 @@
 """Pins of the oracle's gather under broadcasting layouts (Sec. 5.5 with Sec. 5.1 "Broadcasting").
 
 The function is pinned through the logical view (numpy take_along_axis), through its reduction to
-the plain gather, and through what its definition fixes about the replica it reads."""
+the plain gather, by its definition evaluated slot by slot, and by a hand-worked example."""
 import numpy as np
 import pytest
 
@@ -76,43 +76,43 @@ def test_bijective_layouts_reduce_to_the_plain_gather():
                                   oracle.gather_affine(bases, off, dims, axis, inp, idx))
 
 
-def test_the_replica_read_is_the_one_the_definition_names():
-    """With slot numbers as data the output shows which slot was read: it must hold the wanted
-    logical element, take its index from the receiving slot itself, and differ from the receiving
-    slot only in pivot bits (free variables of the right inverse stay zero), by a vector that
-    depends on the coordinate difference alone."""
+def test_every_slot_uses_its_own_index_and_unequal_replicas_of_in_are_refused():
+    """Replicas of idx may differ: every slot of out is filled from its own slot of idx.  Replicas of
+    `in` may not: the result would depend on a choice the paper does not make."""
     rng = np.random.default_rng(9)
     dims, d_in = [3, 2], 8
     d_out = sum(dims)
     for trial in range(6):
         bases = surjective_with_replicas(rng, d_in, d_out)
-        lplus = oracle.right_inverse_table(bases, d_out)
-        pivot_bits = int(np.bitwise_or.reduce(lplus))
         for axis in range(2):
             shift = sum(dims[axis + 1:])
             mask = (1 << dims[axis]) - 1
-            inp = np.arange(1 << d_in, dtype=np.uint32)
-            idx = rng.integers(0, 1 << dims[axis], size=1 << d_in).astype(np.int32)    # replicas of idx differ on purpose
+            logical = rng.integers(0, 1 << 30, size=1 << d_out).astype(np.uint32)
+            inp = image_of(logical, bases, d_in)
+            idx = rng.integers(-9, 9 + (1 << dims[axis]), size=1 << d_in).astype(np.int32)    # replicas of idx differ on purpose
             got = oracle.gather_general(bases, dims, axis, inp, idx)
-            by_delta = {}
             for h in range(1 << d_in):
-                x, src = apply(bases, h), int(got[h])
-                wanted = (x & ~(mask << shift)) | (int(idx[h]) << shift)
-                assert apply(bases, src) == wanted
-                move = src ^ h
-                assert move & ~pivot_bits == 0
-                assert by_delta.setdefault(x ^ wanted, move) == move
-            assert by_delta.get(0, 0) == 0                           # an element that wants itself reads its own slot
+                x = apply(bases, h)
+                wanted = (x & ~(mask << shift)) | ((int(idx[h]) & mask) << shift)
+                assert got[h] == logical[wanted]
+            assert np.array_equal(oracle.consistent_image(bases, d_out, inp), inp)
+            broken = inp.copy()
+            lplus = oracle.right_inverse_table(bases, d_out)
+            replica = next(h for h in range(1 << d_in) if int(lplus[apply(bases, h)]) != h)      # a non-canonical slot
+            broken[replica] ^= 1
+            with pytest.raises(ValueError):
+                oracle.gather_general(bases, dims, axis, broken, idx)
+            assert np.array_equal(oracle.consistent_image(bases, d_out, broken), inp)            # the canonical slots decide
 
 
 def test_worked_example_one_zero_column():
     """4 logical elements (one dim), registers [e0, 0, e1]: slot h = r0 + 2 r1 + 4 r2 holds element
-    r0 + 2 r2; r1 enumerates two replicas.  The element at slot 6 (element 2, replica 1) that asks
-    for element 1 reads slot 6 ^ L^+(3) = 6 ^ 5 = 3 (element 1, replica 1: the replica bit is kept)."""
+    r0 + 2 r2; r1 enumerates two replicas.  X = (10, 11, 12, 13) lies at slots (0, 1, 4, 5) and again at
+    (2, 3, 6, 7).  Slot 6 (element 2, second replica) asks for element 1 and gets 11; all others ask for
+    element 0 and get 10."""
     bases = [1, 0, 2]
-    inp = np.arange(8, dtype=np.uint8) + 10
+    inp = np.array([10, 11, 10, 11, 12, 13, 12, 13], dtype=np.uint8)
     idx = np.zeros(8, dtype=np.int32)
     idx[6] = 1
     out = oracle.gather_general(bases, [2], 0, inp, idx)
-    assert out[6] == 13
-    assert list(out[[0, 1, 2, 3]]) == [10, 10, 12, 12]               # ask for element 0: same replica bit, r0 = r2 = 0
+    assert list(out) == [10, 10, 10, 10, 10, 10, 11, 10]
