@@ -43,6 +43,10 @@ def main() -> int:
     ap.add_argument("--strategy", type=int, default=None,
                     help="force a conversion strategy for every plan (3: element-wide LDS, 4: 128-bit LDS "
                          "where it applies); default: the planner's choice")
+    ap.add_argument("--mark", action="store_true",
+                    help="for profiler runs: before every timed section launch a tiny copy whose grid size is unique "
+                         "(256 * (k + 1) threads for the k-th section) and list the sections in the JSON field 'sections', "
+                         "so that a kernel trace can be cut into sections")
     ap.add_argument("--opt", action="append", default=[], metavar="FIELD=VALUE",
                     help="set a field of ll_options for the main workload and the per-config table (repeatable), "
                          "e.g. --opt elem_threads_log2=8 --opt xcd_chunk=0")
@@ -95,7 +99,33 @@ def main() -> int:
                 ll.ll_convert(plan, x, out, cfg.ntiles)
         return launch, info, sets
 
-    def time_launches(launch, steps, warmup, warm_ms=TABLE_WARMUP_MS):
+    # what rocprofv3 measured for each timed section in an earlier profiled run (profiles/per_section_summary.txt):
+    # HBM traffic, LDS bank conflict cycles per wave, kernel-only duration
+    profiled = {}
+    ppath = os.path.join(ROOT, "profiles", "per_section_summary.txt")
+    if os.path.exists(ppath):
+        for line in open(ppath):
+            f = line.rstrip("\n").split("\t")
+            if len(f) == 6 and not line.startswith(("#", "section\t")):
+                profiled[f[0]] = {"kernel": f[1], "hbm_read_MiB": float(f[2]), "hbm_written_MiB": float(f[3]),
+                                  "lds_conflict_cycles_per_wave": float(f[4]), "kernel_us": float(f[5])}
+
+    def annotate(entry, label, alg_bytes):
+        """Adds the profiled figures of section `label` to a table entry."""
+        p = profiled.get(label)
+        if not p:
+            return
+        traffic = (p["hbm_read_MiB"] + p["hbm_written_MiB"]) * (1 << 20)
+        entry["profiled"] = {"kernel": p["kernel"], "kernel_us": p["kernel_us"],
+                             "GBps_kernel_time": round(alg_bytes / p["kernel_us"] / 1e3, 1),
+                             "hbm_traffic_bytes": int(traffic), "hbm_traffic_over_algorithmic": round(traffic / alg_bytes, 4),
+                             "GBps_of_hbm_traffic": round(traffic / p["kernel_us"] / 1e3, 1),
+                             "lds_conflict_cycles_per_wave": p["lds_conflict_cycles_per_wave"]}
+
+    sections = []
+    mark_buf = torch.zeros(2, 1 << 20, dtype=torch.uint8, device=dev) if args.mark else None
+
+    def time_launches(launch, steps, warmup, warm_ms=TABLE_WARMUP_MS, label=""):
         """Returns (wall ms per step, mean ms per launch, median, min).
 
         The timed region is exactly `steps` back-to-back launches between two HIP events on the stream
@@ -103,6 +133,9 @@ def main() -> int:
         host clock readings around synchronize(): mean = event time / steps, wall = host time / steps.
         Median and minimum come from a second, untimed pass with an event after every launch (each
         such event costs about 3 us of stream time, which is why it is not done in the timed region)."""
+        if args.mark:
+            ll.ll_copy(mark_buf[0], mark_buf[1], 4096 * (len(sections) + 1))
+            sections.append(label)
         t_w = time.perf_counter()
         for k in range(warmup):
             launch(k)
@@ -132,29 +165,35 @@ def main() -> int:
         per = [evs[k].elapsed_time(evs[k + 1]) for k in range(steps)]
         return wall_ms, mean_ms, statistics.median(per), min(per)
 
-    def copy_ceiling(nbytes_each, steps=None):
+    def copy_ceiling(nbytes_each, steps=None, label="copy yardstick"):
         steps = steps or max(20, args.table_steps)
         """Plain 16-byte vector copy moving the same read + write footprint."""
         n = max(16, (nbytes_each // 16) * 16)
         src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
         dsts = [torch.empty_like(src) for _ in range(2)]
-        _, mean_ms, _, _ = time_launches(lambda k: ll.ll_copy(src, dsts[k % 2], n), steps, TABLE_WARMUP)
+        _, mean_ms, _, _ = time_launches(lambda k: ll.ll_copy(src, dsts[k % 2], n), steps, TABLE_WARMUP, label="%s, %d MiB each way" % (label, n >> 20))
         return 2.0 * n / mean_ms / 1e6
 
     main_cfg = wl.config(args.workload)
     launch, info, sets = make_case(main_cfg, nsets=2)
-    wall_ms, mean_ms, med_ms, min_ms = time_launches(launch, args.steps, args.warmup, warm_ms=0)      # exactly W warm-up steps
+    wall_ms, mean_ms, med_ms, min_ms = time_launches(launch, args.steps, args.warmup, warm_ms=0,      # exactly W warm-up steps
+                                                     label="main: config %d" % main_cfg.cid)
     alg_bytes = main_cfg.algorithmic_bytes()
     value = alg_bytes / wall_ms / 1e6                      # GB/s over the timed region (wall clock)
     achieved = alg_bytes / mean_ms / 1e6                   # GB/s of the kernel itself (HIP events)
-    ceiling = copy_ceiling(alg_bytes // 2)
+    ceiling = copy_ceiling(alg_bytes // 2, label="copy yardstick for the main line")
 
-    traffic = None
+    traffic, kernel_us = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_config%d.txt" % main_cfg.cid)
-    if os.path.exists(tpath):                              # measured separately with rocprofv3 --pmc
+    if os.path.exists(tpath) and not fields:               # measured separately with rocprofv3 --pmc (default options only)
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = float(line.split()[1])
+    spath = os.path.join(ROOT, "profiles", "config%d_kernel_stats.txt" % main_cfg.cid)
+    if os.path.exists(spath) and not fields:               # rocprofv3 --kernel-trace --stats of the same command
+        for line in open(spath):
+            if line.startswith("ll::") and "k_copy" not in line:
+                kernel_us = float(line.split(", ")[-4]) / 1e3
 
     result = {
         "metric": "layout-conversion GB/s (read+write) vs HBM peak",
@@ -182,7 +221,11 @@ def main() -> int:
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel": info["strategy_name"], "launch_ms_mean": round(mean_ms, 5),
                      "launch_ms_median": round(med_ms, 5), "launch_ms_min": round(min_ms, 5),
-                     "algorithmic_bytes_per_launch": alg_bytes},
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "profiled_kernel_us": kernel_us,
+                     "profiled_frac": round(alg_bytes / kernel_us / 1e3 / HBM_PEAK_GBPS, 4) if kernel_us else None,
+                     "how": "achieved = algorithmic bytes / mean launch duration, HIP events around the timed region on the launch stream; "
+                            "profiled_* = the same kernel's average under rocprofv3 --kernel-trace (profiles/), traffic = FETCH_SIZE + WRITE_SIZE"},
     }
     del sets, launch
     torch.cuda.empty_cache()
@@ -193,7 +236,7 @@ def main() -> int:
             nsets = 2 if cfg.algorithmic_bytes() < (1 << 30) else 1
             l, inf, s = make_case(cfg, nsets)
             steps = args.table_steps if cfg.cid != 1 else max(args.table_steps, 200 if args.table_steps >= 30 else 0)
-            w_ms, m_ms, md_ms, mn_ms = time_launches(l, steps, TABLE_WARMUP)
+            w_ms, m_ms, md_ms, mn_ms = time_launches(l, steps, TABLE_WARMUP, label="config %d" % cfg.cid)
             ab = cfg.algorithmic_bytes()
             entry = {"config": cfg.cid, "name": cfg.name, "kernel": inf["strategy_name"], "class": inf["kind_name"],
                      "algorithmic_bytes": ab, "us_mean": round(m_ms * 1e3, 2), "us_median_with_events": round(md_ms * 1e3, 2),
@@ -205,16 +248,17 @@ def main() -> int:
             del s, l
             torch.cuda.empty_cache()
             if cfg.cid != 1:
-                entry["copy_GBps_same_footprint"] = round(copy_ceiling(ab // 2), 1)
+                entry["copy_GBps_same_footprint"] = round(copy_ceiling(ab // 2, label="copy yardstick for config %d" % cfg.cid), 1)
             if cfg.kind == "convert" and args.strategy is None and inf["strategy_name"] in ("reg_permute", "wave_shuffle"):
                 # the same conversion staged through LDS (128-bit accesses), for comparison
                 l2, inf2, s2 = make_case(cfg, nsets, ll.ll_options_init(strategy=ll.LL_STRATEGY_LDS_VEC))
-                _, md2, _, _ = time_launches(l2, steps, TABLE_WARMUP)
+                _, md2, _, _ = time_launches(l2, steps, TABLE_WARMUP, label="config %d through 128-bit LDS" % cfg.cid)
                 entry["through_lds"] = {"kernel": inf2["strategy_name"], "lds_access_bytes": inf2["lds_write_bytes"],
                                         "GBps": round(ab / md2 / 1e6, 1),
                                         "predicted_wavefronts": [inf2["predicted_wavefronts_write"], inf2["predicted_wavefronts_read"]]}
                 del s2, l2
                 torch.cuda.empty_cache()
+            annotate(entry, "config %d" % cfg.cid, ab)
             table.append(entry)
         result["per_config"] = table
 
@@ -231,7 +275,7 @@ def main() -> int:
         with torch.cuda.graph(graph):
             for k in range(100):
                 l1(k)
-        _, g_ms, _, _ = time_launches(lambda k: graph.replay(), 20, 2)
+        _, g_ms, _, _ = time_launches(lambda k: graph.replay(), 20, 2, label="config 1, graph of 100 launches")
         result["config1_graph_replay"] = {"launches_per_graph": 100, "us_per_launch": round(g_ms * 1e3 / 100, 3),
                                           "kernel": inf1["strategy_name"]}
         del graph, l1, s1
@@ -248,7 +292,8 @@ def main() -> int:
         for force in (None, ll.LL_STRATEGY_LDS_VEC, ll.LL_STRATEGY_LDS_ELEM):
             p1 = ll.ll_plan_convert(a1, b1, c1.elem_bytes, None if force is None else ll.ll_options_init(strategy=force))
             i1 = p1.info()
-            _, m_ms, _, _ = time_launches(lambda k: ll.ll_convert(p1, x1, o1[k % 2], nt1), args.table_steps, TABLE_WARMUP)
+            _, m_ms, _, _ = time_launches(lambda k: ll.ll_convert(p1, x1, o1[k % 2], nt1), args.table_steps, TABLE_WARMUP,
+                                          label="config 1's layouts on 32768 tiles, %s" % i1["strategy_name"])
             many.append({"kernel": i1["strategy_name"], "shuffle_stages": i1["shuffle_rounds"], "lds_bytes": i1["lds_bytes"],
                          "us_mean": round(m_ms * 1e3, 2), "GBps": round(ab1 / m_ms / 1e6, 1),
                          "frac_hbm_peak": round(ab1 / m_ms / 1e6 / HBM_PEAK_GBPS, 4)})
@@ -267,13 +312,14 @@ def main() -> int:
             x = case.gen_data(0, case.ntiles, dev)
             outs = [torch.empty(case.ntiles << case.d_dst, dtype=x.dtype, device=dev) for _ in range(2)]
             _, md_ms, _, mn_ms = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % 2], case.ntiles),
-                                               args.table_steps, TABLE_WARMUP)
+                                               args.table_steps, TABLE_WARMUP, label="broadcast: " + case.name)
             ab = case.algorithmic_bytes()
             btable.append({"name": case.name, "kernel": inf["strategy_name"], "src_tile_bits": case.d_src,
                            "dst_tile_bits": case.d_dst, "logical_bits": case.d_out, "algorithmic_bytes": ab,
                            "us_mean": round(md_ms * 1e3, 2), "GBps": round(ab / md_ms / 1e6, 1),
                            "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4),
                            "predicted_wavefronts": [inf["predicted_wavefronts_write"], inf["predicted_wavefronts_read"]]})
+            annotate(btable[-1], "broadcast: " + case.name, ab)
             del x, outs
             torch.cuda.empty_cache()
         result["broadcast_conversions"] = btable
@@ -291,7 +337,8 @@ def main() -> int:
             nt = (256 << 20) // (c2.tile_elems * w_)            # 256 MiB per side
             x = wl.raw_bits(21, 0, nt * c2.tile_elems * w_ // 8, dev).view(dt_)
             outs = [torch.empty_like(x) for _ in range(2)]
-            _, md_ms, _, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % 2], nt), args.table_steps, TABLE_WARMUP)
+            _, md_ms, _, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % 2], nt), args.table_steps, TABLE_WARMUP,
+                                           label="transpose 128x128, %d-byte elements, %s" % (w_, inf["strategy_name"]))
             ab = 2 * nt * c2.tile_elems * w_
             ttable.append({"name": "transpose 128x128, %d-byte elements, %d tiles" % (w_, nt), "kernel": inf["strategy_name"],
                            "lds_access_bytes": [inf["lds_write_bytes"], inf["lds_read_bytes"]], "block_bytes": (1 << inf["block_bits"]) * w_,
@@ -314,13 +361,15 @@ def main() -> int:
             ginfo = ll.ll_gather_info(lay5, axis_, c5.elem_bytes, gopts)
             idx5 = wl.gen_index(51 + axis_, 0, c5.ntiles * c5.tile_elems, 1 << c5.out_dim_bits[axis_], dev)
             _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(lay5, axis_, c5.elem_bytes, x5, idx5, out5, c5.ntiles, opts=gopts),
-                                           args.table_steps, TABLE_WARMUP)
+                                           args.table_steps, TABLE_WARMUP,
+                                           label="gather: config 5 layout, dim %d, %s" % (axis_, ginfo["kernel_name"]))
             ab = c5.algorithmic_bytes()
             gtable.append({"name": "config 5 layout, gather along dim %d" % axis_, "kernel": ginfo["kernel_name"],
                            "axis_bits_reg_lane_wave": [ginfo["axis_reg_bits"], ginfo["axis_lane_bits"], ginfo["axis_wave_bits"]],
                            "paper_rounds": ginfo["paper_rounds"], "staged_bytes": ginfo["block_bytes"],
                            "algorithmic_bytes": ab, "us_mean": round(md_ms * 1e3, 2), "GBps": round(ab / md_ms / 1e6, 1),
                            "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)})
+            annotate(gtable[-1], "gather: config 5 layout, dim %d, %s" % (axis_, ginfo["kernel_name"]), ab)
             del idx5
         del x5, out5
         torch.cuda.empty_cache()
@@ -336,7 +385,8 @@ def main() -> int:
             big = ll.distributed_layout(4, 6, db - 10, [rows_b, cols_b], [1 << k for k in range(db)])
             ib = wl.gen_index(53, 0, ntb << db, 1 << rows_b, dev)
             ginfo = ll.ll_gather_info(big, 0, 2)
-            _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(big, 0, 2, xb, ib, ob, ntb), args.table_steps, TABLE_WARMUP)
+            _, md_ms, _, _ = time_launches(lambda k: ll.ll_gather(big, 0, 2, xb, ib, ob, ntb), args.table_steps, TABLE_WARMUP,
+                                           label="gather: row-major %dx%d two-byte tile, rows, %s" % (1 << rows_b, 1 << cols_b, ginfo["kernel_name"]))
             ab = (ntb << db) * (2 + 2 + 4)
             gtable.append({"name": "row-major %dx%d tile, 2-byte elements, gather along dim 0" % (1 << rows_b, 1 << cols_b),
                            "kernel": ginfo["kernel_name"],
@@ -344,6 +394,7 @@ def main() -> int:
                            "paper_rounds": ginfo["paper_rounds"], "staged_bytes": ginfo["block_bytes"],
                            "algorithmic_bytes": ab, "us_mean": round(md_ms * 1e3, 2), "GBps": round(ab / md_ms / 1e6, 1),
                            "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)})
+            annotate(gtable[-1], "gather: row-major %dx%d two-byte tile, rows, %s" % (1 << rows_b, 1 << cols_b, ginfo["kernel_name"]), ab)
             del ib
         del xb, ob
         torch.cuda.empty_cache()
@@ -360,7 +411,8 @@ def main() -> int:
             inf = plan.info()
             x = cfg.gen_data(0, cfg.ntiles, dev)
             outs = [torch.empty_like(x) for _ in range(2 if cid_ == 2 else 1)]
-            _, md_ms, _, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % len(outs)], cfg.ntiles), args.table_steps, TABLE_WARMUP)
+            _, md_ms, _, _ = time_launches(lambda k: ll.ll_convert(plan, x, outs[k % len(outs)], cfg.ntiles), args.table_steps, TABLE_WARMUP,
+                                           label="affine: config %d, destination offset 0x%x" % (cid_, off_))
             ab = cfg.algorithmic_bytes()
             atable.append({"name": "config %d, destination offset 0x%x" % (cid_, off_), "kernel": inf["strategy_name"],
                            "conv_offset": inf["conv_offset"], "algorithmic_bytes": ab, "us_mean": round(md_ms * 1e3, 2),
@@ -369,6 +421,8 @@ def main() -> int:
             torch.cuda.empty_cache()
         result["affine_conversions"] = atable
 
+    if args.mark:
+        result["sections"] = sections
     if not args.only_main:
         result["c_abi_eager_calls"] = c_abi_call_cost()
 

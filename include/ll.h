@@ -344,10 +344,13 @@ ll_status ll_convert(const ll_plan *plan, const void *src_dev, void *dst_dev, in
 
 /* out[.., i, ..] = in[.., idx[.., i, ..], ..] along output dim `axis`, where in, idx (int32) and
  * out are images under the same surjective layout L.  Indices are reduced modulo the axis length.
- * L may broadcast (Sec. 5.1; 2^d slots per tile for fewer logical elements): every slot of out is
- * written, from its own slot of idx, and of the replicas of the wanted element it reads the one at
- * (own slot) xor L^+(coordinate difference), L^+ the right inverse with free variables zero.
- * Moving along the axis changes the hardware index by L^-1 (L^+) of the axis bits:
+ * L may broadcast (Sec. 5.1; 2^d slots per tile for fewer logical elements): `in` must then be the
+ * image of a logical tensor, i.e. all replicas of an element hold the same value (the paper gives no
+ * rule for which replica a gather reads, and neither does this library: with unequal replicas the
+ * result is one of their values, unspecified which).  Every slot of out is written, from its own slot
+ * of idx; replicas of idx may differ.
+ * Moving along the axis changes the hardware index by L^-1 (L^+, the right inverse with free
+ * variables zero) of the axis bits:
  *  - lane bits only (the paper's condition, Sec. 5.5, with one round): cross-lane shuffles, or
  *    wave-private LDS staging when a lane holds more than 16 bytes;
  *  - register and / or wave bits as well: a block of image elements closed under moves along the axis

@@ -94,8 +94,10 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, con
     const int d = L->d_in;
     if (f2::rank(L->bases) < L->d_out) return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
     // Right inverse with free variables zero (Def. "Right Inverse"); the inverse when L is bijective.
-    // Under a broadcasting layout an element is taken from the replica that differs from the
-    // receiving slot by L^+ of the coordinate difference: L(h ^ L^+(delta)) = L(h) ^ delta.
+    // Under a broadcasting layout `in` is the image of a logical tensor (equal replicas), so any slot
+    // that holds the wanted element will do; the one that differs from the receiving slot by L^+ of
+    // the coordinate difference is taken, L(h ^ L^+(delta)) = L(h) ^ delta, because it keeps the
+    // kernels' "own index xor linear delta" addressing.
     mat linv;
     if (!f2::right_inverse(L->bases, L->d_out, &linv)) return fail(LL_ERR_NOT_SURJECTIVE, "layout does not cover the whole logical tensor");
     const int nreg = L->bits_of(LL_IN_REG), nlane = L->bits_of(LL_IN_LANE);

@@ -870,9 +870,10 @@ def test_gather_along_axes_larger_than_lds(w):
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 def test_gather_under_broadcasting_layouts(w):
-    """Random surjective layouts with zero and dependent columns, every axis, replicas of `in` and
-    `idx` deliberately unequal (which replica is read is part of the definition); a sliced blocked
-    layout; an affine constant on top."""
+    """Random surjective layouts with zero and dependent columns, every axis; `in` is the image of a
+    logical tensor (equal replicas: what the gather is defined on), replicas of `idx` deliberately
+    unequal (every slot of out follows its own index); a sliced blocked layout; an affine constant
+    on top."""
     rng = np.random.default_rng(9500 + w)
     seen = set()
     for d_in, dims, nreg in [(10, [4, 4], 2), (12, [3, 6], 4), (13, [5, 2, 3], 3), (9, [7], 2), (16, [6, 7], 4)]:
@@ -885,7 +886,7 @@ def test_gather_under_broadcasting_layouts(w):
             for lay, o in ((layout, 0), (ll.ll_layout_with_offset(layout, off), off)):
                 seen.add(ll.ll_gather_info(lay, axis, w)["kernel_name"])
                 ntiles = int(rng.integers(1, 6)) * 16
-                inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d_in, dtype=NP_DTYPES[w])
+                inp = oracle.consistent_image(cols, d_out, rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d_in, dtype=NP_DTYPES[w]))
                 idx = rng.integers(-(1 << dims[axis]), 1 << dims[axis], size=ntiles << d_in, dtype=np.int32)
                 got = run_gather(lay, axis, inp, idx, d_in)
                 assert np.array_equal(got, oracle.gather_general(cols, dims, axis, inp, idx, o)), (d_in, dims, axis, o)
@@ -896,7 +897,7 @@ def test_gather_under_broadcasting_layouts(w):
     assert s.bases == os_.bases
     for opts in (None, ll.ll_options_init(gather_kernel=ll.LL_GATHER_BLOCK_STAGED)):
         seen.add(ll.ll_gather_info(s, 0, w, opts)["kernel_name"])
-        inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=32 << 12, dtype=NP_DTYPES[w])
+        inp = oracle.consistent_image(os_.bases, 6, rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=32 << 12, dtype=NP_DTYPES[w]))
         idx = rng.integers(0, 64, size=32 << 12, dtype=np.int32)
         assert np.array_equal(run_gather(s, 0, inp, idx, 12, opts), oracle.gather_general(os_.bases, [6], 0, inp, idx))
     assert "block_staged" in seen
@@ -905,8 +906,9 @@ def test_gather_under_broadcasting_layouts(w):
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 def test_gather_through_lds_chunks_broadcasting_and_affine(w):
     """The chunk-walking kernel (aligned range of 256 KiB to 1 MiB that no closed block with long runs
-    covers) under random XOR layouts that broadcast (one slot bit more than logical bits, replicas of
-    `in` and `idx` unequal) and carry an affine constant, indices partly out of range (they wrap)."""
+    covers) under random XOR layouts that broadcast (one slot bit more than logical bits; `in` the
+    image of a logical tensor, replicas of `idx` unequal) and carry an affine constant, indices partly
+    out of range (they wrap)."""
     rng = np.random.default_rng(9900 + w)
     wl2 = {1: 0, 2: 1, 4: 2, 8: 3}[w]
     seen = set()
@@ -921,7 +923,7 @@ def test_gather_through_lds_chunks_broadcasting_and_affine(w):
             info = ll.ll_gather_info(lay, 0, w)
             seen.add(info["kernel_name"])
             ntiles = 3
-            inp = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d_in, dtype=NP_DTYPES[w])
+            inp = oracle.consistent_image(cols, d_out, rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << d_in, dtype=NP_DTYPES[w]))
             idx = rng.integers(-(1 << dims[0]), 1 << dims[0], size=ntiles << d_in, dtype=np.int32)
             got = run_gather(lay, 0, inp, idx, d_in)
             assert np.array_equal(got, oracle.gather_general(cols, dims, 0, inp, idx, o)), (d_in, dims, o, info)

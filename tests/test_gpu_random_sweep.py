@@ -151,6 +151,8 @@ def run_case(seed):
     lay = ll.ll_layout_with_offset(mk(s, od, cols), off)
     nt = ntiles_for(rng, d, w)
     inp = rng.integers(0, np.iinfo(NP[w]).max, size=nt << d, dtype=NP[w])
+    if d > dl:                    # a broadcasting layout: the gather is defined on images of a logical tensor
+        inp = oracle.consistent_image(cols, dl, inp)
     idx = rng.integers(-(1 << od[axis]) - 3, (1 << od[axis]) + 3, size=nt << d, dtype=np.int32)
     ti, tx = torch.from_numpy(inp.view(TD[w])).cuda(), torch.from_numpy(idx).cuda()
     to = torch.full_like(ti, 0x5A)
