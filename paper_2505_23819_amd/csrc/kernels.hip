@@ -305,6 +305,7 @@ static ll_status launch_lds_elem_t(const LdsElemArgs &a, int lds_bytes, hipStrea
 {
     switch (a.thread_bits) {
     case 6: if constexpr (NV == 4) return launch_lds_elem_tb<W, NV, V, 6>(a, lds_bytes, stream); break;   // one wave, a 4 KiB block
+    case 7: if constexpr (NV == 4) return launch_lds_elem_tb<W, NV, V, 7>(a, lds_bytes, stream); break;   // two waves, an 8 KiB block
     case 8: return launch_lds_elem_tb<W, NV, V, 8>(a, lds_bytes, stream);
     case 9: if constexpr (NV <= 4) return launch_lds_elem_tb<W, NV, V, 9>(a, lds_bytes, stream); break;
     case 10: if constexpr (NV <= 4) return launch_lds_elem_tb<W, NV, V, 10>(a, lds_bytes, stream); break;
@@ -340,7 +341,7 @@ static ll_status launch_lds_elem_n(const LdsElemArgs &a, int nvec, int v, int ld
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads, int lds_bytes,
                           void *stream)
 {
-    if (threads != (1 << a.thread_bits) || (a.thread_bits != 6 && (a.thread_bits < 8 || a.thread_bits > 10)))
+    if (threads != (1 << a.thread_bits) || a.thread_bits < 6 || a.thread_bits > 10)
         return fail(LL_ERR_UNSUPPORTED, "LDS kernel runs 64, 256, 512 or 1024 threads per workgroup");
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     if (lds_bytes <= 0 || lds_bytes > 64 * 1024) return fail(LL_ERR_UNSUPPORTED, "LDS block of %d bytes", lds_bytes);
@@ -1304,11 +1305,12 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
 }
 
 template <int W, int TB>
-static ll_status launch_gather_general_wt(const GatherGenArgs &a, hipStream_t s)
+static ll_status launch_gather_general_wt(const GatherGenArgs &a, int lds_alloc, hipStream_t s)
 {
     constexpr int VS = (W == 1) ? 4 : (W == 2) ? 3 : (W == 4) ? 2 : 1;
     const long long block_bytes = (1ll << a.block_bits) * W;
-    const size_t lds_bytes = (size_t)block_bytes + 4u * 128u;      // the block and four delta tables
+    size_t lds_bytes = (size_t)block_bytes + 4u * 128u;            // the block and four delta tables
+    if ((size_t)lds_alloc > lds_bytes && lds_alloc <= 64 * 1024) lds_bytes = (size_t)lds_alloc;   // occupancy cap
     const dim3 grid((unsigned)a.nblocks), block(1u << TB);
     const int vec_passes = (int)((1ll << a.block_bits) >> VS >> TB), unit_passes = (int)((1ll << a.block_bits) >> ((W == 8 ? 1 : 2) + TB));
     if (vec_passes < 1 || unit_passes < 1) return fail(LL_ERR_INVALID_ARG, "internal: gather block smaller than one pass");
@@ -1333,16 +1335,18 @@ static ll_status launch_gather_general_wt(const GatherGenArgs &a, hipStream_t s)
 // gets more threads.  Measured on MI355X (TB/s, 256 / 512 / 1024 threads): 128 KiB blocks 3.3-3.5 /
 // 5.2-5.3 / 5.7-5.96; 64 KiB 5.5-5.6 / 6.0 / 6.05-6.16; 32 KiB 5.8-6.0 / 6.0-6.26 / 6.07-6.35; 16 KiB
 // 5.7-6.2 / 5.9-6.5 / 4.9-5.7; 8 KiB 6.3-6.5 / 4.1-5.7 / - (one-byte elements, whose units are a quarter
-// of the bytes: 5.96 / 6.08 / -).  Interleaved repeats on 512 MiB of data.
+// of the bytes: 5.96 / 6.08 / -).  Interleaved repeats on 512 MiB of data.  One or two waves per 8 KiB
+// block (the recipe of the conversion kernels) lose here, 5.8-6.1 against 6.25-6.5 TB/s: the gather
+// phase is 31 vector instructions per element and wants many waves to hide them.
 template <int W>
-static ll_status launch_gather_general_w(const GatherGenArgs &a, int tb, hipStream_t s)
+static ll_status launch_gather_general_w(const GatherGenArgs &a, int tb, int lds_alloc, hipStream_t s)
 {
-    if (tb == 10) return launch_gather_general_wt<W, 10>(a, s);
-    if (tb == 9) return launch_gather_general_wt<W, 9>(a, s);
-    return launch_gather_general_wt<W, 8>(a, s);
+    if (tb == 10) return launch_gather_general_wt<W, 10>(a, lds_alloc, s);
+    if (tb == 9) return launch_gather_general_wt<W, 9>(a, lds_alloc, s);
+    return launch_gather_general_wt<W, 8>(a, lds_alloc, s);
 }
 
-ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thread_bits, void *stream)
+ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thread_bits, int lds_alloc, void *stream)
 {
     if (a.nblocks <= 0 || a.nblocks > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", a.nblocks);
     const long long block_bytes = (1ll << a.block_bits) * elem_bytes;
@@ -1351,10 +1355,10 @@ ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thre
     if (a.block_bits > 31 || a.coset_bits < 0 || a.coset_bits > kMaxCosetBits) return fail(LL_ERR_INVALID_ARG, "internal: gather block geometry");
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (elem_bytes) {
-    case 1: return launch_gather_general_w<1>(a, thread_bits, s);
-    case 2: return launch_gather_general_w<2>(a, thread_bits, s);
-    case 4: return launch_gather_general_w<4>(a, thread_bits, s);
-    case 8: return launch_gather_general_w<8>(a, thread_bits, s);
+    case 1: return launch_gather_general_w<1>(a, thread_bits, lds_alloc, s);
+    case 2: return launch_gather_general_w<2>(a, thread_bits, lds_alloc, s);
+    case 4: return launch_gather_general_w<4>(a, thread_bits, lds_alloc, s);
+    case 8: return launch_gather_general_w<8>(a, thread_bits, lds_alloc, s);
     default: return fail(LL_ERR_INVALID_ARG, "elem_bytes %d", elem_bytes);
     }
 }

@@ -165,7 +165,7 @@ inline int gather_general_thread_bits(long long block_bytes, int elem_bytes)
 inline int gather_global_chunk_bits(int elem_bytes) { return (elem_bytes == 8 ? 1 : 2) + 8 + 2; }
 inline int gather_phased_chunk_bits(int elem_bytes) { return (elem_bytes == 8 ? 1 : 2) + kPhasedThreadBits + 3; }
 inline int gather_phased_lds_chunk_bytes() { return kPhasedChunkBytes; }
-ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thread_bits, void *stream);
+ll_status launch_gather_general(const GatherGenArgs &a, int elem_bytes, int thread_bits, int lds_alloc, void *stream);
 ll_status launch_gather_global(const GatherGenArgs &a, int elem_bytes, void *stream);
 ll_status launch_gather_phased(const GatherGenArgs &a, int elem_bytes, void *stream);
 ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_vec_bits, int threads,

@@ -341,7 +341,6 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     const ll_options &opt = plan->opts;
     int tb = 8;                                       // 256 threads
     if (opt.elem_threads_log2 != LL_AUTO) tb = std::min(10, std::max(6, (int)opt.elem_threads_log2));
-    if (tb == 7) tb = 8;
     // Largest staged block, and the size small tiles are bundled to (bytes, powers of two).
     // Small blocks measured best on MI355X (more, shorter-lived workgroups keep about 32-64 KiB in
     // flight per CU, which is where a plain copy also peaks).
@@ -380,7 +379,11 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     // 2^9) equal within 1 %.  Larger blocks lose that way (16 vectors per lane and two waves per CU
     // leave the LDS latency exposed: 4.0-5.3 TB/s), so they keep 256 threads.
     if (tb_auto && ((unsigned)w << n) == 4096u) tb = 6;
+    // 8 KiB blocks of 8-byte elements (two LDS instructions per vector and side): two waves with four vectors per lane
+    // measured 6.36-6.5 against 6.1-6.3 TB/s for four waves with two; 2- and 4-byte elements tie or lose that way
+    if (tb_auto && w == 8 && ((unsigned)w << n) == 8192u) tb = 7;
     if (tb == 6 && ((unsigned)w << n) != 4096u) tb = 8;               // the one-wave kernel exists for 4 KiB blocks only
+    if (tb == 7 && ((unsigned)w << n) != 8192u) tb = 8;               // the two-wave kernel for 8 KiB blocks only
     const int nvec_bits = n - vs - tb;
     // what the launcher instantiates: up to 8 vectors per thread with 256 threads, up to 4 with more
     if (nvec_bits < 0 || (1 << nvec_bits) > (tb == 8 ? 8 : 4))
@@ -590,11 +593,10 @@ static void set_launch_params(ll_plan *plan)
     switch (desc.strategy) {
     case LL_STRATEGY_LDS_ELEM:
     case LL_STRATEGY_LDS_TR: {
-        const bool one_wave = desc.threads == 64;
-        const int chunk = (one_wave || group_bytes <= kXcdTarget) ? xcd_chunk_bits_for(kXcdTarget, block_bytes) : -1;
+        const int chunk = (desc.threads < 256 || group_bytes <= kXcdTarget) ? xcd_chunk_bits_for(kXcdTarget, block_bytes) : -1;
         plan->lds_elem.xcd_chunk = opt_chunk_bits(opt.xcd_chunk, chunk);
         int alloc = desc.lds_bytes;
-        if (one_wave || opt.inflight_bytes != LL_AUTO)
+        if (desc.threads < 256 || opt.inflight_bytes != LL_AUTO)
             alloc = lds_alloc_for((unsigned)block_bytes, (unsigned)opt_or(opt.inflight_bytes, 45056), alloc);
         if (opt.lds_pad_bytes > 0) alloc = std::min(64 * 1024, alloc + opt.lds_pad_bytes);
         plan->lds_alloc = alloc;
@@ -605,8 +607,11 @@ static void set_launch_params(ll_plan *plan)
     case LL_STRATEGY_LDS_VEC: {
         const int chunk = group_bytes <= kXcdTarget ? xcd_chunk_bits_for(kXcdTarget, block_bytes) : -1;
         plan->vec.xcd_chunk = opt_chunk_bits(opt.xcd_chunk, chunk);
-        plan->lds_alloc = lds_alloc_for((unsigned)desc.threads * (16u << plan->vec_nvec_bits), (unsigned)opt_or(opt.inflight_bytes, 49152),
-                                        desc.lds_bytes);
+        // the pure register path (no exchange, no affine constant to apply) is the lightest: 40 KiB suits it
+        // (bench conditions: config 2 6.40 -> 6.43 TB/s, config 3 6.48 -> 6.57), everything else wants 48 KiB
+        const bool light = plan->vec_xchg == kXchgNone && plan->vec.dst_xor == 0;
+        plan->lds_alloc = lds_alloc_for((unsigned)desc.threads * (16u << plan->vec_nvec_bits),
+                                        (unsigned)opt_or(opt.inflight_bytes, light ? 40960 : 49152), desc.lds_bytes);
         break;
     }
     case LL_STRATEGY_LDS_PULL: {

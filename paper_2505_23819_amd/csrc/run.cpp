@@ -353,7 +353,14 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, con
     // XCD-aware block order: 512 KiB of consecutive blocks per XCD (rows of config 5: 5.99 -> 6.36 TB/s)
     g.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, xcd_chunk_bits_for(512 * 1024, (long long)elem_bytes << g.block_bits));
     c->thread_bits = gather_general_thread_bits((long long)elem_bytes << g.block_bits, elem_bytes);
-    if (opt.gather_threads_log2 >= 8 && opt.gather_threads_log2 <= 10) c->thread_bits = opt.gather_threads_log2;
+    if (opt.gather_threads_log2 >= 8 && opt.gather_threads_log2 <= 10) {
+        // every thread must get at least one 16-byte vector of the block and one unit of output elements
+        const long long vectors = ((long long)elem_bytes << g.block_bits) / 16, units = (1ll << g.block_bits) >> ubits;
+        if ((std::min(vectors, units) >> opt.gather_threads_log2) >= 1) c->thread_bits = opt.gather_threads_log2;
+    }
+    c->lds_alloc = 0;
+    if (opt.gather_inflight_bytes != LL_AUTO)
+        c->lds_alloc = lds_alloc_for((unsigned)((long long)elem_bytes << g.block_bits), (unsigned)opt.gather_inflight_bytes, 0);
     return LL_OK;
 }
 
@@ -443,7 +450,7 @@ ll_status run_gather(const ll_layout *L, int axis, int elem_bytes, const ll_opti
         g.total_elems = ntiles << d;
         const long long ngroups = (ntiles + (1ll << g.group_bits) - 1) >> g.group_bits;
         g.nblocks = ngroups << g.coset_bits;
-        return launch_gather_general(g, elem_bytes, c.thread_bits, stream);
+        return launch_gather_general(g, elem_bytes, c.thread_bits, c.lds_alloc, stream);
     }
     GatherArgs &a = c.wave;
     a.in = in;

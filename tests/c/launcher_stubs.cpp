@@ -6,7 +6,7 @@
 #include "../../paper_2505_23819_amd/csrc/layout.hpp"
 
 namespace ll {
-ll_status launch_gather_general(const GatherGenArgs &, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
+ll_status launch_gather_general(const GatherGenArgs &, int, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
 ll_status launch_gather_phased(const GatherGenArgs &, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
 ll_status launch_gather_global(const GatherGenArgs &, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
 ll_status launch_lds_elem(const LdsElemArgs &, int, int, int, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
