@@ -930,9 +930,12 @@ __global__ __launch_bounds__(256) void k_gather_rows(const GatherArgs a)
 // lane k of a load or store instruction takes the k-th 16-byte (or 8-byte) piece of the chunk.  The
 // source values of the wave's chunk are staged in a wave-private LDS region, one row per layout
 // lane, and each output element is fetched with one LDS read at the row its index names.  This is
-// the same crossbar the lane shuffle uses (ds_bpermute reads a 64-dword row through it); the
-// condition that lets it run without workgroup synchronisation is the one of Sec. 5.5: the axis
-// stays inside the wave.  Rows are XOR-swizzled so that reads of one register from 32 different
+// the same crossbar the lane shuffle uses (ds_bpermute reads a 64-dword row through it).  No data
+// crosses between waves - the condition of Sec. 5.5, the axis stays inside the wave - so each wave
+// only needs its own LDS writes to be visible before it reads; the kernel is launched with one wave
+// per workgroup by default, and the __syncthreads() between staging and gathering is then a wave-
+// local barrier (with 2 or 4 waves per workgroup, on request, every wave of the group reaches it:
+// none leaves early).  Rows are XOR-swizzled so that reads of one register from 32 different
 // rows fall in 32 different banks (random indices then collide only as often as random lanes do).
 //   unit      the 4- or 8-byte word an element lives in
 //   row s     holds RU units; unit q of row s is stored at unit address s*RU + (q ^ f(s))
