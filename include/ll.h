@@ -232,6 +232,7 @@ typedef struct {
     int32_t copy_xcd_chunk;        /* ll_copy (process defaults only) */
     int32_t debug;                 /* 1: planners say on stderr why a strategy did not apply */
     int32_t gather_waves;          /* waves per workgroup of the wave-level gather kernels (one chunk each): 1, 2 or 4 */
+    int32_t pull_threads_log2;     /* threads per workgroup of the broadcast kernel: 6 (one wave), 7 or 8 */
 } ll_options;
 
 ll_status ll_options_init(ll_options *opts);

@@ -60,7 +60,7 @@ class ll_options(ctypes.Structure):
         "vec_threads", "shuffle_block_bytes", "inflight_bytes", "lds_pad_bytes", "xcd_chunk", "pull_mode",
         "pull_vec_bits", "pull_inflight_bytes", "pull_xcd_chunk", "gather_block_bytes", "gather_lds_max_bytes",
         "gather_min_run_bytes", "gather_phased_max_bytes", "gather_threads_log2", "gather_inflight_bytes",
-        "gather_xcd_chunk", "gather_swizzle_always", "copy_xcd_chunk", "debug", "gather_waves")]
+        "gather_xcd_chunk", "gather_swizzle_always", "copy_xcd_chunk", "debug", "gather_waves", "pull_threads_log2")]
 
 
 class ll_in_dim(ctypes.Structure):

@@ -173,7 +173,7 @@ ll_status launch_lds_elem(const LdsElemArgs &a, int elem_bytes, int nvec, int ld
 ll_status launch_vec(const VecArgs &a, int elem_bytes, int nvec_bits, int tpose, int xchg, int threads, int lds_bytes,
                      void *stream);
 ll_status launch_lds_tr(const LdsElemArgs &a, int elem_bytes, int nvec, int lds_bytes, void *stream);
-ll_status launch_pull(const PullArgs &a, int elem_bytes, int src_iters, int vec_bits, int lds_bytes, void *stream);
+ll_status launch_pull(const PullArgs &a, int elem_bytes, int src_iters, int vec_bits, int thread_bits, int lds_bytes, void *stream);
 ll_status launch_gather(const GatherArgs &a, int elem_bytes, int waves, int lds_alloc, void *stream);
 ll_status launch_copy(const void *src, void *dst, long long bytes, int xcd_chunk_bits, void *stream);
 

@@ -41,6 +41,7 @@ const Field kFields[] = {
     LL_FIELD(copy_xcd_chunk, "LL_COPY_XCD_CHUNK"),
     LL_FIELD(debug, "LL_DEBUG"),
     LL_FIELD(gather_waves, "LL_GATHER_WAVES"),
+    LL_FIELD(pull_threads_log2, "LL_PULL_THREADS_LOG2"),
 };
 #undef LL_FIELD
 int32_t &field(ll_options *o, size_t offset) { return *reinterpret_cast<int32_t *>(reinterpret_cast<char *>(o) + offset); }

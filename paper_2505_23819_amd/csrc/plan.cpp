@@ -621,7 +621,7 @@ static void set_launch_params(ll_plan *plan)
         plan->pull.xcd_chunk = opt_chunk_bits(opt.pull_xcd_chunk, xcd_chunk_bits_for(target, block_bytes));
         plan->lds_alloc = desc.lds_bytes;
         if (opt.pull_inflight_bytes != LL_AUTO)
-            plan->lds_alloc = lds_alloc_for(256u * 16u * (unsigned)plan->pull.dst_iters, (unsigned)opt.pull_inflight_bytes, desc.lds_bytes);
+            plan->lds_alloc = lds_alloc_for((16u << plan->pull_thread_bits) * (unsigned)plan->pull.dst_iters, (unsigned)opt.pull_inflight_bytes, desc.lds_bytes);
         break;
     }
     default:

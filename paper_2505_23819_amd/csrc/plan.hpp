@@ -63,7 +63,7 @@ struct ll_plan {
     ll::VecArgs vec = {};
     int vec_nvec_bits = 0, vec_tpose = 0, vec_xchg = 0;
     ll::PullArgs pull = {};
-    int pull_src_iters = 0, pull_vec_bits = 0;
+    int pull_src_iters = 0, pull_vec_bits = 0, pull_thread_bits = 8;
 };
 
 namespace ll {

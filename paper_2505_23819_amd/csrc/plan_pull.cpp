@@ -32,21 +32,22 @@ static vec xor_sel(const mat &cols, int first, unsigned idx)
 }
 
 // Host-side walk of one block, as the kernel indexes it.
-static ll_status check_pull_block(const PullArgs &a, const mat &rext, vec cconst, int vs, int v, int w, int src_iters, int lds_bytes,
+static ll_status check_pull_block(const PullArgs &a, const mat &rext, vec cconst, int vs, int v, int w, int tb, int src_iters, int lds_bytes,
                                   uint32_t cs, uint32_t cd, uint32_t cr)
 {
+    const int threads = 1 << tb;
     const int E = 1 << vs, A = 1 << v;                // elements per global vector / per LDS access
     const uint64_t src_group = 1ull << (a.d_src + a.group_bits), dst_group = 1ull << (a.d_dst + a.group_bits);
     std::vector<int64_t> held((size_t)lds_bytes / w, -1);
     auto lane_part = [&](const uint32_t *tab, int tid) {
         uint32_t x = 0;
-        for (int b = 0; b < 8; ++b)
+        for (int b = 0; b < tb; ++b)
             if ((tid >> b) & 1) x ^= tab[b];
         return x;
     };
-    for (int tid = 0; tid < 256; ++tid)
+    for (int tid = 0; tid < threads; ++tid)
         for (int i = 0; i < src_iters; ++i) {
-            if ((unsigned)(tid + 256 * i) >= (1u << a.src_vec_bits)) continue;
+            if ((unsigned)(tid + threads * i) >= (1u << a.src_vec_bits)) continue;
             const uint32_t off = cs ^ lane_part(a.lane_src, tid) ^ a.iter_src[i];
             if (off >= src_group || (off & (uint32_t)(E - 1))) return fail(LL_ERR_INVALID_ARG, "internal: bad source offset in broadcast plan");
             for (int s = 0; s < E; ++s) {
@@ -58,7 +59,7 @@ static ll_status check_pull_block(const PullArgs &a, const mat &rext, vec cconst
                 held[addr / w] = (int64_t)off + s;
             }
         }
-    for (int tid = 0; tid < 256; ++tid)
+    for (int tid = 0; tid < threads; ++tid)
         for (int it = 0; it < a.dst_iters; ++it) {
             uint32_t ib = 0, ob = 0;
             for (int b = 0; (it >> b) != 0; ++b)
@@ -80,11 +81,11 @@ static ll_status check_pull_block(const PullArgs &a, const mat &rext, vec cconst
 
 // One attempt with blocks of at most 2^n_max elements.  *too_large: the source vectors behind such a
 // block exceed what one workgroup stages (a source whose 16-byte vectors hold few canonical slots).
-static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int mode, int n_max, ll_plan *plan, bool *too_large)
+static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int mode, int n_max, int tb, ll_plan *plan, bool *too_large)
 {
     const LdsModel hw;
     const int dA = A->d_in, dB = B->d_in, dl = A->d_out;
-    const int vs = ilog2p(16u / (unsigned)w), tb = 8;
+    const int vs = ilog2p(16u / (unsigned)w);
     mat aplus;
     if (!f2::right_inverse(A->bases, dl, &aplus)) return fail(LL_ERR_NOT_SURJECTIVE, "source layout does not cover the whole logical tensor");
     const mat r = f2::compose(aplus, B->bases);                 // dB columns in F2^dA
@@ -263,15 +264,16 @@ static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int
     const int lds_bytes = (1 << ns) * w;
     plan->pull_src_iters = src_iters;
     plan->pull_vec_bits = v;
+    plan->pull_thread_bits = tb;
     {
-        ll_status st = check_pull_block(a, rext, cconst, vs, v, w, src_iters, lds_bytes, a.src_xor, 0, a.lds_rd_xor);
+        ll_status st = check_pull_block(a, rext, cconst, vs, v, w, tb, src_iters, lds_bytes, a.src_xor, 0, a.lds_rd_xor);
         const uint32_t cs0 = a.src_xor, cr0 = a.lds_rd_xor;
         uint32_t cs = cs0, cd = 0, cr = cr0;
         for (int c = 0; c < a.coset_bits && st == LL_OK; ++c) {
-            st = check_pull_block(a, rext, cconst, vs, v, w, src_iters, lds_bytes, cs0 ^ a.coset_src[c], a.coset_dst[c], cr0 ^ a.coset_lds_rd[c]);
+            st = check_pull_block(a, rext, cconst, vs, v, w, tb, src_iters, lds_bytes, cs0 ^ a.coset_src[c], a.coset_dst[c], cr0 ^ a.coset_lds_rd[c]);
             cs ^= a.coset_src[c]; cd ^= a.coset_dst[c]; cr ^= a.coset_lds_rd[c];
         }
-        if (st == LL_OK && a.coset_bits > 1) st = check_pull_block(a, rext, cconst, vs, v, w, src_iters, lds_bytes, cs, cd, cr);
+        if (st == LL_OK && a.coset_bits > 1) st = check_pull_block(a, rext, cconst, vs, v, w, tb, src_iters, lds_bytes, cs, cd, cr);
         if (st != LL_OK) return st;
     }
 
@@ -285,7 +287,7 @@ static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int
     desc.global_vec_bytes = 16;
     desc.lds_write_bytes = desc.lds_read_bytes = w << v;
     desc.lds_bytes = lds_bytes;
-    desc.threads = 256;
+    desc.threads = 1 << tb;
     desc.vectors_per_thread = a.dst_iters;
     desc.block_bits = nd; desc.group_bits = g; desc.segment_bits = k;
     desc.lds_vec_bits = v;
@@ -300,7 +302,8 @@ static ll_status plan_pull_at(const ll_layout *A, const ll_layout *B, int w, int
 
 ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan)
 {
-    const int vs = ilog2p(16u / (unsigned)w), tb = 8;
+    const int vs = ilog2p(16u / (unsigned)w);
+    const int tb = plan->opts.pull_threads_log2 == 6 ? 6 : 8;
     // A destination that replicates 4x or more makes the conversion write-dominated: destination
     // runs first, and 16 KiB blocks (four stores in flight per thread measured fastest on MI355X;
     // read-dominated and balanced conversions do best at 8 KiB).
@@ -313,7 +316,7 @@ ll_status plan_pull(const ll_layout *A, const ll_layout *B, int w, ll_plan *plan
     // source vector per element, 2^vs per thread, which the kernel covers.
     for (int n_max = std::max(vs + tb, ilog2p(max_block / (unsigned)w));; --n_max) {
         bool too_large = false;
-        const ll_status st = plan_pull_at(A, B, w, mode, n_max, plan, &too_large);
+        const ll_status st = plan_pull_at(A, B, w, mode, n_max, tb, plan, &too_large);
         if (st == LL_OK || !too_large || n_max == vs + tb) return st;
     }
 }

@@ -62,7 +62,7 @@ ll_status run_convert(const ll_plan *plan, const void *src, void *dst, long long
         a.ntiles = ntiles;
         const long long groups = (ntiles + (1ll << a.group_bits) - 1) >> a.group_bits;
         a.nblocks = groups << a.coset_bits;
-        return launch_pull(a, desc.elem_bytes, plan->pull_src_iters, plan->pull_vec_bits, plan->lds_alloc, stream);
+        return launch_pull(a, desc.elem_bytes, plan->pull_src_iters, plan->pull_vec_bits, plan->pull_thread_bits, plan->lds_alloc, stream);
     }
     default:
         return fail(LL_ERR_UNSUPPORTED, "plan strategy %d has no kernel", desc.strategy);

@@ -104,6 +104,7 @@ static const ll_options *rand_options(ll_options *o)
     if (ri(0, 2) == 0) o->pull_mode = ri(-1, 3);
     if (ri(0, 2) == 0) o->pull_vec_bits = ri(-1, 5);
     if (ri(0, 2) == 0) o->pull_inflight_bytes = bytes[ri(0, 9)];
+    if (ri(0, 2) == 0) o->pull_threads_log2 = ri(4, 9);
     if (ri(0, 2) == 0) o->gather_block_bytes = bytes[ri(0, 9)];
     if (ri(0, 2) == 0) o->gather_lds_max_bytes = bytes[ri(0, 9)];
     if (ri(0, 2) == 0) o->gather_min_run_bytes = 1 << ri(0, 9);

@@ -12,7 +12,7 @@ ll_status launch_gather_global(const GatherGenArgs &, int, void *) { return fail
 ll_status launch_lds_elem(const LdsElemArgs &, int, int, int, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
 ll_status launch_vec(const VecArgs &, int, int, int, int, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
 ll_status launch_lds_tr(const LdsElemArgs &, int, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
-ll_status launch_pull(const PullArgs &, int, int, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
+ll_status launch_pull(const PullArgs &, int, int, int, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
 ll_status launch_gather(const GatherArgs &, int, int, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
 ll_status launch_copy(const void *, void *, long long, int, void *) { return fail(LL_ERR_DEVICE, "stub: no device code in this build"); }
 }  // namespace ll

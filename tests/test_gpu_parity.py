@@ -298,6 +298,11 @@ def test_convert_paper_zero_column_example(w):
             assert np.array_equal(got, oracle.convert_general(cx, cy, 8, src)), (len(cx), len(cy), ntiles)
 
 
+# the broadcast kernel as planned by default, with one wave per block, and with one wave on 4 KiB blocks
+PULL_OPTION_SETS = (None, lambda: ll.ll_options_init(pull_threads_log2=6),
+                    lambda: ll.ll_options_init(pull_threads_log2=6, block_bytes=4096))
+
+
 @pytest.mark.parametrize("w", [1, 2, 4, 8])
 @pytest.mark.parametrize("da,db,dl", [(9, 8, 8), (8, 10, 8), (12, 12, 10), (14, 13, 12), (16, 14, 12),
                                       (7, 9, 6), (10, 12, 10), (13, 13, 13)])
@@ -307,23 +312,26 @@ def test_convert_random_broadcast_layouts(w, da, db, dl):
         ca, cb = surjective_bases(rng, da, dl), surjective_bases(rng, db, dl)
         a = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, da - 2)], [dl], ca)
         b = ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, db - 2)], [dl], cb)
-        plan = ll.ll_plan_convert(a, b, w)
         ntiles = int(rng.integers(1, 40))
         src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << da, dtype=NP_DTYPES[w])
-        got = run_convert_general(plan, src, da, db)
-        assert np.array_equal(got, oracle.convert_general(ca, cb, dl, src)), (trial, plan.info()["strategy_name"])
+        want = oracle.convert_general(ca, cb, dl, src)
+        for opts in PULL_OPTION_SETS:
+            plan = ll.ll_plan_convert(a, b, w, opts() if opts else None)
+            got = run_convert_general(plan, src, da, db)
+            assert np.array_equal(got, want), (trial, plan.info()["strategy_name"], plan.info()["threads"])
 
 
 @pytest.mark.parametrize("case", wl.broadcast_cases(), ids=lambda c: c.name.split(" (")[0].replace(" ", "_"))
 def test_convert_broadcast_workloads_small(case):
     a = ll.distributed_layout(*case.src_in, case.out_dim_bits, case.src_bases)
     b = ll.distributed_layout(*case.dst_in, case.out_dim_bits, case.dst_bases)
-    plan = ll.ll_plan_convert(a, b, case.elem_bytes)
-    assert plan.info()["kind_name"] == "broadcast"
-    for ntiles in (1, 5):
-        src = wl.to_numpy_bits(case.gen_data(0, ntiles))
-        got = run_convert_general(plan, src, case.d_src, case.d_dst)
-        assert np.array_equal(got, oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, src))
+    for opts in PULL_OPTION_SETS:
+        plan = ll.ll_plan_convert(a, b, case.elem_bytes, opts() if opts else None)
+        assert plan.info()["kind_name"] == "broadcast"
+        for ntiles in (1, 5):
+            src = wl.to_numpy_bits(case.gen_data(0, ntiles))
+            got = run_convert_general(plan, src, case.d_src, case.d_dst)
+            assert np.array_equal(got, oracle.convert_general(case.src_bases, case.dst_bases, case.d_out, src)), plan.info()["threads"]
 
 
 # ---------------------------------------------------------------------------------------------
@@ -737,11 +745,13 @@ def test_convert_broadcast_affine_layouts(w):
             oa, ob = int(rng.integers(0, 1 << dl)), int(rng.integers(0, 1 << dl))
             a = ll.ll_layout_with_offset(ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, da - 2)], [dl], ca), oa)
             b = ll.ll_layout_with_offset(ll.ll_layout_create([(ll.LL_IN_REG, 2), (ll.LL_IN_LANE, db - 2)], [dl], cb), ob)
-            plan = ll.ll_plan_convert(a, b, w)
             ntiles = int(rng.integers(1, 30))
             src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=ntiles << da, dtype=NP_DTYPES[w])
-            got = run_convert_general(plan, src, da, db)
-            assert np.array_equal(got, oracle.convert_general_affine(ca, oa, cb, ob, dl, src)), (da, db, trial)
+            want = oracle.convert_general_affine(ca, oa, cb, ob, dl, src)
+            for opts in PULL_OPTION_SETS:
+                plan = ll.ll_plan_convert(a, b, w, opts() if opts else None)
+                got = run_convert_general(plan, src, da, db)
+                assert np.array_equal(got, want), (da, db, trial, plan.info()["threads"])
 
 
 def test_gather_along_an_axis_of_one_element():
