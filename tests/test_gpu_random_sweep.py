@@ -82,10 +82,68 @@ def ntiles_for(rng, d, w, cap_bits=20):
     return m
 
 
-def run_case(seed):
+def rand_options(seed, kind):
+    """Options drawn from their documented domains (their own generator, so that the case drawn for a seed
+    is the same with and without them): other kernels, block sizes, workgroup shapes and block orders."""
+    rng = np.random.default_rng(seed ^ 0x5EED0)
+    pick = lambda values: int(values[int(rng.integers(0, len(values)))])
+    f = {}
+    if kind == 0:
+        if rng.integers(0, 2):
+            f["strategy"] = pick([ll.LL_STRATEGY_LDS_ELEM, ll.LL_STRATEGY_LDS_VEC, ll.LL_STRATEGY_LDS_TR])
+        if rng.integers(0, 2):
+            f["elem_threads_log2"] = pick([6, 7, 8, 9, 10])
+        if rng.integers(0, 3) == 0:
+            f["block_bytes"] = pick([4096, 8192, 16384, 32768])
+        if rng.integers(0, 3) == 0:
+            f["vec_threads"] = pick([64, 128, 256])
+        if rng.integers(0, 3) == 0:
+            f["shuffle_block_bytes"] = pick([4096, 8192])
+        if rng.integers(0, 3) == 0:
+            f["xcd_chunk"] = pick([0, 1, 2, 16, 256])
+        if rng.integers(0, 3) == 0:
+            f["inflight_bytes"] = pick([16384, 32768, 65536, 131072])
+        if rng.integers(0, 4) == 0:
+            f["pref_bytes"] = pick([4096, 16384])
+    elif kind == 1:
+        if rng.integers(0, 2):
+            f["pull_threads_log2"] = 6
+        if rng.integers(0, 2):
+            f["block_bytes"] = pick([1024, 4096, 8192, 16384])
+        if rng.integers(0, 3) == 0:
+            f["pull_mode"] = pick([0, 1, 2])
+        if rng.integers(0, 3) == 0:
+            f["pull_vec_bits"] = pick([0, 1, 2])
+        if rng.integers(0, 3) == 0:
+            f["pull_xcd_chunk"] = pick([0, 1, 4, 64])
+        if rng.integers(0, 3) == 0:
+            f["pull_inflight_bytes"] = pick([16384, 65536])
+    else:
+        if rng.integers(0, 3):
+            f["gather_kernel"] = pick([ll.LL_GATHER_SHUFFLE, ll.LL_GATHER_WAVE_STAGED, ll.LL_GATHER_BLOCK_STAGED,
+                                       ll.LL_GATHER_SHUFFLE_ROWS])
+        if rng.integers(0, 2):
+            f["gather_waves"] = pick([1, 2, 4])
+        if rng.integers(0, 3) == 0:
+            f["gather_threads_log2"] = pick([8, 9, 10])
+        if rng.integers(0, 3) == 0:
+            f["gather_block_bytes"] = pick([4096, 16384, 65536])
+        if rng.integers(0, 3) == 0:
+            f["gather_lds_max_bytes"] = pick([16384, 65536, 131072])
+        if rng.integers(0, 3) == 0:
+            f["gather_xcd_chunk"] = pick([0, 1, 4, 64])
+        if rng.integers(0, 4) == 0:
+            f["gather_phased_max_bytes"] = pick([262144, 1048576])
+        if rng.integers(0, 4) == 0:
+            f["gather_swizzle_always"] = 1
+    return ll.ll_options_init(**f), tuple(sorted(f.items()))
+
+
+def run_case(seed, with_options=False):
     rng = np.random.default_rng(seed)
     kind = int(rng.integers(0, 3))
     w = int(rng.choice([1, 2, 4, 8]))
+    opts, chosen = rand_options(seed, kind) if with_options else (None, ())
     if kind == 0:
         d = int(rng.integers(2, 19))
         sa = split(rng, d)
@@ -101,10 +159,10 @@ def run_case(seed):
         offa = int(rng.integers(0, 1 << dd)) if rng.integers(0, 3) == 0 else 0
         offb = int(rng.integers(0, 1 << dd)) if rng.integers(0, 3) == 0 else 0
         od = out_dims_of(rng, d)
-        desc = ("conv", seed, w, d, sa, sb, ka, kb, offa, offb)
+        desc = ("conv", seed, w, d, sa, sb, ka, kb, offa, offb, chosen)
         a = ll.ll_layout_with_offset(mk(sa, od, ca), offa)
         b = ll.ll_layout_with_offset(mk(sb, od, cb), offb)
-        plan = ll.ll_plan_convert(a, b, w)
+        plan = ll.ll_plan_convert(a, b, w, opts)
         nt = ntiles_for(rng, d, w)
         src = rng.integers(0, np.iinfo(NP[w]).max, size=nt << d, dtype=NP[w])
         ts = torch.from_numpy(src.view(TD[w])).cuda()
@@ -124,10 +182,10 @@ def run_case(seed):
         offa = int(rng.integers(0, 1 << dl)) if rng.integers(0, 3) == 0 else 0
         offb = int(rng.integers(0, 1 << dl)) if rng.integers(0, 3) == 0 else 0
         od = out_dims_of(rng, dl)
-        desc = ("bcast", seed, w, dl, da, db, sa, sb, ka, kb, offa, offb)
+        desc = ("bcast", seed, w, dl, da, db, sa, sb, ka, kb, offa, offb, chosen)
         a = ll.ll_layout_with_offset(mk(sa, od, ca), offa)
         b = ll.ll_layout_with_offset(mk(sb, od, cb), offb)
-        plan = ll.ll_plan_convert(a, b, w)
+        plan = ll.ll_plan_convert(a, b, w, opts)
         unit = max(1, 16 // w)
         nt = int(rng.integers(1, 12))
         while ((nt << da) % unit) or ((nt << db) % unit):
@@ -147,7 +205,7 @@ def run_case(seed):
     off = int(rng.integers(0, 1 << dl)) if rng.integers(0, 3) == 0 else 0
     od = out_dims_of(rng, dl)
     axis = int(rng.integers(0, len(od)))
-    desc = ("gather", seed, w, dl, d, s, k, off, od, axis)
+    desc = ("gather", seed, w, dl, d, s, k, off, od, axis, chosen)
     lay = ll.ll_layout_with_offset(mk(s, od, cols), off)
     nt = ntiles_for(rng, d, w)
     inp = rng.integers(0, np.iinfo(NP[w]).max, size=nt << d, dtype=NP[w])
@@ -156,7 +214,7 @@ def run_case(seed):
     idx = rng.integers(-(1 << od[axis]) - 3, (1 << od[axis]) + 3, size=nt << d, dtype=np.int32)
     ti, tx = torch.from_numpy(inp.view(TD[w])).cuda(), torch.from_numpy(idx).cuda()
     to = torch.full_like(ti, 0x5A)
-    ll.ll_gather(lay, axis, w, ti, tx, to, nt)
+    ll.ll_gather(lay, axis, w, ti, tx, to, nt, opts=opts)
     torch.cuda.synchronize()
     return desc, to.cpu().numpy().view(NP[w]), oracle.gather_general(cols, od, axis, inp, idx, off)
 
@@ -166,6 +224,21 @@ def test_random_layouts_sizes_and_widths(chunk):
     counts = {"conv": 0, "bcast": 0, "gather": 0}
     for case in range(400):
         res = run_case(77000000 + 1000 * chunk + case)
+        if res is None:
+            continue
+        desc, got, want = res
+        assert np.array_equal(got, want), desc
+        counts[desc[0]] += 1
+    assert min(counts.values()) > 80
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_random_layouts_under_random_options(chunk):
+    """The same kinds of cases with options drawn at random: kernels the planner would not pick by itself,
+    other block sizes, workgroup shapes and block orders must give the same bits."""
+    counts = {"conv": 0, "bcast": 0, "gather": 0}
+    for case in range(400):
+        res = run_case(78000000 + 1000 * chunk + case, with_options=True)
         if res is None:
             continue
         desc, got, want = res
