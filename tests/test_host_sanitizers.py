@@ -2,7 +2,8 @@
 with g++ under AddressSanitizer and UndefinedBehaviorSanitizer against stub launchers, and driven
 by a bounded, seeded fuzz through the C ABI: random layouts (arbitrary XOR columns, distributed,
 broadcasting, memory, affine), element widths, axes and option sets, including option values outside
-their documented domains.  Any sanitizer report, unexpected status or crash fails the test.  No GPU."""
+their documented domains.  Any sanitizer report, unexpected status or crash fails the test.
+A second program uses shared layouts and plans from eight threads at once under ThreadSanitizer.  No GPU."""
 import os
 import subprocess
 
@@ -34,3 +35,21 @@ def test_host_fuzz_under_asan_and_ubsan(fuzz_binary, seed, cases):
     assert res.returncode == 0, (res.stdout[-500:], res.stderr[-3000:])
     assert res.stdout.startswith("cases %d planned" % cases)
     assert "runtime error" not in res.stderr and "AddressSanitizer" not in res.stderr and "LeakSanitizer" not in res.stderr
+
+
+def test_shared_layouts_and_plans_from_many_threads_under_tsan(tmp_path):
+    """Layouts (with their lock-free cache of gather choices) and plans are shared by eight threads that query,
+    plan and launch against the stub launchers; every answer must equal the single-threaded one and
+    ThreadSanitizer must stay silent."""
+    exe = str(tmp_path / "host_threads")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=thread", "-fno-omit-frame-pointer", "-pthread", "-Wall", "-Wextra",
+           "-Wno-unused-parameter"]
+    cmd += [os.path.join(CSRC, f) for f in HOST_SOURCES]
+    cmd += [os.path.join(ROOT, "tests", "c", "launcher_stubs.cpp"), os.path.join(ROOT, "tests", "c", "host_threads.cpp"), "-o", exe]
+    res = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    assert res.returncode == 0, res.stderr[-3000:]
+    env = dict(os.environ, TSAN_OPTIONS="halt_on_error=0:exitcode=66")
+    res = subprocess.run([exe, "8", "30"], capture_output=True, text=True, timeout=600, env=env)
+    assert res.returncode == 0, (res.stdout[-500:], res.stderr[-3000:])
+    assert res.stdout.startswith("threads 8 rounds 30") and res.stdout.strip().endswith("mismatches 0")
+    assert "ThreadSanitizer" not in res.stderr
