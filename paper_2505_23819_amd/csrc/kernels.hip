@@ -1274,7 +1274,8 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
         // When the deltas are consecutive single bits of the block-local index and nothing is swizzled
         // (a row gather in a row-major tile), the LDS offset of a move is the coordinate difference
         // shifted into place: no table lookups.  The choice is uniform and made per pass.
-        auto gather_units = [&](auto shifted) {
+        auto gather_units = [&](auto mode) {
+        constexpr int kMode = decltype(mode)::value;       // 0: four tables, 1: shifted coordinate, 2: two tables (axis of at most 2^10)
 #pragma unroll
         for (int q = 0; q < U; ++q) {
             const uint32_t unit = tid + T * (p + q);
@@ -1284,8 +1285,10 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
             for (int s = 0; s < UE; ++s) {
                 const uint32_t x = (ix[q][s] ^ own_p[q] ^ own_s[s]) & a.axis_mask;
                 uint32_t t;
-                if constexpr (decltype(shifted)::value) {
+                if constexpr (kMode == 1) {
                     t = x << a.field_shift;
+                } else if constexpr (kMode == 2) {
+                    t = table[x & 31u] ^ table[32u + (x >> 5)];
                 } else {
                     t = table[x & 31u];
                     t ^= table[32u + ((x >> 5) & 31u)] ^ table[64u + ((x >> 10) & 31u)] ^ table[96u + (x >> 15)];
@@ -1314,9 +1317,11 @@ __global__ __launch_bounds__(1 << TB) void k_gather_general(const GatherGenArgs 
         }
         };
         if (a.field_shift >= 0)
-            gather_units(std::true_type{});
+            gather_units(std::integral_constant<int, 1>{});
+        else if (a.na <= 10)
+            gather_units(std::integral_constant<int, 2>{});
         else
-            gather_units(std::false_type{});
+            gather_units(std::integral_constant<int, 0>{});
     }
 }
 
