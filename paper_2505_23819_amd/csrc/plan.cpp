@@ -598,6 +598,14 @@ static void set_launch_params(ll_plan *plan)
         int alloc = desc.lds_bytes;
         if (desc.threads < 256 || opt.inflight_bytes != LL_AUTO)
             alloc = lds_alloc_for((unsigned)block_bytes, (unsigned)opt_or(opt.inflight_bytes, 45056), alloc);
+        else if (block_bytes == 8192)
+            // four waves on 8 KiB blocks: six workgroups per CU instead of the eight that fit (1- and 2-byte elements
+            // under random XOR maps and bit permutations: +2..6 %, e.g. 6.27 -> 6.52 TB/s on 2^12-element tiles);
+            // 16 KiB blocks want all the workgroups they can get
+            alloc = lds_alloc_for(8192u, 49152u, alloc);
+        else if (desc.strategy == LL_STRATEGY_LDS_TR && block_bytes == 16384)
+            // the transposing loads on 16 KiB blocks: three to five workgroups per CU 6.16-6.20 TB/s, six and more 5.8
+            alloc = lds_alloc_for(16384u, 65536u, alloc);
         if (opt.lds_pad_bytes > 0) alloc = std::min(64 * 1024, alloc + opt.lds_pad_bytes);
         plan->lds_alloc = alloc;
         break;

@@ -359,8 +359,13 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, con
         if ((std::min(vectors, units) >> opt.gather_threads_log2) >= 1) c->thread_bits = opt.gather_threads_log2;
     }
     c->lds_alloc = 0;
+    const long long staged_bytes = (long long)elem_bytes << g.block_bits;
     if (opt.gather_inflight_bytes != LL_AUTO)
-        c->lds_alloc = lds_alloc_for((unsigned)((long long)elem_bytes << g.block_bits), (unsigned)opt.gather_inflight_bytes, 0);
+        c->lds_alloc = lds_alloc_for((unsigned)staged_bytes, (unsigned)opt.gather_inflight_bytes, 0);
+    else if (staged_bytes == 8192)
+        // 8 KiB blocks: six workgroups per CU instead of the eight that fit (config 5's layout, rows and columns:
+        // 6.43 -> 6.72 and 6.32 -> 6.65 TB/s; row-major 64 x 256 tiles +1..3 %; five workgroups: 5.8)
+        c->lds_alloc = lds_alloc_for(8192u, 49152u, 0);
     return LL_OK;
 }
 
