@@ -1112,14 +1112,15 @@ static ll_status launch_gather_rows_t(const GatherArgs &a, int waves, int lds_al
 }
 
 template <int W, int NREG>
-static ll_status launch_gather_t(const GatherArgs &a, int waves, hipStream_t stream)
+static ll_status launch_gather_t(const GatherArgs &a, int waves, int lds_alloc, hipStream_t stream)
 {
     if constexpr ((1 << NREG) * W < 4 || (1 << NREG) * W > 256) {
         return fail(LL_ERR_UNSUPPORTED, "gather needs 4 to 256 bytes per lane (got %d)", (1 << NREG) * W);
     } else {
         const long long grid = (a.nchunks + waves - 1) / waves;
         if (grid > 0x7fffffffLL) return fail(LL_ERR_INVALID_ARG, "%lld workgroups do not fit one launch", grid);
-        launch((k_gather<W, NREG>), dim3((unsigned)grid), dim3(64u * (unsigned)waves), 0, stream, a);
+        if (lds_alloc < 0 || lds_alloc > 64 * 1024) return fail(LL_ERR_INVALID_ARG, "internal: shuffle gather asked for %d bytes of LDS", lds_alloc);
+        launch((k_gather<W, NREG>), dim3((unsigned)grid), dim3(64u * (unsigned)waves), (size_t)lds_alloc, stream, a);   // LDS only as the occupancy cap
         return check_launch("gather kernel launch");
     }
 }
@@ -1148,13 +1149,13 @@ static ll_status launch_gather_w(const GatherArgs &a, int waves, int lds_alloc, 
         }
     }
     switch (a.nreg) {
-    case 0: return launch_gather_t<W, 0>(a, waves, stream);
-    case 1: return launch_gather_t<W, 1>(a, waves, stream);
-    case 2: return launch_gather_t<W, 2>(a, waves, stream);
-    case 3: return launch_gather_t<W, 3>(a, waves, stream);
-    case 4: return launch_gather_t<W, 4>(a, waves, stream);
-    case 5: return launch_gather_t<W, 5>(a, waves, stream);
-    case 6: return launch_gather_t<W, 6>(a, waves, stream);
+    case 0: return launch_gather_t<W, 0>(a, waves, lds_alloc, stream);
+    case 1: return launch_gather_t<W, 1>(a, waves, lds_alloc, stream);
+    case 2: return launch_gather_t<W, 2>(a, waves, lds_alloc, stream);
+    case 3: return launch_gather_t<W, 3>(a, waves, lds_alloc, stream);
+    case 4: return launch_gather_t<W, 4>(a, waves, lds_alloc, stream);
+    case 5: return launch_gather_t<W, 5>(a, waves, lds_alloc, stream);
+    case 6: return launch_gather_t<W, 6>(a, waves, lds_alloc, stream);
     default: return fail(LL_ERR_UNSUPPORTED, "gather supports at most 6 register bits (got %d)", a.nreg);
     }
 }

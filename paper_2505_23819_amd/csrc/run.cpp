@@ -190,13 +190,20 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, con
         // XCD-aware order.  Measured on MI355X (64 x 256 tiles and relatives, 512 MiB of `in`, TB/s):
         // config 5 four waves per workgroup 6.59, one wave 6.68, with 32 consecutive chunks per XCD 6.84;
         // 5 waves per CU 5.0, 8: 6.35-6.8, 10: 6.84 (6 KiB loaded per wave), 16: 6.55 (4 KiB per wave).
+        // The shuffle kernel on rows of 8 or 16 bytes does best with one wave per workgroup as well, in natural
+        // order and without a cap (16-byte rows of 2- / 4- / 8-byte elements: four waves 6.37 / 6.23 / 6.43, one
+        // wave 6.53 / 6.70 / 6.81; 32 consecutive chunks per XCD: 6.36 / 6.06 / 6.29).
         const bool one_wave = a.staged && row_bytes < 256;
-        c->waves = (opt.gather_waves == 1 || opt.gather_waves == 2 || opt.gather_waves == 4) ? opt.gather_waves : (one_wave ? 1 : 4);
+        const bool one_wave_shuffle = !a.staged && row_bytes >= 8;
+        c->waves = (opt.gather_waves == 1 || opt.gather_waves == 2 || opt.gather_waves == 4) ? opt.gather_waves
+                                                                                               : ((one_wave || one_wave_shuffle) ? 1 : 4);
         const unsigned load_bytes = 64u * ((unsigned)row_bytes + 4u * (1u << nreg));           // per wave: `in` and `idx`
         const unsigned wave_bytes = load_bytes + 64u * (unsigned)row_bytes;                       // ... and `out`
         // 256 KiB of consecutive chunks (in + idx + out) per XCD; 64 KiB of loads in flight per CU, but 8 to 16 waves
         a.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, one_wave ? xcd_chunk_bits_for(256 * 1024, (long long)wave_bytes * c->waves) : -1);
         c->lds_alloc = 0;
+        if (!a.staged && opt.gather_inflight_bytes != LL_AUTO)
+            c->lds_alloc = lds_alloc_for(1u, std::max(1u, (unsigned)opt.gather_inflight_bytes / (load_bytes * (unsigned)c->waves)), 0);
         if (a.staged) {
             unsigned groups = (unsigned)opt_or(opt.gather_inflight_bytes, one_wave ? 65536 : 49152) / (load_bytes * (unsigned)c->waves);
             if (opt.gather_inflight_bytes == LL_AUTO && one_wave) groups = std::min(std::max(groups, 8u / (unsigned)c->waves), 16u);
