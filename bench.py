@@ -27,6 +27,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
 
 
+MAIN_SETS = 4          # buffer sets the main line rotates through
+TABLE_SETS = 3         # ... and each per-config table entry
 TABLE_WARMUP = 10      # untimed launches before each table entry, at least; extended to TABLE_WARMUP_MS of device time
 TABLE_WARMUP_MS = 25.0 # (the first launches after an idle spell or on fresh buffers run up to 10 % slower: clocks ramp up)
 
@@ -175,7 +177,9 @@ def main() -> int:
         return 2.0 * n / mean_ms / 1e6
 
     main_cfg = wl.config(args.workload)
-    launch, info, sets = make_case(main_cfg, nsets=2)
+    # four buffer sets in rotation: nothing is re-read from a cache, and the rate is the mean over four placements of the
+    # buffers (where a buffer lands in HBM moves the same kernel on the same data by up to 5 %)
+    launch, info, sets = make_case(main_cfg, nsets=MAIN_SETS)
     wall_ms, mean_ms, med_ms, min_ms = time_launches(launch, args.steps, args.warmup, warm_ms=0,      # exactly W warm-up steps
                                                      label="main: config %d" % main_cfg.cid)
     alg_bytes = main_cfg.algorithmic_bytes()
@@ -213,7 +217,7 @@ def main() -> int:
                                (main_cfg.cid, main_cfg.name, main_cfg.ntiles, main_cfg.d, main_cfg.elem_bytes),
                    "kernel": info["strategy_name"], "class": info["kind_name"],
                    "threads_per_workgroup": info.get("threads"), "vectors_per_thread": info.get("vectors_per_thread"),
-                   "options": fields or None, "buffer_sets_rotated": 2},
+                   "options": fields or None, "buffer_sets_rotated": MAIN_SETS},
         "fraction_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "copy_kernel_ceiling_GBps": round(ceiling, 1),
         "fraction_of_copy_ceiling": round(achieved / ceiling, 4),
@@ -227,13 +231,14 @@ def main() -> int:
                      "how": "achieved = algorithmic bytes / mean launch duration, HIP events around the timed region on the launch stream; "
                             "profiled_* = the same kernel's average under rocprofv3 --kernel-trace (profiles/), traffic = FETCH_SIZE + WRITE_SIZE"},
     }
+    # Buffers go back to torch's caching allocator, not to the driver: memory that is freed and allocated again
+    # during the run lands less well (configs 2-5 read 0.5-1.3 % lower with a release after every section)
     del sets, launch
-    torch.cuda.empty_cache()
 
     if not args.only_main:
         table = []
         for cfg in wl.configs():
-            nsets = 2 if cfg.algorithmic_bytes() < (1 << 30) else 1
+            nsets = TABLE_SETS
             l, inf, s = make_case(cfg, nsets)
             steps = args.table_steps if cfg.cid != 1 else max(args.table_steps, 200 if args.table_steps >= 30 else 0)
             w_ms, m_ms, md_ms, mn_ms = time_launches(l, steps, TABLE_WARMUP, label="config %d" % cfg.cid)
@@ -246,7 +251,6 @@ def main() -> int:
                 entry.update({"lds_access_bytes": inf["lds_write_bytes"], "lds_bytes": inf["lds_bytes"],
                               "predicted_wavefronts": [inf["predicted_wavefronts_write"], inf["predicted_wavefronts_read"]]})
             del s, l
-            torch.cuda.empty_cache()
             if cfg.cid != 1:
                 entry["copy_GBps_same_footprint"] = round(copy_ceiling(ab // 2, label="copy yardstick for config %d" % cfg.cid), 1)
             if cfg.kind == "convert" and args.strategy is None and inf["strategy_name"] in ("reg_permute", "wave_shuffle"):
@@ -257,7 +261,6 @@ def main() -> int:
                                         "GBps": round(ab / md2 / 1e6, 1),
                                         "predicted_wavefronts": [inf2["predicted_wavefronts_write"], inf2["predicted_wavefronts_read"]]}
                 del s2, l2
-                torch.cuda.empty_cache()
             annotate(entry, "config %d" % cfg.cid, ab)
             table.append(entry)
         result["per_config"] = table
@@ -299,7 +302,6 @@ def main() -> int:
                          "frac_hbm_peak": round(ab1 / m_ms / 1e6 / HBM_PEAK_GBPS, 4)})
         result["config1_layouts_32768_tiles"] = {"algorithmic_bytes": ab1, "kernels": many}
         del x1, o1
-        torch.cuda.empty_cache()
 
         # conversions between layouts that replicate data (zero columns): one copy of every logical
         # element read, every destination slot written
@@ -321,7 +323,6 @@ def main() -> int:
                            "predicted_wavefronts": [inf["predicted_wavefronts_write"], inf["predicted_wavefronts_read"]]})
             annotate(btable[-1], "broadcast: " + case.name, ab)
             del x, outs
-            torch.cuda.empty_cache()
         result["broadcast_conversions"] = btable
 
         # the 128 x 128 transpose of config 2 with 1-byte (float8-sized) and 2-byte elements: the planner's
@@ -346,7 +347,6 @@ def main() -> int:
                            "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4),
                            "predicted_wavefronts": [inf["predicted_wavefronts_write"], inf["predicted_wavefronts_read"]]})
             del x, outs
-            torch.cuda.empty_cache()
         result["narrow_element_transposes"] = ttable
 
         # gather variants on config 5's layout: rows (lane axis) with each of the three kernels, and
@@ -372,7 +372,6 @@ def main() -> int:
             annotate(gtable[-1], "gather: config 5 layout, dim %d, %s" % (axis_, ginfo["kernel_name"]), ab)
             del idx5
         del x5, out5
-        torch.cuda.empty_cache()
         # axes whose aligned block exceeds LDS, row-major two-byte tiles of 2^18 elements (512 KiB), gather along
         # the rows: 512 x 512 is staged as 512 rows x 128-byte runs; 8192 x 32 has no closed block with runs of
         # 64 bytes that fits LDS, its 512 KiB range is walked through LDS in chunks; 32768 x 32 (2 MiB) is read
@@ -397,7 +396,6 @@ def main() -> int:
             annotate(gtable[-1], "gather: row-major %dx%d two-byte tile, rows, %s" % (1 << rows_b, 1 << cols_b, ginfo["kernel_name"]), ab)
             del ib
         del xb, ob
-        torch.cuda.empty_cache()
         result["gather_variants"] = gtable
 
         # affine layouts (y = A x xor b): config 2 with the destination flipped along both dims (element
@@ -418,7 +416,6 @@ def main() -> int:
                            "conv_offset": inf["conv_offset"], "algorithmic_bytes": ab, "us_mean": round(md_ms * 1e3, 2),
                            "GBps": round(ab / md_ms / 1e6, 1), "frac_hbm_peak": round(ab / md_ms / 1e6 / HBM_PEAK_GBPS, 4)})
             del x, outs
-            torch.cuda.empty_cache()
         result["affine_conversions"] = atable
 
     if args.mark:
