@@ -218,21 +218,21 @@ typedef struct {
     int32_t xcd_chunk;             /* consecutive blocks each of the 8 XCDs takes at a time (power of two); 0: natural order */
     int32_t pull_mode;             /* broadcasting plans: 0 balanced, 1 destination runs first, 2 source runs first */
     int32_t pull_vec_bits;         /* log2 elements per LDS access of the broadcast kernel (upper bound) */
-    int32_t pull_inflight_bytes;
-    int32_t pull_xcd_chunk;
+    int32_t pull_inflight_bytes;   /* as inflight_bytes, counted in destination bytes of the broadcast kernel's blocks */
+    int32_t pull_xcd_chunk;        /* as xcd_chunk */
     /* gather tuning */
     int32_t gather_block_bytes;    /* preferred block of the workgroup-staged kernel */
     int32_t gather_lds_max_bytes;  /* largest block it may stage */
     int32_t gather_min_run_bytes;  /* shortest contiguous run a staged block may be made of */
     int32_t gather_phased_max_bytes; /* largest aligned range walked through LDS in chunks */
     int32_t gather_threads_log2;   /* threads per workgroup of the workgroup-staged kernel: 8, 9 or 10 */
-    int32_t gather_inflight_bytes;
-    int32_t gather_xcd_chunk;
+    int32_t gather_inflight_bytes; /* as inflight_bytes: bytes of `in` and `idx` loads (wave-level kernels) or of staged blocks */
+    int32_t gather_xcd_chunk;      /* as xcd_chunk, in chunks of one wave (wave-level kernels) or blocks */
     int32_t gather_swizzle_always; /* 1: swizzle the staged block even when no move along the axis changes bank bits */
     int32_t copy_xcd_chunk;        /* ll_copy (process defaults only) */
     int32_t debug;                 /* 1: planners say on stderr why a strategy did not apply */
     int32_t gather_waves;          /* waves per workgroup of the wave-level gather kernels (one chunk each): 1, 2 or 4 */
-    int32_t pull_threads_log2;     /* threads per workgroup of the broadcast kernel: 6 (one wave), 7 or 8 */
+    int32_t pull_threads_log2;     /* threads per workgroup of the broadcast kernel: 6 (one wave) or 8 */
 } ll_options;
 
 ll_status ll_options_init(ll_options *opts);
