@@ -344,14 +344,21 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
     // Largest staged block, and the size small tiles are bundled to (bytes, powers of two).
     // Small blocks measured best on MI355X (more, shorter-lived workgroups keep about 32-64 KiB in
     // flight per CU, which is where a plain copy also peaks).
-    const unsigned max_block = opt_bytes(opt.block_bytes, 8192u);
+    // 4- and 8-byte elements: 4 KiB, which goes to one wave (below).  Measured against the 8 KiB blocks of four (two)
+    // waves, with their longer runs, TB/s: bit permutations of 4-byte elements on tiles of 2^12 / 2^14 / 2^18 / 2^20 /
+    // 2^22 elements 6.32 / 6.46 / 5.93 / 5.95 / 5.93 -> 6.52 / 6.68 / 6.45 / 6.21 / 6.18 (2^17: 6.68 -> 6.59), configs 1
+    // and 3 through this kernel 6.41 / 6.42 -> 6.61 / 6.56; 8-byte elements, random XOR maps 2^13 / 2^16 / 2^18 / 2^22
+    // 6.55 / 6.30 / 6.18 / 5.48 -> 6.55 / 6.45 / 6.33 / 5.48, bit permutations 2^18 / 2^22 6.39 / 5.18 -> 6.58 / 5.88.
+    // 2-byte elements keep 8 KiB: their 4 KiB blocks have runs of 64 bytes under XOR maps, and permutations of large
+    // tiles lose up to 11 % with the shorter runs.
+    const unsigned max_block = opt_bytes(opt.block_bytes, w >= 4 ? 4096u : 8192u);
     const unsigned pref_block = opt_bytes(opt.pref_bytes, 8192u);
 
     BlockGeom geom;
     const int min_bits = vs + std::max(tb, 8);        // a wave-sized workgroup takes at least four vectors per lane
     const bool tb_auto = opt.elem_threads_log2 == LL_AUTO;
     if (ll_status st = build_blocks(p, d, w, min_bits, max_block, pref_block, &geom); st != LL_OK) return st;
-    if (geom.n == min_bits && (w == 1 || d >= 17) && opt.block_bytes == LL_AUTO) {
+    if (geom.n == min_bits && (w == 1 || (d >= 17 && w == 2)) && opt.block_bytes == LL_AUTO) {
         // One vector per thread and a tile cut into many such blocks: the runs are as short as the
         // limit allows (4-byte elements: 128 bytes on each side, 32 of them scattered over the tile).
         // Runs grow on both sides at once, so the next size is four times the block.  Measured with
@@ -363,6 +370,10 @@ static ll_status plan_lds_elem(const mat &p, int d, int w, ll_plan *plan)
         // 4-byte 2^17 6.1 / 6.25, 2^18 5.8 / 6.3; 8-byte 2^13..2^15 6.5 / 5.8-6.2, 2^17 6.1 / 6.3.
         // Byte elements pay one LDS instruction per byte, and a workgroup that holds only 4 KiB
         // cannot hide that: 2^14..2^20 4.2-5.8 against 6.1-6.5 at every tile size.
+        // (The 4- and 8-byte figures above are those of four waves per 4 KiB block in natural block order.  With one
+        // wave per block and the XCD-aware order the small block wins for them at every size - random XOR maps of
+        // 4-byte elements, 2^17 / 2^18 / 2^20 / 2^22 / 2^24: 6.27 / 6.25 / 6.15 / 5.88 / 5.16 for 16 KiB against
+        // 6.41 / 6.38 / 6.40 / 6.13 / 5.41 - so only bytes and 2-byte elements still widen.)
         BlockGeom wider;
         if (build_blocks(p, d, w, min_bits, 2 * max_block, pref_block, &wider) == LL_OK && wider.k > geom.k &&
             ((unsigned)w << wider.n) <= 2 * max_block)
@@ -555,11 +566,19 @@ static ll_status choose_strategy(const mat &p, int d, int elem_bytes, ll_plan *p
         if (ll_status st = plan_lds_tr(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
         if (applied) return LL_OK;
     }
-    if (!(force >= LL_STRATEGY_LDS_ELEM)) {
+    // Tiles above 128 KiB of 4- and 8-byte elements go to the element-wide LDS kernel straight away: its 4 KiB blocks
+    // for one wave hold up at every tile size, while the register / shuffle kernels (4 or 8 vectors per lane, blocks
+    // scattered over a large tile) fall off.  Sampled on MI355X, planner's former choice -> LDS kernel, TB/s: transposes
+    // of 2^16 .. 2^22-element tiles 5.5-5.8 -> 6.1-6.45 (4-byte, all 13 shapes), 5.4-6.3 -> 5.9-6.5 (8-byte, better in
+    // 12 of 15); six random bit permutations per size, geometric mean: 4-byte 2^16 / 2^17 / 2^18 / 2^20 / 2^22 elements
+    // +1.3 / +0.9 / 0.0 / +3.7 / +6.3 %, 8-byte 2^15 / 2^16 / 2^17 / 2^18 / 2^20 / 2^22 +2.6 / +2.0 / +0.1 / +1.8 / +1.4 /
+    // +1.8 %.  Up to 128 KiB the two are within 1-2 % either way and the register / shuffle path stays.
+    const bool large = force == LL_AUTO && elem_bytes >= 4 && ((long long)elem_bytes << d) > 128 * 1024;
+    if (!(force >= LL_STRATEGY_LDS_ELEM) && !large) {
         if (ll_status st = plan_wave_shuffle(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
         if (applied) return LL_OK;
     }
-    if (force != LL_STRATEGY_LDS_ELEM) {
+    if (force != LL_STRATEGY_LDS_ELEM && !large) {
         if (ll_status st = plan_lds_vec(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
         if (applied) return LL_OK;
     }
@@ -593,8 +612,9 @@ static void set_launch_params(ll_plan *plan)
     switch (desc.strategy) {
     case LL_STRATEGY_LDS_ELEM:
     case LL_STRATEGY_LDS_TR: {
-        const int chunk = (desc.threads < 256 || group_bytes <= kXcdTarget) ? xcd_chunk_bits_for(kXcdTarget, block_bytes) : -1;
-        plan->lds_elem.xcd_chunk = opt_chunk_bits(opt.xcd_chunk, chunk);
+        // at every tile size (four waves per block on tiles above 128 KiB too: random XOR maps, six per size, geometric
+        // mean against the natural order: 2-byte elements 2^18 / 2^20 / 2^22 +4.4 / +1.5 / +2.0 %, bytes +2.5 / +0.7 / +0.4 %)
+        plan->lds_elem.xcd_chunk = opt_chunk_bits(opt.xcd_chunk, xcd_chunk_bits_for(kXcdTarget, block_bytes));
         int alloc = desc.lds_bytes;
         if (desc.threads < 256 || opt.inflight_bytes != LL_AUTO)
             alloc = lds_alloc_for((unsigned)block_bytes, (unsigned)opt_or(opt.inflight_bytes, 45056), alloc);
@@ -613,7 +633,10 @@ static void set_launch_params(ll_plan *plan)
     case LL_STRATEGY_REG_PERMUTE:
     case LL_STRATEGY_WAVE_SHUFFLE:
     case LL_STRATEGY_LDS_VEC: {
-        const int chunk = group_bytes <= kXcdTarget ? xcd_chunk_bits_for(kXcdTarget, block_bytes) : -1;
+        // 2-byte elements at every tile size (transposes of tiles above 128 KiB: 5.6-5.9 TB/s in natural order, 6.0-6.3
+        // with it, all 12 shapes; random bit permutations +1 % on average); 4- and 8-byte elements only reach these
+        // kernels with tiles up to 128 KiB
+        const int chunk = (group_bytes <= kXcdTarget || desc.elem_bytes == 2) ? xcd_chunk_bits_for(kXcdTarget, block_bytes) : -1;
         plan->vec.xcd_chunk = opt_chunk_bits(opt.xcd_chunk, chunk);
         // the pure register path (no exchange, no affine constant to apply) is the lightest: 40 KiB suits it
         // (bench conditions: config 2 6.40 -> 6.43 TB/s, config 3 6.48 -> 6.57), everything else wants 48 KiB

@@ -562,17 +562,23 @@ def test_convert_one_large_tile():
 
 @pytest.mark.parametrize("w,d", [(4, 16), (4, 17), (4, 20), (2, 19), (8, 18), (1, 15)])
 def test_convert_large_tiles_random_xor(w, d):
-    """Large tiles under random XOR layouts (from 2^17 elements on the planner stages wider blocks
-    where the narrow one holds a single vector per thread), a ragged number of tiles."""
+    """Large tiles under random XOR layouts, a ragged number of tiles; 4-byte elements also through 16 KiB blocks of
+    four waves (what 1- and 2-byte elements get from 2^17 elements on)."""
     rng = np.random.default_rng(9700 + 10 * w + d)
     ca, cb = wl.random_invertible_bases(500 + d, d), wl.random_invertible_bases(600 + d, d)
     a, b = ll.distributed_layout(4, 6, d - 10, [d], ca), ll.distributed_layout(4, 6, d - 10, [d], cb)
     plan = ll.ll_plan_convert(a, b, w)
-    if w == 4:            # 16 KiB blocks for four waves from 2^17 elements on, below that 4 KiB blocks for one wave
+    plans = [plan]
+    if w == 4:            # 4 KiB blocks for one wave at every tile size; 16 KiB blocks for four waves on request
         info = plan.info()
-        assert (info["threads"], info["vectors_per_thread"], info["block_bits"]) == ((256, 4, 12) if d >= 17 else (64, 4, 10))
+        assert (info["threads"], info["vectors_per_thread"], info["block_bits"]) == (64, 4, 10)
+        plans.append(ll.ll_plan_convert(a, b, w, ll.ll_options_init(block_bytes=16384)))
+        info = plans[-1].info()
+        assert (info["threads"], info["vectors_per_thread"], info["block_bits"]) == (256, 4, 12)
     src = rng.integers(0, np.iinfo(NP_DTYPES[w]).max, size=3 << d, dtype=NP_DTYPES[w])
-    assert np.array_equal(run_convert(plan, src, d), oracle.convert(ca, cb, src))
+    want = oracle.convert(ca, cb, src)
+    for p in plans:
+        assert np.array_equal(run_convert(p, src, d), want), p.info()["block_bits"]
 
 
 # ---------------------------------------------------------------------------------------------
