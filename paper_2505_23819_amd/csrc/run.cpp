@@ -180,36 +180,43 @@ static ll_status choose_gather(const ll_layout *L, int axis, int elem_bytes, con
         // 5.68 / 5.70 and 5.70 / 5.50, against 5.89 and 6.17 staged by four waves per workgroup (workgroup-
         // staged kernel: 6.28, 6.16).  Hence 32 bytes: staged, 64: butterflies, more: not here at all.
         const int row_bytes = (1 << nreg) * elem_bytes;
-        a.staged = (row_bytes > 16 && row_bytes <= 256 && nreg >= 2) ? ((row_bytes == 64 || row_bytes == 128) ? 2 : 1) : 0;
-        if (opt.gather_kernel == LL_GATHER_SHUFFLE) a.staged = 0;
-        if (opt.gather_kernel == LL_GATHER_WAVE_STAGED) a.staged = row_bytes >= 16 && row_bytes <= 256 && nreg >= 2;
-        if (opt.gather_kernel == LL_GATHER_SHUFFLE_ROWS) a.staged = (row_bytes >= 32 && row_bytes <= 256 && nreg >= 2) ? 2 : 0;
-        c->kernel = a.staged == 2 ? LL_GATHER_SHUFFLE_ROWS : a.staged ? LL_GATHER_WAVE_STAGED : LL_GATHER_SHUFFLE;
-        // The kernels with coalesced pieces run ONE wave per workgroup (a wave's chunk is its own: it goes
-        // on as soon as its loads have landed), a number of waves per CU set through the LDS share, and an
-        // XCD-aware order.  Measured on MI355X (64 x 256 tiles and relatives, 512 MiB of `in`, TB/s):
-        // config 5 four waves per workgroup 6.59, one wave 6.68, with 32 consecutive chunks per XCD 6.84;
-        // 5 waves per CU 5.0, 8: 6.35-6.8, 10: 6.84 (6 KiB loaded per wave), 16: 6.55 (4 KiB per wave).
-        // The shuffle kernel on rows of 8 or 16 bytes does best with one wave per workgroup as well, in natural
-        // order and without a cap (16-byte rows of 2- / 4- / 8-byte elements: four waves 6.37 / 6.23 / 6.43, one
-        // wave 6.53 / 6.70 / 6.81; 32 consecutive chunks per XCD: 6.36 / 6.06 / 6.29).
-        const bool one_wave = a.staged && row_bytes < 256;
-        const bool one_wave_shuffle = !a.staged && row_bytes >= 8;
-        c->waves = (opt.gather_waves == 1 || opt.gather_waves == 2 || opt.gather_waves == 4) ? opt.gather_waves
-                                                                                               : ((one_wave || one_wave_shuffle) ? 1 : 4);
-        const unsigned load_bytes = 64u * ((unsigned)row_bytes + 4u * (1u << nreg));           // per wave: `in` and `idx`
-        const unsigned wave_bytes = load_bytes + 64u * (unsigned)row_bytes;                       // ... and `out`
-        // 256 KiB of consecutive chunks (in + idx + out) per XCD; 64 KiB of loads in flight per CU, but 8 to 16 waves
-        a.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, one_wave ? xcd_chunk_bits_for(256 * 1024, (long long)wave_bytes * c->waves) : -1);
-        c->lds_alloc = 0;
-        if (!a.staged && opt.gather_inflight_bytes != LL_AUTO)
-            c->lds_alloc = lds_alloc_for(1u, std::max(1u, (unsigned)opt.gather_inflight_bytes / (load_bytes * (unsigned)c->waves)), 0);
-        if (a.staged) {
-            unsigned groups = (unsigned)opt_or(opt.gather_inflight_bytes, one_wave ? 65536 : 49152) / (load_bytes * (unsigned)c->waves);
-            if (opt.gather_inflight_bytes == LL_AUTO && one_wave) groups = std::min(std::max(groups, 8u / (unsigned)c->waves), 16u);
-            c->lds_alloc = lds_alloc_for(1u, std::max(groups, 1u), 0);
+        // Rows wider than 16 bytes under an axis that is NOT a plain field of the lane index (lane bits permuted or
+        // mixed): the wave kernels then work out every element's source lane bit by bit, and the workgroup-staged
+        // kernel with its delta tables is far ahead (five random lane-bit orders each, TB/s: 32-byte rows of 2-byte
+        // elements 4.5 against 6.5, 64-byte rows 4.3-5.1 against 6.5; 16-byte rows 6.4 against 6.6, left to the
+        // shuffle kernel).  Those layouts go on to the general case below.
+        if (a.fast || row_bytes <= 16 || wave_kernel_asked) {
+            a.staged = (row_bytes > 16 && row_bytes <= 256 && nreg >= 2) ? ((row_bytes == 64 || row_bytes == 128) ? 2 : 1) : 0;
+            if (opt.gather_kernel == LL_GATHER_SHUFFLE) a.staged = 0;
+            if (opt.gather_kernel == LL_GATHER_WAVE_STAGED) a.staged = row_bytes >= 16 && row_bytes <= 256 && nreg >= 2;
+            if (opt.gather_kernel == LL_GATHER_SHUFFLE_ROWS) a.staged = (row_bytes >= 32 && row_bytes <= 256 && nreg >= 2) ? 2 : 0;
+            c->kernel = a.staged == 2 ? LL_GATHER_SHUFFLE_ROWS : a.staged ? LL_GATHER_WAVE_STAGED : LL_GATHER_SHUFFLE;
+            // The kernels with coalesced pieces run ONE wave per workgroup (a wave's chunk is its own: it goes
+            // on as soon as its loads have landed), a number of waves per CU set through the LDS share, and an
+            // XCD-aware order.  Measured on MI355X (64 x 256 tiles and relatives, 512 MiB of `in`, TB/s):
+            // config 5 four waves per workgroup 6.59, one wave 6.68, with 32 consecutive chunks per XCD 6.84;
+            // 5 waves per CU 5.0, 8: 6.35-6.8, 10: 6.84 (6 KiB loaded per wave), 16: 6.55 (4 KiB per wave).
+            // The shuffle kernel on rows of 8 or 16 bytes does best with one wave per workgroup as well, in natural
+            // order and without a cap (16-byte rows of 2- / 4- / 8-byte elements: four waves 6.37 / 6.23 / 6.43, one
+            // wave 6.53 / 6.70 / 6.81; 32 consecutive chunks per XCD: 6.36 / 6.06 / 6.29).
+            const bool one_wave = a.staged && row_bytes < 256;
+            const bool one_wave_shuffle = !a.staged && row_bytes >= 8;
+            c->waves = (opt.gather_waves == 1 || opt.gather_waves == 2 || opt.gather_waves == 4) ? opt.gather_waves
+                                                                                                   : ((one_wave || one_wave_shuffle) ? 1 : 4);
+            const unsigned load_bytes = 64u * ((unsigned)row_bytes + 4u * (1u << nreg));           // per wave: `in` and `idx`
+            const unsigned wave_bytes = load_bytes + 64u * (unsigned)row_bytes;                       // ... and `out`
+            // 256 KiB of consecutive chunks (in + idx + out) per XCD; 64 KiB of loads in flight per CU, but 8 to 16 waves
+            a.xcd_chunk = opt_chunk_bits(opt.gather_xcd_chunk, one_wave ? xcd_chunk_bits_for(256 * 1024, (long long)wave_bytes * c->waves) : -1);
+            c->lds_alloc = 0;
+            if (!a.staged && opt.gather_inflight_bytes != LL_AUTO)
+                c->lds_alloc = lds_alloc_for(1u, std::max(1u, (unsigned)opt.gather_inflight_bytes / (load_bytes * (unsigned)c->waves)), 0);
+            if (a.staged) {
+                unsigned groups = (unsigned)opt_or(opt.gather_inflight_bytes, one_wave ? 65536 : 49152) / (load_bytes * (unsigned)c->waves);
+                if (opt.gather_inflight_bytes == LL_AUTO && one_wave) groups = std::min(std::max(groups, 8u / (unsigned)c->waves), 16u);
+                c->lds_alloc = lds_alloc_for(1u, std::max(groups, 1u), 0);
+            }
+            return LL_OK;
         }
-        return LL_OK;
     }
 
     // General case: the axis occupies register and / or wave bits (or the layout is not wave64
