@@ -570,9 +570,10 @@ static ll_status choose_strategy(const mat &p, int d, int elem_bytes, ll_plan *p
     // for one wave hold up at every tile size, while the register / shuffle kernels (4 or 8 vectors per lane, blocks
     // scattered over a large tile) fall off.  Sampled on MI355X, planner's former choice -> LDS kernel, TB/s: transposes
     // of 2^16 .. 2^22-element tiles 5.5-5.8 -> 6.1-6.45 (4-byte, all 13 shapes), 5.4-6.3 -> 5.9-6.5 (8-byte, better in
-    // 12 of 15); six random bit permutations per size, geometric mean: 4-byte 2^16 / 2^17 / 2^18 / 2^20 / 2^22 elements
-    // +1.3 / +0.9 / 0.0 / +3.7 / +6.3 %, 8-byte 2^15 / 2^16 / 2^17 / 2^18 / 2^20 / 2^22 +2.6 / +2.0 / +0.1 / +1.8 / +1.4 /
-    // +1.8 %.  Up to 128 KiB the two are within 1-2 % either way and the register / shuffle path stays.
+    // 12 of 15); random bit permutations, five to ten per size on 1 GiB each way, geometric mean: 4-byte 2^15 / 2^16 /
+    // 2^17 / 2^18 / 2^20 elements +0.2 / +2.4 / -0.3 / -0.9 / +4.5 %, 8-byte 2^16 / 2^17 / 2^18 / 2^20 / 2^22 +0.8 / -1.2 /
+    // -1.5 / -0.5 / +2.4 %: a tie for random permutations, a clear gain for structured ones.  Up to 128 KiB the two
+    // are within 1-2 % either way and the register / shuffle path stays.
     const bool large = force == LL_AUTO && elem_bytes >= 4 && ((long long)elem_bytes << d) > 128 * 1024;
     if (!(force >= LL_STRATEGY_LDS_ELEM) && !large) {
         if (ll_status st = plan_wave_shuffle(p, d, elem_bytes, plan, &applied); st != LL_OK) return st;
@@ -612,8 +613,9 @@ static void set_launch_params(ll_plan *plan)
     switch (desc.strategy) {
     case LL_STRATEGY_LDS_ELEM:
     case LL_STRATEGY_LDS_TR: {
-        // at every tile size (four waves per block on tiles above 128 KiB too: random XOR maps, six per size, geometric
-        // mean against the natural order: 2-byte elements 2^18 / 2^20 / 2^22 +4.4 / +1.5 / +2.0 %, bytes +2.5 / +0.7 / +0.4 %)
+        // at every tile size (four waves per block on tiles above 128 KiB too: random XOR maps, five per size on 1 GiB
+        // each way, geometric mean against the natural order: 2-byte elements 2^18 / 2^20 / 2^22 +3.6 / +2.7 / +5.3 %,
+        // bytes +6.5 / +2.0 / +1.4 %)
         plan->lds_elem.xcd_chunk = opt_chunk_bits(opt.xcd_chunk, xcd_chunk_bits_for(kXcdTarget, block_bytes));
         int alloc = desc.lds_bytes;
         if (desc.threads < 256 || opt.inflight_bytes != LL_AUTO)
